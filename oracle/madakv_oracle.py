@@ -1,0 +1,408 @@
+"""MadaKV eviction + decode, written out plainly in NumPy float64.
+
+TEST INFRASTRUCTURE ONLY.  This module is the checker for the HIP library: it is
+imported by the tests, by the smoke check and by the benchmark's CPU-baseline
+leg, and by nothing on the product path.  It imports nothing from the HIP
+package and shares no code with it.
+
+Everything here follows the MadaKV paper (arxiv 2506.15724), Section 3:
+
+  * Sec. 3.1, Eq. 3-5   decode: append K_t, V_t, softmax(q K^T / sqrt(d_k)) V
+  * Sec. 3.3, Eq. 7     proxy-token score  psi(i) = sum_{j in P} alpha_{j->i}
+  * Sec. 3.3, Eq. 6     modality mass      w_v, w_t
+  * Sec. 3.3, Eq. 8     per-head, per-modality budget split (MPA)
+  * Sec. 3.3, Eq. 9     theta-mass sparsity counts k_v, k_t
+  * Sec. 3.3, Eq. 10-11 layer compensation K^l and the budget recurrence (HCC)
+
+The paper leaves several things open (size of the proxy set, theta, how Eq. 10-11
+turn into integers, tie-breaks, pooling).  Each function states the reading it
+takes.  The HCC allocation reading (clamps, apportionment) has no worked example
+in the paper to pin it against: it is "parity unpinned" with respect to the paper
+and is pinned only by its own invariants (exact conservation, Eq. 11 identity,
+sign behaviour, brute-force apportionment).
+
+Conventions
+-----------
+modality id 0 = text, 1 = image (the mask array holds these ids).
+L = context length, W = number of proxy (observation-window) tokens = the last W
+prompt positions, H = KV heads, Hq = query heads, G = Hq / H, d = head_dim.
+Candidates for eviction are positions [0, L-W); the window is always kept and is
+counted inside the per-head budget.
+All arrays are float64 / int64 unless stated.  One call handles one batch item.
+"""
+from __future__ import annotations
+
+import dataclasses
+import math
+
+import numpy as np
+
+TEXT, IMAGE = 0, 1
+
+
+@dataclasses.dataclass
+class Params:
+    """Hyper-parameters of the method (paper Sec. 3.3 names theta, |P| and the
+    layer budget but prints no values; the defaults are this build's reading)."""
+    n_layers: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    ctx_len: int
+    window: int            # |P|
+    budget: int            # tokens kept per KV head per layer, window included
+    pool_k: int = 1        # odd; 1 = Eq. 7 scores used as they are
+    mpa_mode: int = 1      # 1 = Eq. 8 split, 0 = modality-agnostic
+    hcc_mode: int = 1      # 1 = Eq. 9-11, 0 = every head gets the same budget
+    hcc_rho: int = 2       # clamp ratio around the running nominal budget
+    theta: float = 0.9     # Eq. 9 threshold
+    softmax_scale: float = 0.0  # 0 -> 1/sqrt(head_dim)
+
+    @property
+    def scale(self) -> float:
+        return self.softmax_scale if self.softmax_scale > 0 else 1.0 / math.sqrt(self.head_dim)
+
+    @property
+    def group(self) -> int:
+        return self.n_q_heads // self.n_kv_heads
+
+    @property
+    def n_cand(self) -> int:
+        return self.ctx_len - self.window
+
+    @property
+    def keep_all(self) -> bool:
+        return self.budget >= self.ctx_len
+
+
+# --------------------------------------------------------------------------- #
+# Eq. 7: proxy-token scores
+# --------------------------------------------------------------------------- #
+def window_scores(q_win: np.ndarray, k: np.ndarray, scale: float) -> np.ndarray:
+    """psi[h, i] = sum over the proxy rows of the attention they pay to key i.
+
+    q_win : [Hq, W, d]  queries of the last W prompt positions
+    k     : [H, L, d]   keys of the whole prompt
+    Proxy row r sits at absolute position L-W+r and, the prefill being causal,
+    sees keys 0..L-W+r only.  With grouped queries the G query heads that share
+    KV head h (query head j uses KV head j // G) all add into psi[h].
+    Returns psi [H, L].   (Sec. 3.3 Eq. 7; logits scaled as in Eq. 5.)
+    """
+    q_win = np.asarray(q_win, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    Hq, W, d = q_win.shape
+    H, L, _ = k.shape
+    G = Hq // H
+    psi = np.zeros((H, L), dtype=np.float64)
+    pos = np.arange(L)
+    for h in range(H):
+        for g in range(G):
+            logits = scale * (q_win[h * G + g] @ k[h].T)          # [W, L]
+            for r in range(W):
+                p = L - W + r
+                row = np.where(pos <= p, logits[r], -np.inf)
+                row = row - row.max()
+                e = np.exp(row)
+                psi[h] += e / e.sum()
+    return psi
+
+
+# --------------------------------------------------------------------------- #
+# Eq. 6 and Eq. 9: modality mass and theta-mass counts
+# --------------------------------------------------------------------------- #
+def modality_mass(psi_h: np.ndarray, mask: np.ndarray, window: int):
+    """(w[2], n[2]) over the candidates [0, L-W) of one head (Eq. 6)."""
+    L = psi_h.shape[0]
+    c = L - window
+    w = np.zeros(2, dtype=np.float64)
+    n = np.zeros(2, dtype=np.int64)
+    for m in (TEXT, IMAGE):
+        sel = mask[:c] == m
+        n[m] = int(sel.sum())
+        w[m] = float(psi_h[:c][sel].sum())
+    return w, n
+
+
+def theta_mass_count(values: np.ndarray, theta: float) -> int:
+    """Smallest number of entries of `values` whose sum reaches theta * sum(values)
+    (Eq. 9): the entries are taken from the largest down.  0 if there is nothing
+    to cover (no entries or zero mass)."""
+    n = values.shape[0]
+    if n == 0:
+        return 0
+    total = float(values.sum())
+    if total <= 0.0:
+        return 0
+    srt = np.sort(values)[::-1]
+    c = np.cumsum(srt)
+    target = theta * total
+    hit = np.nonzero(c >= target)[0]
+    return int(hit[0]) + 1 if hit.size else n
+
+
+def modality_stats(psi: np.ndarray, mask: np.ndarray, window: int, theta: float):
+    """Per head: w[H,2] (Eq. 6), kcnt[H,2] (Eq. 9), and n_mod[2] candidate counts.
+    Uses the raw Eq. 7 scores (never the pooled ones)."""
+    H, L = psi.shape
+    c = L - window
+    w = np.zeros((H, 2), dtype=np.float64)
+    kcnt = np.zeros((H, 2), dtype=np.int64)
+    n_mod = np.zeros(2, dtype=np.int64)
+    for h in range(H):
+        w[h], n_mod = modality_mass(psi[h], mask, window)
+        for m in (TEXT, IMAGE):
+            kcnt[h, m] = theta_mass_count(psi[h, :c][mask[:c] == m], theta)
+    return w, kcnt, n_mod
+
+
+def text_share(w_t: float, w_v: float, n_t: int, n_v: int) -> float:
+    """Share of the head's attention mass that goes to text (the weight in Eq. 8).
+    If the head put no mass on any candidate, fall back to the token share."""
+    tot = float(w_t) + float(w_v)
+    if tot > 0.0:
+        return float(w_t) / tot
+    return n_t / (n_t + n_v) if (n_t + n_v) > 0 else 0.0
+
+
+# --------------------------------------------------------------------------- #
+# Score pooling (not in the paper; ranking only)
+# --------------------------------------------------------------------------- #
+def pool_scores(psi: np.ndarray, window: int, pool_k: int) -> np.ndarray:
+    """psi_pool[h, i] = max of psi[h, j] over candidates j with |j-i| <= (pool_k-1)/2,
+    for i in [0, L-W).  Position-based, clipped at both ends of the candidate range,
+    blind to modality boundaries.  pool_k = 1 returns the candidate scores as is."""
+    H, L = psi.shape
+    c = L - window
+    r = (pool_k - 1) // 2
+    out = np.empty((H, c), dtype=np.float64)
+    for i in range(c):
+        lo, hi = max(0, i - r), min(c, i + r + 1)
+        out[:, i] = psi[:, lo:hi].max(axis=1)
+    return out
+
+
+# --------------------------------------------------------------------------- #
+# Eq. 9-11: hierarchical compression compensation, in integers
+# --------------------------------------------------------------------------- #
+def _largest_remainder(base: np.ndarray, rem: np.ndarray, extra: int) -> np.ndarray:
+    """Add 1 to the `extra` entries with the largest remainder, ties to the lower index."""
+    out = base.copy()
+    order = sorted(range(len(base)), key=lambda h: (-int(rem[h]), h))
+    for h in order[:extra]:
+        out[h] += 1
+    return out
+
+
+def apportion(total: int, demand: np.ndarray, n_cand: int) -> np.ndarray:
+    """Integers a_h >= 0, a_h <= n_cand, sum a_h == total, proportional to `demand`
+    when scaling down, and proportional to the head-room n_cand - demand when
+    scaling up (Hamilton / largest remainder, ties to the lower head index)."""
+    demand = np.asarray(demand, dtype=np.int64)
+    D = int(demand.sum())
+    if total == D:
+        return demand.copy()
+    if total < D:
+        num = total * demand                      # exact in int64
+        base = num // D
+        rem = num % D
+        return _largest_remainder(base, rem, total - int(base.sum()))
+    room = n_cand - demand
+    S = total - D
+    Rm = int(room.sum())
+    num = S * room
+    base = num // Rm
+    rem = num % Rm
+    return demand + _largest_remainder(base, rem, S - int(base.sum()))
+
+
+def hcc_allocate(kcnt: np.ndarray, p: Params, trace: dict | None = None) -> np.ndarray:
+    """Per-head candidate totals a[N_L, H] from the theta-mass counts kcnt[N_L, H, 2].
+
+    Reading of Eq. 9-11 taken here.  Budgets are counted in candidate tokens
+    (beta = budget - W per head).  A head's demand is its Eq. 9 count k_t + k_v.
+    The model holds one integer pool R = N_L * H * beta.  Layer l (0-based, rem =
+    N_L - l layers left) has the nominal per-head budget phi^l = R / (H * rem);
+    demands are clamped to [phi/rho, rho*phi] (and to [1, n_cand]); the layer draws
+    A = sum of clamped demands, itself clamped so that the layers after it can
+    still be given between beta_floor and n_cand per head; the last layer draws
+    what is left.  Heads receive `apportion(A, demand)`.  Then R -= A, which is
+    Eq. 11 with K^l = sum_h (a_h - phi^l) taken per head (divided by H):
+        phi^{l+1} = phi^l - (K^l / H) / (rem - 1).
+    hcc_mode = 0 gives every head beta.
+    """
+    NL, H, _ = kcnt.shape
+    beta = p.budget - p.window
+    n_c = p.n_cand
+    a = np.zeros((NL, H), dtype=np.int64)
+    if p.hcc_mode == 0:
+        a[:] = beta
+        return a
+    rho = p.hcc_rho
+    beta_floor = max(1, beta // (rho * rho))
+    R = NL * H * beta
+    if trace is not None:
+        trace["phi"], trace["K"], trace["R"] = [], [], []
+    for l in range(NL):
+        rem = NL - l
+        lo = max(1, -((-R) // (rho * H * rem)))            # ceil
+        hi = min(n_c, (rho * R) // (H * rem))
+        dem = np.clip(kcnt[l, :, 0] + kcnt[l, :, 1], lo, hi).astype(np.int64)
+        D = int(dem.sum())
+        if l == NL - 1:
+            A = R
+        else:
+            A = min(max(D, R - (rem - 1) * H * n_c), R - (rem - 1) * H * beta_floor)
+        a[l] = apportion(A, dem, n_c)
+        if trace is not None:
+            phi = R / (H * rem)
+            trace["phi"].append(phi)
+            trace["K"].append(float(a[l].sum()) - H * phi)
+            trace["R"].append(R)
+        R -= A
+    return a
+
+
+def mpa_split(a: int, w_t: float, w_v: float, n_t: int, n_v: int) -> tuple[int, int]:
+    """Eq. 8 in integers: b_t = round-half-up(share_t * a), b_v = a - b_t; a modality
+    that has fewer candidates than its budget hands the surplus to the other."""
+    s_t = text_share(w_t, w_v, n_t, n_v)
+    b_t = int(math.floor(s_t * a + 0.5))
+    b_v = a - b_t
+    if b_t > n_t:
+        b_t, b_v = n_t, a - n_t
+    if b_v > n_v:
+        b_v, b_t = n_v, a - n_v
+    return b_t, b_v
+
+
+def allocate(w: np.ndarray, kcnt: np.ndarray, n_mod: np.ndarray, p: Params,
+             trace: dict | None = None) -> np.ndarray:
+    """budgets[N_L, H, 2] = (b_t, b_v) for one batch item.
+    w[N_L,H,2] are the Eq. 6 masses as they cross the interface (float32 values),
+    kcnt[N_L,H,2] the Eq. 9 counts, n_mod[2] the candidate counts per modality.
+    mpa_mode = 0 puts the whole total in slot 0: selection then ignores modality."""
+    NL, H, _ = kcnt.shape
+    out = np.zeros((NL, H, 2), dtype=np.int64)
+    n_t, n_v = int(n_mod[0]), int(n_mod[1])
+    if p.keep_all:
+        out[:, :, 0], out[:, :, 1] = n_t, n_v
+        return out
+    a = hcc_allocate(kcnt, p, trace)
+    for l in range(NL):
+        for h in range(H):
+            if p.mpa_mode == 0:
+                out[l, h] = (a[l, h], 0)
+            else:
+                out[l, h] = mpa_split(int(a[l, h]), float(np.float32(w[l, h, 0])),
+                                      float(np.float32(w[l, h, 1])), n_t, n_v)
+    return out
+
+
+# --------------------------------------------------------------------------- #
+# Eviction: top-k per head per modality, then gather
+# --------------------------------------------------------------------------- #
+def top_indices(scores: np.ndarray, idx: np.ndarray, b: int) -> np.ndarray:
+    """The b entries of idx with the largest scores; equal scores: lower index first."""
+    if b <= 0:
+        return np.zeros(0, dtype=np.int64)
+    order = sorted(range(len(idx)), key=lambda j: (-scores[j], idx[j]))
+    return idx[np.asarray(order[:b], dtype=np.int64)]
+
+
+def select(psi_pool_h: np.ndarray, mask: np.ndarray, b_t: int, b_v: int,
+           L: int, window: int, mpa_mode: int = 1) -> np.ndarray:
+    """Kept positions of one head: per modality the b_m best-scored candidates, all in
+    ascending position, then the window positions L-W..L-1 (Sec. 3.3, last line of
+    the MPA paragraph: eviction is per head and per modality)."""
+    c = L - window
+    cand = np.arange(c, dtype=np.int64)
+    if mpa_mode == 0:
+        keep = top_indices(psi_pool_h, cand, b_t + b_v)
+    else:
+        parts = []
+        for m, b in ((TEXT, b_t), (IMAGE, b_v)):
+            sel = mask[:c] == m
+            parts.append(top_indices(psi_pool_h[sel], cand[sel], b))
+        keep = np.concatenate(parts)
+    keep = np.sort(keep)
+    return np.concatenate([keep, np.arange(c, L, dtype=np.int64)])
+
+
+def gather(x_h: np.ndarray, kept: np.ndarray) -> np.ndarray:
+    """Rows `kept` of x_h[L, d], copied."""
+    return x_h[kept].copy()
+
+
+# --------------------------------------------------------------------------- #
+# Eq. 3-5: decode over a (reduced) cache
+# --------------------------------------------------------------------------- #
+def attend(q: np.ndarray, k_c: np.ndarray, v_c: np.ndarray, scale: float) -> np.ndarray:
+    """softmax(scale * q k_c^T) v_c for one query vector q[d] (Eq. 5)."""
+    s = scale * (k_c.astype(np.float64) @ q.astype(np.float64))
+    s = s - s.max()
+    e = np.exp(s)
+    return (e / e.sum()) @ v_c.astype(np.float64)
+
+
+def decode_step(q: np.ndarray, k_new, v_new, k_cache: list, v_cache: list, scale: float):
+    """One decode step for one layer of one batch item.
+    q[Hq,d]; k_new, v_new [H,d] or None; k_cache/v_cache: lists of H arrays [len_h, d]
+    which are extended in place by the new row (Eq. 4) before attention (Eq. 5).
+    Returns out[Hq, d]."""
+    Hq, d = q.shape
+    H = len(k_cache)
+    G = Hq // H
+    out = np.zeros((Hq, d), dtype=np.float64)
+    for h in range(H):
+        if k_new is not None:
+            k_cache[h] = np.concatenate([k_cache[h], np.asarray(k_new[h], dtype=np.float64)[None]], 0)
+            v_cache[h] = np.concatenate([v_cache[h], np.asarray(v_new[h], dtype=np.float64)[None]], 0)
+        for g in range(G):
+            out[h * G + g] = attend(q[h * G + g], k_cache[h], v_cache[h], scale)
+    return out
+
+
+# --------------------------------------------------------------------------- #
+# The whole eviction for one batch item
+# --------------------------------------------------------------------------- #
+def score_layer(q_win: np.ndarray, k: np.ndarray, mask: np.ndarray, p: Params,
+                interface_fp32: bool = True):
+    """Eq. 7, Eq. 6, Eq. 9 and pooling for one layer: (psi, psi_pool, w, kcnt, n_mod).
+    With interface_fp32 the scores are rounded to float32 once, as they are when
+    they cross the library boundary, before the statistics are taken from them."""
+    psi = window_scores(q_win, k, p.scale)
+    if interface_fp32:
+        psi = psi.astype(np.float32).astype(np.float64)
+    w, kcnt, n_mod = modality_stats(psi, mask, p.window, p.theta)
+    psi_pool = pool_scores(psi, p.window, p.pool_k)
+    return psi, psi_pool, w, kcnt, n_mod
+
+
+def evict(q_win: np.ndarray, k: np.ndarray, v: np.ndarray, mask: np.ndarray, p: Params):
+    """Full eviction of one batch item.
+    q_win[N_L,Hq,W,d], k,v[N_L,H,L,d], mask[L].
+    Returns dict with psi, psi_pool, w, kcnt, n_mod, budgets, kept (list of lists of
+    index arrays), k_c / v_c (lists of lists of arrays [len, d])."""
+    NL, H, L = k.shape[0], k.shape[1], k.shape[2]
+    res = {"psi": [], "psi_pool": [], "w": [], "kcnt": []}
+    n_mod = None
+    for l in range(NL):
+        psi, psi_pool, w, kcnt, n_mod = score_layer(q_win[l], k[l], mask, p)
+        res["psi"].append(psi); res["psi_pool"].append(psi_pool)
+        res["w"].append(w); res["kcnt"].append(kcnt)
+    for key in ("psi", "psi_pool", "w", "kcnt"):
+        res[key] = np.stack(res[key])
+    res["n_mod"] = n_mod
+    res["budgets"] = allocate(res["w"], res["kcnt"], n_mod, p)
+    res["kept"], res["k_c"], res["v_c"] = [], [], []
+    for l in range(NL):
+        kl, kc, vc = [], [], []
+        for h in range(H):
+            if p.keep_all:
+                kept = np.arange(L, dtype=np.int64)
+            else:
+                b_t, b_v = (int(x) for x in res["budgets"][l, h])
+                kept = select(res["psi_pool"][l, h], mask, b_t, b_v, L, p.window, p.mpa_mode)
+            kl.append(kept); kc.append(gather(k[l, h], kept)); vc.append(gather(v[l, h], kept))
+        res["kept"].append(kl); res["k_c"].append(kc); res["v_c"].append(vc)
+    return res

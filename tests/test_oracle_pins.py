@@ -1,0 +1,440 @@
+"""Pins for the CPU oracle: closed forms, invariants, brute force on tiny inputs and
+special cases that reduce to a textbook routine.  None of these re-type the oracle's
+own formula; each is chosen so that a dropped term, a wrong sign or index or a
+transposed operand in the oracle fails at least one of them.  (No GPU needed.)"""
+import itertools
+import math
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import madakv_oracle as O
+
+
+def rng(seed):
+    return np.random.default_rng(seed)
+
+
+# ------------------------------------------------------------------ Eq. 7 scores
+def test_psi_hand_example_single_row():
+    # One proxy row (W=1) looking at 3 keys along e1: psi is softmax(scale * a_i).
+    scale = 0.5
+    q = np.array([[[1.0, 0.0]]])                       # [Hq=1, W=1, d=2]
+    k = np.array([[[2.0, 7.0], [-1.0, 3.0], [0.5, -4.0]]])
+    z = [math.exp(scale * a) for a in (2.0, -1.0, 0.5)]
+    want = np.array(z) / sum(z)
+    got = O.window_scores(q, k, scale)
+    assert got.shape == (1, 3)
+    np.testing.assert_allclose(got[0], want, rtol=1e-14)
+
+
+def test_psi_hand_example_causal_two_rows():
+    # W=2, L=3: row 0 sits at position 1 and must not see key 2.
+    scale = 1.0
+    q = np.array([[[1.0], [2.0]]])                     # [1, 2, 1]
+    k = np.array([[[0.3], [-0.2], [0.9]]])             # [1, 3, 1]
+    r0 = [math.exp(0.3), math.exp(-0.2)]
+    r1 = [math.exp(0.6), math.exp(-0.4), math.exp(1.8)]
+    want = [r0[0] / sum(r0) + r1[0] / sum(r1), r0[1] / sum(r0) + r1[1] / sum(r1), r1[2] / sum(r1)]
+    got = O.window_scores(q, k, scale)[0]
+    np.testing.assert_allclose(got, want, rtol=1e-14)
+
+
+@pytest.mark.parametrize("Hq,H", [(4, 4), (6, 2)])
+def test_psi_rows_sum_to_one(Hq, H):
+    r = rng(1)
+    W, L, d = 5, 37, 8
+    psi = O.window_scores(r.normal(size=(Hq, W, d)), r.normal(size=(H, L, d)), 0.3)
+    np.testing.assert_allclose(psi.sum(axis=1), (Hq // H) * W, rtol=1e-12)
+    assert (psi >= 0).all()
+
+
+def test_psi_identical_keys_closed_form():
+    r = rng(2)
+    W, L, d = 4, 19, 6
+    k = np.tile(r.normal(size=(1, 1, d)), (2, L, 1))
+    psi = O.window_scores(r.normal(size=(2, W, d)), k, 0.7)
+    want = np.array([sum(1.0 / (L - W + rr + 1) for rr in range(W) if L - W + rr >= i) for i in range(L)])
+    np.testing.assert_allclose(psi[0], want, rtol=1e-12)
+    np.testing.assert_allclose(psi[1], want, rtol=1e-12)
+
+
+def test_psi_last_column_only_from_last_row():
+    r = rng(3)
+    W, L, d = 3, 11, 4
+    q, k = r.normal(size=(1, W, d)), r.normal(size=(1, L, d))
+    psi = O.window_scores(q, k, 0.5)[0]
+    logits = 0.5 * k[0] @ q[0, W - 1]
+    want = math.exp(logits[L - 1]) / sum(math.exp(x) for x in logits)
+    assert psi[L - 1] == pytest.approx(want, rel=1e-12)
+
+
+def test_psi_matches_textbook_masked_softmax():
+    r = rng(4)
+    Hq, H, W, L, d = 6, 3, 4, 29, 8
+    q, k = r.normal(size=(Hq, W, d)), r.normal(size=(H, L, d))
+    tq, tk = torch.from_numpy(q), torch.from_numpy(k)
+    kk = tk.repeat_interleave(Hq // H, dim=0)                           # query head j -> kv head j // G
+    att = torch.einsum("hwd,hld->hwl", tq, kk) * 0.41
+    pos = torch.arange(L)[None, :]
+    row = (L - W + torch.arange(W))[:, None]
+    att = att.masked_fill(pos > row, float("-inf")).softmax(dim=-1)
+    want = att.sum(dim=1).reshape(H, Hq // H, L).sum(dim=1).numpy()
+    np.testing.assert_allclose(O.window_scores(q, k, 0.41), want, rtol=1e-12, atol=1e-300)
+
+
+def test_psi_duplicated_query_heads_scale_by_group():
+    r = rng(5)
+    W, L, d = 3, 17, 4
+    q1, k = r.normal(size=(2, W, d)), r.normal(size=(2, L, d))
+    q3 = np.repeat(q1, 3, axis=0)
+    np.testing.assert_allclose(O.window_scores(q3, k, 0.5), 3 * O.window_scores(q1, k, 0.5), rtol=1e-12)
+
+
+# ------------------------------------------------------------------ Eq. 6 shares
+def test_share_closed_form_constant_logit_per_modality():
+    # logit a on text keys, b on image keys: share_t = n_t e^a / (n_t e^a + n_v e^b),
+    # whatever mass the window columns take.
+    W, L, d = 4, 40, 2
+    a, b, scale = 0.8, -0.3, 0.5
+    mask = np.zeros(L, dtype=np.uint8); mask[5:21] = 1
+    k = np.zeros((1, L, d)); k[0, :, 0] = np.where(mask == 1, b, a) / scale
+    k[0, L - W:, 0] = 0.123
+    q = np.zeros((1, W, d)); q[0, :, 0] = 1.0
+    psi = O.window_scores(q, k, scale)
+    w, kc, n = O.modality_stats(psi, mask, W, 0.9)
+    n_t, n_v = L - W - 16, 16
+    assert tuple(n) == (n_t, n_v)
+    want = n_t * math.exp(a) / (n_t * math.exp(a) + n_v * math.exp(b))
+    assert O.text_share(w[0, 0], w[0, 1], n_t, n_v) == pytest.approx(want, rel=1e-12)
+
+
+def test_share_bounds_and_single_modality():
+    r = rng(6)
+    W, L = 4, 50
+    psi = r.random((3, L))
+    mask = (r.random(L) < 0.5).astype(np.uint8)
+    w, _, n = O.modality_stats(psi, mask, W, 0.9)
+    for h in range(3):
+        s = O.text_share(w[h, 0], w[h, 1], n[0], n[1])
+        assert 0.0 <= s <= 1.0
+        assert s + w[h, 1] / (w[h, 0] + w[h, 1]) == pytest.approx(1.0, abs=1e-15)
+    w1, _, n1 = O.modality_stats(psi, np.zeros(L, np.uint8), W, 0.9)
+    assert O.text_share(w1[0, 0], w1[0, 1], n1[0], n1[1]) == 1.0
+    w2, _, n2 = O.modality_stats(psi, np.ones(L, np.uint8), W, 0.9)
+    assert O.text_share(w2[0, 0], w2[0, 1], n2[0], n2[1]) == 0.0
+    assert O.text_share(0.0, 0.0, 3, 9) == 0.25
+    # window columns are excluded from the masses
+    np.testing.assert_allclose(w[:, 0] + w[:, 1], psi[:, :L - W].sum(axis=1), rtol=1e-13)
+
+
+# ------------------------------------------------------------------ Eq. 9 counts
+def test_theta_count_brute_force_over_subsets():
+    r = rng(7)
+    for trial in range(40):
+        n = int(r.integers(1, 9))
+        v = r.random(n) ** 3
+        theta = float(r.uniform(0.05, 0.99))
+        tot = v.sum()
+        best = None
+        for size in range(1, n + 1):
+            if any(sum(c) >= theta * tot for c in itertools.combinations(v, size)):
+                best = size
+                break
+        assert O.theta_mass_count(v, theta) == best
+
+
+def test_theta_count_special_cases():
+    assert O.theta_mass_count(np.ones(10), 0.5) == 5
+    assert O.theta_mass_count(np.ones(8), 0.75) == 6
+    assert O.theta_mass_count(np.ones(8), 0.70) == 6          # ceil(5.6)
+    onehot = np.zeros(9); onehot[4] = 2.5
+    assert O.theta_mass_count(onehot, 0.9) == 1
+    assert O.theta_mass_count(rng(8).random(20), 1e-9) == 1
+    assert O.theta_mass_count(np.zeros(5), 0.9) == 0
+    assert O.theta_mass_count(np.zeros(0), 0.9) == 0
+    v = rng(9).random(30)
+    ks = [O.theta_mass_count(v, t) for t in np.linspace(0.01, 1.0, 34)]
+    assert all(x <= y for x, y in zip(ks, ks[1:])) and ks[-1] <= 30
+
+
+def test_stats_count_uses_modality_subsets():
+    psi = np.array([[8.0, 1.0, 1.0, 4.0, 4.0, 1.0, 99.0]])      # last column is the window
+    mask = np.array([0, 0, 0, 1, 1, 1, 0], dtype=np.uint8)
+    w, kc, n = O.modality_stats(psi, mask, 1, 0.8)
+    assert tuple(w[0]) == (10.0, 9.0) and tuple(n) == (3, 3)
+    assert tuple(kc[0]) == (1, 2)                               # 8 >= 8 ; 4+4 >= 7.2
+
+
+# ------------------------------------------------------------------ pooling
+def test_pool_brute_force_and_identity():
+    r = rng(10)
+    psi = r.random((2, 23))
+    W = 3
+    np.testing.assert_array_equal(O.pool_scores(psi, W, 1), psi[:, :20])
+    for pk in (3, 5, 7):
+        got = O.pool_scores(psi, W, pk)
+        rad = (pk - 1) // 2
+        for h in range(2):
+            for i in range(20):
+                js = [j for j in range(20) if abs(j - i) <= rad]
+                assert got[h, i] == max(psi[h, j] for j in js)
+        assert (got >= psi[:, :20]).all()
+
+
+# ------------------------------------------------------------------ Eq. 10-11 HCC
+def _params(NL, H, L, W, budget, **kw):
+    return O.Params(n_layers=NL, n_q_heads=H, n_kv_heads=H, head_dim=8, ctx_len=L, window=W, budget=budget, **kw)
+
+
+def test_apportion_hamilton_properties_small():
+    r = rng(11)
+    for trial in range(300):
+        H = int(r.integers(1, 5))
+        n_c = int(r.integers(4, 30))
+        dem = r.integers(1, n_c + 1, size=H)
+        total = int(r.integers(0, H * n_c + 1))
+        a = O.apportion(total, dem, n_c)
+        assert a.sum() == total and (a >= 0).all() and (a <= n_c).all()
+        D = int(dem.sum())
+        if total == D:
+            assert (a == dem).all(); continue
+        if total < D:
+            quota = [Fraction(total * int(x), D) for x in dem]
+            part = a
+        else:
+            room = n_c - dem
+            quota = [Fraction((total - D) * int(x), int(room.sum())) for x in room]
+            part = a - dem
+        fl = [q.numerator // q.denominator for q in quota]
+        fr = [q - f for q, f in zip(quota, fl)]
+        assert all(p in (f, f + 1) for p, f in zip(part, fl))
+        ups = [h for h in range(H) if part[h] == fl[h] + 1]
+        downs = [h for h in range(H) if part[h] == fl[h]]
+        for u in ups:
+            for dn in downs:       # nobody with a strictly larger remainder (or equal and lower index) was skipped
+                assert fr[u] > fr[dn] or (fr[u] == fr[dn] and u < dn)
+
+
+def test_hcc_conservation_bounds_and_split():
+    r = rng(12)
+    for trial in range(60):
+        NL, H = int(r.integers(1, 7)), int(r.integers(1, 6))
+        W = int(r.integers(1, 5)); L = int(r.integers(W + 8, 80))
+        budget = int(r.integers(W + 1, L))
+        p = _params(NL, H, L, W, budget, theta=0.9)
+        n_c = L - W
+        n_t = int(r.integers(0, n_c + 1)); n_v = n_c - n_t
+        kc = np.stack([r.integers(0, n_t + 1, size=(NL, H)), r.integers(0, n_v + 1, size=(NL, H))], -1)
+        w = r.random((NL, H, 2)).astype(np.float32)
+        b = O.allocate(w, kc, np.array([n_t, n_v]), p)
+        assert b.sum() == NL * H * (budget - W)
+        assert (b >= 0).all() and (b[..., 0] <= n_t).all() and (b[..., 1] <= n_v).all()
+        a = O.hcc_allocate(kc, p)
+        assert (b.sum(-1) == a).all()
+
+
+def test_hcc_fixed_point_and_uniform_mode():
+    NL, H, L, W, budget = 5, 4, 100, 4, 24
+    p = _params(NL, H, L, W, budget)
+    kc = np.zeros((NL, H, 2), dtype=np.int64); kc[..., 0] = 12; kc[..., 1] = 8      # demand == beta everywhere
+    assert (O.hcc_allocate(kc, p) == 20).all()
+    kc2 = rng(13).integers(0, 40, size=(NL, H, 2))
+    assert (O.hcc_allocate(kc2, _params(NL, H, L, W, budget, hcc_mode=0)) == 20).all()
+    one = O.hcc_allocate(kc2[:1], _params(1, H, L, W, budget))
+    assert one.sum() == H * 20
+
+
+def test_hcc_sign_of_compensation_and_eq11_replay():
+    NL, H, L, W, budget = 6, 4, 200, 8, 48
+    beta = budget - W
+    p = _params(NL, H, L, W, budget)
+    base = np.zeros((NL, H, 2), dtype=np.int64); base[..., 0] = beta
+    for first, sign in ((beta + 20, +1), (beta - 20, -1)):
+        kc = base.copy(); kc[0, :, 0] = first
+        tr = {}
+        a = O.hcc_allocate(kc, p, tr)
+        assert np.sign(tr["K"][0]) == sign                       # overdraft positive, saving negative
+        later = a[1:].mean()
+        assert (later < beta) if sign > 0 else (later > beta)    # overdraft -> later layers get less
+        # Eq. 11 with K^l taken per head: phi^{l+1} = phi^l - (K^l / H) / (layers left after l)
+        for l in range(NL - 1):
+            want = tr["phi"][l] - (tr["K"][l] / H) / (NL - l - 1)
+            assert tr["phi"][l + 1] == pytest.approx(want, rel=1e-9)
+        # Eq. 10: K^l = sum_h (realised - phi^l)
+        for l in range(NL):
+            assert tr["K"][l] == pytest.approx(sum(float(x) - tr["phi"][l] for x in a[l]), abs=1e-9)
+        assert tr["phi"][0] == beta
+
+
+def test_mpa_split_rounding_and_spill():
+    assert O.mpa_split(7, 1.0, 1.0, 100, 100) == (4, 3)          # 3.5 rounds half up on text
+    assert O.mpa_split(10, 3.0, 1.0, 100, 100) == (8, 2)         # 7.5 -> 8
+    assert O.mpa_split(10, 1.0, 3.0, 100, 100) == (3, 7)         # 2.5 -> 3
+    assert O.mpa_split(10, 9.0, 1.0, 4, 100) == (4, 6)           # text short: surplus to image
+    assert O.mpa_split(10, 1.0, 9.0, 100, 5) == (5, 5)           # image short: surplus to text
+    assert O.mpa_split(10, 0.0, 0.0, 30, 10) == (8, 2)           # no mass: token share 0.75 -> 7.5 -> 8
+    assert O.mpa_split(6, 5.0, 0.0, 10, 10) == (6, 0)
+    # Eq. 8 proportionality on exact numbers
+    assert O.mpa_split(100, 0.25, 0.75, 1000, 1000) == (25, 75)
+
+
+# ------------------------------------------------------------------ selection
+def _brute_select(score, mask, b, L, W):
+    c = L - W
+    keep = []
+    for i in range(c):
+        m = mask[i]
+        ahead = sum(1 for j in range(c) if mask[j] == m and (score[j] > score[i] or (score[j] == score[i] and j < i)))
+        if ahead < b[m]:
+            keep.append(i)
+    return keep + list(range(c, L))
+
+
+def test_select_brute_force_with_ties():
+    r = rng(14)
+    for trial in range(60):
+        W = int(r.integers(1, 4)); L = int(r.integers(W + 3, 40)); c = L - W
+        mask = (r.random(L) < 0.5).astype(np.uint8)
+        score = r.integers(0, 5, size=c).astype(np.float64)       # many exact ties
+        n = [int((mask[:c] == m).sum()) for m in (0, 1)]
+        b = [int(r.integers(0, n[0] + 1)), int(r.integers(0, n[1] + 1))]
+        got = O.select(score, mask, b[0], b[1], L, W)
+        assert list(got) == _brute_select(score, mask, b, L, W)
+        assert (np.diff(got) > 0).all() and list(got[-W:]) == list(range(c, L))
+
+
+def test_select_single_modality_is_plain_topk_and_full():
+    r = rng(15)
+    L, W = 33, 3; c = L - W
+    score = r.random(c)
+    mask = np.zeros(L, np.uint8)
+    got = O.select(score, mask, 7, 0, L, W)
+    want = sorted(np.argsort(-score, kind="stable")[:7].tolist()) + list(range(c, L))
+    assert list(got) == want
+    mask2 = (r.random(L) < 0.4).astype(np.uint8)
+    got_all = O.select(score, mask2, int((mask2[:c] == 0).sum()), int((mask2[:c] == 1).sum()), L, W)
+    assert list(got_all) == list(range(L))
+    # modality-agnostic mode ignores the mask
+    got0 = O.select(score, mask2, 5, 4, L, W, mpa_mode=0)
+    assert list(got0) == sorted(np.argsort(-score, kind="stable")[:9].tolist()) + list(range(c, L))
+
+
+def test_top_indices_vs_lexsort_tiny():
+    r = rng(16)
+    for _ in range(30):
+        n = int(r.integers(1, 25))
+        s = r.integers(0, 4, size=n).astype(np.float64)
+        idx = np.sort(r.choice(100, size=n, replace=False))
+        b = int(r.integers(0, n + 1))
+        want = idx[np.lexsort((idx, -s))[:b]]
+        assert list(O.top_indices(s, idx, b)) == list(want)
+
+
+# ------------------------------------------------------------------ Eq. 3-5 decode
+def _full_attention(q, k, v, scale):
+    tq, tk, tv = (torch.from_numpy(np.asarray(x, dtype=np.float64)) for x in (q, k, v))
+    return (torch.softmax(scale * tk @ tq, dim=0) @ tv).numpy()
+
+
+def test_attend_textbook_and_degenerate_cases():
+    r = rng(17)
+    q, k, v = r.normal(size=8), r.normal(size=(21, 8)), r.normal(size=(21, 8))
+    np.testing.assert_allclose(O.attend(q, k, v, 0.35), _full_attention(q, k, v, 0.35), rtol=1e-12)
+    np.testing.assert_allclose(O.attend(q, k[:1], v[:1], 0.35), v[0], rtol=1e-15)
+    same = np.tile(k[:1], (21, 1))
+    np.testing.assert_allclose(O.attend(q, same, v, 0.35), v.mean(axis=0), rtol=1e-12)
+    perm = r.permutation(21)
+    np.testing.assert_allclose(O.attend(q, k[perm], v[perm], 0.35), O.attend(q, k, v, 0.35), rtol=1e-12, atol=1e-14)
+
+
+def test_decode_append_then_attend_equals_concat_and_gqa_mapping():
+    r = rng(18)
+    Hq, H, d = 4, 2, 8
+    kc = [r.normal(size=(5, d)), r.normal(size=(9, d))]
+    vc = [r.normal(size=(5, d)), r.normal(size=(9, d))]
+    q, kn, vn = r.normal(size=(Hq, d)), r.normal(size=(H, d)), r.normal(size=(H, d))
+    k2, v2 = [x.copy() for x in kc], [x.copy() for x in vc]
+    out = O.decode_step(q, kn, vn, k2, v2, 0.4)
+    assert k2[0].shape == (6, d) and v2[1].shape == (10, d)
+    for j in range(Hq):
+        h = j // 2
+        want = _full_attention(q[j], np.vstack([kc[h], kn[h]]), np.vstack([vc[h], vn[h]]), 0.4)
+        np.testing.assert_allclose(out[j], want, rtol=1e-12)
+    out2 = O.decode_step(q, None, None, k2, v2, 0.4)            # attend only: nothing appended
+    assert k2[0].shape == (6, d)
+    np.testing.assert_allclose(out2, out, rtol=1e-15)
+
+
+# ------------------------------------------------------------------ whole eviction
+def _tiny_problem(seed, NL=3, H=2, G=2, L=48, W=4, d=8):
+    r = rng(seed)
+    mask = np.zeros(L, np.uint8); mask[6:20] = 1; mask[26:38] = 1
+    q = r.normal(size=(NL, H * G, W, d)); k = r.normal(size=(NL, H, L, d)); v = r.normal(size=(NL, H, L, d))
+    return q, k, v, mask
+
+
+def test_budget_at_or_above_context_keeps_everything_and_is_full_attention():
+    q, k, v, mask = _tiny_problem(19)
+    NL, H, L, d = k.shape
+    for budget in (L, L + 7):
+        p = O.Params(n_layers=NL, n_q_heads=4, n_kv_heads=H, head_dim=d, ctx_len=L, window=4, budget=budget)
+        res = O.evict(q, k, v, mask, p)
+        qd = rng(20).normal(size=(4, d))
+        for l in range(NL):
+            for h in range(H):
+                assert list(res["kept"][l][h]) == list(range(L))
+                np.testing.assert_array_equal(res["k_c"][l][h], k[l, h])
+            out = O.decode_step(qd, None, None, res["k_c"][l], res["v_c"][l], p.scale)
+            for j in range(4):
+                np.testing.assert_allclose(out[j], _full_attention(qd[j], k[l, j // 2], v[l, j // 2], p.scale), rtol=1e-12)
+
+
+def test_evict_end_to_end_invariants():
+    q, k, v, mask = _tiny_problem(21)
+    NL, H, L, d = k.shape
+    p = O.Params(n_layers=NL, n_q_heads=4, n_kv_heads=H, head_dim=d, ctx_len=L, window=4, budget=16, pool_k=3)
+    res = O.evict(q, k, v, mask, p)
+    assert res["budgets"].sum() == NL * H * 12
+    for l in range(NL):
+        for h in range(H):
+            kept = res["kept"][l][h]
+            b_t, b_v = res["budgets"][l, h]
+            assert len(kept) == b_t + b_v + 4
+            assert (np.diff(kept) > 0).all()
+            assert int((mask[kept[:-4]] == 0).sum()) == b_t and int((mask[kept[:-4]] == 1).sum()) == b_v
+            np.testing.assert_array_equal(res["k_c"][l][h], k[l, h][kept])
+            np.testing.assert_array_equal(res["v_c"][l][h], v[l, h][kept])
+    # modality-agnostic + uniform mode = plain top-(budget-W) of the pooled window scores
+    p0 = O.Params(n_layers=NL, n_q_heads=4, n_kv_heads=H, head_dim=d, ctx_len=L, window=4, budget=16,
+                  pool_k=3, mpa_mode=0, hcc_mode=0)
+    res0 = O.evict(q, k, v, mask, p0)
+    for l in range(NL):
+        for h in range(H):
+            sp = res0["psi_pool"][l, h]
+            want = sorted(np.argsort(-sp, kind="stable")[:12].tolist()) + list(range(L - 4, L))
+            assert list(res0["kept"][l][h]) == want
+
+
+def test_hcc_hand_worked_examples():
+    """Three allocations carried out by hand (pencil arithmetic, rho = 2) from the
+    reading stated in the oracle: pool R, nominal phi = R/(H*rem), demand clamp
+    [ceil(phi/rho), floor(rho*phi)], layer total clamped so later layers stay
+    feasible, Hamilton apportionment."""
+    def run(NL, H, n_c, beta, dem):
+        W = 2
+        p = _params(NL, H, n_c + W, W, beta + W)
+        kc = np.zeros((NL, H, 2), dtype=np.int64); kc[..., 0] = np.asarray(dem)
+        return O.hcc_allocate(kc, p).tolist()
+    # (1) nobody clamps the layer total.  R=48: l0 lo=4 hi=16, demands (20,18)->(16,16), A=32;
+    #     R=16: l1 lo=2 hi=8, (1,20)->(2,8), A=10; R=6: last layer lo=ceil(6/4)=2,
+    #     (1,5)->(2,5), D=7 > 6: floors (1,4), remainders (5,2) -> (2,4).
+    assert run(3, 2, 20, 8, [[20, 18], [1, 20], [1, 5]]) == [[16, 16], [2, 8], [2, 4]]
+    # (2) upper clamp of the layer total.  R=32, beta_floor=2: l0 D=32 > 32-1*2*2=28 -> A=28 -> (14,14);
+    #     R=4: last layer lo=1 hi=4, (3,9)->(3,4), D=7: floors (1,2), remainders (5,2) -> (2,2).
+    assert run(2, 2, 20, 8, [[20, 18], [3, 9]]) == [[14, 14], [2, 2]]
+    # (3) lower clamp of the layer total.  n_c=10, R=32: l0 (1,1)->(4,4), D=8 < 32-1*2*10=12 -> A=12,
+    #     head-room (6,6) -> (6,6); R=20: last layer lo=5 hi=10, (7,2)->(7,5), D=12, room (3,5) -> (10,10).
+    assert run(2, 2, 10, 8, [[1, 1], [7, 2]]) == [[6, 6], [10, 10]]
