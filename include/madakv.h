@@ -1,0 +1,177 @@
+/*
+ * madakv.h - C ABI of the MadaKV eviction + ragged-decode hot path for one AMD
+ * MI355X (gfx950).
+ *
+ * The calls follow the method of "MadaKV: Adaptive Modality-Perception KV Cache
+ * Eviction" (arxiv 2506.15724), Section 3:
+ *
+ *   madakv_score          Sec. 3.3 Eq. 7 (proxy-token scores), Eq. 6 (modality
+ *                         mass), Eq. 9 (theta-mass sparsity counts), plus score
+ *                         pooling used for ranking only
+ *   madakv_allocate       Sec. 3.3 Eq. 8 (per-head, per-modality budgets) and
+ *                         Eq. 10-11 (layer compensation, budget recurrence)
+ *   madakv_select_gather  Sec. 3.3, end of the MPA paragraph: per-head,
+ *                         per-modality eviction; builds the reduced KV cache
+ *   madakv_decode_attn    Sec. 3.1 Eq. 3-5: append K_t, V_t and attend over the
+ *                         reduced cache
+ *
+ * General rules
+ *   - Plain C, no exceptions.  Every call returns a madakv_status (0 = OK).
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller, contiguous,
+ *     row-major in the stated shape.  Q/K/V-like tensors (q_win, k, v, k_c, v_c, q,
+ *     k_new, v_new, out) and the workspaces must be aligned to 16 bytes; the other
+ *     arrays to their element size (kv_off 8, float / int32 arrays and stats 4).
+ *     The library never allocates, frees or keeps tensor memory.  A null or
+ *     misaligned pointer gives MADAKV_ERR_INVALID_ARG; nothing is enqueued then.
+ *   - All work is enqueued on the caller's stream (a hipStream_t passed as
+ *     void*, NULL = the null stream).  No call synchronises the device.
+ *   - Arguments are validated on the host before anything is enqueued.  Errors
+ *     found there leave all outputs untouched.
+ *   - The handle owns a few KB of device memory (carry state of the layer
+ *     recurrence and cache cursors).  Calls on one handle must not overlap.
+ *   - Layers are addressed as a range [layer0, layer0 + n).  Tensor arguments hold
+ *     only the n layers of the call, layer-major.  madakv_allocate and
+ *     madakv_select_gather carry state from layer to layer and must be called in
+ *     increasing layer order, starting at layer 0 (which resets the state).
+ *   - Modality ids: 0 = text, 1 = image.  Query head j reads KV head j / G,
+ *     G = n_q_heads / n_kv_heads.
+ */
+#ifndef MADAKV_H
+#define MADAKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MADAKV_OK = 0,
+  MADAKV_ERR_INVALID_ARG = -1,        /* null / misaligned pointer, bad layer range, out of decode slack */
+  MADAKV_ERR_BAD_SHAPE = -2,          /* n_q_heads % n_kv_heads, window > ctx_len, unsupported head_dim ... */
+  MADAKV_ERR_BAD_BUDGET = -3,         /* budget <= window while budget < ctx_len */
+  MADAKV_ERR_WORKSPACE_TOO_SMALL = -4,
+  MADAKV_ERR_UNSUPPORTED_DTYPE = -5,
+  MADAKV_ERR_HIP = -6,                /* see madakv_last_hip_error */
+  MADAKV_ERR_UNIMPLEMENTED = -7
+} madakv_status;
+
+enum { MADAKV_FP32 = 0, MADAKV_BF16 = 1 };
+
+/* Hyper-parameters and shapes.  The paper names the proxy-token count, theta and
+ * the layer budget (Sec. 3.3) without giving values; they are set here. */
+typedef struct {
+  int32_t n_layers;        /* 1 .. 1024 */
+  int32_t batch;           /* >= 1 */
+  int32_t n_q_heads;       /* multiple of n_kv_heads */
+  int32_t n_kv_heads;      /* 1 .. 64 */
+  int32_t head_dim;        /* 64 or 128 */
+  int32_t ctx_len;         /* L, prompt length, <= 2^20 */
+  int32_t window;          /* W = number of proxy tokens (the last W prompt positions); G*W <= 256 */
+  int32_t budget;          /* tokens kept per KV head per layer, window included; >= ctx_len keeps all */
+  int32_t dtype;           /* MADAKV_FP32 / MADAKV_BF16: type of Q, K, V and of the reduced cache */
+  int32_t pool_k;          /* odd, 1 .. 63: max-pool width on the scores used for ranking; 1 = none */
+  int32_t mpa_mode;        /* 1 = Eq. 8 modality split; 0 = modality-agnostic top-k */
+  int32_t hcc_mode;        /* 1 = Eq. 9-11 compensation; 0 = every head gets budget - window */
+  int32_t hcc_rho;         /* >= 1: demand clamp ratio around the running nominal budget */
+  float   theta;           /* Eq. 9 threshold, in (0, 1] */
+  float   softmax_scale;   /* 0 = 1/sqrt(head_dim) */
+  int32_t max_new_tokens;  /* decode slack per head in the reduced cache */
+  int32_t out_fp32;        /* decode output: 1 = float, 0 = same as dtype */
+} madakv_config;
+
+/* Per-head statistics that madakv_score hands to madakv_allocate. */
+typedef struct {
+  float   w_t, w_v;        /* Eq. 6 attention mass on text / image candidates */
+  int32_t k_t, k_v;        /* Eq. 9 theta-mass counts */
+} madakv_head_stats;
+
+typedef struct madakv_handle madakv_handle;
+
+/* Creates a handle on the current HIP device.  *out is set only on success.
+ * Errors: INVALID_ARG (null), BAD_SHAPE, BAD_BUDGET, UNSUPPORTED_DTYPE, HIP. */
+int32_t madakv_create(const madakv_config* cfg, madakv_handle** out);
+int32_t madakv_destroy(madakv_handle* h);
+
+/* hipError_t of the last failing HIP call made through this handle (0 if none). */
+int32_t madakv_last_hip_error(const madakv_handle* h);
+
+/* Bytes of caller-provided scratch each call needs when it covers n layers (the
+ * worst case over layer ranges of that size).  Any out pointer may be NULL. */
+int32_t madakv_workspace_bytes(const madakv_handle* h, int32_t n_layers_per_call,
+                               size_t* score_ws, size_t* select_ws, size_t* decode_ws);
+
+/* Rows (tokens) the reduced cache k_c / v_c and kept_idx must hold for the whole
+ * model: n_layers * batch * n_kv_heads * (min(budget, ctx_len) + max_new_tokens).
+ * Known without a device sync because the sum of budgets is conserved exactly. */
+int32_t madakv_compact_capacity_tokens(const madakv_handle* h, int64_t* tokens);
+
+/* Eq. 7, Eq. 6, Eq. 9 and pooling for layers [layer0, layer0 + n).
+ *   q_win    [n, B, Hq, W, d]  queries of the last W prompt positions
+ *   k        [n, B, H, L, d]   prompt keys
+ *   mask     [B, L] uint8      modality id per position
+ *   psi      [n, B, H, L]      out: psi(i) = sum over the G*W proxy rows of the causal
+ *                              softmax(scale * q k^T) they pay to key i
+ *   psi_pool [n, B, H, L-W]    out: max of psi over |j - i| <= (pool_k-1)/2 within the
+ *                              candidates [0, L-W)
+ *   stats    [n, B, H]         out: w_t, w_v, k_t, k_v over the candidates
+ *   n_mod    [B, 2] int32      out: candidate count per modality
+ * ws / ws_bytes: scratch of at least score_ws bytes. */
+int32_t madakv_score(madakv_handle* h, int32_t layer0, int32_t n,
+                     const void* q_win, const void* k, const uint8_t* mask,
+                     float* psi, float* psi_pool, madakv_head_stats* stats, int32_t* n_mod,
+                     void* ws, size_t ws_bytes, void* stream);
+
+/* Eq. 8, Eq. 10-11 for layers [layer0, layer0 + n) in order.
+ *   stats    [n, B, H]        from madakv_score
+ *   n_mod    [B, 2]
+ *   budgets  [n, B, H, 2] int32  out: (b_t, b_v) candidate tokens to keep per modality;
+ *                              b_t + b_v summed over the whole model and over heads is
+ *                              exactly n_layers * H * (budget - W) per batch item.
+ *                              With mpa_mode = 0 the head total is in b_t and b_v = 0.
+ * The remaining pool of each batch item is carried in the handle; layer0 = 0 resets it. */
+int32_t madakv_allocate(madakv_handle* h, int32_t layer0, int32_t n,
+                        const madakv_head_stats* stats, const int32_t* n_mod,
+                        int32_t* budgets, void* stream);
+
+/* Per head and modality: keep the b_m candidates with the largest psi_pool (equal scores:
+ * lower position first), in ascending position, then the W window positions; copy their
+ * K and V rows into the reduced cache.
+ *   psi_pool [n, B, H, L-W], mask [B, L], budgets [n, B, H, 2] (0 <= b_m <= n_mod[m])
+ *   k, v     [n, B, H, L, d]
+ *   kept_idx int32, ragged  out: head (l,b,h) owns kept_idx[kv_off .. kv_off + kv_len)
+ *   kv_off   [n, B, H] int64 out: first row of the head's segment in k_c / v_c / kept_idx
+ *   kv_len   [n, B, H] int32 out: b_t + b_v + W
+ *   k_c, v_c [capacity_tokens, d]  out: the reduced cache; a head's segment has kv_len
+ *                              rows followed by max_new_tokens free rows
+ * Batch item b owns rows [b, b+1) * capacity_tokens / B; inside, layers then heads follow
+ * each other.  Budgets from madakv_allocate fill that space exactly.  If hand-made budgets
+ * add up to more, the first head that does not fit and every head after it in the batch
+ * item get an empty segment (kv_len = 0): nothing is written for them, decode neither
+ * appends to them nor produces a finite output for them.  The write cursor per batch item is carried in the handle; layer0 = 0
+ * resets it.  The decode-step counters of the layers in the call are reset. */
+int32_t madakv_select_gather(madakv_handle* h, int32_t layer0, int32_t n,
+                             const float* psi_pool, const uint8_t* mask, const int32_t* budgets,
+                             const void* k, const void* v,
+                             int32_t* kept_idx, int64_t* kv_off, int32_t* kv_len,
+                             void* k_c, void* v_c,
+                             void* ws, size_t ws_bytes, void* stream);
+
+/* One decode step for layers [layer0, layer0 + n): append k_new, v_new to every head's
+ * segment (Eq. 4), then out = softmax(scale * q k_c^T) v_c over the head's rows (Eq. 5).
+ *   q        [n, B, Hq, d]
+ *   k_new, v_new [n, B, H, d]  both NULL = attend only
+ *   k_c, v_c, kv_off          as produced by madakv_select_gather
+ *   kv_len   [n, B, H]        in/out: incremented by the append
+ *   out      [n, B, Hq, d]    float if out_fp32 else dtype
+ * INVALID_ARG if a layer in the range has already appended max_new_tokens rows. */
+int32_t madakv_decode_attn(madakv_handle* h, int32_t layer0, int32_t n,
+                           const void* q, const void* k_new, const void* v_new,
+                           void* k_c, void* v_c, const int64_t* kv_off, int32_t* kv_len,
+                           void* out, void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MADAKV_H */

@@ -1,0 +1,108 @@
+// Shared device helpers and the launcher interface between the C ABI and the kernels.
+// gfx950 (MI355X) only: 64-lane wavefronts, DPP row operations, bf16 MFMA.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/madakv.h"
+
+namespace madakv {
+
+// Shapes of one call (n layers of the configured model).
+struct Dims {
+  int n;        // layers in the call
+  int B, Hq, H, G;
+  int d;        // head_dim
+  int L, W;     // context length, proxy-token count
+  int M;        // G * W proxy rows per KV head
+  int nc;       // L - W candidates
+  int heads;    // n * B * H
+};
+
+struct ScorePlan { int nsplit; int chunk; int mpad; int group_heads; };
+struct DecodePlan { int nsplit; };
+
+ScorePlan score_plan(const Dims& dm, int dtype);
+DecodePlan decode_plan(const Dims& dm);
+size_t score_ws_bytes(const Dims& dm, int dtype);
+size_t select_ws_bytes(const Dims& dm, const madakv_config& c);
+size_t decode_ws_bytes(const Dims& dm);
+
+// Each launcher validates nothing: shapes were checked by the ABI layer.
+hipError_t launch_score(const Dims& dm, const madakv_config& c, const void* q_win, const void* k,
+                        float* psi, void* ws, hipStream_t st);
+hipError_t launch_stats(const Dims& dm, const madakv_config& c, const float* psi, const uint8_t* mask,
+                        float* psi_pool, madakv_head_stats* stats, int32_t* n_mod, int layer0, hipStream_t st);
+hipError_t launch_allocate(const Dims& dm, const madakv_config& c, int layer0, const madakv_head_stats* stats,
+                           const int32_t* n_mod, int32_t* budgets, long long* pool_state, hipStream_t st);
+hipError_t launch_offsets(const Dims& dm, const madakv_config& c, int layer0, const int32_t* budgets,
+                          int64_t* kv_off, int32_t* kv_len, long long* cursor_state, void* ws,
+                          long long region_tokens, int blocks_per_batch, hipStream_t st);
+hipError_t launch_select(const Dims& dm, const madakv_config& c, const float* psi_pool, const uint8_t* mask,
+                         const int32_t* budgets, const int64_t* kv_off, const int32_t* kv_len, int32_t* kept_idx,
+                         hipStream_t st);
+hipError_t launch_gather(const Dims& dm, const madakv_config& c, const void* k, const void* v,
+                         const int32_t* kept_idx, const int64_t* kv_off, const int32_t* kv_len,
+                         void* k_c, void* v_c, const void* ws, long long region_tokens,
+                         int blocks_per_batch, hipStream_t st);
+hipError_t launch_decode(const Dims& dm, const madakv_config& c, const void* q, const void* k_new,
+                         const void* v_new, void* k_c, void* v_c, const int64_t* kv_off, int32_t* kv_len,
+                         void* out, void* ws, long long capacity_tokens, hipStream_t st);
+
+constexpr int GATHER_ROWS = 64;   // rows of the reduced cache one gather workgroup fills
+
+#ifdef __HIPCC__
+// ---------------------------------------------------------------- device helpers
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+__device__ __forceinline__ float bf16_lo(uint32_t pair) { return __uint_as_float(pair << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t pair) { return __uint_as_float(pair & 0xffff0000u); }
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);   // NaN stays NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float load_elem(const float* p, long long i) { return p[i]; }
+__device__ __forceinline__ float load_elem(const uint16_t* p, long long i) { return bf16_bits_to_f32(p[i]); }
+
+// Sum over the 16 lanes of a DPP row; every lane of the row ends with the total.
+__device__ __forceinline__ float row16_sum(float x) {
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x141, 0xF, 0xF, true));  // row_half_mirror
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x140, 0xF, 0xF, true));  // row_mirror
+  return x;
+}
+
+__device__ __forceinline__ float wave_sum(float x) {
+  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+  return x;
+}
+__device__ __forceinline__ float wave_max(float x) {
+  for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
+  return x;
+}
+__device__ __forceinline__ long long shfl_i64(long long v, int src) {
+  int lo = __shfl((int)(v & 0xffffffffLL), src, 64);
+  int hi = __shfl((int)(v >> 32), src, 64);
+  return ((long long)hi << 32) | (unsigned int)lo;
+}
+__device__ __forceinline__ long long wave_sum_i64(long long v) {
+  for (int o = 32; o > 0; o >>= 1) {
+    int lo = __shfl_xor((int)(v & 0xffffffffLL), o, 64);
+    int hi = __shfl_xor((int)(v >> 32), o, 64);
+    v += ((long long)hi << 32) | (unsigned int)lo;
+  }
+  return v;
+}
+
+// Order-preserving map float -> uint32 (larger float, larger key); -0 is folded onto +0.
+__device__ __forceinline__ uint32_t float_key(float f) {
+  f += 0.0f;
+  uint32_t u = __float_as_uint(f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+#endif
+
+}  // namespace madakv

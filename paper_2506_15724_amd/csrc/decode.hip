@@ -1,0 +1,295 @@
+// Decode over the reduced, ragged cache (paper Sec. 3.1 Eq. 3-5): append the new K/V row to
+// every head's segment (Eq. 4), then out = softmax(scale * q K_c^T) V_c over the rows the
+// head kept (Eq. 5).  The G query heads of a KV head share one pass over its K_c and V_c.
+//
+// This is bandwidth work: 2 * len * d * sizeof(T) bytes per KV head and step, a few flops
+// per byte.  A row is LPR lanes x 16 bytes; a wave reads 64 / LPR rows per load
+// instruction and keeps UNROLL K rows and UNROLL V rows in flight.  The dot product is
+// reduced over the LPR lanes of a row with DPP row operations, the softmax is the usual
+// running max / running sum in the log2 domain with fp32 accumulation.  Each head's rows
+// are cut into `nsplit` equal ranges (one workgroup each) so that a single layer's 128
+// heads still fill 256 CUs; a second kernel merges the partial (max, sum, acc) triples in
+// a fixed order.  The appended row is taken from k_new / v_new by the workgroup whose range
+// holds it, which also stores it in the cache; kv_len is bumped by whoever finalises the
+// head.
+#include "common.h"
+
+#include <algorithm>
+
+namespace madakv {
+
+constexpr float DNEG_BIG = -1.0e30f;
+constexpr int DEC_THREADS = 256;
+
+struct DecodeArgs {
+  const void* q; const void* k_new; const void* v_new; void* k_c; void* v_c;
+  const int64_t* kv_off; int32_t* kv_len; void* out; float* part;
+  int B, H, G, d, nsplit, out_fp32, has_new;
+  long long capacity;   // rows in k_c / v_c
+  float scale_log2;
+};
+
+template <int LPR> __device__ __forceinline__ float row_sum(float x);
+template <> __device__ __forceinline__ float row_sum<16>(float x) { return row16_sum(x); }
+template <> __device__ __forceinline__ float row_sum<8>(float x) {
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true));
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true));
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x141, 0xF, 0xF, true));
+  return x;
+}
+template <> __device__ __forceinline__ float row_sum<32>(float x) {
+  x = row16_sum(x);
+  return x + __shfl_xor(x, 16, 64);
+}
+
+template <typename T> struct Elems;
+template <> struct Elems<uint16_t> {
+  static constexpr int EPL = 8;
+  static __device__ __forceinline__ void unpack(const uint4& r, float* f) {
+    f[0] = bf16_lo(r.x); f[1] = bf16_hi(r.x); f[2] = bf16_lo(r.y); f[3] = bf16_hi(r.y);
+    f[4] = bf16_lo(r.z); f[5] = bf16_hi(r.z); f[6] = bf16_lo(r.w); f[7] = bf16_hi(r.w);
+  }
+};
+template <> struct Elems<float> {
+  static constexpr int EPL = 4;
+  static __device__ __forceinline__ void unpack(const uint4& r, float* f) {
+    f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y); f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
+  }
+};
+
+template <typename T, int LPR, int GT, int UNROLL>
+__global__ __launch_bounds__(DEC_THREADS) void decode_attn_kernel(DecodeArgs a) {
+  constexpr int EPL = Elems<T>::EPL;
+  constexpr int RPI = 64 / LPR;
+  constexpr int D = LPR * EPL;
+  __shared__ float s_ml[4][GT][2];
+  __shared__ float s_acc[4][GT][D];
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane / LPR, piece = lane % LPR;
+  const int split = blockIdx.x;
+  const long long hidx = blockIdx.y;                 // (layer, batch, kv head) of the call
+  const long long lb = hidx / a.H;
+  const int h = (int)(hidx % a.H);
+  const int len_old = a.kv_len[hidx];
+  const long long off = a.kv_off[hidx];
+  // an empty segment (its budgets did not fit the cache) stays empty: no append, output 0/0 = NaN
+  const bool can_append = a.has_new && len_old > 0 && off + len_old < a.capacity;
+  const int len = len_old + (can_append ? 1 : 0);
+
+  // rows [r_begin, r_end) of this split: equal ranges rounded up to whole workgroup strides
+  constexpr int STRIDE = 4 * RPI * UNROLL;
+  int per = (len + a.nsplit - 1) / a.nsplit;
+  per = (per + STRIDE - 1) / STRIDE * STRIDE;
+  const int r_begin = split * per;
+  const int r_end = min(len, r_begin + per);
+
+  // queries of the group, pre-multiplied by scale * log2(e)
+  float qf[GT][EPL];
+  const T* qg = reinterpret_cast<const T*>(a.q) + (lb * a.H + h) * (long long)a.G * D;
+#pragma unroll
+  for (int g = 0; g < GT; ++g) {
+    uint4 raw = make_uint4(0, 0, 0, 0);
+    if (g < a.G) raw = *reinterpret_cast<const uint4*>(qg + (long long)g * D + piece * EPL);
+    Elems<T>::unpack(raw, qf[g]);
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) qf[g][e] *= a.scale_log2;
+  }
+
+  float m[GT], l[GT], acc[GT][EPL];
+#pragma unroll
+  for (int g = 0; g < GT; ++g) {
+    m[g] = DNEG_BIG; l[g] = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
+  }
+
+  const uint4* kc = reinterpret_cast<const uint4*>(a.k_c);
+  const uint4* vc = reinterpret_cast<const uint4*>(a.v_c);
+  const uint4* kn = reinterpret_cast<const uint4*>(a.k_new);
+  const uint4* vn = reinterpret_cast<const uint4*>(a.v_new);
+
+  for (int row0 = r_begin + wave * RPI * UNROLL; row0 < r_end; row0 += STRIDE) {
+    uint4 kraw[UNROLL], vraw[UNROLL];
+    bool valid[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      const int r = row0 + u * RPI + sub;
+      valid[u] = r < r_end;
+      kraw[u] = make_uint4(0, 0, 0, 0); vraw[u] = make_uint4(0, 0, 0, 0);
+      if (valid[u]) {
+        if (can_append && r == len_old) {
+          kraw[u] = kn[hidx * LPR + piece];
+          vraw[u] = vn[hidx * LPR + piece];
+          reinterpret_cast<uint4*>(a.k_c)[(off + r) * LPR + piece] = kraw[u];     // Eq. 4: the row joins the cache
+          reinterpret_cast<uint4*>(a.v_c)[(off + r) * LPR + piece] = vraw[u];
+        } else {
+          kraw[u] = kc[(off + r) * LPR + piece];
+          vraw[u] = vc[(off + r) * LPR + piece];
+        }
+      }
+    }
+    float s[UNROLL][GT];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      float kf[EPL];
+      Elems<T>::unpack(kraw[u], kf);
+#pragma unroll
+      for (int g = 0; g < GT; ++g) {
+        float dot = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) dot = fmaf(qf[g][e], kf[e], dot);
+        s[u][g] = row_sum<LPR>(dot);
+      }
+    }
+    float vf[UNROLL][EPL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) Elems<T>::unpack(vraw[u], vf[u]);
+#pragma unroll
+    for (int g = 0; g < GT; ++g) {
+      float mx = m[g];
+#pragma unroll
+      for (int u = 0; u < UNROLL; ++u) mx = valid[u] ? fmaxf(mx, s[u][g]) : mx;
+      const float sc = exp2f(m[g] - mx);
+      l[g] *= sc;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc[g][e] *= sc;
+#pragma unroll
+      for (int u = 0; u < UNROLL; ++u) {
+        const float p = valid[u] ? exp2f(s[u][g] - mx) : 0.f;
+        l[g] += p;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(p, vf[u][e], acc[g][e]);
+      }
+      m[g] = mx;
+    }
+  }
+
+  // merge the RPI row groups of the wave (fixed butterfly), then the 4 waves through LDS
+#pragma unroll
+  for (int g = 0; g < GT; ++g) {
+    for (int o = LPR; o < 64; o <<= 1) {
+      const float m2 = __shfl_xor(m[g], o, 64), l2 = __shfl_xor(l[g], o, 64);
+      const float mx = fmaxf(m[g], m2);
+      const float c1 = exp2f(m[g] - mx), c2 = exp2f(m2 - mx);
+      l[g] = l[g] * c1 + l2 * c2;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) {
+        const float a2 = __shfl_xor(acc[g][e], o, 64);
+        acc[g][e] = acc[g][e] * c1 + a2 * c2;
+      }
+      m[g] = mx;
+    }
+    if (sub == 0) {
+      if (piece == 0) { s_ml[wave][g][0] = m[g]; s_ml[wave][g][1] = l[g]; }
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) s_acc[wave][g][piece * EPL + e] = acc[g][e];
+    }
+  }
+  __syncthreads();
+  // thread t < D finishes element t of every query head of the group
+  const int t = threadIdx.x;
+  if (t < D) {
+    for (int g = 0; g < a.G; ++g) {
+      float mx = DNEG_BIG;
+      for (int w = 0; w < 4; ++w) mx = fmaxf(mx, s_ml[w][g][0]);
+      float ls = 0.f, av = 0.f;
+      for (int w = 0; w < 4; ++w) {
+        const float c = exp2f(s_ml[w][g][0] - mx);
+        ls += s_ml[w][g][1] * c;
+        av += s_acc[w][g][t] * c;
+      }
+      if (a.nsplit == 1) {
+        const long long o = ((lb * a.H + h) * (long long)a.G + g) * D + t;
+        const float val = av / ls;
+        if (a.out_fp32) reinterpret_cast<float*>(a.out)[o] = val;
+        else if (sizeof(T) == 2) reinterpret_cast<uint16_t*>(a.out)[o] = f32_to_bf16_rne(val);
+        else reinterpret_cast<float*>(a.out)[o] = val;
+      } else {
+        float* p = a.part + ((hidx * a.nsplit + split) * a.G + g) * (long long)(D + 2);
+        p[t] = av;
+        if (t == 0) { p[D] = mx; p[D + 1] = ls; }
+      }
+    }
+  }
+  if (a.nsplit == 1 && can_append && threadIdx.x == 0) a.kv_len[hidx] = len;
+}
+
+// Merges the nsplit partials of each head in split order; also stores the new length.
+template <typename T>
+__global__ __launch_bounds__(128) void decode_merge_kernel(DecodeArgs a) {
+  const long long hidx = blockIdx.x;
+  const long long lb = hidx / a.H;
+  const int h = (int)(hidx % a.H);
+  const int D = a.d;
+  const int t = threadIdx.x;
+  if (t < D) {
+    for (int g = 0; g < a.G; ++g) {
+      float mx = DNEG_BIG;
+      for (int s = 0; s < a.nsplit; ++s) mx = fmaxf(mx, a.part[((hidx * a.nsplit + s) * a.G + g) * (long long)(D + 2) + D]);
+      float ls = 0.f, av = 0.f;
+      for (int s = 0; s < a.nsplit; ++s) {
+        const float* p = a.part + ((hidx * a.nsplit + s) * a.G + g) * (long long)(D + 2);
+        const float c = exp2f(p[D] - mx);
+        ls += p[D + 1] * c;
+        av += p[t] * c;
+      }
+      const long long o = ((lb * a.H + h) * (long long)a.G + g) * D + t;
+      const float val = av / ls;
+      if (a.out_fp32) reinterpret_cast<float*>(a.out)[o] = val;
+      else if (sizeof(T) == 2) reinterpret_cast<uint16_t*>(a.out)[o] = f32_to_bf16_rne(val);
+      else reinterpret_cast<float*>(a.out)[o] = val;
+    }
+  }
+  if (a.has_new && t == 0) {
+    const int len_old = a.kv_len[hidx];
+    if (len_old > 0 && a.kv_off[hidx] + len_old < a.capacity) a.kv_len[hidx] = len_old + 1;
+  }
+}
+
+DecodePlan decode_plan(const Dims& dm) {
+  DecodePlan p;
+  int ns = (1024 + dm.heads - 1) / dm.heads;
+  p.nsplit = std::max(1, std::min(ns, 16));
+  return p;
+}
+
+size_t decode_ws_bytes(const Dims& dm) {
+  DecodePlan p = decode_plan(dm);
+  return (size_t)dm.heads * p.nsplit * dm.G * (dm.d + 2) * sizeof(float) + 64;
+}
+
+template <typename T, int LPR>
+static hipError_t launch_decode_t(const Dims& dm, DecodeArgs& a, hipStream_t st) {
+  dim3 grid(a.nsplit, dm.heads), block(DEC_THREADS);
+  if (dm.G == 1) hipLaunchKernelGGL((decode_attn_kernel<T, LPR, 1, 8>), grid, block, 0, st, a);
+  else if (dm.G == 2) hipLaunchKernelGGL((decode_attn_kernel<T, LPR, 2, 4>), grid, block, 0, st, a);
+  else if (dm.G <= 4) hipLaunchKernelGGL((decode_attn_kernel<T, LPR, 4, 4>), grid, block, 0, st, a);
+  else hipLaunchKernelGGL((decode_attn_kernel<T, LPR, 8, 2>), grid, block, 0, st, a);
+  if (a.nsplit > 1) hipLaunchKernelGGL((decode_merge_kernel<T>), dim3(dm.heads), dim3(128), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_decode(const Dims& dm, const madakv_config& c, const void* q, const void* k_new,
+                         const void* v_new, void* k_c, void* v_c, const int64_t* kv_off, int32_t* kv_len,
+                         void* out, void* ws, long long capacity_tokens, hipStream_t st) {
+  DecodeArgs a;
+  a.capacity = capacity_tokens;
+  a.q = q; a.k_new = k_new; a.v_new = v_new; a.k_c = k_c; a.v_c = v_c; a.kv_off = kv_off; a.kv_len = kv_len;
+  a.out = out; a.part = reinterpret_cast<float*>(ws);
+  a.B = dm.B; a.H = dm.H; a.G = dm.G; a.d = dm.d; a.nsplit = decode_plan(dm).nsplit;
+  a.out_fp32 = c.out_fp32; a.has_new = (k_new != nullptr) ? 1 : 0;
+  const float scale = c.softmax_scale > 0.f ? c.softmax_scale : 1.0f / sqrtf((float)dm.d);
+  a.scale_log2 = scale * 1.4426950408889634f;
+  const int lpr = dm.d * (c.dtype == MADAKV_BF16 ? 2 : 4) / 16;
+  if (c.dtype == MADAKV_BF16) {
+    if (lpr == 8) return launch_decode_t<uint16_t, 8>(dm, a, st);
+    if (lpr == 16) return launch_decode_t<uint16_t, 16>(dm, a, st);
+  } else {
+    if (lpr == 16) return launch_decode_t<float, 16>(dm, a, st);
+    if (lpr == 32) return launch_decode_t<float, 32>(dm, a, st);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace madakv

@@ -1,0 +1,258 @@
+// Eviction (paper Sec. 3.3, modality-specific eviction per attention head): for each head
+// keep, per modality, the b_m candidates with the largest pooled score; equal scores go to
+// the lower position.  Output: kept positions in ascending order, then the W window
+// positions, written into the head's segment of the ragged index array.
+//
+// offsets_kernel   lays the segments out: batch item b owns a fixed region of the reduced
+//                  cache, inside it layers and heads follow each other; a segment has
+//                  kv_len = b_t + b_v + W rows plus max_new_tokens free rows.  It also fills
+//                  a table "first head that overlaps each 64-row block" for the gather.
+// select_kernel    one workgroup per head.  A 3-level radix select (11 + 11 + 10 bits of the
+//                  order-preserving key) on LDS count histograms finds, per modality, the
+//                  threshold key tau_m and how many elements equal to tau_m are still
+//                  needed; one ordered pass then keeps key > tau_m, and key == tau_m while
+//                  its running rank (by position) is below that number.  Block-wide prefix
+//                  sums give the output slots, so the result is ascending by construction.
+#include "common.h"
+
+namespace madakv {
+
+constexpr int SEL_THREADS = 1024;
+constexpr int SEL_BINS = 2048;
+constexpr int SEL_ITEMS = 4;                     // consecutive candidates per thread per pass
+
+struct OffsetsArgs {
+  const int32_t* budgets; int64_t* kv_off; int32_t* kv_len; long long* cursor; int32_t* blk2head; long long* call_range;
+  int n, B, H, L, W, layer0, max_new, keep_all, blocks_per_batch;
+  long long region_tokens;
+};
+
+// One workgroup, wave w handles batch items w, w+nw, ...; lanes are heads.
+__global__ __launch_bounds__(256) void offsets_kernel(OffsetsArgs a) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  for (int b = wave; b < a.B; b += nw) {
+    long long cur = (a.layer0 == 0) ? 0 : a.cursor[b];
+    const long long start = cur;
+    const long long region = (long long)b * a.region_tokens;
+    for (int li = 0; li < a.n; ++li) {
+      const long long idx = ((long long)li * a.B + b) * a.H + lane;
+      long long len = 0;
+      if (lane < a.H) len = a.keep_all ? a.L : (long long)a.budgets[idx * 2] + a.budgets[idx * 2 + 1] + a.W;
+      long long seg = (lane < a.H) ? len + a.max_new : 0;
+      long long incl = seg;                                    // inclusive scan over heads
+      for (int o = 1; o < 64; o <<= 1) {
+        long long t = shfl_i64(incl, max(lane - o, 0));
+        if (lane >= o) incl += t;
+      }
+      // Budgets that do not add up to the configured total could run past the batch item's
+      // region: the first head that does not fit, and every head after it, gets an empty
+      // segment (kv_len 0) at the end of what was laid out, so nothing is written outside.
+      const bool fits = cur + incl <= a.region_tokens;
+      const unsigned long long fitmask = __ballot(fits || lane >= a.H);
+      const int first_bad = fitmask == ~0ULL ? 64 : __ffsll((long long)~fitmask) - 1;
+      const long long used = first_bad == 0 ? 0 : shfl_i64(incl, max(first_bad - 1, 0));
+      if (lane >= first_bad) { len = 0; seg = 0; incl = used; }
+      const long long off = cur + incl - seg;                  // relative to the region start
+      if (lane < a.H) {
+        a.kv_off[idx] = region + off;
+        a.kv_len[idx] = (int32_t)len;
+        // blocks whose first row lies inside this segment
+        const long long b0 = (off + GATHER_ROWS - 1) / GATHER_ROWS, b1 = seg > 0 ? (off + seg - 1) / GATHER_ROWS : b0 - 1;
+        const long long blk_base = start / GATHER_ROWS;       // table is relative to the call's first block
+        for (long long blk = b0; blk <= b1; ++blk) {
+          long long t = blk - blk_base;
+          if (t >= 0 && t < a.blocks_per_batch) a.blk2head[(long long)b * a.blocks_per_batch + t] = li * a.H + lane;
+        }
+        if (li == 0 && lane == 0 && (start % GATHER_ROWS) != 0 && 0 < a.blocks_per_batch)
+          a.blk2head[(long long)b * a.blocks_per_batch] = 0;  // the call starts inside a block: its first head is head 0
+      }
+      cur += shfl_i64(incl, 63);
+    }
+    if (lane == 0) {
+      a.cursor[b] = cur;
+      a.call_range[b * 2] = start;
+      a.call_range[b * 2 + 1] = cur;
+    }
+  }
+}
+
+struct SelectArgs {
+  const float* psi_pool; const uint8_t* mask; const int32_t* budgets; const int64_t* kv_off; const int32_t* kv_len; int32_t* kept_idx;
+  int B, H, L, W, nc, mpa_mode, keep_all;
+};
+
+// exclusive prefix over the workgroup of a packed pair (lo16 | hi16 counts fit: <= 4096 per pass)
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* wave_tot, uint32_t& total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint32_t incl = v;
+  for (int o = 1; o < 64; o <<= 1) {
+    uint32_t t = (uint32_t)__shfl((int)incl, max(lane - o, 0), 64);
+    if (lane >= o) incl += t;
+  }
+  if (lane == 63) wave_tot[wave] = incl;
+  __syncthreads();
+  uint32_t before = 0, tot = 0;
+  for (int w = 0; w < SEL_THREADS / 64; ++w) {
+    uint32_t t = wave_tot[w];
+    if (w < wave) before += t;
+    tot += t;
+  }
+  __syncthreads();
+  total = tot;
+  return before + incl - v;
+}
+
+__global__ __launch_bounds__(SEL_THREADS) void select_kernel(SelectArgs a) {
+  __shared__ uint32_t cnt[2][SEL_BINS];
+  __shared__ uint32_t s_prefix[2], s_need[2], s_done[2];
+  __shared__ uint32_t wave_tot[SEL_THREADS / 64];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int head = blockIdx.x;
+  const int b = (head / a.H) % a.B;
+  const float* sc = a.psi_pool + (long long)head * a.nc;
+  const uint8_t* mask = a.mask + (long long)b * a.L;
+  int32_t* out = a.kept_idx + a.kv_off[head];
+
+  if (a.kv_len[head] == 0) return;               // the segment did not fit the region: nothing to write
+  if (a.keep_all) {
+    for (int i = tid; i < a.L; i += SEL_THREADS) out[i] = i;
+    return;
+  }
+  const uint32_t bud[2] = {(uint32_t)a.budgets[head * 2], (uint32_t)a.budgets[head * 2 + 1]};
+  const int shifts[3] = {21, 10, 0};
+  const int widths[3] = {11, 11, 10};
+
+  for (int level = 0; level < 3; ++level) {
+    for (int e = tid; e < 2 * SEL_BINS; e += SEL_THREADS) (&cnt[0][0])[e] = 0;
+    __syncthreads();
+    const int sh = shifts[level], wd = widths[level];
+    for (int i = tid; i < a.nc; i += SEL_THREADS) {
+      const int m = (a.mpa_mode && mask[i]) ? 1 : 0;
+      const uint32_t key = float_key(sc[i]);
+      bool match = true;
+      if (level > 0) match = (s_done[m] == 0) && ((key >> (sh + wd)) == s_prefix[m]);
+      if (match) atomicAdd(&cnt[m][(key >> sh) & ((1u << wd) - 1u)], 1u);
+    }
+    __syncthreads();
+    if (wave < 2) {
+      const int m = wave;
+      const int nb = 1 << wd;
+      const int per = (nb + 63) / 64;
+      uint32_t lc = 0;
+      for (int j = 0; j < per; ++j) { int bin = nb - 1 - (lane * per + j); if (bin >= 0) lc += cnt[m][bin]; }
+      uint32_t incl = lc;
+      for (int o = 1; o < 64; o <<= 1) {
+        uint32_t t = (uint32_t)__shfl((int)incl, max(lane - o, 0), 64);
+        if (lane >= o) incl += t;
+      }
+      uint32_t need, prefix_prev; bool done;
+      if (level == 0) {
+        const uint32_t ntot = (uint32_t)__shfl((int)incl, 63, 64);
+        need = bud[m] < ntot ? bud[m] : ntot;     // a budget above the candidate count keeps them all
+        done = (need == 0);
+        prefix_prev = 0;
+        if (lane == 0) { s_need[m] = need; s_done[m] = done ? 1u : 0u; s_prefix[m] = 0; }
+      } else {
+        need = s_need[m]; prefix_prev = s_prefix[m]; done = s_done[m] != 0;
+      }
+      const uint32_t before = incl - lc;          // elements in higher bins than this lane's
+      const bool mine = !done && before < need && before + lc >= need;
+      if (mine) {
+        uint32_t acc = before;
+        for (int j = 0; j < per; ++j) {
+          int bin = nb - 1 - (lane * per + j);
+          if (bin < 0) break;
+          uint32_t c = cnt[m][bin];
+          if (acc + c >= need) {
+            s_prefix[m] = (prefix_prev << wd) | (uint32_t)bin;
+            s_need[m] = need - acc;               // still needed from inside this bin
+            break;
+          }
+          acc += c;
+        }
+      }
+    }
+    __syncthreads();
+  }
+  // tau_m = s_prefix (full key); take every key > tau_m and the first s_need[m] keys == tau_m.
+  uint32_t tau[2], ties[2];
+  for (int m = 0; m < 2; ++m) {
+    if (s_done[m]) { tau[m] = 0xffffffffu; ties[m] = 0; }   // nothing to keep: no key exceeds or (needed) equals it
+    else { tau[m] = s_prefix[m]; ties[m] = s_need[m]; }
+  }
+  __syncthreads();
+
+  uint32_t run_eq[2] = {0, 0};
+  uint32_t run_out = 0;
+  for (int base = 0; base < a.nc; base += SEL_THREADS * SEL_ITEMS) {
+    const int i0 = base + tid * SEL_ITEMS;
+    uint32_t key[SEL_ITEMS]; int mod[SEL_ITEMS]; bool inr[SEL_ITEMS];
+    uint32_t eqpack = 0;
+#pragma unroll
+    for (int j = 0; j < SEL_ITEMS; ++j) {
+      const int i = i0 + j;
+      inr[j] = i < a.nc;
+      key[j] = inr[j] ? float_key(sc[i]) : 0u;
+      mod[j] = (inr[j] && a.mpa_mode && mask[i]) ? 1 : 0;
+      if (inr[j] && key[j] == tau[mod[j]] && ties[mod[j]] > 0) eqpack += mod[j] ? 0x10000u : 1u;
+    }
+    uint32_t eqtot;
+    uint32_t eqbefore = block_excl_scan(eqpack, wave_tot, eqtot);
+    uint32_t rank[2] = {run_eq[0] + (eqbefore & 0xffffu), run_eq[1] + (eqbefore >> 16)};
+    bool keep[SEL_ITEMS]; uint32_t nkeep = 0;
+#pragma unroll
+    for (int j = 0; j < SEL_ITEMS; ++j) {
+      keep[j] = false;
+      if (inr[j]) {
+        const int m = mod[j];
+        if (key[j] > tau[m]) keep[j] = true;
+        else if (key[j] == tau[m] && ties[m] > 0) { keep[j] = rank[m] < ties[m]; ++rank[m]; }
+      }
+      nkeep += keep[j] ? 1u : 0u;
+    }
+    uint32_t ktot;
+    uint32_t pos = run_out + block_excl_scan(nkeep, wave_tot, ktot);
+#pragma unroll
+    for (int j = 0; j < SEL_ITEMS; ++j) if (keep[j]) out[pos++] = i0 + j;
+    run_eq[0] += eqtot & 0xffffu; run_eq[1] += eqtot >> 16;
+    run_out += ktot;
+  }
+  for (int r = tid; r < a.W; r += SEL_THREADS) out[run_out + r] = a.nc + r;
+}
+
+size_t select_ws_bytes(const Dims& dm, const madakv_config& c) {
+  long long keep = std::min(c.budget, c.ctx_len);
+  long long per_batch_model = (long long)c.n_layers * dm.H * (keep + c.max_new_tokens);
+  long long per_batch_call = (long long)dm.n * dm.H * ((long long)dm.L + c.max_new_tokens);
+  long long tokens = std::min(per_batch_model, per_batch_call);
+  long long blocks = tokens / GATHER_ROWS + 2;
+  return (size_t)dm.B * blocks * sizeof(int32_t) + (size_t)dm.B * 2 * sizeof(long long) + 64;
+}
+
+hipError_t launch_offsets(const Dims& dm, const madakv_config& c, int layer0, const int32_t* budgets,
+                          int64_t* kv_off, int32_t* kv_len, long long* cursor_state, void* ws,
+                          long long region_tokens, int blocks_per_batch, hipStream_t st) {
+  OffsetsArgs a;
+  a.budgets = budgets; a.kv_off = kv_off; a.kv_len = kv_len; a.cursor = cursor_state;
+  a.call_range = reinterpret_cast<long long*>(ws);
+  a.blk2head = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(ws) + ((size_t)dm.B * 2 * sizeof(long long) + 63) / 64 * 64);
+  a.n = dm.n; a.B = dm.B; a.H = dm.H; a.L = dm.L; a.W = dm.W; a.layer0 = layer0;
+  a.max_new = c.max_new_tokens; a.keep_all = c.budget >= c.ctx_len ? 1 : 0;
+  a.blocks_per_batch = blocks_per_batch; a.region_tokens = region_tokens;
+  hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_select(const Dims& dm, const madakv_config& c, const float* psi_pool, const uint8_t* mask,
+                         const int32_t* budgets, const int64_t* kv_off, const int32_t* kv_len, int32_t* kept_idx,
+                         hipStream_t st) {
+  SelectArgs a;
+  a.psi_pool = psi_pool; a.mask = mask; a.budgets = budgets; a.kv_off = kv_off; a.kv_len = kv_len; a.kept_idx = kept_idx;
+  a.B = dm.B; a.H = dm.H; a.L = dm.L; a.W = dm.W; a.nc = dm.nc; a.mpa_mode = c.mpa_mode;
+  a.keep_all = c.budget >= c.ctx_len ? 1 : 0;
+  hipLaunchKernelGGL(select_kernel, dim3(dm.heads), dim3(SEL_THREADS), 0, st, a);
+  return hipGetLastError();
+}
+
+}  // namespace madakv

@@ -1,0 +1,168 @@
+// Per-head modality statistics over the candidates [0, L-W) (paper Sec. 3.3):
+//   Eq. 6  w_t, w_v   attention mass on text / image candidates
+//   Eq. 9  k_t, k_v   fewest top-scored tokens of a modality that cover theta of its mass
+// plus the max-pooled scores used for ranking, and the candidate counts per modality.
+//
+// One workgroup per (layer, batch, KV head).  Masses are summed in 64-bit fixed point
+// (2^-38 units): integer adds commute, so LDS atomics give the same bits on every run
+// and the counts k_m, which are integers decided by a mass threshold, are reproducible.
+// k_m is found without sorting by a radix descent on the float bit pattern (11 + 11 + 9
+// bits): each level histograms count and mass per bin for the elements that match the
+// prefix found so far and walks the bins from the top to the one where the running
+// mass crosses theta * w_m; the last level pins the threshold value tau exactly, and
+//   k_m = #{psi > tau} + ceil((theta w_m - mass{psi > tau}) / tau).
+#include "common.h"
+
+namespace madakv {
+
+constexpr int STATS_THREADS = 512;
+constexpr int BINS = 2048;
+constexpr float FX_SCALE = 274877906944.0f;      // 2^38
+constexpr float PSI_MAX = 256.0f;                // G * W <= 256 bounds any column sum
+
+struct StatsArgs {
+  const float* psi; const uint8_t* mask; float* psi_pool; madakv_head_stats* stats; int32_t* n_mod;
+  int B, H, L, W, nc, pool_r, layer0, mpa_mode;
+  double theta;
+};
+
+__device__ __forceinline__ unsigned long long to_fx(float v) {
+  v = fminf(fmaxf(v, 0.f), PSI_MAX);
+  return (unsigned long long)(v * FX_SCALE);      // exact product (power of two), truncating convert
+}
+__device__ __forceinline__ uint32_t nonneg_bits(float v) {
+  v = fminf(fmaxf(v, 0.f), PSI_MAX);
+  return __float_as_uint(v);                      // non-negative floats order like their bit patterns
+}
+
+__global__ __launch_bounds__(STATS_THREADS) void stats_kernel(StatsArgs a) {
+  __shared__ uint32_t cnt[2][BINS];
+  __shared__ unsigned long long sum[2][BINS];
+  __shared__ uint32_t s_prefix[2], s_cnt_gt[2], s_n[2], s_done[2], s_bincnt[2];
+  __shared__ unsigned long long s_sum_gt[2], s_w[2], s_target[2], s_binsum[2];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int head = blockIdx.x;
+  const int b = (head / a.H) % a.B;
+  const float* psi = a.psi + (long long)head * a.L;
+  const uint8_t* mask = a.mask + (long long)b * a.L;
+  float* pool = a.psi_pool + (long long)head * a.nc;
+
+  const int shifts[3] = {20, 9, 0};
+  const int widths[3] = {11, 11, 9};
+
+  for (int level = 0; level < 3; ++level) {
+    for (int e = tid; e < 2 * BINS; e += STATS_THREADS) { (&cnt[0][0])[e] = 0; (&sum[0][0])[e] = 0ULL; }
+    __syncthreads();
+    const int sh = shifts[level], wd = widths[level];
+    for (int i = tid; i < a.nc; i += STATS_THREADS) {
+      const float v = psi[i];
+      const int m = mask[i] ? 1 : 0;
+      if (level == 0) {
+        // pooled score for ranking: max over the clipped neighbourhood (raw values)
+        float mx = v;
+        for (int r = 1; r <= a.pool_r; ++r) {
+          if (i - r >= 0) mx = fmaxf(mx, psi[i - r]);
+          if (i + r < a.nc) mx = fmaxf(mx, psi[i + r]);
+        }
+        pool[i] = mx;
+      }
+      const uint32_t key = nonneg_bits(v);
+      bool match = true;
+      if (level > 0) match = (s_done[m] == 0) && ((key >> (sh + wd)) == s_prefix[m]);
+      if (match) {
+        const uint32_t bin = (key >> sh) & ((1u << wd) - 1u);
+        atomicAdd(&cnt[m][bin], 1u);
+        atomicAdd(&sum[m][bin], to_fx(v));
+      }
+    }
+    __syncthreads();
+    // wave m (0 = text, 1 = image) walks its histogram from the top bin down
+    if (wave < 2) {
+      const int m = wave;
+      const int nb = 1 << wd;
+      const int per = (nb + 63) / 64;                 // bins per lane; lane 0 owns the top bins
+      unsigned long long ls = 0ULL; uint32_t lc = 0;
+      for (int j = 0; j < per; ++j) {
+        int bin = nb - 1 - (lane * per + j);
+        if (bin >= 0) { ls += sum[m][bin]; lc += cnt[m][bin]; }
+      }
+      // inclusive scan over lanes (lane 0 first)
+      unsigned long long ss = ls; uint32_t sc = lc;
+      for (int o = 1; o < 64; o <<= 1) {
+        unsigned long long ts = (unsigned long long)shfl_i64((long long)ss, max(lane - o, 0));
+        uint32_t tc = (uint32_t)__shfl((int)sc, max(lane - o, 0), 64);
+        if (lane >= o) { ss += ts; sc += tc; }
+      }
+      // totals, target and the state carried from the level above; at level 0 every lane
+      // derives them from the scan, later levels read what was stored before the barrier
+      unsigned long long target, base_s; uint32_t base_c, prefix_prev; bool done;
+      if (level == 0) {
+        const unsigned long long wtot = (unsigned long long)shfl_i64((long long)ss, 63);
+        const uint32_t ntot = (uint32_t)__shfl((int)sc, 63, 64);
+        // smallest integer >= theta * w: the running mass c reaches theta*w iff c >= it
+        unsigned long long tg = (unsigned long long)ceil(a.theta * (double)wtot);
+        target = tg < wtot ? tg : wtot;
+        done = (wtot == 0ULL || ntot == 0u);
+        base_s = 0ULL; base_c = 0u; prefix_prev = 0u;
+        if (lane == 0) {
+          s_w[m] = wtot; s_n[m] = ntot; s_target[m] = target; s_done[m] = done ? 1u : 0u;
+          s_cnt_gt[m] = 0; s_sum_gt[m] = 0ULL; s_prefix[m] = 0; s_bincnt[m] = 0; s_binsum[m] = 0ULL;
+        }
+      } else {
+        target = s_target[m]; base_s = s_sum_gt[m]; base_c = s_cnt_gt[m];
+        prefix_prev = s_prefix[m]; done = s_done[m] != 0;
+      }
+      // the lane whose bins contain the crossing: mass before its bins < target <= mass after them
+      const unsigned long long before = base_s + ss - ls;
+      const bool mine = !done && (before < target) && (before + ls >= target);
+      if (mine) {
+        unsigned long long acc_s = before; uint32_t acc_c = base_c + sc - lc;
+        for (int j = 0; j < per; ++j) {
+          int bin = nb - 1 - (lane * per + j);
+          if (bin < 0) break;
+          unsigned long long bs = sum[m][bin];
+          if (acc_s + bs >= target) {
+            s_prefix[m] = (prefix_prev << wd) | (uint32_t)bin;
+            s_sum_gt[m] = acc_s; s_cnt_gt[m] = acc_c;
+            s_binsum[m] = bs; s_bincnt[m] = cnt[m][bin];
+            break;
+          }
+          acc_s += bs; acc_c += cnt[m][bin];
+        }
+      }
+    }
+    __syncthreads();
+  }
+
+  if (tid < 2) {
+    const int m = tid;
+    int32_t k = 0;
+    if (!s_done[m]) {
+      // s_prefix is now the full bit pattern of tau; every element in the last bin equals tau
+      const float tau = __uint_as_float(s_prefix[m]);
+      const unsigned long long q = to_fx(tau);
+      const unsigned long long need = s_target[m] - s_sum_gt[m];
+      unsigned long long t = q ? (need + q - 1ULL) / q : 1ULL;
+      if (t < 1ULL) t = 1ULL;
+      if (t > (unsigned long long)s_bincnt[m]) t = s_bincnt[m];
+      k = (int32_t)(s_cnt_gt[m] + (uint32_t)t);
+    }
+    const float w = (float)((double)s_w[m] * (1.0 / (double)FX_SCALE));
+    madakv_head_stats* st = a.stats + head;
+    if (m == 0) { st->w_t = w; st->k_t = k; } else { st->w_v = w; st->k_v = k; }
+    if (head < a.B * a.H && (head % a.H) == 0 && a.n_mod) a.n_mod[b * 2 + m] = (int32_t)s_n[m];
+  }
+}
+
+hipError_t launch_stats(const Dims& dm, const madakv_config& c, const float* psi, const uint8_t* mask,
+                        float* psi_pool, madakv_head_stats* stats, int32_t* n_mod, int layer0, hipStream_t st) {
+  StatsArgs a;
+  a.psi = psi; a.mask = mask; a.psi_pool = psi_pool; a.stats = stats; a.n_mod = n_mod;
+  a.B = dm.B; a.H = dm.H; a.L = dm.L; a.W = dm.W; a.nc = dm.nc; a.pool_r = (c.pool_k - 1) / 2;
+  a.layer0 = layer0; a.mpa_mode = c.mpa_mode; a.theta = (double)c.theta;
+  hipLaunchKernelGGL(stats_kernel, dim3(dm.heads), dim3(STATS_THREADS), 0, st, a);
+  return hipGetLastError();
+}
+
+}  // namespace madakv

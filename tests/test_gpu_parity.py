@@ -1,0 +1,422 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Sizes span several tiles and ragged tails but stay small enough for the
+oracle to finish in seconds.  Stage-isolated checks feed both sides the same upstream
+values; the free-running check runs the whole path and applies the near-tie rules."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import madakv_oracle as O
+from paper_2506_15724_amd import binding as MB
+from paper_2506_15724_amd import workloads as WL
+from tests import parity_utils as PU
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(msg):
+    print(f"[parity] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def small_workloads():
+    C = WL.CONFIGS
+    return {
+        "tiny_fp32": C["tiny"],
+        "bf16_mha": C["llava_layer"].scaled(name="bf16_mha", n_layers=3, batch=2, n_q_heads=4, n_kv_heads=4,
+                                            ctx_len=2000, budget=300, n_images=2, decode_steps=3),
+        "bf16_gqa7": C["qwen_gqa"].scaled(name="bf16_gqa7", n_layers=2, batch=1, n_q_heads=14, n_kv_heads=2,
+                                          ctx_len=1500, budget=200, image_tokens=(64, 300), text_tokens=(16, 128),
+                                          decode_steps=2),
+        "bf16_w64": C["long_128k"].scaled(name="bf16_w64", n_layers=1, batch=1, n_q_heads=3, n_kv_heads=3,
+                                          ctx_len=3000, budget=256, n_images=3, decode_steps=2),
+        "bf16_d64_gqa2": C["llava_layer"].scaled(name="bf16_d64_gqa2", n_layers=2, batch=1, n_q_heads=4, n_kv_heads=2,
+                                                 head_dim=64, ctx_len=1200, budget=150, n_images=1, window=16,
+                                                 decode_steps=2),
+        "fp32_d128": C["tiny"].scaled(name="fp32_d128", n_layers=2, batch=2, n_q_heads=4, n_kv_heads=2, head_dim=128,
+                                      ctx_len=700, window=8, budget=100, pool_k=3, fixed_layout=(), n_images=2,
+                                      image_tokens=(100, 100), text_tokens=(20, 200), decode_steps=2),
+    }
+
+
+def engine(wl, **kw):
+    args = dict(n_layers=wl.n_layers, batch=wl.batch, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
+                head_dim=wl.head_dim, ctx_len=wl.ctx_len, window=wl.window, budget=wl.budget, dtype=wl.dtype,
+                pool_k=wl.pool_k, max_new_tokens=wl.decode_steps, out_fp32=1, device=DEV)
+    args.update(kw)
+    return MB.MadaKV(**args)
+
+
+def stats_struct(w, k, device):
+    """[..., 4] int32 tensor holding {f32 w_t, f32 w_v, i32 k_t, i32 k_v}."""
+    wf = torch.from_numpy(np.asarray(w, dtype=np.float32)).view(torch.int32)
+    ki = torch.from_numpy(np.asarray(k, dtype=np.int32))
+    return torch.cat([wf, ki], dim=-1).contiguous().to(device)
+
+
+@pytest.mark.parametrize("name", list(small_workloads().keys()))
+def test_stagewise_parity(name):
+    wl = small_workloads()[name]
+    NL, B, H, L, W, d = wl.n_layers, wl.batch, wl.n_kv_heads, wl.ctx_len, wl.window, wl.head_dim
+    G, nc = wl.n_q_heads // H, L - W
+    p = PU.oracle_params(wl)
+    say(f"{name}: inputs")
+    q, k, v, mask, masks = PU.make_inputs(wl, DEV)
+    eng = engine(wl)
+    say(f"{name}: madakv_score")
+    eng.score(0, NL, q, k, mask)
+    torch.cuda.synchronize()
+    psi_g = eng.psi.cpu().numpy()
+    pool_g = eng.psi_pool.cpu().numpy()
+    w_g, k_g = eng.stats_host()
+    nmod_g = eng.n_mod.cpu().numpy()
+
+    # ---- S1: psi against the oracle
+    qh, kh, vh = WL.to_f64(q), WL.to_f64(k), WL.to_f64(v)
+    psi_o = np.stack([np.stack([O.window_scores(qh[l, b], kh[l, b], p.scale) for b in range(B)]) for l in range(NL)])
+    nbad, worst = PU.psi_close(psi_g, psi_o, G, W, L)
+    say(f"{name}: psi worst scaled error {worst:.2e}")
+    assert nbad == 0, f"psi: {nbad} entries outside tolerance (worst {worst})"
+    np.testing.assert_allclose(psi_g.sum(-1), G * W, rtol=2e-4)
+
+    # ---- S2: statistics and pooling, both sides reading the GPU's psi bits
+    for l in range(NL):
+        for b in range(B):
+            psi_in = psi_g[l, b].astype(np.float64)
+            w_o, k_o, n_o = O.modality_stats(psi_in, masks[b], W, p.theta)
+            assert tuple(nmod_g[b]) == tuple(n_o)
+            np.testing.assert_allclose(w_g[l, b], w_o, rtol=2e-6, atol=1e-30)
+            np.testing.assert_array_equal(pool_g[l, b], O.pool_scores(psi_in, W, p.pool_k).astype(np.float32))
+            for h in range(H):
+                for m in (0, 1):
+                    if k_g[l, b, h, m] != k_o[h, m]:
+                        vals = psi_in[h, :nc][masks[b][:nc] == m]
+                        assert PU.k_count_ok(int(k_g[l, b, h, m]), vals, p.theta), (l, b, h, m, k_g[l, b, h, m], k_o[h, m])
+
+    # ---- S3: allocation, fed the GPU's own statistics on both sides: bit-exact
+    say(f"{name}: madakv_allocate")
+    eng.allocate(0, NL)
+    torch.cuda.synchronize()
+    bud_g = eng.budgets.cpu().numpy()
+    for b in range(B):
+        bud_o = O.allocate(w_g[:, b], k_g[:, b].astype(np.int64), nmod_g[b], p)
+        np.testing.assert_array_equal(bud_g[:, b], bud_o)
+    assert bud_g.sum() == NL * B * H * (wl.budget - W)
+
+    # ---- S4 + S5: selection and gather, both sides reading the GPU's pooled scores and budgets
+    say(f"{name}: madakv_select_gather")
+    eng.select_gather(0, NL, k, v, mask)
+    torch.cuda.synchronize()
+    kv_off, kv_len = eng.kv_off.cpu().numpy(), eng.kv_len.cpu().numpy()
+    kept_all = eng.kept_idx.cpu().numpy()
+    kc_all, vc_all = eng.k_c.cpu(), eng.v_c.cpu()
+    cap_b = eng.capacity // B
+    for b in range(B):
+        cursor = b * cap_b
+        for l in range(NL):
+            for h in range(H):
+                bt, bv = (int(x) for x in bud_g[l, b, h])
+                assert kv_len[l, b, h] == bt + bv + W
+                assert kv_off[l, b, h] == cursor, "segments must tile the batch item's region"
+                cursor += kv_len[l, b, h] + wl.decode_steps
+                kept_o = O.select(pool_g[l, b, h].astype(np.float64), masks[b], bt, bv, L, W)
+                o = kv_off[l, b, h]
+                kept = kept_all[o:o + kv_len[l, b, h]]
+                np.testing.assert_array_equal(kept, kept_o)
+                assert torch.equal(kc_all[o:o + len(kept)], k[l, b, h].cpu()[kept_o])
+                assert torch.equal(vc_all[o:o + len(kept)], v[l, b, h].cpu()[kept_o])
+
+    # ---- S6: decode steps (append + attend), fp32 output against the fp64 oracle
+    k_cache = [[[WL.to_f64(kc_all[kv_off[l, b, h]:kv_off[l, b, h] + kv_len[l, b, h]]) for h in range(H)]
+                for b in range(B)] for l in range(NL)]
+    v_cache = [[[WL.to_f64(vc_all[kv_off[l, b, h]:kv_off[l, b, h] + kv_len[l, b, h]]) for h in range(H)]
+                for b in range(B)] for l in range(NL)]
+    out = torch.empty(NL, B, wl.n_q_heads, d, dtype=torch.float32, device=DEV)
+    for step in range(wl.decode_steps):
+        dq, dk, dv = [], [], []
+        for l in range(NL):
+            row = [WL.decode_inputs(wl, l, b, step, DEV) for b in range(B)]
+            dq.append(torch.stack([r[0] for r in row])); dk.append(torch.stack([r[1] for r in row]))
+            dv.append(torch.stack([r[2] for r in row]))
+        dq, dk, dv = torch.stack(dq).contiguous(), torch.stack(dk).contiguous(), torch.stack(dv).contiguous()
+        say(f"{name}: madakv_decode_attn step {step}")
+        if step % 2 == 0:
+            eng.decode_attn(0, NL, dq, dk, dv, out)              # all layers in one call
+        else:
+            for l in range(NL):                                  # one call per layer (split-KV path)
+                eng.decode_attn(l, 1, dq[l:l + 1], dk[l:l + 1], dv[l:l + 1], out[l:l + 1])
+        torch.cuda.synchronize()
+        out_g = out.cpu().numpy()
+        for l in range(NL):
+            for b in range(B):
+                ref = O.decode_step(WL.to_f64(dq[l, b]), WL.to_f64(dk[l, b]), WL.to_f64(dv[l, b]),
+                                    k_cache[l][b], v_cache[l][b], p.scale)
+                err = np.abs(out_g[l, b] - ref).max()
+                assert err <= PU.DECODE_ATOL, (step, l, b, err)
+        assert (eng.kv_len.cpu().numpy() == kv_len + step + 1).all()
+    # the appended rows are in the cache
+    kc2 = eng.k_c.cpu()
+    for l in range(NL):
+        for b in range(B):
+            for h in range(H):
+                o = kv_off[l, b, h]
+                got = WL.to_f64(kc2[o:o + kv_len[l, b, h] + wl.decode_steps])
+                np.testing.assert_array_equal(got, k_cache[l][b][h])
+    # beyond the slack the library refuses
+    with pytest.raises(MB.MadaKVError) as ei:
+        eng.decode_attn(0, NL, dq, dk, dv, out)
+    assert ei.value.status == -1
+    eng.decode_attn(0, NL, dq, None, None, out)                 # attend-only is still fine
+    torch.cuda.synchronize()
+    eng.close()
+
+
+@pytest.mark.parametrize("name", ["tiny_fp32", "bf16_mha", "bf16_gqa7"])
+def test_free_running_end_to_end(name):
+    """Whole path on the GPU against the whole oracle, with the near-tie rules."""
+    wl = small_workloads()[name]
+    NL, B, H, L, W = wl.n_layers, wl.batch, wl.n_kv_heads, wl.ctx_len, wl.window
+    nc = L - W
+    p = PU.oracle_params(wl)
+    q, k, v, mask, masks = PU.make_inputs(wl, DEV)
+    eng = engine(wl)
+    say(f"{name}: full eviction")
+    eng.score(0, NL, q, k, mask)
+    eng.allocate(0, NL)
+    eng.select_gather(0, NL, k, v, mask)
+    torch.cuda.synchronize()
+    bud_g = eng.budgets.cpu().numpy()
+    kv_off, kv_len = eng.kv_off.cpu().numpy(), eng.kv_len.cpu().numpy()
+    kept_all = eng.kept_idx.cpu().numpy()
+    w_g, k_g = eng.stats_host()
+    qh, kh, vh = WL.to_f64(q), WL.to_f64(k), WL.to_f64(v)
+    excused = unexcused = budget_diffs = 0
+    for b in range(B):
+        res = O.evict(qh[:, b], kh[:, b], vh[:, b], masks[b], p)
+        np.testing.assert_allclose(w_g[:, b], res["w"], rtol=1e-3)
+        for l in range(NL):
+            for h in range(H):
+                for m in (0, 1):
+                    if k_g[l, b, h, m] != res["kcnt"][l, h, m]:
+                        vals = res["psi"][l, h, :nc][masks[b][:nc] == m]
+                        assert PU.k_count_ok(int(k_g[l, b, h, m]), vals, p.theta)
+                if tuple(bud_g[l, b, h]) != tuple(res["budgets"][l, h]):
+                    budget_diffs += 1          # a k_m or share knife-edge upstream; conservation still holds
+                    continue
+                o = kv_off[l, b, h]
+                kept = kept_all[o:o + kv_len[l, b, h]]
+                e, u = PU.kept_diff_excused(kept, res["kept"][l][h], res["psi_pool"][l, h], masks[b],
+                                            int(bud_g[l, b, h, 0]), int(bud_g[l, b, h, 1]), nc)
+                excused += e; unexcused += u
+    say(f"{name}: excused index mismatches {excused}, unexcused {unexcused}, heads with budget knife-edges {budget_diffs}")
+    assert unexcused == 0
+    assert budget_diffs <= max(1, NL * B * H // 10)
+    assert bud_g.sum() == NL * B * H * (wl.budget - W)
+    eng.close()
+
+
+def test_budget_at_or_above_context_is_full_attention():
+    wl = small_workloads()["bf16_mha"].scaled(budget=2000, n_layers=1, batch=1, decode_steps=1)
+    q, k, v, mask, masks = PU.make_inputs(wl, DEV)
+    eng = engine(wl)
+    say("keep-all: select_gather without scores")
+    MB.madakv_select_gather(eng.h, 0, 1, None, mask, None, k, v, eng.kept_idx, eng.kv_off, eng.kv_len, eng.k_c,
+                            eng.v_c, eng.select_ws)
+    torch.cuda.synchronize()
+    H, L, d = wl.n_kv_heads, wl.ctx_len, wl.head_dim
+    assert (eng.kv_len.cpu().numpy() == L).all()
+    kept = eng.kept_idx.cpu().numpy()
+    off = eng.kv_off.cpu().numpy()
+    for h in range(H):
+        np.testing.assert_array_equal(kept[off[0, 0, h]:off[0, 0, h] + L], np.arange(L))
+        assert torch.equal(eng.k_c[off[0, 0, h]:off[0, 0, h] + L], k[0, 0, h])
+    dq, _, _ = WL.decode_inputs(wl, 0, 0, 0, DEV)
+    out = torch.empty(1, 1, wl.n_q_heads, d, dtype=torch.float32, device=DEV)
+    eng.decode_attn(0, 1, dq[None, None].contiguous(), None, None, out)
+    torch.cuda.synchronize()
+    p = PU.oracle_params(wl)
+    kh, vh = WL.to_f64(k), WL.to_f64(v)
+    for j in range(wl.n_q_heads):
+        ref = O.attend(WL.to_f64(dq[j]), kh[0, 0, j], vh[0, 0, j], p.scale)     # Eq. 5 over the whole prompt
+        assert np.abs(out[0, 0, j].cpu().numpy() - ref).max() <= PU.DECODE_ATOL
+    eng.close()
+
+
+def test_layer_by_layer_calls_match_one_call_and_runs_repeat_bitwise():
+    wl = small_workloads()["bf16_mha"]
+    NL = wl.n_layers
+    q, k, v, mask, masks = PU.make_inputs(wl, DEV)
+    outs = []
+    for mode in ("all", "per_layer", "all"):
+        eng = engine(wl, layers_per_call=NL if mode == "all" else 1)
+        if mode == "all":
+            eng.score(0, NL, q, k, mask); eng.allocate(0, NL); eng.select_gather(0, NL, k, v, mask)
+        else:
+            for l in range(NL):
+                eng.score(l, 1, q[l:l + 1], k[l:l + 1], mask)
+                eng.allocate(l, 1)
+                eng.select_gather(l, 1, k[l:l + 1], v[l:l + 1], mask)
+        torch.cuda.synchronize()
+        outs.append([t.clone() for t in (eng.psi, eng.psi_pool, eng.stats, eng.budgets, eng.kv_off, eng.kv_len)]
+                    + [eng.kept_idx.clone(), eng.k_c.clone()])
+        eng.close()
+    lens, offs = outs[0][5].cpu().numpy(), outs[0][4].cpu().numpy()
+    for other in outs[1:]:
+        for a, b in zip(outs[0][:6], other[:6]):
+            assert torch.equal(a, b)
+        for l in range(NL):
+            for b in range(wl.batch):
+                for h in range(wl.n_kv_heads):
+                    o, n = offs[l, b, h], lens[l, b, h]
+                    assert torch.equal(outs[0][6][o:o + n], other[6][o:o + n])
+                    assert torch.equal(outs[0][7][o:o + n], other[7][o:o + n])
+
+
+def test_ablation_modes_match_oracle():
+    wl = small_workloads()["bf16_mha"]
+    NL, B, H, L, W = wl.n_layers, wl.batch, wl.n_kv_heads, wl.ctx_len, wl.window
+    q, k, v, mask, masks = PU.make_inputs(wl, DEV)
+    for mpa, hcc in ((0, 1), (1, 0), (0, 0)):
+        p = PU.oracle_params(wl, mpa_mode=mpa, hcc_mode=hcc)
+        eng = engine(wl, mpa_mode=mpa, hcc_mode=hcc)
+        say(f"ablation mpa={mpa} hcc={hcc}")
+        eng.score(0, NL, q, k, mask); eng.allocate(0, NL); eng.select_gather(0, NL, k, v, mask)
+        torch.cuda.synchronize()
+        w_g, k_g = eng.stats_host()
+        bud_g, pool_g = eng.budgets.cpu().numpy(), eng.psi_pool.cpu().numpy()
+        kept_all, off, ln = eng.kept_idx.cpu().numpy(), eng.kv_off.cpu().numpy(), eng.kv_len.cpu().numpy()
+        for b in range(B):
+            np.testing.assert_array_equal(bud_g[:, b], O.allocate(w_g[:, b], k_g[:, b].astype(np.int64),
+                                                                 eng.n_mod.cpu().numpy()[b], p))
+            for l in range(NL):
+                for h in range(H):
+                    bt, bv = (int(x) for x in bud_g[l, b, h])
+                    ref = O.select(pool_g[l, b, h].astype(np.float64), masks[b], bt, bv, L, W, mpa)
+                    np.testing.assert_array_equal(kept_all[off[l, b, h]:off[l, b, h] + ln[l, b, h]], ref)
+        if hcc == 0:
+            assert (bud_g.sum(-1) == wl.budget - W).all()
+        eng.close()
+
+
+def test_allocate_random_statistics_bit_exact():
+    """madakv_allocate alone on random statistics (forces every clamp branch), vs the oracle."""
+    r = np.random.default_rng(5)
+    for trial in range(12):
+        NL, B, H = int(r.integers(1, 9)), int(r.integers(1, 4)), int(r.integers(1, 33))
+        W = int(r.integers(1, 9)); L = int(r.integers(W + 40, 600))
+        budget = int(r.integers(W + 1, L))
+        nc = L - W
+        theta = 0.9
+        eng = MB.MadaKV(n_layers=NL, batch=B, n_q_heads=H, n_kv_heads=H, head_dim=64, ctx_len=L, window=W,
+                        budget=budget, dtype="bf16", pool_k=1, hcc_rho=int(r.integers(1, 4)), device=DEV)
+        p = O.Params(n_layers=NL, n_q_heads=H, n_kv_heads=H, head_dim=64, ctx_len=L, window=W, budget=budget,
+                     hcc_rho=eng.cfg.hcc_rho, theta=theta)
+        n_t = r.integers(0, nc + 1, size=B); n_v = nc - n_t
+        skew = r.choice([0.05, 1.0, 3.0])
+        kt = (r.random((NL, B, H)) ** skew * (n_t[None, :, None] + 1)).astype(np.int64).clip(0, n_t[None, :, None])
+        kv_ = (r.random((NL, B, H)) ** skew * (n_v[None, :, None] + 1)).astype(np.int64).clip(0, n_v[None, :, None])
+        kc = np.stack([kt, kv_], -1)
+        w = r.random((NL, B, H, 2)).astype(np.float32)
+        w[r.random((NL, B, H)) < 0.1] = 0.0
+        n_mod = np.stack([n_t, n_v], -1).astype(np.int32)
+        st = stats_struct(w, kc, DEV)
+        nm = torch.from_numpy(n_mod).to(DEV)
+        # in two calls when there are enough layers: the pool is carried in the handle
+        cut = NL // 2
+        if cut:
+            eng.allocate(0, cut, st[:cut], nm, eng.budgets[:cut])
+            eng.allocate(cut, NL - cut, st[cut:], nm, eng.budgets[cut:])
+        else:
+            eng.allocate(0, NL, st, nm, eng.budgets)
+        torch.cuda.synchronize()
+        got = eng.budgets.cpu().numpy()
+        for b in range(B):
+            np.testing.assert_array_equal(got[:, b], O.allocate(w[:, b], kc[:, b], n_mod[b], p))
+        eng.close()
+
+
+def test_select_with_heavy_ties_and_extreme_budgets():
+    """Scores with few distinct values (pooling makes exact ties), budgets 0 and n_m."""
+    r = np.random.default_rng(9)
+    # budget 1400 per head: the six hand-made budgets below add up to less than the 6 * 1400 rows
+    # the reduced cache holds (the library lays segments out in that space)
+    wl = small_workloads()["bf16_mha"].scaled(n_layers=1, batch=1, n_q_heads=6, n_kv_heads=6, ctx_len=5000,
+                                              n_images=3, budget=1400)
+    H, L, W = wl.n_kv_heads, wl.ctx_len, wl.window
+    nc = L - W
+    q, k, v, mask, masks = PU.make_inputs(wl, DEV)
+    eng = engine(wl)
+    m = masks[0]
+    n_t, n_v = int((m[:nc] == 0).sum()), int((m[:nc] == 1).sum())
+    pool = r.integers(0, 6, size=(1, 1, H, nc)).astype(np.float32) * 0.25
+    pool[0, 0, 1] = 1.0                                            # one value only
+    pool[0, 0, 2] = -pool[0, 0, 2]                                 # negative scores order correctly too
+    bud = np.array([[[[0, 0], [n_t, n_v], [7, 0], [0, 9], [n_t - 1, 1], [123, 456]]]], dtype=np.int32)
+    bud[0, 0, 5] = [min(123, n_t), min(456, n_v)]
+    assert int(bud.sum()) + H * (W + wl.decode_steps) <= eng.capacity
+    pool_t, bud_t = torch.from_numpy(pool).to(DEV), torch.from_numpy(bud).to(DEV)
+    say("select: ties and extreme budgets")
+    eng.select_gather(0, 1, k, v, mask, psi_pool=pool_t, budgets=bud_t)
+    torch.cuda.synchronize()
+    kept_all, off, ln = eng.kept_idx.cpu().numpy(), eng.kv_off.cpu().numpy(), eng.kv_len.cpu().numpy()
+    for h in range(H):
+        ref = O.select(pool[0, 0, h].astype(np.float64), m, int(bud[0, 0, h, 0]), int(bud[0, 0, h, 1]), L, W)
+        np.testing.assert_array_equal(kept_all[off[0, 0, h]:off[0, 0, h] + ln[0, 0, h]], ref)
+    eng.close()
+
+
+def test_bf16_output_rounding():
+    wl = small_workloads()["bf16_mha"].scaled(n_layers=1, batch=1, decode_steps=1)
+    q, k, v, mask, masks = PU.make_inputs(wl, DEV)
+    res = {}
+    for of in (1, 0):
+        eng = engine(wl, out_fp32=of)
+        eng.score(0, 1, q, k, mask); eng.allocate(0, 1); eng.select_gather(0, 1, k, v, mask)
+        dq, dk, dv = WL.decode_inputs(wl, 0, 0, 0, DEV)
+        out = torch.empty(1, 1, wl.n_q_heads, wl.head_dim, dtype=torch.float32 if of else torch.bfloat16, device=DEV)
+        eng.decode_attn(0, 1, dq[None, None].contiguous(), dk[None, None].contiguous(), dv[None, None].contiguous(), out)
+        torch.cuda.synchronize()
+        res[of] = out.float().cpu()
+        eng.close()
+    assert torch.equal(res[0], res[1].to(torch.bfloat16).float())   # the bf16 output is the RNE of the fp32 one
+
+
+def test_budgets_beyond_the_cache_leave_heads_empty():
+    """Budgets that add up to more than the reduced cache holds: the library lays out what
+    fits and gives the remaining heads empty segments; nothing is written out of bounds."""
+    wl = small_workloads()["bf16_mha"].scaled(n_layers=1, batch=1, n_q_heads=4, n_kv_heads=4, ctx_len=2000, budget=300,
+                                              decode_steps=1)
+    H, L, W = wl.n_kv_heads, wl.ctx_len, wl.window
+    nc = L - W
+    q, k, v, mask, masks = PU.make_inputs(wl, DEV)
+    eng = engine(wl)
+    m = masks[0]
+    n_t, n_v = int((m[:nc] == 0).sum()), int((m[:nc] == 1).sum())
+    cap = eng.capacity                                             # 4 * 301 rows
+    guard_i = torch.full_like(eng.kept_idx, -7)
+    eng.kept_idx.copy_(guard_i)
+    eng.k_c.fill_(123.0)
+    bud = np.array([[[[100, 100], [min(n_t, 700), min(n_v, 700)], [5, 5], [1, 1]]]], dtype=np.int32)   # head 1 cannot fit
+    pool = np.random.default_rng(3).random((1, 1, H, nc)).astype(np.float32)
+    say("select: budgets larger than the cache")
+    eng.select_gather(0, 1, k, v, mask, psi_pool=torch.from_numpy(pool).to(DEV), budgets=torch.from_numpy(bud).to(DEV))
+    torch.cuda.synchronize()
+    ln, off = eng.kv_len.cpu().numpy()[0, 0], eng.kv_off.cpu().numpy()[0, 0]
+    assert list(ln) == [200 + W, 0, 0, 0]
+    assert off[0] == 0 and (off[1:] == 200 + W + 1).all()
+    kept = eng.kept_idx.cpu().numpy()
+    np.testing.assert_array_equal(kept[:ln[0]], O.select(pool[0, 0, 0].astype(np.float64), m, 100, 100, L, W))
+    assert (kept[ln[0]:] == -7).all()
+    assert (eng.k_c[ln[0]:].float() == 123.0).all()
+    # decode on it: the full head works, the empty heads stay empty and append nothing
+    dq, dk, dv = WL.decode_inputs(wl, 0, 0, 0, DEV)
+    out = torch.empty(1, 1, wl.n_q_heads, wl.head_dim, dtype=torch.float32, device=DEV)
+    eng.decode_attn(0, 1, dq[None, None].contiguous(), dk[None, None].contiguous(), dv[None, None].contiguous(), out)
+    torch.cuda.synchronize()
+    assert list(eng.kv_len.cpu().numpy()[0, 0]) == [200 + W + 1, 0, 0, 0]
+    assert torch.isfinite(out[0, 0, 0]).all()
+    assert (eng.k_c[ln[0] + 1:].float() == 123.0).all()
+    eng.close()
