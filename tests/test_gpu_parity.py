@@ -341,10 +341,10 @@ def test_allocate_random_statistics_bit_exact():
 def test_select_with_heavy_ties_and_extreme_budgets():
     """Scores with few distinct values (pooling makes exact ties), budgets 0 and n_m."""
     r = np.random.default_rng(9)
-    # budget 1400 per head: the six hand-made budgets below add up to less than the 6 * 1400 rows
+    # budget 1600 per head: the six hand-made budgets below add up to less than the 6 * 1603 rows
     # the reduced cache holds (the library lays segments out in that space)
     wl = small_workloads()["bf16_mha"].scaled(n_layers=1, batch=1, n_q_heads=6, n_kv_heads=6, ctx_len=5000,
-                                              n_images=3, budget=1400)
+                                              n_images=3, budget=1600)
     H, L, W = wl.n_kv_heads, wl.ctx_len, wl.window
     nc = L - W
     q, k, v, mask, masks = PU.make_inputs(wl, DEV)
