@@ -1,0 +1,277 @@
+"""Benchmark of the MadaKV hot path on one MI355X.
+
+A step = one pass of the whole path over one batch of synthetic input of the 16K-context
+workload (32 layers, batch 4, 32 heads, L = 16384, budget 2048, window 32):
+    eviction   madakv_score + madakv_allocate + madakv_select_gather over all layers
+    decode     128 steps of madakv_decode_attn over the reduced cache, one call per layer
+Inputs are resident in HBM before the timed region.  The metric is evicted-context
+tokens/s = B * L / (time of the eviction part); the decode step time is reported beside it.
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+
+
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def build_inputs(wl, dev):
+    import torch
+    from paper_2506_15724_amd import workloads as WL
+    NL, B, H, Hq, L, W, d = wl.n_layers, wl.batch, wl.n_kv_heads, wl.n_q_heads, wl.ctx_len, wl.window, wl.head_dim
+    masks = [WL.modality_mask(wl, b) for b in range(B)]
+    k = torch.empty(NL, B, H, L, d, dtype=wl.torch_dtype, device=dev)
+    v = torch.empty(NL, B, H, L, d, dtype=wl.torch_dtype, device=dev)
+    q = torch.empty(NL, B, Hq, W, d, dtype=wl.torch_dtype, device=dev)
+    for l in range(NL):
+        for b in range(B):
+            q[l, b], k[l, b], v[l, b] = WL.layer_inputs(wl, l, b, masks[b], dev)
+    import numpy as np
+    mask = torch.from_numpy(np.stack(masks)).to(dev)
+    return q, k, v, mask, masks
+
+
+class LayerCalls:
+    """Pre-marshalled arguments of the per-layer madakv_decode_attn calls (pointer arithmetic
+    done once, so the timed loop is one foreign call per layer)."""
+
+    def __init__(self, eng, q_all, kn_all, vn_all, out):
+        from paper_2506_15724_amd import binding as MB
+        self.fn = MB.lib().madakv_decode_attn
+        self.h = eng.h
+        c = eng.cfg
+        NL = c.n_layers
+        es = q_all.element_size()
+        self.steps = q_all.shape[0]
+        q_l = q_all[0, 0].numel() * es
+        kn_l = kn_all[0, 0].numel() * es
+        self.q_step, self.kn_step = q_all[0].numel() * es, kn_all[0].numel() * es
+        self.args = []
+        for l in range(NL):
+            self.args.append((l, q_all.data_ptr() + l * q_l, kn_all.data_ptr() + l * kn_l, vn_all.data_ptr() + l * kn_l,
+                              C.c_void_p(eng.kv_off[l].data_ptr()), C.c_void_p(eng.kv_len[l].data_ptr()),
+                              C.c_void_p(out[l].data_ptr())))
+        self.kc, self.vc = C.c_void_p(eng.k_c.data_ptr()), C.c_void_p(eng.v_c.data_ptr())
+        self.ws = C.c_void_p(eng.decode_ws.data_ptr())
+        self.ws_bytes = eng.decode_ws.numel()
+
+    def run_step(self, s, stream):
+        fn, h, kc, vc, ws, wsb = self.fn, self.h, self.kc, self.vc, self.ws, self.ws_bytes
+        qo, ko = s * self.q_step, s * self.kn_step
+        for (l, qp, kp, vp, off, ln, out) in self.args:
+            rc = fn(h, l, 1, C.c_void_p(qp + qo), C.c_void_p(kp + ko), C.c_void_p(vp + ko), kc, vc, off, ln, out, ws, wsb, stream)
+            if rc != 0:
+                raise RuntimeError(f"madakv_decode_attn layer {l} -> {rc}")
+
+
+def cpu_baseline(wl, q, k, v, masks):
+    """The oracle as it stands, timed on the host cores on a bounded sample: the eviction
+    (Eq. 7, 6, 9, pooling, Eq. 8/10/11 for that layer alone, selection, gather) of one layer of
+    one batch item, all its heads; scaled to the whole model by the layer and batch count."""
+    import numpy as np
+    from oracle import madakv_oracle as O
+    from paper_2506_15724_amd import workloads as WL
+    p = O.Params(n_layers=1, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads, head_dim=wl.head_dim, ctx_len=wl.ctx_len,
+                 window=wl.window, budget=wl.budget, pool_k=wl.pool_k)
+    qh, kh, vh = WL.to_f64(q[0, 0])[None], WL.to_f64(k[0, 0])[None], WL.to_f64(v[0, 0])[None]
+    t0 = time.perf_counter()
+    O.evict(qh, kh, vh, masks[0], p)
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
+    except Exception:
+        threads = 1
+    cores = min(threads, len(os.sched_getaffinity(0)))
+    tokens_per_s = wl.ctx_len / (dt * wl.n_layers)      # whole-model eviction of one batch item takes n_layers * dt
+    return {"value": tokens_per_s, "unit": "ctx-tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"eviction of 1 of {wl.n_layers} layers x 1 of {wl.batch} batch items ({wl.n_kv_heads} heads, "
+                      f"L={wl.ctx_len}) took {dt:.2f} s; scaled by the layer count",
+            "seconds": dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="llava_16k")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the multi-layer-launch and full-cache decode timings")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding or collectives in the method's hot path); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2506_15724_amd import binding as MB
+    from paper_2506_15724_amd import workloads as WL
+
+    MB.lib()                                   # fail loudly if the HIP library is missing
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    wl = WL.CONFIGS[a.workload]
+    NL, B, H, Hq, L, W, d = wl.n_layers, wl.batch, wl.n_kv_heads, wl.n_q_heads, wl.ctx_len, wl.window, wl.head_dim
+    es = 2 if wl.dtype == "bf16" else 4
+    S = wl.decode_steps
+    log(f"workload {wl.name}: {NL} layers, B={B}, H={H}, L={L}, d={d}, W={W}, budget={wl.budget}, {S} decode steps")
+    t0 = time.time()
+    q, k, v, mask, masks = build_inputs(wl, dev)
+    torch.cuda.synchronize()
+    log(f"inputs resident in HBM ({(k.numel() + v.numel()) * es / 1e9:.1f} GB of K,V) after {time.time() - t0:.1f} s")
+
+    eng = MB.MadaKV(n_layers=NL, batch=B, n_q_heads=Hq, n_kv_heads=H, head_dim=d, ctx_len=L, window=W, budget=wl.budget,
+                    dtype=wl.dtype, pool_k=wl.pool_k, max_new_tokens=S, out_fp32=0, device=dev)
+    dq = torch.empty(S, NL, B, Hq, d, dtype=wl.torch_dtype, device=dev)
+    dk = torch.empty(S, NL, B, H, d, dtype=wl.torch_dtype, device=dev)
+    dv = torch.empty(S, NL, B, H, d, dtype=wl.torch_dtype, device=dev)
+    for s in range(S):
+        dq[s], dk[s], dv[s] = WL.decode_inputs_all(wl, s, dev)
+    out = torch.empty(NL, B, Hq, d, dtype=wl.torch_dtype, device=dev)
+    calls = LayerCalls(eng, dq, dk, dv, out)
+    stream = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    log(f"decode inputs ready after {time.time() - t0:.1f} s")
+
+    def evict():
+        eng.score(0, NL, q, k, mask)
+        eng.allocate(0, NL)
+        eng.select_gather(0, NL, k, v, mask)
+
+    def one_step(ev):
+        ev[0].record()
+        evict()
+        ev[1].record()
+        for s in range(S):
+            calls.run_step(s, stream)
+        ev[2].record()
+
+    for _ in range(a.warmup):
+        one_step([torch.cuda.Event(enable_timing=True) for _ in range(3)])
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(a.steps)]
+    torch.cuda.synchronize()
+    w0 = time.perf_counter()
+    for i in range(a.steps):
+        one_step(events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - w0
+    evict_ms = [e[0].elapsed_time(e[1]) for e in events]
+    decode_ms = [e[1].elapsed_time(e[2]) for e in events]
+    ms_per_step = wall * 1e3 / a.steps
+    evict_med = float(np.median(evict_ms))
+    decode_med = float(np.median(decode_ms))
+    value = B * L / (evict_med * 1e-3)
+
+    # bytes the decode launches had to move: K and V rows of every head, once per step
+    kv_len_end = eng.kv_len.to(torch.int64).sum().item()          # lengths after the S appends
+    n_heads_total = NL * B * H
+    rows_first = kv_len_end - S * n_heads_total                    # rows before the first append
+    rows_streamed = sum(rows_first + (s + 1) * n_heads_total for s in range(S))
+    decode_bytes = rows_streamed * 2 * d * es
+    launches = S * NL
+    per_launch_us = decode_med * 1e3 / launches
+    achieved = decode_bytes / (decode_med * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "decode_attn_kernel (+ its merge kernel), one launch per layer",
+                "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                "traffic": None, "bytes_per_launch": decode_bytes / launches, "us_per_launch": per_launch_us}
+
+    # eviction bytes: K read once for scoring, kept K,V rows read and written by the gather
+    kept_rows = rows_first
+    evict_bytes = NL * B * H * L * d * es + kept_rows * 4 * d * es
+    result = {
+        "metric": "evicted-context tokens/s (score+select+gather); decode step us at 16K ctx",
+        "value": value, "unit": "ctx-tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {NL} layers, batch {B}, {H} heads MHA, head_dim {d}, L={L}, window {W}, "
+                               f"budget {wl.budget}/head, {S} decode steps", "launches": "eviction: all layers per call; decode: one call per layer"},
+        "evict_ms": evict_med, "evict_ms_min": float(min(evict_ms)),
+        "evict_layer_tokens_per_s": B * L * NL / (evict_med * 1e-3),
+        "evict_algorithmic_GBps": evict_bytes / (evict_med * 1e-3) / 1e9,
+        "decode_step_us": decode_med * 1e3 / S, "decode_step_us_min": float(min(decode_ms)) * 1e3 / S,
+        "decode_GBps": achieved,
+        "roofline": roofline,
+    }
+
+    if not a.no_extras:
+        # (b) the same decode as ONE launch over all layers per step (attend-only, cache as left by the last step)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 20
+        eng.decode_attn(0, NL, dq[0], None, None, out)
+        e0.record()
+        for _ in range(reps):
+            eng.decode_attn(0, NL, dq[0], None, None, out)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        by = kv_len_end * 2 * d * es
+        result["decode_all_layers_one_launch"] = {"us_per_step": ms * 1e3, "GBps": by / (ms * 1e-3) / 1e9,
+                                                  "frac_of_peak": by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        # per-stage eviction times
+        stage = {}
+        for name, fn in (("score", lambda: eng.score(0, NL, q, k, mask)), ("allocate", lambda: eng.allocate(0, NL)),
+                         ("select_gather", lambda: eng.select_gather(0, NL, k, v, mask))):
+            fn(); torch.cuda.synchronize()
+            e0.record(); fn(); e1.record(); torch.cuda.synchronize()
+            stage[name + "_ms"] = e0.elapsed_time(e1)
+        result["evict_stage_ms"] = stage
+        # (c) the same decode kernel over the un-evicted cache (budget >= L keeps every token)
+        try:
+            full = MB.MadaKV(n_layers=NL, batch=B, n_q_heads=Hq, n_kv_heads=H, head_dim=d, ctx_len=L, window=W, budget=L,
+                             dtype=wl.dtype, pool_k=wl.pool_k, max_new_tokens=1, out_fp32=0, layers_per_call=NL, device=dev)
+            # psi buffers of this engine are not needed: free them before the big cache copy
+            full.psi = full.psi_pool = None
+            MB.madakv_select_gather(full.h, 0, NL, None, mask, None, k, v, full.kept_idx, full.kv_off, full.kv_len,
+                                    full.k_c, full.v_c, full.select_ws)
+            fc = LayerCalls(full, dq, dk, dv, out)
+            torch.cuda.synchronize()
+            for l, qp, kp, vp, off, ln, o in fc.args:
+                fc.fn(fc.h, l, 1, C.c_void_p(qp), None, None, fc.kc, fc.vc, off, ln, o, fc.ws, fc.ws_bytes, stream)
+            e0.record()
+            reps = 3
+            for _ in range(reps):
+                for l, qp, kp, vp, off, ln, o in fc.args:
+                    fc.fn(fc.h, l, 1, C.c_void_p(qp), None, None, fc.kc, fc.vc, off, ln, o, fc.ws, fc.ws_bytes, stream)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            by = NL * B * H * L * 2 * d * es
+            result["decode_full_cache"] = {"us_per_step": ms * 1e3, "GBps": by / (ms * 1e-3) / 1e9,
+                                           "frac_of_peak": by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                           "speedup_of_evicted_cache": ms * 1e3 / result["decode_step_us"]}
+            full.close()
+            del full, fc
+        except Exception as ex:                       # memory for the second cache may be short on a shared box
+            result["decode_full_cache"] = {"error": str(ex)[:200]}
+
+    if not a.no_cpu_baseline:
+        log("timing the CPU oracle on a bounded sample")
+        result["cpu_baseline"] = cpu_baseline(wl, q, k, v, masks)
+    else:
+        result["cpu_baseline"] = None
+    eng.close()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -163,7 +163,8 @@ int32_t madakv_select_gather(madakv_handle* h, int32_t layer0, int32_t n,
  *   q        [n, B, Hq, d]
  *   k_new, v_new [n, B, H, d]  both NULL = attend only
  *   k_c, v_c, kv_off          as produced by madakv_select_gather
- *   kv_len   [n, B, H]        in/out: incremented by the append
+ *   kv_len   [n, B, H]        in/out: the array madakv_select_gather filled (the library sizes
+ *                              its launch from the lengths it produced); incremented by the append
  *   out      [n, B, Hq, d]    float if out_fp32 else dtype
  * INVALID_ARG if a layer in the range has already appended max_new_tokens rows. */
 int32_t madakv_decode_attn(madakv_handle* h, int32_t layer0, int32_t n,

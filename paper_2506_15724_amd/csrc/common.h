@@ -20,13 +20,13 @@ struct Dims {
 };
 
 struct ScorePlan { int nsplit; int chunk; int mpad; int group_heads; };
-struct DecodePlan { int nsplit; };
+struct DecodePlan { int chunk_rows; int max_chunks; };
 
 ScorePlan score_plan(const Dims& dm, int dtype);
-DecodePlan decode_plan(const Dims& dm);
+DecodePlan decode_plan(const Dims& dm, const madakv_config& c, int longest_rows);
 size_t score_ws_bytes(const Dims& dm, int dtype);
 size_t select_ws_bytes(const Dims& dm, const madakv_config& c);
-size_t decode_ws_bytes(const Dims& dm);
+size_t decode_ws_bytes(const Dims& dm, const madakv_config& c);
 
 // Each launcher validates nothing: shapes were checked by the ABI layer.
 hipError_t launch_score(const Dims& dm, const madakv_config& c, const void* q_win, const void* k,
@@ -36,7 +36,7 @@ hipError_t launch_stats(const Dims& dm, const madakv_config& c, const float* psi
 hipError_t launch_allocate(const Dims& dm, const madakv_config& c, int layer0, const madakv_head_stats* stats,
                            const int32_t* n_mod, int32_t* budgets, long long* pool_state, hipStream_t st);
 hipError_t launch_offsets(const Dims& dm, const madakv_config& c, int layer0, const int32_t* budgets,
-                          int64_t* kv_off, int32_t* kv_len, long long* cursor_state, void* ws,
+                          int64_t* kv_off, int32_t* kv_len, long long* cursor_state, int32_t* layer_maxlen, void* ws,
                           long long region_tokens, int blocks_per_batch, hipStream_t st);
 hipError_t launch_select(const Dims& dm, const madakv_config& c, const float* psi_pool, const uint8_t* mask,
                          const int32_t* budgets, const int64_t* kv_off, const int32_t* kv_len, int32_t* kept_idx,
@@ -47,7 +47,7 @@ hipError_t launch_gather(const Dims& dm, const madakv_config& c, const void* k, 
                          int blocks_per_batch, hipStream_t st);
 hipError_t launch_decode(const Dims& dm, const madakv_config& c, const void* q, const void* k_new,
                          const void* v_new, void* k_c, void* v_c, const int64_t* kv_off, int32_t* kv_len,
-                         void* out, void* ws, long long capacity_tokens, hipStream_t st);
+                         void* out, void* ws, long long capacity_tokens, int longest_rows, hipStream_t st);
 
 constexpr int GATHER_ROWS = 64;   // rows of the reduced cache one gather workgroup fills
 

@@ -7,14 +7,21 @@
 // instruction and keeps UNROLL K rows and UNROLL V rows in flight.  The dot product is
 // reduced over the LPR lanes of a row with DPP row operations, the softmax is the usual
 // running max / running sum in the log2 domain with fp32 accumulation.  Each head's rows
-// are cut into `nsplit` equal ranges (one workgroup each) so that a single layer's 128
-// heads still fill 256 CUs; a second kernel merges the partial (max, sum, acc) triples in
-// a fixed order.  The appended row is taken from k_new / v_new by the workgroup whose range
-// holds it, which also stores it in the cache; kv_len is bumped by whoever finalises the
-// head.
+// are cut into chunks of `chunk_rows` (one workgroup each): a single layer's 128 ragged heads
+// become ~2000 equal pieces of work that the hardware scheduler spreads over 256 CUs.  The
+// grid is (heads, longest possible head / chunk_rows): workgroups past a head's real length
+// exit at once, and since the chunk index is the slow grid dimension they are dispatched
+// after all the real work.  A second, small kernel merges the partial (max, sum, acc) triples
+// of each head in chunk order.  (Merging inside the first kernel by the last workgroup to
+// arrive needs device-scope fences, which write back and invalidate the whole L2 of an XCD
+// per workgroup: measured 15x slower here.)  A call over >= 1024 heads gives every head one
+// workgroup and needs no merge.  The appended row is taken from k_new / v_new by the
+// workgroup whose chunk holds it, which also stores it in the cache; kv_len is bumped by
+// whoever finalises the head.
 #include "common.h"
 
 #include <algorithm>
+#include <cstdlib>
 
 namespace madakv {
 
@@ -24,7 +31,7 @@ constexpr int DEC_THREADS = 256;
 struct DecodeArgs {
   const void* q; const void* k_new; const void* v_new; void* k_c; void* v_c;
   const int64_t* kv_off; int32_t* kv_len; void* out; float* part;
-  int B, H, G, d, nsplit, out_fp32, has_new;
+  int B, H, G, d, chunk_rows, max_chunks, out_fp32, has_new;
   long long capacity;   // rows in k_c / v_c
   float scale_log2;
 };
@@ -57,32 +64,38 @@ template <> struct Elems<float> {
   }
 };
 
-template <typename T, int LPR, int GT, int UNROLL>
-__global__ __launch_bounds__(DEC_THREADS) void decode_attn_kernel(DecodeArgs a) {
+template <typename T>
+__device__ __forceinline__ void store_out(void* out, int out_fp32, long long o, float val) {
+  if (out_fp32 || sizeof(T) == 4) reinterpret_cast<float*>(out)[o] = val;
+  else reinterpret_cast<uint16_t*>(out)[o] = f32_to_bf16_rne(val);
+}
+
+template <typename T, int LPR, int GT, int UNROLL, int NW>
+__global__ __launch_bounds__(NW * 64) void decode_attn_kernel(DecodeArgs a) {
   constexpr int EPL = Elems<T>::EPL;
   constexpr int RPI = 64 / LPR;
   constexpr int D = LPR * EPL;
-  __shared__ float s_ml[4][GT][2];
-  __shared__ float s_acc[4][GT][D];
+  __shared__ float s_ml[NW][GT][2];
+  __shared__ float s_acc[NW][GT][D];
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int sub = lane / LPR, piece = lane % LPR;
-  const int split = blockIdx.x;
-  const long long hidx = blockIdx.y;                 // (layer, batch, kv head) of the call
-  const long long lb = hidx / a.H;
-  const int h = (int)(hidx % a.H);
+  const long long hidx = blockIdx.x;                 // (layer, batch, kv head) of the call
+  const int chunk = blockIdx.y;                      // which `chunk_rows` rows of the head
   const int len_old = a.kv_len[hidx];
   const long long off = a.kv_off[hidx];
   // an empty segment (its budgets did not fit the cache) stays empty: no append, output 0/0 = NaN
   const bool can_append = a.has_new && len_old > 0 && off + len_old < a.capacity;
   const int len = len_old + (can_append ? 1 : 0);
-
-  // rows [r_begin, r_end) of this split: equal ranges rounded up to whole workgroup strides
-  constexpr int STRIDE = 4 * RPI * UNROLL;
-  int per = (len + a.nsplit - 1) / a.nsplit;
-  per = (per + STRIDE - 1) / STRIDE * STRIDE;
-  const int r_begin = split * per;
-  const int r_end = min(len, r_begin + per);
+  const int nch = max(1, (len + a.chunk_rows - 1) / a.chunk_rows);
+  if (chunk >= nch) return;                          // the grid is sized for the longest possible head
+  const long long lb = hidx / a.H;
+  const int h = (int)(hidx % a.H);
+  const int r_begin = chunk * a.chunk_rows;
+  const int r_end = min(len, r_begin + a.chunk_rows);
+  // the NW waves take turns on consecutive RPI * UNROLL-row slices, so that at any moment the
+  // workgroup reads one contiguous stretch of K and one of V
+  constexpr int WSTEP = RPI * UNROLL;
 
   // queries of the group, pre-multiplied by scale * log2(e)
   float qf[GT][EPL];
@@ -109,7 +122,7 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_attn_kernel(DecodeArgs a) 
   const uint4* kn = reinterpret_cast<const uint4*>(a.k_new);
   const uint4* vn = reinterpret_cast<const uint4*>(a.v_new);
 
-  for (int row0 = r_begin + wave * RPI * UNROLL; row0 < r_end; row0 += STRIDE) {
+  for (int row0 = r_begin + wave * WSTEP; row0 < r_end; row0 += NW * WSTEP) {
     uint4 kraw[UNROLL], vraw[UNROLL];
     bool valid[UNROLL];
 #pragma unroll
@@ -165,7 +178,7 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_attn_kernel(DecodeArgs a) 
     }
   }
 
-  // merge the RPI row groups of the wave (fixed butterfly), then the 4 waves through LDS
+  // merge the RPI row groups of the wave (fixed butterfly), then the NW waves through LDS
 #pragma unroll
   for (int g = 0; g < GT; ++g) {
     for (int o = LPR; o < 64; o <<= 1) {
@@ -189,95 +202,126 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_attn_kernel(DecodeArgs a) 
   __syncthreads();
   // thread t < D finishes element t of every query head of the group
   const int t = threadIdx.x;
+  const long long obase = (lb * a.H + h) * (long long)a.G * D;
   if (t < D) {
     for (int g = 0; g < a.G; ++g) {
       float mx = DNEG_BIG;
-      for (int w = 0; w < 4; ++w) mx = fmaxf(mx, s_ml[w][g][0]);
+      for (int w = 0; w < NW; ++w) mx = fmaxf(mx, s_ml[w][g][0]);
       float ls = 0.f, av = 0.f;
-      for (int w = 0; w < 4; ++w) {
+      for (int w = 0; w < NW; ++w) {
         const float c = exp2f(s_ml[w][g][0] - mx);
         ls += s_ml[w][g][1] * c;
         av += s_acc[w][g][t] * c;
       }
-      if (a.nsplit == 1) {
-        const long long o = ((lb * a.H + h) * (long long)a.G + g) * D + t;
-        const float val = av / ls;
-        if (a.out_fp32) reinterpret_cast<float*>(a.out)[o] = val;
-        else if (sizeof(T) == 2) reinterpret_cast<uint16_t*>(a.out)[o] = f32_to_bf16_rne(val);
-        else reinterpret_cast<float*>(a.out)[o] = val;
+      if (nch == 1) {
+        store_out<T>(a.out, a.out_fp32, obase + (long long)g * D + t, av / ls);
       } else {
-        float* p = a.part + ((hidx * a.nsplit + split) * a.G + g) * (long long)(D + 2);
+        float* p = a.part + ((hidx * a.max_chunks + chunk) * a.G + g) * (long long)(D + 2);
         p[t] = av;
         if (t == 0) { p[D] = mx; p[D + 1] = ls; }
       }
     }
   }
-  if (a.nsplit == 1 && can_append && threadIdx.x == 0) a.kv_len[hidx] = len;
+  // kv_len is read by every chunk of the head: with several chunks per head only the merge
+  // kernel, which runs after all of them, may store the new length
+  if (a.max_chunks == 1 && can_append && threadIdx.x == 0) a.kv_len[hidx] = len;
 }
 
-// Merges the nsplit partials of each head in split order; also stores the new length.
+// Merges the partial (max, sum, acc) triples of every head that was cut into several chunks,
+// in chunk order, and stores the new length.  One workgroup per head, thread t owns element t.
 template <typename T>
 __global__ __launch_bounds__(128) void decode_merge_kernel(DecodeArgs a) {
   const long long hidx = blockIdx.x;
+  const int len_old = a.kv_len[hidx];
+  const bool can_append = a.has_new && len_old > 0 && a.kv_off[hidx] + len_old < a.capacity;
+  const int len = len_old + (can_append ? 1 : 0);
+  const int nch = max(1, (len + a.chunk_rows - 1) / a.chunk_rows);
+  const int t = threadIdx.x;
+  if (nch == 1) {                                    // output already written by the attention kernel
+    if (can_append && t == 0) a.kv_len[hidx] = len;
+    return;
+  }
+  const int D = a.d;
   const long long lb = hidx / a.H;
   const int h = (int)(hidx % a.H);
-  const int D = a.d;
-  const int t = threadIdx.x;
+  const long long obase = (lb * a.H + h) * (long long)a.G * D;
+  const long long cstride = (long long)a.G * (D + 2);
   if (t < D) {
     for (int g = 0; g < a.G; ++g) {
-      float mx = DNEG_BIG;
-      for (int s = 0; s < a.nsplit; ++s) mx = fmaxf(mx, a.part[((hidx * a.nsplit + s) * a.G + g) * (long long)(D + 2) + D]);
-      float ls = 0.f, av = 0.f;
-      for (int s = 0; s < a.nsplit; ++s) {
-        const float* p = a.part + ((hidx * a.nsplit + s) * a.G + g) * (long long)(D + 2);
-        const float c = exp2f(p[D] - mx);
-        ls += p[D + 1] * c;
-        av += p[t] * c;
+      const float* pg = a.part + (hidx * a.max_chunks * a.G + g) * (long long)(D + 2);
+      float m = DNEG_BIG, ls = 0.f, av = 0.f;
+      for (int c0 = 0; c0 < nch; c0 += 8) {          // 24 independent loads in flight per batch
+        float mc[8], lc[8], ac[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const bool ok = c0 + j < nch;
+          const float* p = pg + (long long)(ok ? c0 + j : c0) * cstride;
+          mc[j] = ok ? p[D] : DNEG_BIG; lc[j] = ok ? p[D + 1] : 0.f; ac[j] = ok ? p[t] : 0.f;
+        }
+        float bm = m;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) bm = fmaxf(bm, mc[j]);
+        const float sc = exp2f(m - bm);
+        ls *= sc; av *= sc;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const float w = exp2f(mc[j] - bm);
+          ls = fmaf(lc[j], w, ls);
+          av = fmaf(ac[j], w, av);
+        }
+        m = bm;
       }
-      const long long o = ((lb * a.H + h) * (long long)a.G + g) * D + t;
-      const float val = av / ls;
-      if (a.out_fp32) reinterpret_cast<float*>(a.out)[o] = val;
-      else if (sizeof(T) == 2) reinterpret_cast<uint16_t*>(a.out)[o] = f32_to_bf16_rne(val);
-      else reinterpret_cast<float*>(a.out)[o] = val;
+      store_out<T>(a.out, a.out_fp32, obase + (long long)g * D + t, av / ls);
     }
   }
-  if (a.has_new && t == 0) {
-    const int len_old = a.kv_len[hidx];
-    if (len_old > 0 && a.kv_off[hidx] + len_old < a.capacity) a.kv_len[hidx] = len_old + 1;
-  }
+  if (can_append && t == 0) a.kv_len[hidx] = len;
 }
 
-DecodePlan decode_plan(const Dims& dm) {
+// Rows per workgroup: small for a single layer (many short workgroups balance ragged heads and
+// keep every CU streaming), larger when thousands of heads already fill the chip.
+DecodePlan decode_plan(const Dims& dm, const madakv_config& c, int longest_rows) {
   DecodePlan p;
-  int ns = (1024 + dm.heads - 1) / dm.heads;
-  p.nsplit = std::max(1, std::min(ns, 16));
+  const long long keep = std::min(c.budget, c.ctx_len);
+  const long long est_rows = (long long)dm.heads * keep;
+  (void)est_rows;
+  // longest_rows: upper bound on any head's length in this call (the worst case if unknown)
+  const int longest = std::max(1, std::min(longest_rows, c.ctx_len + c.max_new_tokens));
+  // Measured on MI355X (ragged 16K-context cache): 256-row chunks for a single layer's heads,
+  // 512-row chunks once a call covers >= 1024 heads.  Smaller chunks lose to per-workgroup
+  // start-up cost, one workgroup per head loses to the imbalance of ragged lengths.
+  int rows = dm.heads >= 1024 ? 512 : 256;
+  if (const char* e = getenv("MADAKV_DEC_CHUNK")) { int v = atoi(e); if (v >= 32 && v % 32 == 0 && dm.heads < 1024) rows = v; }
+  if (const char* e = getenv("MADAKV_DEC_BIGCHUNK")) { int v = atoi(e); if (v >= 32 && v % 32 == 0 && dm.heads >= 1024) rows = v; }
+  p.chunk_rows = rows;
+  p.max_chunks = (longest + rows - 1) / rows;
   return p;
 }
 
-size_t decode_ws_bytes(const Dims& dm) {
-  DecodePlan p = decode_plan(dm);
-  return (size_t)dm.heads * p.nsplit * dm.G * (dm.d + 2) * sizeof(float) + 64;
+size_t decode_ws_bytes(const Dims& dm, const madakv_config& c) {
+  DecodePlan p = decode_plan(dm, c, c.ctx_len + c.max_new_tokens);
+  return (size_t)dm.heads * p.max_chunks * dm.G * (dm.d + 2) * sizeof(float) + 64;
 }
 
 template <typename T, int LPR>
 static hipError_t launch_decode_t(const Dims& dm, DecodeArgs& a, hipStream_t st) {
-  dim3 grid(a.nsplit, dm.heads), block(DEC_THREADS);
-  if (dm.G == 1) hipLaunchKernelGGL((decode_attn_kernel<T, LPR, 1, 8>), grid, block, 0, st, a);
-  else if (dm.G == 2) hipLaunchKernelGGL((decode_attn_kernel<T, LPR, 2, 4>), grid, block, 0, st, a);
-  else if (dm.G <= 4) hipLaunchKernelGGL((decode_attn_kernel<T, LPR, 4, 4>), grid, block, 0, st, a);
-  else hipLaunchKernelGGL((decode_attn_kernel<T, LPR, 8, 2>), grid, block, 0, st, a);
-  if (a.nsplit > 1) hipLaunchKernelGGL((decode_merge_kernel<T>), dim3(dm.heads), dim3(128), 0, st, a);
+  dim3 grid(dm.heads, a.max_chunks), block(DEC_THREADS);
+  if (dm.G == 1) hipLaunchKernelGGL((decode_attn_kernel<T, LPR, 1, 8, 4>), grid, block, 0, st, a);
+  else if (dm.G == 2) hipLaunchKernelGGL((decode_attn_kernel<T, LPR, 2, 4, 4>), grid, block, 0, st, a);
+  else if (dm.G <= 4) hipLaunchKernelGGL((decode_attn_kernel<T, LPR, 4, 4, 4>), grid, block, 0, st, a);
+  else hipLaunchKernelGGL((decode_attn_kernel<T, LPR, 8, 2, 4>), grid, block, 0, st, a);
+  if (a.max_chunks > 1) hipLaunchKernelGGL((decode_merge_kernel<T>), dim3(dm.heads), dim3(128), 0, st, a);
   return hipGetLastError();
 }
 
 hipError_t launch_decode(const Dims& dm, const madakv_config& c, const void* q, const void* k_new,
                          const void* v_new, void* k_c, void* v_c, const int64_t* kv_off, int32_t* kv_len,
-                         void* out, void* ws, long long capacity_tokens, hipStream_t st) {
+                         void* out, void* ws, long long capacity_tokens, int longest_rows, hipStream_t st) {
   DecodeArgs a;
   a.capacity = capacity_tokens;
   a.q = q; a.k_new = k_new; a.v_new = v_new; a.k_c = k_c; a.v_c = v_c; a.kv_off = kv_off; a.kv_len = kv_len;
   a.out = out; a.part = reinterpret_cast<float*>(ws);
-  a.B = dm.B; a.H = dm.H; a.G = dm.G; a.d = dm.d; a.nsplit = decode_plan(dm).nsplit;
+  DecodePlan p = decode_plan(dm, c, longest_rows);
+  a.B = dm.B; a.H = dm.H; a.G = dm.G; a.d = dm.d; a.chunk_rows = p.chunk_rows; a.max_chunks = p.max_chunks;
   a.out_fp32 = c.out_fp32; a.has_new = (k_new != nullptr) ? 1 : 0;
   const float scale = c.softmax_scale > 0.f ? c.softmax_scale : 1.0f / sqrtf((float)dm.d);
   a.scale_log2 = scale * 1.4426950408889634f;

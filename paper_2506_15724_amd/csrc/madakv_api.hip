@@ -16,6 +16,14 @@ struct madakv_handle {
   int32_t last_hip_error;
   long long* d_state;              // [2 * B]: HCC pool per batch item, cache cursor per batch item
   std::vector<int32_t> appended;   // decode rows appended so far, per layer
+  // Longest head of each layer after eviction: written by the device, copied to pinned host
+  // memory asynchronously; decode sizes its grid from it once the copy is known to have landed
+  // (event query, never a wait) and from the worst case before that.
+  int32_t* d_maxlen;
+  int32_t* h_maxlen;
+  hipEvent_t maxlen_event;
+  bool maxlen_pending;
+  int sel_layers_done;             // layers [0, sel_layers_done) have been through select_gather in this pass
 };
 
 namespace {
@@ -86,11 +94,19 @@ int32_t madakv_create(const madakv_config* cfg, madakv_handle** out) {
   h->cfg = *cfg;
   h->last_hip_error = 0;
   h->d_state = nullptr;
+  h->d_maxlen = nullptr; h->h_maxlen = nullptr; h->maxlen_event = nullptr;
+  h->maxlen_pending = false; h->sel_layers_done = 0;
   h->appended.assign(cfg->n_layers, 0);
   hipError_t e = hipGetDevice(&h->device);
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&h->d_state), sizeof(long long) * 2 * cfg->batch);
   if (e == hipSuccess) e = hipMemset(h->d_state, 0, sizeof(long long) * 2 * cfg->batch);
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&h->d_maxlen), sizeof(int32_t) * cfg->n_layers);
+  if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&h->h_maxlen), sizeof(int32_t) * cfg->n_layers, hipHostMallocDefault);
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&h->maxlen_event, hipEventDisableTiming);
   if (e != hipSuccess) {
+    if (h->d_maxlen) (void)hipFree(h->d_maxlen);
+    if (h->h_maxlen) (void)hipHostFree(h->h_maxlen);
+    if (h->maxlen_event) (void)hipEventDestroy(h->maxlen_event);
     if (h->d_state) (void)hipFree(h->d_state);
     delete h;
     return MADAKV_ERR_HIP;
@@ -102,6 +118,9 @@ int32_t madakv_create(const madakv_config* cfg, madakv_handle** out) {
 int32_t madakv_destroy(madakv_handle* h) {
   if (!h) return MADAKV_ERR_INVALID_ARG;
   hipError_t e = hipFree(h->d_state);
+  (void)hipFree(h->d_maxlen);
+  (void)hipHostFree(h->h_maxlen);
+  (void)hipEventDestroy(h->maxlen_event);
   delete h;
   return e == hipSuccess ? MADAKV_OK : MADAKV_ERR_HIP;
 }
@@ -114,7 +133,7 @@ int32_t madakv_workspace_bytes(const madakv_handle* h, int32_t n_layers_per_call
   Dims dm = make_dims(h->cfg, n_layers_per_call);
   if (score_ws) *score_ws = score_ws_bytes(dm, h->cfg.dtype);
   if (select_ws) *select_ws = select_ws_bytes(dm, h->cfg);
-  if (decode_ws) *decode_ws = decode_ws_bytes(dm);
+  if (decode_ws) *decode_ws = decode_ws_bytes(dm, h->cfg);
   return MADAKV_OK;
 }
 
@@ -169,10 +188,15 @@ int32_t madakv_select_gather(madakv_handle* h, int32_t layer0, int32_t n,
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   const long long region = region_tokens(c);
   const int bpb = blocks_per_batch(c, n);
-  hipError_t e = launch_offsets(dm, c, layer0, budgets, kv_off, kv_len, h->d_state + c.batch, ws, region, bpb, st);
+  hipError_t e = launch_offsets(dm, c, layer0, budgets, kv_off, kv_len, h->d_state + c.batch, h->d_maxlen + layer0, ws, region, bpb, st);
   if (e == hipSuccess) e = launch_select(dm, c, psi_pool, mask, budgets, kv_off, kv_len, kept_idx, st);
   if (e == hipSuccess) e = launch_gather(dm, c, k, v, kept_idx, kv_off, kv_len, k_c, v_c, ws, region, bpb, st);
   for (int l = layer0; l < layer0 + n; ++l) h->appended[l] = 0;
+  // hand the per-layer longest length to the host without waiting for it
+  if (e == hipSuccess) e = hipMemcpyAsync(h->h_maxlen + layer0, h->d_maxlen + layer0, sizeof(int32_t) * n, hipMemcpyDeviceToHost, st);
+  if (e == hipSuccess) e = hipEventRecord(h->maxlen_event, st);
+  h->sel_layers_done = (e == hipSuccess) ? layer0 + n : 0;
+  h->maxlen_pending = true;
   return hip_fail(h, e);
 }
 
@@ -187,13 +211,21 @@ int32_t madakv_decode_attn(madakv_handle* h, int32_t layer0, int32_t n,
   if ((k_new == nullptr) != (v_new == nullptr)) return MADAKV_ERR_INVALID_ARG;
   if (k_new && (!aligned16(k_new) || !aligned16(v_new))) return MADAKV_ERR_INVALID_ARG;
   Dims dm = make_dims(h->cfg, n);
-  if (ws_bytes < decode_ws_bytes(dm)) return MADAKV_ERR_WORKSPACE_TOO_SMALL;
+  if (ws_bytes < decode_ws_bytes(dm, h->cfg)) return MADAKV_ERR_WORKSPACE_TOO_SMALL;
   if (k_new) {
     for (int l = layer0; l < layer0 + n; ++l)
       if (h->appended[l] >= h->cfg.max_new_tokens) return MADAKV_ERR_INVALID_ARG;
   }
+  // upper bound on the rows of any head in the call (after this call's append)
+  int longest = h->cfg.ctx_len + h->cfg.max_new_tokens;
+  if (h->maxlen_pending && hipEventQuery(h->maxlen_event) == hipSuccess) h->maxlen_pending = false;
+  if (!h->maxlen_pending && layer0 + n <= h->sel_layers_done) {
+    int mx = 0;
+    for (int l = layer0; l < layer0 + n; ++l) mx = std::max(mx, h->h_maxlen[l] + h->appended[l] + 1);
+    longest = std::min(longest, mx);
+  }
   hipError_t e = launch_decode(dm, h->cfg, q, k_new, v_new, k_c, v_c, kv_off, kv_len, out, ws,
-                               region_tokens(h->cfg) * h->cfg.batch,
+                               region_tokens(h->cfg) * h->cfg.batch, longest,
                                reinterpret_cast<hipStream_t>(stream));
   if (e == hipSuccess && k_new) for (int l = layer0; l < layer0 + n; ++l) h->appended[l] += 1;
   return hip_fail(h, e);

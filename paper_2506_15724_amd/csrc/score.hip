@@ -18,6 +18,7 @@ namespace madakv {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
 
 constexpr float NEG_BIG = -1.0e30f;
 constexpr int SCORE_THREADS = 256;
@@ -29,6 +30,7 @@ struct ScoreArgs {
   float* rowstat;      // [heads, nsplit, mpad, 2]
   int H, G, d, L, W, M, mpad, nsplit, chunk;
   int head0;           // first head of this launch (grid.y indexes head0 + y)
+  int dbg;             // experiment switches (0 in production)
   float scale_log2;    // softmax scale * log2(e)
 };
 
@@ -39,23 +41,51 @@ __device__ __forceinline__ void merge_ml(float& m, float& l, float m2, float l2)
 }
 
 // ------------------------------------------------------------------------------------
-// bf16 MFMA path.  One workgroup = 4 waves works on one (head, L-chunk).  A wave owns up
-// to two 32-row blocks of Q and a 32-key tile of K at a time:
-//   D[i = proxy row][j = key] = sum_k A[i][k] * B[k][j],  A = Q block, B = K tile^T.
-// Lane l feeds key (l & 31): its B fragments are 16-byte pieces of that key's row, read
-// straight from global memory (half (l >> 5) of the row, contiguous); the A fragments
-// come from the Q tile staged in LDS.  In D a lane holds one key column and 16 rows, so
-// the column sum is in-lane and the row statistics need one cross-lane merge at the end.
-// WPT waves share a key tile when there are more than two row blocks.
+// bf16 MFMA path.  One workgroup = 4 waves works on one (head, L-chunk); a wave streams
+// 32-key subtiles of K:
+//   D[i = proxy row][j = key] = sum_k A[i][k] * B[k][j],  A = 32-row block of Q, B = K subtile^T.
+// HBM side: a subtile (32 rows of 256 B) is fetched with fully coalesced 16-byte loads (16
+// lanes cover one row), PF subtiles ahead of the arithmetic, into registers.  That is
+// what hides the HBM latency: a subtile's arithmetic takes a fraction of a microsecond.
+// MFMA side: an operand lane needs the whole row of "its" key, a layout that would touch 64
+// different cache lines per load instruction if read from global memory directly; so the
+// subtile is parked in a wave-private LDS tile (rows padded by 16 bytes: the 128-bit reads of
+// 32 different rows fall into different banks) and the B fragments are read from there.  The
+// tile is private to the wave: no workgroup barrier in the loop, LDS operations of one wave
+// execute in order.
+// In D a lane holds one key column and 16 rows: the column sum is in-lane, the row
+// statistics need one cross-lane merge at the end of the chunk.
+// The 4 waves form KG key groups x WPT row-block groups (WPT * KG = 4): with at most two
+// row blocks (M <= 64) every wave has its own keys; with more, WPT waves take the same keys
+// and different row blocks, and their column sums meet in LDS.
 // ------------------------------------------------------------------------------------
-template <int D, int WPT, int PASS>
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }   // x <= ~0 here; tiny results may flush to 0
+
+template <int OP>   // 0 = max, 1 = sum over the 32 lanes of a half-wave; every lane gets the result
+__device__ __forceinline__ float half_reduce(float x) {
+#define MADAKV_DPP(ctrl) __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), ctrl, 0xF, 0xF, true))
+  float y;
+  y = MADAKV_DPP(0xB1);  x = OP ? x + y : fmaxf(x, y);     // quad_perm [1,0,3,2]
+  y = MADAKV_DPP(0x4E);  x = OP ? x + y : fmaxf(x, y);     // quad_perm [2,3,0,1]
+  y = MADAKV_DPP(0x141); x = OP ? x + y : fmaxf(x, y);     // row_half_mirror
+  y = MADAKV_DPP(0x140); x = OP ? x + y : fmaxf(x, y);     // row_mirror
+#undef MADAKV_DPP
+  y = __shfl_xor(x, 16, 64); x = OP ? x + y : fmaxf(x, y); // the two 16-lane rows of the half
+  return x;
+}
+
+template <int D, int WPT, int NRB, int PASS>
 __global__ __launch_bounds__(SCORE_THREADS) void score_mfma_kernel(ScoreArgs a) {
   constexpr int KS = D / 16;                  // MFMA k-steps
-  constexpr int QSTRIDE = D + 8;              // bf16 elements per LDS row (16 B pad: conflict-free b128 reads)
-  constexpr int KG = 4 / WPT;                 // key groups (waves that own different tiles)
+  constexpr int RS = D + 8;                   // bf16 elements per LDS row (16 B pad)
+  constexpr int KG = 4 / WPT;                 // key groups
+  constexpr int PPR = D / 8;                  // 16-byte pieces per row
+  constexpr int LPS = 32 * PPR / 64;          // 16-byte loads per lane per subtile
+  constexpr int PF = 2;                       // subtiles in flight per wave
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  uint16_t* qs = reinterpret_cast<uint16_t*>(smem);                                 // [mpad][QSTRIDE]
-  float* fbuf = reinterpret_cast<float*>(smem + (size_t)a.mpad * QSTRIDE * 2);      // pass 1: [4][mpad][2]; pass 2: off[mpad] + red[4][32]
+  uint16_t* qs = reinterpret_cast<uint16_t*>(smem);                       // [mpad][RS]
+  uint16_t* kt_all = qs + (size_t)a.mpad * RS;                            // [4 waves][32][RS]
+  float* fbuf = reinterpret_cast<float*>(kt_all + 4 * 32 * RS);           // pass 1: [KG][mpad][2]; pass 2: off[mpad] + red[2][4][32]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int split = blockIdx.x;
@@ -64,14 +94,35 @@ __global__ __launch_bounds__(SCORE_THREADS) void score_mfma_kernel(ScoreArgs a) 
   const long long lb = head / a.H;            // (layer, batch) index
   const uint16_t* qg = reinterpret_cast<const uint16_t*>(a.q_win) + (lb * a.H + kvh) * (long long)a.G * a.W * D;
   const uint16_t* kg = reinterpret_cast<const uint16_t*>(a.k) + (long long)head * a.L * D;
-  const int MB = a.mpad / 32;
+  const int chunk0 = split * a.chunk;
+  const int chunk1 = min(a.L, chunk0 + a.chunk);
+  const int nsub = (chunk1 - chunk0 + 31) / 32;
+  const int niter = (nsub + KG - 1) / KG;     // the same for every wave (the pass-2 merge uses workgroup barriers)
+  const int wsub = wave % WPT;                // row blocks of this wave: wsub, wsub + WPT
+  const int kgid = wave / WPT;                // subtiles of this wave: kgid, kgid + KG, ...
+  uint16_t* kt = kt_all + (size_t)wave * 32 * RS;
+
+  // PF subtiles of K on their way before anything else
+  u32x4_t pre0[LPS], pre1[LPS];                // two register sets = PF subtiles in flight
+  static_assert(PF == 2, "the loop body below is written out for two register sets");
+#define MADAKV_LOAD_SUB(DST, IT)                                                                 \
+  {                                                                                              \
+    const int lt0 = chunk0 + ((IT) * KG + kgid) * 32;                                            \
+    _Pragma("unroll") for (int i = 0; i < LPS; ++i) {                                            \
+      const int idx = i * 64 + lane;                                                             \
+      const int lkey = min(lt0 + idx / PPR, a.L - 1); /* past the end: a valid row, masked later */ \
+      DST[i] = *reinterpret_cast<const u32x4_t*>(kg + (long long)lkey * D + (idx % PPR) * 8);      \
+    }                                                                                            \
+  }
+  MADAKV_LOAD_SUB(pre0, 0)
+  MADAKV_LOAD_SUB(pre1, 1)
 
   // stage Q (the G*W rows of this KV head are contiguous), zero the padding rows
-  for (int e = tid; e < a.mpad * (D / 8); e += SCORE_THREADS) {
-    int r = e / (D / 8), c = e % (D / 8);
+  for (int e = tid; e < a.mpad * PPR; e += SCORE_THREADS) {
+    const int r = e / PPR, c = e % PPR;
     uint4 val = make_uint4(0, 0, 0, 0);
     if (r < a.M) val = *reinterpret_cast<const uint4*>(qg + (long long)r * D + c * 8);
-    *reinterpret_cast<uint4*>(qs + r * QSTRIDE + c * 8) = val;
+    *reinterpret_cast<uint4*>(qs + r * RS + c * 8) = val;
   }
   float* offs = fbuf;                          // pass 2 only
   if (PASS == 2) {
@@ -84,101 +135,126 @@ __global__ __launch_bounds__(SCORE_THREADS) void score_mfma_kernel(ScoreArgs a) 
   }
   __syncthreads();
 
-  const int wsub = wave % WPT;                 // which row blocks of the tile this wave owns
-  const int kgid = wave / WPT;                 // which tiles of the chunk
-  const int nrb = (MB - wsub + WPT - 1) / WPT; // 0, 1 or 2 row blocks: wsub, wsub + WPT
   const int half = lane >> 5, col = lane & 31;
-  const int chunk0 = split * a.chunk;
-  const int chunk1 = min(a.L, chunk0 + a.chunk);
   const int first_masked = a.L - a.W + 1;      // keys below this are visible to every proxy row
 
-  float st_m[2][16], st_l[2][16], off_r[2][16];
+  float st_m[NRB][16], st_l[NRB][16], off_r[NRB][16];
 #pragma unroll
-  for (int b = 0; b < 2; ++b)
+  for (int b = 0; b < NRB; ++b)
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
       st_m[b][j] = NEG_BIG; st_l[b][j] = 0.f;
-      int row = (wsub + b * WPT) * 32 + (j >> 2) * 8 + half * 4 + (j & 3);
-      off_r[b][j] = (PASS == 2 && b < nrb) ? offs[row] : 0.f;
+      const int row = min((wsub + b * WPT) * 32 + (j >> 2) * 8 + half * 4 + (j & 3), a.mpad - 1);
+      off_r[b][j] = (PASS == 2) ? offs[row] : 0.f;
     }
-  float* red = fbuf + a.mpad;                  // pass 2, WPT > 1: [4][32] partial column sums
+  float* red = fbuf + a.mpad;                  // pass 2, WPT > 1: [2][4][32] partial column sums
+  const int MB = a.mpad / 32;
 
-  // every wave runs the same number of iterations (the loop holds workgroup barriers);
-  // a tile that starts past the chunk is computed on clamped rows and fully masked
-  const int niter = (chunk1 - chunk0 + KG * 32 - 1) / (KG * 32);
-  for (int it = 0; it < niter; ++it) {
-    const int t0 = chunk0 + (it * KG + kgid) * 32;
-    const int key = t0 + col;
-    const int keyc = min(key, a.L - 1);        // ragged tail: load a valid row, mask it below
-    bf16x8_t bfrag[KS];
-    const uint16_t* kp = kg + (long long)keyc * D + half * (D / 2);
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) bfrag[ks] = *reinterpret_cast<const bf16x8_t*>(kp + ks * 8);
-    const bool tail = (t0 + 32 > first_masked) || (t0 + 32 > chunk1);
-    float colsum = 0.f;
-#pragma unroll
-    for (int b = 0; b < 2; ++b) {
-      if (b < nrb) {
-        const int rb = wsub + b * WPT;
-        f32x16_t acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        const uint16_t* qrow = qs + (rb * 32 + col) * QSTRIDE + half * (D / 2);
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          bf16x8_t afrag = *reinterpret_cast<const bf16x8_t*>(qrow + ks * 8);
-          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag[ks], acc, 0, 0, 0);
-        }
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-          const float s2 = acc[j] * a.scale_log2;
-          bool valid = true;
-          if (tail) {
-            const int row = rb * 32 + (j >> 2) * 8 + half * 4 + (j & 3);
-            const int pos = a.L - a.W + (row % a.W);            // absolute position of the proxy row
-            valid = (key < chunk1) && (key <= pos) && (row < a.M);
-          }
-          if (PASS == 1) {
-            const float mn = valid ? fmaxf(st_m[b][j], s2) : st_m[b][j];
-            st_l[b][j] = st_l[b][j] * exp2f(st_m[b][j] - mn) + (valid ? exp2f(s2 - mn) : 0.f);
-            st_m[b][j] = mn;
-          } else {
-            const float p = exp2f(s2 - off_r[b][j]);
-            colsum += valid ? p : 0.f;
-          }
-        }
-      }
-    }
-    if (PASS == 2) {
-      colsum += __shfl_xor(colsum, 32, 64);    // the two halves hold different rows of the same key
-      if (WPT == 1) {
-        if (half == 0 && key < chunk1) a.psi[(long long)head * a.L + key] = colsum;
-      } else {
-        if (half == 0) red[wave * 32 + col] = colsum;
-        __syncthreads();
-        if (wsub == 0 && half == 0 && key < chunk1) {
-          float s = 0.f;
-#pragma unroll
-          for (int w = 0; w < WPT; ++w) s += red[(kgid * WPT + w) * 32 + col];
-          a.psi[(long long)head * a.L + key] = s;
-        }
-        __syncthreads();
-      }
-    }
+  // one subtile per step: registers -> LDS tile -> MFMA -> statistics / column sums.
+  // (Written as a macro applied to each register set: the sets must stay in registers, and
+  // any indirection over them makes the compiler park them in scratch memory.)
+#define MADAKV_STEP(SRC, IT)  {  const int it = (IT);  if (it < niter) { \
+_Pragma("unroll") \
+    for (int i = 0; i < LPS; ++i) { \
+      const int idx = i * 64 + lane; \
+      *reinterpret_cast<u32x4_t*>(kt + (idx / PPR) * RS + (idx % PPR) * 8) = SRC[i]; \
+    } \
+    MADAKV_LOAD_SUB(SRC, it + PF) \
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); \
+    __builtin_amdgcn_wave_barrier(); \
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront"); \
+    const int t0 = chunk0 + (it * KG + kgid) * 32; \
+    const int key = t0 + col; \
+    const bool tail = (t0 + 32 > first_masked) || (t0 + 32 > chunk1); \
+    const uint16_t* krow = kt + col * RS + half * (D / 2); \
+    bf16x8_t bfrag[KS]; \
+_Pragma("unroll") \
+    for (int ks = 0; ks < KS; ++ks) bfrag[ks] = *reinterpret_cast<const bf16x8_t*>(krow + ks * 8); \
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); \
+    __builtin_amdgcn_wave_barrier(); \
+    float colsum = 0.f; \
+    if (a.dbg & 1) { colsum = (float)bfrag[0][0] + (float)bfrag[KS - 1][7]; } else \
+_Pragma("unroll") \
+    for (int b = 0; b < NRB; ++b) { \
+      const int rb = wsub + b * WPT; \
+      if (rb < MB) { \
+        f32x16_t acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}; \
+        const uint16_t* qrow = qs + (rb * 32 + col) * RS + half * (D / 2); \
+_Pragma("unroll") \
+        for (int ks = 0; ks < KS; ++ks) { \
+          bf16x8_t afrag = *reinterpret_cast<const bf16x8_t*>(qrow + ks * 8); \
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag[ks], acc, 0, 0, 0); \
+        } \
+        if (!tail) { \
+_Pragma("unroll") \
+          for (int j = 0; j < 16; ++j) { \
+            const float s2 = acc[j] * a.scale_log2; \
+            if (PASS == 1) { \
+              const float dlt = s2 - st_m[b][j]; \
+              const float e = fast_exp2(-fabsf(dlt)); \
+              st_l[b][j] = dlt > 0.f ? fmaf(st_l[b][j], e, 1.0f) : st_l[b][j] + e; \
+              st_m[b][j] = fmaxf(st_m[b][j], s2); \
+            } else { \
+              colsum += fast_exp2(s2 - off_r[b][j]); \
+            } \
+          } \
+        } else { \
+_Pragma("unroll") \
+          for (int j = 0; j < 16; ++j) { \
+            const float s2 = acc[j] * a.scale_log2; \
+            const int row = rb * 32 + (j >> 2) * 8 + half * 4 + (j & 3); \
+            const int pos = a.L - a.W + (row % a.W); \
+            const bool valid = (key < chunk1) && (key <= pos) && (row < a.M); \
+            if (PASS == 1) { \
+              const float dlt = s2 - st_m[b][j]; \
+              const float e = fast_exp2(-fabsf(dlt)); \
+              const float nl = dlt > 0.f ? fmaf(st_l[b][j], e, 1.0f) : st_l[b][j] + e; \
+              st_l[b][j] = valid ? nl : st_l[b][j]; \
+              st_m[b][j] = valid ? fmaxf(st_m[b][j], s2) : st_m[b][j]; \
+            } else { \
+              const float pr = fast_exp2(s2 - off_r[b][j]); \
+              colsum += valid ? pr : 0.f; \
+            } \
+          } \
+        } \
+      } \
+    } \
+    if (PASS == 2) { \
+      colsum += __shfl_xor(colsum, 32, 64); \
+      if (WPT == 1) { \
+        if (half == 0 && key < chunk1) a.psi[(long long)head * a.L + key] = colsum; \
+      } else { \
+        if (half == 0) red[((it & 1) * 4 + wave) * 32 + col] = colsum; \
+        __syncthreads(); \
+        if (wsub == 0 && half == 0 && key < chunk1) { \
+          float s = 0.f; \
+_Pragma("unroll") \
+          for (int w = 0; w < WPT; ++w) s += red[((it & 1) * 4 + kgid * WPT + w) * 32 + col]; \
+          a.psi[(long long)head * a.L + key] = s; \
+        } \
+      } \
+    } \
+  } }
+  for (int it0 = 0; it0 < niter; it0 += PF) {
+    MADAKV_STEP(pre0, it0)
+    MADAKV_STEP(pre1, it0 + 1)
   }
+#undef MADAKV_STEP
+#undef MADAKV_LOAD_SUB
 
   if (PASS == 1) {
-    // merge over the 32 key columns of each half, then over the key groups through LDS
-    float* part = fbuf;                        // [4 waves][mpad][2]
+    // per row: maximum over the 32 key columns of the half, sums rescaled to it and added;
+    // then the key groups meet in LDS
+    float* part = fbuf;                        // [KG][mpad][2]
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
+    for (int b = 0; b < NRB; ++b) {
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
-        float m = st_m[b][j], l = st_l[b][j];
-        for (int o = 1; o < 32; o <<= 1) {
-          float m2 = __shfl_xor(m, o, 64), l2 = __shfl_xor(l, o, 64);
-          merge_ml(m, l, m2, l2);
-        }
-        if (b < nrb && col == 0) {
-          int row = (wsub + b * WPT) * 32 + (j >> 2) * 8 + half * 4 + (j & 3);
+        const float m = half_reduce<0>(st_m[b][j]);
+        const float l = half_reduce<1>(st_l[b][j] * fast_exp2(st_m[b][j] - m));
+        const int rb = wsub + b * WPT;
+        if (rb < MB && col == 0) {
+          const int row = rb * 32 + (j >> 2) * 8 + half * 4 + (j & 3);
           part[(kgid * a.mpad + row) * 2] = m;
           part[(kgid * a.mpad + row) * 2 + 1] = l;
         }
@@ -264,20 +340,24 @@ static bool use_mfma(const Dims& dm, int dtype) { return dtype == MADAKV_BF16 &&
 ScorePlan score_plan(const Dims& dm, int dtype) {
   ScorePlan p;
   p.mpad = (dm.M + 31) / 32 * 32;
-  // enough workgroups to fill 256 CUs a few times over, chunks a multiple of 128 keys
-  int want = std::max(1, (2048 + dm.heads - 1) / dm.heads);
-  int max_split = std::max(1, dm.L / 512);
-  int ns = std::min(std::min(want, max_split), 64);
+  // Both sweeps run over all heads of the call in one launch each.  (Splitting the call into
+  // groups of heads whose K fits the 256 MB memory-side cache, so that the second sweep finds
+  // its data there, was measured slower at every group size: MADAKV_SCORE_GROUP_MB tries it.)
+  long long head_bytes = (long long)dm.L * dm.d * (dtype == MADAKV_BF16 ? 2 : 4);
+  p.group_heads = dm.heads;
+  if (const char* e = getenv("MADAKV_SCORE_GROUP_MB")) {
+    long long gh = std::max(1LL, (long long)std::max(1, atoi(e)) * 1024 * 1024 / head_bytes);
+    p.group_heads = (int)std::min<long long>(gh, dm.heads);
+  }
+  // enough workgroups per launch to fill 256 CUs several times over; chunks are a multiple
+  // of 128 keys (4 waves x 32-key tiles) and at least 256 keys long
+  int want = std::max(1, (2048 + p.group_heads - 1) / p.group_heads);
+  int max_split = std::max(1, dm.L / 256);
+  int ns = std::min(std::min(want, max_split), 128);
   int chunk = ((dm.L + ns - 1) / ns + 127) / 128 * 128;
+  if (const char* e = getenv("MADAKV_SCORE_CHUNK")) { int v = atoi(e); if (v >= 128 && v % 128 == 0) chunk = std::max(chunk, std::min(v, (dm.L + 127) / 128 * 128)); }
   p.nsplit = (dm.L + chunk - 1) / chunk;
   p.chunk = chunk;
-  // heads per launch pair: keep the K bytes of a group small enough that the second
-  // sweep can find them in the memory-side cache
-  long long head_bytes = (long long)dm.L * dm.d * (dtype == MADAKV_BF16 ? 2 : 4);
-  long long group_mb = 96;
-  if (const char* e = getenv("MADAKV_SCORE_GROUP_MB")) group_mb = std::max(1, atoi(e));
-  long long gh = std::max(1LL, group_mb * 1024 * 1024 / head_bytes);
-  p.group_heads = (int)std::min<long long>(gh, dm.heads);
   return p;
 }
 
@@ -286,18 +366,18 @@ size_t score_ws_bytes(const Dims& dm, int dtype) {
   return (size_t)dm.heads * p.nsplit * p.mpad * 2 * sizeof(float);
 }
 
-template <int D, int WPT>
+template <int D, int WPT, int NRB>
 static void launch_mfma_pair(const ScoreArgs& a0, int heads, size_t lds1, size_t lds2, hipStream_t st) {
   ScoreArgs a = a0;
   dim3 grid(a.nsplit, heads);
   if (lds1 > 48 * 1024 || lds2 > 48 * 1024) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_mfma_kernel<D, WPT, 1>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_mfma_kernel<D, WPT, NRB, 1>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_mfma_kernel<D, WPT, 2>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_mfma_kernel<D, WPT, NRB, 2>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
   }
-  hipLaunchKernelGGL((score_mfma_kernel<D, WPT, 1>), grid, dim3(SCORE_THREADS), lds1, st, a);
-  hipLaunchKernelGGL((score_mfma_kernel<D, WPT, 2>), grid, dim3(SCORE_THREADS), lds2, st, a);
+  hipLaunchKernelGGL((score_mfma_kernel<D, WPT, NRB, 1>), grid, dim3(SCORE_THREADS), lds1, st, a);
+  hipLaunchKernelGGL((score_mfma_kernel<D, WPT, NRB, 2>), grid, dim3(SCORE_THREADS), lds2, st, a);
 }
 
 hipError_t launch_score(const Dims& dm, const madakv_config& c, const void* q_win, const void* k,
@@ -307,20 +387,26 @@ hipError_t launch_score(const Dims& dm, const madakv_config& c, const void* q_wi
   a.q_win = q_win; a.k = k; a.psi = psi; a.rowstat = reinterpret_cast<float*>(ws);
   a.H = dm.H; a.G = dm.G; a.d = dm.d; a.L = dm.L; a.W = dm.W; a.M = dm.M;
   a.mpad = p.mpad; a.nsplit = p.nsplit; a.chunk = p.chunk; a.head0 = 0;
+  a.dbg = 0;
+  if (const char* e = getenv("MADAKV_SCORE_DBG")) a.dbg = atoi(e);
   float scale = c.softmax_scale > 0.f ? c.softmax_scale : 1.0f / sqrtf((float)dm.d);
   a.scale_log2 = scale * 1.4426950408889634f;
   for (int h0 = 0; h0 < dm.heads; h0 += p.group_heads) {
     int nh = std::min(p.group_heads, dm.heads - h0);
     a.head0 = h0;
     if (use_mfma(dm, c.dtype)) {
-      int MB = p.mpad / 32;
-      int wpt = MB <= 2 ? 1 : (MB <= 4 ? 2 : 4);
-      size_t qbytes = (size_t)p.mpad * (dm.d + 8) * 2;
-      size_t lds1 = qbytes + (size_t)4 * p.mpad * 2 * sizeof(float);
-      size_t lds2 = qbytes + ((size_t)p.mpad + 128) * sizeof(float);
-#define MADAKV_SCORE_CASE(DD, WW) launch_mfma_pair<DD, WW>(a, nh, lds1, lds2, st)
-      if (dm.d == 128) { if (wpt == 1) MADAKV_SCORE_CASE(128, 1); else if (wpt == 2) MADAKV_SCORE_CASE(128, 2); else MADAKV_SCORE_CASE(128, 4); }
-      else             { if (wpt == 1) MADAKV_SCORE_CASE(64, 1);  else if (wpt == 2) MADAKV_SCORE_CASE(64, 2);  else MADAKV_SCORE_CASE(64, 4); }
+      // row blocks of 32 proxy rows: 1-2 -> every wave its own keys; 3-4 -> pairs of waves share
+      // keys; 5-8 -> all four waves share keys.  NRB = row blocks per wave.
+      const int MB = p.mpad / 32;
+      const size_t qbytes = ((size_t)p.mpad + 4 * 32) * (dm.d + 8) * 2;      // Q tile + one K subtile per wave
+      const size_t lds1 = qbytes + (size_t)4 * p.mpad * 2 * sizeof(float);
+      const size_t lds2 = qbytes + ((size_t)p.mpad + 2 * 4 * 32) * sizeof(float);
+#define MADAKV_SCORE_CASE(DD, WW, NN) launch_mfma_pair<DD, WW, NN>(a, nh, lds1, lds2, st)
+#define MADAKV_SCORE_BY_MB(DD) \
+      if (MB == 1) MADAKV_SCORE_CASE(DD, 1, 1); else if (MB == 2) MADAKV_SCORE_CASE(DD, 1, 2); \
+      else if (MB <= 4) MADAKV_SCORE_CASE(DD, 2, 2); else MADAKV_SCORE_CASE(DD, 4, 2)
+      if (dm.d == 128) { MADAKV_SCORE_BY_MB(128); } else { MADAKV_SCORE_BY_MB(64); }
+#undef MADAKV_SCORE_BY_MB
 #undef MADAKV_SCORE_CASE
     } else {
       size_t lds = ((size_t)dm.M * dm.d + dm.M) * sizeof(float);

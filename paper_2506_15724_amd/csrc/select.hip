@@ -22,7 +22,7 @@ constexpr int SEL_BINS = 2048;
 constexpr int SEL_ITEMS = 4;                     // consecutive candidates per thread per pass
 
 struct OffsetsArgs {
-  const int32_t* budgets; int64_t* kv_off; int32_t* kv_len; long long* cursor; int32_t* blk2head; long long* call_range;
+  const int32_t* budgets; int64_t* kv_off; int32_t* kv_len; long long* cursor; int32_t* blk2head; long long* call_range; int32_t* layer_maxlen;
   int n, B, H, L, W, layer0, max_new, keep_all, blocks_per_batch;
   long long region_tokens;
 };
@@ -30,6 +30,8 @@ struct OffsetsArgs {
 // One workgroup, wave w handles batch items w, w+nw, ...; lanes are heads.
 __global__ __launch_bounds__(256) void offsets_kernel(OffsetsArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  for (int li = threadIdx.x; li < a.n; li += blockDim.x) a.layer_maxlen[li] = 0;
+  __syncthreads();
   for (int b = wave; b < a.B; b += nw) {
     long long cur = (a.layer0 == 0) ? 0 : a.cursor[b];
     const long long start = cur;
@@ -53,6 +55,10 @@ __global__ __launch_bounds__(256) void offsets_kernel(OffsetsArgs a) {
       const long long used = first_bad == 0 ? 0 : shfl_i64(incl, max(first_bad - 1, 0));
       if (lane >= first_bad) { len = 0; seg = 0; incl = used; }
       const long long off = cur + incl - seg;                  // relative to the region start
+      // longest segment of the layer: lets the host size the decode grid without a sync
+      int mx = (int)len;
+      for (int o = 32; o > 0; o >>= 1) mx = max(mx, __shfl_xor(mx, o, 64));
+      if (lane == 0) atomicMax(&a.layer_maxlen[li], mx);
       if (lane < a.H) {
         a.kv_off[idx] = region + off;
         a.kv_len[idx] = (int32_t)len;
@@ -231,9 +237,10 @@ size_t select_ws_bytes(const Dims& dm, const madakv_config& c) {
 }
 
 hipError_t launch_offsets(const Dims& dm, const madakv_config& c, int layer0, const int32_t* budgets,
-                          int64_t* kv_off, int32_t* kv_len, long long* cursor_state, void* ws,
+                          int64_t* kv_off, int32_t* kv_len, long long* cursor_state, int32_t* layer_maxlen, void* ws,
                           long long region_tokens, int blocks_per_batch, hipStream_t st) {
   OffsetsArgs a;
+  a.layer_maxlen = layer_maxlen;
   a.budgets = budgets; a.kv_off = kv_off; a.kv_len = kv_len; a.cursor = cursor_state;
   a.call_range = reinterpret_cast<long long*>(ws);
   a.blk2head = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(ws) + ((size_t)dm.B * 2 * sizeof(long long) + 63) / 64 * 64);

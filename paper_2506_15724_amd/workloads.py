@@ -200,6 +200,22 @@ def decode_inputs(wl: Workload, l: int, b: int, step: int, device="cpu"):
     return q.to(dt), kn.to(dt), vn.to(dt)
 
 
+def decode_inputs_all(wl: Workload, step: int, device="cpu"):
+    """(q[NL,B,Hq,d], k_new[NL,B,H,d], v_new[NL,B,H,d]) of one decode step for the whole model,
+    drawn in one go (one generator per step); same recipe as decode_inputs."""
+    NL, B, H, Hq, d = wl.n_layers, wl.batch, wl.n_kv_heads, wl.n_q_heads, wl.head_dim
+    G = Hq // H
+    g = _torch_gen(wl, device, 5, step)
+    ps, us = zip(*[zip(*[head_preferences(wl, l, b, device) for b in range(B)]) for l in range(NL)])
+    p = torch.stack([torch.stack(x) for x in ps])                    # [NL, B, H]
+    u = torch.stack([torch.stack(x) for x in us])                    # [NL, B, H, d]
+    q = torch.randn(NL, B, Hq, d, generator=g, device=device) + u.repeat_interleave(G, dim=2)
+    kn = torch.randn(NL, B, H, d, generator=g, device=device) + 2.0 * p[..., None] * u
+    vn = torch.randn(NL, B, H, d, generator=g, device=device)
+    dt = wl.torch_dtype
+    return q.to(dt).contiguous(), kn.to(dt).contiguous(), vn.to(dt).contiguous()
+
+
 def to_f64(t: torch.Tensor) -> np.ndarray:
     """Exact float64 copy of a tensor's values on the host (what the checker reads)."""
     return t.detach().to("cpu", torch.float64).numpy()
