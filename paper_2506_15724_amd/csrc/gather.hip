@@ -9,6 +9,9 @@
 
 namespace madakv {
 
+// native vector type: arrays of it stay in registers (the HIP uint4 struct ends up in scratch)
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
+
 struct GatherArgs {
   const void* k; const void* v; const int32_t* kept_idx; const int64_t* kv_off; const int32_t* kv_len;
   void* k_c; void* v_c; const long long* call_range; const int32_t* blk2head;
@@ -31,39 +34,69 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
   const long long region = (long long)b * a.region_tokens;
   const int nh = a.n * a.H;
   int hh = a.blk2head[(long long)b * a.blocks_per_batch + blockIdx.x];
-  const uint4* kin = reinterpret_cast<const uint4*>(a.k);
-  const uint4* vin = reinterpret_cast<const uint4*>(a.v);
-  uint4* kout = reinterpret_cast<uint4*>(a.k_c);
-  uint4* vout = reinterpret_cast<uint4*>(a.v_c);
+  const u32x4_t* kin = reinterpret_cast<const u32x4_t*>(a.k);
+  const u32x4_t* vin = reinterpret_cast<const u32x4_t*>(a.v);
+  u32x4_t* kout = reinterpret_cast<u32x4_t*>(a.k_c);
+  u32x4_t* vout = reinterpret_cast<u32x4_t*>(a.v_c);
 
-  uint4 kv[ITERS], vv[ITERS];
-  long long dst[ITERS];
+  // Phases, so that dependent index loads never sit between the row loads of another row
+  // (load counters retire in order: a wait for an index would also wait for every row load
+  // issued before it): kept positions + the segment table of the next few heads, then all
+  // row loads, then all stores.
+  long long dst[ITERS]; int kidx[ITERS]; bool inr[ITERS];
 #pragma unroll
   for (int it = 0; it < ITERS; ++it) {
     const long long r = row0 + wave * ROWS_PER_WAVE + it * RPI + sub;     // row relative to the region
-    dst[it] = -1;
-    if (r >= start && r < end) {
-      // advance to the head whose segment holds row r (segments tile the range without gaps)
-      int h2 = hh;
-      while (h2 + 1 < nh) {
-        const int li = (h2 + 1) / a.H, h = (h2 + 1) % a.H;
-        if (a.kv_off[((long long)li * a.B + b) * a.H + h] - region > r) break;
-        ++h2;
+    inr[it] = r >= start && r < end;
+    dst[it] = region + r;
+    kidx[it] = inr[it] ? a.kept_idx[dst[it]] : 0;                          // free slots hold garbage: unused below
+  }
+  // segments of the first head overlapping the block and its successors (they tile the range)
+  constexpr int NC = 4;
+  long long coff[NC + 1]; int clen[NC];
+#pragma unroll
+  for (int c = 0; c <= NC; ++c) {
+    const int hc = min(hh + c, nh - 1);
+    const long long hidx = ((long long)(hc / a.H) * a.B + b) * a.H + (hc % a.H);
+    coff[c] = (hh + c < nh) ? a.kv_off[hidx] - region : end;               // past the last head: the end of the range
+    if (c < NC) clen[c] = a.kv_len[hidx];
+  }
+  long long src[ITERS];
+#pragma unroll
+  for (int it = 0; it < ITERS; ++it) {
+    const long long r = dst[it] - region;
+    src[it] = -1;
+    if (inr[it]) {
+      int hsel = hh; long long hoff = coff[0]; int hlen = clen[0];
+#pragma unroll
+      for (int c = 1; c < NC; ++c)
+        if (hh + c < nh && coff[c] <= r) { hsel = hh + c; hoff = coff[c]; hlen = clen[c]; }
+      if (hh + NC < nh && coff[NC] <= r) {
+        // more than NC segments start inside this block (very short segments): walk on
+        int h2 = hh + NC;
+        while (h2 + 1 < nh) {
+          const int li = (h2 + 1) / a.H, h = (h2 + 1) % a.H;
+          if (a.kv_off[((long long)li * a.B + b) * a.H + h] - region > r) break;
+          ++h2;
+        }
+        const long long hidx = ((long long)(h2 / a.H) * a.B + b) * a.H + (h2 % a.H);
+        hsel = h2; hoff = a.kv_off[hidx] - region; hlen = a.kv_len[hidx];
       }
-      const int li = h2 / a.H, h = h2 % a.H;
-      const long long hidx = ((long long)li * a.B + b) * a.H + h;
-      const long long j = region + r - a.kv_off[hidx];
-      if (j < a.kv_len[hidx]) {                 // rows past kv_len are the free decode slots
-        const long long src = hidx * a.L + a.kept_idx[region + r];
-        kv[it] = kin[src * LPR + piece];
-        vv[it] = vin[src * LPR + piece];
-        dst[it] = region + r;
-      }
+      const long long hidx = ((long long)(hsel / a.H) * a.B + b) * a.H + (hsel % a.H);
+      if (r - hoff < hlen)                       // rows past kv_len are the free decode slots
+        src[it] = hidx * a.L + kidx[it];
     }
+  }
+  u32x4_t kv[ITERS], vv[ITERS];
+#pragma unroll
+  for (int it = 0; it < ITERS; ++it) {
+    const long long s0 = src[it] >= 0 ? src[it] : 0;     // an in-bounds dummy keeps the load unconditional
+    kv[it] = kin[s0 * LPR + piece];
+    vv[it] = vin[s0 * LPR + piece];
   }
 #pragma unroll
   for (int it = 0; it < ITERS; ++it) {
-    if (dst[it] >= 0) {
+    if (src[it] >= 0) {
       kout[dst[it] * LPR + piece] = kv[it];
       vout[dst[it] * LPR + piece] = vv[it];
     }

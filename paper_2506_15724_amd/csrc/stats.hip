@@ -4,7 +4,8 @@
 // plus the max-pooled scores used for ranking, and the candidate counts per modality.
 //
 // One workgroup per (layer, batch, KV head).  Masses are summed in 64-bit fixed point
-// (2^-38 units): integer adds commute, so LDS atomics give the same bits on every run
+// (2^-44 units; a head's scores sum to G*W <= 256, so the total stays below 2^52): integer
+// adds commute, so LDS atomics give the same bits on every run
 // and the counts k_m, which are integers decided by a mass threshold, are reproducible.
 // k_m is found without sorting by a radix descent on the float bit pattern (11 + 11 + 9
 // bits): each level histograms count and mass per bin for the elements that match the
@@ -17,7 +18,7 @@ namespace madakv {
 
 constexpr int STATS_THREADS = 512;
 constexpr int BINS = 2048;
-constexpr float FX_SCALE = 274877906944.0f;      // 2^38
+constexpr float FX_SCALE = 17592186044416.0f;    // 2^44
 constexpr float PSI_MAX = 256.0f;                // G * W <= 256 bounds any column sum
 
 struct StatsArgs {
@@ -28,7 +29,7 @@ struct StatsArgs {
 
 __device__ __forceinline__ unsigned long long to_fx(float v) {
   v = fminf(fmaxf(v, 0.f), PSI_MAX);
-  return (unsigned long long)(v * FX_SCALE);      // exact product (power of two), truncating convert
+  return __float2ull_rn(v * FX_SCALE);            // exact product (power of two); exact integer for v >= 2^-21
 }
 __device__ __forceinline__ uint32_t nonneg_bits(float v) {
   v = fminf(fmaxf(v, 0.f), PSI_MAX);

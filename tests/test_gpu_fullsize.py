@@ -1,0 +1,185 @@
+"""Parity at the full sizes of the five named configurations, in the launch configuration the
+benchmark times (eviction: all layers per call; decode: one call per layer).  The oracle
+cannot run whole models of this size in seconds, so each test checks
+  * sampled heads element by element against the oracle (scores, statistics, pooled scores,
+    kept indices, gathered rows, decode output), each stage fed the GPU's upstream values, and
+  * properties that hold for every head at any size (row sums of the softmax, exact
+    conservation of the budget, ascending unique in-range indices, segment tiling)."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import madakv_oracle as O
+from paper_2506_15724_amd import binding as MB
+from paper_2506_15724_amd import workloads as WL
+from tests import parity_utils as PU
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(msg):
+    print(f"[fullsize] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def run_full(wl, samples, decode_steps=2):
+    NL, B, H, Hq, L, W, d = wl.n_layers, wl.batch, wl.n_kv_heads, wl.n_q_heads, wl.ctx_len, wl.window, wl.head_dim
+    G, nc = Hq // H, L - W
+    p = PU.oracle_params(wl)
+    say(f"{wl.name}: generating inputs on the GPU")
+    masks = [WL.modality_mask(wl, b) for b in range(B)]
+    k = torch.empty(NL, B, H, L, d, dtype=wl.torch_dtype, device=DEV)
+    v = torch.empty(NL, B, H, L, d, dtype=wl.torch_dtype, device=DEV)
+    q = torch.empty(NL, B, Hq, W, d, dtype=wl.torch_dtype, device=DEV)
+    for l in range(NL):
+        for b in range(B):
+            q[l, b], k[l, b], v[l, b] = WL.layer_inputs(wl, l, b, masks[b], DEV)
+    mask = torch.from_numpy(np.stack(masks)).to(DEV)
+    eng = MB.MadaKV(n_layers=NL, batch=B, n_q_heads=Hq, n_kv_heads=H, head_dim=d, ctx_len=L, window=W, budget=wl.budget,
+                    dtype=wl.dtype, pool_k=wl.pool_k, max_new_tokens=decode_steps, out_fp32=1, device=DEV)
+    say(f"{wl.name}: score + allocate + select_gather over all {NL} layers")
+    eng.score(0, NL, q, k, mask)
+    eng.allocate(0, NL)
+    eng.select_gather(0, NL, k, v, mask)
+    torch.cuda.synchronize()
+
+    # ---- properties over every head
+    psi_sum = eng.psi.sum(-1)
+    assert torch.allclose(psi_sum, torch.full_like(psi_sum, float(G * W)), rtol=3e-4), "softmax rows must sum to 1"
+    bud = eng.budgets.to(torch.int64)
+    per_batch = bud.sum(dim=(0, 2, 3)).cpu().numpy()
+    assert (per_batch == NL * H * (wl.budget - W)).all(), "budgets are conserved exactly per batch item"
+    n_mod = eng.n_mod.cpu().numpy()
+    assert (bud[..., 0] >= 0).all() and (bud[..., 1] >= 0).all()
+    for b in range(B):
+        assert int(bud[:, b, :, 0].max()) <= n_mod[b, 0] and int(bud[:, b, :, 1].max()) <= n_mod[b, 1]
+        assert tuple(n_mod[b]) == (int((masks[b][:nc] == 0).sum()), int((masks[b][:nc] == 1).sum()))
+    kv_len, kv_off = eng.kv_len.cpu().numpy().astype(np.int64), eng.kv_off.cpu().numpy()
+    assert (kv_len == bud.sum(-1).cpu().numpy() + W).all()
+    cap_b = eng.capacity // B
+    for b in range(B):                                      # segments tile the batch item's region in (layer, head) order
+        seg = (kv_len[:, b] + decode_steps).reshape(-1)
+        want = b * cap_b + np.concatenate([[0], np.cumsum(seg)[:-1]])
+        assert (kv_off[:, b].reshape(-1) == want).all()
+        assert want[-1] + seg[-1] == (b + 1) * cap_b
+    # kept indices of every head: ascending, in range, window suffix (checked on the device)
+    idx = eng.kept_idx
+    offs_t, lens_t = eng.kv_off.reshape(-1), eng.kv_len.reshape(-1).to(torch.int64)
+    pos = torch.arange(eng.capacity, device=DEV)
+    seg_id = torch.bucketize(pos, offs_t.sort().values, right=True) - 1
+    order = offs_t.argsort()
+    start = offs_t[order][seg_id]
+    rel = pos - start
+    valid = rel < lens_t[order][seg_id]
+    nxt_valid = valid[1:] & valid[:-1] & (seg_id[1:] == seg_id[:-1])
+    assert (idx[1:][nxt_valid] > idx[:-1][nxt_valid]).all(), "kept positions ascend within every head"
+    assert (idx[valid] >= 0).all() and (idx[valid] < L).all()
+    last = valid & (rel == lens_t[order][seg_id] - 1)
+    assert (idx[last] == L - 1).all(), "the window closes every segment"
+
+    # ---- sampled heads against the oracle
+    for (l, b, h) in samples:
+        say(f"{wl.name}: oracle on layer {l} batch {b} head {h}")
+        qh = WL.to_f64(q[l, b, h * G:(h + 1) * G]); kh = WL.to_f64(k[l, b, h:h + 1])
+        psi_o = O.window_scores(qh, kh, p.scale)[0]
+        psi_g = eng.psi[l, b, h].cpu().numpy()
+        nbad, worst = PU.psi_close(psi_g, psi_o, G, W, L)
+        assert nbad == 0, (l, b, h, worst)
+        psi_in = psi_g.astype(np.float64)[None]
+        w_o, k_o, _ = O.modality_stats(psi_in, masks[b], W, p.theta)
+        st = eng.stats[l, b, h].cpu()
+        w_g = st[:2].view(torch.float32).numpy(); k_g = st[2:].numpy()
+        np.testing.assert_allclose(w_g, w_o[0], rtol=2e-6)
+        for m in (0, 1):
+            if k_g[m] != k_o[0, m]:
+                assert PU.k_count_ok(int(k_g[m]), psi_in[0, :nc][masks[b][:nc] == m], p.theta)
+        pool_g = eng.psi_pool[l, b, h].cpu().numpy()
+        np.testing.assert_array_equal(pool_g, O.pool_scores(psi_in, W, p.pool_k)[0].astype(np.float32))
+        bt, bv = (int(x) for x in eng.budgets[l, b, h].cpu())
+        kept_o = O.select(pool_g.astype(np.float64), masks[b], bt, bv, L, W)
+        o, n = int(kv_off[l, b, h]), int(kv_len[l, b, h])
+        np.testing.assert_array_equal(eng.kept_idx[o:o + n].cpu().numpy(), kept_o)
+        sel = torch.from_numpy(kept_o).to(DEV)
+        assert torch.equal(eng.k_c[o:o + n], k[l, b, h][sel]) and torch.equal(eng.v_c[o:o + n], v[l, b, h][sel])
+
+    # ---- decode: one call per layer, as the benchmark does; sampled heads against Eq. 5
+    out = torch.empty(NL, B, Hq, d, dtype=torch.float32, device=DEV)
+    caches = {s: [WL.to_f64(eng.k_c[int(kv_off[s]):int(kv_off[s]) + int(kv_len[s])]),
+                  WL.to_f64(eng.v_c[int(kv_off[s]):int(kv_off[s]) + int(kv_len[s])])] for s in samples}
+    for step in range(decode_steps):
+        dq, dk, dv = WL.decode_inputs_all(wl, step, DEV)
+        say(f"{wl.name}: decode step {step}, one call per layer")
+        for l in range(NL):
+            eng.decode_attn(l, 1, dq[l:l + 1], dk[l:l + 1], dv[l:l + 1], out[l:l + 1])
+        torch.cuda.synchronize()
+        assert torch.isfinite(out).all()
+        for (l, b, h) in samples:
+            kc, vc = caches[(l, b, h)]
+            kc = np.concatenate([kc, WL.to_f64(dk[l, b, h])[None]]); vc = np.concatenate([vc, WL.to_f64(dv[l, b, h])[None]])
+            caches[(l, b, h)] = [kc, vc]
+            for g in range(G):
+                ref = O.attend(WL.to_f64(dq[l, b, h * G + g]), kc, vc, p.scale)
+                err = np.abs(out[l, b, h * G + g].cpu().numpy() - ref).max()
+                assert err <= PU.DECODE_ATOL, (step, l, b, h, g, err)
+    assert (eng.kv_len.cpu().numpy() == kv_len + decode_steps).all()
+    # all layers in one call gives the same numbers as one call per layer (attend only)
+    out2 = torch.empty_like(out)
+    eng.decode_attn(0, NL, dq, None, None, out2)
+    for l in range(NL):
+        eng.decode_attn(l, 1, dq[l:l + 1], None, None, out[l:l + 1])
+    torch.cuda.synchronize()
+    assert torch.allclose(out, out2, atol=2e-5, rtol=1e-4)
+    eng.close()
+    del k, v, q
+    torch.cuda.empty_cache()
+
+
+def test_full_llava_layer():
+    wl = WL.CONFIGS["llava_layer"]
+    run_full(wl, [(0, 0, h) for h in (0, 7, 19, 31)])
+
+
+def test_full_llava_16k():
+    wl = WL.CONFIGS["llava_16k"]
+    run_full(wl, [(0, 0, 0), (3, 1, 5), (15, 2, 17), (16, 3, 30), (31, 3, 31)])
+
+
+def test_full_qwen_gqa():
+    wl = WL.CONFIGS["qwen_gqa"]
+    run_full(wl, [(0, 0, 0), (13, 0, 2), (27, 0, 3)])
+
+
+@pytest.mark.parametrize("budget", [512, 4096])
+def test_full_long_128k(budget):
+    wl = WL.CONFIGS["long_128k"].scaled(budget=budget)
+    run_full(wl, [(0, 0, 0), (0, 0, 13), (0, 0, 31)])
+
+
+def test_hcc_drafts_take_both_signs_on_the_16k_workload():
+    """The layer-temperature profile of the generator is there so that the compensation K^l of
+    Eq. 10 is positive in some layers and negative in others; checked on the GPU's budgets."""
+    wl = WL.CONFIGS["llava_16k"].scaled(batch=1)
+    NL, H, W = wl.n_layers, wl.n_kv_heads, wl.window
+    masks = [WL.modality_mask(wl, 0)]
+    mask = torch.from_numpy(np.stack(masks)).to(DEV)
+    eng = MB.MadaKV(n_layers=NL, batch=1, n_q_heads=H, n_kv_heads=H, head_dim=wl.head_dim, ctx_len=wl.ctx_len, window=W,
+                    budget=wl.budget, dtype="bf16", pool_k=wl.pool_k, device=DEV, layers_per_call=1)
+    for l in range(NL):
+        ql, kl, _ = WL.layer_inputs(wl, l, 0, masks[0], DEV)
+        eng.score(l, 1, ql[None, None].contiguous(), kl[None, None].contiguous(), mask)
+        eng.allocate(l, 1)
+    torch.cuda.synchronize()
+    tot = eng.budgets.sum(dim=(1, 2, 3)).cpu().numpy().astype(np.int64)          # layer totals A_l
+    beta = wl.budget - W
+    R, signs = NL * H * beta, []
+    for l in range(NL):
+        phi = R / (H * (NL - l))
+        signs.append(np.sign(tot[l] - H * phi))
+        R -= int(tot[l])
+    assert R == 0
+    say(f"layer drafts relative to the running nominal: {''.join('+' if s > 0 else '-' if s < 0 else '0' for s in signs)}")
+    assert (np.array(signs) > 0).any() and (np.array(signs) < 0).any()
+    eng.close()
