@@ -77,30 +77,49 @@ class LayerCalls:
                 raise RuntimeError(f"madakv_decode_attn layer {l} -> {rc}")
 
 
-def cpu_baseline(wl, q, k, v, masks):
-    """The oracle as it stands, timed on the host cores on a bounded sample: the eviction
-    (Eq. 7, 6, 9, pooling, Eq. 8/10/11 for that layer alone, selection, gather) of one layer of
-    one batch item, all its heads; scaled to the whole model by the layer and batch count."""
-    import numpy as np
+def cpu_baseline(wl, q, k, v, masks, n_sample_layers=8):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the same
+    workload: the whole eviction (Eq. 7, 6, 9, pooling, Eq. 8/10/11, selection, gather) of every
+    `stride`-th layer of every batch item, run as a model of that many layers; scaled to the
+    full layer count."""
     from oracle import madakv_oracle as O
     from paper_2506_15724_amd import workloads as WL
-    p = O.Params(n_layers=1, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads, head_dim=wl.head_dim, ctx_len=wl.ctx_len,
-                 window=wl.window, budget=wl.budget, pool_k=wl.pool_k)
-    qh, kh, vh = WL.to_f64(q[0, 0])[None], WL.to_f64(k[0, 0])[None], WL.to_f64(v[0, 0])[None]
-    t0 = time.perf_counter()
-    O.evict(qh, kh, vh, masks[0], p)
-    dt = time.perf_counter() - t0
+    NL, B = wl.n_layers, wl.batch
+    n_s = min(n_sample_layers, NL)
+    layers = [int(round(i * (NL - 1) / max(1, n_s - 1))) for i in range(n_s)] if n_s > 1 else [0]
+    p = O.Params(n_layers=n_s, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads, head_dim=wl.head_dim,
+                 ctx_len=wl.ctx_len, window=wl.window, budget=wl.budget, pool_k=wl.pool_k)
+    dt = 0.0
+    for b in range(B):
+        qh = WL.to_f64(q[layers, b]); kh = WL.to_f64(k[layers, b]); vh = WL.to_f64(v[layers, b])
+        t0 = time.perf_counter()
+        O.evict(qh, kh, vh, masks[b], p)
+        dt += time.perf_counter() - t0
+        del qh, kh, vh
     try:
         from threadpoolctl import threadpool_info
         threads = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
     except Exception:
         threads = 1
     cores = min(threads, len(os.sched_getaffinity(0)))
-    tokens_per_s = wl.ctx_len / (dt * wl.n_layers)      # whole-model eviction of one batch item takes n_layers * dt
-    return {"value": tokens_per_s, "unit": "ctx-tokens/s", "cores": cores, "kind": "oracle",
-            "sample": f"eviction of 1 of {wl.n_layers} layers x 1 of {wl.batch} batch items ({wl.n_kv_heads} heads, "
-                      f"L={wl.ctx_len}) took {dt:.2f} s; scaled by the layer count",
-            "seconds": dt}
+    full_seconds = dt * NL / n_s                      # all layers of all batch items
+    return {"value": B * wl.ctx_len / full_seconds, "unit": "ctx-tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"NumPy fp64 oracle, eviction of {n_s} of {NL} layers (layers {layers}) x all {B} batch items, "
+                      f"{wl.n_kv_heads} heads, L={wl.ctx_len}: {dt:.1f} s measured, scaled by {NL}/{n_s}",
+            "seconds_measured": dt}
+
+
+def read_traffic(kernel_tag):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
+    (profiles/<kernel_tag>_traffic.txt, line `traffic_bytes_per_launch=<n>`), or None."""
+    path = os.path.join(ROOT, "profiles", f"{kernel_tag}_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch="):
+                return float(line.split("=", 1)[1])
+    except OSError:
+        pass
+    return None
 
 
 def main():
@@ -111,6 +130,10 @@ def main():
     ap.add_argument("--workload", default="llava_16k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the multi-layer-launch and full-cache decode timings")
+    ap.add_argument("--decode-steps", type=int, default=0,
+                    help="decode steps per bench step (default: the workload's own count; fewer only for profiling runs)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain 1 GiB device copy a few times (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding or collectives in the method's hot path); "
@@ -128,10 +151,18 @@ def main():
         sys.exit(2)
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if a.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(3)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": 1 << 30, "calibrate_copy_bytes_written": 1 << 30, "launches": 4}))
+        return
     wl = WL.CONFIGS[a.workload]
     NL, B, H, Hq, L, W, d = wl.n_layers, wl.batch, wl.n_kv_heads, wl.n_q_heads, wl.ctx_len, wl.window, wl.head_dim
     es = 2 if wl.dtype == "bf16" else 4
-    S = wl.decode_steps
+    S = a.decode_steps if a.decode_steps > 0 else wl.decode_steps
     log(f"workload {wl.name}: {NL} layers, B={B}, H={H}, L={L}, d={d}, W={W}, budget={wl.budget}, {S} decode steps")
     t0 = time.time()
     q, k, v, mask, masks = build_inputs(wl, dev)
@@ -192,7 +223,8 @@ def main():
     achieved = decode_bytes / (decode_med * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": "decode_attn_kernel (+ its merge kernel), one launch per layer",
                 "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                "traffic": None, "bytes_per_launch": decode_bytes / launches, "us_per_launch": per_launch_us}
+                "traffic": read_traffic("decode_attn_kernel_llava_16k") if wl.name == "llava_16k" else None,
+                "bytes_per_launch": decode_bytes / launches, "us_per_launch": per_launch_us}
 
     # eviction bytes: K read once for scoring, kept K,V rows read and written by the gather
     kept_rows = rows_first
