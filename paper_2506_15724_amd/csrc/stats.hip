@@ -56,25 +56,45 @@ __global__ __launch_bounds__(STATS_THREADS) void stats_kernel(StatsArgs a) {
     for (int e = tid; e < 2 * BINS; e += STATS_THREADS) { (&cnt[0][0])[e] = 0; (&sum[0][0])[e] = 0ULL; }
     __syncthreads();
     const int sh = shifts[level], wd = widths[level];
-    for (int i = tid; i < a.nc; i += STATS_THREADS) {
-      const float v = psi[i];
-      const int m = mask[i] ? 1 : 0;
+    // U elements per thread per trip, all their loads issued before any is used: the loop is
+    // bound by load latency, not by the atomics
+    constexpr int U = 8;
+    for (int i0 = tid; i0 < a.nc; i0 += STATS_THREADS * U) {
+      float v[U]; int m[U]; bool ok[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int i = i0 + u * STATS_THREADS;
+        ok[u] = i < a.nc;
+        v[u] = ok[u] ? psi[i] : 0.f;
+        m[u] = (ok[u] && mask[i]) ? 1 : 0;
+      }
       if (level == 0) {
         // pooled score for ranking: max over the clipped neighbourhood (raw values)
-        float mx = v;
+        float mx[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) mx[u] = v[u];
         for (int r = 1; r <= a.pool_r; ++r) {
-          if (i - r >= 0) mx = fmaxf(mx, psi[i - r]);
-          if (i + r < a.nc) mx = fmaxf(mx, psi[i + r]);
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            const int i = i0 + u * STATS_THREADS;
+            const float lo = (ok[u] && i - r >= 0) ? psi[i - r] : mx[u];
+            const float hi = (ok[u] && i + r < a.nc) ? psi[i + r] : mx[u];
+            mx[u] = fmaxf(mx[u], fmaxf(lo, hi));
+          }
         }
-        pool[i] = mx;
+#pragma unroll
+        for (int u = 0; u < U; ++u) if (ok[u]) pool[i0 + u * STATS_THREADS] = mx[u];
       }
-      const uint32_t key = nonneg_bits(v);
-      bool match = true;
-      if (level > 0) match = (s_done[m] == 0) && ((key >> (sh + wd)) == s_prefix[m]);
-      if (match) {
-        const uint32_t bin = (key >> sh) & ((1u << wd) - 1u);
-        atomicAdd(&cnt[m][bin], 1u);
-        atomicAdd(&sum[m][bin], to_fx(v));
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const uint32_t key = nonneg_bits(v[u]);
+        bool match = ok[u];
+        if (level > 0) match = match && (s_done[m[u]] == 0) && ((key >> (sh + wd)) == s_prefix[m[u]]);
+        if (match) {
+          const uint32_t bin = (key >> sh) & ((1u << wd) - 1u);
+          atomicAdd(&cnt[m[u]][bin], 1u);
+          atomicAdd(&sum[m[u]][bin], to_fx(v[u]));
+        }
       }
     }
     __syncthreads();
