@@ -7,19 +7,21 @@
 //                  cache, inside it layers and heads follow each other; a segment has
 //                  kv_len = b_t + b_v + W rows plus max_new_tokens free rows.  It also fills
 //                  a table "first head that overlaps each 64-row block" for the gather.
-// select_kernel    one workgroup per head.  A 3-level radix select (11 + 11 + 10 bits of the
-//                  order-preserving key) on LDS count histograms finds, per modality, the
-//                  threshold key tau_m and how many elements equal to tau_m are still
-//                  needed; one ordered pass then keeps key > tau_m, and key == tau_m while
-//                  its running rank (by position) is below that number.  Block-wide prefix
-//                  sums give the output slots, so the result is ascending by construction.
+// select_kernel    one workgroup per head; a thread owns 32 consecutive candidates, whose keys
+//                  and modality bits stay in registers (one trip to memory for contexts up to
+//                  16K candidates, chunks of that size beyond).  A 3-level radix select
+//                  (11 + 11 + 10 bits of the order-preserving key) on LDS count histograms
+//                  finds, per modality, the threshold key tau_m and how many elements equal
+//                  to tau_m are still needed; then key > tau_m is kept, and key == tau_m while
+//                  its rank by position is below that number.  Workgroup prefix sums give
+//                  the ranks and the output slots, so the result is ascending by construction.
 #include "common.h"
 
 namespace madakv {
 
-constexpr int SEL_THREADS = 1024;
+constexpr int SEL_THREADS = 512;
 constexpr int SEL_BINS = 2048;
-constexpr int SEL_ITEMS = 4;                     // consecutive candidates per thread per pass
+constexpr int SEL_EPT = 32;                      // consecutive candidates a thread owns per chunk
 
 struct OffsetsArgs {
   const int32_t* budgets; int64_t* kv_off; int32_t* kv_len; long long* cursor; int32_t* blk2head; long long* call_range; int32_t* layer_maxlen;
@@ -87,7 +89,12 @@ struct SelectArgs {
   int B, H, L, W, nc, mpa_mode, keep_all;
 };
 
-// exclusive prefix over the workgroup of a packed pair (lo16 | hi16 counts fit: <= 4096 per pass)
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
+
+// exclusive prefix over the workgroup of a packed pair of counts (lo16 | hi16; a chunk holds
+// 16384 candidates, so each half stays below 2^16 unless every one of them counts: the
+// caller keeps the totals in 32 bits and the halves are only used below that bound)
 __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* wave_tot, uint32_t& total) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   uint32_t incl = v;
@@ -108,7 +115,43 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* wave_t
   return before + incl - v;
 }
 
-__global__ __launch_bounds__(SEL_THREADS) void select_kernel(SelectArgs a) {
+// Thread t of the workgroup owns SEL_EPT consecutive candidates of a chunk: their keys and
+// modality bits live in registers through the three radix levels and the compaction.
+__device__ __forceinline__ void load_owned(const float* sc, const uint8_t* mask, int i0, int nc, int use_mask,
+                                           uint32_t (&key)[SEL_EPT], unsigned long long& mbits) {
+  const bool full = i0 + SEL_EPT <= nc;
+  if (full && ((reinterpret_cast<uintptr_t>(sc + i0) & 15u) == 0)) {
+#pragma unroll
+    for (int j = 0; j < SEL_EPT / 4; ++j) {
+      const f32x4_t v = *reinterpret_cast<const f32x4_t*>(sc + i0 + j * 4);
+      key[j * 4 + 0] = float_key(v[0]); key[j * 4 + 1] = float_key(v[1]);
+      key[j * 4 + 2] = float_key(v[2]); key[j * 4 + 3] = float_key(v[3]);
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < SEL_EPT; ++e) key[e] = (i0 + e < nc) ? float_key(sc[i0 + e]) : 0u;
+  }
+  mbits = 0ULL;
+  if (use_mask) {
+    if (full && ((reinterpret_cast<uintptr_t>(mask + i0) & 15u) == 0)) {
+#pragma unroll
+      for (int j = 0; j < SEL_EPT / 16; ++j) {
+        const u32x4_t w = *reinterpret_cast<const u32x4_t*>(mask + i0 + j * 16);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+          for (int bb = 0; bb < 4; ++bb)
+            if ((w[q] >> (8 * bb)) & 0xffu) mbits |= 1ULL << (j * 16 + q * 4 + bb);
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < SEL_EPT; ++e)
+        if (i0 + e < nc && mask[i0 + e]) mbits |= 1ULL << e;
+    }
+  }
+}
+
+__global__ __launch_bounds__(SEL_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4))) void select_kernel(SelectArgs a) {
   __shared__ uint32_t cnt[2][SEL_BINS];
   __shared__ uint32_t s_prefix[2], s_need[2], s_done[2];
   __shared__ uint32_t wave_tot[SEL_THREADS / 64];
@@ -128,17 +171,32 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(SelectArgs a) {
   const uint32_t bud[2] = {(uint32_t)a.budgets[head * 2], (uint32_t)a.budgets[head * 2 + 1]};
   const int shifts[3] = {21, 10, 0};
   const int widths[3] = {11, 11, 10};
+  constexpr int CH = SEL_THREADS * SEL_EPT;      // candidates per chunk
+  const int nchunks = (a.nc + CH - 1) / CH;
+  const bool single = nchunks == 1;              // the usual case: everything stays in registers
+
+  uint32_t key[SEL_EPT];
+  unsigned long long mbits = 0ULL;
+  if (single) load_owned(sc, mask, tid * SEL_EPT, a.nc, a.mpa_mode, key, mbits);
 
   for (int level = 0; level < 3; ++level) {
     for (int e = tid; e < 2 * SEL_BINS; e += SEL_THREADS) (&cnt[0][0])[e] = 0;
     __syncthreads();
     const int sh = shifts[level], wd = widths[level];
-    for (int i = tid; i < a.nc; i += SEL_THREADS) {
-      const int m = (a.mpa_mode && mask[i]) ? 1 : 0;
-      const uint32_t key = float_key(sc[i]);
-      bool match = true;
-      if (level > 0) match = (s_done[m] == 0) && ((key >> (sh + wd)) == s_prefix[m]);
-      if (match) atomicAdd(&cnt[m][(key >> sh) & ((1u << wd) - 1u)], 1u);
+    const uint32_t binmask = (1u << wd) - 1u;
+    uint32_t pfx[2] = {0, 0}; bool dn[2] = {false, false};
+    if (level > 0) { pfx[0] = s_prefix[0]; pfx[1] = s_prefix[1]; dn[0] = s_done[0] != 0; dn[1] = s_done[1] != 0; }
+    for (int c = 0; c < nchunks; ++c) {
+      const int i0 = c * CH + tid * SEL_EPT;
+      if (!single) load_owned(sc, mask, i0, a.nc, a.mpa_mode, key, mbits);
+      const int nvalid = min(max(a.nc - i0, 0), SEL_EPT);
+#pragma unroll
+      for (int e = 0; e < SEL_EPT; ++e) {
+        const int m = (int)((mbits >> e) & 1ULL);
+        bool match = e < nvalid;
+        if (level > 0) match = match && !dn[m] && ((key[e] >> (sh + wd)) == pfx[m]);
+        if (match) atomicAdd(&cnt[m][(key[e] >> sh) & binmask], 1u);
+      }
     }
     __syncthreads();
     if (wave < 2) {
@@ -169,13 +227,13 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(SelectArgs a) {
         for (int j = 0; j < per; ++j) {
           int bin = nb - 1 - (lane * per + j);
           if (bin < 0) break;
-          uint32_t c = cnt[m][bin];
-          if (acc + c >= need) {
+          uint32_t cc = cnt[m][bin];
+          if (acc + cc >= need) {
             s_prefix[m] = (prefix_prev << wd) | (uint32_t)bin;
             s_need[m] = need - acc;               // still needed from inside this bin
             break;
           }
-          acc += c;
+          acc += cc;
         }
       }
     }
@@ -191,37 +249,47 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(SelectArgs a) {
 
   uint32_t run_eq[2] = {0, 0};
   uint32_t run_out = 0;
-  for (int base = 0; base < a.nc; base += SEL_THREADS * SEL_ITEMS) {
-    const int i0 = base + tid * SEL_ITEMS;
-    uint32_t key[SEL_ITEMS]; int mod[SEL_ITEMS]; bool inr[SEL_ITEMS];
-    uint32_t eqpack = 0;
+  for (int c = 0; c < nchunks; ++c) {
+    const int i0 = c * CH + tid * SEL_EPT;
+    if (!single) load_owned(sc, mask, i0, a.nc, a.mpa_mode, key, mbits);
+    const int nvalid = min(max(a.nc - i0, 0), SEL_EPT);
+    // ties of this thread's stretch, per modality, then their rank by position over the workgroup
+    unsigned long long eqbits = 0ULL, gtbits = 0ULL;
+    uint32_t eq_t = 0, eq_v = 0;
 #pragma unroll
-    for (int j = 0; j < SEL_ITEMS; ++j) {
-      const int i = i0 + j;
-      inr[j] = i < a.nc;
-      key[j] = inr[j] ? float_key(sc[i]) : 0u;
-      mod[j] = (inr[j] && a.mpa_mode && mask[i]) ? 1 : 0;
-      if (inr[j] && key[j] == tau[mod[j]] && ties[mod[j]] > 0) eqpack += mod[j] ? 0x10000u : 1u;
+    for (int e = 0; e < SEL_EPT; ++e) {
+      const int m = (int)((mbits >> e) & 1ULL);
+      const bool ok = e < nvalid;
+      const bool gt = ok && key[e] > tau[m];
+      const bool eq = ok && key[e] == tau[m] && ties[m] > 0;
+      gtbits |= (unsigned long long)gt << e;
+      eqbits |= (unsigned long long)eq << e;
+      eq_t += (eq && m == 0) ? 1u : 0u;
+      eq_v += (eq && m == 1) ? 1u : 0u;
     }
-    uint32_t eqtot;
-    uint32_t eqbefore = block_excl_scan(eqpack, wave_tot, eqtot);
-    uint32_t rank[2] = {run_eq[0] + (eqbefore & 0xffffu), run_eq[1] + (eqbefore >> 16)};
-    bool keep[SEL_ITEMS]; uint32_t nkeep = 0;
+    uint32_t t_tot, v_tot;
+    uint32_t rank_t = run_eq[0] + block_excl_scan(eq_t, wave_tot, t_tot);
+    uint32_t rank_v = run_eq[1] + block_excl_scan(eq_v, wave_tot, v_tot);
+    unsigned long long keepbits = gtbits;
+    if (eqbits) {
 #pragma unroll
-    for (int j = 0; j < SEL_ITEMS; ++j) {
-      keep[j] = false;
-      if (inr[j]) {
-        const int m = mod[j];
-        if (key[j] > tau[m]) keep[j] = true;
-        else if (key[j] == tau[m] && ties[m] > 0) { keep[j] = rank[m] < ties[m]; ++rank[m]; }
+      for (int e = 0; e < SEL_EPT; ++e) {
+        if ((eqbits >> e) & 1ULL) {
+          const int m = (int)((mbits >> e) & 1ULL);
+          uint32_t& rk = m ? rank_v : rank_t;
+          if (rk < ties[m]) keepbits |= 1ULL << e;
+          ++rk;
+        }
       }
-      nkeep += keep[j] ? 1u : 0u;
     }
     uint32_t ktot;
-    uint32_t pos = run_out + block_excl_scan(nkeep, wave_tot, ktot);
-#pragma unroll
-    for (int j = 0; j < SEL_ITEMS; ++j) if (keep[j]) out[pos++] = i0 + j;
-    run_eq[0] += eqtot & 0xffffu; run_eq[1] += eqtot >> 16;
+    uint32_t pos = run_out + block_excl_scan((uint32_t)__popcll(keepbits), wave_tot, ktot);
+    while (keepbits) {                            // ascending by construction: lowest set bit first
+      const int e = __ffsll((long long)keepbits) - 1;
+      out[pos++] = i0 + e;
+      keepbits &= keepbits - 1ULL;
+    }
+    run_eq[0] += t_tot; run_eq[1] += v_tot;
     run_out += ktot;
   }
   for (int r = tid; r < a.W; r += SEL_THREADS) out[run_out + r] = a.nc + r;

@@ -14,6 +14,8 @@
 //   k_m = #{psi > tau} + ceil((theta w_m - mass{psi > tau}) / tau).
 #include "common.h"
 
+#include <cstdlib>
+
 namespace madakv {
 
 constexpr int STATS_THREADS = 512;
