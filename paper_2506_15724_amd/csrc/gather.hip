@@ -7,6 +7,8 @@
 // instruction and keeps UNROLL such loads of K and of V in flight before it stores.
 #include "common.h"
 
+#include <algorithm>
+
 namespace madakv {
 
 // native vector type: arrays of it stay in registers (the HIP uint4 struct ends up in scratch)
@@ -16,6 +18,7 @@ struct GatherArgs {
   const void* k; const void* v; const int32_t* kept_idx; const int64_t* kv_off; const int32_t* kv_len;
   void* k_c; void* v_c; const long long* call_range; const int32_t* blk2head;
   int n, B, H, L, blocks_per_batch;
+  int li0, li1;          // layers [li0, li1) of the call are gathered by this launch
   long long region_tokens;
 };
 
@@ -25,15 +28,19 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
   constexpr int ROWS_PER_WAVE = GATHER_ROWS / 4;
   constexpr int ITERS = ROWS_PER_WAVE / RPI;
   const int b = blockIdx.y;
-  const long long start = a.call_range[b * 2], end = a.call_range[b * 2 + 1];
+  const long long region = (long long)b * a.region_tokens;
+  const long long call_start = a.call_range[b * 2], call_end = a.call_range[b * 2 + 1];
+  // rows of the launch's layers: from the first head of layer li0 to the first head of layer li1
+  const long long start = a.li0 == 0 ? call_start : a.kv_off[((long long)a.li0 * a.B + b) * a.H] - region;
+  const long long end = a.li1 >= a.n ? call_end : a.kv_off[((long long)a.li1 * a.B + b) * a.H] - region;
   const long long blk = start / GATHER_ROWS + blockIdx.x;
+  const long long tbl = blk - call_start / GATHER_ROWS;          // the block table is relative to the call's first block
   const long long row0 = blk * GATHER_ROWS;
   if (row0 >= end) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int sub = lane / LPR, piece = lane % LPR;
-  const long long region = (long long)b * a.region_tokens;
   const int nh = a.n * a.H;
-  int hh = a.blk2head[(long long)b * a.blocks_per_batch + blockIdx.x];
+  int hh = a.blk2head[(long long)b * a.blocks_per_batch + tbl];
   const u32x4_t* kin = reinterpret_cast<const u32x4_t*>(a.k);
   const u32x4_t* vin = reinterpret_cast<const u32x4_t*>(a.v);
   u32x4_t* kout = reinterpret_cast<u32x4_t*>(a.k_c);
@@ -103,19 +110,20 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
   }
 }
 
-hipError_t launch_gather(const Dims& dm, const madakv_config& c, const void* k, const void* v,
+hipError_t launch_gather(const Dims& dm, const madakv_config& c, int li0, int nli, const void* k, const void* v,
                          const int32_t* kept_idx, const int64_t* kv_off, const int32_t* kv_len,
                          void* k_c, void* v_c, const void* ws, long long region_tokens,
-                         int blocks_per_batch, hipStream_t st) {
+                         int blocks_per_batch, int grid_blocks, hipStream_t st) {
   GatherArgs a;
   a.k = k; a.v = v; a.kept_idx = kept_idx; a.kv_off = kv_off; a.kv_len = kv_len; a.k_c = k_c; a.v_c = v_c;
   a.call_range = reinterpret_cast<const long long*>(ws);
   a.blk2head = reinterpret_cast<const int32_t*>(reinterpret_cast<const char*>(ws) + ((size_t)dm.B * 2 * sizeof(long long) + 63) / 64 * 64);
   a.n = dm.n; a.B = dm.B; a.H = dm.H; a.L = dm.L; a.blocks_per_batch = blocks_per_batch;
   a.region_tokens = region_tokens;
+  a.li0 = li0; a.li1 = li0 + nli;
   const int row_bytes = dm.d * (c.dtype == MADAKV_BF16 ? 2 : 4);
   const int lpr = row_bytes / 16;
-  dim3 grid(blocks_per_batch, dm.B);
+  dim3 grid(std::min(grid_blocks, blocks_per_batch), dm.B);
   if (lpr == 8) hipLaunchKernelGGL((gather_kernel<8>), grid, dim3(256), 0, st, a);
   else if (lpr == 16) hipLaunchKernelGGL((gather_kernel<16>), grid, dim3(256), 0, st, a);
   else if (lpr == 32) hipLaunchKernelGGL((gather_kernel<32>), grid, dim3(256), 0, st, a);

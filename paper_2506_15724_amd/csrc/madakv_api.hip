@@ -10,6 +10,8 @@
 
 using namespace madakv;
 
+constexpr int MAX_GROUPS = 4;      // layer groups a multi-layer call is cut into for the overlap
+
 struct madakv_handle {
   madakv_config cfg;
   int device;
@@ -23,6 +25,11 @@ struct madakv_handle {
   int32_t* h_maxlen;
   hipEvent_t maxlen_event;
   bool maxlen_pending;
+  // Side stream and events for the overlap of the bandwidth-bound kernels (score sweeps, gather)
+  // with the latency-bound per-head kernels (statistics, selection) inside one call.  The side
+  // stream forks from and joins the caller's stream through events; default priority.
+  hipStream_t side;
+  hipEvent_t ev_grp[MAX_GROUPS], ev_fork, ev_join;
   int sel_layers_done;             // layers [0, sel_layers_done) have been through select_gather in this pass
 };
 
@@ -81,6 +88,23 @@ int32_t validate(const madakv_config& c) {
   return MADAKV_OK;
 }
 
+void destroy_side(madakv_handle* h) {
+  if (h->side) { (void)hipStreamSynchronize(h->side); (void)hipStreamDestroy(h->side); }
+  if (h->ev_fork) (void)hipEventDestroy(h->ev_fork);
+  if (h->ev_join) (void)hipEventDestroy(h->ev_join);
+  for (int g = 0; g < MAX_GROUPS; ++g) if (h->ev_grp[g]) (void)hipEventDestroy(h->ev_grp[g]);
+}
+
+// Layers per group when a call over n layers is cut up for the overlap (1 group below 4 layers).
+int group_layers(int n) { return n >= MAX_GROUPS ? (n + MAX_GROUPS - 1) / MAX_GROUPS : n; }
+
+size_t score_ws_for_call(const madakv_config& c, int n) {
+  const int gl = group_layers(n);
+  size_t need = score_ws_bytes(make_dims(c, gl), c.dtype);
+  if (n % gl) need = std::max(need, score_ws_bytes(make_dims(c, n % gl), c.dtype));
+  return need;
+}
+
 }  // namespace
 
 extern "C" {
@@ -96,17 +120,24 @@ int32_t madakv_create(const madakv_config* cfg, madakv_handle** out) {
   h->d_state = nullptr;
   h->d_maxlen = nullptr; h->h_maxlen = nullptr; h->maxlen_event = nullptr;
   h->maxlen_pending = false; h->sel_layers_done = 0;
+  h->side = nullptr; h->ev_fork = nullptr; h->ev_join = nullptr;
+  for (int g = 0; g < MAX_GROUPS; ++g) h->ev_grp[g] = nullptr;
   h->appended.assign(cfg->n_layers, 0);
   hipError_t e = hipGetDevice(&h->device);
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&h->d_state), sizeof(long long) * 2 * cfg->batch);
   if (e == hipSuccess) e = hipMemset(h->d_state, 0, sizeof(long long) * 2 * cfg->batch);
-  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&h->d_maxlen), sizeof(int32_t) * cfg->n_layers);
-  if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&h->h_maxlen), sizeof(int32_t) * cfg->n_layers, hipHostMallocDefault);
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&h->d_maxlen), sizeof(int32_t) * cfg->n_layers * cfg->batch);
+  if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&h->h_maxlen), sizeof(int32_t) * cfg->n_layers * cfg->batch, hipHostMallocDefault);
   if (e == hipSuccess) e = hipEventCreateWithFlags(&h->maxlen_event, hipEventDisableTiming);
+  if (e == hipSuccess) e = hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking);
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming);
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&h->ev_join, hipEventDisableTiming);
+  for (int g = 0; g < MAX_GROUPS && e == hipSuccess; ++g) e = hipEventCreateWithFlags(&h->ev_grp[g], hipEventDisableTiming);
   if (e != hipSuccess) {
     if (h->d_maxlen) (void)hipFree(h->d_maxlen);
     if (h->h_maxlen) (void)hipHostFree(h->h_maxlen);
     if (h->maxlen_event) (void)hipEventDestroy(h->maxlen_event);
+    destroy_side(h);
     if (h->d_state) (void)hipFree(h->d_state);
     delete h;
     return MADAKV_ERR_HIP;
@@ -121,6 +152,7 @@ int32_t madakv_destroy(madakv_handle* h) {
   (void)hipFree(h->d_maxlen);
   (void)hipHostFree(h->h_maxlen);
   (void)hipEventDestroy(h->maxlen_event);
+  destroy_side(h);
   delete h;
   return e == hipSuccess ? MADAKV_OK : MADAKV_ERR_HIP;
 }
@@ -131,7 +163,7 @@ int32_t madakv_workspace_bytes(const madakv_handle* h, int32_t n_layers_per_call
                                size_t* score_ws, size_t* select_ws, size_t* decode_ws) {
   if (!h || n_layers_per_call < 1 || n_layers_per_call > h->cfg.n_layers) return MADAKV_ERR_INVALID_ARG;
   Dims dm = make_dims(h->cfg, n_layers_per_call);
-  if (score_ws) *score_ws = score_ws_bytes(dm, h->cfg.dtype);
+  if (score_ws) *score_ws = score_ws_for_call(h->cfg, n_layers_per_call);
   if (select_ws) *select_ws = select_ws_bytes(dm, h->cfg);
   if (decode_ws) *decode_ws = decode_ws_bytes(dm, h->cfg);
   return MADAKV_OK;
@@ -151,11 +183,37 @@ int32_t madakv_score(madakv_handle* h, int32_t layer0, int32_t n,
   if (r != MADAKV_OK) return r;
   if (bad_ptr(q_win) || bad_ptr(k) || bad_ptr(mask, 1) || bad_ptr(psi, 4) || bad_ptr(psi_pool, 4) || bad_ptr(stats, 4) ||
       bad_ptr(n_mod, 4) || bad_ptr(ws)) return MADAKV_ERR_INVALID_ARG;
-  Dims dm = make_dims(h->cfg, n);
-  if (ws_bytes < score_ws_bytes(dm, h->cfg.dtype)) return MADAKV_ERR_WORKSPACE_TOO_SMALL;
+  if (ws_bytes < score_ws_for_call(h->cfg, n)) return MADAKV_ERR_WORKSPACE_TOO_SMALL;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-  hipError_t e = launch_score(dm, h->cfg, q_win, k, psi, ws, st);
-  if (e == hipSuccess) e = launch_stats(dm, h->cfg, psi, mask, psi_pool, stats, n_mod, layer0, st);
+  const madakv_config& c = h->cfg;
+  // The call is cut into up to MAX_GROUPS layer groups: the score sweeps of a group run on the
+  // caller's stream, its statistics on the side stream, under the sweeps of the next group.
+  const int gl = group_layers(n);
+  const bool overlap = gl < n;
+  const size_t es = c.dtype == MADAKV_BF16 ? 2 : 4;
+  hipError_t e = hipSuccess;
+  int gi = 0;
+  for (int g0 = 0; g0 < n && e == hipSuccess; g0 += gl, ++gi) {
+    Dims dg = make_dims(c, std::min(gl, n - g0));
+    const size_t lb = (size_t)g0 * c.batch;                        // (layer, batch) pairs before the group
+    const char* qg = static_cast<const char*>(q_win) + lb * c.n_q_heads * c.window * c.head_dim * es;
+    const char* kg = static_cast<const char*>(k) + lb * c.n_kv_heads * (size_t)c.ctx_len * c.head_dim * es;
+    float* psi_g = psi + lb * c.n_kv_heads * (size_t)c.ctx_len;
+    float* pool_g = psi_pool + lb * c.n_kv_heads * (size_t)(c.ctx_len - c.window);
+    e = launch_score(dg, c, qg, kg, psi_g, ws, st);
+    hipStream_t ss = st;
+    if (overlap && e == hipSuccess) {
+      e = hipEventRecord(h->ev_grp[gi], st);
+      if (e == hipSuccess) e = hipStreamWaitEvent(h->side, h->ev_grp[gi], 0);
+      ss = h->side;
+    }
+    if (e == hipSuccess)
+      e = launch_stats(dg, c, psi_g, mask, pool_g, stats + lb * c.n_kv_heads, g0 == 0 ? n_mod : nullptr, layer0 + g0, ss);
+  }
+  if (overlap && e == hipSuccess) {
+    e = hipEventRecord(h->ev_join, h->side);
+    if (e == hipSuccess) e = hipStreamWaitEvent(st, h->ev_join, 0);
+  }
   return hip_fail(h, e);
 }
 
@@ -188,12 +246,15 @@ int32_t madakv_select_gather(madakv_handle* h, int32_t layer0, int32_t n,
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   const long long region = region_tokens(c);
   const int bpb = blocks_per_batch(c, n);
-  hipError_t e = launch_offsets(dm, c, layer0, budgets, kv_off, kv_len, h->d_state + c.batch, h->d_maxlen + layer0, ws, region, bpb, st);
+  hipError_t e = launch_offsets(dm, c, layer0, budgets, kv_off, kv_len, h->d_state + c.batch, h->d_maxlen + (size_t)layer0 * c.batch, ws, region, bpb, st);
+  // (Running the selection of one layer group on the side stream under the gather of the
+  // previous group was measured: the two starve each other and nothing is gained.)
   if (e == hipSuccess) e = launch_select(dm, c, psi_pool, mask, budgets, kv_off, kv_len, kept_idx, st);
-  if (e == hipSuccess) e = launch_gather(dm, c, k, v, kept_idx, kv_off, kv_len, k_c, v_c, ws, region, bpb, st);
+  if (e == hipSuccess) e = launch_gather(dm, c, 0, n, k, v, kept_idx, kv_off, kv_len, k_c, v_c, ws, region, bpb, bpb, st);
   for (int l = layer0; l < layer0 + n; ++l) h->appended[l] = 0;
   // hand the per-layer longest length to the host without waiting for it
-  if (e == hipSuccess) e = hipMemcpyAsync(h->h_maxlen + layer0, h->d_maxlen + layer0, sizeof(int32_t) * n, hipMemcpyDeviceToHost, st);
+  if (e == hipSuccess) e = hipMemcpyAsync(h->h_maxlen + (size_t)layer0 * c.batch, h->d_maxlen + (size_t)layer0 * c.batch,
+                                             sizeof(int32_t) * n * c.batch, hipMemcpyDeviceToHost, st);
   if (e == hipSuccess) e = hipEventRecord(h->maxlen_event, st);
   h->sel_layers_done = (e == hipSuccess) ? layer0 + n : 0;
   h->maxlen_pending = true;
@@ -221,7 +282,8 @@ int32_t madakv_decode_attn(madakv_handle* h, int32_t layer0, int32_t n,
   if (h->maxlen_pending && hipEventQuery(h->maxlen_event) == hipSuccess) h->maxlen_pending = false;
   if (!h->maxlen_pending && layer0 + n <= h->sel_layers_done) {
     int mx = 0;
-    for (int l = layer0; l < layer0 + n; ++l) mx = std::max(mx, h->h_maxlen[l] + h->appended[l] + 1);
+    for (int l = layer0; l < layer0 + n; ++l)
+      for (int b = 0; b < h->cfg.batch; ++b) mx = std::max(mx, h->h_maxlen[(size_t)l * h->cfg.batch + b] + h->appended[l] + 1);
     longest = std::min(longest, mx);
   }
   hipError_t e = launch_decode(dm, h->cfg, q, k_new, v_new, k_c, v_c, kv_off, kv_len, out, ws,

@@ -28,6 +28,8 @@ struct ScoreArgs {
   const void* k;       // [heads, L, d]
   float* psi;          // [heads, L]
   float* rowstat;      // [heads, nsplit, mpad, 2]
+  float* sink;         // 32 floats nobody reads: keeps the psi store of sweep 2 unconditional (both half-waves
+                       // store the same value; a store under a branch makes the load waits pessimistic)
   int H, G, d, L, W, M, mpad, nsplit, chunk;
   int head0;           // first head of this launch (grid.y indexes head0 + y)
   int dbg;             // experiment switches (0 in production)
@@ -222,7 +224,7 @@ _Pragma("unroll") \
     if (PASS == 2) { \
       colsum += __shfl_xor(colsum, 32, 64); \
       if (WPT == 1) { \
-        if (half == 0 && key < chunk1) a.psi[(long long)head * a.L + key] = colsum; \
+        { float* dst = (key < chunk1) ? a.psi + ((long long)head * a.L + key) : a.sink + col; *dst = colsum; } \
       } else { \
         if (half == 0) red[((it & 1) * 4 + wave) * 32 + col] = colsum; \
         __syncthreads(); \
@@ -363,7 +365,7 @@ ScorePlan score_plan(const Dims& dm, int dtype) {
 
 size_t score_ws_bytes(const Dims& dm, int dtype) {
   ScorePlan p = score_plan(dm, dtype);
-  return (size_t)dm.heads * p.nsplit * p.mpad * 2 * sizeof(float);
+  return (size_t)dm.heads * p.nsplit * p.mpad * 2 * sizeof(float) + 256;   // row statistics + the store sink
 }
 
 template <int D, int WPT, int NRB>
@@ -385,6 +387,7 @@ hipError_t launch_score(const Dims& dm, const madakv_config& c, const void* q_wi
   ScorePlan p = score_plan(dm, c.dtype);
   ScoreArgs a;
   a.q_win = q_win; a.k = k; a.psi = psi; a.rowstat = reinterpret_cast<float*>(ws);
+  a.sink = a.rowstat + (size_t)dm.heads * score_plan(dm, c.dtype).nsplit * score_plan(dm, c.dtype).mpad * 2;
   a.H = dm.H; a.G = dm.G; a.d = dm.d; a.L = dm.L; a.W = dm.W; a.M = dm.M;
   a.mpad = p.mpad; a.nsplit = p.nsplit; a.chunk = p.chunk; a.head0 = 0;
   a.dbg = 0;

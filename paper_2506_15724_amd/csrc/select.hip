@@ -29,58 +29,81 @@ struct OffsetsArgs {
   long long region_tokens;
 };
 
-// One workgroup, wave w handles batch items w, w+nw, ...; lanes are heads.
-__global__ __launch_bounds__(256) void offsets_kernel(OffsetsArgs a) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
-  for (int li = threadIdx.x; li < a.n; li += blockDim.x) a.layer_maxlen[li] = 0;
+// One workgroup per batch item; thread f of a trip owns head f of the call's (layer, head)
+// sequence.  Offsets are a prefix sum over that sequence (wave shuffles + one LDS hop).
+constexpr int OFF_THREADS = 1024;
+constexpr int OFF_MAX_LAYERS = 1024;
+
+__global__ __launch_bounds__(OFF_THREADS) void offsets_kernel(OffsetsArgs a) {
+  __shared__ long long s_wtot[OFF_THREADS / 64];
+  __shared__ long long s_used;
+  __shared__ int s_first_bad;
+  __shared__ int s_lmax[OFF_MAX_LAYERS];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int b = blockIdx.x;
+  const int nh = a.n * a.H;
+  const long long start = (a.layer0 == 0) ? 0 : a.cursor[b];
+  const long long region = (long long)b * a.region_tokens;
+  const long long blk_base = start / GATHER_ROWS;            // the block table is relative to the call's first block
+  for (int li = tid; li < a.n; li += OFF_THREADS) s_lmax[li] = 0;
+  if (tid == 0) { s_first_bad = 0x7fffffff; s_used = 0; }
   __syncthreads();
-  for (int b = wave; b < a.B; b += nw) {
-    long long cur = (a.layer0 == 0) ? 0 : a.cursor[b];
-    const long long start = cur;
-    const long long region = (long long)b * a.region_tokens;
-    for (int li = 0; li < a.n; ++li) {
-      const long long idx = ((long long)li * a.B + b) * a.H + lane;
-      long long len = 0;
-      if (lane < a.H) len = a.keep_all ? a.L : (long long)a.budgets[idx * 2] + a.budgets[idx * 2 + 1] + a.W;
-      long long seg = (lane < a.H) ? len + a.max_new : 0;
-      long long incl = seg;                                    // inclusive scan over heads
-      for (int o = 1; o < 64; o <<= 1) {
-        long long t = shfl_i64(incl, max(lane - o, 0));
-        if (lane >= o) incl += t;
-      }
-      // Budgets that do not add up to the configured total could run past the batch item's
-      // region: the first head that does not fit, and every head after it, gets an empty
-      // segment (kv_len 0) at the end of what was laid out, so nothing is written outside.
-      const bool fits = cur + incl <= a.region_tokens;
-      const unsigned long long fitmask = __ballot(fits || lane >= a.H);
-      const int first_bad = fitmask == ~0ULL ? 64 : __ffsll((long long)~fitmask) - 1;
-      const long long used = first_bad == 0 ? 0 : shfl_i64(incl, max(first_bad - 1, 0));
-      if (lane >= first_bad) { len = 0; seg = 0; incl = used; }
-      const long long off = cur + incl - seg;                  // relative to the region start
-      // longest segment of the layer: lets the host size the decode grid without a sync
-      int mx = (int)len;
-      for (int o = 32; o > 0; o >>= 1) mx = max(mx, __shfl_xor(mx, o, 64));
-      if (lane == 0) atomicMax(&a.layer_maxlen[li], mx);
-      if (lane < a.H) {
-        a.kv_off[idx] = region + off;
-        a.kv_len[idx] = (int32_t)len;
-        // blocks whose first row lies inside this segment
-        const long long b0 = (off + GATHER_ROWS - 1) / GATHER_ROWS, b1 = seg > 0 ? (off + seg - 1) / GATHER_ROWS : b0 - 1;
-        const long long blk_base = start / GATHER_ROWS;       // table is relative to the call's first block
-        for (long long blk = b0; blk <= b1; ++blk) {
-          long long t = blk - blk_base;
-          if (t >= 0 && t < a.blocks_per_batch) a.blk2head[(long long)b * a.blocks_per_batch + t] = li * a.H + lane;
-        }
-        if (li == 0 && lane == 0 && (start % GATHER_ROWS) != 0 && 0 < a.blocks_per_batch)
-          a.blk2head[(long long)b * a.blocks_per_batch] = 0;  // the call starts inside a block: its first head is head 0
-      }
-      cur += shfl_i64(incl, 63);
+  long long carry = 0;                                        // rows laid out by earlier trips
+  bool overflowed = false;                                    // a head did not fit: every later head is empty
+  for (int f0 = 0; f0 < nh; f0 += OFF_THREADS) {
+    const int f = f0 + tid;
+    const bool act = f < nh;
+    const int li = act ? f / a.H : 0, h = act ? f % a.H : 0;
+    const long long idx = ((long long)li * a.B + b) * a.H + h;
+    long long len = 0;
+    if (act) len = a.keep_all ? a.L : (long long)a.budgets[idx * 2] + a.budgets[idx * 2 + 1] + a.W;
+    long long seg = act ? len + a.max_new : 0;
+    long long incl = seg;
+    for (int o = 1; o < 64; o <<= 1) {
+      long long t = shfl_i64(incl, max(lane - o, 0));
+      if (lane >= o) incl += t;
     }
-    if (lane == 0) {
-      a.cursor[b] = cur;
-      a.call_range[b * 2] = start;
-      a.call_range[b * 2 + 1] = cur;
+    if (lane == 63) s_wtot[wave] = incl;
+    __syncthreads();
+    long long before = 0, tot = 0;
+    for (int w = 0; w < OFF_THREADS / 64; ++w) { const long long t = s_wtot[w]; if (w < wave) before += t; tot += t; }
+    const long long abs_incl = carry + before + incl;         // rows up to and including this head's segment
+    // Budgets that do not add up to the configured total could run past the batch item's
+    // region: the first head that does not fit, and every head after it, gets an empty
+    // segment (kv_len 0) at the end of what was laid out, so nothing is written outside.
+    const bool bad = act && (overflowed || start + abs_incl > a.region_tokens);
+    if (bad && !overflowed) atomicMin(&s_first_bad, f);
+    __syncthreads();
+    const int first_bad = s_first_bad;
+    if (!overflowed && first_bad == f) s_used = abs_incl - seg;
+    __syncthreads();
+    const bool now_over = first_bad != 0x7fffffff;
+    const long long used = s_used;
+    long long off;
+    if (bad) { len = 0; seg = 0; off = start + used; }
+    else off = start + abs_incl - seg;                        // relative to the region start
+    if (act) {
+      atomicMax(&s_lmax[li], (int)len);                       // longest segment of the layer, for the decode grid
+      a.kv_off[idx] = region + off;
+      a.kv_len[idx] = (int32_t)len;
+      // blocks whose first row lies inside this segment
+      const long long b0 = (off + GATHER_ROWS - 1) / GATHER_ROWS, b1 = seg > 0 ? (off + seg - 1) / GATHER_ROWS : b0 - 1;
+      for (long long blk = b0; blk <= b1; ++blk) {
+        const long long t = blk - blk_base;
+        if (t >= 0 && t < a.blocks_per_batch) a.blk2head[(long long)b * a.blocks_per_batch + t] = f;
+      }
+      if (f == 0 && (start % GATHER_ROWS) != 0 && 0 < a.blocks_per_batch)
+        a.blk2head[(long long)b * a.blocks_per_batch] = 0;    // the call starts inside a block: its first head is head 0
     }
+    carry = now_over ? used : carry + tot;
+    overflowed = now_over;
+    __syncthreads();
+  }
+  for (int li = tid; li < a.n; li += OFF_THREADS) a.layer_maxlen[(long long)li * a.B + b] = s_lmax[li];
+  if (tid == 0) {
+    a.cursor[b] = start + carry;
+    a.call_range[b * 2] = start;
+    a.call_range[b * 2 + 1] = start + carry;
   }
 }
 
@@ -315,7 +338,7 @@ hipError_t launch_offsets(const Dims& dm, const madakv_config& c, int layer0, co
   a.n = dm.n; a.B = dm.B; a.H = dm.H; a.L = dm.L; a.W = dm.W; a.layer0 = layer0;
   a.max_new = c.max_new_tokens; a.keep_all = c.budget >= c.ctx_len ? 1 : 0;
   a.blocks_per_batch = blocks_per_batch; a.region_tokens = region_tokens;
-  hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(256), 0, st, a);
+  hipLaunchKernelGGL(offsets_kernel, dim3(dm.B), dim3(OFF_THREADS), 0, st, a);
   return hipGetLastError();
 }
 

@@ -19,6 +19,7 @@
 namespace madakv {
 
 constexpr int STATS_THREADS = 512;
+constexpr int STATS_EPT = 32;                    // consecutive candidates a thread owns per chunk
 constexpr int BINS = 2048;
 constexpr float FX_SCALE = 17592186044416.0f;    // 2^44
 constexpr float PSI_MAX = 256.0f;                // G * W <= 256 bounds any column sum
@@ -38,7 +39,76 @@ __device__ __forceinline__ uint32_t nonneg_bits(float v) {
   return __float_as_uint(v);                      // non-negative floats order like their bit patterns
 }
 
-__global__ __launch_bounds__(STATS_THREADS) void stats_kernel(StatsArgs a) {
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
+
+// Thread t owns STATS_EPT consecutive candidates of a chunk; values and modality bits stay in
+// registers through the three levels when the head fits one chunk (16384 candidates).
+__device__ __forceinline__ void load_owned(const float* psi, const uint8_t* mask, int i0, int nc,
+                                           float (&v)[STATS_EPT], uint32_t& mbits) {
+  const bool full = i0 + STATS_EPT <= nc;
+  if (full && ((reinterpret_cast<uintptr_t>(psi + i0) & 15u) == 0)) {
+#pragma unroll
+    for (int j = 0; j < STATS_EPT / 4; ++j) {
+      const f32x4_t x = *reinterpret_cast<const f32x4_t*>(psi + i0 + j * 4);
+      v[j * 4 + 0] = x[0]; v[j * 4 + 1] = x[1]; v[j * 4 + 2] = x[2]; v[j * 4 + 3] = x[3];
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < STATS_EPT; ++e) v[e] = (i0 + e < nc) ? psi[i0 + e] : 0.f;
+  }
+  mbits = 0u;
+  if (full && ((reinterpret_cast<uintptr_t>(mask + i0) & 15u) == 0)) {
+#pragma unroll
+    for (int j = 0; j < STATS_EPT / 16; ++j) {
+      const u32x4_t w = *reinterpret_cast<const u32x4_t*>(mask + i0 + j * 16);
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int bb = 0; bb < 4; ++bb)
+          if ((w[q] >> (8 * bb)) & 0xffu) mbits |= 1u << (j * 16 + q * 4 + bb);
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < STATS_EPT; ++e)
+      if (i0 + e < nc && mask[i0 + e]) mbits |= 1u << e;
+  }
+}
+
+// max-pool of half-width R over the candidates: the thread's own stretch plus R neighbours
+// on each side from memory; positions outside [0, nc) do not take part
+template <int R>
+__device__ __forceinline__ void pool_owned(const float* psi, float* pool, int i0, int nc, const float (&v)[STATS_EPT]) {
+  float ext[STATS_EPT + 2 * R + 1];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int il = i0 - R + r, ir = i0 + STATS_EPT + r;
+    ext[r] = (il >= 0 && il < nc) ? psi[il] : -__builtin_inff();
+    ext[R + STATS_EPT + r] = (ir < nc) ? psi[ir] : -__builtin_inff();
+  }
+#pragma unroll
+  for (int e = 0; e < STATS_EPT; ++e) ext[R + e] = (i0 + e < nc) ? v[e] : -__builtin_inff();
+  float o[STATS_EPT];
+#pragma unroll
+  for (int e = 0; e < STATS_EPT; ++e) {
+    float mx = ext[R + e];
+#pragma unroll
+    for (int r = 1; r <= R; ++r) mx = fmaxf(mx, fmaxf(ext[R + e - r], ext[R + e + r]));
+    o[e] = mx;
+  }
+  if (i0 + STATS_EPT <= nc && ((reinterpret_cast<uintptr_t>(pool + i0) & 15u) == 0)) {
+#pragma unroll
+    for (int j = 0; j < STATS_EPT / 4; ++j) {
+      f32x4_t x = {o[j * 4], o[j * 4 + 1], o[j * 4 + 2], o[j * 4 + 3]};
+      *reinterpret_cast<f32x4_t*>(pool + i0 + j * 4) = x;
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < STATS_EPT; ++e) if (i0 + e < nc) pool[i0 + e] = o[e];
+  }
+}
+
+__global__ __launch_bounds__(STATS_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4))) void stats_kernel(StatsArgs a) {
   __shared__ uint32_t cnt[2][BINS];
   __shared__ unsigned long long sum[2][BINS];
   __shared__ uint32_t s_prefix[2], s_cnt_gt[2], s_n[2], s_done[2], s_bincnt[2];
@@ -53,49 +123,54 @@ __global__ __launch_bounds__(STATS_THREADS) void stats_kernel(StatsArgs a) {
 
   const int shifts[3] = {20, 9, 0};
   const int widths[3] = {11, 11, 9};
+  constexpr int CH = STATS_THREADS * STATS_EPT;
+  const int nchunks = (a.nc + CH - 1) / CH;
+  const bool single = nchunks == 1;
+
+  float v[STATS_EPT];
+  uint32_t mbits = 0u;
+  if (single) load_owned(psi, mask, tid * STATS_EPT, a.nc, v, mbits);
 
   for (int level = 0; level < 3; ++level) {
     for (int e = tid; e < 2 * BINS; e += STATS_THREADS) { (&cnt[0][0])[e] = 0; (&sum[0][0])[e] = 0ULL; }
     __syncthreads();
     const int sh = shifts[level], wd = widths[level];
-    // U elements per thread per trip, all their loads issued before any is used: the loop is
-    // bound by load latency, not by the atomics
-    constexpr int U = 8;
-    for (int i0 = tid; i0 < a.nc; i0 += STATS_THREADS * U) {
-      float v[U]; int m[U]; bool ok[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int i = i0 + u * STATS_THREADS;
-        ok[u] = i < a.nc;
-        v[u] = ok[u] ? psi[i] : 0.f;
-        m[u] = (ok[u] && mask[i]) ? 1 : 0;
-      }
-      if (level == 0) {
-        // pooled score for ranking: max over the clipped neighbourhood (raw values)
-        float mx[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) mx[u] = v[u];
-        for (int r = 1; r <= a.pool_r; ++r) {
-#pragma unroll
-          for (int u = 0; u < U; ++u) {
-            const int i = i0 + u * STATS_THREADS;
-            const float lo = (ok[u] && i - r >= 0) ? psi[i - r] : mx[u];
-            const float hi = (ok[u] && i + r < a.nc) ? psi[i + r] : mx[u];
-            mx[u] = fmaxf(mx[u], fmaxf(lo, hi));
-          }
+    const uint32_t binmask = (1u << wd) - 1u;
+    uint32_t pfx[2] = {0, 0}; bool dn[2] = {false, false};
+    if (level > 0) { pfx[0] = s_prefix[0]; pfx[1] = s_prefix[1]; dn[0] = s_done[0] != 0; dn[1] = s_done[1] != 0; }
+    for (int c = 0; c < nchunks; ++c) {
+      const int i0 = c * CH + tid * STATS_EPT;
+      if (!single) load_owned(psi, mask, i0, a.nc, v, mbits);
+      const int nvalid = min(max(a.nc - i0, 0), STATS_EPT);
+      if (level == 0 && nvalid > 0) {
+        // pooled score for ranking (raw values); widths up to 7 from registers, wider ones the slow way
+        switch (a.pool_r) {
+          case 0: pool_owned<0>(psi, pool, i0, a.nc, v); break;
+          case 1: pool_owned<1>(psi, pool, i0, a.nc, v); break;
+          case 2: pool_owned<2>(psi, pool, i0, a.nc, v); break;
+          case 3: pool_owned<3>(psi, pool, i0, a.nc, v); break;
+          default:
+            for (int e = 0; e < nvalid; ++e) {
+              const int i = i0 + e;
+              float mx = psi[i];
+              for (int r = 1; r <= a.pool_r; ++r) {
+                if (i - r >= 0) mx = fmaxf(mx, psi[i - r]);
+                if (i + r < a.nc) mx = fmaxf(mx, psi[i + r]);
+              }
+              pool[i] = mx;
+            }
         }
-#pragma unroll
-        for (int u = 0; u < U; ++u) if (ok[u]) pool[i0 + u * STATS_THREADS] = mx[u];
       }
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const uint32_t key = nonneg_bits(v[u]);
-        bool match = ok[u];
-        if (level > 0) match = match && (s_done[m[u]] == 0) && ((key >> (sh + wd)) == s_prefix[m[u]]);
+      for (int e = 0; e < STATS_EPT; ++e) {
+        const int m = (int)((mbits >> e) & 1u);
+        const uint32_t key = nonneg_bits(v[e]);
+        bool match = e < nvalid;
+        if (level > 0) match = match && !dn[m] && ((key >> (sh + wd)) == pfx[m]);
         if (match) {
-          const uint32_t bin = (key >> sh) & ((1u << wd) - 1u);
-          atomicAdd(&cnt[m[u]][bin], 1u);
-          atomicAdd(&sum[m[u]][bin], to_fx(v[u]));
+          const uint32_t bin = (key >> sh) & binmask;
+          atomicAdd(&cnt[m][bin], 1u);
+          atomicAdd(&sum[m][bin], to_fx(v[e]));
         }
       }
     }

@@ -36,6 +36,9 @@ def small_workloads():
         "bf16_d64_gqa2": C["llava_layer"].scaled(name="bf16_d64_gqa2", n_layers=2, batch=1, n_q_heads=4, n_kv_heads=2,
                                                  head_dim=64, ctx_len=1200, budget=150, n_images=1, window=16,
                                                  decode_steps=2),
+        # odd lengths: candidate rows start at unaligned addresses (scalar load paths, ragged tiles)
+        "bf16_odd": C["llava_layer"].scaled(name="bf16_odd", n_layers=2, batch=2, n_q_heads=6, n_kv_heads=3,
+                                            ctx_len=1501, window=17, budget=211, n_images=1, pool_k=5, decode_steps=2),
         "fp32_d128": C["tiny"].scaled(name="fp32_d128", n_layers=2, batch=2, n_q_heads=4, n_kv_heads=2, head_dim=128,
                                       ctx_len=700, window=8, budget=100, pool_k=3, fixed_layout=(), n_images=2,
                                       image_tokens=(100, 100), text_tokens=(20, 200), decode_steps=2),
