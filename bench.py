@@ -95,6 +95,15 @@ def cpu_baseline(wl, q, k, v, masks, n_sample_layers=8):
         t0 = time.perf_counter()
         O.evict(qh, kh, vh, masks[b], p)
         dt += time.perf_counter() - t0
+        if b == 0:                                    # the same thing with the BLAS pool held to one thread
+            try:
+                from threadpoolctl import threadpool_limits
+                with threadpool_limits(limits=1):
+                    t0 = time.perf_counter()
+                    O.evict(qh, kh, vh, masks[b], p)
+                    dt_single = time.perf_counter() - t0
+            except Exception:
+                dt_single = None
         del qh, kh, vh
     try:
         from threadpoolctl import threadpool_info
@@ -106,7 +115,10 @@ def cpu_baseline(wl, q, k, v, masks, n_sample_layers=8):
     return {"value": B * wl.ctx_len / full_seconds, "unit": "ctx-tokens/s", "cores": cores, "kind": "oracle",
             "sample": f"NumPy fp64 oracle, eviction of {n_s} of {NL} layers (layers {layers}) x all {B} batch items, "
                       f"{wl.n_kv_heads} heads, L={wl.ctx_len}: {dt:.1f} s measured, scaled by {NL}/{n_s}",
-            "seconds_measured": dt}
+            "seconds_measured": dt,
+            "one_blas_thread": None if dt_single is None else
+            {"value": wl.ctx_len / (dt_single * NL / n_s), "unit": "ctx-tokens/s", "cores": 1,
+             "sample": f"same {n_s} layers, batch item 0 only: {dt_single:.1f} s"}}
 
 
 def read_traffic(kernel_tag):

@@ -281,15 +281,18 @@ __global__ __launch_bounds__(128) void decode_merge_kernel(DecodeArgs a) {
 // keep every CU streaming), larger when thousands of heads already fill the chip.
 DecodePlan decode_plan(const Dims& dm, const madakv_config& c, int longest_rows) {
   DecodePlan p;
-  const long long keep = std::min(c.budget, c.ctx_len);
-  const long long est_rows = (long long)dm.heads * keep;
-  (void)est_rows;
   // longest_rows: upper bound on any head's length in this call (the worst case if unknown)
   const int longest = std::max(1, std::min(longest_rows, c.ctx_len + c.max_new_tokens));
-  // Measured on MI355X (ragged 16K-context cache): 256-row chunks for a single layer's heads,
-  // 512-row chunks once a call covers >= 1024 heads.  Smaller chunks lose to per-workgroup
-  // start-up cost, one workgroup per head loses to the imbalance of ragged lengths.
-  int rows = dm.heads >= 1024 ? 512 : 256;
+  // Measured on MI355X: 256-row chunks for a single layer's ragged heads at a 16K context
+  // (smaller chunks lose to per-workgroup start-up cost, one workgroup per head to the imbalance
+  // of ragged lengths), growing to 1024 rows when the heads are long (un-evicted cache), so that
+  // the chip sees about eight workgroups per CU; 512 rows once a call covers >= 1024 heads.
+  int rows = 512;
+  if (dm.heads < 1024) {
+    const long long typical = std::min(c.budget, c.ctx_len) + c.max_new_tokens;    // rows of an average head
+    const long long per = ((long long)dm.heads * typical + 2047) / 2048;
+    rows = (int)std::min<long long>(1024, std::max<long long>(256, per / 256 * 256));
+  }
   if (const char* e = getenv("MADAKV_DEC_CHUNK")) { int v = atoi(e); if (v >= 32 && v % 32 == 0 && dm.heads < 1024) rows = v; }
   if (const char* e = getenv("MADAKV_DEC_BIGCHUNK")) { int v = atoi(e); if (v >= 32 && v % 32 == 0 && dm.heads >= 1024) rows = v; }
   p.chunk_rows = rows;
