@@ -279,6 +279,23 @@ def main():
             e0.record(); fn(); e1.record(); torch.cuda.synchronize()
             stage[name + "_ms"] = e0.elapsed_time(e1)
         result["evict_stage_ms"] = stage
+        # eviction time of the switchable readings / baseline policies on the same inputs
+        variants = {"heads_share_layer_total": dict(hcc_mode=2), "text_first": dict(mpa_mode=2),
+                    "modality_agnostic_uniform": dict(mpa_mode=0, hcc_mode=0), "average_pool": dict(pool_mode=1),
+                    "shares_over_all_columns": dict(share_mode=1), "sink_recent": dict(select_mode=1)}
+        vres = {}
+        for name, kw in variants.items():
+            ve = MB.MadaKV(n_layers=NL, batch=B, n_q_heads=Hq, n_kv_heads=H, head_dim=d, ctx_len=L, window=W,
+                           budget=wl.budget, dtype=wl.dtype, pool_k=wl.pool_k, max_new_tokens=1, out_fp32=0, device=dev, **kw)
+            for rep in range(2):
+                e0.record()
+                ve.score(0, NL, q, k, mask); ve.allocate(0, NL); ve.select_gather(0, NL, k, v, mask)
+                e1.record()
+            torch.cuda.synchronize()
+            vres[name] = {"evict_ms": e0.elapsed_time(e1), "ctx_tokens_per_s": B * L / (e0.elapsed_time(e1) * 1e-3)}
+            ve.close()
+            del ve
+        result["evict_variants"] = vres
         # (c) the same decode kernel over the un-evicted cache (budget >= L keeps every token)
         try:
             full = MB.MadaKV(n_layers=NL, batch=B, n_q_heads=Hq, n_kv_heads=H, head_dim=d, ctx_len=L, window=W, budget=L,

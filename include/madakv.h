@@ -72,13 +72,20 @@ typedef struct {
   int32_t budget;          /* tokens kept per KV head per layer, window included; >= ctx_len keeps all */
   int32_t dtype;           /* MADAKV_FP32 / MADAKV_BF16: type of Q, K, V and of the reduced cache */
   int32_t pool_k;          /* odd, 1 .. 63: max-pool width on the scores used for ranking; 1 = none */
-  int32_t mpa_mode;        /* 1 = Eq. 8 modality split; 0 = modality-agnostic top-k */
-  int32_t hcc_mode;        /* 1 = Eq. 9-11 compensation; 0 = every head gets budget - window */
+  int32_t mpa_mode;        /* 1 = Eq. 8 modality split; 0 = modality-agnostic top-k; 2 / 3 = fixed priority
+                              baselines: text / image takes all it can, the other modality the rest */
+  int32_t hcc_mode;        /* 1 = Eq. 9-11 compensation, head totals follow demand; 0 = every head gets
+                              budget - window; 2 = Eq. 9-11 layer totals shared equally by the heads */
   int32_t hcc_rho;         /* >= 1: demand clamp ratio around the running nominal budget */
   float   theta;           /* Eq. 9 threshold, in (0, 1] */
   float   softmax_scale;   /* 0 = 1/sqrt(head_dim) */
   int32_t max_new_tokens;  /* decode slack per head in the reduced cache */
   int32_t out_fp32;        /* decode output: 1 = float, 0 = same as dtype */
+  int32_t pool_mode;       /* 0 = max-pool, 1 = average-pool (same clipped neighbourhood) */
+  int32_t share_mode;      /* Eq. 6 masses over 0 = the candidates, 1 = all L columns (window included) */
+  int32_t select_mode;     /* 0 = top scores per modality; 1 = score-free baseline: the first sink_tokens
+                              candidates and the most recent ones, b_t + b_v in total */
+  int32_t sink_tokens;     /* >= 0, used by select_mode 1 */
 } madakv_config;
 
 /* Per-head statistics that madakv_score hands to madakv_allocate. */

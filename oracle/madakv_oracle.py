@@ -52,8 +52,13 @@ class Params:
     window: int            # |P|
     budget: int            # tokens kept per KV head per layer, window included
     pool_k: int = 1        # odd; 1 = Eq. 7 scores used as they are
-    mpa_mode: int = 1      # 1 = Eq. 8 split, 0 = modality-agnostic
-    hcc_mode: int = 1      # 1 = Eq. 9-11, 0 = every head gets the same budget
+    mpa_mode: int = 1      # 1 = Eq. 8 split, 0 = modality-agnostic, 2 = text first, 3 = image first (fixed priority)
+    hcc_mode: int = 1      # 1 = Eq. 9-11 with demand-driven head totals, 0 = every head gets the same budget,
+                           # 2 = Eq. 9-11 layer totals shared equally by the heads of the layer (Eq. 8 as printed)
+    pool_mode: int = 0     # 0 = max-pool, 1 = average-pool
+    share_mode: int = 0    # Eq. 6 sums over 0 = the candidates, 1 = all L columns (window included)
+    select_mode: int = 0   # 0 = top scores, 1 = first `sink_tokens` + most recent candidates (score-free baseline)
+    sink_tokens: int = 4
     hcc_rho: int = 2       # clamp ratio around the running nominal budget
     theta: float = 0.9     # Eq. 9 threshold
     softmax_scale: float = 0.0  # 0 -> 1/sqrt(head_dim)
@@ -140,9 +145,11 @@ def theta_mass_count(values: np.ndarray, theta: float) -> int:
     return int(hit[0]) + 1 if hit.size else n
 
 
-def modality_stats(psi: np.ndarray, mask: np.ndarray, window: int, theta: float):
+def modality_stats(psi: np.ndarray, mask: np.ndarray, window: int, theta: float, share_mode: int = 0):
     """Per head: w[H,2] (Eq. 6), kcnt[H,2] (Eq. 9), and n_mod[2] candidate counts.
-    Uses the raw Eq. 7 scores (never the pooled ones)."""
+    Uses the raw Eq. 7 scores (never the pooled ones).  share_mode = 1 is the other reading
+    of Eq. 6: X_v, X_t are all prompt positions, so the window columns add to w (the counts
+    of Eq. 9 and n_mod stay on the candidates, the only tokens that can be evicted)."""
     H, L = psi.shape
     c = L - window
     w = np.zeros((H, 2), dtype=np.float64)
@@ -150,6 +157,9 @@ def modality_stats(psi: np.ndarray, mask: np.ndarray, window: int, theta: float)
     n_mod = np.zeros(2, dtype=np.int64)
     for h in range(H):
         w[h], n_mod = modality_mass(psi[h], mask, window)
+        if share_mode == 1:
+            for m in (TEXT, IMAGE):
+                w[h, m] += float(psi[h, c:][mask[c:] == m].sum())
         for m in (TEXT, IMAGE):
             kcnt[h, m] = theta_mass_count(psi[h, :c][mask[:c] == m], theta)
     return w, kcnt, n_mod
@@ -167,17 +177,18 @@ def text_share(w_t: float, w_v: float, n_t: int, n_v: int) -> float:
 # --------------------------------------------------------------------------- #
 # Score pooling (not in the paper; ranking only)
 # --------------------------------------------------------------------------- #
-def pool_scores(psi: np.ndarray, window: int, pool_k: int) -> np.ndarray:
+def pool_scores(psi: np.ndarray, window: int, pool_k: int, pool_mode: int = 0) -> np.ndarray:
     """psi_pool[h, i] = max of psi[h, j] over candidates j with |j-i| <= (pool_k-1)/2,
     for i in [0, L-W).  Position-based, clipped at both ends of the candidate range,
-    blind to modality boundaries.  pool_k = 1 returns the candidate scores as is."""
+    blind to modality boundaries.  pool_k = 1 returns the candidate scores as is.
+    pool_mode = 1 takes the mean of the same (clipped) neighbourhood instead of the max."""
     H, L = psi.shape
     c = L - window
     r = (pool_k - 1) // 2
     out = np.empty((H, c), dtype=np.float64)
     for i in range(c):
         lo, hi = max(0, i - r), min(c, i + r + 1)
-        out[:, i] = psi[:, lo:hi].max(axis=1)
+        out[:, i] = psi[:, lo:hi].max(axis=1) if pool_mode == 0 else psi[:, lo:hi].mean(axis=1)
     return out
 
 
@@ -228,7 +239,8 @@ def hcc_allocate(kcnt: np.ndarray, p: Params, trace: dict | None = None) -> np.n
     what is left.  Heads receive `apportion(A, demand)`.  Then R -= A, which is
     Eq. 11 with K^l = sum_h (a_h - phi^l) taken per head (divided by H):
         phi^{l+1} = phi^l - (K^l / H) / (rem - 1).
-    hcc_mode = 0 gives every head beta.
+    hcc_mode = 0 gives every head beta.  hcc_mode = 2 keeps the layer totals A but gives every
+    head of a layer the same share of it.
     """
     NL, H, _ = kcnt.shape
     beta = p.budget - p.window
@@ -252,7 +264,12 @@ def hcc_allocate(kcnt: np.ndarray, p: Params, trace: dict | None = None) -> np.n
             A = R
         else:
             A = min(max(D, R - (rem - 1) * H * n_c), R - (rem - 1) * H * beta_floor)
-        a[l] = apportion(A, dem, n_c)
+        if p.hcc_mode == 2:
+            # Eq. 8 as printed: one budget phi^l for every head of the layer; the layer total of
+            # Eq. 10-11 is shared equally, the A mod H spare tokens go to the lowest heads
+            a[l] = A // H + (np.arange(H) < A % H)
+        else:
+            a[l] = apportion(A, dem, n_c)
         if trace is not None:
             phi = R / (H * rem)
             trace["phi"].append(phi)
@@ -262,10 +279,16 @@ def hcc_allocate(kcnt: np.ndarray, p: Params, trace: dict | None = None) -> np.n
     return a
 
 
-def mpa_split(a: int, w_t: float, w_v: float, n_t: int, n_v: int) -> tuple[int, int]:
+def mpa_split(a: int, w_t: float, w_v: float, n_t: int, n_v: int, mpa_mode: int = 1) -> tuple[int, int]:
     """Eq. 8 in integers: b_t = round-half-up(share_t * a), b_v = a - b_t; a modality
-    that has fewer candidates than its budget hands the surplus to the other."""
+    that has fewer candidates than its budget hands the surplus to the other.
+    mpa_mode 2 / 3 are the fixed-priority baselines the paper argues against (Sec. 1, 2):
+    the preferred modality (text / image) takes all it can, the other gets the rest."""
     s_t = text_share(w_t, w_v, n_t, n_v)
+    if mpa_mode == 2:
+        s_t = 1.0
+    elif mpa_mode == 3:
+        s_t = 0.0
     b_t = int(math.floor(s_t * a + 0.5))
     b_v = a - b_t
     if b_t > n_t:
@@ -294,7 +317,7 @@ def allocate(w: np.ndarray, kcnt: np.ndarray, n_mod: np.ndarray, p: Params,
                 out[l, h] = (a[l, h], 0)
             else:
                 out[l, h] = mpa_split(int(a[l, h]), float(np.float32(w[l, h, 0])),
-                                      float(np.float32(w[l, h, 1])), n_t, n_v)
+                                      float(np.float32(w[l, h, 1])), n_t, n_v, p.mpa_mode)
     return out
 
 
@@ -307,6 +330,16 @@ def top_indices(scores: np.ndarray, idx: np.ndarray, b: int) -> np.ndarray:
         return np.zeros(0, dtype=np.int64)
     order = sorted(range(len(idx)), key=lambda j: (-scores[j], idx[j]))
     return idx[np.asarray(order[:b], dtype=np.int64)]
+
+
+def select_sink_recent(total: int, L: int, window: int, sink_tokens: int) -> np.ndarray:
+    """Score-free baseline (attention sinks + recency): the first min(sink, total) candidates and
+    the most recent total - that many candidates, then the window."""
+    c = L - window
+    total = min(total, c)
+    s = min(sink_tokens, total)
+    keep = np.concatenate([np.arange(s, dtype=np.int64), np.arange(c - (total - s), c, dtype=np.int64)])
+    return np.concatenate([keep, np.arange(c, L, dtype=np.int64)])
 
 
 def select(psi_pool_h: np.ndarray, mask: np.ndarray, b_t: int, b_v: int,
@@ -373,8 +406,8 @@ def score_layer(q_win: np.ndarray, k: np.ndarray, mask: np.ndarray, p: Params,
     psi = window_scores(q_win, k, p.scale)
     if interface_fp32:
         psi = psi.astype(np.float32).astype(np.float64)
-    w, kcnt, n_mod = modality_stats(psi, mask, p.window, p.theta)
-    psi_pool = pool_scores(psi, p.window, p.pool_k)
+    w, kcnt, n_mod = modality_stats(psi, mask, p.window, p.theta, p.share_mode)
+    psi_pool = pool_scores(psi, p.window, p.pool_k, p.pool_mode)
     return psi, psi_pool, w, kcnt, n_mod
 
 
@@ -402,7 +435,10 @@ def evict(q_win: np.ndarray, k: np.ndarray, v: np.ndarray, mask: np.ndarray, p: 
                 kept = np.arange(L, dtype=np.int64)
             else:
                 b_t, b_v = (int(x) for x in res["budgets"][l, h])
-                kept = select(res["psi_pool"][l, h], mask, b_t, b_v, L, p.window, p.mpa_mode)
+                if p.select_mode == 1:
+                    kept = select_sink_recent(b_t + b_v, L, p.window, p.sink_tokens)
+                else:
+                    kept = select(res["psi_pool"][l, h], mask, b_t, b_v, L, p.window, p.mpa_mode)
             kl.append(kept); kc.append(gather(k[l, h], kept)); vc.append(gather(v[l, h], kept))
         res["kept"].append(kl); res["k_c"].append(kc); res["v_c"].append(vc)
     return res

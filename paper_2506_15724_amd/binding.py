@@ -26,7 +26,8 @@ class Config(C.Structure):
                 ("window", C.c_int32), ("budget", C.c_int32), ("dtype", C.c_int32),
                 ("pool_k", C.c_int32), ("mpa_mode", C.c_int32), ("hcc_mode", C.c_int32),
                 ("hcc_rho", C.c_int32), ("theta", C.c_float), ("softmax_scale", C.c_float),
-                ("max_new_tokens", C.c_int32), ("out_fp32", C.c_int32)]
+                ("max_new_tokens", C.c_int32), ("out_fp32", C.c_int32), ("pool_mode", C.c_int32),
+                ("share_mode", C.c_int32), ("select_mode", C.c_int32), ("sink_tokens", C.c_int32)]
 
 
 class MadaKVError(RuntimeError):
@@ -133,10 +134,11 @@ class MadaKV:
 
     def __init__(self, *, n_layers, batch, n_q_heads, n_kv_heads, head_dim, ctx_len, window, budget,
                  dtype="bf16", pool_k=7, mpa_mode=1, hcc_mode=1, hcc_rho=2, theta=0.9, softmax_scale=0.0,
-                 max_new_tokens=0, out_fp32=1, layers_per_call=None, device="cuda:0"):
+                 max_new_tokens=0, out_fp32=1, pool_mode=0, share_mode=0, select_mode=0, sink_tokens=4,
+                 layers_per_call=None, device="cuda:0"):
         self.cfg = Config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, ctx_len, window, budget,
                           BF16 if dtype == "bf16" else FP32, pool_k, mpa_mode, hcc_mode, hcc_rho, theta,
-                          softmax_scale, max_new_tokens, out_fp32)
+                          softmax_scale, max_new_tokens, out_fp32, pool_mode, share_mode, select_mode, sink_tokens)
         self.device = torch.device(device)
         self.tdtype = torch.bfloat16 if dtype == "bf16" else torch.float32
         with torch.cuda.device(self.device):

@@ -70,7 +70,10 @@ __global__ __launch_bounds__(64) void allocate_kernel(AllocArgs a) {
         const long long amin = R - (rem - 1) * H * nc, amax = R - (rem - 1) * H * bf;
         A = D < amin ? amin : (D > amax ? amax : D);
       }
-      if (A == D) {
+      if (a.hcc_mode == 2) {
+        // Eq. 8 as printed: one budget per layer; the A mod H spare tokens go to the lowest heads
+        ah = A / H + (lane < A % H ? 1 : 0);
+      } else if (A == D) {
         ah = dem;
       } else if (A < D) {
         const long long num = A * dem;
@@ -98,6 +101,8 @@ __global__ __launch_bounds__(64) void allocate_kernel(AllocArgs a) {
         double share;
         if (tot > 0.0) share = wt / tot;
         else share = (n_t + n_v) > 0 ? (double)n_t / (double)(n_t + n_v) : 0.0;
+        if (a.mpa_mode == 2) share = 1.0;            // fixed priority baselines: text first / image first
+        else if (a.mpa_mode == 3) share = 0.0;
         bt = (long long)floor(share * (double)ah + 0.5);
         bv = ah - bt;
         if (bt > n_t) { bt = n_t; bv = ah - n_t; }

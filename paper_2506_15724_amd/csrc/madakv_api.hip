@@ -84,7 +84,8 @@ int32_t validate(const madakv_config& c) {
   if (c.hcc_rho < 1 || c.hcc_rho > 1024) return MADAKV_ERR_INVALID_ARG;
   if (!(c.theta > 0.f) || c.theta > 1.f) return MADAKV_ERR_INVALID_ARG;
   if (c.softmax_scale < 0.f || c.max_new_tokens < 0) return MADAKV_ERR_INVALID_ARG;
-  if ((c.mpa_mode | 1) != 1 || (c.hcc_mode | 1) != 1 || (c.out_fp32 | 1) != 1) return MADAKV_ERR_INVALID_ARG;
+  if (c.mpa_mode < 0 || c.mpa_mode > 3 || c.hcc_mode < 0 || c.hcc_mode > 2 || (c.out_fp32 | 1) != 1) return MADAKV_ERR_INVALID_ARG;
+  if ((c.pool_mode | 1) != 1 || (c.share_mode | 1) != 1 || (c.select_mode | 1) != 1 || c.sink_tokens < 0) return MADAKV_ERR_INVALID_ARG;
   return MADAKV_OK;
 }
 

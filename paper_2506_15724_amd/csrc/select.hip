@@ -109,7 +109,7 @@ __global__ __launch_bounds__(OFF_THREADS) void offsets_kernel(OffsetsArgs a) {
 
 struct SelectArgs {
   const float* psi_pool; const uint8_t* mask; const int32_t* budgets; const int64_t* kv_off; const int32_t* kv_len; int32_t* kept_idx;
-  int B, H, L, W, nc, mpa_mode, keep_all;
+  int B, H, L, W, nc, mpa_mode, keep_all, select_mode, sink_tokens;
 };
 
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
@@ -192,6 +192,14 @@ __global__ __launch_bounds__(SEL_THREADS) __attribute__((amdgpu_waves_per_eu(4, 
     return;
   }
   const uint32_t bud[2] = {(uint32_t)a.budgets[head * 2], (uint32_t)a.budgets[head * 2 + 1]};
+  if (a.select_mode == 1) {
+    // score-free baseline: the first `sink` candidates and the most recent ones, then the window
+    const int total = min((int)(bud[0] + bud[1]), a.nc);
+    const int sink = min(a.sink_tokens, total);
+    for (int j = tid; j < total + a.W; j += SEL_THREADS)
+      out[j] = j < sink ? j : (j < total ? a.nc - (total - j) : a.nc + (j - total));
+    return;
+  }
   const int shifts[3] = {21, 10, 0};
   const int widths[3] = {11, 11, 10};
   constexpr int CH = SEL_THREADS * SEL_EPT;      // candidates per chunk
@@ -349,6 +357,7 @@ hipError_t launch_select(const Dims& dm, const madakv_config& c, const float* ps
   a.psi_pool = psi_pool; a.mask = mask; a.budgets = budgets; a.kv_off = kv_off; a.kv_len = kv_len; a.kept_idx = kept_idx;
   a.B = dm.B; a.H = dm.H; a.L = dm.L; a.W = dm.W; a.nc = dm.nc; a.mpa_mode = c.mpa_mode;
   a.keep_all = c.budget >= c.ctx_len ? 1 : 0;
+  a.select_mode = c.select_mode; a.sink_tokens = c.sink_tokens;
   hipLaunchKernelGGL(select_kernel, dim3(dm.heads), dim3(SEL_THREADS), 0, st, a);
   return hipGetLastError();
 }

@@ -26,7 +26,7 @@ constexpr float PSI_MAX = 256.0f;                // G * W <= 256 bounds any colu
 
 struct StatsArgs {
   const float* psi; const uint8_t* mask; float* psi_pool; madakv_head_stats* stats; int32_t* n_mod;
-  int B, H, L, W, nc, pool_r, layer0, mpa_mode;
+  int B, H, L, W, nc, pool_r, layer0, mpa_mode, pool_mode, share_mode;
   double theta;
 };
 
@@ -77,24 +77,34 @@ __device__ __forceinline__ void load_owned(const float* psi, const uint8_t* mask
 
 // max-pool of half-width R over the candidates: the thread's own stretch plus R neighbours
 // on each side from memory; positions outside [0, nc) do not take part
-template <int R>
+template <int R, int AVG>
 __device__ __forceinline__ void pool_owned(const float* psi, float* pool, int i0, int nc, const float (&v)[STATS_EPT]) {
+  const float none = AVG ? 0.f : -__builtin_inff();          // what a position outside [0, nc) contributes
   float ext[STATS_EPT + 2 * R + 1];
 #pragma unroll
   for (int r = 0; r < R; ++r) {
     const int il = i0 - R + r, ir = i0 + STATS_EPT + r;
-    ext[r] = (il >= 0 && il < nc) ? psi[il] : -__builtin_inff();
-    ext[R + STATS_EPT + r] = (ir < nc) ? psi[ir] : -__builtin_inff();
+    ext[r] = (il >= 0 && il < nc) ? psi[il] : none;
+    ext[R + STATS_EPT + r] = (ir < nc) ? psi[ir] : none;
   }
 #pragma unroll
-  for (int e = 0; e < STATS_EPT; ++e) ext[R + e] = (i0 + e < nc) ? v[e] : -__builtin_inff();
+  for (int e = 0; e < STATS_EPT; ++e) ext[R + e] = (i0 + e < nc) ? v[e] : none;
   float o[STATS_EPT];
 #pragma unroll
   for (int e = 0; e < STATS_EPT; ++e) {
-    float mx = ext[R + e];
+    if (AVG) {
+      float sm = 0.f;                                          // left to right over the clipped neighbourhood
 #pragma unroll
-    for (int r = 1; r <= R; ++r) mx = fmaxf(mx, fmaxf(ext[R + e - r], ext[R + e + r]));
-    o[e] = mx;
+      for (int r = -R; r <= R; ++r) sm += ext[R + e + r];
+      const int i = i0 + e;
+      const int cntw = min(i + R, nc - 1) - max(i - R, 0) + 1;
+      o[e] = sm / (float)cntw;
+    } else {
+      float mx = ext[R + e];
+#pragma unroll
+      for (int r = 1; r <= R; ++r) mx = fmaxf(mx, fmaxf(ext[R + e - r], ext[R + e + r]));
+      o[e] = mx;
+    }
   }
   if (i0 + STATS_EPT <= nc && ((reinterpret_cast<uintptr_t>(pool + i0) & 15u) == 0)) {
 #pragma unroll
@@ -112,7 +122,7 @@ __global__ __launch_bounds__(STATS_THREADS) __attribute__((amdgpu_waves_per_eu(4
   __shared__ uint32_t cnt[2][BINS];
   __shared__ unsigned long long sum[2][BINS];
   __shared__ uint32_t s_prefix[2], s_cnt_gt[2], s_n[2], s_done[2], s_bincnt[2];
-  __shared__ unsigned long long s_sum_gt[2], s_w[2], s_target[2], s_binsum[2];
+  __shared__ unsigned long long s_sum_gt[2], s_w[2], s_target[2], s_binsum[2], s_wwin[2];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int head = blockIdx.x;
@@ -127,6 +137,13 @@ __global__ __launch_bounds__(STATS_THREADS) __attribute__((amdgpu_waves_per_eu(4
   const int nchunks = (a.nc + CH - 1) / CH;
   const bool single = nchunks == 1;
 
+  if (tid < 2) s_wwin[tid] = 0ULL;
+  __syncthreads();
+  if (a.share_mode && tid < a.W) {
+    // the other reading of Eq. 6: the proxy columns count towards the masses as well
+    const int i = a.nc + tid;
+    atomicAdd(&s_wwin[mask[i] ? 1 : 0], to_fx(psi[i]));
+  }
   float v[STATS_EPT];
   uint32_t mbits = 0u;
   if (single) load_owned(psi, mask, tid * STATS_EPT, a.nc, v, mbits);
@@ -144,20 +161,21 @@ __global__ __launch_bounds__(STATS_THREADS) __attribute__((amdgpu_waves_per_eu(4
       const int nvalid = min(max(a.nc - i0, 0), STATS_EPT);
       if (level == 0 && nvalid > 0) {
         // pooled score for ranking (raw values); widths up to 7 from registers, wider ones the slow way
-        switch (a.pool_r) {
-          case 0: pool_owned<0>(psi, pool, i0, a.nc, v); break;
-          case 1: pool_owned<1>(psi, pool, i0, a.nc, v); break;
-          case 2: pool_owned<2>(psi, pool, i0, a.nc, v); break;
-          case 3: pool_owned<3>(psi, pool, i0, a.nc, v); break;
+        switch (a.pool_r + (a.pool_mode ? 100 : 0)) {
+          case 0: case 100: pool_owned<0, 0>(psi, pool, i0, a.nc, v); break;
+          case 1: pool_owned<1, 0>(psi, pool, i0, a.nc, v); break;
+          case 2: pool_owned<2, 0>(psi, pool, i0, a.nc, v); break;
+          case 3: pool_owned<3, 0>(psi, pool, i0, a.nc, v); break;
+          case 101: pool_owned<1, 1>(psi, pool, i0, a.nc, v); break;
+          case 102: pool_owned<2, 1>(psi, pool, i0, a.nc, v); break;
+          case 103: pool_owned<3, 1>(psi, pool, i0, a.nc, v); break;
           default:
             for (int e = 0; e < nvalid; ++e) {
               const int i = i0 + e;
-              float mx = psi[i];
-              for (int r = 1; r <= a.pool_r; ++r) {
-                if (i - r >= 0) mx = fmaxf(mx, psi[i - r]);
-                if (i + r < a.nc) mx = fmaxf(mx, psi[i + r]);
-              }
-              pool[i] = mx;
+              const int lo = max(i - a.pool_r, 0), hi = min(i + a.pool_r, a.nc - 1);
+              float acc = a.pool_mode ? 0.f : psi[i];
+              for (int j = lo; j <= hi; ++j) acc = a.pool_mode ? acc + psi[j] : fmaxf(acc, psi[j]);
+              pool[i] = a.pool_mode ? acc / (float)(hi - lo + 1) : acc;
             }
         }
       }
@@ -246,7 +264,7 @@ __global__ __launch_bounds__(STATS_THREADS) __attribute__((amdgpu_waves_per_eu(4
       if (t > (unsigned long long)s_bincnt[m]) t = s_bincnt[m];
       k = (int32_t)(s_cnt_gt[m] + (uint32_t)t);
     }
-    const float w = (float)((double)s_w[m] * (1.0 / (double)FX_SCALE));
+    const float w = (float)((double)(s_w[m] + s_wwin[m]) * (1.0 / (double)FX_SCALE));
     madakv_head_stats* st = a.stats + head;
     if (m == 0) { st->w_t = w; st->k_t = k; } else { st->w_v = w; st->k_v = k; }
     if (head < a.B * a.H && (head % a.H) == 0 && a.n_mod) a.n_mod[b * 2 + m] = (int32_t)s_n[m];
@@ -258,7 +276,7 @@ hipError_t launch_stats(const Dims& dm, const madakv_config& c, const float* psi
   StatsArgs a;
   a.psi = psi; a.mask = mask; a.psi_pool = psi_pool; a.stats = stats; a.n_mod = n_mod;
   a.B = dm.B; a.H = dm.H; a.L = dm.L; a.W = dm.W; a.nc = dm.nc; a.pool_r = (c.pool_k - 1) / 2;
-  a.layer0 = layer0; a.mpa_mode = c.mpa_mode; a.theta = (double)c.theta;
+  a.layer0 = layer0; a.mpa_mode = c.mpa_mode; a.pool_mode = c.pool_mode; a.share_mode = c.share_mode; a.theta = (double)c.theta;
   hipLaunchKernelGGL(stats_kernel, dim3(dm.heads), dim3(STATS_THREADS), 0, st, a);
   return hipGetLastError();
 }

@@ -423,3 +423,67 @@ def test_budgets_beyond_the_cache_leave_heads_empty():
     assert torch.isfinite(out[0, 0, 0]).all()
     assert (eng.k_c[ln[0] + 1:].float() == 123.0).all()
     eng.close()
+
+
+VARIANTS = {
+    "heads_share_layer_total": dict(hcc_mode=2),
+    "text_first": dict(mpa_mode=2),
+    "image_first": dict(mpa_mode=3),
+    "average_pool": dict(pool_mode=1, pool_k=5),
+    "shares_over_all_columns": dict(share_mode=1),
+    "sink_recent": dict(select_mode=1, sink_tokens=4),
+    "sink_recent_uniform": dict(select_mode=1, sink_tokens=9, hcc_mode=0, mpa_mode=0),
+}
+
+
+@pytest.mark.parametrize("variant", list(VARIANTS.keys()))
+def test_alternative_readings_and_baselines(variant):
+    """The switchable readings / baseline policies, stage by stage against their oracle branch."""
+    kw = VARIANTS[variant]
+    wl = small_workloads()["bf16_mha"]
+    if "pool_k" in kw:
+        wl = wl.scaled(pool_k=kw["pool_k"])
+    NL, B, H, L, W = wl.n_layers, wl.batch, wl.n_kv_heads, wl.ctx_len, wl.window
+    nc = L - W
+    okw = {k: v for k, v in kw.items() if k != "pool_k"}
+    p = PU.oracle_params(wl, **okw)
+    q, k, v, mask, masks = PU.make_inputs(wl, DEV)
+    eng = engine(wl, **okw)
+    say(f"variant {variant}")
+    eng.score(0, NL, q, k, mask); eng.allocate(0, NL); eng.select_gather(0, NL, k, v, mask)
+    torch.cuda.synchronize()
+    psi_g, pool_g = eng.psi.cpu().numpy(), eng.psi_pool.cpu().numpy()
+    w_g, k_g = eng.stats_host()
+    nmod = eng.n_mod.cpu().numpy()
+    bud_g = eng.budgets.cpu().numpy()
+    kept_all, off, ln = eng.kept_idx.cpu().numpy(), eng.kv_off.cpu().numpy(), eng.kv_len.cpu().numpy()
+    for b in range(B):
+        for l in range(NL):
+            psi_in = psi_g[l, b].astype(np.float64)
+            w_o, k_o, _ = O.modality_stats(psi_in, masks[b], W, p.theta, p.share_mode)
+            np.testing.assert_allclose(w_g[l, b], w_o, rtol=2e-6)
+            pool_o = O.pool_scores(psi_in, W, p.pool_k, p.pool_mode)
+            if p.pool_mode == 0:
+                np.testing.assert_array_equal(pool_g[l, b], pool_o.astype(np.float32))
+            else:
+                np.testing.assert_allclose(pool_g[l, b], pool_o, rtol=2e-6, atol=1e-30)
+            for h in range(H):
+                for m in (0, 1):
+                    if k_g[l, b, h, m] != k_o[h, m]:
+                        assert PU.k_count_ok(int(k_g[l, b, h, m]), psi_in[h, :nc][masks[b][:nc] == m], p.theta)
+        np.testing.assert_array_equal(bud_g[:, b], O.allocate(w_g[:, b], k_g[:, b].astype(np.int64), nmod[b], p))
+        for l in range(NL):
+            for h in range(H):
+                bt, bv = (int(x) for x in bud_g[l, b, h])
+                if p.select_mode == 1:
+                    ref = O.select_sink_recent(bt + bv, L, W, p.sink_tokens)
+                else:
+                    ref = O.select(pool_g[l, b, h].astype(np.float64), masks[b], bt, bv, L, W, p.mpa_mode)
+                o = off[l, b, h]
+                np.testing.assert_array_equal(kept_all[o:o + ln[l, b, h]], ref)
+                assert torch.equal(eng.k_c[o:o + len(ref)].cpu(), k[l, b, h].cpu()[ref])
+    assert bud_g.sum() == NL * B * H * (wl.budget - W)
+    if variant == "heads_share_layer_total":
+        tot = bud_g.sum(-1)
+        assert ((tot.max(-1) - tot.min(-1)) <= 1).all()
+    eng.close()

@@ -438,3 +438,62 @@ def test_hcc_hand_worked_examples():
     # (3) lower clamp of the layer total.  n_c=10, R=32: l0 (1,1)->(4,4), D=8 < 32-1*2*10=12 -> A=12,
     #     head-room (6,6) -> (6,6); R=20: last layer lo=5 hi=10, (7,2)->(7,5), D=12, room (3,5) -> (10,10).
     assert run(2, 2, 10, 8, [[1, 1], [7, 2]]) == [[6, 6], [10, 10]]
+
+
+# ------------------------------------------------------------------ alternative readings and baseline policies
+def test_uniform_within_layer_totals():
+    r = rng(30)
+    NL, H, L, W, budget = 6, 5, 120, 4, 30
+    kc = np.stack([r.integers(0, 60, size=(NL, H)), r.integers(0, 50, size=(NL, H))], -1)
+    a1 = O.hcc_allocate(kc, _params(NL, H, L, W, budget))
+    a2 = O.hcc_allocate(kc, _params(NL, H, L, W, budget, hcc_mode=2))
+    assert (a1.sum(axis=1) == a2.sum(axis=1)).all()                     # same layer totals (Eq. 10-11)
+    assert a2.sum() == NL * H * (budget - W)
+    assert ((a2.max(axis=1) - a2.min(axis=1)) <= 1).all()               # one budget per layer (Eq. 8), spare tokens to the low heads
+    assert (np.diff(a2, axis=1) <= 0).all()
+
+
+def test_fixed_priority_splits():
+    assert O.mpa_split(10, 1.0, 9.0, 100, 100, mpa_mode=2) == (10, 0)
+    assert O.mpa_split(10, 1.0, 9.0, 4, 100, mpa_mode=2) == (4, 6)       # text first, the rest to image
+    assert O.mpa_split(10, 9.0, 1.0, 100, 100, mpa_mode=3) == (0, 10)
+    assert O.mpa_split(10, 9.0, 1.0, 100, 7, mpa_mode=3) == (3, 7)       # image first
+
+
+def test_average_pool_brute_force():
+    r = rng(31)
+    psi = r.random((2, 19)); W = 3
+    np.testing.assert_array_equal(O.pool_scores(psi, W, 1, pool_mode=1), psi[:, :16])
+    got = O.pool_scores(psi, W, 5, pool_mode=1)
+    for h in range(2):
+        for i in range(16):
+            js = [j for j in range(16) if abs(j - i) <= 2]
+            assert got[h, i] == pytest.approx(sum(psi[h, j] for j in js) / len(js), rel=1e-14)
+    np.testing.assert_allclose(O.pool_scores(np.full((1, 12), 0.25), 2, 7, pool_mode=1), 0.25, rtol=1e-15)
+
+
+def test_shares_over_all_columns():
+    r = rng(32)
+    Hq, H, W, L, d = 4, 2, 5, 33, 8
+    psi = O.window_scores(r.normal(size=(Hq, W, d)), r.normal(size=(H, L, d)), 0.4)
+    mask = (r.random(L) < 0.5).astype(np.uint8); mask[L - W:] = 0
+    w0, k0, n0 = O.modality_stats(psi, mask, W, 0.9, share_mode=0)
+    w1, k1, n1 = O.modality_stats(psi, mask, W, 0.9, share_mode=1)
+    np.testing.assert_allclose(w1.sum(axis=1), (Hq // H) * W, rtol=1e-12)   # all the mass of the proxy rows
+    np.testing.assert_allclose(w1[:, 1], w0[:, 1], rtol=1e-15)             # the window is text: image mass unchanged
+    np.testing.assert_allclose(w1[:, 0] - w0[:, 0], psi[:, L - W:].sum(axis=1), rtol=1e-12)
+    assert (k0 == k1).all() and (n0 == n1).all()
+
+
+def test_sink_recent_baseline():
+    assert list(O.select_sink_recent(7, 20, 3, 4)) == [0, 1, 2, 3, 14, 15, 16, 17, 18, 19]
+    assert list(O.select_sink_recent(2, 20, 3, 4)) == [0, 1, 17, 18, 19]
+    assert list(O.select_sink_recent(99, 10, 2, 4)) == list(range(10))
+    q, k, v, mask = _tiny_problem(33)
+    NL, H, L, d = k.shape
+    p = O.Params(n_layers=NL, n_q_heads=4, n_kv_heads=H, head_dim=d, ctx_len=L, window=4, budget=16, select_mode=1,
+                 hcc_mode=0, sink_tokens=2)
+    res = O.evict(q, k, v, mask, p)
+    for l in range(NL):
+        for h in range(H):
+            assert list(res["kept"][l][h]) == [0, 1] + list(range(34, 48))
