@@ -283,13 +283,16 @@ def main():
         variants = {"heads_share_layer_total": dict(hcc_mode=2), "text_first": dict(mpa_mode=2),
                     "modality_agnostic_uniform": dict(mpa_mode=0, hcc_mode=0), "average_pool": dict(pool_mode=1),
                     "shares_over_all_columns": dict(share_mode=1), "sink_recent": dict(select_mode=1)}
+        variants["three_modalities"] = dict(n_modalities=3)
+        mask3 = torch.from_numpy(np.stack([WL.modality_mask(wl.scaled(n_modalities=3), b) for b in range(B)])).to(dev)
         vres = {}
         for name, kw in variants.items():
+            vmask = mask3 if name == "three_modalities" else mask
             ve = MB.MadaKV(n_layers=NL, batch=B, n_q_heads=Hq, n_kv_heads=H, head_dim=d, ctx_len=L, window=W,
                            budget=wl.budget, dtype=wl.dtype, pool_k=wl.pool_k, max_new_tokens=1, out_fp32=0, device=dev, **kw)
             for rep in range(2):
                 e0.record()
-                ve.score(0, NL, q, k, mask); ve.allocate(0, NL); ve.select_gather(0, NL, k, v, mask)
+                ve.score(0, NL, q, k, vmask); ve.allocate(0, NL); ve.select_gather(0, NL, k, v, vmask)
                 e1.record()
             torch.cuda.synchronize()
             vres[name] = {"evict_ms": e0.elapsed_time(e1), "ctx_tokens_per_s": B * L / (e0.elapsed_time(e1) * 1e-3)}

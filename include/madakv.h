@@ -33,7 +33,8 @@
  *     only the n layers of the call, layer-major.  madakv_allocate and
  *     madakv_select_gather carry state from layer to layer and must be called in
  *     increasing layer order, starting at layer 0 (which resets the state).
- *   - Modality ids: 0 = text, 1 = image.  Query head j reads KV head j / G,
+ *   - Modality ids: 0 = text, 1 = image (2, 3: further modalities when n_modalities says so).
+ *     Query head j reads KV head j / G,
  *     G = n_q_heads / n_kv_heads.
  */
 #ifndef MADAKV_H
@@ -86,9 +87,13 @@ typedef struct {
   int32_t select_mode;     /* 0 = top scores per modality; 1 = score-free baseline: the first sink_tokens
                               candidates and the most recent ones, b_t + b_v in total */
   int32_t sink_tokens;     /* >= 0, used by select_mode 1 */
+  int32_t n_modalities;    /* M, 2 .. 4: modality ids in the mask are 0 .. M-1 (the paper has text = 0 and
+                              image = 1; more modalities are the extension its Sec. 6 names) */
 } madakv_config;
 
-/* Per-head statistics that madakv_score hands to madakv_allocate. */
+/* Per-head statistics that madakv_score hands to madakv_allocate: a record of M floats
+ * (Eq. 6 attention mass per modality) followed by M int32 (Eq. 9 theta-mass counts).  With
+ * two modalities the record is this struct. */
 typedef struct {
   float   w_t, w_v;        /* Eq. 6 attention mass on text / image candidates */
   int32_t k_t, k_v;        /* Eq. 9 theta-mass counts */
@@ -122,34 +127,34 @@ int32_t madakv_compact_capacity_tokens(const madakv_handle* h, int64_t* tokens);
  *                              softmax(scale * q k^T) they pay to key i
  *   psi_pool [n, B, H, L-W]    out: max of psi over |j - i| <= (pool_k-1)/2 within the
  *                              candidates [0, L-W)
- *   stats    [n, B, H]         out: w_t, w_v, k_t, k_v over the candidates
- *   n_mod    [B, 2] int32      out: candidate count per modality
+ *   stats    [n, B, H]         out: records {float w[M]; int32 k[M]} over the candidates
+ *   n_mod    [B, M] int32      out: candidate count per modality
  * ws / ws_bytes: scratch of at least score_ws bytes. */
 int32_t madakv_score(madakv_handle* h, int32_t layer0, int32_t n,
                      const void* q_win, const void* k, const uint8_t* mask,
-                     float* psi, float* psi_pool, madakv_head_stats* stats, int32_t* n_mod,
+                     float* psi, float* psi_pool, void* stats, int32_t* n_mod,
                      void* ws, size_t ws_bytes, void* stream);
 
 /* Eq. 8, Eq. 10-11 for layers [layer0, layer0 + n) in order.
  *   stats    [n, B, H]        from madakv_score
- *   n_mod    [B, 2]
- *   budgets  [n, B, H, 2] int32  out: (b_t, b_v) candidate tokens to keep per modality;
- *                              b_t + b_v summed over the whole model and over heads is
+ *   n_mod    [B, M]
+ *   budgets  [n, B, H, M] int32  out: candidate tokens to keep per modality ((b_t, b_v) for M = 2);
+ *                              their sum over modalities, heads and the whole model is
  *                              exactly n_layers * H * (budget - W) per batch item.
- *                              With mpa_mode = 0 the head total is in b_t and b_v = 0.
+ *                              With mpa_mode = 0 the head total is in slot 0, the others are 0.
  * The remaining pool of each batch item is carried in the handle; layer0 = 0 resets it. */
 int32_t madakv_allocate(madakv_handle* h, int32_t layer0, int32_t n,
-                        const madakv_head_stats* stats, const int32_t* n_mod,
+                        const void* stats, const int32_t* n_mod,
                         int32_t* budgets, void* stream);
 
 /* Per head and modality: keep the b_m candidates with the largest psi_pool (equal scores:
  * lower position first), in ascending position, then the W window positions; copy their
  * K and V rows into the reduced cache.
- *   psi_pool [n, B, H, L-W], mask [B, L], budgets [n, B, H, 2] (0 <= b_m <= n_mod[m])
+ *   psi_pool [n, B, H, L-W], mask [B, L], budgets [n, B, H, M] (0 <= b_m <= n_mod[m])
  *   k, v     [n, B, H, L, d]
  *   kept_idx int32, ragged  out: head (l,b,h) owns kept_idx[kv_off .. kv_off + kv_len)
  *   kv_off   [n, B, H] int64 out: first row of the head's segment in k_c / v_c / kept_idx
- *   kv_len   [n, B, H] int32 out: b_t + b_v + W
+ *   kv_len   [n, B, H] int32 out: sum of the head's budgets + W
  *   k_c, v_c [capacity_tokens, d]  out: the reduced cache; a head's segment has kv_len
  *                              rows followed by max_new_tokens free rows
  * Batch item b owns rows [b, b+1) * capacity_tokens / B; inside, layers then heads follow

@@ -59,6 +59,7 @@ class Params:
     share_mode: int = 0    # Eq. 6 sums over 0 = the candidates, 1 = all L columns (window included)
     select_mode: int = 0   # 0 = top scores, 1 = first `sink_tokens` + most recent candidates (score-free baseline)
     sink_tokens: int = 4
+    n_modalities: int = 2  # the paper has text and image; more (audio, video: its Sec. 6) make Eq. 6, 8, 9 M-way
     hcc_rho: int = 2       # clamp ratio around the running nominal budget
     theta: float = 0.9     # Eq. 9 threshold
     softmax_scale: float = 0.0  # 0 -> 1/sqrt(head_dim)
@@ -115,13 +116,13 @@ def window_scores(q_win: np.ndarray, k: np.ndarray, scale: float) -> np.ndarray:
 # --------------------------------------------------------------------------- #
 # Eq. 6 and Eq. 9: modality mass and theta-mass counts
 # --------------------------------------------------------------------------- #
-def modality_mass(psi_h: np.ndarray, mask: np.ndarray, window: int):
-    """(w[2], n[2]) over the candidates [0, L-W) of one head (Eq. 6)."""
+def modality_mass(psi_h: np.ndarray, mask: np.ndarray, window: int, n_modalities: int = 2):
+    """(w[M], n[M]) over the candidates [0, L-W) of one head (Eq. 6, one sum per modality)."""
     L = psi_h.shape[0]
     c = L - window
-    w = np.zeros(2, dtype=np.float64)
-    n = np.zeros(2, dtype=np.int64)
-    for m in (TEXT, IMAGE):
+    w = np.zeros(n_modalities, dtype=np.float64)
+    n = np.zeros(n_modalities, dtype=np.int64)
+    for m in range(n_modalities):
         sel = mask[:c] == m
         n[m] = int(sel.sum())
         w[m] = float(psi_h[:c][sel].sum())
@@ -145,22 +146,24 @@ def theta_mass_count(values: np.ndarray, theta: float) -> int:
     return int(hit[0]) + 1 if hit.size else n
 
 
-def modality_stats(psi: np.ndarray, mask: np.ndarray, window: int, theta: float, share_mode: int = 0):
-    """Per head: w[H,2] (Eq. 6), kcnt[H,2] (Eq. 9), and n_mod[2] candidate counts.
+def modality_stats(psi: np.ndarray, mask: np.ndarray, window: int, theta: float, share_mode: int = 0,
+                   n_modalities: int = 2):
+    """Per head: w[H,M] (Eq. 6), kcnt[H,M] (Eq. 9), and n_mod[M] candidate counts.
     Uses the raw Eq. 7 scores (never the pooled ones).  share_mode = 1 is the other reading
     of Eq. 6: X_v, X_t are all prompt positions, so the window columns add to w (the counts
     of Eq. 9 and n_mod stay on the candidates, the only tokens that can be evicted)."""
     H, L = psi.shape
     c = L - window
-    w = np.zeros((H, 2), dtype=np.float64)
-    kcnt = np.zeros((H, 2), dtype=np.int64)
-    n_mod = np.zeros(2, dtype=np.int64)
+    M = n_modalities
+    w = np.zeros((H, M), dtype=np.float64)
+    kcnt = np.zeros((H, M), dtype=np.int64)
+    n_mod = np.zeros(M, dtype=np.int64)
     for h in range(H):
-        w[h], n_mod = modality_mass(psi[h], mask, window)
+        w[h], n_mod = modality_mass(psi[h], mask, window, M)
         if share_mode == 1:
-            for m in (TEXT, IMAGE):
+            for m in range(M):
                 w[h, m] += float(psi[h, c:][mask[c:] == m].sum())
-        for m in (TEXT, IMAGE):
+        for m in range(M):
             kcnt[h, m] = theta_mass_count(psi[h, :c][mask[:c] == m], theta)
     return w, kcnt, n_mod
 
@@ -258,7 +261,7 @@ def hcc_allocate(kcnt: np.ndarray, p: Params, trace: dict | None = None) -> np.n
         rem = NL - l
         lo = max(1, -((-R) // (rho * H * rem)))            # ceil
         hi = min(n_c, (rho * R) // (H * rem))
-        dem = np.clip(kcnt[l, :, 0] + kcnt[l, :, 1], lo, hi).astype(np.int64)
+        dem = np.clip(kcnt[l].sum(axis=-1), lo, hi).astype(np.int64)
         D = int(dem.sum())
         if l == NL - 1:
             A = R
@@ -298,26 +301,62 @@ def mpa_split(a: int, w_t: float, w_v: float, n_t: int, n_v: int, mpa_mode: int 
     return b_t, b_v
 
 
+def mpa_split_n(a: int, w: np.ndarray, n: np.ndarray, mpa_mode: int = 1) -> list[int]:
+    """Eq. 8 for M modalities, in integers.  Two modalities: exactly `mpa_split`.  More:
+    quotas share_m * a are floored and the spare tokens go one each to the largest fractional
+    parts (ties: lower modality id); a modality short of candidates is cut to what it has and
+    the surplus goes to the others in order of decreasing share (ties: lower id), each up to its
+    room.  mpa_mode 2 / 3 fill the modalities greedily in ascending / descending id order."""
+    M = len(n)
+    n = [int(x) for x in n]
+    if M == 2:
+        return list(mpa_split(a, float(w[0]), float(w[1]), n[0], n[1], mpa_mode))
+    if mpa_mode in (2, 3):
+        order = range(M) if mpa_mode == 2 else range(M - 1, -1, -1)
+        b, left = [0] * M, a
+        for m in order:
+            b[m] = min(left, n[m]); left -= b[m]
+        return b
+    tot = 0.0
+    for m in range(M):
+        tot += float(w[m])
+    nt = sum(n)
+    share = [(float(w[m]) / tot) if tot > 0.0 else ((n[m] / nt) if nt > 0 else 0.0) for m in range(M)]
+    quota = [share[m] * a for m in range(M)]
+    b = [int(math.floor(x)) for x in quota]
+    frac = [quota[m] - b[m] for m in range(M)]
+    spare = a - sum(b)
+    for m in sorted(range(M), key=lambda m: (-frac[m], m))[:max(spare, 0)]:
+        b[m] += 1
+    surplus = 0
+    for m in range(M):
+        if b[m] > n[m]:
+            surplus += b[m] - n[m]; b[m] = n[m]
+    for m in sorted(range(M), key=lambda m: (-share[m], m)):
+        give = min(surplus, n[m] - b[m])
+        b[m] += give; surplus -= give
+    return b
+
+
 def allocate(w: np.ndarray, kcnt: np.ndarray, n_mod: np.ndarray, p: Params,
              trace: dict | None = None) -> np.ndarray:
-    """budgets[N_L, H, 2] = (b_t, b_v) for one batch item.
-    w[N_L,H,2] are the Eq. 6 masses as they cross the interface (float32 values),
-    kcnt[N_L,H,2] the Eq. 9 counts, n_mod[2] the candidate counts per modality.
+    """budgets[N_L, H, M] for one batch item.
+    w[N_L,H,M] are the Eq. 6 masses as they cross the interface (float32 values),
+    kcnt[N_L,H,M] the Eq. 9 counts, n_mod[M] the candidate counts per modality.
     mpa_mode = 0 puts the whole total in slot 0: selection then ignores modality."""
-    NL, H, _ = kcnt.shape
-    out = np.zeros((NL, H, 2), dtype=np.int64)
-    n_t, n_v = int(n_mod[0]), int(n_mod[1])
+    NL, H, M = kcnt.shape
+    out = np.zeros((NL, H, M), dtype=np.int64)
     if p.keep_all:
-        out[:, :, 0], out[:, :, 1] = n_t, n_v
+        out[:, :, :] = np.asarray(n_mod, dtype=np.int64)[None, None, :]
         return out
     a = hcc_allocate(kcnt, p, trace)
     for l in range(NL):
         for h in range(H):
             if p.mpa_mode == 0:
-                out[l, h] = (a[l, h], 0)
+                out[l, h, 0] = a[l, h]
             else:
-                out[l, h] = mpa_split(int(a[l, h]), float(np.float32(w[l, h, 0])),
-                                      float(np.float32(w[l, h, 1])), n_t, n_v, p.mpa_mode)
+                w32 = np.asarray(w[l, h], dtype=np.float32).astype(np.float64)
+                out[l, h] = mpa_split_n(int(a[l, h]), w32, n_mod, p.mpa_mode)
     return out
 
 
@@ -356,6 +395,22 @@ def select(psi_pool_h: np.ndarray, mask: np.ndarray, b_t: int, b_v: int,
         for m, b in ((TEXT, b_t), (IMAGE, b_v)):
             sel = mask[:c] == m
             parts.append(top_indices(psi_pool_h[sel], cand[sel], b))
+        keep = np.concatenate(parts)
+    keep = np.sort(keep)
+    return np.concatenate([keep, np.arange(c, L, dtype=np.int64)])
+
+
+def select_n(psi_pool_h: np.ndarray, mask: np.ndarray, budgets, L: int, window: int, mpa_mode: int = 1) -> np.ndarray:
+    """`select` for any number of modalities: budgets[m] best-scored candidates of modality m."""
+    c = L - window
+    cand = np.arange(c, dtype=np.int64)
+    if mpa_mode == 0:
+        keep = top_indices(psi_pool_h, cand, int(sum(budgets)))
+    else:
+        parts = []
+        for m, b in enumerate(budgets):
+            sel = mask[:c] == m
+            parts.append(top_indices(psi_pool_h[sel], cand[sel], int(b)))
         keep = np.concatenate(parts)
     keep = np.sort(keep)
     return np.concatenate([keep, np.arange(c, L, dtype=np.int64)])
@@ -406,7 +461,7 @@ def score_layer(q_win: np.ndarray, k: np.ndarray, mask: np.ndarray, p: Params,
     psi = window_scores(q_win, k, p.scale)
     if interface_fp32:
         psi = psi.astype(np.float32).astype(np.float64)
-    w, kcnt, n_mod = modality_stats(psi, mask, p.window, p.theta, p.share_mode)
+    w, kcnt, n_mod = modality_stats(psi, mask, p.window, p.theta, p.share_mode, p.n_modalities)
     psi_pool = pool_scores(psi, p.window, p.pool_k, p.pool_mode)
     return psi, psi_pool, w, kcnt, n_mod
 
@@ -434,11 +489,11 @@ def evict(q_win: np.ndarray, k: np.ndarray, v: np.ndarray, mask: np.ndarray, p: 
             if p.keep_all:
                 kept = np.arange(L, dtype=np.int64)
             else:
-                b_t, b_v = (int(x) for x in res["budgets"][l, h])
+                bud = [int(x) for x in res["budgets"][l, h]]
                 if p.select_mode == 1:
-                    kept = select_sink_recent(b_t + b_v, L, p.window, p.sink_tokens)
+                    kept = select_sink_recent(sum(bud), L, p.window, p.sink_tokens)
                 else:
-                    kept = select(res["psi_pool"][l, h], mask, b_t, b_v, L, p.window, p.mpa_mode)
+                    kept = select_n(res["psi_pool"][l, h], mask, bud, L, p.window, p.mpa_mode)
             kl.append(kept); kc.append(gather(k[l, h], kept)); vc.append(gather(v[l, h], kept))
         res["kept"].append(kl); res["k_c"].append(kc); res["v_c"].append(vc)
     return res

@@ -27,7 +27,8 @@ class Config(C.Structure):
                 ("pool_k", C.c_int32), ("mpa_mode", C.c_int32), ("hcc_mode", C.c_int32),
                 ("hcc_rho", C.c_int32), ("theta", C.c_float), ("softmax_scale", C.c_float),
                 ("max_new_tokens", C.c_int32), ("out_fp32", C.c_int32), ("pool_mode", C.c_int32),
-                ("share_mode", C.c_int32), ("select_mode", C.c_int32), ("sink_tokens", C.c_int32)]
+                ("share_mode", C.c_int32), ("select_mode", C.c_int32), ("sink_tokens", C.c_int32),
+                ("n_modalities", C.c_int32)]
 
 
 class MadaKVError(RuntimeError):
@@ -135,10 +136,10 @@ class MadaKV:
     def __init__(self, *, n_layers, batch, n_q_heads, n_kv_heads, head_dim, ctx_len, window, budget,
                  dtype="bf16", pool_k=7, mpa_mode=1, hcc_mode=1, hcc_rho=2, theta=0.9, softmax_scale=0.0,
                  max_new_tokens=0, out_fp32=1, pool_mode=0, share_mode=0, select_mode=0, sink_tokens=4,
-                 layers_per_call=None, device="cuda:0"):
+                 n_modalities=2, layers_per_call=None, device="cuda:0"):
         self.cfg = Config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, ctx_len, window, budget,
                           BF16 if dtype == "bf16" else FP32, pool_k, mpa_mode, hcc_mode, hcc_rho, theta,
-                          softmax_scale, max_new_tokens, out_fp32, pool_mode, share_mode, select_mode, sink_tokens)
+                          softmax_scale, max_new_tokens, out_fp32, pool_mode, share_mode, select_mode, sink_tokens, n_modalities)
         self.device = torch.device(device)
         self.tdtype = torch.bfloat16 if dtype == "bf16" else torch.float32
         with torch.cuda.device(self.device):
@@ -151,11 +152,12 @@ class MadaKV:
         self.select_ws = torch.empty(max(sel_ws, 16), dtype=torch.uint8, device=dev)
         self.decode_ws = torch.empty(max(d_ws, d1, 16), dtype=torch.uint8, device=dev)
         NL, B, H, L, W = n_layers, batch, n_kv_heads, ctx_len, window
+        M = self.M = n_modalities
         self.psi = torch.empty(NL, B, H, L, dtype=torch.float32, device=dev)
         self.psi_pool = torch.empty(NL, B, H, L - W, dtype=torch.float32, device=dev)
-        self.stats = torch.empty(NL, B, H, 4, dtype=torch.int32, device=dev)      # {f32 w_t, f32 w_v, i32 k_t, i32 k_v}
-        self.n_mod = torch.empty(B, 2, dtype=torch.int32, device=dev)
-        self.budgets = torch.empty(NL, B, H, 2, dtype=torch.int32, device=dev)
+        self.stats = torch.empty(NL, B, H, 2 * M, dtype=torch.int32, device=dev)  # {f32 w[M]; i32 k[M]}
+        self.n_mod = torch.empty(B, M, dtype=torch.int32, device=dev)
+        self.budgets = torch.empty(NL, B, H, M, dtype=torch.int32, device=dev)
         self.capacity = madakv_compact_capacity_tokens(self.h)
         self.kept_idx = torch.empty(self.capacity, dtype=torch.int32, device=dev)
         self.kv_off = torch.empty(NL, B, H, dtype=torch.int64, device=dev)
@@ -200,6 +202,6 @@ class MadaKV:
     # host copies of the statistics in their declared types
     def stats_host(self):
         s = self.stats.cpu()
-        w = s[..., :2].contiguous().view(torch.float32).numpy()
-        k = s[..., 2:].contiguous().numpy()
+        w = s[..., :self.M].contiguous().view(torch.float32).numpy()
+        k = s[..., self.M:].contiguous().numpy()
         return w, k

@@ -16,8 +16,8 @@
 namespace madakv {
 
 struct AllocArgs {
-  const madakv_head_stats* stats; const int32_t* n_mod; int32_t* budgets; long long* pool;
-  int n, B, H, NL, layer0, nc, beta, rho, mpa_mode, hcc_mode, keep_all;
+  const void* stats; const int32_t* n_mod; int32_t* budgets; long long* pool;
+  int n, B, H, NL, layer0, nc, beta, rho, mpa_mode, hcc_mode, keep_all, M;
 };
 
 // +1 for the `extra` lanes with the largest remainder (ties: lower lane first).
@@ -35,7 +35,12 @@ __global__ __launch_bounds__(64) void allocate_kernel(AllocArgs a) {
   const int b = blockIdx.x;
   const int lane = threadIdx.x;
   const bool act = lane < a.H;
-  const long long n_t = a.n_mod[b * 2], n_v = a.n_mod[b * 2 + 1];
+  constexpr int MAXM = 4;
+  const int M = a.M;
+  long long nm[MAXM];
+#pragma unroll
+  for (int m = 0; m < MAXM; ++m) nm[m] = m < M ? a.n_mod[b * M + m] : 0;
+  const long long n_t = nm[0], n_v = nm[1];
   const long long H = a.H, nc = a.nc, rho = a.rho, beta = a.beta;
   long long R = (a.layer0 == 0) ? (long long)a.NL * H * beta : a.pool[b];
   long long bf = beta / (rho * rho);
@@ -44,11 +49,18 @@ __global__ __launch_bounds__(64) void allocate_kernel(AllocArgs a) {
   for (int li = 0; li < a.n; ++li) {
     const int l = a.layer0 + li;
     const long long idx = ((long long)li * a.B + b) * a.H + lane;
-    madakv_head_stats st = {0.f, 0.f, 0, 0};
-    if (act) st = a.stats[idx];
+    // the head's record: M float masses (Eq. 6) then M int32 counts (Eq. 9)
+    float wm[MAXM]; long long km = 0;
+    const float* rec = reinterpret_cast<const float*>(a.stats) + idx * 2 * M;
+#pragma unroll
+    for (int m = 0; m < MAXM; ++m) {
+      wm[m] = (act && m < M) ? rec[m] : 0.f;
+      if (act && m < M) km += reinterpret_cast<const int32_t*>(rec)[M + m];
+    }
     long long ah;
     if (a.keep_all) {
-      if (act) { a.budgets[idx * 2] = (int32_t)n_t; a.budgets[idx * 2 + 1] = (int32_t)n_v; }
+#pragma unroll
+      for (int m = 0; m < MAXM; ++m) if (act && m < M) a.budgets[idx * M + m] = (int32_t)nm[m];
       continue;
     }
     if (!a.hcc_mode) {
@@ -59,7 +71,7 @@ __global__ __launch_bounds__(64) void allocate_kernel(AllocArgs a) {
       if (lo < 1) lo = 1;
       long long hi = (rho * R) / (H * rem);
       if (hi > nc) hi = nc;
-      long long dem = (long long)st.k_t + (long long)st.k_v;
+      long long dem = km;
       dem = dem < lo ? lo : (dem > hi ? hi : dem);
       if (!act) dem = 0;
       const long long D = wave_sum_i64(dem);
@@ -90,13 +102,13 @@ __global__ __launch_bounds__(64) void allocate_kernel(AllocArgs a) {
       }
       R -= A;
     }
-    if (act) {
+    if (act && M == 2) {
       long long bt, bv;
       if (a.mpa_mode == 0) {
         bt = ah; bv = 0;
       } else {
         // Eq. 8: the share is formed in double from the float masses that crossed the interface
-        const double wt = (double)st.w_t, wv = (double)st.w_v;
+        const double wt = (double)wm[0], wv = (double)wm[1];
         const double tot = wt + wv;
         double share;
         if (tot > 0.0) share = wt / tot;
@@ -110,14 +122,66 @@ __global__ __launch_bounds__(64) void allocate_kernel(AllocArgs a) {
       }
       a.budgets[idx * 2] = (int32_t)bt;
       a.budgets[idx * 2 + 1] = (int32_t)bv;
+    } else if (act) {
+      // Eq. 8, M-way: floor the quotas, spare tokens to the largest fractional parts (ties: lower
+      // id); a modality short of candidates is cut to what it has, the surplus goes to the others
+      // in order of decreasing share (ties: lower id).  All loops are over at most 4 modalities.
+      long long bm[MAXM] = {0, 0, 0, 0};
+      if (a.mpa_mode == 0) {
+        bm[0] = ah;
+      } else if (a.mpa_mode == 2 || a.mpa_mode == 3) {
+        long long left = ah;
+        for (int j = 0; j < M; ++j) {
+          const int m = a.mpa_mode == 2 ? j : M - 1 - j;
+          bm[m] = left < nm[m] ? left : nm[m];
+          left -= bm[m];
+        }
+      } else {
+        double tot = 0.0; long long nt = 0;
+        for (int m = 0; m < M; ++m) { tot += (double)wm[m]; nt += nm[m]; }
+        double share[MAXM] = {0, 0, 0, 0}, frac[MAXM] = {0, 0, 0, 0};
+        long long sumb = 0;
+        for (int m = 0; m < M; ++m) {
+          share[m] = tot > 0.0 ? (double)wm[m] / tot : (nt > 0 ? (double)nm[m] / (double)nt : 0.0);
+          const double quota = share[m] * (double)ah;
+          bm[m] = (long long)floor(quota);
+          frac[m] = quota - (double)bm[m];
+          sumb += bm[m];
+        }
+        const long long spare = ah - sumb;
+        long long add[MAXM] = {0, 0, 0, 0};
+        for (int m = 0; m < M; ++m) {
+          int rank = 0;
+          for (int o = 0; o < M; ++o) if (frac[o] > frac[m] || (frac[o] == frac[m] && o < m)) ++rank;
+          add[m] = rank < spare ? 1 : 0;
+        }
+        long long surplus = 0;
+        for (int m = 0; m < M; ++m) {
+          bm[m] += add[m];
+          if (bm[m] > nm[m]) { surplus += bm[m] - nm[m]; bm[m] = nm[m]; }
+        }
+        for (int r = 0; r < M; ++r) {                 // r-th largest share takes what it has room for
+          for (int m = 0; m < M; ++m) {
+            int rank = 0;
+            for (int o = 0; o < M; ++o) if (share[o] > share[m] || (share[o] == share[m] && o < m)) ++rank;
+            if (rank == r) {
+              const long long room = nm[m] - bm[m];
+              const long long give = surplus < room ? surplus : room;
+              bm[m] += give; surplus -= give;
+            }
+          }
+        }
+      }
+      for (int m = 0; m < M; ++m) a.budgets[idx * M + m] = (int32_t)bm[m];
     }
   }
   if (lane == 0 && !a.keep_all) a.pool[b] = R;
 }
 
-hipError_t launch_allocate(const Dims& dm, const madakv_config& c, int layer0, const madakv_head_stats* stats,
+hipError_t launch_allocate(const Dims& dm, const madakv_config& c, int layer0, const void* stats,
                            const int32_t* n_mod, int32_t* budgets, long long* pool_state, hipStream_t st) {
   AllocArgs a;
+  a.M = c.n_modalities;
   a.stats = stats; a.n_mod = n_mod; a.budgets = budgets; a.pool = pool_state;
   a.n = dm.n; a.B = dm.B; a.H = dm.H; a.NL = c.n_layers; a.layer0 = layer0; a.nc = dm.nc;
   a.beta = c.budget - c.window; a.rho = c.hcc_rho; a.mpa_mode = c.mpa_mode; a.hcc_mode = c.hcc_mode;

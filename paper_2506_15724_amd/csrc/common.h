@@ -32,8 +32,8 @@ size_t decode_ws_bytes(const Dims& dm, const madakv_config& c);
 hipError_t launch_score(const Dims& dm, const madakv_config& c, const void* q_win, const void* k,
                         float* psi, void* ws, hipStream_t st);
 hipError_t launch_stats(const Dims& dm, const madakv_config& c, const float* psi, const uint8_t* mask,
-                        float* psi_pool, madakv_head_stats* stats, int32_t* n_mod, int layer0, hipStream_t st);
-hipError_t launch_allocate(const Dims& dm, const madakv_config& c, int layer0, const madakv_head_stats* stats,
+                        float* psi_pool, void* stats, int32_t* n_mod, int layer0, hipStream_t st);
+hipError_t launch_allocate(const Dims& dm, const madakv_config& c, int layer0, const void* stats,
                            const int32_t* n_mod, int32_t* budgets, long long* pool_state, hipStream_t st);
 hipError_t launch_offsets(const Dims& dm, const madakv_config& c, int layer0, const int32_t* budgets,
                           int64_t* kv_off, int32_t* kv_len, long long* cursor_state, int32_t* layer_maxlen, void* ws,

@@ -79,6 +79,7 @@ int32_t validate(const madakv_config& c) {
   const int M = c.n_q_heads / c.n_kv_heads * c.window;
   if (M > 256) return MADAKV_ERR_BAD_SHAPE;
   if (c.dtype == MADAKV_FP32 && (long long)M * c.head_dim > 12288) return MADAKV_ERR_BAD_SHAPE;   // Q tile of the FMA path must fit LDS
+  if (c.n_modalities < 2 || c.n_modalities > 4) return MADAKV_ERR_BAD_SHAPE;
   if (c.pool_k < 1 || c.pool_k > 63 || (c.pool_k & 1) == 0) return MADAKV_ERR_BAD_SHAPE;
   if (c.budget < 1 || (c.budget < c.ctx_len && c.budget <= c.window)) return MADAKV_ERR_BAD_BUDGET;
   if (c.hcc_rho < 1 || c.hcc_rho > 1024) return MADAKV_ERR_INVALID_ARG;
@@ -178,7 +179,7 @@ int32_t madakv_compact_capacity_tokens(const madakv_handle* h, int64_t* tokens) 
 
 int32_t madakv_score(madakv_handle* h, int32_t layer0, int32_t n,
                      const void* q_win, const void* k, const uint8_t* mask,
-                     float* psi, float* psi_pool, madakv_head_stats* stats, int32_t* n_mod,
+                     float* psi, float* psi_pool, void* stats, int32_t* n_mod,
                      void* ws, size_t ws_bytes, void* stream) {
   int32_t r = check_range(h, layer0, n);
   if (r != MADAKV_OK) return r;
@@ -209,7 +210,8 @@ int32_t madakv_score(madakv_handle* h, int32_t layer0, int32_t n,
       ss = h->side;
     }
     if (e == hipSuccess)
-      e = launch_stats(dg, c, psi_g, mask, pool_g, stats + lb * c.n_kv_heads, g0 == 0 ? n_mod : nullptr, layer0 + g0, ss);
+      e = launch_stats(dg, c, psi_g, mask, pool_g, static_cast<char*>(stats) + lb * c.n_kv_heads * 8 * (size_t)c.n_modalities,
+                       g0 == 0 ? n_mod : nullptr, layer0 + g0, ss);
   }
   if (overlap && e == hipSuccess) {
     e = hipEventRecord(h->ev_join, h->side);
@@ -219,7 +221,7 @@ int32_t madakv_score(madakv_handle* h, int32_t layer0, int32_t n,
 }
 
 int32_t madakv_allocate(madakv_handle* h, int32_t layer0, int32_t n,
-                        const madakv_head_stats* stats, const int32_t* n_mod,
+                        const void* stats, const int32_t* n_mod,
                         int32_t* budgets, void* stream) {
   int32_t r = check_range(h, layer0, n);
   if (r != MADAKV_OK) return r;

@@ -21,11 +21,12 @@ namespace madakv {
 
 constexpr int SEL_THREADS = 512;
 constexpr int SEL_BINS = 2048;
+
 constexpr int SEL_EPT = 32;                      // consecutive candidates a thread owns per chunk
 
 struct OffsetsArgs {
   const int32_t* budgets; int64_t* kv_off; int32_t* kv_len; long long* cursor; int32_t* blk2head; long long* call_range; int32_t* layer_maxlen;
-  int n, B, H, L, W, layer0, max_new, keep_all, blocks_per_batch;
+  int n, B, H, L, W, layer0, max_new, keep_all, blocks_per_batch, M;
   long long region_tokens;
 };
 
@@ -56,7 +57,10 @@ __global__ __launch_bounds__(OFF_THREADS) void offsets_kernel(OffsetsArgs a) {
     const int li = act ? f / a.H : 0, h = act ? f % a.H : 0;
     const long long idx = ((long long)li * a.B + b) * a.H + h;
     long long len = 0;
-    if (act) len = a.keep_all ? a.L : (long long)a.budgets[idx * 2] + a.budgets[idx * 2 + 1] + a.W;
+    if (act) {
+      len = a.keep_all ? a.L : a.W;
+      if (!a.keep_all) for (int m = 0; m < a.M; ++m) len += a.budgets[idx * a.M + m];
+    }
     long long seg = act ? len + a.max_new : 0;
     long long incl = seg;
     for (int o = 1; o < 64; o <<= 1) {
@@ -109,7 +113,7 @@ __global__ __launch_bounds__(OFF_THREADS) void offsets_kernel(OffsetsArgs a) {
 
 struct SelectArgs {
   const float* psi_pool; const uint8_t* mask; const int32_t* budgets; const int64_t* kv_off; const int32_t* kv_len; int32_t* kept_idx;
-  int B, H, L, W, nc, mpa_mode, keep_all, select_mode, sink_tokens;
+  int B, H, L, W, nc, mpa_mode, keep_all, select_mode, sink_tokens, M;
 };
 
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
@@ -138,9 +142,39 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* wave_t
   return before + incl - v;
 }
 
+// the same for four 16-bit counts packed in 64 bits (one count per modality)
+__device__ __forceinline__ unsigned long long block_excl_scan64(unsigned long long v, unsigned long long* wave_tot,
+                                                                unsigned long long& total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  unsigned long long incl = v;
+  for (int o = 1; o < 64; o <<= 1) {
+    unsigned long long t = (unsigned long long)shfl_i64((long long)incl, max(lane - o, 0));
+    if (lane >= o) incl += t;
+  }
+  if (lane == 63) wave_tot[wave] = incl;
+  __syncthreads();
+  unsigned long long before = 0, tot = 0;
+  for (int w = 0; w < SEL_THREADS / 64; ++w) {
+    unsigned long long t = wave_tot[w];
+    if (w < wave) before += t;
+    tot += t;
+  }
+  __syncthreads();
+  total = tot;
+  return before + incl - v;
+}
+
+template <typename T, int N>
+__device__ __forceinline__ T pick(const T (&x)[N], int m) {              // x[m] without indexing registers by m
+  T r = x[0];
+#pragma unroll
+  for (int j = 1; j < N; ++j) r = (m == j) ? x[j] : r;
+  return r;
+}
+
 // Thread t of the workgroup owns SEL_EPT consecutive candidates of a chunk: their keys and
 // modality bits live in registers through the three radix levels and the compaction.
-__device__ __forceinline__ void load_owned(const float* sc, const uint8_t* mask, int i0, int nc, int use_mask,
+__device__ __forceinline__ void load_owned(const float* sc, const uint8_t* mask, int i0, int nc, int use_mask, int M,
                                            uint32_t (&key)[SEL_EPT], unsigned long long& mbits) {
   const bool full = i0 + SEL_EPT <= nc;
   if (full && ((reinterpret_cast<uintptr_t>(sc + i0) & 15u) == 0)) {
@@ -154,7 +188,8 @@ __device__ __forceinline__ void load_owned(const float* sc, const uint8_t* mask,
 #pragma unroll
     for (int e = 0; e < SEL_EPT; ++e) key[e] = (i0 + e < nc) ? float_key(sc[i0 + e]) : 0u;
   }
-  mbits = 0ULL;
+  mbits = 0ULL;                                   // modality ids, two bits per element
+  const uint32_t top = (uint32_t)(M - 1);
   if (use_mask) {
     if (full && ((reinterpret_cast<uintptr_t>(mask + i0) & 15u) == 0)) {
 #pragma unroll
@@ -164,20 +199,23 @@ __device__ __forceinline__ void load_owned(const float* sc, const uint8_t* mask,
         for (int q = 0; q < 4; ++q)
 #pragma unroll
           for (int bb = 0; bb < 4; ++bb)
-            if ((w[q] >> (8 * bb)) & 0xffu) mbits |= 1ULL << (j * 16 + q * 4 + bb);
+            mbits |= (unsigned long long)min((w[q] >> (8 * bb)) & 0xffu, top) << (2 * (j * 16 + q * 4 + bb));
       }
     } else {
 #pragma unroll
       for (int e = 0; e < SEL_EPT; ++e)
-        if (i0 + e < nc && mask[i0 + e]) mbits |= 1ULL << e;
+        if (i0 + e < nc) mbits |= (unsigned long long)min((uint32_t)mask[i0 + e], top) << (2 * e);
     }
   }
 }
 
-__global__ __launch_bounds__(SEL_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4))) void select_kernel(SelectArgs a) {
-  __shared__ uint32_t cnt[2][SEL_BINS];
-  __shared__ uint32_t s_prefix[2], s_need[2], s_done[2];
+template <int MM>   // modalities the kernel is built for (2: the paper's text / image; 4: up to four)
+__global__ __launch_bounds__(SEL_THREADS) __attribute__((amdgpu_waves_per_eu(MM == 2 ? 4 : 2, 4))) void select_kernel(SelectArgs a) {
+  __shared__ uint32_t cnt[MM][SEL_BINS];
+  __shared__ uint32_t s_prefix[MM], s_need[MM], s_done[MM];
   __shared__ uint32_t wave_tot[SEL_THREADS / 64];
+  __shared__ unsigned long long wave_tot64[SEL_THREADS / 64];
+  const int M = a.M;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int head = blockIdx.x;
@@ -191,10 +229,15 @@ __global__ __launch_bounds__(SEL_THREADS) __attribute__((amdgpu_waves_per_eu(4, 
     for (int i = tid; i < a.L; i += SEL_THREADS) out[i] = i;
     return;
   }
-  const uint32_t bud[2] = {(uint32_t)a.budgets[head * 2], (uint32_t)a.budgets[head * 2 + 1]};
+  uint32_t bud[MM];
+#pragma unroll
+  for (int m = 0; m < MM; ++m) bud[m] = m < M ? (uint32_t)a.budgets[(long long)head * M + m] : 0u;
   if (a.select_mode == 1) {
     // score-free baseline: the first `sink` candidates and the most recent ones, then the window
-    const int total = min((int)(bud[0] + bud[1]), a.nc);
+    uint32_t btot = 0;
+#pragma unroll
+    for (int m = 0; m < MM; ++m) btot += bud[m];
+    const int total = min((int)btot, a.nc);
     const int sink = min(a.sink_tokens, total);
     for (int j = tid; j < total + a.W; j += SEL_THREADS)
       out[j] = j < sink ? j : (j < total ? a.nc - (total - j) : a.nc + (j - total));
@@ -208,29 +251,33 @@ __global__ __launch_bounds__(SEL_THREADS) __attribute__((amdgpu_waves_per_eu(4, 
 
   uint32_t key[SEL_EPT];
   unsigned long long mbits = 0ULL;
-  if (single) load_owned(sc, mask, tid * SEL_EPT, a.nc, a.mpa_mode, key, mbits);
+  if (single) load_owned(sc, mask, tid * SEL_EPT, a.nc, a.mpa_mode, M, key, mbits);
 
   for (int level = 0; level < 3; ++level) {
-    for (int e = tid; e < 2 * SEL_BINS; e += SEL_THREADS) (&cnt[0][0])[e] = 0;
+    for (int e = tid; e < M * SEL_BINS; e += SEL_THREADS) (&cnt[0][0])[e] = 0;
     __syncthreads();
     const int sh = shifts[level], wd = widths[level];
     const uint32_t binmask = (1u << wd) - 1u;
-    uint32_t pfx[2] = {0, 0}; bool dn[2] = {false, false};
-    if (level > 0) { pfx[0] = s_prefix[0]; pfx[1] = s_prefix[1]; dn[0] = s_done[0] != 0; dn[1] = s_done[1] != 0; }
+    uint32_t pfx[MM]; bool dn[MM];
+#pragma unroll
+    for (int m = 0; m < MM; ++m) {
+      pfx[m] = (level > 0 && m < M) ? s_prefix[m] : 0u;
+      dn[m] = (level > 0 && m < M) ? s_done[m] != 0 : false;
+    }
     for (int c = 0; c < nchunks; ++c) {
       const int i0 = c * CH + tid * SEL_EPT;
-      if (!single) load_owned(sc, mask, i0, a.nc, a.mpa_mode, key, mbits);
+      if (!single) load_owned(sc, mask, i0, a.nc, a.mpa_mode, M, key, mbits);
       const int nvalid = min(max(a.nc - i0, 0), SEL_EPT);
 #pragma unroll
       for (int e = 0; e < SEL_EPT; ++e) {
-        const int m = (int)((mbits >> e) & 1ULL);
+        const int m = (int)((mbits >> (2 * e)) & 3ULL);
         bool match = e < nvalid;
-        if (level > 0) match = match && !dn[m] && ((key[e] >> (sh + wd)) == pfx[m]);
+        if (level > 0) match = match && !pick(dn, m) && ((key[e] >> (sh + wd)) == pick(pfx, m));
         if (match) atomicAdd(&cnt[m][(key[e] >> sh) & binmask], 1u);
       }
     }
     __syncthreads();
-    if (wave < 2) {
+    if (wave < M) {
       const int m = wave;
       const int nb = 1 << wd;
       const int per = (nb + 63) / 64;
@@ -244,7 +291,8 @@ __global__ __launch_bounds__(SEL_THREADS) __attribute__((amdgpu_waves_per_eu(4, 
       uint32_t need, prefix_prev; bool done;
       if (level == 0) {
         const uint32_t ntot = (uint32_t)__shfl((int)incl, 63, 64);
-        need = bud[m] < ntot ? bud[m] : ntot;     // a budget above the candidate count keeps them all
+        const uint32_t bm = pick(bud, m);
+        need = bm < ntot ? bm : ntot;              // a budget above the candidate count keeps them all
         done = (need == 0);
         prefix_prev = 0;
         if (lane == 0) { s_need[m] = need; s_done[m] = done ? 1u : 0u; s_prefix[m] = 0; }
@@ -271,45 +319,50 @@ __global__ __launch_bounds__(SEL_THREADS) __attribute__((amdgpu_waves_per_eu(4, 
     __syncthreads();
   }
   // tau_m = s_prefix (full key); take every key > tau_m and the first s_need[m] keys == tau_m.
-  uint32_t tau[2], ties[2];
-  for (int m = 0; m < 2; ++m) {
-    if (s_done[m]) { tau[m] = 0xffffffffu; ties[m] = 0; }   // nothing to keep: no key exceeds or (needed) equals it
+  uint32_t tau[MM], ties[MM];
+#pragma unroll
+  for (int m = 0; m < MM; ++m) {
+    if (m >= M || s_done[m]) { tau[m] = 0xffffffffu; ties[m] = 0; }   // nothing to keep: no key exceeds or (needed) equals it
     else { tau[m] = s_prefix[m]; ties[m] = s_need[m]; }
   }
   __syncthreads();
 
-  uint32_t run_eq[2] = {0, 0};
+  uint32_t run_eq[MM];
+#pragma unroll
+  for (int m = 0; m < MM; ++m) run_eq[m] = 0;
   uint32_t run_out = 0;
   for (int c = 0; c < nchunks; ++c) {
     const int i0 = c * CH + tid * SEL_EPT;
-    if (!single) load_owned(sc, mask, i0, a.nc, a.mpa_mode, key, mbits);
+    if (!single) load_owned(sc, mask, i0, a.nc, a.mpa_mode, M, key, mbits);
     const int nvalid = min(max(a.nc - i0, 0), SEL_EPT);
-    // ties of this thread's stretch, per modality, then their rank by position over the workgroup
-    unsigned long long eqbits = 0ULL, gtbits = 0ULL;
-    uint32_t eq_t = 0, eq_v = 0;
+    // ties of this thread's stretch, per modality (four 16-bit counts), then their rank by
+    // position over the workgroup
+    unsigned long long eqbits = 0ULL, gtbits = 0ULL, eqcnt = 0ULL;
 #pragma unroll
     for (int e = 0; e < SEL_EPT; ++e) {
-      const int m = (int)((mbits >> e) & 1ULL);
+      const int m = (int)((mbits >> (2 * e)) & 3ULL);
       const bool ok = e < nvalid;
-      const bool gt = ok && key[e] > tau[m];
-      const bool eq = ok && key[e] == tau[m] && ties[m] > 0;
+      const uint32_t tm = pick(tau, m);
+      const bool gt = ok && key[e] > tm;
+      const bool eq = ok && key[e] == tm && pick(ties, m) > 0;
       gtbits |= (unsigned long long)gt << e;
       eqbits |= (unsigned long long)eq << e;
-      eq_t += (eq && m == 0) ? 1u : 0u;
-      eq_v += (eq && m == 1) ? 1u : 0u;
+      eqcnt += (unsigned long long)eq << (16 * m);
     }
-    uint32_t t_tot, v_tot;
-    uint32_t rank_t = run_eq[0] + block_excl_scan(eq_t, wave_tot, t_tot);
-    uint32_t rank_v = run_eq[1] + block_excl_scan(eq_v, wave_tot, v_tot);
+    unsigned long long eqtot;
+    const unsigned long long eqbefore = block_excl_scan64(eqcnt, wave_tot64, eqtot);
+    uint32_t rank[MM];
+#pragma unroll
+    for (int m = 0; m < MM; ++m) rank[m] = run_eq[m] + (uint32_t)((eqbefore >> (16 * m)) & 0xffffULL);
     unsigned long long keepbits = gtbits;
     if (eqbits) {
 #pragma unroll
       for (int e = 0; e < SEL_EPT; ++e) {
         if ((eqbits >> e) & 1ULL) {
-          const int m = (int)((mbits >> e) & 1ULL);
-          uint32_t& rk = m ? rank_v : rank_t;
-          if (rk < ties[m]) keepbits |= 1ULL << e;
-          ++rk;
+          const int m = (int)((mbits >> (2 * e)) & 3ULL);
+          if (pick(rank, m) < pick(ties, m)) keepbits |= 1ULL << e;
+#pragma unroll
+          for (int mm = 0; mm < MM; ++mm) rank[mm] += (mm == m) ? 1u : 0u;
         }
       }
     }
@@ -320,7 +373,8 @@ __global__ __launch_bounds__(SEL_THREADS) __attribute__((amdgpu_waves_per_eu(4, 
       out[pos++] = i0 + e;
       keepbits &= keepbits - 1ULL;
     }
-    run_eq[0] += t_tot; run_eq[1] += v_tot;
+#pragma unroll
+    for (int m = 0; m < MM; ++m) run_eq[m] += (uint32_t)((eqtot >> (16 * m)) & 0xffffULL);
     run_out += ktot;
   }
   for (int r = tid; r < a.W; r += SEL_THREADS) out[run_out + r] = a.nc + r;
@@ -343,7 +397,7 @@ hipError_t launch_offsets(const Dims& dm, const madakv_config& c, int layer0, co
   a.budgets = budgets; a.kv_off = kv_off; a.kv_len = kv_len; a.cursor = cursor_state;
   a.call_range = reinterpret_cast<long long*>(ws);
   a.blk2head = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(ws) + ((size_t)dm.B * 2 * sizeof(long long) + 63) / 64 * 64);
-  a.n = dm.n; a.B = dm.B; a.H = dm.H; a.L = dm.L; a.W = dm.W; a.layer0 = layer0;
+  a.n = dm.n; a.B = dm.B; a.H = dm.H; a.L = dm.L; a.W = dm.W; a.layer0 = layer0; a.M = c.n_modalities;
   a.max_new = c.max_new_tokens; a.keep_all = c.budget >= c.ctx_len ? 1 : 0;
   a.blocks_per_batch = blocks_per_batch; a.region_tokens = region_tokens;
   hipLaunchKernelGGL(offsets_kernel, dim3(dm.B), dim3(OFF_THREADS), 0, st, a);
@@ -357,8 +411,9 @@ hipError_t launch_select(const Dims& dm, const madakv_config& c, const float* ps
   a.psi_pool = psi_pool; a.mask = mask; a.budgets = budgets; a.kv_off = kv_off; a.kv_len = kv_len; a.kept_idx = kept_idx;
   a.B = dm.B; a.H = dm.H; a.L = dm.L; a.W = dm.W; a.nc = dm.nc; a.mpa_mode = c.mpa_mode;
   a.keep_all = c.budget >= c.ctx_len ? 1 : 0;
-  a.select_mode = c.select_mode; a.sink_tokens = c.sink_tokens;
-  hipLaunchKernelGGL(select_kernel, dim3(dm.heads), dim3(SEL_THREADS), 0, st, a);
+  a.select_mode = c.select_mode; a.sink_tokens = c.sink_tokens; a.M = c.n_modalities;
+  if (a.M == 2) hipLaunchKernelGGL((select_kernel<2>), dim3(dm.heads), dim3(SEL_THREADS), 0, st, a);
+  else hipLaunchKernelGGL((select_kernel<4>), dim3(dm.heads), dim3(SEL_THREADS), 0, st, a);
   return hipGetLastError();
 }
 

@@ -25,8 +25,8 @@ constexpr float FX_SCALE = 17592186044416.0f;    // 2^44
 constexpr float PSI_MAX = 256.0f;                // G * W <= 256 bounds any column sum
 
 struct StatsArgs {
-  const float* psi; const uint8_t* mask; float* psi_pool; madakv_head_stats* stats; int32_t* n_mod;
-  int B, H, L, W, nc, pool_r, layer0, mpa_mode, pool_mode, share_mode;
+  const float* psi; const uint8_t* mask; float* psi_pool; void* stats; int32_t* n_mod;
+  int B, H, L, W, nc, pool_r, layer0, mpa_mode, pool_mode, share_mode, M;
   double theta;
 };
 
@@ -44,8 +44,8 @@ typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
 
 // Thread t owns STATS_EPT consecutive candidates of a chunk; values and modality bits stay in
 // registers through the three levels when the head fits one chunk (16384 candidates).
-__device__ __forceinline__ void load_owned(const float* psi, const uint8_t* mask, int i0, int nc,
-                                           float (&v)[STATS_EPT], uint32_t& mbits) {
+__device__ __forceinline__ void load_owned(const float* psi, const uint8_t* mask, int i0, int nc, int M,
+                                           float (&v)[STATS_EPT], unsigned long long& mbits) {
   const bool full = i0 + STATS_EPT <= nc;
   if (full && ((reinterpret_cast<uintptr_t>(psi + i0) & 15u) == 0)) {
 #pragma unroll
@@ -57,7 +57,9 @@ __device__ __forceinline__ void load_owned(const float* psi, const uint8_t* mask
 #pragma unroll
     for (int e = 0; e < STATS_EPT; ++e) v[e] = (i0 + e < nc) ? psi[i0 + e] : 0.f;
   }
-  mbits = 0u;
+  // modality ids, two bits per element (ids above the last modality count as the last one)
+  mbits = 0ULL;
+  const uint32_t top = (uint32_t)(M - 1);
   if (full && ((reinterpret_cast<uintptr_t>(mask + i0) & 15u) == 0)) {
 #pragma unroll
     for (int j = 0; j < STATS_EPT / 16; ++j) {
@@ -66,12 +68,12 @@ __device__ __forceinline__ void load_owned(const float* psi, const uint8_t* mask
       for (int q = 0; q < 4; ++q)
 #pragma unroll
         for (int bb = 0; bb < 4; ++bb)
-          if ((w[q] >> (8 * bb)) & 0xffu) mbits |= 1u << (j * 16 + q * 4 + bb);
+          mbits |= (unsigned long long)min((w[q] >> (8 * bb)) & 0xffu, top) << (2 * (j * 16 + q * 4 + bb));
     }
   } else {
 #pragma unroll
     for (int e = 0; e < STATS_EPT; ++e)
-      if (i0 + e < nc && mask[i0 + e]) mbits |= 1u << e;
+      if (i0 + e < nc) mbits |= (unsigned long long)min((uint32_t)mask[i0 + e], top) << (2 * e);
   }
 }
 
@@ -118,11 +120,14 @@ __device__ __forceinline__ void pool_owned(const float* psi, float* pool, int i0
   }
 }
 
+template <int MM>   // modalities the kernel is built for (2 or 4)
 __global__ __launch_bounds__(STATS_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4))) void stats_kernel(StatsArgs a) {
-  __shared__ uint32_t cnt[2][BINS];
-  __shared__ unsigned long long sum[2][BINS];
-  __shared__ uint32_t s_prefix[2], s_cnt_gt[2], s_n[2], s_done[2], s_bincnt[2];
-  __shared__ unsigned long long s_sum_gt[2], s_w[2], s_target[2], s_binsum[2], s_wwin[2];
+  extern __shared__ __attribute__((aligned(16))) unsigned char stats_smem[];
+  unsigned long long* sum = reinterpret_cast<unsigned long long*>(stats_smem);      // [M][BINS] masses
+  uint32_t* cnt = reinterpret_cast<uint32_t*>(sum + (size_t)a.M * BINS);             // [M][BINS] counts
+  __shared__ uint32_t s_prefix[MM], s_cnt_gt[MM], s_n[MM], s_done[MM], s_bincnt[MM];
+  __shared__ unsigned long long s_sum_gt[MM], s_w[MM], s_target[MM], s_binsum[MM], s_wwin[MM];
+  const int M = a.M;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int head = blockIdx.x;
@@ -137,27 +142,28 @@ __global__ __launch_bounds__(STATS_THREADS) __attribute__((amdgpu_waves_per_eu(4
   const int nchunks = (a.nc + CH - 1) / CH;
   const bool single = nchunks == 1;
 
-  if (tid < 2) s_wwin[tid] = 0ULL;
+  if (tid < MM) s_wwin[tid] = 0ULL;
   __syncthreads();
   if (a.share_mode && tid < a.W) {
     // the other reading of Eq. 6: the proxy columns count towards the masses as well
     const int i = a.nc + tid;
-    atomicAdd(&s_wwin[mask[i] ? 1 : 0], to_fx(psi[i]));
+    atomicAdd(&s_wwin[min((int)mask[i], M - 1)], to_fx(psi[i]));
   }
   float v[STATS_EPT];
-  uint32_t mbits = 0u;
-  if (single) load_owned(psi, mask, tid * STATS_EPT, a.nc, v, mbits);
+  unsigned long long mbits = 0ULL;
+  if (single) load_owned(psi, mask, tid * STATS_EPT, a.nc, M, v, mbits);
 
   for (int level = 0; level < 3; ++level) {
-    for (int e = tid; e < 2 * BINS; e += STATS_THREADS) { (&cnt[0][0])[e] = 0; (&sum[0][0])[e] = 0ULL; }
+    for (int e = tid; e < M * BINS; e += STATS_THREADS) { cnt[e] = 0; sum[e] = 0ULL; }
     __syncthreads();
     const int sh = shifts[level], wd = widths[level];
     const uint32_t binmask = (1u << wd) - 1u;
-    uint32_t pfx[2] = {0, 0}; bool dn[2] = {false, false};
-    if (level > 0) { pfx[0] = s_prefix[0]; pfx[1] = s_prefix[1]; dn[0] = s_done[0] != 0; dn[1] = s_done[1] != 0; }
+    uint32_t pfx[MM]; bool dn[MM];
+#pragma unroll
+    for (int m = 0; m < MM; ++m) { pfx[m] = (level > 0 && m < M) ? s_prefix[m] : 0u; dn[m] = (level > 0 && m < M) ? s_done[m] != 0 : false; }
     for (int c = 0; c < nchunks; ++c) {
       const int i0 = c * CH + tid * STATS_EPT;
-      if (!single) load_owned(psi, mask, i0, a.nc, v, mbits);
+      if (!single) load_owned(psi, mask, i0, a.nc, M, v, mbits);
       const int nvalid = min(max(a.nc - i0, 0), STATS_EPT);
       if (level == 0 && nvalid > 0) {
         // pooled score for ranking (raw values); widths up to 7 from registers, wider ones the slow way
@@ -181,27 +187,31 @@ __global__ __launch_bounds__(STATS_THREADS) __attribute__((amdgpu_waves_per_eu(4
       }
 #pragma unroll
       for (int e = 0; e < STATS_EPT; ++e) {
-        const int m = (int)((mbits >> e) & 1u);
+        const int m = (int)((mbits >> (2 * e)) & 3ULL);
         const uint32_t key = nonneg_bits(v[e]);
         bool match = e < nvalid;
-        if (level > 0) match = match && !dn[m] && ((key >> (sh + wd)) == pfx[m]);
+        // (the per-modality state is picked with selects: indexing a register array by m would spill it)
+        uint32_t pm = pfx[0]; bool dm_ = dn[0];
+#pragma unroll
+        for (int j = 1; j < MM; ++j) { pm = (m == j) ? pfx[j] : pm; dm_ = (m == j) ? dn[j] : dm_; }
+        if (level > 0) match = match && !dm_ && ((key >> (sh + wd)) == pm);
         if (match) {
           const uint32_t bin = (key >> sh) & binmask;
-          atomicAdd(&cnt[m][bin], 1u);
-          atomicAdd(&sum[m][bin], to_fx(v[e]));
+          atomicAdd(&cnt[m * BINS + bin], 1u);
+          atomicAdd(&sum[m * BINS + bin], to_fx(v[e]));
         }
       }
     }
     __syncthreads();
-    // wave m (0 = text, 1 = image) walks its histogram from the top bin down
-    if (wave < 2) {
+    // wave m walks the histogram of modality m from the top bin down
+    if (wave < M) {
       const int m = wave;
       const int nb = 1 << wd;
       const int per = (nb + 63) / 64;                 // bins per lane; lane 0 owns the top bins
       unsigned long long ls = 0ULL; uint32_t lc = 0;
       for (int j = 0; j < per; ++j) {
         int bin = nb - 1 - (lane * per + j);
-        if (bin >= 0) { ls += sum[m][bin]; lc += cnt[m][bin]; }
+        if (bin >= 0) { ls += sum[m * BINS + bin]; lc += cnt[m * BINS + bin]; }
       }
       // inclusive scan over lanes (lane 0 first)
       unsigned long long ss = ls; uint32_t sc = lc;
@@ -237,21 +247,21 @@ __global__ __launch_bounds__(STATS_THREADS) __attribute__((amdgpu_waves_per_eu(4
         for (int j = 0; j < per; ++j) {
           int bin = nb - 1 - (lane * per + j);
           if (bin < 0) break;
-          unsigned long long bs = sum[m][bin];
+          unsigned long long bs = sum[m * BINS + bin];
           if (acc_s + bs >= target) {
             s_prefix[m] = (prefix_prev << wd) | (uint32_t)bin;
             s_sum_gt[m] = acc_s; s_cnt_gt[m] = acc_c;
-            s_binsum[m] = bs; s_bincnt[m] = cnt[m][bin];
+            s_binsum[m] = bs; s_bincnt[m] = cnt[m * BINS + bin];
             break;
           }
-          acc_s += bs; acc_c += cnt[m][bin];
+          acc_s += bs; acc_c += cnt[m * BINS + bin];
         }
       }
     }
     __syncthreads();
   }
 
-  if (tid < 2) {
+  if (tid < M) {
     const int m = tid;
     int32_t k = 0;
     if (!s_done[m]) {
@@ -265,19 +275,30 @@ __global__ __launch_bounds__(STATS_THREADS) __attribute__((amdgpu_waves_per_eu(4
       k = (int32_t)(s_cnt_gt[m] + (uint32_t)t);
     }
     const float w = (float)((double)(s_w[m] + s_wwin[m]) * (1.0 / (double)FX_SCALE));
-    madakv_head_stats* st = a.stats + head;
-    if (m == 0) { st->w_t = w; st->k_t = k; } else { st->w_v = w; st->k_v = k; }
-    if (head < a.B * a.H && (head % a.H) == 0 && a.n_mod) a.n_mod[b * 2 + m] = (int32_t)s_n[m];
+    // a head's record: M float masses, then M int32 counts (two modalities: madakv_head_stats)
+    float* rec = reinterpret_cast<float*>(a.stats) + (long long)head * 2 * M;
+    rec[m] = w;
+    reinterpret_cast<int32_t*>(rec)[M + m] = k;
+    if (head < a.B * a.H && (head % a.H) == 0 && a.n_mod) a.n_mod[b * M + m] = (int32_t)s_n[m];
   }
 }
 
 hipError_t launch_stats(const Dims& dm, const madakv_config& c, const float* psi, const uint8_t* mask,
-                        float* psi_pool, madakv_head_stats* stats, int32_t* n_mod, int layer0, hipStream_t st) {
+                        float* psi_pool, void* stats, int32_t* n_mod, int layer0, hipStream_t st) {
   StatsArgs a;
   a.psi = psi; a.mask = mask; a.psi_pool = psi_pool; a.stats = stats; a.n_mod = n_mod;
   a.B = dm.B; a.H = dm.H; a.L = dm.L; a.W = dm.W; a.nc = dm.nc; a.pool_r = (c.pool_k - 1) / 2;
   a.layer0 = layer0; a.mpa_mode = c.mpa_mode; a.pool_mode = c.pool_mode; a.share_mode = c.share_mode; a.theta = (double)c.theta;
-  hipLaunchKernelGGL(stats_kernel, dim3(dm.heads), dim3(STATS_THREADS), 0, st, a);
+  a.M = c.n_modalities;
+  const size_t lds = (size_t)a.M * BINS * (sizeof(unsigned long long) + sizeof(uint32_t));
+  if (a.M == 2) {
+    if (lds > 48 * 1024)
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&stats_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipLaunchKernelGGL((stats_kernel<2>), dim3(dm.heads), dim3(STATS_THREADS), lds, st, a);
+  } else {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&stats_kernel<4>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipLaunchKernelGGL((stats_kernel<4>), dim3(dm.heads), dim3(STATS_THREADS), lds, st, a);
+  }
   return hipGetLastError();
 }
 

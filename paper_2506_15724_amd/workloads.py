@@ -44,6 +44,7 @@ class Workload:
     bimodal_pref: bool
     fixed_layout: tuple = ()   # explicit (modality, length) runs
     cfg_id: int = 0
+    n_modalities: int = 2      # > 2: the non-text runs cycle through modality ids 1 .. M-1
 
     @property
     def torch_dtype(self):
@@ -129,7 +130,7 @@ def modality_mask(wl: Workload, b: int) -> np.ndarray:
     parts = []
     for j in range(len(img)):
         parts.append(np.zeros(int(text[j]), np.uint8))
-        parts.append(np.ones(int(img[j]), np.uint8))
+        parts.append(np.full(int(img[j]), 1 + j % (wl.n_modalities - 1), np.uint8))
     parts.append(np.zeros(int(text[len(img)]), np.uint8))
     mask = np.concatenate(parts)
     assert mask.shape[0] == L and (mask[L - wl.window:] == 0).all()
@@ -163,6 +164,17 @@ def head_preferences(wl: Workload, l: int, b: int, device="cpu"):
     return p.to(device), u.to(device)
 
 
+def modality_coefficients(wl: Workload, l: int, b: int, device="cpu"):
+    """coef[H, M]: how strongly the keys of each modality carry the head's bias direction.
+    Two modalities: (2 p_h, 2 (1 - p_h)).  More: M times a seeded point of the simplex."""
+    p, _ = head_preferences(wl, l, b, device)
+    if wl.n_modalities == 2:
+        return torch.stack([2.0 * p, 2.0 * (1.0 - p)], dim=1)
+    g = _torch_gen(wl, "cpu", 6, l, b)
+    e = -torch.log(torch.rand(wl.n_kv_heads, wl.n_modalities, generator=g).clamp_min(1e-6))
+    return (wl.n_modalities * e / e.sum(dim=1, keepdim=True)).to(device)
+
+
 def layer_inputs(wl: Workload, l: int, b: int, mask: np.ndarray, device="cpu"):
     """(q_win[Hq,W,d], k[H,L,d], v[H,L,d]) of one layer of one batch item, in wl's dtype.
     K,V,Q ~ N(0,1); the head bias u_h is added to the window queries, and to the keys
@@ -172,8 +184,12 @@ def layer_inputs(wl: Workload, l: int, b: int, mask: np.ndarray, device="cpu"):
     G = Hq // H
     g = _torch_gen(wl, device, 3, l, b)
     p, u = head_preferences(wl, l, b, device)
-    m = torch.from_numpy(mask.astype(np.float32)).to(device)                 # 1 on image
-    coef = 2.0 * (p[:, None] * (1.0 - m)[None, :] + (1.0 - p)[:, None] * m[None, :])   # [H, L]
+    if wl.n_modalities == 2:
+        m = torch.from_numpy(mask.astype(np.float32)).to(device)             # 1 on image
+        coef = 2.0 * (p[:, None] * (1.0 - m)[None, :] + (1.0 - p)[:, None] * m[None, :])   # [H, L]
+    else:
+        table = modality_coefficients(wl, l, b, device)                      # [H, M]
+        coef = table[:, torch.from_numpy(mask.astype(np.int64)).to(device)]  # [H, L]
     k = torch.randn(H, L, d, generator=g, device=device)
     k += coef[:, :, None] * u[:, None, :]
     if wl.heavy_hitters > 0:

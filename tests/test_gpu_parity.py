@@ -487,3 +487,74 @@ def test_alternative_readings_and_baselines(variant):
         tot = bud_g.sum(-1)
         assert ((tot.max(-1) - tot.min(-1)) <= 1).all()
     eng.close()
+
+
+@pytest.mark.parametrize("M,mpa", [(3, 1), (4, 1), (3, 2), (3, 0), (4, 3)])
+def test_more_than_two_modalities(M, mpa):
+    """Eq. 6, 8, 9 and the selection with M modalities, stage by stage against the oracle."""
+    wl = small_workloads()["bf16_mha"].scaled(name=f"bf16_m{M}", n_images=5, ctx_len=4100, budget=500, n_modalities=M)
+    NL, B, H, L, W = wl.n_layers, wl.batch, wl.n_kv_heads, wl.ctx_len, wl.window
+    nc = L - W
+    p = PU.oracle_params(wl, n_modalities=M, mpa_mode=mpa)
+    q, k, v, mask, masks = PU.make_inputs(wl, DEV)
+    assert int(mask.max()) == M - 1
+    eng = engine(wl, n_modalities=M, mpa_mode=mpa)
+    say(f"{M} modalities, mpa_mode {mpa}")
+    eng.score(0, NL, q, k, mask); eng.allocate(0, NL); eng.select_gather(0, NL, k, v, mask)
+    torch.cuda.synchronize()
+    psi_g, pool_g = eng.psi.cpu().numpy(), eng.psi_pool.cpu().numpy()
+    w_g, k_g = eng.stats_host()
+    assert w_g.shape[-1] == M and k_g.shape[-1] == M
+    nmod = eng.n_mod.cpu().numpy()
+    bud_g = eng.budgets.cpu().numpy()
+    kept_all, off, ln = eng.kept_idx.cpu().numpy(), eng.kv_off.cpu().numpy(), eng.kv_len.cpu().numpy()
+    for b in range(B):
+        for l in range(NL):
+            psi_in = psi_g[l, b].astype(np.float64)
+            w_o, k_o, n_o = O.modality_stats(psi_in, masks[b], W, p.theta, 0, M)
+            assert tuple(nmod[b]) == tuple(n_o)
+            np.testing.assert_allclose(w_g[l, b], w_o, rtol=2e-6, atol=1e-30)
+            np.testing.assert_array_equal(pool_g[l, b], O.pool_scores(psi_in, W, p.pool_k).astype(np.float32))
+            for h in range(H):
+                for m in range(M):
+                    if k_g[l, b, h, m] != k_o[h, m]:
+                        assert PU.k_count_ok(int(k_g[l, b, h, m]), psi_in[h, :nc][masks[b][:nc] == m], p.theta)
+        np.testing.assert_array_equal(bud_g[:, b], O.allocate(w_g[:, b], k_g[:, b].astype(np.int64), nmod[b], p))
+        for l in range(NL):
+            for h in range(H):
+                bud = [int(x) for x in bud_g[l, b, h]]
+                assert ln[l, b, h] == sum(bud) + W
+                ref = O.select_n(pool_g[l, b, h].astype(np.float64), masks[b], bud, L, W, mpa)
+                o = off[l, b, h]
+                np.testing.assert_array_equal(kept_all[o:o + ln[l, b, h]], ref)
+                assert torch.equal(eng.k_c[o:o + len(ref)].cpu(), k[l, b, h].cpu()[ref])
+                assert torch.equal(eng.v_c[o:o + len(ref)].cpu(), v[l, b, h].cpu()[ref])
+    assert bud_g.sum() == NL * B * H * (wl.budget - W)
+    eng.close()
+
+
+def test_allocate_random_statistics_three_and_four_modalities():
+    """madakv_allocate alone on random M-way statistics (every branch of the split), vs the oracle."""
+    r = np.random.default_rng(6)
+    for trial in range(16):
+        M = 3 + trial % 2
+        NL, B, H = int(r.integers(1, 6)), int(r.integers(1, 3)), int(r.integers(1, 20))
+        W = int(r.integers(1, 9)); L = int(r.integers(W + 60, 500))
+        budget = int(r.integers(W + 1, L)); nc = L - W
+        eng = MB.MadaKV(n_layers=NL, batch=B, n_q_heads=H, n_kv_heads=H, head_dim=64, ctx_len=L, window=W,
+                        budget=budget, dtype="bf16", pool_k=1, n_modalities=M, device=DEV)
+        p = O.Params(n_layers=NL, n_q_heads=H, n_kv_heads=H, head_dim=64, ctx_len=L, window=W, budget=budget, n_modalities=M)
+        cuts = np.sort(r.integers(0, nc + 1, size=(B, M - 1)), axis=1)
+        n_mod = np.diff(np.concatenate([np.zeros((B, 1), int), cuts, np.full((B, 1), nc)], axis=1), axis=1).astype(np.int32)
+        kc = (r.random((NL, B, H, M)) ** r.choice([0.2, 1.0, 3.0]) * (n_mod[None, :, None, :] + 1)).astype(np.int64)
+        kc = np.minimum(kc, n_mod[None, :, None, :])
+        w = r.random((NL, B, H, M)).astype(np.float32)
+        w[r.random((NL, B, H)) < 0.1] = 0.0
+        w[r.random((NL, B, H, M)) < 0.15] = 0.0
+        st = stats_struct(w, kc, DEV)
+        eng.allocate(0, NL, st, torch.from_numpy(n_mod).to(DEV), eng.budgets)
+        torch.cuda.synchronize()
+        got = eng.budgets.cpu().numpy()
+        for b in range(B):
+            np.testing.assert_array_equal(got[:, b], O.allocate(w[:, b], kc[:, b], n_mod[b], p))
+        eng.close()

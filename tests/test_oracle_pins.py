@@ -497,3 +497,66 @@ def test_sink_recent_baseline():
     for l in range(NL):
         for h in range(H):
             assert list(res["kept"][l][h]) == [0, 1] + list(range(34, 48))
+
+
+# ------------------------------------------------------------------ more than two modalities (Eq. 6, 8, 9 M-way)
+def test_three_modality_split_hand_examples():
+    assert O.mpa_split_n(10, np.array([1.0, 1.0, 2.0]), [100, 100, 100]) == [3, 2, 5]      # quotas 2.5 2.5 5: the spare token to the lower id
+    assert O.mpa_split_n(10, np.array([8.0, 1.0, 1.0]), [3, 100, 100]) == [3, 6, 1]        # modality 0 short: surplus by share, ties to the lower id
+    assert O.mpa_split_n(7, np.array([0.0, 0.0, 0.0]), [10, 30, 60]) == [1, 2, 4]          # no mass: token shares .1 .3 .6 -> .7 2.1 4.2, spare to 0.7
+    assert O.mpa_split_n(10, np.array([1.0, 5.0, 1.0]), [4, 3, 100], mpa_mode=2) == [4, 3, 3]
+    assert O.mpa_split_n(10, np.array([1.0, 5.0, 1.0]), [4, 3, 100], mpa_mode=3) == [0, 0, 10]
+    assert O.mpa_split_n(9, np.array([2.0, 1.0]), [100, 100]) == list(O.mpa_split(9, 2.0, 1.0, 100, 100))
+
+
+def test_m_way_split_properties():
+    r = rng(40)
+    for _ in range(300):
+        M = int(r.integers(3, 5))
+        n = r.integers(0, 40, size=M)
+        a = int(r.integers(0, n.sum() + 1))
+        w = r.random(M) ** 2
+        if r.random() < 0.1:
+            w[:] = 0.0
+        b = O.mpa_split_n(a, w, n)
+        assert sum(b) == a and all(0 <= b[m] <= n[m] for m in range(M))
+        tot = w.sum()
+        share = w / tot if tot > 0 else n / max(1, n.sum())
+        if all(math.ceil(share[m] * a) <= n[m] for m in range(M)):      # nobody short of candidates: quota rule
+            assert all(math.floor(share[m] * a) <= b[m] <= math.ceil(share[m] * a) for m in range(M))
+
+
+def test_three_modality_stats_and_selection():
+    psi = np.array([[8.0, 1.0, 6.0, 4.0, 4.0, 1.0, 3.0, 3.0, 3.0, 99.0]])          # last column is the window
+    mask = np.array([0, 0, 2, 1, 1, 1, 2, 2, 2, 0], dtype=np.uint8)
+    w, kc, n = O.modality_stats(psi, mask, 1, 0.8, n_modalities=3)
+    assert tuple(w[0]) == (9.0, 9.0, 15.0) and tuple(n) == (2, 3, 4)
+    assert tuple(kc[0]) == (1, 2, 3)                                               # 8 >= 7.2 ; 4+4 >= 7.2 ; 6+3+3 >= 12
+    got = O.select_n(psi[0, :9], mask, [1, 2, 2], 10, 1)
+    assert list(got) == [0, 2, 3, 4, 6, 9]
+    r = rng(41)
+    for _ in range(30):
+        W = 2; L = int(r.integers(8, 30)); c = L - W
+        m3 = r.integers(0, 3, size=L).astype(np.uint8)
+        sc = r.integers(0, 4, size=c).astype(np.float64)
+        nm = [int((m3[:c] == m).sum()) for m in range(3)]
+        bud = [int(r.integers(0, nm[m] + 1)) for m in range(3)]
+        want = [i for i in range(c) if sum(1 for j in range(c) if m3[j] == m3[i] and (sc[j] > sc[i] or (sc[j] == sc[i] and j < i))) < bud[m3[i]]]
+        assert list(O.select_n(sc, m3, bud, L, W)) == want + list(range(c, L))
+
+
+def test_three_modality_eviction_invariants():
+    r = rng(42)
+    NL, H, G, L, W, d = 3, 2, 2, 60, 4, 8
+    mask = np.zeros(L, np.uint8); mask[5:20] = 1; mask[25:45] = 2
+    q = r.normal(size=(NL, H * G, W, d)); k = r.normal(size=(NL, H, L, d)); v = r.normal(size=(NL, H, L, d))
+    p = O.Params(n_layers=NL, n_q_heads=H * G, n_kv_heads=H, head_dim=d, ctx_len=L, window=W, budget=20, n_modalities=3)
+    res = O.evict(q, k, v, mask, p)
+    assert res["budgets"].shape == (NL, H, 3) and res["budgets"].sum() == NL * H * 16
+    for l in range(NL):
+        for h in range(H):
+            kept = res["kept"][l][h]
+            for m in range(3):
+                assert int((mask[kept[:-W]] == m).sum()) == res["budgets"][l, h, m]
+            sh = res["w"][l, h] / res["w"][l, h].sum()
+            assert abs(sh.sum() - 1.0) < 1e-12 and (sh >= 0).all()
