@@ -227,54 +227,267 @@ __global__ __launch_bounds__(NW * 64) void decode_attn_kernel(DecodeArgs a) {
   if (a.max_chunks == 1 && can_append && threadIdx.x == 0) a.kv_len[hidx] = len;
 }
 
+// ------------------------------------------------------------------------------------
+// Grouped-query variant (bf16, G >= 2): both contractions run on the 16x16x32 bf16 MFMA, so
+// that the G query heads of a KV head cost no more vector instructions than one.
+//   S^T[key][q] = K_tile . Q^T     A = 16 keys x 32 dims read straight from the cache rows
+//                                  (a lane takes 16 bytes of "its" key), B = Q, kept in registers
+//   O[q][d]    += P . V_tile       contraction over 32 keys.  In S^T a lane holds 4 keys of each
+//                                  16-key block for its query; the contraction index is numbered
+//                                  so that exactly those 8 keys are the lane's A fragment of P
+//                                  (no cross-lane movement); V needs the matching rows per output
+//                                  column, read as 2-byte elements from a wave-private LDS tile
+//                                  that the V rows were written to with coalesced 16-byte loads.
+// P goes through the MFMA as bf16 hi + lo parts (two MFMAs), which keeps fp32-level accuracy.
+// The running max / sum live per query in the lanes of S^T; the rescale factors are fetched
+// into the O layout with four lane reads per tile.
+// ------------------------------------------------------------------------------------
+typedef __attribute__((ext_vector_type(8))) __bf16 dbf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float df32x4_t;
+typedef __attribute__((ext_vector_type(4))) unsigned int du32x4_t;
+
+template <int D>
+__global__ __launch_bounds__(DEC_THREADS) void decode_gqa_kernel(DecodeArgs a) {
+  constexpr int GT = 8;                // query heads per KV head supported (rows 8..15 of the MFMA tile are padding)
+  constexpr int NW = 4;
+  constexpr int KS = D / 32;           // MFMA steps over the head dimension
+  constexpr int DB = D / 16;           // 16-column blocks of the output
+  constexpr int RS = D + 8;            // bf16 elements per LDS row of the V tile (16 B pad)
+  constexpr int LPR = D / 8;           // lanes per row in a coalesced 16-byte load
+  constexpr int RPI = 64 / LPR;        // rows per load instruction
+  constexpr int VL = 32 / RPI;         // load instructions per 32-row V tile
+  __shared__ float s_ml[NW][GT][2];
+  __shared__ __attribute__((aligned(16))) uint16_t s_v[NW][32][RS];
+  // the per-wave results reuse the V tiles once every wave is through with them
+  static_assert(sizeof(float) * NW * GT * D <= sizeof(uint16_t) * NW * 32 * RS, "results must fit the V tiles");
+  float (*s_acc)[GT][D] = reinterpret_cast<float (*)[GT][D]>(&s_v[0][0][0]);
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int j16 = lane & 15, c = lane >> 4;
+  const long long hidx = blockIdx.x;
+  const int chunk = blockIdx.y;
+  const int len_old = a.kv_len[hidx];
+  const long long off = a.kv_off[hidx];
+  const bool can_append = a.has_new && len_old > 0 && off + len_old < a.capacity;
+  const int len = len_old + (can_append ? 1 : 0);
+  const int nch = max(1, (len + a.chunk_rows - 1) / a.chunk_rows);
+  if (chunk >= nch) return;
+  const long long lb = hidx / a.H;
+  const int h = (int)(hidx % a.H);
+  const int r_begin = chunk * a.chunk_rows;
+  const int r_end = min(len, r_begin + a.chunk_rows);
+
+  const uint16_t* kc = reinterpret_cast<const uint16_t*>(a.k_c);
+  const uint16_t* vc = reinterpret_cast<const uint16_t*>(a.v_c);
+  const uint16_t* kn = reinterpret_cast<const uint16_t*>(a.k_new);
+  const uint16_t* vn = reinterpret_cast<const uint16_t*>(a.v_new);
+  uint16_t* kcw = reinterpret_cast<uint16_t*>(a.k_c);
+  uint16_t* vcw = reinterpret_cast<uint16_t*>(a.v_c);
+
+  // Q as the B operand: lane (q = j16, c) holds dims [32 ks + 8 c, +8) of query q
+  dbf16x8_t qb[KS];
+  const uint16_t* qg = reinterpret_cast<const uint16_t*>(a.q) + (lb * a.H + h) * (long long)a.G * D;
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    du32x4_t raw = {0u, 0u, 0u, 0u};
+    if (j16 < a.G) raw = *reinterpret_cast<const du32x4_t*>(qg + (long long)j16 * D + ks * 32 + c * 8);
+    qb[ks] = __builtin_bit_cast(dbf16x8_t, raw);
+  }
+
+  float m_run = DNEG_BIG, l_run = 0.f;       // for query j16 (every lane group c holds a copy of m, a share of l)
+  df32x4_t oacc[DB];                         // O[q = 4c + r][d = 16 db + j16]
+#pragma unroll
+  for (int db = 0; db < DB; ++db) oacc[db] = df32x4_t{0.f, 0.f, 0.f, 0.f};
+  uint16_t* vt = &s_v[wave][0][0];
+  const int vsub = lane / LPR, vpiece = lane % LPR;
+
+  // Registers hold the K fragments and V rows of the tile being worked on; each set is refilled
+  // with the next tile's data as soon as it has been consumed (V: once parked in LDS, K: after
+  // the S^T MFMAs), so the loads fly under the softmax and the P.V MFMAs.  Rows past the end of
+  // the chunk are clamped to its last row (valid memory) and masked where they are used.
+  du32x4_t kraw[2][KS], vraw[VL];
+#define MADAKV_LOAD_V(T0)                                                                          \
+  _Pragma("unroll") for (int i = 0; i < VL; ++i) {                                                 \
+    const int r = (T0) + i * RPI + vsub;                                                           \
+    const int rc = min(r, r_end - 1);                                                              \
+    const bool fresh = can_append && rc == len_old;                                                \
+    vraw[i] = *reinterpret_cast<const du32x4_t*>((fresh ? vn + hidx * D : vc + (off + rc) * D) + vpiece * 8); \
+    if (fresh && r == rc) *reinterpret_cast<du32x4_t*>(vcw + (off + rc) * D + vpiece * 8) = vraw[i]; /* Eq. 4 */ \
+  }
+#define MADAKV_LOAD_K(T0)                                                                          \
+  _Pragma("unroll") for (int blk = 0; blk < 2; ++blk) {                                            \
+    const int r = (T0) + blk * 16 + j16;                                                           \
+    const int rc = min(r, r_end - 1);                                                              \
+    const bool fresh = can_append && rc == len_old;                                                \
+    const uint16_t* kp = fresh ? kn + hidx * D : kc + (off + rc) * D;                              \
+    _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                            \
+      kraw[blk][ks] = *reinterpret_cast<const du32x4_t*>(kp + ks * 32 + c * 8);                    \
+      if (fresh && r == rc) *reinterpret_cast<du32x4_t*>(kcw + (off + rc) * D + ks * 32 + c * 8) = kraw[blk][ks]; \
+    }                                                                                              \
+  }
+  const int t_first = r_begin + wave * 32;
+  if (t_first < r_end) {
+    MADAKV_LOAD_V(t_first)
+    MADAKV_LOAD_K(t_first)
+  }
+  for (int t0 = t_first; t0 < r_end; t0 += NW * 32) {
+    const int t_next = t0 + NW * 32;
+    // ---- V rows of the tile: parked in the wave's LDS tile, then the registers are refilled
+#pragma unroll
+    for (int i = 0; i < VL; ++i)
+      *reinterpret_cast<du32x4_t*>(vt + (i * RPI + vsub) * RS + vpiece * 8) = vraw[i];
+    MADAKV_LOAD_V(t_next)
+    // ---- S^T for the two 16-key blocks
+    float p[2][4];
+    float tmax = DNEG_BIG;
+    df32x4_t sacc[2];
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk) {
+      sacc[blk] = df32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        sacc[blk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(dbf16x8_t, kraw[blk][ks]), qb[ks], sacc[blk], 0, 0, 0);
+    }
+    MADAKV_LOAD_K(t_next)
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) {
+        const int key = t0 + blk * 16 + 4 * c + rr;      // in S^T the lane holds keys 4c..4c+3 of the block
+        p[blk][rr] = key < r_end ? sacc[blk][rr] * a.scale_log2 : DNEG_BIG;
+        tmax = fmaxf(tmax, p[blk][rr]);
+      }
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+    const float m_new = fmaxf(m_run, tmax);
+    const float alpha = exp2f(m_run - m_new);
+    m_run = m_new;
+    float psum = 0.f;
+    uint32_t hi[4], lo[4];                                // P as bf16 hi + lo, 8 keys per lane: the A fragment
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float pv = exp2f(p[e >> 2][e & 3] - m_new);
+      psum += pv;
+      const uint32_t hb = f32_to_bf16_rne(pv);
+      const uint32_t lb2 = f32_to_bf16_rne(pv - bf16_bits_to_f32(hb));
+      if (e & 1) { hi[e >> 1] |= hb << 16; lo[e >> 1] |= lb2 << 16; }
+      else { hi[e >> 1] = hb; lo[e >> 1] = lb2; }
+    }
+    l_run = l_run * alpha + psum;
+    const dbf16x8_t pa_hi = __builtin_bit_cast(dbf16x8_t, du32x4_t{hi[0], hi[1], hi[2], hi[3]});
+    const dbf16x8_t pa_lo = __builtin_bit_cast(dbf16x8_t, du32x4_t{lo[0], lo[1], lo[2], lo[3]});
+    // rescale factors of the queries this lane holds in the O layout (q = 4c + r)
+    float al[4];
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) al[rr] = __shfl(alpha, (c << 4) | (4 * c + rr), 64);
+    // the V tile must be complete before it is read with another lane mapping (same wave: in order)
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      // B fragment: for output column 16 db + j16 the 8 keys of this lane group (4c..4c+3 of either block)
+      uint32_t w[4];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int row = (e >> 2) * 16 + 4 * c + (e & 3);
+        const uint32_t x = vt[row * RS + db * 16 + j16];
+        if (e & 1) w[e >> 1] |= x << 16; else w[e >> 1] = x;
+      }
+      const dbf16x8_t vb = __builtin_bit_cast(dbf16x8_t, du32x4_t{w[0], w[1], w[2], w[3]});
+      df32x4_t o = oacc[db];
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) o[rr] *= al[rr];
+      o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_hi, vb, o, 0, 0, 0);
+      o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa_lo, vb, o, 0, 0, 0);
+      oacc[db] = o;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  }
+#undef MADAKV_LOAD_V
+#undef MADAKV_LOAD_K
+
+  // ---- per wave: total of the sums over the lane groups, then everything to LDS in [q][d] form
+  l_run += __shfl_xor(l_run, 16, 64);
+  l_run += __shfl_xor(l_run, 32, 64);
+  __syncthreads();                                   // all V tiles are dead: their space takes the results
+  if (c == 0 && j16 < GT) { s_ml[wave][j16][0] = m_run; s_ml[wave][j16][1] = l_run; }
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+      const int q = 4 * c + rr;
+      if (q < GT) s_acc[wave][q][db * 16 + j16] = oacc[db][rr];
+    }
+  __syncthreads();
+  const int t = threadIdx.x;
+  const long long obase = (lb * a.H + h) * (long long)a.G * D;
+  if (t < D) {
+    for (int g = 0; g < a.G; ++g) {
+      float mx = DNEG_BIG;
+      for (int w = 0; w < NW; ++w) mx = fmaxf(mx, s_ml[w][g][0]);
+      float ls = 0.f, av = 0.f;
+      for (int w = 0; w < NW; ++w) {
+        const float cf = exp2f(s_ml[w][g][0] - mx);
+        ls += s_ml[w][g][1] * cf;
+        av += s_acc[w][g][t] * cf;
+      }
+      if (nch == 1) {
+        store_out<uint16_t>(a.out, a.out_fp32, obase + (long long)g * D + t, av / ls);
+      } else {
+        float* pp = a.part + ((hidx * a.max_chunks + chunk) * a.G + g) * (long long)(D + 2);
+        pp[t] = av;
+        if (t == 0) { pp[D] = mx; pp[D + 1] = ls; }
+      }
+    }
+  }
+  if (a.max_chunks == 1 && can_append && threadIdx.x == 0) a.kv_len[hidx] = len;
+}
+
 // Merges the partial (max, sum, acc) triples of every head that was cut into several chunks,
 // in chunk order, and stores the new length.  One workgroup per head, thread t owns element t.
 template <typename T>
-__global__ __launch_bounds__(128) void decode_merge_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(1024) void decode_merge_kernel(DecodeArgs a) {
   const long long hidx = blockIdx.x;
   const int len_old = a.kv_len[hidx];
+  __syncthreads();                                   // every wave has read the length before anyone stores the new one
   const bool can_append = a.has_new && len_old > 0 && a.kv_off[hidx] + len_old < a.capacity;
   const int len = len_old + (can_append ? 1 : 0);
   const int nch = max(1, (len + a.chunk_rows - 1) / a.chunk_rows);
-  const int t = threadIdx.x;
-  if (nch == 1) {                                    // output already written by the attention kernel
-    if (can_append && t == 0) a.kv_len[hidx] = len;
-    return;
-  }
+  if (can_append && threadIdx.x == 0) a.kv_len[hidx] = len;
+  if (nch == 1) return;                              // output already written by the attention kernel
   const int D = a.d;
+  const int g = threadIdx.x / D, t = threadIdx.x % D;   // one thread per (query head of the group, element)
+  if (g >= a.G) return;
   const long long lb = hidx / a.H;
   const int h = (int)(hidx % a.H);
   const long long obase = (lb * a.H + h) * (long long)a.G * D;
   const long long cstride = (long long)a.G * (D + 2);
-  if (t < D) {
-    for (int g = 0; g < a.G; ++g) {
-      const float* pg = a.part + (hidx * a.max_chunks * a.G + g) * (long long)(D + 2);
-      float m = DNEG_BIG, ls = 0.f, av = 0.f;
-      for (int c0 = 0; c0 < nch; c0 += 8) {          // 24 independent loads in flight per batch
-        float mc[8], lc[8], ac[8];
+  const float* pg = a.part + (hidx * a.max_chunks * a.G + g) * (long long)(D + 2);
+  float m = DNEG_BIG, ls = 0.f, av = 0.f;
+  for (int c0 = 0; c0 < nch; c0 += 8) {              // 24 independent loads in flight per batch
+    float mc[8], lc[8], ac[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const bool ok = c0 + j < nch;
-          const float* p = pg + (long long)(ok ? c0 + j : c0) * cstride;
-          mc[j] = ok ? p[D] : DNEG_BIG; lc[j] = ok ? p[D + 1] : 0.f; ac[j] = ok ? p[t] : 0.f;
-        }
-        float bm = m;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) bm = fmaxf(bm, mc[j]);
-        const float sc = exp2f(m - bm);
-        ls *= sc; av *= sc;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const float w = exp2f(mc[j] - bm);
-          ls = fmaf(lc[j], w, ls);
-          av = fmaf(ac[j], w, av);
-        }
-        m = bm;
-      }
-      store_out<T>(a.out, a.out_fp32, obase + (long long)g * D + t, av / ls);
+    for (int j = 0; j < 8; ++j) {
+      const bool ok = c0 + j < nch;
+      const float* p = pg + (long long)(ok ? c0 + j : c0) * cstride;
+      mc[j] = ok ? p[D] : DNEG_BIG; lc[j] = ok ? p[D + 1] : 0.f; ac[j] = ok ? p[t] : 0.f;
     }
+    float bm = m;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) bm = fmaxf(bm, mc[j]);
+    const float sc = exp2f(m - bm);
+    ls *= sc; av *= sc;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float w = exp2f(mc[j] - bm);
+      ls = fmaf(lc[j], w, ls);
+      av = fmaf(ac[j], w, av);
+    }
+    m = bm;
   }
-  if (can_append && t == 0) a.kv_len[hidx] = len;
+  store_out<T>(a.out, a.out_fp32, obase + (long long)g * D + t, av / ls);
 }
 
 // Rows per workgroup: small for a single layer (many short workgroups balance ragged heads and
@@ -291,7 +504,8 @@ DecodePlan decode_plan(const Dims& dm, const madakv_config& c, int longest_rows)
   if (dm.heads < 1024) {
     const long long typical = std::min(c.budget, c.ctx_len) + c.max_new_tokens;    // rows of an average head
     const long long per = ((long long)dm.heads * typical + 2047) / 2048;
-    rows = (int)std::min<long long>(1024, std::max<long long>(256, per / 256 * 256));
+    const long long by_len = typical / 64;                     // a long head is not cut into more than ~64 chunks
+    rows = (int)std::min<long long>(1024, std::max<long long>(256, std::max(per, by_len) / 256 * 256));
   }
   if (const char* e = getenv("MADAKV_DEC_CHUNK")) { int v = atoi(e); if (v >= 32 && v % 32 == 0 && dm.heads < 1024) rows = v; }
   if (const char* e = getenv("MADAKV_DEC_BIGCHUNK")) { int v = atoi(e); if (v >= 32 && v % 32 == 0 && dm.heads >= 1024) rows = v; }
@@ -308,11 +522,18 @@ size_t decode_ws_bytes(const Dims& dm, const madakv_config& c) {
 template <typename T, int LPR>
 static hipError_t launch_decode_t(const Dims& dm, DecodeArgs& a, hipStream_t st) {
   dim3 grid(dm.heads, a.max_chunks), block(DEC_THREADS);
+  if (sizeof(T) == 2 && dm.G >= 2) {
+    // grouped queries in bf16: the MFMA kernel
+    if (dm.d == 128) hipLaunchKernelGGL((decode_gqa_kernel<128>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((decode_gqa_kernel<64>), grid, block, 0, st, a);
+    if (a.max_chunks > 1) hipLaunchKernelGGL((decode_merge_kernel<T>), dim3(dm.heads), dim3(dm.G * dm.d), 0, st, a);
+    return hipGetLastError();
+  }
   if (dm.G == 1) hipLaunchKernelGGL((decode_attn_kernel<T, LPR, 1, 8, 4>), grid, block, 0, st, a);
   else if (dm.G == 2) hipLaunchKernelGGL((decode_attn_kernel<T, LPR, 2, 4, 4>), grid, block, 0, st, a);
   else if (dm.G <= 4) hipLaunchKernelGGL((decode_attn_kernel<T, LPR, 4, 4, 4>), grid, block, 0, st, a);
   else hipLaunchKernelGGL((decode_attn_kernel<T, LPR, 8, 2, 4>), grid, block, 0, st, a);
-  if (a.max_chunks > 1) hipLaunchKernelGGL((decode_merge_kernel<T>), dim3(dm.heads), dim3(128), 0, st, a);
+  if (a.max_chunks > 1) hipLaunchKernelGGL((decode_merge_kernel<T>), dim3(dm.heads), dim3(dm.G * dm.d), 0, st, a);
   return hipGetLastError();
 }
 
