@@ -558,3 +558,76 @@ def test_allocate_random_statistics_three_and_four_modalities():
         for b in range(B):
             np.testing.assert_array_equal(got[:, b], O.allocate(w[:, b], kc[:, b], n_mod[b], p))
         eng.close()
+
+
+def test_error_paths_and_streams():
+    """Host-side refusals on a live handle (nothing is enqueued), and calls on a non-default stream."""
+    wl = small_workloads()["bf16_mha"].scaled(n_layers=2, batch=1, decode_steps=1)
+    NL, H, L, W, d = wl.n_layers, wl.n_kv_heads, wl.ctx_len, wl.window, wl.head_dim
+    q, k, v, mask, masks = PU.make_inputs(wl, DEV)
+    eng = engine(wl)
+    lib = MB.lib()
+    import ctypes as C
+    vp = lambda t: C.c_void_p(t.data_ptr())
+    guard = eng.psi.clone().fill_(-3.0); eng.psi.copy_(guard)
+    # layer range outside the model, null tensor, misaligned tensor, workspace too small
+    assert lib.madakv_score(eng.h, 1, 2, vp(q), vp(k), vp(mask), vp(eng.psi), vp(eng.psi_pool), vp(eng.stats), vp(eng.n_mod),
+                            vp(eng.score_ws), eng.score_ws.numel(), None) == -1
+    assert lib.madakv_score(eng.h, 0, 2, None, vp(k), vp(mask), vp(eng.psi), vp(eng.psi_pool), vp(eng.stats), vp(eng.n_mod),
+                            vp(eng.score_ws), eng.score_ws.numel(), None) == -1
+    assert lib.madakv_score(eng.h, 0, 2, vp(q), C.c_void_p(k.data_ptr() + 2), vp(mask), vp(eng.psi), vp(eng.psi_pool), vp(eng.stats),
+                            vp(eng.n_mod), vp(eng.score_ws), eng.score_ws.numel(), None) == -1
+    assert lib.madakv_score(eng.h, 0, 2, vp(q), vp(k), vp(mask), vp(eng.psi), vp(eng.psi_pool), vp(eng.stats), vp(eng.n_mod),
+                            vp(eng.score_ws), 8, None) == -4
+    assert lib.madakv_decode_attn(eng.h, 0, 1, vp(q), vp(k), None, vp(eng.k_c), vp(eng.v_c), vp(eng.kv_off), vp(eng.kv_len),
+                                  vp(eng.psi), vp(eng.decode_ws), eng.decode_ws.numel(), None) == -1      # k_new without v_new
+    torch.cuda.synchronize()
+    assert torch.equal(eng.psi, guard), "a refused call must leave its outputs untouched"
+    assert lib.madakv_last_hip_error(eng.h) == 0
+    # the same eviction on a side stream gives the same bits as on the default stream
+    eng.score(0, NL, q, k, mask); eng.allocate(0, NL); eng.select_gather(0, NL, k, v, mask)
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in (eng.psi, eng.budgets, eng.kv_len, eng.kept_idx, eng.k_c)]
+    eng2 = engine(wl)
+    st = torch.cuda.Stream()
+    st.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(st):
+        eng2.score(0, NL, q, k, mask); eng2.allocate(0, NL); eng2.select_gather(0, NL, k, v, mask)
+    st.synchronize()
+    n = int(eng.kv_len.sum()) + 0
+    assert torch.equal(eng2.psi, ref[0]) and torch.equal(eng2.budgets, ref[1]) and torch.equal(eng2.kv_len, ref[2])
+    off, ln = eng.kv_off.cpu().numpy(), eng.kv_len.cpu().numpy()
+    for l in range(NL):
+        for h in range(H):
+            o, m = off[l, 0, h], ln[l, 0, h]
+            assert torch.equal(eng2.kept_idx[o:o + m], ref[3][o:o + m]) and torch.equal(eng2.k_c[o:o + m], ref[4][o:o + m])
+    eng.close(); eng2.close()
+
+
+def test_two_handles_and_handle_reuse():
+    """Two handles of different shape interleaved, and a second prompt on the same handle."""
+    wa = small_workloads()["bf16_mha"].scaled(n_layers=2, batch=1)
+    wb = small_workloads()["bf16_d64_gqa2"]
+    ea, eb = engine(wa), engine(wb)
+    qa, ka, va, ma, _ = PU.make_inputs(wa, DEV)
+    qb, kb, vb, mb, _ = PU.make_inputs(wb, DEV)
+    ea.score(0, 2, qa, ka, ma); eb.score(0, 2, qb, kb, mb)
+    ea.allocate(0, 2); eb.allocate(0, 2)
+    ea.select_gather(0, 2, ka, va, ma); eb.select_gather(0, 2, kb, vb, mb)
+    torch.cuda.synchronize()
+    first = [t.clone() for t in (ea.budgets, ea.kv_off, ea.kv_len, ea.kept_idx)]
+    assert int(ea.budgets.sum()) == 2 * wa.n_kv_heads * (wa.budget - wa.window)
+    assert int(eb.budgets.sum()) == 2 * wb.n_kv_heads * (wb.budget - wb.window)
+    # a second prompt (other seed -> other layer data), then the first again: same bits as the first time
+    wa2 = wa.scaled(cfg_id=77)
+    q2, k2, v2, m2, _ = PU.make_inputs(wa2, DEV)
+    ea.score(0, 2, q2, k2, m2); ea.allocate(0, 2); ea.select_gather(0, 2, k2, v2, m2)
+    ea.score(0, 2, qa, ka, ma); ea.allocate(0, 2); ea.select_gather(0, 2, ka, va, ma)
+    torch.cuda.synchronize()
+    assert torch.equal(ea.budgets, first[0]) and torch.equal(ea.kv_off, first[1]) and torch.equal(ea.kv_len, first[2])
+    off, ln = ea.kv_off.cpu().numpy(), ea.kv_len.cpu().numpy()
+    for l in range(2):
+        for h in range(wa.n_kv_heads):
+            o, m = off[l, 0, h], ln[l, 0, h]
+            assert torch.equal(ea.kept_idx[o:o + m], first[3][o:o + m])
+    ea.close(); eb.close()
