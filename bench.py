@@ -299,6 +299,26 @@ def main():
             ve.close()
             del ve
         result["evict_variants"] = vres
+        # eviction when the caller's prefill hands over the proxy rows' log-sum-exp (one pass over K).
+        # The normalisers are made here with torch, outside the timed region, as a prefill kernel would.
+        scale = 1.0 / (d ** 0.5)
+        G = Hq // H
+        lse = torch.empty(NL, B, Hq, W, dtype=torch.float32, device=dev)
+        pos = torch.arange(L, device=dev)[None, None, :]
+        rowpos = (L - W + torch.arange(W, device=dev))[None, :, None]
+        for l in range(NL):
+            for b in range(B):
+                lg = torch.einsum("hgwd,hld->hgwl", q[l, b].view(H, G, W, d).float(), k[l, b].float()).mul_(scale)
+                lg = lg.view(Hq, W, L).masked_fill_(pos > rowpos, float("-inf"))
+                lse[l, b] = torch.logsumexp(lg, dim=-1)
+                del lg
+        for rep in range(2):
+            e0.record()
+            eng.score_lse(0, NL, q, k, mask, lse); eng.allocate(0, NL); eng.select_gather(0, NL, k, v, mask)
+            e1.record()
+        torch.cuda.synchronize()
+        result["evict_with_row_lse"] = {"evict_ms": e0.elapsed_time(e1), "ctx_tokens_per_s": B * L / (e0.elapsed_time(e1) * 1e-3)}
+        del lse
         # (c) the same decode kernel over the un-evicted cache (budget >= L keeps every token)
         try:
             full = MB.MadaKV(n_layers=NL, batch=B, n_q_heads=Hq, n_kv_heads=H, head_dim=d, ctx_len=L, window=W, budget=L,

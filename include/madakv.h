@@ -135,6 +135,16 @@ int32_t madakv_score(madakv_handle* h, int32_t layer0, int32_t n,
                      float* psi, float* psi_pool, void* stats, int32_t* n_mod,
                      void* ws, size_t ws_bytes, void* stream);
 
+/* madakv_score for a caller whose prefill attention kept the softmax normalisers of the proxy
+ * rows (any flash-attention kernel has them): with
+ *   row_lse  [n, B, Hq, W] float  natural log of sum_i exp(scale * q_r . k_i) over the keys row r sees
+ * the first of the two passes over K is not needed and psi costs one pass.  Everything else as
+ * in madakv_score; the results are the same up to the rounding of row_lse. */
+int32_t madakv_score_lse(madakv_handle* h, int32_t layer0, int32_t n,
+                         const void* q_win, const void* k, const uint8_t* mask, const float* row_lse,
+                         float* psi, float* psi_pool, void* stats, int32_t* n_mod,
+                         void* ws, size_t ws_bytes, void* stream);
+
 /* Eq. 8, Eq. 10-11 for layers [layer0, layer0 + n) in order.
  *   stats    [n, B, H]        from madakv_score
  *   n_mod    [B, M]

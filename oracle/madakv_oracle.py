@@ -113,6 +113,38 @@ def window_scores(q_win: np.ndarray, k: np.ndarray, scale: float) -> np.ndarray:
     return psi
 
 
+def proxy_row_lse(q_win: np.ndarray, k: np.ndarray, scale: float) -> np.ndarray:
+    """lse[j, r] = log sum_i exp(scale * q_win[j, r] . k[j // G, i]) over the keys proxy row r sees:
+    the softmax normaliser a prefill attention kernel has for these rows anyway."""
+    q_win = np.asarray(q_win, dtype=np.float64); k = np.asarray(k, dtype=np.float64)
+    Hq, W, d = q_win.shape
+    H, L, _ = k.shape
+    G = Hq // H
+    out = np.zeros((Hq, W), dtype=np.float64)
+    for j in range(Hq):
+        logits = scale * (q_win[j] @ k[j // G].T)
+        for r in range(W):
+            row = logits[r, :L - W + r + 1]
+            mx = row.max()
+            out[j, r] = mx + math.log(np.exp(row - mx).sum())
+    return out
+
+
+def window_scores_from_lse(q_win: np.ndarray, k: np.ndarray, lse: np.ndarray, scale: float) -> np.ndarray:
+    """Eq. 7 when the row normalisers are given: psi[h, i] = sum over proxy rows of exp(logit - lse)."""
+    q_win = np.asarray(q_win, dtype=np.float64); k = np.asarray(k, dtype=np.float64)
+    Hq, W, d = q_win.shape
+    H, L, _ = k.shape
+    G = Hq // H
+    psi = np.zeros((H, L), dtype=np.float64)
+    for j in range(Hq):
+        logits = scale * (q_win[j] @ k[j // G].T)
+        for r in range(W):
+            n = L - W + r + 1
+            psi[j // G, :n] += np.exp(logits[r, :n] - lse[j, r])
+    return psi
+
+
 # --------------------------------------------------------------------------- #
 # Eq. 6 and Eq. 9: modality mass and theta-mass counts
 # --------------------------------------------------------------------------- #

@@ -54,6 +54,7 @@ def lib() -> C.CDLL:
         L.madakv_workspace_bytes.argtypes = [vp, i32, C.POINTER(sz), C.POINTER(sz), C.POINTER(sz)]
         L.madakv_compact_capacity_tokens.argtypes = [vp, C.POINTER(C.c_int64)]
         L.madakv_score.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.madakv_score_lse.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.madakv_allocate.argtypes = [vp, i32, i32, vp, vp, vp, vp]
         L.madakv_select_gather.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.madakv_decode_attn.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -64,7 +65,7 @@ def lib() -> C.CDLL:
 
 
 EXPORTS = ["madakv_create", "madakv_destroy", "madakv_last_hip_error", "madakv_workspace_bytes",
-           "madakv_compact_capacity_tokens", "madakv_score", "madakv_allocate", "madakv_select_gather",
+           "madakv_compact_capacity_tokens", "madakv_score", "madakv_score_lse", "madakv_allocate", "madakv_select_gather",
            "madakv_decode_attn"]
 
 
@@ -110,6 +111,12 @@ def madakv_compact_capacity_tokens(h) -> int:
 def madakv_score(h, layer0, n, q_win, k, mask, psi, psi_pool, stats, n_mod, ws):
     _check("madakv_score", lib().madakv_score(h, layer0, n, _ptr(q_win), _ptr(k), _ptr(mask), _ptr(psi), _ptr(psi_pool),
                                               _ptr(stats), _ptr(n_mod), _ptr(ws), ws.numel() * ws.element_size(), _stream()))
+
+
+def madakv_score_lse(h, layer0, n, q_win, k, mask, row_lse, psi, psi_pool, stats, n_mod, ws):
+    _check("madakv_score_lse", lib().madakv_score_lse(h, layer0, n, _ptr(q_win), _ptr(k), _ptr(mask), _ptr(row_lse), _ptr(psi),
+                                                      _ptr(psi_pool), _ptr(stats), _ptr(n_mod), _ptr(ws),
+                                                      ws.numel() * ws.element_size(), _stream()))
 
 
 def madakv_allocate(h, layer0, n, stats, n_mod, budgets):
@@ -183,6 +190,10 @@ class MadaKV:
     def score(self, l0, n, q_win, k, mask):
         madakv_score(self.h, l0, n, q_win, k, mask, self._sl(self.psi, l0, n), self._sl(self.psi_pool, l0, n),
                      self._sl(self.stats, l0, n), self.n_mod, self.score_ws)
+
+    def score_lse(self, l0, n, q_win, k, mask, row_lse):
+        madakv_score_lse(self.h, l0, n, q_win, k, mask, row_lse, self._sl(self.psi, l0, n), self._sl(self.psi_pool, l0, n),
+                         self._sl(self.stats, l0, n), self.n_mod, self.score_ws)
 
     def allocate(self, l0, n, stats=None, n_mod=None, budgets=None):
         madakv_allocate(self.h, l0, n, self._sl(self.stats, l0, n) if stats is None else stats,

@@ -29,7 +29,7 @@ size_t select_ws_bytes(const Dims& dm, const madakv_config& c);
 size_t decode_ws_bytes(const Dims& dm, const madakv_config& c);
 
 // Each launcher validates nothing: shapes were checked by the ABI layer.
-hipError_t launch_score(const Dims& dm, const madakv_config& c, const void* q_win, const void* k,
+hipError_t launch_score(const Dims& dm, const madakv_config& c, const void* q_win, const void* k, const float* row_lse,
                         float* psi, void* ws, hipStream_t st);
 hipError_t launch_stats(const Dims& dm, const madakv_config& c, const float* psi, const uint8_t* mask,
                         float* psi_pool, void* stats, int32_t* n_mod, int layer0, hipStream_t st);

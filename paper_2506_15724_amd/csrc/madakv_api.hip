@@ -177,10 +177,10 @@ int32_t madakv_compact_capacity_tokens(const madakv_handle* h, int64_t* tokens) 
   return MADAKV_OK;
 }
 
-int32_t madakv_score(madakv_handle* h, int32_t layer0, int32_t n,
-                     const void* q_win, const void* k, const uint8_t* mask,
-                     float* psi, float* psi_pool, void* stats, int32_t* n_mod,
-                     void* ws, size_t ws_bytes, void* stream) {
+static int32_t score_impl(madakv_handle* h, int32_t layer0, int32_t n,
+                          const void* q_win, const void* k, const uint8_t* mask, const float* row_lse,
+                          float* psi, float* psi_pool, void* stats, int32_t* n_mod,
+                          void* ws, size_t ws_bytes, void* stream) {
   int32_t r = check_range(h, layer0, n);
   if (r != MADAKV_OK) return r;
   if (bad_ptr(q_win) || bad_ptr(k) || bad_ptr(mask, 1) || bad_ptr(psi, 4) || bad_ptr(psi_pool, 4) || bad_ptr(stats, 4) ||
@@ -202,7 +202,8 @@ int32_t madakv_score(madakv_handle* h, int32_t layer0, int32_t n,
     const char* kg = static_cast<const char*>(k) + lb * c.n_kv_heads * (size_t)c.ctx_len * c.head_dim * es;
     float* psi_g = psi + lb * c.n_kv_heads * (size_t)c.ctx_len;
     float* pool_g = psi_pool + lb * c.n_kv_heads * (size_t)(c.ctx_len - c.window);
-    e = launch_score(dg, c, qg, kg, psi_g, ws, st);
+    const float* lse_g = row_lse ? row_lse + lb * c.n_q_heads * c.window : nullptr;
+    e = launch_score(dg, c, qg, kg, lse_g, psi_g, ws, st);
     hipStream_t ss = st;
     if (overlap && e == hipSuccess) {
       e = hipEventRecord(h->ev_grp[gi], st);
@@ -218,6 +219,21 @@ int32_t madakv_score(madakv_handle* h, int32_t layer0, int32_t n,
     if (e == hipSuccess) e = hipStreamWaitEvent(st, h->ev_join, 0);
   }
   return hip_fail(h, e);
+}
+
+int32_t madakv_score(madakv_handle* h, int32_t layer0, int32_t n,
+                     const void* q_win, const void* k, const uint8_t* mask,
+                     float* psi, float* psi_pool, void* stats, int32_t* n_mod,
+                     void* ws, size_t ws_bytes, void* stream) {
+  return score_impl(h, layer0, n, q_win, k, mask, nullptr, psi, psi_pool, stats, n_mod, ws, ws_bytes, stream);
+}
+
+int32_t madakv_score_lse(madakv_handle* h, int32_t layer0, int32_t n,
+                         const void* q_win, const void* k, const uint8_t* mask, const float* row_lse,
+                         float* psi, float* psi_pool, void* stats, int32_t* n_mod,
+                         void* ws, size_t ws_bytes, void* stream) {
+  if (row_lse == nullptr || (reinterpret_cast<uintptr_t>(row_lse) & 3u)) return MADAKV_ERR_INVALID_ARG;
+  return score_impl(h, layer0, n, q_win, k, mask, row_lse, psi, psi_pool, stats, n_mod, ws, ws_bytes, stream);
 }
 
 int32_t madakv_allocate(madakv_handle* h, int32_t layer0, int32_t n,

@@ -28,6 +28,7 @@ struct ScoreArgs {
   const void* k;       // [heads, L, d]
   float* psi;          // [heads, L]
   float* rowstat;      // [heads, nsplit, mpad, 2]
+  const float* lse;    // optional [heads/H * Hq, W]: natural log-sum-exp of each proxy row's scaled logits (sweep 1 not needed)
   float* sink;         // 32 floats nobody reads: keeps the psi store of sweep 2 unconditional (both half-waves
                        // store the same value; a store under a branch makes the load waits pessimistic)
   int H, G, d, L, W, M, mpad, nsplit, chunk;
@@ -131,7 +132,11 @@ __global__ __launch_bounds__(SCORE_THREADS) void score_mfma_kernel(ScoreArgs a) 
     const float* rs = a.rowstat + (long long)head * a.nsplit * a.mpad * 2;
     for (int r = tid; r < a.mpad; r += SCORE_THREADS) {
       float m = NEG_BIG, l = 0.f;
-      for (int s = 0; s < a.nsplit; ++s) merge_ml(m, l, rs[(s * a.mpad + r) * 2], rs[(s * a.mpad + r) * 2 + 1]);
+      if (a.lse) {                                               // the caller's prefill attention already has the row normalisers
+        if (r < a.M) { m = a.lse[(lb * a.H + kvh) * (long long)a.G * a.W + r] * 1.4426950408889634f; l = 1.f; }
+      } else {
+        for (int s = 0; s < a.nsplit; ++s) merge_ml(m, l, rs[(s * a.mpad + r) * 2], rs[(s * a.mpad + r) * 2 + 1]);
+      }
       offs[r] = (r < a.M) ? m + log2f(l) : __builtin_inff();     // padding rows contribute exp2(-inf) = 0
     }
   }
@@ -294,7 +299,8 @@ __global__ __launch_bounds__(SCORE_THREADS) void score_simple_kernel(ScoreArgs a
     const float* rs = a.rowstat + (long long)head * a.nsplit * a.mpad * 2;
     for (int r = tid; r < a.M; r += SCORE_THREADS) {
       float m = NEG_BIG, l = 0.f;
-      for (int s = 0; s < a.nsplit; ++s) merge_ml(m, l, rs[(s * a.mpad + r) * 2], rs[(s * a.mpad + r) * 2 + 1]);
+      if (a.lse) { m = a.lse[(lb * a.H + kvh) * (long long)a.G * a.W + r] * 1.4426950408889634f; l = 1.f; }
+      else for (int s = 0; s < a.nsplit; ++s) merge_ml(m, l, rs[(s * a.mpad + r) * 2], rs[(s * a.mpad + r) * 2 + 1]);
       offs[r] = m + log2f(l);
     }
   }
@@ -378,14 +384,15 @@ static void launch_mfma_pair(const ScoreArgs& a0, int heads, size_t lds1, size_t
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_mfma_kernel<D, WPT, NRB, 2>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
   }
-  hipLaunchKernelGGL((score_mfma_kernel<D, WPT, NRB, 1>), grid, dim3(SCORE_THREADS), lds1, st, a);
+  if (!a.lse) hipLaunchKernelGGL((score_mfma_kernel<D, WPT, NRB, 1>), grid, dim3(SCORE_THREADS), lds1, st, a);
   hipLaunchKernelGGL((score_mfma_kernel<D, WPT, NRB, 2>), grid, dim3(SCORE_THREADS), lds2, st, a);
 }
 
-hipError_t launch_score(const Dims& dm, const madakv_config& c, const void* q_win, const void* k,
+hipError_t launch_score(const Dims& dm, const madakv_config& c, const void* q_win, const void* k, const float* row_lse,
                         float* psi, void* ws, hipStream_t st) {
   ScorePlan p = score_plan(dm, c.dtype);
   ScoreArgs a;
+  a.lse = row_lse;
   a.q_win = q_win; a.k = k; a.psi = psi; a.rowstat = reinterpret_cast<float*>(ws);
   a.sink = a.rowstat + (size_t)dm.heads * score_plan(dm, c.dtype).nsplit * score_plan(dm, c.dtype).mpad * 2;
   a.H = dm.H; a.G = dm.G; a.d = dm.d; a.L = dm.L; a.W = dm.W; a.M = dm.M;
@@ -415,10 +422,10 @@ hipError_t launch_score(const Dims& dm, const madakv_config& c, const void* q_wi
       size_t lds = ((size_t)dm.M * dm.d + dm.M) * sizeof(float);
       dim3 grid(a.nsplit, nh);
       if (c.dtype == MADAKV_BF16) {
-        hipLaunchKernelGGL((score_simple_kernel<uint16_t, 1>), grid, dim3(SCORE_THREADS), lds, st, a);
+        if (!a.lse) hipLaunchKernelGGL((score_simple_kernel<uint16_t, 1>), grid, dim3(SCORE_THREADS), lds, st, a);
         hipLaunchKernelGGL((score_simple_kernel<uint16_t, 2>), grid, dim3(SCORE_THREADS), lds, st, a);
       } else {
-        hipLaunchKernelGGL((score_simple_kernel<float, 1>), grid, dim3(SCORE_THREADS), lds, st, a);
+        if (!a.lse) hipLaunchKernelGGL((score_simple_kernel<float, 1>), grid, dim3(SCORE_THREADS), lds, st, a);
         hipLaunchKernelGGL((score_simple_kernel<float, 2>), grid, dim3(SCORE_THREADS), lds, st, a);
       }
     }

@@ -631,3 +631,30 @@ def test_two_handles_and_handle_reuse():
             o, m = off[l, 0, h], ln[l, 0, h]
             assert torch.equal(ea.kept_idx[o:o + m], first[3][o:o + m])
     ea.close(); eb.close()
+
+
+@pytest.mark.parametrize("name", ["bf16_mha", "bf16_gqa7", "tiny_fp32"])
+def test_score_with_given_row_normalisers(name):
+    """madakv_score_lse: one pass over K when the caller supplies the proxy rows' log-sum-exp."""
+    wl = small_workloads()[name]
+    NL, B, H, L, W = wl.n_layers, wl.batch, wl.n_kv_heads, wl.ctx_len, wl.window
+    G = wl.n_q_heads // H
+    p = PU.oracle_params(wl)
+    q, k, v, mask, masks = PU.make_inputs(wl, DEV)
+    qh, kh = WL.to_f64(q), WL.to_f64(k)
+    lse_o = np.stack([np.stack([O.proxy_row_lse(qh[l, b], kh[l, b], p.scale) for b in range(B)]) for l in range(NL)])
+    lse = torch.from_numpy(lse_o.astype(np.float32)).to(DEV).contiguous()
+    eng = engine(wl)
+    say(f"{name}: madakv_score_lse")
+    eng.score_lse(0, NL, q, k, mask, lse)
+    torch.cuda.synchronize()
+    psi_1 = eng.psi.clone(); stats_1 = eng.stats.clone(); pool_1 = eng.psi_pool.clone()
+    psi_o = np.stack([np.stack([O.window_scores(qh[l, b], kh[l, b], p.scale) for b in range(B)]) for l in range(NL)])
+    nbad, worst = PU.psi_close(psi_1.cpu().numpy(), psi_o, G, W, L)
+    assert nbad == 0, worst
+    eng.score(0, NL, q, k, mask)
+    torch.cuda.synchronize()
+    assert torch.allclose(eng.psi, psi_1, rtol=2e-5, atol=1e-12)        # same scores either way (lse rounded to fp32)
+    with pytest.raises(MB.MadaKVError):
+        MB.madakv_score_lse(eng.h, 0, NL, q, k, mask, None, eng.psi, eng.psi_pool, eng.stats, eng.n_mod, eng.score_ws)
+    eng.close()

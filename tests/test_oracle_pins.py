@@ -560,3 +560,19 @@ def test_three_modality_eviction_invariants():
                 assert int((mask[kept[:-W]] == m).sum()) == res["budgets"][l, h, m]
             sh = res["w"][l, h] / res["w"][l, h].sum()
             assert abs(sh.sum() - 1.0) < 1e-12 and (sh >= 0).all()
+
+
+def test_row_lse_and_scores_from_it():
+    r = rng(50)
+    Hq, H, W, L, d = 4, 2, 3, 21, 8
+    q, k = r.normal(size=(Hq, W, d)), r.normal(size=(H, L, d))
+    lse = O.proxy_row_lse(q, k, 0.37)
+    tq, tk = torch.from_numpy(q), torch.from_numpy(k).repeat_interleave(2, dim=0)
+    att = torch.einsum("hwd,hld->hwl", tq, tk) * 0.37
+    pos = torch.arange(L)[None, :]; row = (L - W + torch.arange(W))[:, None]
+    want = torch.logsumexp(att.masked_fill(pos > row, float("-inf")), dim=-1).numpy()
+    np.testing.assert_allclose(lse, want, rtol=1e-13)
+    np.testing.assert_allclose(O.window_scores_from_lse(q, k, lse, 0.37), O.window_scores(q, k, 0.37), rtol=1e-12)
+    # a normaliser that is off by log 2 halves that row's contribution
+    lse2 = lse.copy(); lse2[:, :] += math.log(2.0)
+    np.testing.assert_allclose(O.window_scores_from_lse(q, k, lse2, 0.37), 0.5 * O.window_scores(q, k, 0.37), rtol=1e-12)
