@@ -21,7 +21,6 @@
 #include "common.h"
 
 #include <algorithm>
-#include <cstdlib>
 
 namespace madakv {
 
@@ -507,8 +506,6 @@ DecodePlan decode_plan(const Dims& dm, const madakv_config& c, int longest_rows)
     const long long by_len = typical / 64;                     // a long head is not cut into more than ~64 chunks
     rows = (int)std::min<long long>(1024, std::max<long long>(256, std::max(per, by_len) / 256 * 256));
   }
-  if (const char* e = getenv("MADAKV_DEC_CHUNK")) { int v = atoi(e); if (v >= 32 && v % 32 == 0 && dm.heads < 1024) rows = v; }
-  if (const char* e = getenv("MADAKV_DEC_BIGCHUNK")) { int v = atoi(e); if (v >= 32 && v % 32 == 0 && dm.heads >= 1024) rows = v; }
   p.chunk_rows = rows;
   p.max_chunks = (longest + rows - 1) / rows;
   return p;

@@ -12,7 +12,6 @@
 #include "common.h"
 
 #include <algorithm>
-#include <cstdlib>
 
 namespace madakv {
 
@@ -33,7 +32,6 @@ struct ScoreArgs {
                        // store the same value; a store under a branch makes the load waits pessimistic)
   int H, G, d, L, W, M, mpad, nsplit, chunk;
   int head0;           // first head of this launch (grid.y indexes head0 + y)
-  int dbg;             // experiment switches (0 in production)
   float scale_log2;    // softmax scale * log2(e)
 };
 
@@ -180,7 +178,6 @@ _Pragma("unroll") \
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); \
     __builtin_amdgcn_wave_barrier(); \
     float colsum = 0.f; \
-    if (a.dbg & 1) { colsum = (float)bfrag[0][0] + (float)bfrag[KS - 1][7]; } else \
 _Pragma("unroll") \
     for (int b = 0; b < NRB; ++b) { \
       const int rb = wsub + b * WPT; \
@@ -348,22 +345,17 @@ static bool use_mfma(const Dims& dm, int dtype) { return dtype == MADAKV_BF16 &&
 ScorePlan score_plan(const Dims& dm, int dtype) {
   ScorePlan p;
   p.mpad = (dm.M + 31) / 32 * 32;
-  // Both sweeps run over all heads of the call in one launch each.  (Splitting the call into
-  // groups of heads whose K fits the 256 MB memory-side cache, so that the second sweep finds
-  // its data there, was measured slower at every group size: MADAKV_SCORE_GROUP_MB tries it.)
-  long long head_bytes = (long long)dm.L * dm.d * (dtype == MADAKV_BF16 ? 2 : 4);
-  p.group_heads = dm.heads;
-  if (const char* e = getenv("MADAKV_SCORE_GROUP_MB")) {
-    long long gh = std::max(1LL, (long long)std::max(1, atoi(e)) * 1024 * 1024 / head_bytes);
-    p.group_heads = (int)std::min<long long>(gh, dm.heads);
-  }
+  // Both sweeps run over all heads of the call in one launch each, at most 65535 heads at a
+  // time (the grid's y limit).  (Splitting a call into groups of heads whose K fits the 256 MB
+  // memory-side cache, so that the second sweep finds its data there, was measured slower at
+  // every group size.)
+  p.group_heads = std::min(dm.heads, 65535);
   // enough workgroups per launch to fill 256 CUs several times over; chunks are a multiple
   // of 128 keys (4 waves x 32-key tiles) and at least 256 keys long
   int want = std::max(1, (2048 + p.group_heads - 1) / p.group_heads);
   int max_split = std::max(1, dm.L / 256);
   int ns = std::min(std::min(want, max_split), 128);
   int chunk = ((dm.L + ns - 1) / ns + 127) / 128 * 128;
-  if (const char* e = getenv("MADAKV_SCORE_CHUNK")) { int v = atoi(e); if (v >= 128 && v % 128 == 0) chunk = std::max(chunk, std::min(v, (dm.L + 127) / 128 * 128)); }
   p.nsplit = (dm.L + chunk - 1) / chunk;
   p.chunk = chunk;
   return p;
@@ -397,8 +389,6 @@ hipError_t launch_score(const Dims& dm, const madakv_config& c, const void* q_wi
   a.sink = a.rowstat + (size_t)dm.heads * score_plan(dm, c.dtype).nsplit * score_plan(dm, c.dtype).mpad * 2;
   a.H = dm.H; a.G = dm.G; a.d = dm.d; a.L = dm.L; a.W = dm.W; a.M = dm.M;
   a.mpad = p.mpad; a.nsplit = p.nsplit; a.chunk = p.chunk; a.head0 = 0;
-  a.dbg = 0;
-  if (const char* e = getenv("MADAKV_SCORE_DBG")) a.dbg = atoi(e);
   float scale = c.softmax_scale > 0.f ? c.softmax_scale : 1.0f / sqrtf((float)dm.d);
   a.scale_log2 = scale * 1.4426950408889634f;
   for (int h0 = 0; h0 < dm.heads; h0 += p.group_heads) {

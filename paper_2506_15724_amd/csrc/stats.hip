@@ -14,7 +14,6 @@
 //   k_m = #{psi > tau} + ceil((theta w_m - mass{psi > tau}) / tau).
 #include "common.h"
 
-#include <cstdlib>
 
 namespace madakv {
 
