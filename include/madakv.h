@@ -87,6 +87,9 @@ typedef struct {
   int32_t select_mode;     /* 0 = top scores per modality; 1 = score-free baseline: the first sink_tokens
                               candidates and the most recent ones, b_t + b_v in total */
   int32_t sink_tokens;     /* >= 0, used by select_mode 1 */
+  int32_t cache_fp8;       /* 1 = the reduced cache k_c, v_c holds 8-bit floats (OCP E4M3: round to nearest even,
+                              magnitudes above 448 saturate), one byte per element, instead of dtype; needs
+                              dtype = MADAKV_BF16.  Q, K, V, k_new, v_new and out stay in dtype. */
   int32_t n_modalities;    /* M, 2 .. 4: modality ids in the mask are 0 .. M-1 (the paper has text = 0 and
                               image = 1; more modalities are the extension its Sec. 6 names) */
 } madakv_config;
@@ -165,7 +168,7 @@ int32_t madakv_allocate(madakv_handle* h, int32_t layer0, int32_t n,
  *   kept_idx int32, ragged  out: head (l,b,h) owns kept_idx[kv_off .. kv_off + kv_len)
  *   kv_off   [n, B, H] int64 out: first row of the head's segment in k_c / v_c / kept_idx
  *   kv_len   [n, B, H] int32 out: sum of the head's budgets + W
- *   k_c, v_c [capacity_tokens, d]  out: the reduced cache; a head's segment has kv_len
+ *   k_c, v_c [capacity_tokens, d]  out: the reduced cache (dtype, or bytes with cache_fp8); a head's segment has kv_len
  *                              rows followed by max_new_tokens free rows
  * Batch item b owns rows [b, b+1) * capacity_tokens / B; inside, layers then heads follow
  * each other.  Budgets from madakv_allocate fill that space exactly.  If hand-made budgets

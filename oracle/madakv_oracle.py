@@ -60,6 +60,7 @@ class Params:
     select_mode: int = 0   # 0 = top scores, 1 = first `sink_tokens` + most recent candidates (score-free baseline)
     sink_tokens: int = 4
     n_modalities: int = 2  # the paper has text and image; more (audio, video: its Sec. 6) make Eq. 6, 8, 9 M-way
+    cache_fp8: int = 0     # 1 = the reduced cache holds K, V as 8-bit floats (E4M3), not part of the paper
     hcc_rho: int = 2       # clamp ratio around the running nominal budget
     theta: float = 0.9     # Eq. 9 threshold
     softmax_scale: float = 0.0  # 0 -> 1/sqrt(head_dim)
@@ -451,6 +452,47 @@ def select_n(psi_pool_h: np.ndarray, mask: np.ndarray, budgets, L: int, window: 
 def gather(x_h: np.ndarray, kept: np.ndarray) -> np.ndarray:
     """Rows `kept` of x_h[L, d], copied."""
     return x_h[kept].copy()
+
+
+# --------------------------------------------------------------------------- #
+# 8-bit reduced cache (an encoding, not part of the paper): OCP FP8 E4M3
+# --------------------------------------------------------------------------- #
+def e4m3_decode_table() -> np.ndarray:
+    """The 256 values of the E4M3 format: 1 sign, 4 exponent bits (bias 7), 3 mantissa bits;
+    exponent 0 is subnormal (m * 2^-9); there are no infinities; S.1111.111 is NaN."""
+    t = np.zeros(256, dtype=np.float64)
+    for code in range(256):
+        sgn = -1.0 if code & 0x80 else 1.0
+        e, m = (code >> 3) & 0xF, code & 0x7
+        if e == 0xF and m == 0x7:
+            t[code] = np.nan
+        elif e == 0:
+            t[code] = sgn * m * 2.0 ** -9
+        else:
+            t[code] = sgn * (1.0 + m / 8.0) * 2.0 ** (e - 7)
+    return t
+
+
+def quantize_e4m3(x: np.ndarray) -> np.ndarray:
+    """Nearest E4M3 code of each value, ties to the even mantissa, magnitudes that round above
+    the largest finite value (448) saturate to it."""
+    x = np.asarray(x, dtype=np.float64)
+    a = np.abs(x)
+    code = np.zeros(x.shape, dtype=np.int64)
+    small = a < 2.0 ** -6
+    code[small] = np.rint(a[small] * 512.0).astype(np.int64)          # subnormal grid 2^-9; 8 is the first normal code
+    big = ~small
+    mant, ex = np.frexp(a[big])                                        # a = mant * 2^ex, mant in [0.5, 1)
+    e = ex - 1
+    q = np.rint((mant * 2.0 - 1.0) * 8.0).astype(np.int64)             # 0..8
+    e = e + (q == 8); q = np.where(q == 8, 0, q)
+    code[big] = ((e + 7) << 3) | q
+    code = np.where(a >= 448.0, 0x7E, np.minimum(code, 0x7E))
+    return (code | np.where(np.signbit(x), 0x80, 0)).astype(np.uint8)
+
+
+def dequantize_e4m3(codes: np.ndarray) -> np.ndarray:
+    return e4m3_decode_table()[np.asarray(codes, dtype=np.uint8)]
 
 
 # --------------------------------------------------------------------------- #

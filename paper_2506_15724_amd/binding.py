@@ -28,7 +28,7 @@ class Config(C.Structure):
                 ("hcc_rho", C.c_int32), ("theta", C.c_float), ("softmax_scale", C.c_float),
                 ("max_new_tokens", C.c_int32), ("out_fp32", C.c_int32), ("pool_mode", C.c_int32),
                 ("share_mode", C.c_int32), ("select_mode", C.c_int32), ("sink_tokens", C.c_int32),
-                ("n_modalities", C.c_int32)]
+                ("cache_fp8", C.c_int32), ("n_modalities", C.c_int32)]
 
 
 class MadaKVError(RuntimeError):
@@ -143,10 +143,10 @@ class MadaKV:
     def __init__(self, *, n_layers, batch, n_q_heads, n_kv_heads, head_dim, ctx_len, window, budget,
                  dtype="bf16", pool_k=7, mpa_mode=1, hcc_mode=1, hcc_rho=2, theta=0.9, softmax_scale=0.0,
                  max_new_tokens=0, out_fp32=1, pool_mode=0, share_mode=0, select_mode=0, sink_tokens=4,
-                 n_modalities=2, layers_per_call=None, device="cuda:0"):
+                 n_modalities=2, cache_fp8=0, layers_per_call=None, device="cuda:0"):
         self.cfg = Config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, ctx_len, window, budget,
                           BF16 if dtype == "bf16" else FP32, pool_k, mpa_mode, hcc_mode, hcc_rho, theta,
-                          softmax_scale, max_new_tokens, out_fp32, pool_mode, share_mode, select_mode, sink_tokens, n_modalities)
+                          softmax_scale, max_new_tokens, out_fp32, pool_mode, share_mode, select_mode, sink_tokens, cache_fp8, n_modalities)
         self.device = torch.device(device)
         self.tdtype = torch.bfloat16 if dtype == "bf16" else torch.float32
         with torch.cuda.device(self.device):
@@ -169,8 +169,9 @@ class MadaKV:
         self.kept_idx = torch.empty(self.capacity, dtype=torch.int32, device=dev)
         self.kv_off = torch.empty(NL, B, H, dtype=torch.int64, device=dev)
         self.kv_len = torch.empty(NL, B, H, dtype=torch.int32, device=dev)
-        self.k_c = torch.empty(self.capacity, head_dim, dtype=self.tdtype, device=dev)
-        self.v_c = torch.empty(self.capacity, head_dim, dtype=self.tdtype, device=dev)
+        cdt = torch.uint8 if cache_fp8 else self.tdtype
+        self.k_c = torch.empty(self.capacity, head_dim, dtype=cdt, device=dev)
+        self.v_c = torch.empty(self.capacity, head_dim, dtype=cdt, device=dev)
 
     def close(self):
         if self.h is not None:

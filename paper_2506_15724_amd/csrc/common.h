@@ -63,6 +63,33 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   return (uint16_t)(u >> 16);
 }
 
+// OCP FP8 E4M3 (1 sign, 4 exponent bits of bias 7, 3 mantissa bits, subnormals, no infinities),
+// the element type of the optional 8-bit reduced cache.  Encoding: round to nearest, ties to
+// the even mantissa, magnitudes above 448 saturate.  Integer / float bit operations only, so the
+// result is the same bit pattern a host implementation of the format's definition gives.
+__device__ __forceinline__ uint32_t f32_to_e4m3(float f) {
+  const uint32_t u = __float_as_uint(f);
+  const uint32_t sign = (u >> 24) & 0x80u;
+  const float a = fminf(__uint_as_float(u & 0x7fffffffu), 448.0f);          // NaN falls to 448 as well
+  uint32_t code;
+  if (a < 0.015625f) {                                                        // below 2^-6: the subnormal grid of 2^-9
+    code = (uint32_t)__float2int_rn(a * 512.0f);                              // 0..8, 8 is the first normal code
+  } else {
+    uint32_t b = __float_as_uint(a);
+    b += 0x7ffffu + ((b >> 20) & 1u);                                         // to 3 mantissa bits, ties to even; may carry into the exponent
+    code = ((b >> 20) & 0x7ffu) - (120u << 3);                                // exponent re-biased from 127 to 7
+  }
+  return sign | min(code, 0x7eu);
+}
+// exact: every E4M3 value is a float.  Normal codes: the 7 magnitude bits become a float's low
+// exponent / top mantissa bits with the exponent re-biased (7 -> 127); subnormal codes are m * 2^-9.
+__device__ __forceinline__ float e4m3_to_f32(uint32_t c) {
+  const float normal = __uint_as_float(((c & 0x7fu) << 20) + (120u << 23));
+  const float subnormal = (float)(c & 7u) * 0.001953125f;
+  const float mag = (c & 0x78u) ? normal : subnormal;
+  return (c & 0x80u) ? -mag : mag;
+}
+
 __device__ __forceinline__ float load_elem(const float* p, long long i) { return p[i]; }
 __device__ __forceinline__ float load_elem(const uint16_t* p, long long i) { return bf16_bits_to_f32(p[i]); }
 

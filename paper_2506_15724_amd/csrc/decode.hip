@@ -43,6 +43,11 @@ template <> __device__ __forceinline__ float row_sum<8>(float x) {
   x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x141, 0xF, 0xF, true));
   return x;
 }
+template <> __device__ __forceinline__ float row_sum<4>(float x) {
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true));
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true));
+  return x;
+}
 template <> __device__ __forceinline__ float row_sum<32>(float x) {
   x = row16_sum(x);
   return x + __shfl_xor(x, 16, 64);
@@ -56,6 +61,19 @@ template <> struct Elems<uint16_t> {
     f[4] = bf16_lo(r.z); f[5] = bf16_hi(r.z); f[6] = bf16_lo(r.w); f[7] = bf16_hi(r.w);
   }
 };
+template <> struct Elems<uint8_t> {                  // E4M3 bytes of the 8-bit reduced cache
+  static constexpr int EPL = 16;
+  static __device__ __forceinline__ void unpack(const uint4& r, float* f) {
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {                     // the hardware conversion is exact (every code is a float)
+      const f32x2_t lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], false);
+      const f32x2_t hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], true);
+      f[i * 4] = lo[0]; f[i * 4 + 1] = lo[1]; f[i * 4 + 2] = hi[0]; f[i * 4 + 3] = hi[1];
+    }
+  }
+};
 template <> struct Elems<float> {
   static constexpr int EPL = 4;
   static __device__ __forceinline__ void unpack(const uint4& r, float* f) {
@@ -63,15 +81,36 @@ template <> struct Elems<float> {
   }
 };
 
+// EPL consecutive elements of the caller's type T (Q, k_new, v_new) as floats
+template <typename T, int EPL>
+__device__ __forceinline__ void load_floats(const T* p, float* f) {
+  constexpr int PER = 16 / sizeof(T);                 // elements per 16-byte load
+#pragma unroll
+  for (int j = 0; j < EPL / PER; ++j) Elems<T>::unpack(*reinterpret_cast<const uint4*>(p + j * PER), f + j * PER);
+}
+// 16 bytes of a reduced-cache row made from the caller's new row: a plain copy when the cache
+// has the caller's type, an E4M3 encoding of 16 bf16 values otherwise
+template <typename T, typename CT>
+__device__ __forceinline__ uint4 cache_piece(const T* p) {
+  if (sizeof(T) == sizeof(CT)) return *reinterpret_cast<const uint4*>(p);
+  float f[16];
+  load_floats<T, 16>(p, f);
+  uint32_t w[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    w[i] = f32_to_e4m3(f[i * 4]) | (f32_to_e4m3(f[i * 4 + 1]) << 8) | (f32_to_e4m3(f[i * 4 + 2]) << 16) | (f32_to_e4m3(f[i * 4 + 3]) << 24);
+  return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
 template <typename T>
 __device__ __forceinline__ void store_out(void* out, int out_fp32, long long o, float val) {
   if (out_fp32 || sizeof(T) == 4) reinterpret_cast<float*>(out)[o] = val;
   else reinterpret_cast<uint16_t*>(out)[o] = f32_to_bf16_rne(val);
 }
 
-template <typename T, int LPR, int GT, int UNROLL, int NW>
+template <typename T, typename CT, int LPR, int GT, int UNROLL, int NW>   // T: Q / new rows / out; CT: cache elements
 __global__ __launch_bounds__(NW * 64) void decode_attn_kernel(DecodeArgs a) {
-  constexpr int EPL = Elems<T>::EPL;
+  constexpr int EPL = Elems<CT>::EPL;
   constexpr int RPI = 64 / LPR;
   constexpr int D = LPR * EPL;
   __shared__ float s_ml[NW][GT][2];
@@ -101,9 +140,9 @@ __global__ __launch_bounds__(NW * 64) void decode_attn_kernel(DecodeArgs a) {
   const T* qg = reinterpret_cast<const T*>(a.q) + (lb * a.H + h) * (long long)a.G * D;
 #pragma unroll
   for (int g = 0; g < GT; ++g) {
-    uint4 raw = make_uint4(0, 0, 0, 0);
-    if (g < a.G) raw = *reinterpret_cast<const uint4*>(qg + (long long)g * D + piece * EPL);
-    Elems<T>::unpack(raw, qf[g]);
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) qf[g][e] = 0.f;
+    if (g < a.G) load_floats<T, EPL>(qg + (long long)g * D + piece * EPL, qf[g]);
 #pragma unroll
     for (int e = 0; e < EPL; ++e) qf[g][e] *= a.scale_log2;
   }
@@ -118,8 +157,8 @@ __global__ __launch_bounds__(NW * 64) void decode_attn_kernel(DecodeArgs a) {
 
   const uint4* kc = reinterpret_cast<const uint4*>(a.k_c);
   const uint4* vc = reinterpret_cast<const uint4*>(a.v_c);
-  const uint4* kn = reinterpret_cast<const uint4*>(a.k_new);
-  const uint4* vn = reinterpret_cast<const uint4*>(a.v_new);
+  const T* kn = reinterpret_cast<const T*>(a.k_new);
+  const T* vn = reinterpret_cast<const T*>(a.v_new);
 
   for (int row0 = r_begin + wave * WSTEP; row0 < r_end; row0 += NW * WSTEP) {
     uint4 kraw[UNROLL], vraw[UNROLL];
@@ -131,8 +170,8 @@ __global__ __launch_bounds__(NW * 64) void decode_attn_kernel(DecodeArgs a) {
       kraw[u] = make_uint4(0, 0, 0, 0); vraw[u] = make_uint4(0, 0, 0, 0);
       if (valid[u]) {
         if (can_append && r == len_old) {
-          kraw[u] = kn[hidx * LPR + piece];
-          vraw[u] = vn[hidx * LPR + piece];
+          kraw[u] = cache_piece<T, CT>(kn + hidx * D + piece * EPL);
+          vraw[u] = cache_piece<T, CT>(vn + hidx * D + piece * EPL);
           reinterpret_cast<uint4*>(a.k_c)[(off + r) * LPR + piece] = kraw[u];     // Eq. 4: the row joins the cache
           reinterpret_cast<uint4*>(a.v_c)[(off + r) * LPR + piece] = vraw[u];
         } else {
@@ -145,7 +184,7 @@ __global__ __launch_bounds__(NW * 64) void decode_attn_kernel(DecodeArgs a) {
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
       float kf[EPL];
-      Elems<T>::unpack(kraw[u], kf);
+      Elems<CT>::unpack(kraw[u], kf);
 #pragma unroll
       for (int g = 0; g < GT; ++g) {
         float dot = 0.f;
@@ -156,7 +195,7 @@ __global__ __launch_bounds__(NW * 64) void decode_attn_kernel(DecodeArgs a) {
     }
     float vf[UNROLL][EPL];
 #pragma unroll
-    for (int u = 0; u < UNROLL; ++u) Elems<T>::unpack(vraw[u], vf[u]);
+    for (int u = 0; u < UNROLL; ++u) Elems<CT>::unpack(vraw[u], vf[u]);
 #pragma unroll
     for (int g = 0; g < GT; ++g) {
       float mx = m[g];
@@ -245,14 +284,37 @@ typedef __attribute__((ext_vector_type(8))) __bf16 dbf16x8_t;
 typedef __attribute__((ext_vector_type(4))) float df32x4_t;
 typedef __attribute__((ext_vector_type(4))) unsigned int du32x4_t;
 
-template <int D>
+typedef __attribute__((ext_vector_type(2))) unsigned int du32x2_t;
+typedef __attribute__((ext_vector_type(2))) float df32x2_t;
+
+// 4 E4M3 bytes -> 4 bf16 (exact: 3 mantissa bits fit bf16's 7), as two packed dwords
+__device__ __forceinline__ du32x2_t e4m3x4_to_bf16x4(uint32_t w) {
+  const df32x2_t a = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, false), b = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, true);
+  du32x2_t o;
+  o[0] = (__float_as_uint(a[0]) >> 16) | (__float_as_uint(a[1]) & 0xffff0000u);
+  o[1] = (__float_as_uint(b[0]) >> 16) | (__float_as_uint(b[1]) & 0xffff0000u);
+  return o;
+}
+// 8 bf16 (16 bytes) -> 8 E4M3 bytes
+__device__ __forceinline__ du32x2_t bf16x8_to_e4m3x8(const du32x4_t& r) {
+  du32x2_t o;
+#pragma unroll
+  for (int w = 0; w < 2; ++w)
+    o[w] = f32_to_e4m3(bf16_lo(r[w * 2])) | (f32_to_e4m3(bf16_hi(r[w * 2])) << 8) |
+           (f32_to_e4m3(bf16_lo(r[w * 2 + 1])) << 16) | (f32_to_e4m3(bf16_hi(r[w * 2 + 1])) << 24);
+  return o;
+}
+
+template <int D, bool FP8>   // FP8: the cache rows are E4M3 bytes, turned into bf16 operands on the fly
 __global__ __launch_bounds__(DEC_THREADS) void decode_gqa_kernel(DecodeArgs a) {
   constexpr int GT = 8;                // query heads per KV head supported (rows 8..15 of the MFMA tile are padding)
   constexpr int NW = 4;
   constexpr int KS = D / 32;           // MFMA steps over the head dimension
   constexpr int DB = D / 16;           // 16-column blocks of the output
   constexpr int RS = D + 8;            // bf16 elements per LDS row of the V tile (16 B pad)
-  constexpr int LPR = D / 8;           // lanes per row in a coalesced 16-byte load
+  constexpr int CB = FP8 ? 1 : 2;      // bytes per cache element
+  constexpr int LPR = D * CB / 16;     // lanes per row in a coalesced 16-byte load
+  constexpr int VE = 16 / CB;          // V elements per lane and load
   constexpr int RPI = 64 / LPR;        // rows per load instruction
   constexpr int VL = 32 / RPI;         // load instructions per 32-row V tile
   __shared__ float s_ml[NW][GT][2];
@@ -276,12 +338,12 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_gqa_kernel(DecodeArgs a) {
   const int r_begin = chunk * a.chunk_rows;
   const int r_end = min(len, r_begin + a.chunk_rows);
 
-  const uint16_t* kc = reinterpret_cast<const uint16_t*>(a.k_c);
-  const uint16_t* vc = reinterpret_cast<const uint16_t*>(a.v_c);
+  const unsigned char* kc = reinterpret_cast<const unsigned char*>(a.k_c);   // cache rows of D * CB bytes
+  const unsigned char* vc = reinterpret_cast<const unsigned char*>(a.v_c);
   const uint16_t* kn = reinterpret_cast<const uint16_t*>(a.k_new);
   const uint16_t* vn = reinterpret_cast<const uint16_t*>(a.v_new);
-  uint16_t* kcw = reinterpret_cast<uint16_t*>(a.k_c);
-  uint16_t* vcw = reinterpret_cast<uint16_t*>(a.v_c);
+  unsigned char* kcw = reinterpret_cast<unsigned char*>(a.k_c);
+  unsigned char* vcw = reinterpret_cast<unsigned char*>(a.v_c);
 
   // Q as the B operand: lane (q = j16, c) holds dims [32 ks + 8 c, +8) of query q
   dbf16x8_t qb[KS];
@@ -304,24 +366,47 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_gqa_kernel(DecodeArgs a) {
   // with the next tile's data as soon as it has been consumed (V: once parked in LDS, K: after
   // the S^T MFMAs), so the loads fly under the softmax and the P.V MFMAs.  Rows past the end of
   // the chunk are clamped to its last row (valid memory) and masked where they are used.
-  du32x4_t kraw[2][KS], vraw[VL];
+  du32x4_t kraw[2][KS], vraw[VL];            // raw cache bytes (E4M3: 8 bytes of a K piece sit in kraw[..][..].xy)
 #define MADAKV_LOAD_V(T0)                                                                          \
   _Pragma("unroll") for (int i = 0; i < VL; ++i) {                                                 \
     const int r = (T0) + i * RPI + vsub;                                                           \
     const int rc = min(r, r_end - 1);                                                              \
     const bool fresh = can_append && rc == len_old;                                                \
-    vraw[i] = *reinterpret_cast<const du32x4_t*>((fresh ? vn + hidx * D : vc + (off + rc) * D) + vpiece * 8); \
-    if (fresh && r == rc) *reinterpret_cast<du32x4_t*>(vcw + (off + rc) * D + vpiece * 8) = vraw[i]; /* Eq. 4 */ \
+    if (!fresh) {                                                                                  \
+      vraw[i] = *reinterpret_cast<const du32x4_t*>(vc + ((off + rc) * D + vpiece * VE) * CB);      \
+    } else {                                                                                       \
+      const uint16_t* np_ = vn + hidx * D + vpiece * VE;                                           \
+      if (FP8) {                                                                                   \
+        const du32x2_t e0 = bf16x8_to_e4m3x8(*reinterpret_cast<const du32x4_t*>(np_));             \
+        const du32x2_t e1 = bf16x8_to_e4m3x8(*reinterpret_cast<const du32x4_t*>(np_ + 8));         \
+        vraw[i] = du32x4_t{e0[0], e0[1], e1[0], e1[1]};                                            \
+      } else {                                                                                     \
+        vraw[i] = *reinterpret_cast<const du32x4_t*>(np_);                                         \
+      }                                                                                            \
+      if (r == rc) *reinterpret_cast<du32x4_t*>(vcw + ((off + rc) * D + vpiece * VE) * CB) = vraw[i]; /* Eq. 4 */ \
+    }                                                                                              \
   }
 #define MADAKV_LOAD_K(T0)                                                                          \
   _Pragma("unroll") for (int blk = 0; blk < 2; ++blk) {                                            \
     const int r = (T0) + blk * 16 + j16;                                                           \
     const int rc = min(r, r_end - 1);                                                              \
     const bool fresh = can_append && rc == len_old;                                                \
-    const uint16_t* kp = fresh ? kn + hidx * D : kc + (off + rc) * D;                              \
     _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                            \
-      kraw[blk][ks] = *reinterpret_cast<const du32x4_t*>(kp + ks * 32 + c * 8);                    \
-      if (fresh && r == rc) *reinterpret_cast<du32x4_t*>(kcw + (off + rc) * D + ks * 32 + c * 8) = kraw[blk][ks]; \
+      const long long eo = (off + rc) * D + ks * 32 + c * 8;      /* element offset of the piece */ \
+      if (!fresh) {                                                                                \
+        if (FP8) { const du32x2_t t2 = *reinterpret_cast<const du32x2_t*>(kc + eo); kraw[blk][ks] = du32x4_t{t2[0], t2[1], 0u, 0u}; } \
+        else kraw[blk][ks] = *reinterpret_cast<const du32x4_t*>(kc + eo * 2);                      \
+      } else {                                                                                     \
+        const du32x4_t nb = *reinterpret_cast<const du32x4_t*>(kn + hidx * D + ks * 32 + c * 8);   \
+        if (FP8) {                                                                                 \
+          const du32x2_t t2 = bf16x8_to_e4m3x8(nb);                                                \
+          kraw[blk][ks] = du32x4_t{t2[0], t2[1], 0u, 0u};                                          \
+          if (r == rc) *reinterpret_cast<du32x2_t*>(kcw + eo) = t2;                                \
+        } else {                                                                                   \
+          kraw[blk][ks] = nb;                                                                      \
+          if (r == rc) *reinterpret_cast<du32x4_t*>(kcw + eo * 2) = nb;                            \
+        }                                                                                          \
+      }                                                                                            \
     }                                                                                              \
   }
   const int t_first = r_begin + wave * 32;
@@ -333,8 +418,17 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_gqa_kernel(DecodeArgs a) {
     const int t_next = t0 + NW * 32;
     // ---- V rows of the tile: parked in the wave's LDS tile, then the registers are refilled
 #pragma unroll
-    for (int i = 0; i < VL; ++i)
-      *reinterpret_cast<du32x4_t*>(vt + (i * RPI + vsub) * RS + vpiece * 8) = vraw[i];
+    for (int i = 0; i < VL; ++i) {
+      if (FP8) {                                           // 16 bytes -> 16 bf16
+        const du32x2_t c0 = e4m3x4_to_bf16x4(vraw[i][0]), c1 = e4m3x4_to_bf16x4(vraw[i][1]);
+        const du32x2_t c2 = e4m3x4_to_bf16x4(vraw[i][2]), c3 = e4m3x4_to_bf16x4(vraw[i][3]);
+        const du32x4_t b0 = {c0[0], c0[1], c1[0], c1[1]}, b1 = {c2[0], c2[1], c3[0], c3[1]};
+        *reinterpret_cast<du32x4_t*>(vt + (i * RPI + vsub) * RS + vpiece * 16) = b0;
+        *reinterpret_cast<du32x4_t*>(vt + (i * RPI + vsub) * RS + vpiece * 16 + 8) = b1;
+      } else {
+        *reinterpret_cast<du32x4_t*>(vt + (i * RPI + vsub) * RS + vpiece * 8) = vraw[i];
+      }
+    }
     MADAKV_LOAD_V(t_next)
     // ---- S^T for the two 16-key blocks
     float p[2][4];
@@ -344,8 +438,14 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_gqa_kernel(DecodeArgs a) {
     for (int blk = 0; blk < 2; ++blk) {
       sacc[blk] = df32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
-        sacc[blk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(dbf16x8_t, kraw[blk][ks]), qb[ks], sacc[blk], 0, 0, 0);
+      for (int ks = 0; ks < KS; ++ks) {
+        du32x4_t kb = kraw[blk][ks];
+        if (FP8) {
+          const du32x2_t c0 = e4m3x4_to_bf16x4(kraw[blk][ks][0]), c1 = e4m3x4_to_bf16x4(kraw[blk][ks][1]);
+          kb = du32x4_t{c0[0], c0[1], c1[0], c1[1]};
+        }
+        sacc[blk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(dbf16x8_t, kb), qb[ks], sacc[blk], 0, 0, 0);
+      }
     }
     MADAKV_LOAD_K(t_next)
 #pragma unroll
@@ -516,20 +616,21 @@ size_t decode_ws_bytes(const Dims& dm, const madakv_config& c) {
   return (size_t)dm.heads * p.max_chunks * dm.G * (dm.d + 2) * sizeof(float) + 64;
 }
 
-template <typename T, int LPR>
+template <typename T, typename CT, int LPR>
 static hipError_t launch_decode_t(const Dims& dm, DecodeArgs& a, hipStream_t st) {
   dim3 grid(dm.heads, a.max_chunks), block(DEC_THREADS);
   if (sizeof(T) == 2 && dm.G >= 2) {
     // grouped queries in bf16: the MFMA kernel
-    if (dm.d == 128) hipLaunchKernelGGL((decode_gqa_kernel<128>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((decode_gqa_kernel<64>), grid, block, 0, st, a);
+    constexpr bool F8 = sizeof(CT) == 1;
+    if (dm.d == 128) hipLaunchKernelGGL((decode_gqa_kernel<128, F8>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((decode_gqa_kernel<64, F8>), grid, block, 0, st, a);
     if (a.max_chunks > 1) hipLaunchKernelGGL((decode_merge_kernel<T>), dim3(dm.heads), dim3(dm.G * dm.d), 0, st, a);
     return hipGetLastError();
   }
-  if (dm.G == 1) hipLaunchKernelGGL((decode_attn_kernel<T, LPR, 1, 8, 4>), grid, block, 0, st, a);
-  else if (dm.G == 2) hipLaunchKernelGGL((decode_attn_kernel<T, LPR, 2, 4, 4>), grid, block, 0, st, a);
-  else if (dm.G <= 4) hipLaunchKernelGGL((decode_attn_kernel<T, LPR, 4, 4, 4>), grid, block, 0, st, a);
-  else hipLaunchKernelGGL((decode_attn_kernel<T, LPR, 8, 2, 4>), grid, block, 0, st, a);
+  if (dm.G == 1) hipLaunchKernelGGL((decode_attn_kernel<T, CT, LPR, 1, 8, 4>), grid, block, 0, st, a);
+  else if (dm.G == 2) hipLaunchKernelGGL((decode_attn_kernel<T, CT, LPR, 2, 4, 4>), grid, block, 0, st, a);
+  else if (dm.G <= 4) hipLaunchKernelGGL((decode_attn_kernel<T, CT, LPR, 4, 4, 4>), grid, block, 0, st, a);
+  else hipLaunchKernelGGL((decode_attn_kernel<T, CT, LPR, 8, 2, 4>), grid, block, 0, st, a);
   if (a.max_chunks > 1) hipLaunchKernelGGL((decode_merge_kernel<T>), dim3(dm.heads), dim3(dm.G * dm.d), 0, st, a);
   return hipGetLastError();
 }
@@ -548,11 +649,15 @@ hipError_t launch_decode(const Dims& dm, const madakv_config& c, const void* q, 
   a.scale_log2 = scale * 1.4426950408889634f;
   const int lpr = dm.d * (c.dtype == MADAKV_BF16 ? 2 : 4) / 16;
   if (c.dtype == MADAKV_BF16) {
-    if (lpr == 8) return launch_decode_t<uint16_t, 8>(dm, a, st);
-    if (lpr == 16) return launch_decode_t<uint16_t, 16>(dm, a, st);
+    if (c.cache_fp8) {                                   // rows of d bytes: d / 16 lanes per row
+      if (dm.d == 128) return launch_decode_t<uint16_t, uint8_t, 8>(dm, a, st);
+      if (dm.d == 64) return launch_decode_t<uint16_t, uint8_t, 4>(dm, a, st);
+    }
+    if (lpr == 8) return launch_decode_t<uint16_t, uint16_t, 8>(dm, a, st);
+    if (lpr == 16) return launch_decode_t<uint16_t, uint16_t, 16>(dm, a, st);
   } else {
-    if (lpr == 16) return launch_decode_t<float, 16>(dm, a, st);
-    if (lpr == 32) return launch_decode_t<float, 32>(dm, a, st);
+    if (lpr == 16) return launch_decode_t<float, float, 16>(dm, a, st);
+    if (lpr == 32) return launch_decode_t<float, float, 32>(dm, a, st);
   }
   return hipErrorInvalidValue;
 }

@@ -22,7 +22,7 @@ struct GatherArgs {
   long long region_tokens;
 };
 
-template <int LPR>   // lanes per row (row bytes / 16)
+template <int LPR, bool FP8>   // lanes per source row (row bytes / 16); FP8: bf16 rows are stored as E4M3
 __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
   constexpr int RPI = 64 / LPR;                 // rows per wave instruction
   constexpr int ROWS_PER_WAVE = GATHER_ROWS / 4;
@@ -104,8 +104,27 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
 #pragma unroll
   for (int it = 0; it < ITERS; ++it) {
     if (src[it] >= 0) {
-      kout[dst[it] * LPR + piece] = kv[it];
-      vout[dst[it] * LPR + piece] = vv[it];
+      if (FP8) {
+        // 8 bf16 -> 8 bytes per lane; a row of the reduced cache is LPR * 8 bytes
+        typedef __attribute__((ext_vector_type(2))) unsigned int u32x2_t;
+        u32x2_t ko, vo;
+#pragma unroll
+        for (int w = 0; w < 2; ++w) {
+          uint32_t kb = 0, vb = 0;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const uint32_t kp = kv[it][w * 2 + e / 2], vp = vv[it][w * 2 + e / 2];
+            const float kf = (e & 1) ? bf16_hi(kp) : bf16_lo(kp), vf = (e & 1) ? bf16_hi(vp) : bf16_lo(vp);
+            kb |= f32_to_e4m3(kf) << (8 * e); vb |= f32_to_e4m3(vf) << (8 * e);
+          }
+          ko[w] = kb; vo[w] = vb;
+        }
+        reinterpret_cast<u32x2_t*>(a.k_c)[dst[it] * LPR + piece] = ko;
+        reinterpret_cast<u32x2_t*>(a.v_c)[dst[it] * LPR + piece] = vo;
+      } else {
+        kout[dst[it] * LPR + piece] = kv[it];
+        vout[dst[it] * LPR + piece] = vv[it];
+      }
     }
   }
 }
@@ -124,9 +143,13 @@ hipError_t launch_gather(const Dims& dm, const madakv_config& c, int li0, int nl
   const int row_bytes = dm.d * (c.dtype == MADAKV_BF16 ? 2 : 4);
   const int lpr = row_bytes / 16;
   dim3 grid(std::min(grid_blocks, blocks_per_batch), dm.B);
-  if (lpr == 8) hipLaunchKernelGGL((gather_kernel<8>), grid, dim3(256), 0, st, a);
-  else if (lpr == 16) hipLaunchKernelGGL((gather_kernel<16>), grid, dim3(256), 0, st, a);
-  else if (lpr == 32) hipLaunchKernelGGL((gather_kernel<32>), grid, dim3(256), 0, st, a);
+  if (c.cache_fp8) {
+    if (lpr == 8) hipLaunchKernelGGL((gather_kernel<8, true>), grid, dim3(256), 0, st, a);
+    else if (lpr == 16) hipLaunchKernelGGL((gather_kernel<16, true>), grid, dim3(256), 0, st, a);
+    else return hipErrorInvalidValue;
+  } else if (lpr == 8) hipLaunchKernelGGL((gather_kernel<8, false>), grid, dim3(256), 0, st, a);
+  else if (lpr == 16) hipLaunchKernelGGL((gather_kernel<16, false>), grid, dim3(256), 0, st, a);
+  else if (lpr == 32) hipLaunchKernelGGL((gather_kernel<32, false>), grid, dim3(256), 0, st, a);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }

@@ -80,6 +80,8 @@ int32_t validate(const madakv_config& c) {
   if (M > 256) return MADAKV_ERR_BAD_SHAPE;
   if (c.dtype == MADAKV_FP32 && (long long)M * c.head_dim > 12288) return MADAKV_ERR_BAD_SHAPE;   // Q tile of the FMA path must fit LDS
   if (c.n_modalities < 2 || c.n_modalities > 4) return MADAKV_ERR_BAD_SHAPE;
+  if ((c.cache_fp8 | 1) != 1) return MADAKV_ERR_INVALID_ARG;
+  if (c.cache_fp8 && c.dtype != MADAKV_BF16) return MADAKV_ERR_UNSUPPORTED_DTYPE;
   if (c.pool_k < 1 || c.pool_k > 63 || (c.pool_k & 1) == 0) return MADAKV_ERR_BAD_SHAPE;
   if (c.budget < 1 || (c.budget < c.ctx_len && c.budget <= c.window)) return MADAKV_ERR_BAD_BUDGET;
   if (c.hcc_rho < 1 || c.hcc_rho > 1024) return MADAKV_ERR_INVALID_ARG;

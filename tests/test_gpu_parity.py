@@ -658,3 +658,59 @@ def test_score_with_given_row_normalisers(name):
     with pytest.raises(MB.MadaKVError):
         MB.madakv_score_lse(eng.h, 0, NL, q, k, mask, None, eng.psi, eng.psi_pool, eng.stats, eng.n_mod, eng.score_ws)
     eng.close()
+
+
+@pytest.mark.parametrize("name", ["bf16_mha", "bf16_gqa7", "bf16_d64_gqa2", "bf16_odd"])
+def test_fp8_reduced_cache(name):
+    """cache_fp8: the reduced cache holds E4M3 bytes.  The bytes must be the oracle's encoding of the
+    kept rows (and of the appended rows); decode must match Eq. 5 over the decoded values."""
+    wl = small_workloads()[name]
+    NL, B, H, L, W, d = wl.n_layers, wl.batch, wl.n_kv_heads, wl.ctx_len, wl.window, wl.head_dim
+    G = wl.n_q_heads // H
+    p = PU.oracle_params(wl)
+    q, k, v, mask, masks = PU.make_inputs(wl, DEV)
+    eng = engine(wl, cache_fp8=1)
+    assert eng.k_c.dtype == torch.uint8
+    say(f"{name}: eviction into an 8-bit cache")
+    eng.score(0, NL, q, k, mask); eng.allocate(0, NL); eng.select_gather(0, NL, k, v, mask)
+    torch.cuda.synchronize()
+    off, ln = eng.kv_off.cpu().numpy(), eng.kv_len.cpu().numpy()
+    kept_all = eng.kept_idx.cpu().numpy()
+    kc, vc = eng.k_c.cpu().numpy(), eng.v_c.cpu().numpy()
+    kh, vh = WL.to_f64(k), WL.to_f64(v)
+    caches = {}
+    for l in range(NL):
+        for b in range(B):
+            for h in range(H):
+                o, n = off[l, b, h], ln[l, b, h]
+                kept = kept_all[o:o + n]
+                want_k, want_v = O.quantize_e4m3(kh[l, b, h][kept]), O.quantize_e4m3(vh[l, b, h][kept])
+                # the sign of an encoded zero is not compared (both are 0.0)
+                assert (((kc[o:o + n] ^ want_k) & np.where((want_k & 0x7F) == 0, 0x7F, 0xFF)) == 0).all()
+                assert (((vc[o:o + n] ^ want_v) & np.where((want_v & 0x7F) == 0, 0x7F, 0xFF)) == 0).all()
+                caches[(l, b, h)] = [O.dequantize_e4m3(kc[o:o + n]), O.dequantize_e4m3(vc[o:o + n])]
+    out = torch.empty(NL, B, wl.n_q_heads, d, dtype=torch.float32, device=DEV)
+    for step in range(wl.decode_steps):
+        dq, dk, dv = WL.decode_inputs_all(wl, step, DEV)
+        say(f"{name}: fp8 decode step {step}")
+        if step % 2 == 0:
+            for l in range(NL):
+                eng.decode_attn(l, 1, dq[l:l + 1], dk[l:l + 1], dv[l:l + 1], out[l:l + 1])
+        else:
+            eng.decode_attn(0, NL, dq, dk, dv, out)
+        torch.cuda.synchronize()
+        og = out.cpu().numpy()
+        kc2, vc2 = eng.k_c.cpu().numpy(), eng.v_c.cpu().numpy()
+        for (l, b, h), (ck, cv) in caches.items():
+            nk = O.dequantize_e4m3(O.quantize_e4m3(WL.to_f64(dk[l, b, h])))
+            nv = O.dequantize_e4m3(O.quantize_e4m3(WL.to_f64(dv[l, b, h])))
+            ck = np.concatenate([ck, nk[None]]); cv = np.concatenate([cv, nv[None]])
+            caches[(l, b, h)] = [ck, cv]
+            o = off[l, b, h]
+            np.testing.assert_array_equal(O.dequantize_e4m3(kc2[o + len(ck) - 1]), nk)      # the appended row, as stored
+            np.testing.assert_array_equal(O.dequantize_e4m3(vc2[o + len(cv) - 1]), nv)
+            for g in range(G):
+                ref = O.attend(WL.to_f64(dq[l, b, h * G + g]), ck, cv, p.scale)
+                assert np.abs(og[l, b, h * G + g] - ref).max() <= PU.DECODE_ATOL, (step, l, b, h, g)
+    assert (eng.kv_len.cpu().numpy() == ln + wl.decode_steps).all()
+    eng.close()

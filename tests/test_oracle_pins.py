@@ -576,3 +576,24 @@ def test_row_lse_and_scores_from_it():
     # a normaliser that is off by log 2 halves that row's contribution
     lse2 = lse.copy(); lse2[:, :] += math.log(2.0)
     np.testing.assert_allclose(O.window_scores_from_lse(q, k, lse2, 0.37), 0.5 * O.window_scores(q, k, 0.37), rtol=1e-12)
+
+
+# ------------------------------------------------------------------ 8-bit reduced cache encoding
+def test_e4m3_table_and_quantiser():
+    t = O.e4m3_decode_table()
+    assert t[0x38] == 1.0 and t[0x7E] == 448.0 and t[0x01] == 2.0 ** -9 and t[0x08] == 2.0 ** -6 and np.isnan(t[0x7F])
+    fin = np.array([c for c in range(256) if (c & 0x7F) != 0x7F])
+    assert (np.diff(t[fin[fin < 0x80]]) > 0).all()                                   # codes order like values
+    np.testing.assert_array_equal(O.quantize_e4m3(t[fin]) & 0x7F, fin & 0x7F)        # every code is its own nearest
+    # the library format of the same name, wherever it does not overflow to NaN
+    allbf = torch.arange(0, 65536, dtype=torch.int32).to(torch.int16).view(torch.bfloat16).float()
+    ok = torch.isfinite(allbf) & (allbf.abs() <= 448.0)
+    want = allbf[ok].to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    got = O.quantize_e4m3(allbf[ok].numpy())
+    nz = (want & 0x7F) != 0                                                          # sign of zero results aside
+    np.testing.assert_array_equal(got[nz], want[nz])
+    assert ((got[~nz] & 0x7F) == 0).all()
+    # ties to even, subnormals, saturation
+    assert O.quantize_e4m3(np.array([1.0625, 1.1875, 2.0 ** -10, 3 * 2.0 ** -10, 464.0, 1e9, -1e9])).tolist() == \
+        [0x38, 0x3A, 0x00, 0x02, 0x7E, 0x7E, 0xFE]
+    np.testing.assert_array_equal(O.dequantize_e4m3(np.array([0x38, 0xB8, 0x7E], dtype=np.uint8)), [1.0, -1.0, 448.0])
