@@ -183,3 +183,10 @@ def test_hcc_drafts_take_both_signs_on_the_16k_workload():
     say(f"layer drafts relative to the running nominal: {''.join('+' if s > 0 else '-' if s < 0 else '0' for s in signs)}")
     assert (np.array(signs) > 0).any() and (np.array(signs) < 0).any()
     eng.close()
+
+
+def test_maximum_context_length():
+    """ctx_len at the library's limit (2^20): every per-head kernel runs its multi-chunk path."""
+    wl = WL.CONFIGS["long_128k"].scaled(name="max_ctx", ctx_len=1 << 20, n_q_heads=2, n_kv_heads=2, n_images=1500,
+                                        budget=4096, window=32)
+    run_full(wl, [(0, 0, 1)], decode_steps=1)

@@ -714,3 +714,75 @@ def test_fp8_reduced_cache(name):
                 assert np.abs(og[l, b, h * G + g] - ref).max() <= PU.DECODE_ATOL, (step, l, b, h, g)
     assert (eng.kv_len.cpu().numpy() == ln + wl.decode_steps).all()
     eng.close()
+
+
+def _run_and_check_whole_path(wl, decode_steps=1):
+    """Whole path on a (possibly degenerate) shape, every head against the oracle stage by stage."""
+    NL, B, H, L, W, d = wl.n_layers, wl.batch, wl.n_kv_heads, wl.ctx_len, wl.window, wl.head_dim
+    G, nc = wl.n_q_heads // H, L - W
+    p = PU.oracle_params(wl)
+    q, k, v, mask, masks = PU.make_inputs(wl, DEV)
+    eng = engine(wl, max_new_tokens=decode_steps)
+    eng.score(0, NL, q, k, mask); eng.allocate(0, NL); eng.select_gather(0, NL, k, v, mask)
+    torch.cuda.synchronize()
+    psi_g, pool_g = eng.psi.cpu().numpy(), eng.psi_pool.cpu().numpy()
+    w_g, k_g = eng.stats_host()
+    nmod, bud_g = eng.n_mod.cpu().numpy(), eng.budgets.cpu().numpy()
+    off, ln, kept_all = eng.kv_off.cpu().numpy(), eng.kv_len.cpu().numpy(), eng.kept_idx.cpu().numpy()
+    qh, kh, vh = WL.to_f64(q), WL.to_f64(k), WL.to_f64(v)
+    out = torch.empty(NL, B, wl.n_q_heads, d, dtype=torch.float32, device=DEV)
+    dq, dk, dv = WL.decode_inputs_all(wl, 0, DEV)
+    eng.decode_attn(0, NL, dq, dk, dv, out)
+    torch.cuda.synchronize()
+    og = out.cpu().numpy()
+    for b in range(B):
+        for l in range(NL):
+            psi_o = O.window_scores(qh[l, b], kh[l, b], p.scale)
+            assert PU.psi_close(psi_g[l, b], psi_o, G, W, L)[0] == 0
+            psi_in = psi_g[l, b].astype(np.float64)
+            w_o, k_o, n_o = O.modality_stats(psi_in, masks[b], W, p.theta)
+            assert tuple(nmod[b]) == tuple(n_o)
+            np.testing.assert_allclose(w_g[l, b], w_o, rtol=2e-6, atol=1e-30)
+            if not p.keep_all:
+                np.testing.assert_array_equal(pool_g[l, b], O.pool_scores(psi_in, W, p.pool_k).astype(np.float32))
+        np.testing.assert_array_equal(bud_g[:, b], O.allocate(w_g[:, b], k_g[:, b].astype(np.int64), nmod[b], p))
+        for l in range(NL):
+            for h in range(H):
+                bt, bv = (int(x) for x in bud_g[l, b, h])
+                ref = np.arange(L) if p.keep_all else O.select(pool_g[l, b, h].astype(np.float64), masks[b], bt, bv, L, W)
+                o = off[l, b, h]
+                np.testing.assert_array_equal(kept_all[o:o + ln[l, b, h]], ref)
+                kc = np.concatenate([kh[l, b, h][ref], WL.to_f64(dk[l, b, h])[None]])
+                vc = np.concatenate([vh[l, b, h][ref], WL.to_f64(dv[l, b, h])[None]])
+                for g in range(G):
+                    r = O.attend(WL.to_f64(dq[l, b, h * G + g]), kc, vc, p.scale)
+                    assert np.abs(og[l, b, h * G + g] - r).max() <= PU.DECODE_ATOL
+    eng.close()
+
+
+@pytest.mark.parametrize("shape", [
+    dict(ctx_len=3, window=1, budget=2),                  # one candidate kept of two
+    dict(ctx_len=2, window=1, budget=2),                  # budget = context: keep all
+    dict(ctx_len=40, window=1, budget=2),                 # a single proxy token, one candidate per head
+    dict(ctx_len=33, window=32, budget=33),               # window = context - 1
+    dict(ctx_len=300, window=16, budget=299),             # all but one candidate
+    dict(ctx_len=257, window=16, budget=17),              # beta = 1
+])
+def test_degenerate_shapes(shape):
+    L, W = shape["ctx_len"], shape["window"]
+    t0 = max(1, (L - W) // 3)
+    im = (L - W) - t0
+    layout = ((0, t0),) + (((1, im),) if im > 0 else ()) + ((0, W),)          # text, image, the (text) window
+    wl = WL.CONFIGS["tiny"].scaled(name="degenerate", dtype="bf16", n_layers=2, batch=1, n_q_heads=2, n_kv_heads=2,
+                                   head_dim=64, pool_k=3, fixed_layout=layout, **shape)
+    _run_and_check_whole_path(wl)
+
+
+def test_widest_shapes():
+    """64 KV heads (the lane limit of the allocation kernel), 8 query heads per KV head (the group limit)."""
+    wl = WL.CONFIGS["llava_layer"].scaled(name="wide", n_layers=2, batch=1, n_q_heads=64, n_kv_heads=64, head_dim=64,
+                                          ctx_len=900, window=8, budget=120, n_images=1)
+    _run_and_check_whole_path(wl)
+    wl = WL.CONFIGS["llava_layer"].scaled(name="g8", n_layers=1, batch=2, n_q_heads=16, n_kv_heads=2, head_dim=128,
+                                          ctx_len=1300, window=32, budget=200, n_images=1)
+    _run_and_check_whole_path(wl)
