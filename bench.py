@@ -299,6 +299,17 @@ def main():
             ve.close()
             del ve
         result["evict_variants"] = vres
+        # the same eviction called layer by layer (three calls per layer), as a prefill that frees each
+        # layer's full K, V right after evicting it would drive it
+        for rep in range(2):
+            e0.record()
+            for l in range(NL):
+                eng.score(l, 1, q[l:l + 1], k[l:l + 1], mask)
+                eng.allocate(l, 1)
+                eng.select_gather(l, 1, k[l:l + 1], v[l:l + 1], mask)
+            e1.record()
+        torch.cuda.synchronize()
+        result["evict_layer_by_layer"] = {"evict_ms": e0.elapsed_time(e1), "ctx_tokens_per_s": B * L / (e0.elapsed_time(e1) * 1e-3)}
         # the 8-bit (E4M3) reduced cache: eviction, then decode one call per layer and all layers in one call
         try:
             f8 = MB.MadaKV(n_layers=NL, batch=B, n_q_heads=Hq, n_kv_heads=H, head_dim=d, ctx_len=L, window=W,

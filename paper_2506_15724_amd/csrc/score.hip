@@ -158,7 +158,7 @@ __global__ __launch_bounds__(SCORE_THREADS) void score_mfma_kernel(ScoreArgs a) 
   // one subtile per step: registers -> LDS tile -> MFMA -> statistics / column sums.
   // (Written as a macro applied to each register set: the sets must stay in registers, and
   // any indirection over them makes the compiler park them in scratch memory.)
-#define MADAKV_STEP(SRC, IT)  {  const int it = (IT);  if (it < niter) { \
+#define MADAKV_STEP(SRC, IT)  {  const int it = (IT);  { \
 _Pragma("unroll") \
     for (int i = 0; i < LPS; ++i) { \
       const int idx = i * 64 + lane; \
@@ -239,9 +239,15 @@ _Pragma("unroll") \
       } \
     } \
   } }
-  for (int it0 = 0; it0 < niter; it0 += PF) {
+  // Four unconditional steps per trip; the step count is rounded up (a step past the end works on
+  // clamped rows and is fully masked).  A step under a condition would leave the compiler unsure how
+  // many loads are in flight after it, and it would then wait for all of them at every step.
+  const int niter4 = (niter + 2 * PF - 1) / (2 * PF) * (2 * PF);
+  for (int it0 = 0; it0 < niter4; it0 += 2 * PF) {
     MADAKV_STEP(pre0, it0)
     MADAKV_STEP(pre1, it0 + 1)
+    MADAKV_STEP(pre0, it0 + 2)
+    MADAKV_STEP(pre1, it0 + 3)
   }
 #undef MADAKV_STEP
 #undef MADAKV_LOAD_SUB
@@ -343,6 +349,7 @@ __global__ __launch_bounds__(SCORE_THREADS) void score_simple_kernel(ScoreArgs a
 static bool use_mfma(const Dims& dm, int dtype) { return dtype == MADAKV_BF16 && (dm.d == 64 || dm.d == 128); }
 
 ScorePlan score_plan(const Dims& dm, int dtype) {
+  (void)dtype;
   ScorePlan p;
   p.mpad = (dm.M + 31) / 32 * 32;
   // Both sweeps run over all heads of the call in one launch each, at most 65535 heads at a

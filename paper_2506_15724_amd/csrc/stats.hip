@@ -25,7 +25,7 @@ constexpr float PSI_MAX = 256.0f;                // G * W <= 256 bounds any colu
 
 struct StatsArgs {
   const float* psi; const uint8_t* mask; float* psi_pool; void* stats; int32_t* n_mod;
-  int B, H, L, W, nc, pool_r, layer0, mpa_mode, pool_mode, share_mode, M;
+  int B, H, L, W, nc, pool_r, pool_mode, share_mode, M;
   double theta;
 };
 
@@ -287,7 +287,8 @@ hipError_t launch_stats(const Dims& dm, const madakv_config& c, const float* psi
   StatsArgs a;
   a.psi = psi; a.mask = mask; a.psi_pool = psi_pool; a.stats = stats; a.n_mod = n_mod;
   a.B = dm.B; a.H = dm.H; a.L = dm.L; a.W = dm.W; a.nc = dm.nc; a.pool_r = (c.pool_k - 1) / 2;
-  a.layer0 = layer0; a.mpa_mode = c.mpa_mode; a.pool_mode = c.pool_mode; a.share_mode = c.share_mode; a.theta = (double)c.theta;
+  (void)layer0;
+  a.pool_mode = c.pool_mode; a.share_mode = c.share_mode; a.theta = (double)c.theta;
   a.M = c.n_modalities;
   const size_t lds = (size_t)a.M * BINS * (sizeof(unsigned long long) + sizeof(uint32_t));
   if (a.M == 2) {
