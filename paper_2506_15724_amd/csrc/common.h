@@ -124,6 +124,29 @@ __device__ __forceinline__ long long wave_sum_i64(long long v) {
   return v;
 }
 
+// Inclusive prefix sum over the 64 lanes (lane 0 first) with DPP row operations: shifts by 1, 2, 4, 8
+// inside each row of 16 lanes, then the last lane of row 0 / 2 is added to row 1 / 3 and the last
+// lane of row 1 to rows 2 and 3.
+__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t x) {
+#define MADAKV_DPP_ADD(ctrl, rmask, bctl) \
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, ctrl, rmask, 0xF, bctl)
+  MADAKV_DPP_ADD(0x111, 0xF, true);   // row_shr:1
+  MADAKV_DPP_ADD(0x112, 0xF, true);   // row_shr:2
+  MADAKV_DPP_ADD(0x114, 0xF, true);   // row_shr:4
+  MADAKV_DPP_ADD(0x118, 0xF, true);   // row_shr:8
+  MADAKV_DPP_ADD(0x142, 0xA, false);  // row_bcast:15 into rows 1 and 3
+  MADAKV_DPP_ADD(0x143, 0xC, false);  // row_bcast:31 into rows 2 and 3
+#undef MADAKV_DPP_ADD
+  return x;
+}
+// the same for 64-bit values below 2^63 / 64, as three 21-bit limbs (no carries between lanes' limbs)
+__device__ __forceinline__ unsigned long long wave_incl_scan_u63(unsigned long long v) {
+  const uint32_t l0 = wave_incl_scan_u32((uint32_t)(v & 0x1fffffULL));
+  const uint32_t l1 = wave_incl_scan_u32((uint32_t)((v >> 21) & 0x1fffffULL));
+  const uint32_t l2 = wave_incl_scan_u32((uint32_t)(v >> 42));
+  return (unsigned long long)l0 + ((unsigned long long)l1 << 21) + ((unsigned long long)l2 << 42);
+}
+
 // Order-preserving map float -> uint32 (larger float, larger key); -0 is folded onto +0.
 __device__ __forceinline__ uint32_t float_key(float f) {
   f += 0.0f;

@@ -281,13 +281,13 @@ __global__ __launch_bounds__(SEL_THREADS) __attribute__((amdgpu_waves_per_eu(MM 
       const int m = wave;
       const int nb = 1 << wd;
       const int per = (nb + 63) / 64;
+      // lane l owns the `per` bins below nb - l * per; it sums them starting at a lane-dependent
+      // offset so that the 64 lanes read different LDS banks
       uint32_t lc = 0;
-      for (int j = 0; j < per; ++j) { int bin = nb - 1 - (lane * per + j); if (bin >= 0) lc += cnt[m][bin]; }
-      uint32_t incl = lc;
-      for (int o = 1; o < 64; o <<= 1) {
-        uint32_t t = (uint32_t)__shfl((int)incl, max(lane - o, 0), 64);
-        if (lane >= o) incl += t;
-      }
+#pragma unroll
+      for (int j = 0; j < 32; ++j)
+        if (j < per) lc += cnt[m][nb - 1 - (lane * per + ((j + lane) & (per - 1)))];
+      const uint32_t incl = wave_incl_scan_u32(lc);
       uint32_t need, prefix_prev; bool done;
       if (level == 0) {
         const uint32_t ntot = (uint32_t)__shfl((int)incl, 63, 64);
@@ -300,19 +300,20 @@ __global__ __launch_bounds__(SEL_THREADS) __attribute__((amdgpu_waves_per_eu(MM 
         need = s_need[m]; prefix_prev = s_prefix[m]; done = s_done[m] != 0;
       }
       const uint32_t before = incl - lc;          // elements in higher bins than this lane's
-      const bool mine = !done && before < need && before + lc >= need;
-      if (mine) {
-        uint32_t acc = before;
-        for (int j = 0; j < per; ++j) {
-          int bin = nb - 1 - (lane * per + j);
-          if (bin < 0) break;
-          uint32_t cc = cnt[m][bin];
-          if (acc + cc >= need) {
-            s_prefix[m] = (prefix_prev << wd) | (uint32_t)bin;
-            s_need[m] = need - acc;               // still needed from inside this bin
-            break;
-          }
-          acc += cc;
+      const unsigned long long owner = __ballot(!done && before < need && before + lc >= need);
+      if (owner) {
+        // the owner's bins, one per lane, scanned the same way: the bin where the count reaches `need`
+        const int src = __ffsll((long long)owner) - 1;
+        const uint32_t bsrc = (uint32_t)__shfl((int)before, src, 64);
+        const uint32_t v = lane < per ? cnt[m][nb - 1 - (src * per + lane)] : 0u;
+        const uint32_t inc2 = wave_incl_scan_u32(v);
+        const uint32_t bef2 = bsrc + inc2 - v;
+        const unsigned long long hit = __ballot(lane < per && bef2 < need && bef2 + v >= need);
+        const int hl = __ffsll((long long)hit) - 1;
+        const uint32_t acc = (uint32_t)__shfl((int)bef2, hl, 64);
+        if (lane == 0) {
+          s_prefix[m] = (prefix_prev << wd) | (uint32_t)(nb - 1 - (src * per + hl));
+          s_need[m] = need - acc;                   // still needed from inside this bin
         }
       }
     }

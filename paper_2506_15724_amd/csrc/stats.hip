@@ -207,18 +207,19 @@ __global__ __launch_bounds__(STATS_THREADS) __attribute__((amdgpu_waves_per_eu(4
       const int m = wave;
       const int nb = 1 << wd;
       const int per = (nb + 63) / 64;                 // bins per lane; lane 0 owns the top bins
+      // lane l owns the `per` bins below nb - l * per; it sums them starting at a lane-dependent
+      // offset so that the 64 lanes read different LDS banks
       unsigned long long ls = 0ULL; uint32_t lc = 0;
-      for (int j = 0; j < per; ++j) {
-        int bin = nb - 1 - (lane * per + j);
-        if (bin >= 0) { ls += sum[m * BINS + bin]; lc += cnt[m * BINS + bin]; }
+#pragma unroll
+      for (int j = 0; j < 32; ++j) {
+        if (j < per) {
+          const int bin = nb - 1 - (lane * per + ((j + lane) & (per - 1)));
+          ls += sum[m * BINS + bin]; lc += cnt[m * BINS + bin];
+        }
       }
-      // inclusive scan over lanes (lane 0 first)
-      unsigned long long ss = ls; uint32_t sc = lc;
-      for (int o = 1; o < 64; o <<= 1) {
-        unsigned long long ts = (unsigned long long)shfl_i64((long long)ss, max(lane - o, 0));
-        uint32_t tc = (uint32_t)__shfl((int)sc, max(lane - o, 0), 64);
-        if (lane >= o) { ss += ts; sc += tc; }
-      }
+      // inclusive scan over lanes (lane 0 first); a head's masses stay below 2^52
+      const unsigned long long ss = wave_incl_scan_u63(ls);
+      const uint32_t sc = wave_incl_scan_u32(lc);
       // totals, target and the state carried from the level above; at level 0 every lane
       // derives them from the scan, later levels read what was stored before the barrier
       unsigned long long target, base_s; uint32_t base_c, prefix_prev; bool done;
@@ -240,20 +241,24 @@ __global__ __launch_bounds__(STATS_THREADS) __attribute__((amdgpu_waves_per_eu(4
       }
       // the lane whose bins contain the crossing: mass before its bins < target <= mass after them
       const unsigned long long before = base_s + ss - ls;
-      const bool mine = !done && (before < target) && (before + ls >= target);
-      if (mine) {
-        unsigned long long acc_s = before; uint32_t acc_c = base_c + sc - lc;
-        for (int j = 0; j < per; ++j) {
-          int bin = nb - 1 - (lane * per + j);
-          if (bin < 0) break;
-          unsigned long long bs = sum[m * BINS + bin];
-          if (acc_s + bs >= target) {
-            s_prefix[m] = (prefix_prev << wd) | (uint32_t)bin;
-            s_sum_gt[m] = acc_s; s_cnt_gt[m] = acc_c;
-            s_binsum[m] = bs; s_bincnt[m] = cnt[m * BINS + bin];
-            break;
-          }
-          acc_s += bs; acc_c += cnt[m * BINS + bin];
+      const unsigned long long owner = __ballot(!done && (before < target) && (before + ls >= target));
+      if (owner) {
+        // the owner's bins, one per lane, scanned the same way: the bin where the mass reaches the target
+        const int src = __ffsll((long long)owner) - 1;
+        const unsigned long long bs0 = (unsigned long long)shfl_i64((long long)before, src);
+        const uint32_t bc0 = base_c + (uint32_t)__shfl((int)(sc - lc), src, 64);
+        const int bin = nb - 1 - (src * per + min(lane, per - 1));
+        const unsigned long long vs = lane < per ? sum[m * BINS + bin] : 0ULL;
+        const uint32_t vc = lane < per ? cnt[m * BINS + bin] : 0u;
+        const unsigned long long is = wave_incl_scan_u63(vs);
+        const uint32_t ic = wave_incl_scan_u32(vc);
+        const unsigned long long bef = bs0 + is - vs;
+        const unsigned long long hit = __ballot(lane < per && bef < target && bef + vs >= target);
+        const int hl = __ffsll((long long)hit) - 1;
+        if (lane == hl) {
+          s_prefix[m] = (prefix_prev << wd) | (uint32_t)bin;
+          s_sum_gt[m] = bef; s_cnt_gt[m] = bc0 + ic - vc;
+          s_binsum[m] = vs; s_bincnt[m] = vc;
         }
       }
     }
