@@ -183,6 +183,19 @@ int32_t madakv_select_gather(madakv_handle* h, int32_t layer0, int32_t n,
                              void* k_c, void* v_c,
                              void* ws, size_t ws_bytes, void* stream);
 
+/* madakv_score + madakv_allocate + madakv_select_gather for layers [layer0, layer0 + n) in one call,
+ * with the same arguments and the same results bit for bit.  A call over four or more layers is
+ * cut into four layer groups: the statistics, allocation and selection of a group run on a side
+ * stream under the score passes of the following groups, the gathers follow on the caller's
+ * stream.  Keep-all configurations (budget >= ctx_len) have nothing to score: use
+ * madakv_select_gather for them.  score_ws / select_ws: at least what madakv_workspace_bytes
+ * reports for n layers. */
+int32_t madakv_evict(madakv_handle* h, int32_t layer0, int32_t n,
+                     const void* q_win, const void* k, const void* v, const uint8_t* mask,
+                     float* psi, float* psi_pool, void* stats, int32_t* n_mod, int32_t* budgets,
+                     int32_t* kept_idx, int64_t* kv_off, int32_t* kv_len, void* k_c, void* v_c,
+                     void* score_ws, size_t score_ws_size, void* select_ws, size_t select_ws_size, void* stream);
+
 /* One decode step for layers [layer0, layer0 + n): append k_new, v_new to every head's
  * segment (Eq. 4), then out = softmax(scale * q k_c^T) v_c over the head's rows (Eq. 5).
  *   q        [n, B, Hq, d]

@@ -57,6 +57,7 @@ def lib() -> C.CDLL:
         L.madakv_score_lse.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.madakv_allocate.argtypes = [vp, i32, i32, vp, vp, vp, vp]
         L.madakv_select_gather.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.madakv_evict.argtypes = [vp, i32, i32] + [vp] * 14 + [vp, sz, vp, sz, vp]
         L.madakv_decode_attn.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         for name in EXPORTS:
             getattr(L, name).restype = i32
@@ -65,7 +66,7 @@ def lib() -> C.CDLL:
 
 
 EXPORTS = ["madakv_create", "madakv_destroy", "madakv_last_hip_error", "madakv_workspace_bytes",
-           "madakv_compact_capacity_tokens", "madakv_score", "madakv_score_lse", "madakv_allocate", "madakv_select_gather",
+           "madakv_compact_capacity_tokens", "madakv_score", "madakv_score_lse", "madakv_allocate", "madakv_select_gather", "madakv_evict",
            "madakv_decode_attn"]
 
 
@@ -127,6 +128,15 @@ def madakv_select_gather(h, layer0, n, psi_pool, mask, budgets, k, v, kept_idx, 
     _check("madakv_select_gather", lib().madakv_select_gather(
         h, layer0, n, _ptr(psi_pool), _ptr(mask), _ptr(budgets), _ptr(k), _ptr(v), _ptr(kept_idx), _ptr(kv_off),
         _ptr(kv_len), _ptr(k_c), _ptr(v_c), _ptr(ws), ws.numel() * ws.element_size(), _stream()))
+
+
+def madakv_evict(h, layer0, n, q_win, k, v, mask, psi, psi_pool, stats, n_mod, budgets, kept_idx, kv_off, kv_len, k_c, v_c,
+                 score_ws, select_ws):
+    _check("madakv_evict", lib().madakv_evict(
+        h, layer0, n, _ptr(q_win), _ptr(k), _ptr(v), _ptr(mask), _ptr(psi), _ptr(psi_pool), _ptr(stats), _ptr(n_mod),
+        _ptr(budgets), _ptr(kept_idx), _ptr(kv_off), _ptr(kv_len), _ptr(k_c), _ptr(v_c),
+        _ptr(score_ws), score_ws.numel() * score_ws.element_size(), _ptr(select_ws),
+        select_ws.numel() * select_ws.element_size(), _stream()))
 
 
 def madakv_decode_attn(h, layer0, n, q, k_new, v_new, k_c, v_c, kv_off, kv_len, out, ws):
@@ -206,6 +216,12 @@ class MadaKV:
                              self._sl(self.budgets, l0, n) if budgets is None else budgets, k, v, self.kept_idx,
                              self._sl(self.kv_off, l0, n), self._sl(self.kv_len, l0, n), self.k_c, self.v_c,
                              self.select_ws)
+
+    def evict(self, l0, n, q_win, k, v, mask):
+        madakv_evict(self.h, l0, n, q_win, k, v, mask, self._sl(self.psi, l0, n), self._sl(self.psi_pool, l0, n),
+                     self._sl(self.stats, l0, n), self.n_mod, self._sl(self.budgets, l0, n), self.kept_idx,
+                     self._sl(self.kv_off, l0, n), self._sl(self.kv_len, l0, n), self.k_c, self.v_c,
+                     self.score_ws, self.select_ws)
 
     def decode_attn(self, l0, n, q, k_new, v_new, out):
         madakv_decode_attn(self.h, l0, n, q, k_new, v_new, self.k_c, self.v_c, self._sl(self.kv_off, l0, n),

@@ -29,7 +29,7 @@ struct madakv_handle {
   // with the latency-bound per-head kernels (statistics, selection) inside one call.  The side
   // stream forks from and joins the caller's stream through events; default priority.
   hipStream_t side;
-  hipEvent_t ev_grp[MAX_GROUPS], ev_fork, ev_join;
+  hipEvent_t ev_grp[MAX_GROUPS], ev_sel[MAX_GROUPS], ev_fork, ev_join;
   int sel_layers_done;             // layers [0, sel_layers_done) have been through select_gather in this pass
 };
 
@@ -97,6 +97,7 @@ void destroy_side(madakv_handle* h) {
   if (h->ev_fork) (void)hipEventDestroy(h->ev_fork);
   if (h->ev_join) (void)hipEventDestroy(h->ev_join);
   for (int g = 0; g < MAX_GROUPS; ++g) if (h->ev_grp[g]) (void)hipEventDestroy(h->ev_grp[g]);
+  for (int g = 0; g < MAX_GROUPS; ++g) if (h->ev_sel[g]) (void)hipEventDestroy(h->ev_sel[g]);
 }
 
 // Layers per group when a call over n layers is cut up for the overlap (1 group below 4 layers).
@@ -125,7 +126,7 @@ int32_t madakv_create(const madakv_config* cfg, madakv_handle** out) {
   h->d_maxlen = nullptr; h->h_maxlen = nullptr; h->maxlen_event = nullptr;
   h->maxlen_pending = false; h->sel_layers_done = 0;
   h->side = nullptr; h->ev_fork = nullptr; h->ev_join = nullptr;
-  for (int g = 0; g < MAX_GROUPS; ++g) h->ev_grp[g] = nullptr;
+  for (int g = 0; g < MAX_GROUPS; ++g) { h->ev_grp[g] = nullptr; h->ev_sel[g] = nullptr; }
   h->appended.assign(cfg->n_layers, 0);
   hipError_t e = hipGetDevice(&h->device);
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&h->d_state), sizeof(long long) * 2 * cfg->batch);
@@ -137,6 +138,7 @@ int32_t madakv_create(const madakv_config* cfg, madakv_handle** out) {
   if (e == hipSuccess) e = hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming);
   if (e == hipSuccess) e = hipEventCreateWithFlags(&h->ev_join, hipEventDisableTiming);
   for (int g = 0; g < MAX_GROUPS && e == hipSuccess; ++g) e = hipEventCreateWithFlags(&h->ev_grp[g], hipEventDisableTiming);
+  for (int g = 0; g < MAX_GROUPS && e == hipSuccess; ++g) e = hipEventCreateWithFlags(&h->ev_sel[g], hipEventDisableTiming);
   if (e != hipSuccess) {
     if (h->d_maxlen) (void)hipFree(h->d_maxlen);
     if (h->h_maxlen) (void)hipHostFree(h->h_maxlen);
@@ -168,7 +170,12 @@ int32_t madakv_workspace_bytes(const madakv_handle* h, int32_t n_layers_per_call
   if (!h || n_layers_per_call < 1 || n_layers_per_call > h->cfg.n_layers) return MADAKV_ERR_INVALID_ARG;
   Dims dm = make_dims(h->cfg, n_layers_per_call);
   if (score_ws) *score_ws = score_ws_for_call(h->cfg, n_layers_per_call);
-  if (select_ws) *select_ws = select_ws_bytes(dm, h->cfg);
+  if (select_ws) {
+    // enough for madakv_select_gather over n layers and for madakv_evict (one slice per layer group)
+    const int gl = group_layers(n_layers_per_call);
+    const size_t slices = ((select_ws_bytes(make_dims(h->cfg, gl), h->cfg) + 255) / 256 * 256) * ((n_layers_per_call + gl - 1) / gl);
+    *select_ws = std::max(select_ws_bytes(dm, h->cfg), slices);
+  }
   if (decode_ws) *decode_ws = decode_ws_bytes(dm, h->cfg);
   return MADAKV_OK;
 }
@@ -274,6 +281,80 @@ int32_t madakv_select_gather(madakv_handle* h, int32_t layer0, int32_t n,
   if (e == hipSuccess) e = launch_gather(dm, c, 0, n, k, v, kept_idx, kv_off, kv_len, k_c, v_c, ws, region, bpb, bpb, st);
   for (int l = layer0; l < layer0 + n; ++l) h->appended[l] = 0;
   // hand the per-layer longest length to the host without waiting for it
+  if (e == hipSuccess) e = hipMemcpyAsync(h->h_maxlen + (size_t)layer0 * c.batch, h->d_maxlen + (size_t)layer0 * c.batch,
+                                             sizeof(int32_t) * n * c.batch, hipMemcpyDeviceToHost, st);
+  if (e == hipSuccess) e = hipEventRecord(h->maxlen_event, st);
+  h->sel_layers_done = (e == hipSuccess) ? layer0 + n : 0;
+  h->maxlen_pending = true;
+  return hip_fail(h, e);
+}
+
+int32_t madakv_evict(madakv_handle* h, int32_t layer0, int32_t n,
+                     const void* q_win, const void* k, const void* v, const uint8_t* mask,
+                     float* psi, float* psi_pool, void* stats, int32_t* n_mod, int32_t* budgets,
+                     int32_t* kept_idx, int64_t* kv_off, int32_t* kv_len, void* k_c, void* v_c,
+                     void* score_ws, size_t score_ws_size, void* select_ws, size_t select_ws_size, void* stream) {
+  int32_t r = check_range(h, layer0, n);
+  if (r != MADAKV_OK) return r;
+  const madakv_config& c = h->cfg;
+  if (bad_ptr(q_win) || bad_ptr(k) || bad_ptr(v) || bad_ptr(mask, 1) || bad_ptr(psi, 4) || bad_ptr(psi_pool, 4) ||
+      bad_ptr(stats, 4) || bad_ptr(n_mod, 4) || bad_ptr(budgets, 4) || bad_ptr(kept_idx, 4) || bad_ptr(kv_off, 8) ||
+      bad_ptr(kv_len, 4) || bad_ptr(k_c) || bad_ptr(v_c) || bad_ptr(score_ws) || bad_ptr(select_ws))
+    return MADAKV_ERR_INVALID_ARG;
+  const int gl = group_layers(n);
+  const int ngroups = (n + gl - 1) / gl;
+  // every layer group gets its own slice of the selection workspace (its block table is still in
+  // use by its gather while the next group's table is being written)
+  const size_t sel_slice = (select_ws_bytes(make_dims(c, gl), c) + 255) / 256 * 256;
+  if (score_ws_size < score_ws_for_call(c, n) || select_ws_size < sel_slice * ngroups) return MADAKV_ERR_WORKSPACE_TOO_SMALL;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  const bool overlap = ngroups > 1;
+  const size_t es = c.dtype == MADAKV_BF16 ? 2 : 4;
+  const long long region = region_tokens(c);
+  const size_t M = (size_t)c.n_modalities;
+  hipError_t e = hipSuccess;
+  // Caller's stream: the score sweeps of every group, then the gathers.  Side stream: statistics,
+  // allocation, segment layout and selection of a group, as soon as its sweeps are done, under the
+  // sweeps of the following groups (these kernels are latency- and LDS-bound, the sweeps HBM-bound).
+  int gi = 0;
+  for (int g0 = 0; g0 < n && e == hipSuccess; g0 += gl, ++gi) {
+    const int ng = std::min(gl, n - g0);
+    Dims dg = make_dims(c, ng);
+    const size_t lb = (size_t)g0 * c.batch, heads0 = lb * c.n_kv_heads;
+    const char* qg = static_cast<const char*>(q_win) + lb * c.n_q_heads * c.window * c.head_dim * es;
+    const char* kg = static_cast<const char*>(k) + heads0 * (size_t)c.ctx_len * c.head_dim * es;
+    float* psi_g = psi + heads0 * (size_t)c.ctx_len;
+    float* pool_g = psi_pool + heads0 * (size_t)(c.ctx_len - c.window);
+    char* stats_g = static_cast<char*>(stats) + heads0 * 8 * M;
+    int32_t* bud_g = budgets + heads0 * M;
+    char* ws_g = static_cast<char*>(select_ws) + sel_slice * gi;
+    e = launch_score(dg, c, qg, kg, nullptr, psi_g, score_ws, st);
+    hipStream_t ss = st;
+    if (overlap && e == hipSuccess) {
+      e = hipEventRecord(h->ev_grp[gi], st);
+      if (e == hipSuccess) e = hipStreamWaitEvent(h->side, h->ev_grp[gi], 0);
+      ss = h->side;
+    }
+    if (e == hipSuccess) e = launch_stats(dg, c, psi_g, mask, pool_g, stats_g, g0 == 0 ? n_mod : nullptr, layer0 + g0, ss);
+    if (e == hipSuccess) e = launch_allocate(dg, c, layer0 + g0, stats_g, n_mod, bud_g, h->d_state, ss);
+    if (e == hipSuccess) e = launch_offsets(dg, c, layer0 + g0, bud_g, kv_off + heads0, kv_len + heads0, h->d_state + c.batch,
+                                            h->d_maxlen + (size_t)(layer0 + g0) * c.batch, ws_g, region, blocks_per_batch(c, ng), ss);
+    if (e == hipSuccess) e = launch_select(dg, c, pool_g, mask, bud_g, kv_off + heads0, kv_len + heads0, kept_idx, ss);
+    if (overlap && e == hipSuccess) e = hipEventRecord(h->ev_sel[gi], h->side);
+  }
+  gi = 0;
+  for (int g0 = 0; g0 < n && e == hipSuccess; g0 += gl, ++gi) {
+    const int ng = std::min(gl, n - g0);
+    Dims dg = make_dims(c, ng);
+    const size_t heads0 = (size_t)g0 * c.batch * c.n_kv_heads;
+    const char* kg = static_cast<const char*>(k) + heads0 * (size_t)c.ctx_len * c.head_dim * es;
+    const char* vg = static_cast<const char*>(v) + heads0 * (size_t)c.ctx_len * c.head_dim * es;
+    const char* ws_g = static_cast<const char*>(select_ws) + sel_slice * gi;
+    if (overlap) e = hipStreamWaitEvent(st, h->ev_sel[gi], 0);
+    const int bpb = blocks_per_batch(c, ng);
+    if (e == hipSuccess) e = launch_gather(dg, c, 0, ng, kg, vg, kept_idx, kv_off + heads0, kv_len + heads0, k_c, v_c, ws_g, region, bpb, bpb, st);
+  }
+  for (int l = layer0; l < layer0 + n; ++l) h->appended[l] = 0;
   if (e == hipSuccess) e = hipMemcpyAsync(h->h_maxlen + (size_t)layer0 * c.batch, h->d_maxlen + (size_t)layer0 * c.batch,
                                              sizeof(int32_t) * n * c.batch, hipMemcpyDeviceToHost, st);
   if (e == hipSuccess) e = hipEventRecord(h->maxlen_event, st);

@@ -786,3 +786,35 @@ def test_widest_shapes():
     wl = WL.CONFIGS["llava_layer"].scaled(name="g8", n_layers=1, batch=2, n_q_heads=16, n_kv_heads=2, head_dim=128,
                                           ctx_len=1300, window=32, budget=200, n_images=1)
     _run_and_check_whole_path(wl)
+
+
+@pytest.mark.parametrize("nl", [3, 6, 9])
+def test_fused_eviction_call_matches_the_three_calls(nl):
+    """madakv_evict (pipelined over layer groups on two streams) against score + allocate + select_gather."""
+    wl = small_workloads()["bf16_mha"].scaled(n_layers=nl, batch=2, ctx_len=1900)
+    NL = wl.n_layers
+    q, k, v, mask, masks = PU.make_inputs(wl, DEV)
+    a = engine(wl)
+    a.score(0, NL, q, k, mask); a.allocate(0, NL); a.select_gather(0, NL, k, v, mask)
+    torch.cuda.synchronize()
+    b = engine(wl)
+    for rep in range(2):                                    # twice: the handle's streams and carries are reused
+        say(f"madakv_evict over {NL} layers, pass {rep}")
+        b.evict(0, NL, q, k, v, mask)
+        torch.cuda.synchronize()
+        for name in ("psi", "psi_pool", "stats", "n_mod", "budgets", "kv_off", "kv_len"):
+            assert torch.equal(getattr(a, name), getattr(b, name)), name
+        off, ln = a.kv_off.cpu().numpy(), a.kv_len.cpu().numpy()
+        for l in range(NL):
+            for bb in range(wl.batch):
+                for h in range(wl.n_kv_heads):
+                    o, n = off[l, bb, h], ln[l, bb, h]
+                    assert torch.equal(a.kept_idx[o:o + n], b.kept_idx[o:o + n])
+                    assert torch.equal(a.k_c[o:o + n], b.k_c[o:o + n]) and torch.equal(a.v_c[o:o + n], b.v_c[o:o + n])
+    # decode right after the fused call (sized from the lengths it handed to the host)
+    dq, dk, dv = WL.decode_inputs_all(wl, 0, DEV)
+    oa = torch.empty(NL, wl.batch, wl.n_q_heads, wl.head_dim, dtype=torch.float32, device=DEV); ob = torch.empty_like(oa)
+    a.decode_attn(0, NL, dq, dk, dv, oa); b.decode_attn(0, NL, dq, dk, dv, ob)
+    torch.cuda.synchronize()
+    assert torch.equal(oa, ob)
+    a.close(); b.close()
