@@ -101,12 +101,31 @@ void destroy_side(madakv_handle* h) {
 }
 
 // Layers per group when a call over n layers is cut up for the overlap (1 group below 4 layers).
-int group_layers(int n) { return n >= MAX_GROUPS ? (n + MAX_GROUPS - 1) / MAX_GROUPS : n; }
+// A call over n >= 4 layers is cut into MAX_GROUPS layer groups for the overlap: a short last group
+// (its statistics / selection have nothing to hide under) and the rest split evenly.  Fills
+// begin[0 .. groups] and returns the number of groups.
+int layer_groups(int n, int* begin) {
+  if (n < MAX_GROUPS) { begin[0] = 0; begin[1] = n; return 1; }
+  const int last = std::max(1, n / 16);
+  const int rest = n - last;
+  begin[0] = 0;
+  for (int g = 1; g < MAX_GROUPS; ++g) begin[g] = (int)((long long)rest * g / (MAX_GROUPS - 1));
+  begin[MAX_GROUPS] = n;
+  return MAX_GROUPS;
+}
+int largest_group(int n) {
+  int b[MAX_GROUPS + 1];
+  const int ng = layer_groups(n, b);
+  int m = 0;
+  for (int g = 0; g < ng; ++g) m = std::max(m, b[g + 1] - b[g]);
+  return m;
+}
 
 size_t score_ws_for_call(const madakv_config& c, int n) {
-  const int gl = group_layers(n);
-  size_t need = score_ws_bytes(make_dims(c, gl), c.dtype);
-  if (n % gl) need = std::max(need, score_ws_bytes(make_dims(c, n % gl), c.dtype));
+  int b[MAX_GROUPS + 1];
+  const int ng = layer_groups(n, b);
+  size_t need = 0;
+  for (int g = 0; g < ng; ++g) need = std::max(need, score_ws_bytes(make_dims(c, b[g + 1] - b[g]), c.dtype));
   return need;
 }
 
@@ -172,8 +191,8 @@ int32_t madakv_workspace_bytes(const madakv_handle* h, int32_t n_layers_per_call
   if (score_ws) *score_ws = score_ws_for_call(h->cfg, n_layers_per_call);
   if (select_ws) {
     // enough for madakv_select_gather over n layers and for madakv_evict (one slice per layer group)
-    const int gl = group_layers(n_layers_per_call);
-    const size_t slices = ((select_ws_bytes(make_dims(h->cfg, gl), h->cfg) + 255) / 256 * 256) * ((n_layers_per_call + gl - 1) / gl);
+    const int gl = largest_group(n_layers_per_call);
+    const size_t slices = ((select_ws_bytes(make_dims(h->cfg, gl), h->cfg) + 255) / 256 * 256) * MAX_GROUPS;
     *select_ws = std::max(select_ws_bytes(dm, h->cfg), slices);
   }
   if (decode_ws) *decode_ws = decode_ws_bytes(dm, h->cfg);
@@ -199,13 +218,14 @@ static int32_t score_impl(madakv_handle* h, int32_t layer0, int32_t n,
   const madakv_config& c = h->cfg;
   // The call is cut into up to MAX_GROUPS layer groups: the score sweeps of a group run on the
   // caller's stream, its statistics on the side stream, under the sweeps of the next group.
-  const int gl = group_layers(n);
-  const bool overlap = gl < n;
+  int gb[MAX_GROUPS + 1];
+  const int ngroups = layer_groups(n, gb);
+  const bool overlap = ngroups > 1;
   const size_t es = c.dtype == MADAKV_BF16 ? 2 : 4;
   hipError_t e = hipSuccess;
-  int gi = 0;
-  for (int g0 = 0; g0 < n && e == hipSuccess; g0 += gl, ++gi) {
-    Dims dg = make_dims(c, std::min(gl, n - g0));
+  for (int gi = 0; gi < ngroups && e == hipSuccess; ++gi) {
+    const int g0 = gb[gi];
+    Dims dg = make_dims(c, gb[gi + 1] - g0);
     const size_t lb = (size_t)g0 * c.batch;                        // (layer, batch) pairs before the group
     const char* qg = static_cast<const char*>(q_win) + lb * c.n_q_heads * c.window * c.head_dim * es;
     const char* kg = static_cast<const char*>(k) + lb * c.n_kv_heads * (size_t)c.ctx_len * c.head_dim * es;
@@ -301,8 +321,9 @@ int32_t madakv_evict(madakv_handle* h, int32_t layer0, int32_t n,
       bad_ptr(stats, 4) || bad_ptr(n_mod, 4) || bad_ptr(budgets, 4) || bad_ptr(kept_idx, 4) || bad_ptr(kv_off, 8) ||
       bad_ptr(kv_len, 4) || bad_ptr(k_c) || bad_ptr(v_c) || bad_ptr(score_ws) || bad_ptr(select_ws))
     return MADAKV_ERR_INVALID_ARG;
-  const int gl = group_layers(n);
-  const int ngroups = (n + gl - 1) / gl;
+  int gb[MAX_GROUPS + 1];
+  const int ngroups = layer_groups(n, gb);
+  const int gl = largest_group(n);
   // every layer group gets its own slice of the selection workspace (its block table is still in
   // use by its gather while the next group's table is being written)
   const size_t sel_slice = (select_ws_bytes(make_dims(c, gl), c) + 255) / 256 * 256;
@@ -316,9 +337,8 @@ int32_t madakv_evict(madakv_handle* h, int32_t layer0, int32_t n,
   // Caller's stream: the score sweeps of every group, then the gathers.  Side stream: statistics,
   // allocation, segment layout and selection of a group, as soon as its sweeps are done, under the
   // sweeps of the following groups (these kernels are latency- and LDS-bound, the sweeps HBM-bound).
-  int gi = 0;
-  for (int g0 = 0; g0 < n && e == hipSuccess; g0 += gl, ++gi) {
-    const int ng = std::min(gl, n - g0);
+  for (int gi = 0; gi < ngroups && e == hipSuccess; ++gi) {
+    const int g0 = gb[gi], ng = gb[gi + 1] - g0;
     Dims dg = make_dims(c, ng);
     const size_t lb = (size_t)g0 * c.batch, heads0 = lb * c.n_kv_heads;
     const char* qg = static_cast<const char*>(q_win) + lb * c.n_q_heads * c.window * c.head_dim * es;
@@ -342,9 +362,8 @@ int32_t madakv_evict(madakv_handle* h, int32_t layer0, int32_t n,
     if (e == hipSuccess) e = launch_select(dg, c, pool_g, mask, bud_g, kv_off + heads0, kv_len + heads0, kept_idx, ss);
     if (overlap && e == hipSuccess) e = hipEventRecord(h->ev_sel[gi], h->side);
   }
-  gi = 0;
-  for (int g0 = 0; g0 < n && e == hipSuccess; g0 += gl, ++gi) {
-    const int ng = std::min(gl, n - g0);
+  for (int gi = 0; gi < ngroups && e == hipSuccess; ++gi) {
+    const int g0 = gb[gi], ng = gb[gi + 1] - g0;
     Dims dg = make_dims(c, ng);
     const size_t heads0 = (size_t)g0 * c.batch * c.n_kv_heads;
     const char* kg = static_cast<const char*>(k) + heads0 * (size_t)c.ctx_len * c.head_dim * es;
