@@ -31,6 +31,7 @@ struct ScoreArgs {
   float* sink;         // 32 floats nobody reads: keeps the psi store of sweep 2 unconditional (both half-waves
                        // store the same value; a store under a branch makes the load waits pessimistic)
   int H, G, d, L, W, M, mpad, nsplit, chunk;
+  int nmerge;          // chunks whose row statistics sweep 2 still has to merge (1 after score_combine_kernel)
   int head0;           // first head of this launch (grid.y indexes head0 + y)
   float scale_log2;    // softmax scale * log2(e)
 };
@@ -133,7 +134,7 @@ __global__ __launch_bounds__(SCORE_THREADS) void score_mfma_kernel(ScoreArgs a) 
       if (a.lse) {                                               // the caller's prefill attention already has the row normalisers
         if (r < a.M) { m = a.lse[(lb * a.H + kvh) * (long long)a.G * a.W + r] * 1.4426950408889634f; l = 1.f; }
       } else {
-        for (int s = 0; s < a.nsplit; ++s) merge_ml(m, l, rs[(s * a.mpad + r) * 2], rs[(s * a.mpad + r) * 2 + 1]);
+        for (int s = 0; s < a.nmerge; ++s) merge_ml(m, l, rs[(s * a.mpad + r) * 2], rs[(s * a.mpad + r) * 2 + 1]);
       }
       offs[r] = (r < a.M) ? m + log2f(l) : __builtin_inff();     // padding rows contribute exp2(-inf) = 0
     }
@@ -303,7 +304,7 @@ __global__ __launch_bounds__(SCORE_THREADS) void score_simple_kernel(ScoreArgs a
     for (int r = tid; r < a.M; r += SCORE_THREADS) {
       float m = NEG_BIG, l = 0.f;
       if (a.lse) { m = a.lse[(lb * a.H + kvh) * (long long)a.G * a.W + r] * 1.4426950408889634f; l = 1.f; }
-      else for (int s = 0; s < a.nsplit; ++s) merge_ml(m, l, rs[(s * a.mpad + r) * 2], rs[(s * a.mpad + r) * 2 + 1]);
+      else for (int s = 0; s < a.nmerge; ++s) merge_ml(m, l, rs[(s * a.mpad + r) * 2], rs[(s * a.mpad + r) * 2 + 1]);
       offs[r] = m + log2f(l);
     }
   }
@@ -346,6 +347,21 @@ __global__ __launch_bounds__(SCORE_THREADS) void score_simple_kernel(ScoreArgs a
 }
 
 // ------------------------------------------------------------------------------------
+// With many chunks per head every sweep-2 workgroup would redo the same merge of the chunks' row
+// statistics: this small kernel does it once per head and leaves the result in the first chunk's slot.
+__global__ __launch_bounds__(256) void score_combine_kernel(ScoreArgs a) {
+  const int head = a.head0 + blockIdx.x;
+  float* rs = a.rowstat + (long long)head * a.nsplit * a.mpad * 2;
+  for (int r = threadIdx.x; r < a.mpad; r += blockDim.x) {
+    float m = NEG_BIG, l = 0.f;
+    for (int s = 0; s < a.nsplit; ++s) merge_ml(m, l, rs[(s * a.mpad + r) * 2], rs[(s * a.mpad + r) * 2 + 1]);
+    rs[r * 2] = m; rs[r * 2 + 1] = l;
+  }
+}
+
+// chunks per head from which the merge is hoisted out of sweep 2
+constexpr int COMBINE_FROM = 8;
+
 static bool use_mfma(const Dims& dm, int dtype) { return dtype == MADAKV_BF16 && (dm.d == 64 || dm.d == 128); }
 
 ScorePlan score_plan(const Dims& dm, int dtype) {
@@ -383,7 +399,10 @@ static void launch_mfma_pair(const ScoreArgs& a0, int heads, size_t lds1, size_t
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_mfma_kernel<D, WPT, NRB, 2>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
   }
-  if (!a.lse) hipLaunchKernelGGL((score_mfma_kernel<D, WPT, NRB, 1>), grid, dim3(SCORE_THREADS), lds1, st, a);
+  if (!a.lse) {
+    hipLaunchKernelGGL((score_mfma_kernel<D, WPT, NRB, 1>), grid, dim3(SCORE_THREADS), lds1, st, a);
+    if (a.nsplit >= COMBINE_FROM) { hipLaunchKernelGGL(score_combine_kernel, dim3(heads), dim3(256), 0, st, a); a.nmerge = 1; }
+  }
   hipLaunchKernelGGL((score_mfma_kernel<D, WPT, NRB, 2>), grid, dim3(SCORE_THREADS), lds2, st, a);
 }
 
@@ -395,7 +414,7 @@ hipError_t launch_score(const Dims& dm, const madakv_config& c, const void* q_wi
   a.q_win = q_win; a.k = k; a.psi = psi; a.rowstat = reinterpret_cast<float*>(ws);
   a.sink = a.rowstat + (size_t)dm.heads * score_plan(dm, c.dtype).nsplit * score_plan(dm, c.dtype).mpad * 2;
   a.H = dm.H; a.G = dm.G; a.d = dm.d; a.L = dm.L; a.W = dm.W; a.M = dm.M;
-  a.mpad = p.mpad; a.nsplit = p.nsplit; a.chunk = p.chunk; a.head0 = 0;
+  a.mpad = p.mpad; a.nsplit = p.nsplit; a.nmerge = p.nsplit; a.chunk = p.chunk; a.head0 = 0;
   float scale = c.softmax_scale > 0.f ? c.softmax_scale : 1.0f / sqrtf((float)dm.d);
   a.scale_log2 = scale * 1.4426950408889634f;
   for (int h0 = 0; h0 < dm.heads; h0 += p.group_heads) {
