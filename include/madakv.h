@@ -27,8 +27,10 @@
  *     void*, NULL = the null stream).  No call synchronises the device.
  *   - Arguments are validated on the host before anything is enqueued.  Errors
  *     found there leave all outputs untouched.
- *   - The handle owns a few KB of device memory (carry state of the layer
- *     recurrence and cache cursors).  Calls on one handle must not overlap.
+ *   - The handle belongs to the HIP device that was current in madakv_create; that device must
+ *     be current in every later call on it.  It owns a few KB of device memory (carry state of
+ *     the layer recurrence and cache cursors), a little pinned host memory, one extra stream of
+ *     default priority and a few events.  Calls on one handle must not overlap.
  *   - Layers are addressed as a range [layer0, layer0 + n).  Tensor arguments hold
  *     only the n layers of the call, layer-major.  madakv_allocate and
  *     madakv_select_gather carry state from layer to layer and must be called in
