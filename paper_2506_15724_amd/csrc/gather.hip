@@ -98,8 +98,8 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
 #pragma unroll
   for (int it = 0; it < ITERS; ++it) {
     const long long s0 = src[it] >= 0 ? src[it] : 0;     // an in-bounds dummy keeps the load unconditional
-    kv[it] = kin[s0 * LPR + piece];
-    vv[it] = vin[s0 * LPR + piece];
+    kv[it] = __builtin_nontemporal_load(kin + s0 * LPR + piece);     // rows are read once: keep them out of the caches
+    vv[it] = __builtin_nontemporal_load(vin + s0 * LPR + piece);
   }
 #pragma unroll
   for (int it = 0; it < ITERS; ++it) {

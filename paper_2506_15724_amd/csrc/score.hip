@@ -113,7 +113,7 @@ __global__ __launch_bounds__(SCORE_THREADS) void score_mfma_kernel(ScoreArgs a) 
     _Pragma("unroll") for (int i = 0; i < LPS; ++i) {                                            \
       const int idx = i * 64 + lane;                                                             \
       const int lkey = min(lt0 + idx / PPR, a.L - 1); /* past the end: a valid row, masked later */ \
-      DST[i] = *reinterpret_cast<const u32x4_t*>(kg + (long long)lkey * D + (idx % PPR) * 8);      \
+      DST[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(kg + (long long)lkey * D + (idx % PPR) * 8)); \
     }                                                                                            \
   }
   MADAKV_LOAD_SUB(pre0, 0)
