@@ -122,8 +122,8 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
         reinterpret_cast<u32x2_t*>(a.k_c)[dst[it] * LPR + piece] = ko;
         reinterpret_cast<u32x2_t*>(a.v_c)[dst[it] * LPR + piece] = vo;
       } else {
-        kout[dst[it] * LPR + piece] = kv[it];
-        vout[dst[it] * LPR + piece] = vv[it];
+        __builtin_nontemporal_store(kv[it], kout + dst[it] * LPR + piece);
+        __builtin_nontemporal_store(vv[it], vout + dst[it] * LPR + piece);
       }
     }
   }
