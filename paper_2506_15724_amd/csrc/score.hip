@@ -227,7 +227,7 @@ _Pragma("unroll") \
     if (PASS == 2) { \
       colsum += __shfl_xor(colsum, 32, 64); \
       if (WPT == 1) { \
-        { float* dst = (key < chunk1) ? a.psi + ((long long)head * a.L + key) : a.sink + col; *dst = colsum; } \
+        { float* dst = (key < chunk1) ? a.psi + ((long long)head * a.L + key) : a.sink + col; __builtin_nontemporal_store(colsum, dst); } \
       } else { \
         if (half == 0) red[((it & 1) * 4 + wave) * 32 + col] = colsum; \
         __syncthreads(); \
