@@ -77,7 +77,7 @@ __device__ __forceinline__ float half_reduce(float x) {
 }
 
 template <int D, int WPT, int NRB, int PASS>
-__global__ __launch_bounds__(SCORE_THREADS) void score_mfma_kernel(ScoreArgs a) {
+__global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void score_mfma_kernel(ScoreArgs a) {
   constexpr int KS = D / 16;                  // MFMA k-steps
   constexpr int RS = D + 8;                   // bf16 elements per LDS row (16 B pad)
   constexpr int KG = 4 / WPT;                 // key groups
@@ -154,6 +154,11 @@ __global__ __launch_bounds__(SCORE_THREADS) void score_mfma_kernel(ScoreArgs a) 
       off_r[b][j] = (PASS == 2) ? offs[row] : 0.f;
     }
   float* red = fbuf + a.mpad;                  // pass 2, WPT > 1: [2][4][32] partial column sums
+  // with a single row block per wave the Q fragments stay in registers (no LDS reads in the loop)
+  bf16x8_t areg[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks)
+    areg[ks] = *reinterpret_cast<const bf16x8_t*>(qs + (min(wsub, a.mpad / 32 - 1) * 32 + col) * RS + half * (D / 2) + ks * 8);
   const int MB = a.mpad / 32;
 
   // one subtile per step: registers -> LDS tile -> MFMA -> statistics / column sums.
@@ -187,7 +192,7 @@ _Pragma("unroll") \
         const uint16_t* qrow = qs + (rb * 32 + col) * RS + half * (D / 2); \
 _Pragma("unroll") \
         for (int ks = 0; ks < KS; ++ks) { \
-          bf16x8_t afrag = *reinterpret_cast<const bf16x8_t*>(qrow + ks * 8); \
+          const bf16x8_t afrag = (NRB == 1) ? areg[ks] : *reinterpret_cast<const bf16x8_t*>(qrow + ks * 8); \
           acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag[ks], acc, 0, 0, 0); \
         } \
         if (!tail) { \
