@@ -9,9 +9,14 @@
 // can still get between beta_floor and n_cand tokens per head; the last layer draws what is
 // left.  Heads share the layer total by largest remainder (ties to the lower head), scaled
 // by demand when it has to shrink and by head-room when it has to grow.  All cross-head
-// sums and ranks are wavefront shuffles; arithmetic is 64-bit integer except the one
-// double multiply of the Eq. 8 share.
+// sums and ranks are wavefront shuffles; arithmetic is 64-bit integer except the double
+// multiply (and, with more than two modalities, the subtraction) of the Eq. 8 share.  Those
+// must round after every operation, as the reference arithmetic does: a fused multiply-add
+// keeps the exact product and changes which of two nearly equal fractional parts is the
+// larger, so contraction is switched off for this file.
 #include "common.h"
+
+#pragma clang fp contract(off)
 
 namespace madakv {
 

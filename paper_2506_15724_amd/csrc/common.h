@@ -26,7 +26,8 @@ ScorePlan score_plan(const Dims& dm, int dtype);
 DecodePlan decode_plan(const Dims& dm, const madakv_config& c, int longest_rows);
 size_t score_ws_bytes(const Dims& dm, int dtype);
 size_t select_ws_bytes(const Dims& dm, const madakv_config& c);
-size_t decode_ws_bytes(const Dims& dm, const madakv_config& c);
+size_t decode_ws_bytes(const Dims& dm, const madakv_config& c);                             // worst case over head lengths
+size_t decode_ws_bytes_for(const Dims& dm, const madakv_config& c, int longest_rows);     // for a known longest head
 
 // Each launcher validates nothing: shapes were checked by the ABI layer.
 hipError_t launch_score(const Dims& dm, const madakv_config& c, const void* q_win, const void* k, const float* row_lse,

@@ -13,9 +13,12 @@
 // exit at once, and since the chunk index is the slow grid dimension they are dispatched
 // after all the real work.  A second, small kernel merges the partial (max, sum, acc) triples
 // of each head in chunk order.  (Merging inside the first kernel by the last workgroup to
-// arrive needs device-scope fences, which write back and invalidate the whole L2 of an XCD
-// per workgroup: measured 15x slower here.)  A call over >= 1024 heads gives every head one
-// workgroup and needs no merge.  The appended row is taken from k_new / v_new by the
+// arrive was measured twice and lost both times: with device-scope fences, which write back and
+// invalidate the whole L2 of an XCD per workgroup, 15x slower; with fence-free agent-scope
+// atomic stores / loads of the partials and one arrival counter per head, 10% slower per call
+// on 128 heads of ~2K rows and 4x slower on 32 heads of ~4K rows: every workgroup then ends in
+// a store acknowledgement plus an atomic round trip, and the last one adds a dependent read.)
+// The appended row is taken from k_new / v_new by the
 // workgroup whose chunk holds it, which also stores it in the cache; kv_len is bumped by
 // whoever finalises the head.
 #include "common.h"
@@ -619,10 +622,11 @@ DecodePlan decode_plan(const Dims& dm, const madakv_config& c, int longest_rows)
   return p;
 }
 
-size_t decode_ws_bytes(const Dims& dm, const madakv_config& c) {
-  DecodePlan p = decode_plan(dm, c, c.ctx_len + c.max_new_tokens);
+size_t decode_ws_bytes_for(const Dims& dm, const madakv_config& c, int longest_rows) {
+  DecodePlan p = decode_plan(dm, c, longest_rows);
   return (size_t)dm.heads * p.max_chunks * dm.G * (dm.d + 2) * sizeof(float) + 64;
 }
+size_t decode_ws_bytes(const Dims& dm, const madakv_config& c) { return decode_ws_bytes_for(dm, c, c.ctx_len + c.max_new_tokens); }
 
 template <typename T, typename CT, int LPR>
 static hipError_t launch_decode_t(const Dims& dm, DecodeArgs& a, hipStream_t st) {

@@ -24,13 +24,15 @@ struct madakv_handle {
   int32_t* d_maxlen;
   int32_t* h_maxlen;
   hipEvent_t maxlen_event;
-  bool maxlen_pending;
+  // per layer: 0 = nothing known (decode sizes its grid for the worst case), 1 = copy enqueued on
+  // maxlen_stream and covered by maxlen_event, 2 = the value in h_maxlen has landed
+  std::vector<uint8_t> maxlen_state;
+  hipStream_t maxlen_stream;
   // Side stream and events for the overlap of the bandwidth-bound kernels (score sweeps, gather)
   // with the latency-bound per-head kernels (statistics, selection) inside one call.  The side
   // stream forks from and joins the caller's stream through events; default priority.
   hipStream_t side;
   hipEvent_t ev_grp[MAX_GROUPS], ev_sel[MAX_GROUPS], ev_fork, ev_join;
-  int sel_layers_done;             // layers [0, sel_layers_done) have been through select_gather in this pass
 };
 
 namespace {
@@ -129,6 +131,78 @@ size_t score_ws_for_call(const madakv_config& c, int n) {
   return need;
 }
 
+// Hands the longest segment of layers [layer0, layer0 + n) to the host without waiting: an
+// asynchronous copy into pinned memory plus an event.  A new pass (layer0 == 0) forgets what was
+// known about every layer; a failed enqueue leaves the layers of the call unknown.
+hipError_t publish_maxlen(madakv_handle* h, int layer0, int n, hipStream_t st, hipError_t e) {
+  const madakv_config& c = h->cfg;
+  if (layer0 == 0) std::fill(h->maxlen_state.begin(), h->maxlen_state.end(), (uint8_t)0);
+  // copies still in flight on another stream are not covered by the event recorded below
+  if (h->maxlen_stream != st)
+    for (auto& sflag : h->maxlen_state) if (sflag == 1) sflag = 0;
+  for (int l = layer0; l < layer0 + n; ++l) h->maxlen_state[l] = 0;
+  if (e == hipSuccess) e = hipMemcpyAsync(h->h_maxlen + (size_t)layer0 * c.batch, h->d_maxlen + (size_t)layer0 * c.batch,
+                                             sizeof(int32_t) * n * c.batch, hipMemcpyDeviceToHost, st);
+  if (e == hipSuccess) e = hipEventRecord(h->maxlen_event, st);
+  if (e == hipSuccess) {
+    for (int l = layer0; l < layer0 + n; ++l) h->maxlen_state[l] = 1;
+    h->maxlen_stream = st;
+  }
+  return e;
+}
+
+// Upper bound on the rows of any head of layers [layer0, layer0 + n) after this call's append:
+// from the lengths the eviction produced when they are known to have reached the host, the
+// worst case otherwise.
+int longest_rows(madakv_handle* h, int layer0, int n) {
+  const madakv_config& c = h->cfg;
+  const int worst = c.ctx_len + c.max_new_tokens;
+  bool pending = false;
+  for (int l = layer0; l < layer0 + n; ++l) pending = pending || h->maxlen_state[l] == 1;
+  if (pending && hipEventQuery(h->maxlen_event) == hipSuccess)
+    for (auto& sflag : h->maxlen_state) if (sflag == 1) sflag = 2;
+  int mx = 0;
+  for (int l = layer0; l < layer0 + n; ++l) {
+    if (h->maxlen_state[l] != 2) return worst;
+    for (int b = 0; b < c.batch; ++b) mx = std::max(mx, h->h_maxlen[(size_t)l * c.batch + b] + h->appended[l] + 1);
+  }
+  return std::min(worst, mx);
+}
+
+// After work was put on the side stream: the caller's stream waits for it, also when an
+// enqueue in between failed (the first error is kept).
+hipError_t join_side(madakv_handle* h, hipStream_t st, hipError_t e) {
+  hipError_t j = hipEventRecord(h->ev_join, h->side);
+  if (j == hipSuccess) j = hipStreamWaitEvent(st, h->ev_join, 0);
+  return e != hipSuccess ? e : j;
+}
+
+int32_t decode_impl(madakv_handle* h, int32_t layer0, int32_t n,
+                    const void* q, const void* k_new, const void* v_new,
+                    void* k_c, void* v_c, const int64_t* kv_off, int32_t* kv_len,
+                    void* out, void* ws, size_t ws_bytes, bool ws_is_static, void* stream) {
+  int32_t r = check_range(h, layer0, n);
+  if (r != MADAKV_OK) return r;
+  if (bad_ptr(q) || bad_ptr(k_c) || bad_ptr(v_c) || bad_ptr(kv_off, 8) || bad_ptr(kv_len, 4) || bad_ptr(out) || bad_ptr(ws))
+    return MADAKV_ERR_INVALID_ARG;
+  if ((k_new == nullptr) != (v_new == nullptr)) return MADAKV_ERR_INVALID_ARG;
+  if (k_new && (!aligned16(k_new) || !aligned16(v_new))) return MADAKV_ERR_INVALID_ARG;
+  Dims dm = make_dims(h->cfg, n);
+  const int longest = longest_rows(h, layer0, n);
+  // a caller's workspace is sized for the worst case; the static one must hold what this launch uses
+  const size_t need = ws_is_static ? decode_ws_bytes_for(dm, h->cfg, longest) : decode_ws_bytes(dm, h->cfg);
+  if (ws_bytes < need) return MADAKV_ERR_WORKSPACE_TOO_SMALL;
+  if (k_new) {
+    for (int l = layer0; l < layer0 + n; ++l)
+      if (h->appended[l] >= h->cfg.max_new_tokens) return MADAKV_ERR_INVALID_ARG;
+  }
+  hipError_t e = launch_decode(dm, h->cfg, q, k_new, v_new, k_c, v_c, kv_off, kv_len, out, ws,
+                               region_tokens(h->cfg) * h->cfg.batch, longest,
+                               reinterpret_cast<hipStream_t>(stream));
+  if (e == hipSuccess && k_new) for (int l = layer0; l < layer0 + n; ++l) h->appended[l] += 1;
+  return hip_fail(h, e);
+}
+
 }  // namespace
 
 extern "C" {
@@ -143,7 +217,7 @@ int32_t madakv_create(const madakv_config* cfg, madakv_handle** out) {
   h->last_hip_error = 0;
   h->d_state = nullptr;
   h->d_maxlen = nullptr; h->h_maxlen = nullptr; h->maxlen_event = nullptr;
-  h->maxlen_pending = false; h->sel_layers_done = 0;
+  h->maxlen_state.assign(cfg->n_layers, 0); h->maxlen_stream = nullptr;
   h->side = nullptr; h->ev_fork = nullptr; h->ev_join = nullptr;
   for (int g = 0; g < MAX_GROUPS; ++g) { h->ev_grp[g] = nullptr; h->ev_sel[g] = nullptr; }
   h->appended.assign(cfg->n_layers, 0);
@@ -152,6 +226,7 @@ int32_t madakv_create(const madakv_config* cfg, madakv_handle** out) {
   if (e == hipSuccess) e = hipMemset(h->d_state, 0, sizeof(long long) * 2 * cfg->batch);
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&h->d_maxlen), sizeof(int32_t) * cfg->n_layers * cfg->batch);
   if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&h->h_maxlen), sizeof(int32_t) * cfg->n_layers * cfg->batch, hipHostMallocDefault);
+  if (e == hipSuccess) memset(h->h_maxlen, 0, sizeof(int32_t) * cfg->n_layers * cfg->batch);
   if (e == hipSuccess) e = hipEventCreateWithFlags(&h->maxlen_event, hipEventDisableTiming);
   if (e == hipSuccess) e = hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking);
   if (e == hipSuccess) e = hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming);
@@ -243,10 +318,7 @@ static int32_t score_impl(madakv_handle* h, int32_t layer0, int32_t n,
       e = launch_stats(dg, c, psi_g, mask, pool_g, static_cast<char*>(stats) + lb * c.n_kv_heads * 8 * (size_t)c.n_modalities,
                        g0 == 0 ? n_mod : nullptr, layer0 + g0, ss);
   }
-  if (overlap && e == hipSuccess) {
-    e = hipEventRecord(h->ev_join, h->side);
-    if (e == hipSuccess) e = hipStreamWaitEvent(st, h->ev_join, 0);
-  }
+  if (overlap) e = join_side(h, st, e);
   return hip_fail(h, e);
 }
 
@@ -300,12 +372,7 @@ int32_t madakv_select_gather(madakv_handle* h, int32_t layer0, int32_t n,
   if (e == hipSuccess) e = launch_select(dm, c, psi_pool, mask, budgets, kv_off, kv_len, kept_idx, st);
   if (e == hipSuccess) e = launch_gather(dm, c, 0, n, k, v, kept_idx, kv_off, kv_len, k_c, v_c, ws, region, bpb, bpb, st);
   for (int l = layer0; l < layer0 + n; ++l) h->appended[l] = 0;
-  // hand the per-layer longest length to the host without waiting for it
-  if (e == hipSuccess) e = hipMemcpyAsync(h->h_maxlen + (size_t)layer0 * c.batch, h->d_maxlen + (size_t)layer0 * c.batch,
-                                             sizeof(int32_t) * n * c.batch, hipMemcpyDeviceToHost, st);
-  if (e == hipSuccess) e = hipEventRecord(h->maxlen_event, st);
-  h->sel_layers_done = (e == hipSuccess) ? layer0 + n : 0;
-  h->maxlen_pending = true;
+  e = publish_maxlen(h, layer0, n, st, e);
   return hip_fail(h, e);
 }
 
@@ -373,12 +440,9 @@ int32_t madakv_evict(madakv_handle* h, int32_t layer0, int32_t n,
     const int bpb = blocks_per_batch(c, ng);
     if (e == hipSuccess) e = launch_gather(dg, c, 0, ng, kg, vg, kept_idx, kv_off + heads0, kv_len + heads0, k_c, v_c, ws_g, region, bpb, bpb, st);
   }
+  if (overlap && e != hipSuccess) e = join_side(h, st, e);   // an enqueue failed: whatever did reach the side stream is still joined
   for (int l = layer0; l < layer0 + n; ++l) h->appended[l] = 0;
-  if (e == hipSuccess) e = hipMemcpyAsync(h->h_maxlen + (size_t)layer0 * c.batch, h->d_maxlen + (size_t)layer0 * c.batch,
-                                             sizeof(int32_t) * n * c.batch, hipMemcpyDeviceToHost, st);
-  if (e == hipSuccess) e = hipEventRecord(h->maxlen_event, st);
-  h->sel_layers_done = (e == hipSuccess) ? layer0 + n : 0;
-  h->maxlen_pending = true;
+  e = publish_maxlen(h, layer0, n, st, e);
   return hip_fail(h, e);
 }
 
@@ -386,32 +450,7 @@ int32_t madakv_decode_attn(madakv_handle* h, int32_t layer0, int32_t n,
                            const void* q, const void* k_new, const void* v_new,
                            void* k_c, void* v_c, const int64_t* kv_off, int32_t* kv_len,
                            void* out, void* ws, size_t ws_bytes, void* stream) {
-  int32_t r = check_range(h, layer0, n);
-  if (r != MADAKV_OK) return r;
-  if (bad_ptr(q) || bad_ptr(k_c) || bad_ptr(v_c) || bad_ptr(kv_off, 8) || bad_ptr(kv_len, 4) || bad_ptr(out) || bad_ptr(ws))
-    return MADAKV_ERR_INVALID_ARG;
-  if ((k_new == nullptr) != (v_new == nullptr)) return MADAKV_ERR_INVALID_ARG;
-  if (k_new && (!aligned16(k_new) || !aligned16(v_new))) return MADAKV_ERR_INVALID_ARG;
-  Dims dm = make_dims(h->cfg, n);
-  if (ws_bytes < decode_ws_bytes(dm, h->cfg)) return MADAKV_ERR_WORKSPACE_TOO_SMALL;
-  if (k_new) {
-    for (int l = layer0; l < layer0 + n; ++l)
-      if (h->appended[l] >= h->cfg.max_new_tokens) return MADAKV_ERR_INVALID_ARG;
-  }
-  // upper bound on the rows of any head in the call (after this call's append)
-  int longest = h->cfg.ctx_len + h->cfg.max_new_tokens;
-  if (h->maxlen_pending && hipEventQuery(h->maxlen_event) == hipSuccess) h->maxlen_pending = false;
-  if (!h->maxlen_pending && layer0 + n <= h->sel_layers_done) {
-    int mx = 0;
-    for (int l = layer0; l < layer0 + n; ++l)
-      for (int b = 0; b < h->cfg.batch; ++b) mx = std::max(mx, h->h_maxlen[(size_t)l * h->cfg.batch + b] + h->appended[l] + 1);
-    longest = std::min(longest, mx);
-  }
-  hipError_t e = launch_decode(dm, h->cfg, q, k_new, v_new, k_c, v_c, kv_off, kv_len, out, ws,
-                               region_tokens(h->cfg) * h->cfg.batch, longest,
-                               reinterpret_cast<hipStream_t>(stream));
-  if (e == hipSuccess && k_new) for (int l = layer0; l < layer0 + n; ++l) h->appended[l] += 1;
-  return hip_fail(h, e);
+  return decode_impl(h, layer0, n, q, k_new, v_new, k_c, v_c, kv_off, kv_len, out, ws, ws_bytes, false, stream);
 }
 
 }  // extern "C"

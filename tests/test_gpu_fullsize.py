@@ -25,7 +25,9 @@ def say(msg):
     sys.stdout.flush()
 
 
-def run_full(wl, samples, decode_steps=2):
+def run_full(wl, samples, decode_steps=2, check_steps=None):
+    """check_steps: the decode steps whose sampled heads are compared with the oracle (all of them
+    when None); the oracle's copy of a sampled head's cache grows at every step either way."""
     NL, B, H, Hq, L, W, d = wl.n_layers, wl.batch, wl.n_kv_heads, wl.n_q_heads, wl.ctx_len, wl.window, wl.head_dim
     G, nc = Hq // H, L - W
     p = PU.oracle_params(wl)
@@ -111,20 +113,28 @@ def run_full(wl, samples, decode_steps=2):
                   WL.to_f64(eng.v_c[int(kv_off[s]):int(kv_off[s]) + int(kv_len[s])])] for s in samples}
     for step in range(decode_steps):
         dq, dk, dv = WL.decode_inputs_all(wl, step, DEV)
-        say(f"{wl.name}: decode step {step}, one call per layer")
+        if check_steps is None or step in check_steps or step % 32 == 0:
+            say(f"{wl.name}: decode step {step}, one call per layer")
         for l in range(NL):
             eng.decode_attn(l, 1, dq[l:l + 1], dk[l:l + 1], dv[l:l + 1], out[l:l + 1])
         torch.cuda.synchronize()
-        assert torch.isfinite(out).all()
+        checked = check_steps is None or step in check_steps
+        if checked:
+            assert torch.isfinite(out).all()
         for (l, b, h) in samples:
             kc, vc = caches[(l, b, h)]
             kc = np.concatenate([kc, WL.to_f64(dk[l, b, h])[None]]); vc = np.concatenate([vc, WL.to_f64(dv[l, b, h])[None]])
             caches[(l, b, h)] = [kc, vc]
-            for g in range(G):
+            for g in range(G if checked else 0):
                 ref = O.attend(WL.to_f64(dq[l, b, h * G + g]), kc, vc, p.scale)
                 err = np.abs(out[l, b, h * G + g].cpu().numpy() - ref).max()
                 assert err <= PU.DECODE_ATOL, (step, l, b, h, g, err)
     assert (eng.kv_len.cpu().numpy() == kv_len + decode_steps).all()
+    # the appended rows of the sampled heads are in the cache, bit for bit, behind the kept ones
+    for (l, b, h) in samples:
+        o, n = int(kv_off[l, b, h]), int(kv_len[l, b, h]) + decode_steps
+        np.testing.assert_array_equal(WL.to_f64(eng.k_c[o:o + n]), caches[(l, b, h)][0])
+        np.testing.assert_array_equal(WL.to_f64(eng.v_c[o:o + n]), caches[(l, b, h)][1])
     # all layers in one call gives the same numbers as one call per layer (attend only)
     out2 = torch.empty_like(out)
     eng.decode_attn(0, NL, dq, None, None, out2)
@@ -143,8 +153,10 @@ def test_full_llava_layer():
 
 
 def test_full_llava_16k():
+    # all 128 decode steps the configuration names, sampled heads checked at the first, a middle and the last one
     wl = WL.CONFIGS["llava_16k"]
-    run_full(wl, [(0, 0, 0), (3, 1, 5), (15, 2, 17), (16, 3, 30), (31, 3, 31)])
+    run_full(wl, [(0, 0, 0), (3, 1, 5), (15, 2, 17), (16, 3, 30), (31, 3, 31)], decode_steps=wl.decode_steps,
+             check_steps={0, 1, wl.decode_steps // 2, wl.decode_steps - 1})
 
 
 def test_full_qwen_gqa():
@@ -154,8 +166,10 @@ def test_full_qwen_gqa():
 
 @pytest.mark.parametrize("budget", [512, 4096])
 def test_full_long_128k(budget):
+    # all 256 decode steps the configuration names
     wl = WL.CONFIGS["long_128k"].scaled(budget=budget)
-    run_full(wl, [(0, 0, 0), (0, 0, 13), (0, 0, 31)])
+    run_full(wl, [(0, 0, 0), (0, 0, 13), (0, 0, 31)], decode_steps=wl.decode_steps,
+             check_steps={0, 1, wl.decode_steps // 2, wl.decode_steps - 1})
 
 
 def test_hcc_drafts_take_both_signs_on_the_16k_workload():

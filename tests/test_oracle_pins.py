@@ -597,3 +597,9 @@ def test_e4m3_table_and_quantiser():
     assert O.quantize_e4m3(np.array([1.0625, 1.1875, 2.0 ** -10, 3 * 2.0 ** -10, 464.0, 1e9, -1e9])).tolist() == \
         [0x38, 0x3A, 0x00, 0x02, 0x7E, 0x7E, 0xFE]
     np.testing.assert_array_equal(O.dequantize_e4m3(np.array([0x38, 0xB8, 0x7E], dtype=np.uint8)), [1.0, -1.0, 448.0])
+
+
+def test_split_products_on_a_half_go_up_to_text():
+    """Eq. 8 in integers, hand-worked: share_t * a exactly on x.5 rounds up (to text)."""
+    for wt, wv, a, bt in [(1.0, 1.0, 7, 4), (3.0, 1.0, 6, 5), (1.0, 3.0, 6, 2), (0.25, 0.75, 1002, 251), (5.0, 3.0, 4, 3)]:
+        assert O.mpa_split(a, wt, wv, a, a) == (bt, a - bt)
