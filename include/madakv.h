@@ -212,6 +212,27 @@ int32_t madakv_decode_attn(madakv_handle* h, int32_t layer0, int32_t n,
                            void* k_c, void* v_c, const int64_t* kv_off, int32_t* kv_len,
                            void* out, void* ws, size_t ws_bytes, void* stream);
 
+/* madakv_decode_attn for callers that cannot allocate device memory and so have no workspace to
+ * pass: code running under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, kernels and results as madakv_decode_attn, without ws: the partial
+ * results of heads that are cut into several chunks go to an array of
+ * MADAKV_STATIC_SCRATCH_BYTES bytes that is part of the library's device code (one copy per GPU,
+ * held until the process ends).  The call allocates and frees nothing.
+ *   - MADAKV_ERR_WORKSPACE_TOO_SMALL if this launch needs more than the array holds: the need is
+ *     (heads in the call) * (chunks of the longest head) * G * (head_dim + 2) * 4 bytes, with
+ *     chunks of 256 .. 1024 rows (512 once the call covers >= 1024 heads); the longest head is
+ *     taken from what the eviction produced once that has reached the host, from ctx_len +
+ *     max_new_tokens before.  One layer of 128 heads of up to 16K rows fits.  Nothing is
+ *     enqueued in that case.
+ *   - Every call on one GPU, from any handle, uses the same array: calls that may run
+ *     concurrently on one GPU (different streams) race on it and must not be issued.  Nothing in
+ *     the array has to survive between calls. */
+#define MADAKV_STATIC_SCRATCH_BYTES ((size_t)8 << 20)
+int32_t madakv_decode_attn_static(madakv_handle* h, int32_t layer0, int32_t n,
+                                  const void* q, const void* k_new, const void* v_new,
+                                  void* k_c, void* v_c, const int64_t* kv_off, int32_t* kv_len,
+                                  void* out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

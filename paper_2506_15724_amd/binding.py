@@ -59,6 +59,7 @@ def lib() -> C.CDLL:
         L.madakv_select_gather.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.madakv_evict.argtypes = [vp, i32, i32] + [vp] * 14 + [vp, sz, vp, sz, vp]
         L.madakv_decode_attn.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.madakv_decode_attn_static.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         for name in EXPORTS:
             getattr(L, name).restype = i32
         _lib = L
@@ -67,7 +68,7 @@ def lib() -> C.CDLL:
 
 EXPORTS = ["madakv_create", "madakv_destroy", "madakv_last_hip_error", "madakv_workspace_bytes",
            "madakv_compact_capacity_tokens", "madakv_score", "madakv_score_lse", "madakv_allocate", "madakv_select_gather", "madakv_evict",
-           "madakv_decode_attn"]
+           "madakv_decode_attn", "madakv_decode_attn_static"]
 
 
 def _ptr(t):
@@ -143,6 +144,11 @@ def madakv_decode_attn(h, layer0, n, q, k_new, v_new, k_c, v_c, kv_off, kv_len, 
     _check("madakv_decode_attn", lib().madakv_decode_attn(
         h, layer0, n, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_c), _ptr(v_c), _ptr(kv_off), _ptr(kv_len),
         _ptr(out), _ptr(ws), ws.numel() * ws.element_size(), _stream()))
+
+
+def madakv_decode_attn_static(h, layer0, n, q, k_new, v_new, k_c, v_c, kv_off, kv_len, out):
+    _check("madakv_decode_attn_static", lib().madakv_decode_attn_static(
+        h, layer0, n, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_c), _ptr(v_c), _ptr(kv_off), _ptr(kv_len), _ptr(out), _stream()))
 
 
 # ---- a thin holder for the handle and the buffers a full run needs -------------------
@@ -226,6 +232,10 @@ class MadaKV:
     def decode_attn(self, l0, n, q, k_new, v_new, out):
         madakv_decode_attn(self.h, l0, n, q, k_new, v_new, self.k_c, self.v_c, self._sl(self.kv_off, l0, n),
                            self._sl(self.kv_len, l0, n), out, self.decode_ws)
+
+    def decode_attn_static(self, l0, n, q, k_new, v_new, out):
+        madakv_decode_attn_static(self.h, l0, n, q, k_new, v_new, self.k_c, self.v_c, self._sl(self.kv_off, l0, n),
+                                  self._sl(self.kv_len, l0, n), out)
 
     # host copies of the statistics in their declared types
     def stats_host(self):

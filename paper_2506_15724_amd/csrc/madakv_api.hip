@@ -5,12 +5,23 @@
 #include <algorithm>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
 using namespace madakv;
 
 constexpr int MAX_GROUPS = 4;      // layer groups a multi-layer call is cut into for the overlap
+
+// Scratch of madakv_decode_attn_static: the partial results of heads that are cut into several
+// chunks.  One copy per GPU, at an address of its own on each, held until the process ends.  In
+// host code the name below is only a handle for hipGetSymbolAddress; the device address is
+// resolved once per device (static_scratch_on_current_device) and passed to the kernels.
+constexpr size_t STATIC_SCRATCH_BYTES = MADAKV_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+static void* g_scratch_ptr[MAX_DEVICES];
+static std::mutex g_scratch_mutex;
 
 struct madakv_handle {
   madakv_config cfg;
@@ -28,6 +39,7 @@ struct madakv_handle {
   // maxlen_stream and covered by maxlen_event, 2 = the value in h_maxlen has landed
   std::vector<uint8_t> maxlen_state;
   hipStream_t maxlen_stream;
+  void* static_scratch;            // this device's copy of the static scratch array
   // Side stream and events for the overlap of the bandwidth-bound kernels (score sweeps, gather)
   // with the latency-bound per-head kernels (statistics, selection) inside one call.  The side
   // stream forks from and joins the caller's stream through events; default priority.
@@ -177,6 +189,20 @@ hipError_t join_side(madakv_handle* h, hipStream_t st, hipError_t e) {
   return e != hipSuccess ? e : j;
 }
 
+// Device address of the static scratch array on the current device (resolved once per device).
+hipError_t static_scratch_on_current_device(int device, void** out) {
+  if (device < 0 || device >= MAX_DEVICES) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void* ptr = nullptr;
+    hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    g_scratch_ptr[device] = ptr;
+  }
+  *out = g_scratch_ptr[device];
+  return hipSuccess;
+}
+
 int32_t decode_impl(madakv_handle* h, int32_t layer0, int32_t n,
                     const void* q, const void* k_new, const void* v_new,
                     void* k_c, void* v_c, const int64_t* kv_off, int32_t* kv_len,
@@ -221,7 +247,9 @@ int32_t madakv_create(const madakv_config* cfg, madakv_handle** out) {
   h->side = nullptr; h->ev_fork = nullptr; h->ev_join = nullptr;
   for (int g = 0; g < MAX_GROUPS; ++g) { h->ev_grp[g] = nullptr; h->ev_sel[g] = nullptr; }
   h->appended.assign(cfg->n_layers, 0);
+  h->static_scratch = nullptr;
   hipError_t e = hipGetDevice(&h->device);
+  if (e == hipSuccess) e = static_scratch_on_current_device(h->device, &h->static_scratch);
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&h->d_state), sizeof(long long) * 2 * cfg->batch);
   if (e == hipSuccess) e = hipMemset(h->d_state, 0, sizeof(long long) * 2 * cfg->batch);
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&h->d_maxlen), sizeof(int32_t) * cfg->n_layers * cfg->batch);
@@ -451,6 +479,16 @@ int32_t madakv_decode_attn(madakv_handle* h, int32_t layer0, int32_t n,
                            void* k_c, void* v_c, const int64_t* kv_off, int32_t* kv_len,
                            void* out, void* ws, size_t ws_bytes, void* stream) {
   return decode_impl(h, layer0, n, q, k_new, v_new, k_c, v_c, kv_off, kv_len, out, ws, ws_bytes, false, stream);
+}
+
+int32_t madakv_decode_attn_static(madakv_handle* h, int32_t layer0, int32_t n,
+                                  const void* q, const void* k_new, const void* v_new,
+                                  void* k_c, void* v_c, const int64_t* kv_off, int32_t* kv_len,
+                                  void* out, void* stream) {
+  if (!h) return MADAKV_ERR_INVALID_ARG;
+  // no allocation on this path: this device's copy of the static array is all it uses beyond the caller's tensors
+  return decode_impl(h, layer0, n, q, k_new, v_new, k_c, v_c, kv_off, kv_len, out, h->static_scratch, STATIC_SCRATCH_BYTES,
+                     true, stream);
 }
 
 }  // extern "C"

@@ -84,3 +84,5 @@ def test_null_arguments():
     assert lib.madakv_workspace_bytes(None, 1, None, None, None) == -1
     assert lib.madakv_compact_capacity_tokens(None, None) == -1
     assert lib.madakv_last_hip_error(None) == 0
+    assert lib.madakv_decode_attn(None, 0, 1, None, None, None, None, None, None, None, None, None, 0, None) == -1
+    assert lib.madakv_decode_attn_static(None, 0, 1, None, None, None, None, None, None, None, None, None) == -1
