@@ -12,6 +12,7 @@
 #include "common.h"
 
 #include <algorithm>
+#include <cstdlib>
 
 namespace madakv {
 
@@ -32,6 +33,13 @@ struct ScoreArgs {
                        // store the same value; a store under a branch makes the load waits pessimistic)
   int H, G, d, L, W, M, mpad, nsplit, chunk;
   int nmerge;          // chunks whose row statistics sweep 2 still has to merge (1 after score_combine_kernel)
+  // one-sweep kernel: row statistics of the head's chunks as (max, sum) pairs in one 64-bit word each,
+  // [heads, fsplit, mpad], all ones = not yet there; status[0] != 0 = a workgroup gave up waiting
+  unsigned long long* xchg;
+  int* status;         // status[0]: workgroups of one-sweep launches that gave up waiting so far (diagnostic counter,
+                       // the first word of the workspace; never cleared here)
+  int fsplit;          // chunks per head of the one-sweep kernel
+  int spin_limit;      // polls a workgroup of the one-sweep kernel spends on one missing word before it goes its own way
   int head0;           // first head of this launch (grid.y indexes head0 + y)
   float scale_log2;    // softmax scale * log2(e)
 };
@@ -287,6 +295,269 @@ _Pragma("unroll") \
 }
 
 // ------------------------------------------------------------------------------------
+// One sweep over K (bf16, at most two row blocks: G*W <= 64).  The logits of a workgroup's
+// keys fit in its registers: a wave keeps the D tiles of its NS subtiles (NS * NRB * 16 floats
+// per lane) instead of reducing them on the fly.  After its last subtile a workgroup knows the
+// (max, sum) of every proxy row over its own keys; the workgroups of a head exchange these
+// through memory, every one merges all of them in the same fixed order, and the column sums
+// come out of the registers: K is read once and multiplied once.
+//
+// The exchange: a (max, sum) pair is one 64-bit word, stored with a relaxed agent-scope atomic
+// store and read with relaxed agent-scope atomic loads until it differs from the all-ones
+// pattern the array is filled with before the launch; the word carries its own arrival, so no
+// fence and no counter is needed.  A workgroup waits only for workgroups of its own head.  Those
+// have consecutive workgroup ids (the chunk index is the fast grid dimension), workgroups are
+// dispatched in id order, and a head has far fewer chunks than the chip has workgroup slots, so
+// the workgroups waited for are already running or next in line for the slots that free up.
+// The wait is bounded all the same: a workgroup that runs out of patience counts itself in
+// status[0] and computes the row statistics of the whole head on its own with plain FMA code
+// (slow, and its last bits differ from the exchanged ones, but it depends on nobody).
+// ------------------------------------------------------------------------------------
+constexpr unsigned long long XCHG_EMPTY = ~0ULL;
+constexpr int FUSED_SPIN_LIMIT = 1 << 16;     // default spin_limit: polls of ~1 us each
+
+__global__ __launch_bounds__(256) void score_xchg_init_kernel(unsigned long long* xchg, long long n) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) xchg[i] = XCHG_EMPTY;
+}
+
+// Row statistics of a whole head by one workgroup, without matrix cores and without anybody
+// else: wave w takes rows w, w + 4, ...; lanes stride over the keys the row sees.  Q comes from
+// the staged tile.  Leaves offs[r] = max + log2(sum) (log2 domain), +inf for padding rows.
+template <int D>
+__device__ __forceinline__ void score_head_stats_alone(const ScoreArgs& a, const uint16_t* kg, const uint16_t* qs, float* offs) {
+  constexpr int RS = D + 8;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int r = wave; r < a.mpad; r += 4) {
+    float m = NEG_BIG, l = 0.f;
+    if (r < a.M) {
+      const int pos = a.L - a.W + (r % a.W);
+      for (int key = lane; key <= pos; key += 64) {
+        float sdot = 0.f;
+        for (int c = 0; c < D / 8; ++c) {
+          const uint4 kk = *reinterpret_cast<const uint4*>(kg + (long long)key * D + c * 8);
+          const uint4 qq = *reinterpret_cast<const uint4*>(qs + r * RS + c * 8);
+          sdot = fmaf(bf16_lo(kk.x), bf16_lo(qq.x), sdot); sdot = fmaf(bf16_hi(kk.x), bf16_hi(qq.x), sdot);
+          sdot = fmaf(bf16_lo(kk.y), bf16_lo(qq.y), sdot); sdot = fmaf(bf16_hi(kk.y), bf16_hi(qq.y), sdot);
+          sdot = fmaf(bf16_lo(kk.z), bf16_lo(qq.z), sdot); sdot = fmaf(bf16_hi(kk.z), bf16_hi(qq.z), sdot);
+          sdot = fmaf(bf16_lo(kk.w), bf16_lo(qq.w), sdot); sdot = fmaf(bf16_hi(kk.w), bf16_hi(qq.w), sdot);
+        }
+        const float s2 = sdot * a.scale_log2;
+        const float mn = fmaxf(m, s2);
+        l = l * exp2f(m - mn) + exp2f(s2 - mn);
+        m = mn;
+      }
+      for (int o = 1; o < 64; o <<= 1) {
+        const float m2 = __shfl_xor(m, o, 64), l2 = __shfl_xor(l, o, 64);
+        merge_ml(m, l, m2, l2);
+      }
+    }
+    if (lane == 0) offs[r] = (r < a.M) ? m + log2f(l) : __builtin_inff();
+  }
+}
+
+template <int D, int NRB, int NS>
+__global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void score_fused_kernel(ScoreArgs a) {
+  constexpr int KS = D / 16;                  // MFMA k-steps
+  constexpr int RS = D + 8;                   // bf16 elements per LDS row (16 B pad)
+  constexpr int PPR = D / 8;                  // 16-byte pieces per row
+  constexpr int LPS = 32 * PPR / 64;          // 16-byte loads per lane per subtile
+  constexpr int CK = 4 * NS * 32;             // keys per workgroup
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  uint16_t* qs = reinterpret_cast<uint16_t*>(smem);                       // [mpad][RS]
+  uint16_t* kt_all = qs + (size_t)a.mpad * RS;                            // [4 waves][32][RS]
+  float* part = reinterpret_cast<float*>(kt_all + 4 * 32 * RS);           // [4 waves][mpad][2]
+  float* offs = part + 4 * a.mpad * 2;                                    // [mpad]
+  float* pm = offs + a.mpad;                                              // [256 / mpad parts][mpad][2]
+  __shared__ int s_fail;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int split = blockIdx.x;
+  const int head = a.head0 + blockIdx.y;
+  const int kvh = head % a.H;
+  const long long lb = head / a.H;            // (layer, batch) index
+  const uint16_t* qg = reinterpret_cast<const uint16_t*>(a.q_win) + (lb * a.H + kvh) * (long long)a.G * a.W * D;
+  const uint16_t* kg = reinterpret_cast<const uint16_t*>(a.k) + (long long)head * a.L * D;
+  const int chunk0 = split * CK;
+  const int chunk1 = min(a.L, chunk0 + CK);
+  uint16_t* kt = kt_all + (size_t)wave * 32 * RS;
+  if (tid == 0) s_fail = 0;
+
+  // subtile `it` of this wave: keys chunk0 + (it * 4 + wave) * 32 ...; two subtiles in flight
+  u32x4_t pre[2][LPS];
+#define MADAKV_FUSED_LOAD(SET, IT)                                                               \
+  {                                                                                              \
+    const int lt0 = chunk0 + ((IT) * 4 + wave) * 32;                                             \
+    _Pragma("unroll") for (int i = 0; i < LPS; ++i) {                                            \
+      const int idx = i * 64 + lane;                                                             \
+      const int lkey = min(lt0 + idx / PPR, a.L - 1); /* past the end: a valid row, masked later */ \
+      pre[SET][i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(kg + (long long)lkey * D + (idx % PPR) * 8)); \
+    }                                                                                            \
+  }
+  MADAKV_FUSED_LOAD(0, 0)
+  if (NS > 1) MADAKV_FUSED_LOAD(1, 1)
+
+  for (int e = tid; e < a.mpad * PPR; e += SCORE_THREADS) {               // Q tile, padding rows zero
+    const int r = e / PPR, c = e % PPR;
+    uint4 val = make_uint4(0, 0, 0, 0);
+    if (r < a.M) val = *reinterpret_cast<const uint4*>(qg + (long long)r * D + c * 8);
+    *reinterpret_cast<uint4*>(qs + r * RS + c * 8) = val;
+  }
+  __syncthreads();
+
+  const int half = lane >> 5, col = lane & 31;
+  const int first_masked = a.L - a.W + 1;      // keys below this are visible to every proxy row
+  bf16x8_t areg[KS];                           // one row block: its Q fragments stay in registers
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks)
+    areg[ks] = *reinterpret_cast<const bf16x8_t*>(qs + col * RS + half * (D / 2) + ks * 8);
+
+  float lg[NS][NRB][16];                       // scaled logits (log2 domain); masked entries hold NEG_BIG
+#pragma unroll
+  for (int it = 0; it < NS; ++it) {
+#pragma unroll
+    for (int i = 0; i < LPS; ++i) {
+      const int idx = i * 64 + lane;
+      *reinterpret_cast<u32x4_t*>(kt + (idx / PPR) * RS + (idx % PPR) * 8) = pre[it & 1][i];
+    }
+    if (it + 2 < NS) MADAKV_FUSED_LOAD(it & 1, it + 2)
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const int t0 = chunk0 + (it * 4 + wave) * 32;
+    const int key = t0 + col;
+    const bool tail = (t0 + 32 > first_masked) || (t0 + 32 > chunk1);
+    const uint16_t* krow = kt + col * RS + half * (D / 2);
+    bf16x8_t bfrag[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) bfrag[ks] = *reinterpret_cast<const bf16x8_t*>(krow + ks * 8);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int b = 0; b < NRB; ++b) {
+      f32x16_t acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      const uint16_t* qrow = qs + (b * 32 + col) * RS + half * (D / 2);
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const bf16x8_t afrag = (NRB == 1) ? areg[ks] : *reinterpret_cast<const bf16x8_t*>(qrow + ks * 8);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, bfrag[ks], acc, 0, 0, 0);
+      }
+      if (!tail) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) lg[it][b][j] = acc[j] * a.scale_log2;
+      } else {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          const int row = b * 32 + (j >> 2) * 8 + half * 4 + (j & 3);
+          const int pos = a.L - a.W + (row % a.W);
+          const bool valid = (key < chunk1) && (key <= pos) && (row < a.M);
+          lg[it][b][j] = valid ? acc[j] * a.scale_log2 : NEG_BIG;
+        }
+      }
+    }
+  }
+#undef MADAKV_FUSED_LOAD
+
+  // ---- (max, sum) of every row over this workgroup's keys: lanes, then waves (fixed order)
+#pragma unroll
+  for (int b = 0; b < NRB; ++b) {
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      float mx = lg[0][b][j];
+#pragma unroll
+      for (int it = 1; it < NS; ++it) mx = fmaxf(mx, lg[it][b][j]);
+      const float m = half_reduce<0>(mx);
+      float sm = 0.f;
+#pragma unroll
+      for (int it = 0; it < NS; ++it) sm += fast_exp2(lg[it][b][j] - m);   // masked entries against a real maximum: 0
+      const float l = half_reduce<1>(sm);
+      if (col == 0) {
+        const int row = b * 32 + (j >> 2) * 8 + half * 4 + (j & 3);
+        part[(wave * a.mpad + row) * 2] = m;
+        part[(wave * a.mpad + row) * 2 + 1] = l;
+      }
+    }
+  }
+  __syncthreads();
+  // a row none of whose keys here is visible has max NEG_BIG and a meaningless sum: merging it with
+  // anything real scales it by exp2(NEG_BIG - m) = 0
+  const int nparts = SCORE_THREADS / a.mpad;    // mpad is 32 or 64
+  const int r = tid % a.mpad, pt = tid / a.mpad;
+  if (a.fsplit == 1) {
+    if (tid < a.mpad) {
+      float m = NEG_BIG, l = 0.f;
+      for (int w = 0; w < 4; ++w) merge_ml(m, l, part[(w * a.mpad + tid) * 2], part[(w * a.mpad + tid) * 2 + 1]);
+      offs[tid] = (tid < a.M) ? m + log2f(l) : __builtin_inff();
+    }
+  } else {
+    unsigned long long* xh = a.xchg + (long long)head * a.fsplit * a.mpad;
+    if (tid < a.mpad) {
+      float m = NEG_BIG, l = 0.f;
+      for (int w = 0; w < 4; ++w) merge_ml(m, l, part[(w * a.mpad + tid) * 2], part[(w * a.mpad + tid) * 2 + 1]);
+      unsigned long long word = ((unsigned long long)__float_as_uint(l) << 32) | __float_as_uint(m);
+      if (word == XCHG_EMPTY) word = 0x7fc000007fc00000ULL;            // cannot happen with finite inputs
+      __hip_atomic_store(xh + (long long)split * a.mpad + tid, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    // thread (r, pt) merges the chunks [pt * cpp, (pt + 1) * cpp) of row r in order, eight loads at a time
+    const int cpp = (a.fsplit + nparts - 1) / nparts;
+    int s = min(pt * cpp, a.fsplit);
+    const int s1 = min(s + cpp, a.fsplit);
+    float m = NEG_BIG, l = 0.f;
+    int patience = a.spin_limit;
+    bool fail = false;
+    while (s < s1) {
+      unsigned long long v[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        v[j] = __hip_atomic_load(xh + (long long)min(s + j, s1 - 1) * a.mpad + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      int got = 0;
+      bool open = true;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        open = open && (s + j < s1) && (v[j] != XCHG_EMPTY);
+        if (open) { merge_ml(m, l, __uint_as_float((uint32_t)v[j]), __uint_as_float((uint32_t)(v[j] >> 32))); ++got; }
+      }
+      s += got;
+      if (got == 0) {
+        if (--patience == 0) { fail = true; break; }
+        __builtin_amdgcn_s_sleep(8);
+      }
+    }
+    if (fail) s_fail = 1;
+    pm[(pt * a.mpad + r) * 2] = m;
+    pm[(pt * a.mpad + r) * 2 + 1] = l;
+    __syncthreads();
+    if (__builtin_expect(s_fail, 0)) {         // uniform over the workgroup
+      if (tid == 0) atomicAdd(a.status, 1);
+      score_head_stats_alone<D>(a, kg, qs, offs);
+    } else if (tid < a.mpad) {
+      float mm = NEG_BIG, ll = 0.f;
+      for (int q = 0; q < nparts; ++q) merge_ml(mm, ll, pm[(q * a.mpad + tid) * 2], pm[(q * a.mpad + tid) * 2 + 1]);
+      offs[tid] = (tid < a.M) ? mm + log2f(ll) : __builtin_inff();
+    }
+  }
+  __syncthreads();
+
+  // ---- column sums from the registers
+  float off_r[NRB][16];
+#pragma unroll
+  for (int b = 0; b < NRB; ++b)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) off_r[b][j] = offs[b * 32 + (j >> 2) * 8 + half * 4 + (j & 3)];
+#pragma unroll
+  for (int it = 0; it < NS; ++it) {
+    float colsum = 0.f;
+#pragma unroll
+    for (int b = 0; b < NRB; ++b)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) colsum += fast_exp2(lg[it][b][j] - off_r[b][j]);
+    colsum += __shfl_xor(colsum, 32, 64);
+    const int key = chunk0 + (it * 4 + wave) * 32 + col;
+    if (half == 0 && key < chunk1) __builtin_nontemporal_store(colsum, a.psi + ((long long)head * a.L + key));
+  }
+}
+
+// ------------------------------------------------------------------------------------
 // Plain FMA path (fp32 inputs, or bf16 with an odd head_dim).  Same two sweeps.
 // Sweep 1: wave w takes rows w, w+4, ...; lanes stride over the keys of the chunk.
 // Sweep 2: one thread per key, loop over the rows.
@@ -389,9 +660,25 @@ ScorePlan score_plan(const Dims& dm, int dtype) {
   return p;
 }
 
-size_t score_ws_bytes(const Dims& dm, int dtype) {
+// One sweep when the logits of a workgroup's keys fit in registers (at most two row blocks) and a
+// head has few enough chunks that all its workgroups are certain to be on the chip together.
+constexpr int FUSED_NS1 = 8, FUSED_NS2 = 6;           // subtiles per wave with one / two row blocks
+constexpr int FUSED_MAX_SPLIT = 64;
+static int fused_chunk(const Dims& dm) { return 4 * 32 * ((dm.M + 31) / 32 == 1 ? FUSED_NS1 : FUSED_NS2); }
+static int fused_split(const Dims& dm) { return (dm.L + fused_chunk(dm) - 1) / fused_chunk(dm); }
+static bool use_fused(const Dims& dm, int dtype) {
+  static const bool off = [] { const char* e = getenv("MADAKV_SCORE_TWO_SWEEPS"); return e && atoi(e) != 0; }();
+  return !off && use_mfma(dm, dtype) && dm.M <= 64 && fused_split(dm) <= FUSED_MAX_SPLIT;
+}
+
+static size_t rowstat_bytes(const Dims& dm, int dtype) {
   ScorePlan p = score_plan(dm, dtype);
-  return (size_t)dm.heads * p.nsplit * p.mpad * 2 * sizeof(float) + 256;   // row statistics + the store sink
+  return ((size_t)dm.heads * p.nsplit * p.mpad * 2 * sizeof(float) + 255) / 256 * 256;
+}
+size_t score_ws_bytes(const Dims& dm, int dtype) {
+  // the counter of lone workgroups, the row statistics of the two sweeps, the store sink, the exchange array of the one-sweep kernel
+  size_t xchg = use_mfma(dm, dtype) && dm.M <= 64 && fused_split(dm) <= FUSED_MAX_SPLIT ? (size_t)dm.heads * fused_split(dm) * ((dm.M + 31) / 32 * 32) * 8 : 0;
+  return 256 + rowstat_bytes(dm, dtype) + 256 + (xchg + 255) / 256 * 256;
 }
 
 template <int D, int WPT, int NRB>
@@ -403,6 +690,18 @@ static void launch_mfma_pair(const ScoreArgs& a0, int heads, size_t lds1, size_t
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_mfma_kernel<D, WPT, NRB, 2>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
+  }
+  if (!a.lse && a.fsplit > 0 && WPT == 1) {
+    constexpr int NS = NRB == 1 ? FUSED_NS1 : FUSED_NS2;
+    const long long nx = (long long)heads * a.fsplit * a.mpad;
+    if (a.fsplit > 1)
+      hipLaunchKernelGGL(score_xchg_init_kernel, dim3((unsigned)((nx + 255) / 256)), dim3(256), 0, st,
+                         a.xchg + (long long)a.head0 * a.fsplit * a.mpad, nx);
+    const size_t ldsf = ((size_t)a.mpad + 4 * 32) * (D + 8) * 2 + ((size_t)4 * a.mpad * 2 + a.mpad + 512) * sizeof(float);
+    if (ldsf > 48 * 1024)
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_fused_kernel<D, NRB, NS>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)ldsf);
+    hipLaunchKernelGGL((score_fused_kernel<D, NRB, NS>), dim3(a.fsplit, heads), dim3(SCORE_THREADS), ldsf, st, a);
+    return;
   }
   if (!a.lse) {
     hipLaunchKernelGGL((score_mfma_kernel<D, WPT, NRB, 1>), grid, dim3(SCORE_THREADS), lds1, st, a);
@@ -416,8 +715,15 @@ hipError_t launch_score(const Dims& dm, const madakv_config& c, const void* q_wi
   ScorePlan p = score_plan(dm, c.dtype);
   ScoreArgs a;
   a.lse = row_lse;
-  a.q_win = q_win; a.k = k; a.psi = psi; a.rowstat = reinterpret_cast<float*>(ws);
-  a.sink = a.rowstat + (size_t)dm.heads * score_plan(dm, c.dtype).nsplit * score_plan(dm, c.dtype).mpad * 2;
+  a.q_win = q_win; a.k = k; a.psi = psi;
+  a.status = reinterpret_cast<int*>(ws);
+  a.rowstat = reinterpret_cast<float*>(static_cast<char*>(ws) + 256);
+  a.sink = reinterpret_cast<float*>(static_cast<char*>(ws) + 256 + rowstat_bytes(dm, c.dtype));
+  a.xchg = reinterpret_cast<unsigned long long*>(static_cast<char*>(ws) + 256 + rowstat_bytes(dm, c.dtype) + 256);
+  a.fsplit = (!row_lse && use_fused(dm, c.dtype)) ? fused_split(dm) : 0;
+  // (a test can force the lone-workgroup path of the one-sweep kernel from the host with a spin limit of 1)
+  const char* spin = getenv("MADAKV_SCORE_SPIN_LIMIT");
+  a.spin_limit = spin && atoi(spin) > 0 ? atoi(spin) : FUSED_SPIN_LIMIT;
   a.H = dm.H; a.G = dm.G; a.d = dm.d; a.L = dm.L; a.W = dm.W; a.M = dm.M;
   a.mpad = p.mpad; a.nsplit = p.nsplit; a.nmerge = p.nsplit; a.chunk = p.chunk; a.head0 = 0;
   float scale = c.softmax_scale > 0.f ? c.softmax_scale : 1.0f / sqrtf((float)dm.d);

@@ -605,6 +605,48 @@ def test_allocate_rounds_after_every_operation():
         eng.close()
 
 
+@pytest.mark.parametrize("name", ["bf16_mha", "bf16_w64", "bf16_d64_gqa2", "bf16_odd"])
+def test_one_sweep_scoring_and_its_lone_workgroup_path(name):
+    """Scoring in one sweep over K: the workgroups of a head exchange their row statistics through
+    memory and wait for each other, with a bounded wait.  In a normal run nobody gives up (the
+    counter in the first word of the workspace stays 0).  With the wait cut to a single poll from
+    the host, workgroups that find a word missing compute the head's statistics on their own: every
+    kernel still ends normally and the scores still match the oracle."""
+    import os
+    wl = small_workloads()[name]
+    NL, B, H, L, W = wl.n_layers, wl.batch, wl.n_kv_heads, wl.ctx_len, wl.window
+    G = wl.n_q_heads // H
+    p = PU.oracle_params(wl)
+    q, k, v, mask, masks = PU.make_inputs(wl, DEV)
+    qh, kh = WL.to_f64(q), WL.to_f64(k)
+    psi_o = np.stack([np.stack([O.window_scores(qh[l, b], kh[l, b], p.scale) for b in range(B)]) for l in range(NL)])
+    eng = engine(wl)
+    eng.score_ws.zero_()
+    eng.score(0, NL, q, k, mask)
+    torch.cuda.synchronize()
+    assert int(eng.score_ws[:4].view(torch.int32)[0]) == 0, "a workgroup gave up waiting in an ordinary run"
+    psi_1 = eng.psi.clone()
+    nbad, worst = PU.psi_close(psi_1.cpu().numpy(), psi_o, G, W, L)
+    assert nbad == 0, worst
+    os.environ["MADAKV_SCORE_SPIN_LIMIT"] = "1"
+    try:
+        say(f"{name}: scoring with the wait cut to one poll")
+        eng.score(0, NL, q, k, mask)
+        torch.cuda.synchronize()
+    finally:
+        del os.environ["MADAKV_SCORE_SPIN_LIMIT"]
+    lone = int(eng.score_ws[:4].view(torch.int32)[0])
+    say(f"{name}: {lone} workgroups went their own way")
+    nbad, worst = PU.psi_close(eng.psi.cpu().numpy(), psi_o, G, W, L)
+    assert nbad == 0, worst
+    np.testing.assert_allclose(eng.psi.sum(-1).cpu().numpy(), G * W, rtol=2e-4)
+    # and the ordinary run repeats bit for bit
+    eng.score(0, NL, q, k, mask)
+    torch.cuda.synchronize()
+    assert torch.equal(eng.psi, psi_1)
+    eng.close()
+
+
 def test_error_paths_and_streams():
     """Host-side refusals on a live handle (nothing is enqueued), and calls on a non-default stream."""
     wl = small_workloads()["bf16_mha"].scaled(n_layers=2, batch=1, decode_steps=1)
