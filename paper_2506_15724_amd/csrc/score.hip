@@ -356,8 +356,18 @@ __device__ __forceinline__ void score_head_stats_alone(const ScoreArgs& a, const
   }
 }
 
+#ifndef MADAKV_FUSED_NS1      // tuning constants of the one-sweep kernel (measured on MI355X)
+#define MADAKV_FUSED_NS1 8    // subtiles per wave with one row block
+#define MADAKV_FUSED_NS2 6    // ... with two row blocks
+#define MADAKV_FUSED_PF 2     // subtiles in flight per wave
+#define MADAKV_FUSED_WPE 2    // waves per SIMD
+#endif
+#ifndef MADAKV_FUSED_MAX_SPLIT
+#define MADAKV_FUSED_MAX_SPLIT 64   // most chunks per head the one-sweep kernel is used for
+#endif
 template <int D, int NRB, int NS>
-__global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void score_fused_kernel(ScoreArgs a) {
+__global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(MADAKV_FUSED_WPE, MADAKV_FUSED_WPE))) void score_fused_kernel(ScoreArgs a) {
+  constexpr int PF = MADAKV_FUSED_PF < NS ? MADAKV_FUSED_PF : NS;
   constexpr int KS = D / 16;                  // MFMA k-steps
   constexpr int RS = D + 8;                   // bf16 elements per LDS row (16 B pad)
   constexpr int PPR = D / 8;                  // 16-byte pieces per row
@@ -383,8 +393,8 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(2
   uint16_t* kt = kt_all + (size_t)wave * 32 * RS;
   if (tid == 0) s_fail = 0;
 
-  // subtile `it` of this wave: keys chunk0 + (it * 4 + wave) * 32 ...; two subtiles in flight
-  u32x4_t pre[2][LPS];
+  // subtile `it` of this wave: keys chunk0 + (it * 4 + wave) * 32 ...; PF subtiles in flight
+  u32x4_t pre[PF][LPS];
 #define MADAKV_FUSED_LOAD(SET, IT)                                                               \
   {                                                                                              \
     const int lt0 = chunk0 + ((IT) * 4 + wave) * 32;                                             \
@@ -394,8 +404,8 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(2
       pre[SET][i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(kg + (long long)lkey * D + (idx % PPR) * 8)); \
     }                                                                                            \
   }
-  MADAKV_FUSED_LOAD(0, 0)
-  if (NS > 1) MADAKV_FUSED_LOAD(1, 1)
+#pragma unroll
+  for (int it = 0; it < PF; ++it) MADAKV_FUSED_LOAD(it, it)
 
   for (int e = tid; e < a.mpad * PPR; e += SCORE_THREADS) {               // Q tile, padding rows zero
     const int r = e / PPR, c = e % PPR;
@@ -418,9 +428,9 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(2
 #pragma unroll
     for (int i = 0; i < LPS; ++i) {
       const int idx = i * 64 + lane;
-      *reinterpret_cast<u32x4_t*>(kt + (idx / PPR) * RS + (idx % PPR) * 8) = pre[it & 1][i];
+      *reinterpret_cast<u32x4_t*>(kt + (idx / PPR) * RS + (idx % PPR) * 8) = pre[it % PF][i];
     }
-    if (it + 2 < NS) MADAKV_FUSED_LOAD(it & 1, it + 2)
+    if (it + PF < NS) MADAKV_FUSED_LOAD(it % PF, it + PF)
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -662,8 +672,8 @@ ScorePlan score_plan(const Dims& dm, int dtype) {
 
 // One sweep when the logits of a workgroup's keys fit in registers (at most two row blocks) and a
 // head has few enough chunks that all its workgroups are certain to be on the chip together.
-constexpr int FUSED_NS1 = 8, FUSED_NS2 = 6;           // subtiles per wave with one / two row blocks
-constexpr int FUSED_MAX_SPLIT = 64;
+constexpr int FUSED_NS1 = MADAKV_FUSED_NS1, FUSED_NS2 = MADAKV_FUSED_NS2;
+constexpr int FUSED_MAX_SPLIT = MADAKV_FUSED_MAX_SPLIT;
 static int fused_chunk(const Dims& dm) { return 4 * 32 * ((dm.M + 31) / 32 == 1 ? FUSED_NS1 : FUSED_NS2); }
 static int fused_split(const Dims& dm) { return (dm.L + fused_chunk(dm) - 1) / fused_chunk(dm); }
 static bool use_fused(const Dims& dm, int dtype) {
