@@ -677,7 +677,8 @@ constexpr int FUSED_MAX_SPLIT = MADAKV_FUSED_MAX_SPLIT;
 static int fused_chunk(const Dims& dm) { return 4 * 32 * ((dm.M + 31) / 32 == 1 ? FUSED_NS1 : FUSED_NS2); }
 static int fused_split(const Dims& dm) { return (dm.L + fused_chunk(dm) - 1) / fused_chunk(dm); }
 static bool use_fused(const Dims& dm, int dtype) {
-  static const bool off = [] { const char* e = getenv("MADAKV_SCORE_TWO_SWEEPS"); return e && atoi(e) != 0; }();
+  const char* e = getenv("MADAKV_SCORE_TWO_SWEEPS");      // diagnostic switch: the two-sweep kernels everywhere
+  const bool off = e && atoi(e) != 0;
   return !off && use_mfma(dm, dtype) && dm.M <= 64 && fused_split(dm) <= FUSED_MAX_SPLIT;
 }
 
