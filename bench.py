@@ -509,6 +509,25 @@ def main():
             del f8, f8c
         except Exception as ex:
             result["fp8_cache"] = {"error": str(ex)[:200]}
+        # the paged reduced cache (64-row pages, appended rows in pages taken on demand): eviction and decode step
+        try:
+            pgd = MB.MadaKV(n_layers=NL, batch=B, n_q_heads=Hq, n_kv_heads=H, head_dim=d, ctx_len=L, window=W, budget=wl.budget,
+                            dtype=wl.dtype, pool_k=wl.pool_k, max_new_tokens=S, out_fp32=0, page_rows=64, device=dev)
+            pg_evict = timed(lambda: pgd.evict(0, NL, q, k, v, mask))
+            pgc = LayerCalls(pgd, dq, dk, dv, out)
+            nst = min(S, 96)                             # far enough for every head to take a page
+            pgc.run_step(0, stream)
+            e0.record()
+            for s_ in range(1, nst):
+                pgc.run_step(s_, stream)
+            e1.record()
+            torch.cuda.synchronize()
+            result["paged_cache"] = {"page_rows": 64, "evict_ms": pg_evict, "decode_step_us": e0.elapsed_time(e1) / (nst - 1) * 1e3,
+                                     "capacity_rows_vs_contiguous": pgd.capacity / eng.capacity}
+            pgd.close()
+            del pgd, pgc
+        except Exception as ex:
+            result["paged_cache"] = {"error": str(ex)[:200]}
         # eviction when the caller's prefill hands over the proxy rows' log-sum-exp (one pass over K).
         # The normalisers are made here with torch, outside the timed region, as a prefill kernel would.
         scale = 1.0 / (d ** 0.5)

@@ -14,6 +14,9 @@
  *                         per-modality eviction; builds the reduced KV cache
  *   madakv_decode_attn    Sec. 3.1 Eq. 3-5: append K_t, V_t and attend over the
  *                         reduced cache
+ *   madakv_evict          Sec. 3.3 Eq. 6-11 and the eviction itself: the first three calls in one
+ *   madakv_score_lse      Sec. 3.3 Eq. 7 with the softmax normalisers of the proxy rows given
+ *                         (the prefill attention of Sec. 3.1 Eq. 5 has them)
  *
  * General rules
  *   - Plain C, no exceptions.  Every call returns a madakv_status (0 = OK).
@@ -23,8 +26,14 @@
  *     arrays to their element size (kv_off 8, float / int32 arrays and stats 4).
  *     The library never allocates, frees or keeps tensor memory.  A null or
  *     misaligned pointer gives MADAKV_ERR_INVALID_ARG; nothing is enqueued then.
- *   - All work is enqueued on the caller's stream (a hipStream_t passed as
- *     void*, NULL = the null stream).  No call synchronises the device.
+ *   - All work is ordered on the caller's stream (a hipStream_t passed as void*, NULL = the
+ *     null stream): it starts after what the stream held before the call and is complete, as far
+ *     as the stream is concerned, before anything enqueued after it.  madakv_allocate,
+ *     madakv_select_gather and madakv_decode_attn enqueue on that stream only.  madakv_score,
+ *     madakv_score_lse and madakv_evict over four or more layers also use the handle's own
+ *     stream for the per-head statistics / selection kernels of one layer group while the next
+ *     group is scored; that stream forks from and joins the caller's stream through events inside
+ *     the call.  No call synchronises the device.
  *   - Arguments are validated on the host before anything is enqueued.  Errors
  *     found there leave all outputs untouched.
  *   - The handle belongs to the HIP device that was current in madakv_create; that device must
@@ -94,6 +103,11 @@ typedef struct {
                               dtype = MADAKV_BF16.  Q, K, V, k_new, v_new and out stay in dtype. */
   int32_t n_modalities;    /* M, 2 .. 4: modality ids in the mask are 0 .. M-1 (the paper has text = 0 and
                               image = 1; more modalities are the extension its Sec. 6 names) */
+  int32_t page_rows;       /* 0 = every head's segment of the reduced cache is its kept rows followed by
+                              max_new_tokens free rows; 16, 32, 64, 128 or 256 = paged reduced cache: a segment
+                              is the kept rows rounded up to whole pages of that many rows, and the rows decode
+                              appends (Sec. 3.1 Eq. 4) continue in pages taken on demand from a pool all heads
+                              of a batch item share, so no head reserves room for generation up front */
 } madakv_config;
 
 /* Per-head statistics that madakv_score hands to madakv_allocate: a record of M floats
@@ -120,9 +134,16 @@ int32_t madakv_workspace_bytes(const madakv_handle* h, int32_t n_layers_per_call
                                size_t* score_ws, size_t* select_ws, size_t* decode_ws);
 
 /* Rows (tokens) the reduced cache k_c / v_c and kept_idx must hold for the whole
- * model: n_layers * batch * n_kv_heads * (min(budget, ctx_len) + max_new_tokens).
+ * model: n_layers * batch * n_kv_heads * (min(budget, ctx_len) + max_new_tokens); with a paged
+ * cache n_layers * batch * n_kv_heads * (ceil(min(budget, ctx_len) / page_rows) + 1 +
+ * ceil(max_new_tokens / page_rows)) pages of page_rows rows.
  * Known without a device sync because the sum of budgets is conserved exactly. */
 int32_t madakv_compact_capacity_tokens(const madakv_handle* h, int64_t* tokens);
+
+/* Environment variables (diagnostics, read at every scoring call; not needed in normal use):
+ *   MADAKV_SCORE_TWO_SWEEPS=1   score with the two-sweep kernels (K read twice) everywhere
+ *   MADAKV_SCORE_SPIN_LIMIT=n   polls a workgroup of the one-sweep scoring kernel spends on a missing word
+ *                               before it computes the head's row statistics alone (default 65536) */
 
 /* Eq. 7, Eq. 6, Eq. 9 and pooling for layers [layer0, layer0 + n).
  *   q_win    [n, B, Hq, W, d]  queries of the last W prompt positions
@@ -134,13 +155,17 @@ int32_t madakv_compact_capacity_tokens(const madakv_handle* h, int64_t* tokens);
  *                              candidates [0, L-W)
  *   stats    [n, B, H]         out: records {float w[M]; int32 k[M]} over the candidates
  *   n_mod    [B, M] int32      out: candidate count per modality
- * ws / ws_bytes: scratch of at least score_ws bytes. */
+ * ws / ws_bytes: scratch of at least score_ws bytes.  Its first int32 is a diagnostic counter the
+ * library only ever adds to: workgroups of the one-sweep scoring kernel that gave up waiting for the
+ * row statistics of their head's other workgroups and computed them alone (0 in normal operation if
+ * the caller cleared it). */
 int32_t madakv_score(madakv_handle* h, int32_t layer0, int32_t n,
                      const void* q_win, const void* k, const uint8_t* mask,
                      float* psi, float* psi_pool, void* stats, int32_t* n_mod,
                      void* ws, size_t ws_bytes, void* stream);
 
-/* madakv_score for a caller whose prefill attention kept the softmax normalisers of the proxy
+/* Sec. 3.3 Eq. 7 (then Eq. 6, Eq. 9, pooling as in madakv_score) for a caller whose prefill attention
+ * (Sec. 3.1 Eq. 5 on the last W prompt positions) kept the softmax normalisers of the proxy
  * rows (any flash-attention kernel has them): with
  *   row_lse  [n, B, Hq, W] float  natural log of sum_i exp(scale * q_r . k_i) over the keys row r sees
  * the first of the two passes over K is not needed and psi costs one pass.  Everything else as
@@ -185,7 +210,8 @@ int32_t madakv_select_gather(madakv_handle* h, int32_t layer0, int32_t n,
                              void* k_c, void* v_c,
                              void* ws, size_t ws_bytes, void* stream);
 
-/* madakv_score + madakv_allocate + madakv_select_gather for layers [layer0, layer0 + n) in one call,
+/* Sec. 3.3 as a whole (Eq. 7, 6, 9, then Eq. 8, 10, 11, then the per-head, per-modality eviction):
+ * madakv_score + madakv_allocate + madakv_select_gather for layers [layer0, layer0 + n) in one call,
  * with the same arguments and the same results bit for bit.  A call over four or more layers is
  * cut into four layer groups: the statistics, allocation and selection of a group run on a side
  * stream under the score passes of the following groups, the gathers follow on the caller's
@@ -211,6 +237,16 @@ int32_t madakv_decode_attn(madakv_handle* h, int32_t layer0, int32_t n,
                            const void* q, const void* k_new, const void* v_new,
                            void* k_c, void* v_c, const int64_t* kv_off, int32_t* kv_len,
                            void* out, void* ws, size_t ws_bytes, void* stream);
+
+/* Paged reduced cache (page_rows > 0): where the rows of a head are.  Rows [0, table[0] * page_rows) of head
+ * (l, b, h) sit at kv_off[l, b, h] + r (its initial pages follow each other); row r beyond that sits in page
+ * table[1 + (r - table[0] * page_rows) / page_rows] at slot r % page_rows, a page p covering rows
+ * [p * page_rows, (p + 1) * page_rows) of k_c / v_c.  *table is a device pointer into the handle (valid
+ * until madakv_destroy, NULL without paging) to int32 [n_layers * batch * n_kv_heads][*entries_per_head],
+ * head-major in (layer, batch, head) order; madakv_select_gather / madakv_evict write entry 0,
+ * madakv_decode_attn the others as pages get taken (from the top of the batch item's region downwards;
+ * a new pass starting at layer 0 returns them all). */
+int32_t madakv_page_table(const madakv_handle* h, const int32_t** table, int32_t* entries_per_head);
 
 /* madakv_decode_attn for callers that cannot allocate device memory and so have no workspace to
  * pass: code running under HIP graph capture, tight serving loops, harnesses that forbid

@@ -28,7 +28,7 @@ class Config(C.Structure):
                 ("hcc_rho", C.c_int32), ("theta", C.c_float), ("softmax_scale", C.c_float),
                 ("max_new_tokens", C.c_int32), ("out_fp32", C.c_int32), ("pool_mode", C.c_int32),
                 ("share_mode", C.c_int32), ("select_mode", C.c_int32), ("sink_tokens", C.c_int32),
-                ("cache_fp8", C.c_int32), ("n_modalities", C.c_int32)]
+                ("cache_fp8", C.c_int32), ("n_modalities", C.c_int32), ("page_rows", C.c_int32)]
 
 
 class MadaKVError(RuntimeError):
@@ -60,6 +60,7 @@ def lib() -> C.CDLL:
         L.madakv_evict.argtypes = [vp, i32, i32] + [vp] * 14 + [vp, sz, vp, sz, vp]
         L.madakv_decode_attn.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.madakv_decode_attn_static.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.madakv_page_table.argtypes = [vp, C.POINTER(vp), C.POINTER(i32)]
         for name in EXPORTS:
             getattr(L, name).restype = i32
         _lib = L
@@ -68,7 +69,7 @@ def lib() -> C.CDLL:
 
 EXPORTS = ["madakv_create", "madakv_destroy", "madakv_last_hip_error", "madakv_workspace_bytes",
            "madakv_compact_capacity_tokens", "madakv_score", "madakv_score_lse", "madakv_allocate", "madakv_select_gather", "madakv_evict",
-           "madakv_decode_attn", "madakv_decode_attn_static"]
+           "madakv_decode_attn", "madakv_decode_attn_static", "madakv_page_table"]
 
 
 def _ptr(t):
@@ -151,6 +152,13 @@ def madakv_decode_attn_static(h, layer0, n, q, k_new, v_new, k_c, v_c, kv_off, k
         h, layer0, n, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_c), _ptr(v_c), _ptr(kv_off), _ptr(kv_len), _ptr(out), _stream()))
 
 
+def madakv_page_table(h):
+    """(device address of the page table or None, entries per head)"""
+    ptr, n = C.c_void_p(), C.c_int32()
+    _check("madakv_page_table", lib().madakv_page_table(h, C.byref(ptr), C.byref(n)))
+    return ptr.value, n.value
+
+
 # ---- a thin holder for the handle and the buffers a full run needs -------------------
 class MadaKV:
     """Owns one library handle plus the device buffers of the interface (allocated with
@@ -159,10 +167,10 @@ class MadaKV:
     def __init__(self, *, n_layers, batch, n_q_heads, n_kv_heads, head_dim, ctx_len, window, budget,
                  dtype="bf16", pool_k=7, mpa_mode=1, hcc_mode=1, hcc_rho=2, theta=0.9, softmax_scale=0.0,
                  max_new_tokens=0, out_fp32=1, pool_mode=0, share_mode=0, select_mode=0, sink_tokens=4,
-                 n_modalities=2, cache_fp8=0, layers_per_call=None, device="cuda:0"):
+                 n_modalities=2, cache_fp8=0, page_rows=0, layers_per_call=None, device="cuda:0"):
         self.cfg = Config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, ctx_len, window, budget,
                           BF16 if dtype == "bf16" else FP32, pool_k, mpa_mode, hcc_mode, hcc_rho, theta,
-                          softmax_scale, max_new_tokens, out_fp32, pool_mode, share_mode, select_mode, sink_tokens, cache_fp8, n_modalities)
+                          softmax_scale, max_new_tokens, out_fp32, pool_mode, share_mode, select_mode, sink_tokens, cache_fp8, n_modalities, page_rows)
         self.device = torch.device(device)
         self.tdtype = torch.bfloat16 if dtype == "bf16" else torch.float32
         with torch.cuda.device(self.device):
@@ -236,6 +244,19 @@ class MadaKV:
     def decode_attn_static(self, l0, n, q, k_new, v_new, out):
         madakv_decode_attn_static(self.h, l0, n, q, k_new, v_new, self.k_c, self.v_c, self._sl(self.kv_off, l0, n),
                                   self._sl(self.kv_len, l0, n), out)
+
+    def page_table_host(self):
+        """Host copy of the page table as int32 [n_layers, B, H, entries] (paged cache only)."""
+        ptr, n = madakv_page_table(self.h)
+        c = self.cfg
+        import numpy as np
+        out = np.empty((c.n_layers, c.batch, c.n_kv_heads, n), dtype=np.int32)
+        torch.cuda.synchronize()
+        hip = C.CDLL("libamdhip64.so")                       # the runtime torch has already loaded
+        hip.hipMemcpy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int]
+        rc = hip.hipMemcpy(out.ctypes.data, ptr, out.nbytes, 2)      # device to host
+        assert rc == 0, f"hipMemcpy -> {rc}"
+        return out
 
     # host copies of the statistics in their declared types
     def stats_host(self):

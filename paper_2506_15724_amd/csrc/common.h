@@ -19,6 +19,23 @@ struct Dims {
   int heads;    // n * B * H
 };
 
+// Paged reduced cache (config.page_rows > 0): a head's kept rows fill whole pages that follow each other
+// (so selection and gather see one contiguous segment), the rows decode appends go on into the free
+// slots of the last of those pages and then into pages taken, on demand, from the top of the batch
+// item's region.  table[head][0] = number of initial pages, table[head][1 + j] = page of the j-th
+// page taken later; pool_top[b] = pages taken from the top of batch item b's region so far.
+struct Paging {
+  int page_rows;              // 0 = contiguous segments with max_new_tokens free rows each
+  int entries;                // table entries per head
+  int32_t* table;             // [n_layers * B * H][entries], owned by the handle
+  unsigned long long* pool_top;   // [B]
+  long long region_tokens;    // rows of one batch item's region
+  long long init_limit;       // rows of a region the initial segments may fill (the rest is kept for appended pages)
+};
+long long region_tokens_of(const madakv_config& c);     // rows of the reduced cache one batch item owns
+long long init_limit_of(const madakv_config& c);
+int page_table_entries(const madakv_config& c);
+
 struct ScorePlan { int nsplit; int chunk; int mpad; int group_heads; };
 struct DecodePlan { int chunk_rows; int max_chunks; };
 
@@ -38,7 +55,7 @@ hipError_t launch_allocate(const Dims& dm, const madakv_config& c, int layer0, c
                            const int32_t* n_mod, int32_t* budgets, long long* pool_state, hipStream_t st);
 hipError_t launch_offsets(const Dims& dm, const madakv_config& c, int layer0, const int32_t* budgets,
                           int64_t* kv_off, int32_t* kv_len, long long* cursor_state, int32_t* layer_maxlen, void* ws,
-                          long long region_tokens, int blocks_per_batch, hipStream_t st);
+                          const Paging& pg, int blocks_per_batch, hipStream_t st);
 hipError_t launch_select(const Dims& dm, const madakv_config& c, const float* psi_pool, const uint8_t* mask,
                          const int32_t* budgets, const int64_t* kv_off, const int32_t* kv_len, int32_t* kept_idx,
                          hipStream_t st);
@@ -48,7 +65,7 @@ hipError_t launch_gather(const Dims& dm, const madakv_config& c, int li0, int nl
                          int blocks_per_batch, int grid_blocks, hipStream_t st);
 hipError_t launch_decode(const Dims& dm, const madakv_config& c, const void* q, const void* k_new,
                          const void* v_new, void* k_c, void* v_c, const int64_t* kv_off, int32_t* kv_len,
-                         void* out, void* ws, long long capacity_tokens, int longest_rows, hipStream_t st);
+                         void* out, void* ws, long long capacity_tokens, int longest_rows, const Paging& pg, int layer0, hipStream_t st);
 
 constexpr int GATHER_ROWS = 64;   // rows of the reduced cache one gather workgroup fills
 

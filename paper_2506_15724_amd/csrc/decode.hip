@@ -39,6 +39,11 @@ struct DecodeArgs {
   const int64_t* kv_off; int32_t* kv_len; void* out; float* part;
   int B, H, G, d, chunk_rows, max_chunks, out_fp32, has_new;
   long long capacity;   // rows in k_c / v_c
+  // paged cache (page_rows > 0): see struct Paging
+  int page_rows, page_shift, tbl_entries;
+  int32_t* page_tbl; unsigned long long* pool_top;
+  long long region_pages;      // pages in one batch item's region
+  long long head0;             // index of the call's first head in the whole model (layer0 * B * H)
   float scale_log2;
 };
 
@@ -123,6 +128,58 @@ __device__ __forceinline__ void store_out(void* out, int out_fp32, long long o, 
   else reinterpret_cast<uint16_t*>(out)[o] = f32_to_bf16_rne(val);
 }
 
+// ---- where row r of a head lives ---------------------------------------------------------
+// Contiguous segments: at off + r.  Paged cache: the first init_rows rows (the head's initial pages,
+// which follow each other) likewise; later rows in pages listed in the head's table.  `fresh`
+// is the page this workgroup has just taken for the row being appended, if it had to take one
+// (the table entry it wrote is not yet visible to its other threads).
+struct RowMap {
+  long long off;
+  int init_rows;               // INT_MAX without paging
+  const int32_t* tbl;          // the head's table (entries 1.. = pages taken later)
+  int shift, fresh_slot;
+  long long fresh_page;
+  __device__ __forceinline__ long long operator()(int r) const {
+    if (r < init_rows) return off + r;
+    const int q = r - init_rows, j = q >> shift;
+    const long long pg = (j == fresh_slot) ? fresh_page : (long long)tbl[1 + j];
+    return (pg << shift) + (q & ((1 << shift) - 1));
+  }
+};
+
+__device__ __forceinline__ bool can_append_to(const DecodeArgs& a, long long off, int len_old) {
+  // an empty segment (its budgets did not fit the cache) stays empty; contiguous segments also end at the cache's end
+  return a.has_new && len_old > 0 && (a.page_rows ? true : off + len_old < a.capacity);
+}
+
+// All threads of the workgroup.  rows [r_begin, r_end) are the workgroup's; when the appended row is
+// among them and starts a new page, thread 0 takes the next page from the top of the batch item's region.
+__device__ __forceinline__ RowMap make_row_map(const DecodeArgs& a, long long hidx, long long off, int len_old, bool can_append,
+                                               int r_begin, int r_end) {
+  RowMap m;
+  m.off = off; m.init_rows = 0x7fffffff; m.tbl = nullptr; m.shift = 0; m.fresh_slot = -1; m.fresh_page = 0;
+  if (!a.page_rows) return m;
+  __shared__ long long s_fresh;
+  int32_t* tbl = a.page_tbl + (a.head0 + hidx) * a.tbl_entries;
+  m.tbl = tbl; m.shift = a.page_shift;
+  m.init_rows = tbl[0] << a.page_shift;
+  const int q = len_old - m.init_rows;
+  const bool takes = can_append && len_old >= r_begin && len_old < r_end && q >= 0 && (q & (a.page_rows - 1)) == 0;   // uniform
+  if (takes) {
+    if (threadIdx.x == 0) {
+      const long long b = ((a.head0 + hidx) / a.H) % a.B;
+      const unsigned long long nth = atomicAdd(a.pool_top + b, 1ULL);
+      const long long page = (b + 1) * a.region_pages - 1 - (long long)nth;
+      tbl[1 + (q >> a.page_shift)] = (int32_t)page;
+      s_fresh = page;
+    }
+    __syncthreads();
+    m.fresh_slot = q >> a.page_shift;
+    m.fresh_page = s_fresh;
+  }
+  return m;
+}
+
 template <typename T, typename CT, int LPR, int GT, int UNROLL, int NW>   // T: Q / new rows / out; CT: cache elements
 __global__ __launch_bounds__(NW * 64) void decode_attn_kernel(DecodeArgs a) {
   constexpr int EPL = Elems<CT>::EPL;
@@ -138,7 +195,7 @@ __global__ __launch_bounds__(NW * 64) void decode_attn_kernel(DecodeArgs a) {
   const int len_old = a.kv_len[hidx];
   const long long off = a.kv_off[hidx];
   // an empty segment (its budgets did not fit the cache) stays empty: no append, output 0/0 = NaN
-  const bool can_append = a.has_new && len_old > 0 && off + len_old < a.capacity;
+  const bool can_append = can_append_to(a, off, len_old);
   const int len = len_old + (can_append ? 1 : 0);
   const int nch = max(1, (len + a.chunk_rows - 1) / a.chunk_rows);
   if (chunk >= nch) return;                          // the grid is sized for the longest possible head
@@ -146,6 +203,7 @@ __global__ __launch_bounds__(NW * 64) void decode_attn_kernel(DecodeArgs a) {
   const int h = (int)(hidx % a.H);
   const int r_begin = chunk * a.chunk_rows;
   const int r_end = min(len, r_begin + a.chunk_rows);
+  const RowMap at = make_row_map(a, hidx, off, len_old, can_append, r_begin, r_end);
   // the NW waves take turns on consecutive RPI * UNROLL-row slices, so that at any moment the
   // workgroup reads one contiguous stretch of K and one of V
   constexpr int WSTEP = RPI * UNROLL;
@@ -187,11 +245,11 @@ __global__ __launch_bounds__(NW * 64) void decode_attn_kernel(DecodeArgs a) {
         if (can_append && r == len_old) {
           kraw[u] = cache_piece<T, CT>(kn + hidx * D + piece * EPL);
           vraw[u] = cache_piece<T, CT>(vn + hidx * D + piece * EPL);
-          reinterpret_cast<uint4*>(a.k_c)[(off + r) * LPR + piece] = kraw[u];     // Eq. 4: the row joins the cache
-          reinterpret_cast<uint4*>(a.v_c)[(off + r) * LPR + piece] = vraw[u];
+          reinterpret_cast<uint4*>(a.k_c)[at(r) * LPR + piece] = kraw[u];     // Eq. 4: the row joins the cache
+          reinterpret_cast<uint4*>(a.v_c)[at(r) * LPR + piece] = vraw[u];
         } else {
-          kraw[u] = stream_load16(kc + (off + r) * LPR + piece);
-          vraw[u] = stream_load16(vc + (off + r) * LPR + piece);
+          kraw[u] = stream_load16(kc + at(r) * LPR + piece);
+          vraw[u] = stream_load16(vc + at(r) * LPR + piece);
         }
       }
     }
@@ -344,7 +402,7 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_gqa_kernel(DecodeArgs a) {
   const int chunk = blockIdx.y;
   const int len_old = a.kv_len[hidx];
   const long long off = a.kv_off[hidx];
-  const bool can_append = a.has_new && len_old > 0 && off + len_old < a.capacity;
+  const bool can_append = can_append_to(a, off, len_old);
   const int len = len_old + (can_append ? 1 : 0);
   const int nch = max(1, (len + a.chunk_rows - 1) / a.chunk_rows);
   if (chunk >= nch) return;
@@ -352,6 +410,7 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_gqa_kernel(DecodeArgs a) {
   const int h = (int)(hidx % a.H);
   const int r_begin = chunk * a.chunk_rows;
   const int r_end = min(len, r_begin + a.chunk_rows);
+  const RowMap at = make_row_map(a, hidx, off, len_old, can_append, r_begin, r_end);
 
   const unsigned char* kc = reinterpret_cast<const unsigned char*>(a.k_c);   // cache rows of D * CB bytes
   const unsigned char* vc = reinterpret_cast<const unsigned char*>(a.v_c);
@@ -388,7 +447,7 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_gqa_kernel(DecodeArgs a) {
     const int rc = min(r, r_end - 1);                                                              \
     const bool fresh = can_append && rc == len_old;                                                \
     if (!fresh) {                                                                                  \
-      vraw[i] = __builtin_nontemporal_load(reinterpret_cast<const du32x4_t*>(vc + ((off + rc) * D + vpiece * VE) * CB)); \
+      vraw[i] = __builtin_nontemporal_load(reinterpret_cast<const du32x4_t*>(vc + (at(rc) * D + vpiece * VE) * CB)); \
     } else {                                                                                       \
       const uint16_t* np_ = vn + hidx * D + vpiece * VE;                                           \
       if (FP8) {                                                                                   \
@@ -398,7 +457,7 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_gqa_kernel(DecodeArgs a) {
       } else {                                                                                     \
         vraw[i] = *reinterpret_cast<const du32x4_t*>(np_);                                         \
       }                                                                                            \
-      if (r == rc) *reinterpret_cast<du32x4_t*>(vcw + ((off + rc) * D + vpiece * VE) * CB) = vraw[i]; /* Eq. 4 */ \
+      if (r == rc) *reinterpret_cast<du32x4_t*>(vcw + (at(rc) * D + vpiece * VE) * CB) = vraw[i]; /* Eq. 4 */ \
     }                                                                                              \
   }
 #define MADAKV_LOAD_K(T0)                                                                          \
@@ -407,7 +466,7 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_gqa_kernel(DecodeArgs a) {
     const int rc = min(r, r_end - 1);                                                              \
     const bool fresh = can_append && rc == len_old;                                                \
     _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                            \
-      const long long eo = (off + rc) * D + ks * 32 + c * 8;      /* element offset of the piece */ \
+      const long long eo = at(rc) * D + ks * 32 + c * 8;        /* element offset of the piece */ \
       if (!fresh) {                                                                                \
         if (FP8) { const du32x2_t t2 = __builtin_nontemporal_load(reinterpret_cast<const du32x2_t*>(kc + eo)); kraw[blk][ks] = du32x4_t{t2[0], t2[1], 0u, 0u}; } \
         else kraw[blk][ks] = __builtin_nontemporal_load(reinterpret_cast<const du32x4_t*>(kc + eo * 2)); \
@@ -566,7 +625,7 @@ __global__ __launch_bounds__(1024) void decode_merge_kernel(DecodeArgs a) {
   const long long hidx = blockIdx.x;
   const int len_old = a.kv_len[hidx];
   __syncthreads();                                   // every wave has read the length before anyone stores the new one
-  const bool can_append = a.has_new && len_old > 0 && a.kv_off[hidx] + len_old < a.capacity;
+  const bool can_append = can_append_to(a, a.kv_off[hidx], len_old);
   const int len = len_old + (can_append ? 1 : 0);
   const int nch = max(1, (len + a.chunk_rows - 1) / a.chunk_rows);
   if (can_append && threadIdx.x == 0) a.kv_len[hidx] = len;
@@ -653,9 +712,14 @@ static hipError_t launch_decode_t(const Dims& dm, DecodeArgs& a, hipStream_t st)
 
 hipError_t launch_decode(const Dims& dm, const madakv_config& c, const void* q, const void* k_new,
                          const void* v_new, void* k_c, void* v_c, const int64_t* kv_off, int32_t* kv_len,
-                         void* out, void* ws, long long capacity_tokens, int longest_rows, hipStream_t st) {
+                         void* out, void* ws, long long capacity_tokens, int longest_rows, const Paging& pg, int layer0, hipStream_t st) {
   DecodeArgs a;
   a.capacity = capacity_tokens;
+  a.page_rows = pg.page_rows; a.tbl_entries = pg.entries; a.page_tbl = pg.table; a.pool_top = pg.pool_top;
+  a.page_shift = 0;
+  while (pg.page_rows && (1 << a.page_shift) < pg.page_rows) ++a.page_shift;
+  a.region_pages = pg.page_rows ? pg.region_tokens / pg.page_rows : 0;
+  a.head0 = (long long)layer0 * dm.B * dm.H;
   a.q = q; a.k_new = k_new; a.v_new = v_new; a.k_c = k_c; a.v_c = v_c; a.kv_off = kv_off; a.kv_len = kv_len;
   a.out = out; a.part = reinterpret_cast<float*>(ws);
   DecodePlan p = decode_plan(dm, c, longest_rows);

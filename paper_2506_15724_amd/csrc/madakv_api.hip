@@ -27,7 +27,8 @@ struct madakv_handle {
   madakv_config cfg;
   int device;
   int32_t last_hip_error;
-  long long* d_state;              // [2 * B]: HCC pool per batch item, cache cursor per batch item
+  long long* d_state;              // [3 * B]: HCC pool, cache cursor, pages taken for appended rows (paged cache), per batch item
+  int32_t* d_page_tbl;             // paged cache: [n_layers * B * H][entries] page table (null otherwise)
   std::vector<int32_t> appended;   // decode rows appended so far, per layer
   // Longest head of each layer after eviction: written by the device, copied to pinned host
   // memory asynchronously; decode sizes its grid from it once the copy is known to have landed
@@ -47,6 +48,26 @@ struct madakv_handle {
   hipEvent_t ev_grp[MAX_GROUPS], ev_sel[MAX_GROUPS], ev_fork, ev_join;
 };
 
+namespace madakv {
+// Rows of the reduced cache one batch item owns.  Contiguous segments: every head has its kept rows plus
+// max_new_tokens free ones.  Paged: the kept rows of all heads in whole pages (the sum of budgets is
+// conserved, so at most one partly filled page per head) plus, shared by all heads, the pages
+// max_new_tokens appended rows per head can ever need.
+int page_table_entries(const madakv_config& c) {
+  return c.page_rows ? 2 + (c.max_new_tokens + c.page_rows - 1) / c.page_rows : 0;
+}
+long long init_limit_of(const madakv_config& c) {
+  const long long heads = (long long)c.n_layers * c.n_kv_heads, keep = std::min(c.budget, c.ctx_len);
+  if (!c.page_rows) return heads * (keep + c.max_new_tokens);
+  return heads * ((keep + c.page_rows - 1) / c.page_rows + 1) * c.page_rows;
+}
+long long region_tokens_of(const madakv_config& c) {
+  if (!c.page_rows) return init_limit_of(c);
+  const long long heads = (long long)c.n_layers * c.n_kv_heads;
+  return init_limit_of(c) + heads * ((c.max_new_tokens + c.page_rows - 1) / c.page_rows) * c.page_rows;
+}
+}  // namespace madakv
+
 namespace {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -61,12 +82,19 @@ Dims make_dims(const madakv_config& c, int n) {
   return dm;
 }
 
-long long region_tokens(const madakv_config& c) {
-  return (long long)c.n_layers * c.n_kv_heads * ((long long)std::min(c.budget, c.ctx_len) + c.max_new_tokens);
+long long region_tokens(const madakv_config& c) { return region_tokens_of(c); }
+
+Paging make_paging(const madakv_handle* h) {
+  const madakv_config& c = h->cfg;
+  Paging pg;
+  pg.page_rows = c.page_rows; pg.entries = page_table_entries(c); pg.table = h->d_page_tbl;
+  pg.pool_top = reinterpret_cast<unsigned long long*>(h->d_state + 2 * c.batch);
+  pg.region_tokens = region_tokens_of(c); pg.init_limit = init_limit_of(c);
+  return pg;
 }
 
 int blocks_per_batch(const madakv_config& c, int n) {
-  long long per_call = (long long)n * c.n_kv_heads * ((long long)c.ctx_len + c.max_new_tokens);
+  long long per_call = (long long)n * c.n_kv_heads * ((long long)c.ctx_len + c.max_new_tokens + 2 * c.page_rows);
   long long tokens = std::min(region_tokens(c), per_call);
   return (int)(tokens / GATHER_ROWS + 2);
 }
@@ -102,6 +130,8 @@ int32_t validate(const madakv_config& c) {
   if (!(c.theta > 0.f) || c.theta > 1.f) return MADAKV_ERR_INVALID_ARG;
   if (c.softmax_scale < 0.f || c.max_new_tokens < 0) return MADAKV_ERR_INVALID_ARG;
   if (c.mpa_mode < 0 || c.mpa_mode > 3 || c.hcc_mode < 0 || c.hcc_mode > 2 || (c.out_fp32 | 1) != 1) return MADAKV_ERR_INVALID_ARG;
+  if (c.page_rows != 0 && c.page_rows != 16 && c.page_rows != 32 && c.page_rows != 64 && c.page_rows != 128 && c.page_rows != 256)
+    return MADAKV_ERR_INVALID_ARG;
   if ((c.pool_mode | 1) != 1 || (c.share_mode | 1) != 1 || (c.select_mode | 1) != 1 || c.sink_tokens < 0) return MADAKV_ERR_INVALID_ARG;
   return MADAKV_OK;
 }
@@ -223,7 +253,7 @@ int32_t decode_impl(madakv_handle* h, int32_t layer0, int32_t n,
       if (h->appended[l] >= h->cfg.max_new_tokens) return MADAKV_ERR_INVALID_ARG;
   }
   hipError_t e = launch_decode(dm, h->cfg, q, k_new, v_new, k_c, v_c, kv_off, kv_len, out, ws,
-                               region_tokens(h->cfg) * h->cfg.batch, longest,
+                               region_tokens(h->cfg) * h->cfg.batch, longest, make_paging(h), layer0,
                                reinterpret_cast<hipStream_t>(stream));
   if (e == hipSuccess && k_new) for (int l = layer0; l < layer0 + n; ++l) h->appended[l] += 1;
   return hip_fail(h, e);
@@ -247,11 +277,16 @@ int32_t madakv_create(const madakv_config* cfg, madakv_handle** out) {
   h->side = nullptr; h->ev_fork = nullptr; h->ev_join = nullptr;
   for (int g = 0; g < MAX_GROUPS; ++g) { h->ev_grp[g] = nullptr; h->ev_sel[g] = nullptr; }
   h->appended.assign(cfg->n_layers, 0);
-  h->static_scratch = nullptr;
+  h->static_scratch = nullptr; h->d_page_tbl = nullptr;
   hipError_t e = hipGetDevice(&h->device);
   if (e == hipSuccess) e = static_scratch_on_current_device(h->device, &h->static_scratch);
-  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&h->d_state), sizeof(long long) * 2 * cfg->batch);
-  if (e == hipSuccess) e = hipMemset(h->d_state, 0, sizeof(long long) * 2 * cfg->batch);
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&h->d_state), sizeof(long long) * 3 * cfg->batch);
+  if (e == hipSuccess) e = hipMemset(h->d_state, 0, sizeof(long long) * 3 * cfg->batch);
+  if (cfg->page_rows) {
+    const size_t tb = sizeof(int32_t) * (size_t)cfg->n_layers * cfg->batch * cfg->n_kv_heads * page_table_entries(*cfg);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&h->d_page_tbl), tb);
+    if (e == hipSuccess) e = hipMemset(h->d_page_tbl, 0, tb);
+  }
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&h->d_maxlen), sizeof(int32_t) * cfg->n_layers * cfg->batch);
   if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&h->h_maxlen), sizeof(int32_t) * cfg->n_layers * cfg->batch, hipHostMallocDefault);
   if (e == hipSuccess) memset(h->h_maxlen, 0, sizeof(int32_t) * cfg->n_layers * cfg->batch);
@@ -263,6 +298,7 @@ int32_t madakv_create(const madakv_config* cfg, madakv_handle** out) {
   for (int g = 0; g < MAX_GROUPS && e == hipSuccess; ++g) e = hipEventCreateWithFlags(&h->ev_sel[g], hipEventDisableTiming);
   if (e != hipSuccess) {
     if (h->d_maxlen) (void)hipFree(h->d_maxlen);
+    if (h->d_page_tbl) (void)hipFree(h->d_page_tbl);
     if (h->h_maxlen) (void)hipHostFree(h->h_maxlen);
     if (h->maxlen_event) (void)hipEventDestroy(h->maxlen_event);
     destroy_side(h);
@@ -278,6 +314,7 @@ int32_t madakv_destroy(madakv_handle* h) {
   if (!h) return MADAKV_ERR_INVALID_ARG;
   hipError_t e = hipFree(h->d_state);
   (void)hipFree(h->d_maxlen);
+  if (h->d_page_tbl) (void)hipFree(h->d_page_tbl);
   (void)hipHostFree(h->h_maxlen);
   (void)hipEventDestroy(h->maxlen_event);
   destroy_side(h);
@@ -394,7 +431,7 @@ int32_t madakv_select_gather(madakv_handle* h, int32_t layer0, int32_t n,
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   const long long region = region_tokens(c);
   const int bpb = blocks_per_batch(c, n);
-  hipError_t e = launch_offsets(dm, c, layer0, budgets, kv_off, kv_len, h->d_state + c.batch, h->d_maxlen + (size_t)layer0 * c.batch, ws, region, bpb, st);
+  hipError_t e = launch_offsets(dm, c, layer0, budgets, kv_off, kv_len, h->d_state + c.batch, h->d_maxlen + (size_t)layer0 * c.batch, ws, make_paging(h), bpb, st);
   // (Running the selection of one layer group on the side stream under the gather of the
   // previous group was measured: the two starve each other and nothing is gained.)
   if (e == hipSuccess) e = launch_select(dm, c, psi_pool, mask, budgets, kv_off, kv_len, kept_idx, st);
@@ -453,7 +490,7 @@ int32_t madakv_evict(madakv_handle* h, int32_t layer0, int32_t n,
     if (e == hipSuccess) e = launch_stats(dg, c, psi_g, mask, pool_g, stats_g, g0 == 0 ? n_mod : nullptr, layer0 + g0, ss);
     if (e == hipSuccess) e = launch_allocate(dg, c, layer0 + g0, stats_g, n_mod, bud_g, h->d_state, ss);
     if (e == hipSuccess) e = launch_offsets(dg, c, layer0 + g0, bud_g, kv_off + heads0, kv_len + heads0, h->d_state + c.batch,
-                                            h->d_maxlen + (size_t)(layer0 + g0) * c.batch, ws_g, region, blocks_per_batch(c, ng), ss);
+                                            h->d_maxlen + (size_t)(layer0 + g0) * c.batch, ws_g, make_paging(h), blocks_per_batch(c, ng), ss);
     if (e == hipSuccess) e = launch_select(dg, c, pool_g, mask, bud_g, kv_off + heads0, kv_len + heads0, kept_idx, ss);
     if (overlap && e == hipSuccess) e = hipEventRecord(h->ev_sel[gi], h->side);
   }
@@ -489,6 +526,13 @@ int32_t madakv_decode_attn_static(madakv_handle* h, int32_t layer0, int32_t n,
   // no allocation on this path: this device's copy of the static array is all it uses beyond the caller's tensors
   return decode_impl(h, layer0, n, q, k_new, v_new, k_c, v_c, kv_off, kv_len, out, h->static_scratch, STATIC_SCRATCH_BYTES,
                      true, stream);
+}
+
+int32_t madakv_page_table(const madakv_handle* h, const int32_t** table, int32_t* entries_per_head) {
+  if (!h || !table || !entries_per_head) return MADAKV_ERR_INVALID_ARG;
+  *table = h->d_page_tbl;
+  *entries_per_head = page_table_entries(h->cfg);
+  return MADAKV_OK;
 }
 
 }  // extern "C"

@@ -27,7 +27,10 @@ constexpr int SEL_EPT = 32;                      // consecutive candidates a thr
 struct OffsetsArgs {
   const int32_t* budgets; int64_t* kv_off; int32_t* kv_len; long long* cursor; int32_t* blk2head; long long* call_range; int32_t* layer_maxlen;
   int n, B, H, L, W, layer0, max_new, keep_all, blocks_per_batch, M;
-  long long region_tokens;
+  long long region_tokens;       // rows of one batch item's region
+  long long init_limit;          // rows of it the segments laid out here may fill
+  int page_rows, tbl_entries;    // paged cache: segments are whole pages, no free rows reserved per head
+  int32_t* page_tbl; unsigned long long* pool_top;
 };
 
 // One workgroup per batch item; thread f of a trip owns head f of the call's (layer, head)
@@ -48,6 +51,7 @@ __global__ __launch_bounds__(OFF_THREADS) void offsets_kernel(OffsetsArgs a) {
   const long long blk_base = start / GATHER_ROWS;            // the block table is relative to the call's first block
   for (int li = tid; li < a.n; li += OFF_THREADS) s_lmax[li] = 0;
   if (tid == 0) { s_first_bad = 0x7fffffff; s_used = 0; }
+  if (tid == 0 && a.page_rows && a.layer0 == 0) a.pool_top[b] = 0ULL;   // a new pass: every page taken for appended rows is free again
   __syncthreads();
   long long carry = 0;                                        // rows laid out by earlier trips
   bool overflowed = false;                                    // a head did not fit: every later head is empty
@@ -62,6 +66,7 @@ __global__ __launch_bounds__(OFF_THREADS) void offsets_kernel(OffsetsArgs a) {
       if (!a.keep_all) for (int m = 0; m < a.M; ++m) len += a.budgets[idx * a.M + m];
     }
     long long seg = act ? len + a.max_new : 0;
+    if (a.page_rows) seg = act ? (len + a.page_rows - 1) / a.page_rows * a.page_rows : 0;
     long long incl = seg;
     for (int o = 1; o < 64; o <<= 1) {
       long long t = shfl_i64(incl, max(lane - o, 0));
@@ -75,7 +80,7 @@ __global__ __launch_bounds__(OFF_THREADS) void offsets_kernel(OffsetsArgs a) {
     // Budgets that do not add up to the configured total could run past the batch item's
     // region: the first head that does not fit, and every head after it, gets an empty
     // segment (kv_len 0) at the end of what was laid out, so nothing is written outside.
-    const bool bad = act && (overflowed || start + abs_incl > a.region_tokens);
+    const bool bad = act && (overflowed || start + abs_incl > a.init_limit);
     if (bad && !overflowed) atomicMin(&s_first_bad, f);
     __syncthreads();
     const int first_bad = s_first_bad;
@@ -90,6 +95,7 @@ __global__ __launch_bounds__(OFF_THREADS) void offsets_kernel(OffsetsArgs a) {
       atomicMax(&s_lmax[li], (int)len);                       // longest segment of the layer, for the decode grid
       a.kv_off[idx] = region + off;
       a.kv_len[idx] = (int32_t)len;
+      if (a.page_rows) a.page_tbl[(((long long)(a.layer0 + li) * a.B + b) * a.H + h) * a.tbl_entries] = (int32_t)(seg / a.page_rows);
       // blocks whose first row lies inside this segment
       const long long b0 = (off + GATHER_ROWS - 1) / GATHER_ROWS, b1 = seg > 0 ? (off + seg - 1) / GATHER_ROWS : b0 - 1;
       for (long long blk = b0; blk <= b1; ++blk) {
@@ -382,9 +388,8 @@ __global__ __launch_bounds__(SEL_THREADS) __attribute__((amdgpu_waves_per_eu(MM 
 }
 
 size_t select_ws_bytes(const Dims& dm, const madakv_config& c) {
-  long long keep = std::min(c.budget, c.ctx_len);
-  long long per_batch_model = (long long)c.n_layers * dm.H * (keep + c.max_new_tokens);
-  long long per_batch_call = (long long)dm.n * dm.H * ((long long)dm.L + c.max_new_tokens);
+  long long per_batch_model = region_tokens_of(c);
+  long long per_batch_call = (long long)dm.n * dm.H * ((long long)dm.L + c.max_new_tokens + 2 * c.page_rows);
   long long tokens = std::min(per_batch_model, per_batch_call);
   long long blocks = tokens / GATHER_ROWS + 2;
   return (size_t)dm.B * blocks * sizeof(int32_t) + (size_t)dm.B * 2 * sizeof(long long) + 64;
@@ -392,7 +397,7 @@ size_t select_ws_bytes(const Dims& dm, const madakv_config& c) {
 
 hipError_t launch_offsets(const Dims& dm, const madakv_config& c, int layer0, const int32_t* budgets,
                           int64_t* kv_off, int32_t* kv_len, long long* cursor_state, int32_t* layer_maxlen, void* ws,
-                          long long region_tokens, int blocks_per_batch, hipStream_t st) {
+                          const Paging& pg, int blocks_per_batch, hipStream_t st) {
   OffsetsArgs a;
   a.layer_maxlen = layer_maxlen;
   a.budgets = budgets; a.kv_off = kv_off; a.kv_len = kv_len; a.cursor = cursor_state;
@@ -400,7 +405,8 @@ hipError_t launch_offsets(const Dims& dm, const madakv_config& c, int layer0, co
   a.blk2head = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(ws) + ((size_t)dm.B * 2 * sizeof(long long) + 63) / 64 * 64);
   a.n = dm.n; a.B = dm.B; a.H = dm.H; a.L = dm.L; a.W = dm.W; a.layer0 = layer0; a.M = c.n_modalities;
   a.max_new = c.max_new_tokens; a.keep_all = c.budget >= c.ctx_len ? 1 : 0;
-  a.blocks_per_batch = blocks_per_batch; a.region_tokens = region_tokens;
+  a.blocks_per_batch = blocks_per_batch; a.region_tokens = pg.region_tokens; a.init_limit = pg.init_limit;
+  a.page_rows = pg.page_rows; a.tbl_entries = pg.entries; a.page_tbl = pg.table; a.pool_top = pg.pool_top;
   hipLaunchKernelGGL(offsets_kernel, dim3(dm.B), dim3(OFF_THREADS), 0, st, a);
   return hipGetLastError();
 }

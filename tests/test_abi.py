@@ -41,7 +41,7 @@ def test_config_struct_matches_header_layout():
 def good(**kw):
     base = dict(n_layers=2, batch=1, n_q_heads=8, n_kv_heads=8, head_dim=128, ctx_len=1024, window=32, budget=256,
                 dtype=MB.BF16, pool_k=7, mpa_mode=1, hcc_mode=1, hcc_rho=2, theta=0.9, softmax_scale=0.0,
-                max_new_tokens=4, out_fp32=1, pool_mode=0, share_mode=0, select_mode=0, sink_tokens=4, cache_fp8=0, n_modalities=2)
+                max_new_tokens=4, out_fp32=1, pool_mode=0, share_mode=0, select_mode=0, sink_tokens=4, cache_fp8=0, n_modalities=2, page_rows=0)
     base.update(kw)
     return MB.Config(*[base[f[0]] for f in MB.Config._fields_])
 
@@ -68,6 +68,8 @@ def good(**kw):
     (dict(cache_fp8=2), -1),
     (dict(n_modalities=5), -2),
     (dict(select_mode=1, sink_tokens=-1), -1),
+    (dict(page_rows=48), -1),                      # pages are 16 .. 256 rows, powers of two
+    (dict(page_rows=512), -1),
 ])
 def test_create_rejects_bad_config_on_host(kw, status):
     h = C.c_void_p()

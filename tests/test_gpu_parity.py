@@ -647,6 +647,101 @@ def test_one_sweep_scoring_and_its_lone_workgroup_path(name):
     eng.close()
 
 
+def _logical_rows(eng, cache, l, b, h, length, P):
+    """Rows 0..length-1 of a head of the paged cache, read back through the page table."""
+    tbl = eng.page_table_host()[l, b, h]
+    off = int(eng.kv_off[l, b, h])
+    init = int(tbl[0]) * P
+    idx = [off + r if r < init else int(tbl[1 + (r - init) // P]) * P + (r - init) % P for r in range(length)]
+    return cache[torch.tensor(idx, device=cache.device)]
+
+
+@pytest.mark.parametrize("name,P,fp8", [("bf16_mha", 16, 0), ("bf16_gqa7", 32, 0), ("bf16_odd", 16, 0), ("bf16_mha", 64, 1),
+                                        ("fp32_d128", 16, 0)])
+def test_paged_reduced_cache(name, P, fp8):
+    """page_rows > 0: kept rows in whole pages, appended rows in pages taken on demand.  The eviction
+    gives the same kept positions and rows as with contiguous segments; many decode steps, crossing
+    page boundaries in every head, give bit for bit the outputs of the contiguous cache and match the
+    oracle; the rows read back through the page table are the kept rows followed by the appended ones."""
+    steps = 2 * P + 5
+    wl = small_workloads()[name].scaled(decode_steps=steps)
+    NL, B, H, L, W, d = wl.n_layers, wl.batch, wl.n_kv_heads, wl.ctx_len, wl.window, wl.head_dim
+    p = PU.oracle_params(wl)
+    q, k, v, mask, masks = PU.make_inputs(wl, DEV)
+    flat, paged = engine(wl, cache_fp8=fp8), engine(wl, cache_fp8=fp8, page_rows=P)
+    for eng in (flat, paged):
+        eng.score(0, NL, q, k, mask); eng.allocate(0, NL); eng.select_gather(0, NL, k, v, mask)
+    torch.cuda.synchronize()
+    assert torch.equal(flat.budgets, paged.budgets) and torch.equal(flat.kv_len, paged.kv_len)
+    len0 = paged.kv_len.cpu().numpy()
+    off_f, off_p = flat.kv_off.cpu().numpy(), paged.kv_off.cpu().numpy()
+    tbl = paged.page_table_host()
+    cap_b = paged.capacity // B
+    for b in range(B):
+        cursor = b * cap_b
+        for l in range(NL):
+            for h in range(H):
+                n = int(len0[l, b, h])
+                assert off_p[l, b, h] == cursor and off_p[l, b, h] % P == 0 and tbl[l, b, h, 0] == -(-n // P)
+                cursor += -(-n // P) * P
+                assert torch.equal(paged.kept_idx[off_p[l, b, h]:off_p[l, b, h] + n], flat.kept_idx[off_f[l, b, h]:off_f[l, b, h] + n])
+                assert torch.equal(paged.k_c[off_p[l, b, h]:off_p[l, b, h] + n], flat.k_c[off_f[l, b, h]:off_f[l, b, h] + n])
+                assert torch.equal(paged.v_c[off_p[l, b, h]:off_p[l, b, h] + n], flat.v_c[off_f[l, b, h]:off_f[l, b, h] + n])
+    # the oracle's copy of two sampled heads' caches (decoded values for the 8-bit cache)
+    dec = (lambda t: O.dequantize_e4m3(t.cpu().numpy())) if fp8 else WL.to_f64
+    samples = [(0, 0, 0), (NL - 1, B - 1, H - 1)]
+    caches = {s: [dec(flat.k_c[off_f[s]:off_f[s] + int(len0[s])]), dec(flat.v_c[off_f[s]:off_f[s] + int(len0[s])])] for s in samples}
+    out_f = torch.empty(NL, B, wl.n_q_heads, d, dtype=torch.float32, device=DEV)
+    out_p = torch.empty_like(out_f)
+    G = wl.n_q_heads // H
+    quant = (lambda x: O.dequantize_e4m3(O.quantize_e4m3(x))) if fp8 else (lambda x: x)
+    for step in range(steps):
+        dq, dk, dv = WL.decode_inputs_all(wl, step, DEV)
+        for eng, out in ((flat, out_f), (paged, out_p)):
+            if step % 3 == 0:
+                eng.decode_attn(0, NL, dq, dk, dv, out)
+            else:
+                for l in range(NL):
+                    eng.decode_attn(l, 1, dq[l:l + 1], dk[l:l + 1], dv[l:l + 1], out[l:l + 1])
+        torch.cuda.synchronize()
+        assert torch.equal(out_f, out_p), f"paged and contiguous caches differ at step {step}"
+        for (l, b, h) in samples:
+            kc, vc = caches[(l, b, h)]
+            kc = np.concatenate([kc, quant(WL.to_f64(dk[l, b, h]))[None]]); vc = np.concatenate([vc, quant(WL.to_f64(dv[l, b, h]))[None]])
+            caches[(l, b, h)] = [kc, vc]
+            if step in (0, P, steps - 1):
+                for g in range(G):
+                    ref = O.attend(WL.to_f64(dq[l, b, h * G + g]), kc, vc, p.scale)
+                    assert np.abs(out_p[l, b, h * G + g].cpu().numpy() - ref).max() <= PU.DECODE_ATOL
+    assert (paged.kv_len.cpu().numpy() == len0 + steps).all()
+    # every head took the pages its appended rows needed, all different, all inside its batch item's region
+    tbl = paged.page_table_host()
+    for b in range(B):
+        taken = []
+        for l in range(NL):
+            for h in range(H):
+                n0 = int(len0[l, b, h]); init = int(tbl[l, b, h, 0])
+                extra = max(0, -(-(n0 + steps - init * P) // P))
+                taken += [int(x) for x in tbl[l, b, h, 1:1 + extra]]
+        assert len(set(taken)) == len(taken)
+        assert all(b * cap_b // P <= x < (b + 1) * cap_b // P for x in taken)
+    for (l, b, h) in samples:
+        n = int(len0[l, b, h]) + steps
+        np.testing.assert_array_equal(dec(_logical_rows(paged, paged.k_c, l, b, h, n, P)), caches[(l, b, h)][0])
+        np.testing.assert_array_equal(dec(_logical_rows(paged, paged.v_c, l, b, h, n, P)), caches[(l, b, h)][1])
+    # a new pass hands every page back
+    paged.select_gather(0, NL, k, v, mask)
+    dq, dk, dv = WL.decode_inputs_all(wl, 0, DEV)
+    paged.decode_attn(0, NL, dq, dk, dv, out_p)
+    flat.select_gather(0, NL, k, v, mask)
+    flat.decode_attn(0, NL, dq, dk, dv, out_f)
+    torch.cuda.synchronize()
+    assert torch.equal(out_f, out_p)
+    with pytest.raises(MB.MadaKVError):
+        MB.MadaKV(n_layers=1, batch=1, n_q_heads=1, n_kv_heads=1, head_dim=64, ctx_len=100, window=4, budget=20, page_rows=24, device=DEV)
+    flat.close(); paged.close()
+
+
 def test_error_paths_and_streams():
     """Host-side refusals on a live handle (nothing is enqueued), and calls on a non-default stream."""
     wl = small_workloads()["bf16_mha"].scaled(n_layers=2, batch=1, decode_steps=1)
