@@ -262,6 +262,7 @@ def main():
     NL, B, H, Hq, L, W, d = wl.n_layers, wl.batch, wl.n_kv_heads, wl.n_q_heads, wl.ctx_len, wl.window, wl.head_dim
     es = 2 if wl.dtype == "bf16" else 4
     S = a.decode_steps if a.decode_steps > 0 else wl.decode_steps
+    G_ = Hq // H
     log(f"workload {wl.name}: {NL} layers, B={B}, H={H}, L={L}, d={d}, W={W}, budget={wl.budget}, {S} decode steps")
     t0 = time.time()
     q, k, v, mask, masks = build_inputs(wl, dev)
@@ -576,6 +577,28 @@ def main():
             del full, fc
         except Exception as ex:                       # memory for the second cache may be short on a shared box
             result["decode_full_cache"] = {"error": str(ex)[:200]}
+
+    if not a.no_extras and wl.budget < L and G_ * W <= 64:
+        # re-eviction during generation: 64 decode steps, then every head back to its prompt-time length
+        # (one-sweep scoring over the rows of the reduced cache, per-head split, selection, in-place compaction)
+        try:
+            eng.evict(0, NL, q, k, v, mask)
+            nst = min(S, 64)
+            for s_ in range(nst):
+                calls.run_step(s_, stream)
+            qr = dq[:W].permute(1, 2, 3, 0, 4).contiguous() if S >= W else torch.randn(NL, B, Hq, W, d, device=dev).to(wl.torch_dtype)
+            rows_before = int(eng.kv_len.to(torch.int64).sum().item())
+            eng.reevict_ws = torch.empty(MB.madakv_reevict_workspace_bytes(eng.h, NL), dtype=torch.uint8, device=dev)
+            torch.cuda.synchronize()
+            e0.record(); eng.reevict(0, NL, qr, mask); e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            result["reevict"] = {"after_decode_steps": nst, "ms": ms, "cache_rows_before": rows_before,
+                                 "cache_rows_after": int(eng.kv_len.to(torch.int64).sum().item()),
+                                 "algorithmic_GBps": (rows_before * d * es + 4 * int(eng.kv_len.to(torch.int64).sum().item()) * d * es) / (ms * 1e-3) / 1e9,
+                                 "note": "bytes = K rows of the grown cache read once for scoring + surviving K,V rows read and written"}
+        except Exception as ex:
+            result["reevict"] = {"error": str(ex)[:200]}
 
     if not a.no_extras and wl.name == "llava_16k":
         # the other named configurations that are large enough to time: the Qwen-shaped grouped-query model

@@ -238,6 +238,36 @@ int32_t madakv_decode_attn(madakv_handle* h, int32_t layer0, int32_t n,
                            void* k_c, void* v_c, const int64_t* kv_off, int32_t* kv_len,
                            void* out, void* ws, size_t ws_bytes, void* stream);
 
+/* Re-eviction during generation (the paper evicts once, after the prefill, Sec. 3.3; its Sec. 6 leaves long
+ * generation open).  After some decode steps every head's segment holds its kept rows, the W window rows and
+ * the appended rows.  The call brings each head of layers [layer0, layer0 + n) back to the length the prompt
+ * eviction gave it, in place:
+ *   - the last W rows of the segment are the new proxy set; q_recent holds their queries;
+ *   - every earlier row is a candidate, scored as in Eq. 7 over the rows of the segment (proxy row r sees
+ *     the rows up to its own), pooled over neighbouring rows as configured;
+ *   - the head's total stays budgets_total = (length after the last (re-)eviction) - W: the layer
+ *     compensation of Eq. 9-11 is a prefill decision and is not re-run;
+ *   - the total is split over the modalities by the current masses (Eq. 6, Eq. 8, same integer rules as
+ *     madakv_allocate; a prompt token has the modality of its position in `mask`, a generated token is text);
+ *   - per modality the best-scored candidates survive (equal scores: lower row), in row order, followed by
+ *     the W proxy rows; K, V and kept_idx rows move down inside the segment.
+ *   q_recent [n, B, Hq, W, d]   queries of the tokens in the last W rows of every segment, oldest first
+ *   mask     [B, L]
+ *   k_c, v_c, kept_idx, kv_off  as left by madakv_select_gather / madakv_evict and madakv_decode_attn;
+ *                               kept_idx entries of generated tokens read ctx_len + (index of the token
+ *                               in the generation) afterwards
+ *   kv_len   [n, B, H]          in/out: back to its value after the prompt eviction
+ *   budgets  [n, B, H, M]       out: the new split
+ *   ws                          madakv_reevict_workspace_bytes(h, n) bytes
+ * The decode-step counters of the layers are reset: max_new_tokens rows can be appended again.
+ * MADAKV_ERR_UNIMPLEMENTED with a paged or 8-bit cache, dtype fp32, G * W > 64 or segments longer than
+ * 65536 rows; MADAKV_ERR_BAD_BUDGET when budget >= ctx_len (nothing was evicted). */
+int32_t madakv_reevict_workspace_bytes(const madakv_handle* h, int32_t n_layers_per_call, size_t* bytes);
+int32_t madakv_reevict(madakv_handle* h, int32_t layer0, int32_t n,
+                       const void* q_recent, const uint8_t* mask,
+                       void* k_c, void* v_c, int32_t* kept_idx, const int64_t* kv_off, int32_t* kv_len,
+                       int32_t* budgets, void* ws, size_t ws_bytes, void* stream);
+
 /* Paged reduced cache (page_rows > 0): where the rows of a head are.  Rows [0, table[0] * page_rows) of head
  * (l, b, h) sit at kv_off[l, b, h] + r (its initial pages follow each other); row r beyond that sits in page
  * table[1 + (r - table[0] * page_rows) / page_rows] at slot r % page_rows, a page p covering rows

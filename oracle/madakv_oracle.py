@@ -525,6 +525,39 @@ def decode_step(q: np.ndarray, k_new, v_new, k_cache: list, v_cache: list, scale
 
 
 # --------------------------------------------------------------------------- #
+# Re-eviction during generation (not in the paper, which evicts once after the prefill; its
+# Sec. 6 leaves long generation open)
+# --------------------------------------------------------------------------- #
+def reevict_head(q_recent_h: np.ndarray, k_rows: np.ndarray, v_rows: np.ndarray, origin: np.ndarray, mask: np.ndarray,
+                 total: int, p: Params):
+    """One KV head whose cache has grown by appended rows is brought back to `total` + W rows.
+    q_recent_h [G, W, d]: queries of the tokens in the last W rows; k_rows, v_rows [len, d]: the
+    head's cache; origin [len]: original position of every row (< ctx_len: a prompt position whose
+    modality the mask gives; >= ctx_len: a generated token, which is text).
+    The steps are those of the prompt eviction applied to the rows of the cache, per head: Eq. 7
+    with the last W rows as proxies (proxy r sees rows up to its own), Eq. 6 masses and candidate
+    counts over the rows before them, pooling over neighbouring rows, the Eq. 8 split of the
+    unchanged total, the best candidates per modality (ties: lower row), then the proxies.
+    Returns (sel rows, budgets, w, n_mod, psi, psi_pool)."""
+    n, W = k_rows.shape[0], p.window
+    rowmod = np.where(origin < p.ctx_len, mask[np.minimum(origin, p.ctx_len - 1)], TEXT).astype(mask.dtype)
+    rowmod = np.minimum(rowmod, p.n_modalities - 1)
+    psi = window_scores(q_recent_h, k_rows[None], p.scale)[0]
+    psi = psi.astype(np.float32).astype(np.float64)                       # the scores cross an fp32 interface
+    w, n_mod = modality_mass(psi, rowmod, 0 if p.share_mode else W, p.n_modalities)
+    if p.share_mode:                                                      # masses over all rows, counts over the candidates
+        n_mod = modality_mass(psi, rowmod, W, p.n_modalities)[1]
+    pool = pool_scores(psi[None], W, p.pool_k, p.pool_mode)[0]
+    w32 = np.asarray(w, dtype=np.float32).astype(np.float64)
+    bud = [min(total, n - W), 0] + [0] * (p.n_modalities - 2) if p.mpa_mode == 0 else mpa_split_n(min(total, n - W), w32, n_mod, p.mpa_mode)
+    if p.select_mode == 1:
+        sel = select_sink_recent(sum(bud), n, W, p.sink_tokens)
+    else:
+        sel = select_n(pool, rowmod, bud, n, W, p.mpa_mode)
+    return sel, bud, w, n_mod, psi, pool
+
+
+# --------------------------------------------------------------------------- #
 # The whole eviction for one batch item
 # --------------------------------------------------------------------------- #
 def score_layer(q_win: np.ndarray, k: np.ndarray, mask: np.ndarray, p: Params,

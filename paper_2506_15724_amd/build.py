@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmadakv.so")
-SOURCES = ["madakv_api.hip", "score.hip", "stats.hip", "allocate.hip", "select.hip", "gather.hip", "decode.hip"]
+SOURCES = ["madakv_api.hip", "score.hip", "stats.hip", "allocate.hip", "select.hip", "gather.hip", "decode.hip", "reevict.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

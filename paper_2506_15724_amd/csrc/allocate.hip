@@ -15,6 +15,7 @@
 // keeps the exact product and changes which of two nearly equal fractional parts is the
 // larger, so contraction is switched off for this file.
 #include "common.h"
+#include "mpa_split.h"
 
 #pragma clang fp contract(off)
 
@@ -45,7 +46,6 @@ __global__ __launch_bounds__(64) void allocate_kernel(AllocArgs a) {
   long long nm[MAXM];
 #pragma unroll
   for (int m = 0; m < MAXM; ++m) nm[m] = m < M ? a.n_mod[b * M + m] : 0;
-  const long long n_t = nm[0], n_v = nm[1];
   const long long H = a.H, nc = a.nc, rho = a.rho, beta = a.beta;
   long long R = (a.layer0 == 0) ? (long long)a.NL * H * beta : a.pool[b];
   long long bf = beta / (rho * rho);
@@ -107,76 +107,9 @@ __global__ __launch_bounds__(64) void allocate_kernel(AllocArgs a) {
       }
       R -= A;
     }
-    if (act && M == 2) {
-      long long bt, bv;
-      if (a.mpa_mode == 0) {
-        bt = ah; bv = 0;
-      } else {
-        // Eq. 8: the share is formed in double from the float masses that crossed the interface
-        const double wt = (double)wm[0], wv = (double)wm[1];
-        const double tot = wt + wv;
-        double share;
-        if (tot > 0.0) share = wt / tot;
-        else share = (n_t + n_v) > 0 ? (double)n_t / (double)(n_t + n_v) : 0.0;
-        if (a.mpa_mode == 2) share = 1.0;            // fixed priority baselines: text first / image first
-        else if (a.mpa_mode == 3) share = 0.0;
-        bt = (long long)floor(share * (double)ah + 0.5);
-        bv = ah - bt;
-        if (bt > n_t) { bt = n_t; bv = ah - n_t; }
-        if (bv > n_v) { bv = n_v; bt = ah - n_v; }
-      }
-      a.budgets[idx * 2] = (int32_t)bt;
-      a.budgets[idx * 2 + 1] = (int32_t)bv;
-    } else if (act) {
-      // Eq. 8, M-way: floor the quotas, spare tokens to the largest fractional parts (ties: lower
-      // id); a modality short of candidates is cut to what it has, the surplus goes to the others
-      // in order of decreasing share (ties: lower id).  All loops are over at most 4 modalities.
-      long long bm[MAXM] = {0, 0, 0, 0};
-      if (a.mpa_mode == 0) {
-        bm[0] = ah;
-      } else if (a.mpa_mode == 2 || a.mpa_mode == 3) {
-        long long left = ah;
-        for (int j = 0; j < M; ++j) {
-          const int m = a.mpa_mode == 2 ? j : M - 1 - j;
-          bm[m] = left < nm[m] ? left : nm[m];
-          left -= bm[m];
-        }
-      } else {
-        double tot = 0.0; long long nt = 0;
-        for (int m = 0; m < M; ++m) { tot += (double)wm[m]; nt += nm[m]; }
-        double share[MAXM] = {0, 0, 0, 0}, frac[MAXM] = {0, 0, 0, 0};
-        long long sumb = 0;
-        for (int m = 0; m < M; ++m) {
-          share[m] = tot > 0.0 ? (double)wm[m] / tot : (nt > 0 ? (double)nm[m] / (double)nt : 0.0);
-          const double quota = share[m] * (double)ah;
-          bm[m] = (long long)floor(quota);
-          frac[m] = quota - (double)bm[m];
-          sumb += bm[m];
-        }
-        const long long spare = ah - sumb;
-        long long add[MAXM] = {0, 0, 0, 0};
-        for (int m = 0; m < M; ++m) {
-          int rank = 0;
-          for (int o = 0; o < M; ++o) if (frac[o] > frac[m] || (frac[o] == frac[m] && o < m)) ++rank;
-          add[m] = rank < spare ? 1 : 0;
-        }
-        long long surplus = 0;
-        for (int m = 0; m < M; ++m) {
-          bm[m] += add[m];
-          if (bm[m] > nm[m]) { surplus += bm[m] - nm[m]; bm[m] = nm[m]; }
-        }
-        for (int r = 0; r < M; ++r) {                 // r-th largest share takes what it has room for
-          for (int m = 0; m < M; ++m) {
-            int rank = 0;
-            for (int o = 0; o < M; ++o) if (share[o] > share[m] || (share[o] == share[m] && o < m)) ++rank;
-            if (rank == r) {
-              const long long room = nm[m] - bm[m];
-              const long long give = surplus < room ? surplus : room;
-              bm[m] += give; surplus -= give;
-            }
-          }
-        }
-      }
+    if (act) {
+      long long bm[MAXM];
+      mpa_split_device(ah, wm, nm, M, a.mpa_mode, bm);
       for (int m = 0; m < M; ++m) a.budgets[idx * M + m] = (int32_t)bm[m];
     }
   }

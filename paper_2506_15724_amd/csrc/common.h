@@ -58,7 +58,17 @@ hipError_t launch_offsets(const Dims& dm, const madakv_config& c, int layer0, co
                           const Paging& pg, int blocks_per_batch, hipStream_t st);
 hipError_t launch_select(const Dims& dm, const madakv_config& c, const float* psi_pool, const uint8_t* mask,
                          const int32_t* budgets, const int64_t* kv_off, const int32_t* kv_len, int32_t* kept_idx,
-                         hipStream_t st);
+                         hipStream_t st, const int32_t* seg_len = nullptr, const uint8_t* rowmod = nullptr);
+// re-eviction during generation (reevict.hip, and the one-sweep scoring kernel on ragged segments)
+bool score_ragged_supported(const Dims& dm, const madakv_config& c, int longest_rows);
+size_t score_ragged_ws_bytes(const Dims& dm, const madakv_config& c, int longest_rows);
+hipError_t launch_score_ragged(const Dims& dm, const madakv_config& c, const void* q_recent, const void* k_c,
+                               const int64_t* seg_off, const int32_t* seg_len, int longest_rows, float* psi_c, void* ws, hipStream_t st);
+hipError_t launch_restats(const Dims& dm, const madakv_config& c, const float* psi_c, const int32_t* kept_idx, const uint8_t* mask,
+                          const int64_t* seg_off, const int32_t* seg_len, int appended, float* pool_c, uint8_t* rowmod,
+                          void* stats, int32_t* budgets, hipStream_t st);
+hipError_t launch_compact(const Dims& dm, const madakv_config& c, void* k_c, void* v_c, int32_t* kept_idx, const int32_t* sel,
+                          const int64_t* seg_off, int32_t* kv_len, const int32_t* budgets, int appended, int gen_base, hipStream_t st);
 hipError_t launch_gather(const Dims& dm, const madakv_config& c, int li0, int nli, const void* k, const void* v,
                          const int32_t* kept_idx, const int64_t* kv_off, const int32_t* kv_len,
                          void* k_c, void* v_c, const void* ws, long long region_tokens,

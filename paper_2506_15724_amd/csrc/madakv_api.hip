@@ -29,7 +29,8 @@ struct madakv_handle {
   int32_t last_hip_error;
   long long* d_state;              // [3 * B]: HCC pool, cache cursor, pages taken for appended rows (paged cache), per batch item
   int32_t* d_page_tbl;             // paged cache: [n_layers * B * H][entries] page table (null otherwise)
-  std::vector<int32_t> appended;   // decode rows appended so far, per layer
+  std::vector<int32_t> appended;   // decode rows appended since the last (re-)eviction, per layer
+  std::vector<int32_t> gen_base;   // tokens generated before that, per layer (their original positions are ctx_len + 0, 1, ...)
   // Longest head of each layer after eviction: written by the device, copied to pinned host
   // memory asynchronously; decode sizes its grid from it once the copy is known to have landed
   // (event query, never a wait) and from the worst case before that.
@@ -277,6 +278,7 @@ int32_t madakv_create(const madakv_config* cfg, madakv_handle** out) {
   h->side = nullptr; h->ev_fork = nullptr; h->ev_join = nullptr;
   for (int g = 0; g < MAX_GROUPS; ++g) { h->ev_grp[g] = nullptr; h->ev_sel[g] = nullptr; }
   h->appended.assign(cfg->n_layers, 0);
+  h->gen_base.assign(cfg->n_layers, 0);
   h->static_scratch = nullptr; h->d_page_tbl = nullptr;
   hipError_t e = hipGetDevice(&h->device);
   if (e == hipSuccess) e = static_scratch_on_current_device(h->device, &h->static_scratch);
@@ -436,7 +438,7 @@ int32_t madakv_select_gather(madakv_handle* h, int32_t layer0, int32_t n,
   // previous group was measured: the two starve each other and nothing is gained.)
   if (e == hipSuccess) e = launch_select(dm, c, psi_pool, mask, budgets, kv_off, kv_len, kept_idx, st);
   if (e == hipSuccess) e = launch_gather(dm, c, 0, n, k, v, kept_idx, kv_off, kv_len, k_c, v_c, ws, region, bpb, bpb, st);
-  for (int l = layer0; l < layer0 + n; ++l) h->appended[l] = 0;
+  for (int l = layer0; l < layer0 + n; ++l) { h->appended[l] = 0; h->gen_base[l] = 0; }
   e = publish_maxlen(h, layer0, n, st, e);
   return hip_fail(h, e);
 }
@@ -506,7 +508,7 @@ int32_t madakv_evict(madakv_handle* h, int32_t layer0, int32_t n,
     if (e == hipSuccess) e = launch_gather(dg, c, 0, ng, kg, vg, kept_idx, kv_off + heads0, kv_len + heads0, k_c, v_c, ws_g, region, bpb, bpb, st);
   }
   if (overlap && e != hipSuccess) e = join_side(h, st, e);   // an enqueue failed: whatever did reach the side stream is still joined
-  for (int l = layer0; l < layer0 + n; ++l) h->appended[l] = 0;
+  for (int l = layer0; l < layer0 + n; ++l) { h->appended[l] = 0; h->gen_base[l] = 0; }
   e = publish_maxlen(h, layer0, n, st, e);
   return hip_fail(h, e);
 }
@@ -526,6 +528,73 @@ int32_t madakv_decode_attn_static(madakv_handle* h, int32_t layer0, int32_t n,
   // no allocation on this path: this device's copy of the static array is all it uses beyond the caller's tensors
   return decode_impl(h, layer0, n, q, k_new, v_new, k_c, v_c, kv_off, kv_len, out, h->static_scratch, STATIC_SCRATCH_BYTES,
                      true, stream);
+}
+
+namespace {
+// workspace of madakv_reevict: per-row arrays over the whole reduced cache (rows are addressed as in k_c),
+// the per-head records of the call, the exchange array of the scoring kernel
+struct ReevictWs { size_t psi, pool, sel, rowmod, stats, score, total; };
+ReevictWs reevict_layout(const madakv_handle* h, int n) {
+  const madakv_config& c = h->cfg;
+  const size_t cap = (size_t)(region_tokens(c) * c.batch);
+  const Dims dm = make_dims(c, n);
+  auto up = [](size_t x) { return (x + 255) / 256 * 256; };
+  ReevictWs w;
+  w.psi = 0; w.pool = up(cap * 4); w.sel = w.pool + up(cap * 4); w.rowmod = w.sel + up(cap * 4);
+  w.stats = w.rowmod + up(cap);
+  w.score = w.stats + up((size_t)dm.heads * 8 * c.n_modalities);
+  w.total = w.score + score_ragged_ws_bytes(dm, c, c.ctx_len + c.max_new_tokens);
+  return w;
+}
+}  // namespace
+
+int32_t madakv_reevict_workspace_bytes(const madakv_handle* h, int32_t n_layers_per_call, size_t* bytes) {
+  if (!h || !bytes || n_layers_per_call < 1 || n_layers_per_call > h->cfg.n_layers) return MADAKV_ERR_INVALID_ARG;
+  *bytes = reevict_layout(h, n_layers_per_call).total;
+  return MADAKV_OK;
+}
+
+int32_t madakv_reevict(madakv_handle* h, int32_t layer0, int32_t n,
+                       const void* q_recent, const uint8_t* mask,
+                       void* k_c, void* v_c, int32_t* kept_idx, const int64_t* kv_off, int32_t* kv_len,
+                       int32_t* budgets, void* ws, size_t ws_bytes, void* stream) {
+  int32_t r = check_range(h, layer0, n);
+  if (r != MADAKV_OK) return r;
+  const madakv_config& c = h->cfg;
+  if (bad_ptr(q_recent) || bad_ptr(mask, 1) || bad_ptr(k_c) || bad_ptr(v_c) || bad_ptr(kept_idx, 4) || bad_ptr(kv_off, 8) ||
+      bad_ptr(kv_len, 4) || bad_ptr(budgets, 4) || bad_ptr(ws)) return MADAKV_ERR_INVALID_ARG;
+  if (c.budget >= c.ctx_len) return MADAKV_ERR_BAD_BUDGET;                 // nothing was evicted, nothing to bring back
+  const int longest = longest_rows(h, layer0, n);
+  if (c.page_rows || c.cache_fp8 || !score_ragged_supported(make_dims(c, n), c, longest)) return MADAKV_ERR_UNIMPLEMENTED;
+  const ReevictWs w = reevict_layout(h, n);
+  if (ws_bytes < w.total) return MADAKV_ERR_WORKSPACE_TOO_SMALL;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  char* wsb = static_cast<char*>(ws);
+  float* psi_c = reinterpret_cast<float*>(wsb + w.psi);
+  float* pool_c = reinterpret_cast<float*>(wsb + w.pool);
+  int32_t* sel = reinterpret_cast<int32_t*>(wsb + w.sel);
+  uint8_t* rowmod = reinterpret_cast<uint8_t*>(wsb + w.rowmod);
+  const size_t es = c.dtype == MADAKV_BF16 ? 2 : 4;
+  hipError_t e = hipSuccess;
+  // layers that have appended the same number of rows since their last (re-)eviction go in one set of launches
+  for (int l0 = layer0; l0 < layer0 + n && e == hipSuccess;) {
+    int l1 = l0 + 1;
+    while (l1 < layer0 + n && h->appended[l1] == h->appended[l0] && h->gen_base[l1] == h->gen_base[l0]) ++l1;
+    const Dims dr = make_dims(c, l1 - l0);
+    const size_t heads0 = (size_t)(l0 - layer0) * c.batch * c.n_kv_heads;
+    const char* qr = static_cast<const char*>(q_recent) + (size_t)(l0 - layer0) * c.batch * c.n_q_heads * c.window * c.head_dim * es;
+    char* stats_r = wsb + w.stats + heads0 * 8 * c.n_modalities;
+    int32_t* bud_r = budgets + heads0 * c.n_modalities;
+    e = launch_score_ragged(dr, c, qr, k_c, kv_off + heads0, kv_len + heads0, longest, psi_c, wsb + w.score, st);
+    if (e == hipSuccess) e = launch_restats(dr, c, psi_c, kept_idx, mask, kv_off + heads0, kv_len + heads0, h->appended[l0], pool_c, rowmod,
+                                            stats_r, bud_r, st);
+    if (e == hipSuccess) e = launch_select(dr, c, pool_c, mask, bud_r, kv_off + heads0, kv_len + heads0, sel, st, kv_len + heads0, rowmod);
+    if (e == hipSuccess) e = launch_compact(dr, c, k_c, v_c, kept_idx, sel, kv_off + heads0, kv_len + heads0, bud_r, h->appended[l0],
+                                            h->gen_base[l0], st);
+    if (e == hipSuccess) for (int l = l0; l < l1; ++l) { h->gen_base[l] += h->appended[l]; h->appended[l] = 0; }
+    l0 = l1;
+  }
+  return hip_fail(h, e);
 }
 
 int32_t madakv_page_table(const madakv_handle* h, const int32_t** table, int32_t* entries_per_head) {

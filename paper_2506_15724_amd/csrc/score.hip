@@ -39,6 +39,8 @@ struct ScoreArgs {
   int* status;         // status[0]: workgroups of one-sweep launches that gave up waiting so far (diagnostic counter,
                        // the first word of the workspace; never cleared here)
   int fsplit;          // chunks per head of the one-sweep kernel
+  const int64_t* seg_off;   // one-sweep kernel on ragged heads (null: every head has L keys at head * L): first row and
+  const int32_t* seg_len;   // number of rows of each head in k; psi is indexed the same way
   int spin_limit;      // polls a workgroup of the one-sweep kernel spends on one missing word before it goes its own way
   int head0;           // first head of this launch (grid.y indexes head0 + y)
   float scale_log2;    // softmax scale * log2(e)
@@ -325,13 +327,13 @@ __global__ __launch_bounds__(256) void score_xchg_init_kernel(unsigned long long
 // else: wave w takes rows w, w + 4, ...; lanes stride over the keys the row sees.  Q comes from
 // the staged tile.  Leaves offs[r] = max + log2(sum) (log2 domain), +inf for padding rows.
 template <int D>
-__device__ __forceinline__ void score_head_stats_alone(const ScoreArgs& a, const uint16_t* kg, const uint16_t* qs, float* offs) {
+__device__ __forceinline__ void score_head_stats_alone(const ScoreArgs& a, int Lh, const uint16_t* kg, const uint16_t* qs, float* offs) {
   constexpr int RS = D + 8;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   for (int r = wave; r < a.mpad; r += 4) {
     float m = NEG_BIG, l = 0.f;
     if (r < a.M) {
-      const int pos = a.L - a.W + (r % a.W);
+      const int pos = Lh - a.W + (r % a.W);
       for (int key = lane; key <= pos; key += 64) {
         float sdot = 0.f;
         for (int c = 0; c < D / 8; ++c) {
@@ -387,9 +389,14 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(M
   const int kvh = head % a.H;
   const long long lb = head / a.H;            // (layer, batch) index
   const uint16_t* qg = reinterpret_cast<const uint16_t*>(a.q_win) + (lb * a.H + kvh) * (long long)a.G * a.W * D;
-  const uint16_t* kg = reinterpret_cast<const uint16_t*>(a.k) + (long long)head * a.L * D;
+  // keys of this head: L rows at head * L, or (ragged: the rows of a reduced cache) seg_len rows at seg_off
+  const int Lh = a.seg_len ? a.seg_len[head] : a.L;
+  const long long base = a.seg_off ? a.seg_off[head] : (long long)head * a.L;
+  const int fs = a.seg_len ? (Lh + CK - 1) / CK : a.fsplit;      // chunks of this head (the grid is sized for the longest)
+  if (split >= fs) return;
+  const uint16_t* kg = reinterpret_cast<const uint16_t*>(a.k) + base * D;
   const int chunk0 = split * CK;
-  const int chunk1 = min(a.L, chunk0 + CK);
+  const int chunk1 = min(Lh, chunk0 + CK);
   uint16_t* kt = kt_all + (size_t)wave * 32 * RS;
   if (tid == 0) s_fail = 0;
 
@@ -400,7 +407,7 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(M
     const int lt0 = chunk0 + ((IT) * 4 + wave) * 32;                                             \
     _Pragma("unroll") for (int i = 0; i < LPS; ++i) {                                            \
       const int idx = i * 64 + lane;                                                             \
-      const int lkey = min(lt0 + idx / PPR, a.L - 1); /* past the end: a valid row, masked later */ \
+      const int lkey = min(lt0 + idx / PPR, Lh - 1); /* past the end: a valid row, masked later */ \
       pre[SET][i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(kg + (long long)lkey * D + (idx % PPR) * 8)); \
     }                                                                                            \
   }
@@ -416,7 +423,7 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(M
   __syncthreads();
 
   const int half = lane >> 5, col = lane & 31;
-  const int first_masked = a.L - a.W + 1;      // keys below this are visible to every proxy row
+  const int first_masked = Lh - a.W + 1;      // keys below this are visible to every proxy row
   bf16x8_t areg[KS];                           // one row block: its Q fragments stay in registers
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks)
@@ -459,7 +466,7 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(M
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
           const int row = b * 32 + (j >> 2) * 8 + half * 4 + (j & 3);
-          const int pos = a.L - a.W + (row % a.W);
+          const int pos = Lh - a.W + (row % a.W);
           const bool valid = (key < chunk1) && (key <= pos) && (row < a.M);
           lg[it][b][j] = valid ? acc[j] * a.scale_log2 : NEG_BIG;
         }
@@ -493,7 +500,7 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(M
   // anything real scales it by exp2(NEG_BIG - m) = 0
   const int nparts = SCORE_THREADS / a.mpad;    // mpad is 32 or 64
   const int r = tid % a.mpad, pt = tid / a.mpad;
-  if (a.fsplit == 1) {
+  if (fs == 1) {
     if (tid < a.mpad) {
       float m = NEG_BIG, l = 0.f;
       for (int w = 0; w < 4; ++w) merge_ml(m, l, part[(w * a.mpad + tid) * 2], part[(w * a.mpad + tid) * 2 + 1]);
@@ -509,9 +516,9 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(M
       __hip_atomic_store(xh + (long long)split * a.mpad + tid, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     // thread (r, pt) merges the chunks [pt * cpp, (pt + 1) * cpp) of row r in order, eight loads at a time
-    const int cpp = (a.fsplit + nparts - 1) / nparts;
-    int s = min(pt * cpp, a.fsplit);
-    const int s1 = min(s + cpp, a.fsplit);
+    const int cpp = (fs + nparts - 1) / nparts;
+    int s = min(pt * cpp, fs);
+    const int s1 = min(s + cpp, fs);
     float m = NEG_BIG, l = 0.f;
     int patience = a.spin_limit;
     bool fail = false;
@@ -539,7 +546,7 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(M
     __syncthreads();
     if (__builtin_expect(s_fail, 0)) {         // uniform over the workgroup
       if (tid == 0) atomicAdd(a.status, 1);
-      score_head_stats_alone<D>(a, kg, qs, offs);
+      score_head_stats_alone<D>(a, Lh, kg, qs, offs);
     } else if (tid < a.mpad) {
       float mm = NEG_BIG, ll = 0.f;
       for (int q = 0; q < nparts; ++q) merge_ml(mm, ll, pm[(q * a.mpad + tid) * 2], pm[(q * a.mpad + tid) * 2 + 1]);
@@ -563,7 +570,7 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(M
       for (int j = 0; j < 16; ++j) colsum += fast_exp2(lg[it][b][j] - off_r[b][j]);
     colsum += __shfl_xor(colsum, 32, 64);
     const int key = chunk0 + (it * 4 + wave) * 32 + col;
-    if (half == 0 && key < chunk1) __builtin_nontemporal_store(colsum, a.psi + ((long long)head * a.L + key));
+    if (half == 0 && key < chunk1) __builtin_nontemporal_store(colsum, a.psi + (base + key));
   }
 }
 
@@ -721,6 +728,40 @@ static void launch_mfma_pair(const ScoreArgs& a0, int heads, size_t lds1, size_t
   hipLaunchKernelGGL((score_mfma_kernel<D, WPT, NRB, 2>), grid, dim3(SCORE_THREADS), lds2, st, a);
 }
 
+// ---- the one-sweep kernel on ragged heads: the rows of a reduced cache, scored against the most recent queries
+static int ragged_split(const Dims& dm, int longest_rows) { return (std::max(longest_rows, 1) + fused_chunk(dm) - 1) / fused_chunk(dm); }
+bool score_ragged_supported(const Dims& dm, const madakv_config& c, int longest_rows) {
+  return use_mfma(dm, c.dtype) && dm.M <= 64 && ragged_split(dm, longest_rows) <= FUSED_MAX_SPLIT;
+}
+size_t score_ragged_ws_bytes(const Dims& dm, const madakv_config& c, int longest_rows) {
+  (void)c;
+  return 256 + ((size_t)dm.heads * ragged_split(dm, longest_rows) * ((dm.M + 31) / 32 * 32) * 8 + 255) / 256 * 256;
+}
+hipError_t launch_score_ragged(const Dims& dm, const madakv_config& c, const void* q_recent, const void* k_c,
+                               const int64_t* seg_off, const int32_t* seg_len, int longest_rows, float* psi_c, void* ws, hipStream_t st) {
+  ScoreArgs a;
+  a.lse = nullptr; a.q_win = q_recent; a.k = k_c; a.psi = psi_c;
+  a.status = reinterpret_cast<int*>(ws);
+  a.rowstat = nullptr; a.sink = nullptr;
+  a.xchg = reinterpret_cast<unsigned long long*>(static_cast<char*>(ws) + 256);
+  a.seg_off = seg_off; a.seg_len = seg_len;
+  a.H = dm.H; a.G = dm.G; a.d = dm.d; a.L = dm.L; a.W = dm.W; a.M = dm.M;
+  a.mpad = (dm.M + 31) / 32 * 32; a.nsplit = 0; a.nmerge = 0; a.chunk = 0; a.head0 = 0;
+  a.fsplit = ragged_split(dm, longest_rows);
+  const char* spin = getenv("MADAKV_SCORE_SPIN_LIMIT");
+  a.spin_limit = spin && atoi(spin) > 0 ? atoi(spin) : FUSED_SPIN_LIMIT;
+  const float scale = c.softmax_scale > 0.f ? c.softmax_scale : 1.0f / sqrtf((float)dm.d);
+  a.scale_log2 = scale * 1.4426950408889634f;
+  const int MB = a.mpad / 32;
+  for (int h0 = 0; h0 < dm.heads; h0 += 65535) {
+    const int nh = std::min(65535, dm.heads - h0);
+    a.head0 = h0;
+    if (dm.d == 128) { if (MB == 1) launch_mfma_pair<128, 1, 1>(a, nh, 0, 0, st); else launch_mfma_pair<128, 1, 2>(a, nh, 0, 0, st); }
+    else { if (MB == 1) launch_mfma_pair<64, 1, 1>(a, nh, 0, 0, st); else launch_mfma_pair<64, 1, 2>(a, nh, 0, 0, st); }
+  }
+  return hipGetLastError();
+}
+
 hipError_t launch_score(const Dims& dm, const madakv_config& c, const void* q_win, const void* k, const float* row_lse,
                         float* psi, void* ws, hipStream_t st) {
   ScorePlan p = score_plan(dm, c.dtype);
@@ -732,6 +773,7 @@ hipError_t launch_score(const Dims& dm, const madakv_config& c, const void* q_wi
   a.sink = reinterpret_cast<float*>(static_cast<char*>(ws) + 256 + rowstat_bytes(dm, c.dtype));
   a.xchg = reinterpret_cast<unsigned long long*>(static_cast<char*>(ws) + 256 + rowstat_bytes(dm, c.dtype) + 256);
   a.fsplit = (!row_lse && use_fused(dm, c.dtype)) ? fused_split(dm) : 0;
+  a.seg_off = nullptr; a.seg_len = nullptr;
   // (a test can force the lone-workgroup path of the one-sweep kernel from the host with a spin limit of 1)
   const char* spin = getenv("MADAKV_SCORE_SPIN_LIMIT");
   a.spin_limit = spin && atoi(spin) > 0 ? atoi(spin) : FUSED_SPIN_LIMIT;

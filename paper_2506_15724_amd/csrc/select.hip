@@ -120,6 +120,7 @@ __global__ __launch_bounds__(OFF_THREADS) void offsets_kernel(OffsetsArgs a) {
 struct SelectArgs {
   const float* psi_pool; const uint8_t* mask; const int32_t* budgets; const int64_t* kv_off; const int32_t* kv_len; int32_t* kept_idx;
   int B, H, L, W, nc, mpa_mode, keep_all, select_mode, sink_tokens, M;
+  const int32_t* seg_len; const uint8_t* rowmod;   // ragged candidates (re-eviction), else null
 };
 
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
@@ -226,8 +227,13 @@ __global__ __launch_bounds__(SEL_THREADS) __attribute__((amdgpu_waves_per_eu(MM 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int head = blockIdx.x;
   const int b = (head / a.H) % a.B;
-  const float* sc = a.psi_pool + (long long)head * a.nc;
-  const uint8_t* mask = a.mask + (long long)b * a.L;
+  // candidates of this head: the L - W prompt positions before the window with the batch item's modality
+  // mask, or (ragged: the rows of a reduced cache, re-eviction) the rows before the head's last W with a
+  // modality byte per row; scores and output are indexed the same way
+  const bool ragged = a.seg_len != nullptr;
+  const int nc = ragged ? a.seg_len[head] - a.W : a.nc;
+  const float* sc = ragged ? a.psi_pool + a.kv_off[head] : a.psi_pool + (long long)head * a.nc;
+  const uint8_t* mask = ragged ? a.rowmod + a.kv_off[head] : a.mask + (long long)b * a.L;
   int32_t* out = a.kept_idx + a.kv_off[head];
 
   if (a.kv_len[head] == 0) return;               // the segment did not fit the region: nothing to write
@@ -243,21 +249,21 @@ __global__ __launch_bounds__(SEL_THREADS) __attribute__((amdgpu_waves_per_eu(MM 
     uint32_t btot = 0;
 #pragma unroll
     for (int m = 0; m < MM; ++m) btot += bud[m];
-    const int total = min((int)btot, a.nc);
+    const int total = min((int)btot, nc);
     const int sink = min(a.sink_tokens, total);
     for (int j = tid; j < total + a.W; j += SEL_THREADS)
-      out[j] = j < sink ? j : (j < total ? a.nc - (total - j) : a.nc + (j - total));
+      out[j] = j < sink ? j : (j < total ? nc - (total - j) : nc + (j - total));
     return;
   }
   const int shifts[3] = {21, 10, 0};
   const int widths[3] = {11, 11, 10};
   constexpr int CH = SEL_THREADS * SEL_EPT;      // candidates per chunk
-  const int nchunks = (a.nc + CH - 1) / CH;
+  const int nchunks = (nc + CH - 1) / CH;
   const bool single = nchunks == 1;              // the usual case: everything stays in registers
 
   uint32_t key[SEL_EPT];
   unsigned long long mbits = 0ULL;
-  if (single) load_owned(sc, mask, tid * SEL_EPT, a.nc, a.mpa_mode, M, key, mbits);
+  if (single) load_owned(sc, mask, tid * SEL_EPT, nc, a.mpa_mode, M, key, mbits);
 
   for (int level = 0; level < 3; ++level) {
     for (int e = tid; e < M * SEL_BINS; e += SEL_THREADS) (&cnt[0][0])[e] = 0;
@@ -272,8 +278,8 @@ __global__ __launch_bounds__(SEL_THREADS) __attribute__((amdgpu_waves_per_eu(MM 
     }
     for (int c = 0; c < nchunks; ++c) {
       const int i0 = c * CH + tid * SEL_EPT;
-      if (!single) load_owned(sc, mask, i0, a.nc, a.mpa_mode, M, key, mbits);
-      const int nvalid = min(max(a.nc - i0, 0), SEL_EPT);
+      if (!single) load_owned(sc, mask, i0, nc, a.mpa_mode, M, key, mbits);
+      const int nvalid = min(max(nc - i0, 0), SEL_EPT);
 #pragma unroll
       for (int e = 0; e < SEL_EPT; ++e) {
         const int m = (int)((mbits >> (2 * e)) & 3ULL);
@@ -340,8 +346,8 @@ __global__ __launch_bounds__(SEL_THREADS) __attribute__((amdgpu_waves_per_eu(MM 
   uint32_t run_out = 0;
   for (int c = 0; c < nchunks; ++c) {
     const int i0 = c * CH + tid * SEL_EPT;
-    if (!single) load_owned(sc, mask, i0, a.nc, a.mpa_mode, M, key, mbits);
-    const int nvalid = min(max(a.nc - i0, 0), SEL_EPT);
+    if (!single) load_owned(sc, mask, i0, nc, a.mpa_mode, M, key, mbits);
+    const int nvalid = min(max(nc - i0, 0), SEL_EPT);
     // ties of this thread's stretch, per modality (four 16-bit counts), then their rank by
     // position over the workgroup
     unsigned long long eqbits = 0ULL, gtbits = 0ULL, eqcnt = 0ULL;
@@ -384,7 +390,7 @@ __global__ __launch_bounds__(SEL_THREADS) __attribute__((amdgpu_waves_per_eu(MM 
     for (int m = 0; m < MM; ++m) run_eq[m] += (uint32_t)((eqtot >> (16 * m)) & 0xffffULL);
     run_out += ktot;
   }
-  for (int r = tid; r < a.W; r += SEL_THREADS) out[run_out + r] = a.nc + r;
+  for (int r = tid; r < a.W; r += SEL_THREADS) out[run_out + r] = nc + r;
 }
 
 size_t select_ws_bytes(const Dims& dm, const madakv_config& c) {
@@ -413,11 +419,12 @@ hipError_t launch_offsets(const Dims& dm, const madakv_config& c, int layer0, co
 
 hipError_t launch_select(const Dims& dm, const madakv_config& c, const float* psi_pool, const uint8_t* mask,
                          const int32_t* budgets, const int64_t* kv_off, const int32_t* kv_len, int32_t* kept_idx,
-                         hipStream_t st) {
+                         hipStream_t st, const int32_t* seg_len, const uint8_t* rowmod) {
   SelectArgs a;
+  a.seg_len = seg_len; a.rowmod = rowmod;
   a.psi_pool = psi_pool; a.mask = mask; a.budgets = budgets; a.kv_off = kv_off; a.kv_len = kv_len; a.kept_idx = kept_idx;
   a.B = dm.B; a.H = dm.H; a.L = dm.L; a.W = dm.W; a.nc = dm.nc; a.mpa_mode = c.mpa_mode;
-  a.keep_all = c.budget >= c.ctx_len ? 1 : 0;
+  a.keep_all = (c.budget >= c.ctx_len && !seg_len) ? 1 : 0;
   a.select_mode = c.select_mode; a.sink_tokens = c.sink_tokens; a.M = c.n_modalities;
   if (a.M == 2) hipLaunchKernelGGL((select_kernel<2>), dim3(dm.heads), dim3(SEL_THREADS), 0, st, a);
   else hipLaunchKernelGGL((select_kernel<4>), dim3(dm.heads), dim3(SEL_THREADS), 0, st, a);

@@ -742,6 +742,119 @@ def test_paged_reduced_cache(name, P, fp8):
     flat.close(); paged.close()
 
 
+@pytest.mark.parametrize("name", ["bf16_mha", "bf16_w64", "bf16_d64_gqa2", "bf16_odd"])
+def test_reeviction_during_generation(name):
+    """madakv_reevict after some decode steps, twice: every head is brought back to the length the prompt
+    eviction gave it.  Stage by stage against the oracle on the GPU's own upstream values (scores within
+    the psi tolerance, then masses 2e-6, budgets / surviving rows / moved K, V rows / original positions
+    bit for bit), and decode afterwards against Eq. 5 over the oracle's copy of the new cache."""
+    rounds = (5, 3)
+    wl = small_workloads()[name].scaled(decode_steps=max(rounds))
+    NL, B, H, Hq, L, W, d = wl.n_layers, wl.batch, wl.n_kv_heads, wl.n_q_heads, wl.ctx_len, wl.window, wl.head_dim
+    G = Hq // H
+    p = PU.oracle_params(wl)
+    q, k, v, mask, masks = PU.make_inputs(wl, DEV)
+    eng = engine(wl)
+    eng.score(0, NL, q, k, mask); eng.allocate(0, NL); eng.select_gather(0, NL, k, v, mask)
+    torch.cuda.synchronize()
+    off = eng.kv_off.cpu().numpy()
+    len0 = eng.kv_len.cpu().numpy().copy()
+    cap = eng.capacity
+    # the oracle's view of every head: rows (float64), original positions
+    heads = [(l, b, h) for l in range(NL) for b in range(B) for h in range(H)]
+    rows_k = {s: WL.to_f64(eng.k_c[off[s]:off[s] + len0[s]]) for s in heads}
+    rows_v = {s: WL.to_f64(eng.v_c[off[s]:off[s] + len0[s]]) for s in heads}
+    origin = {s: eng.kept_idx[off[s]:off[s] + len0[s]].cpu().numpy().astype(np.int64) for s in heads}
+    q_hist = [q[:, :, :, r] for r in range(W)]                 # queries of the tokens in the last W rows, oldest first
+    out = torch.empty(NL, B, Hq, d, dtype=torch.float32, device=DEV)
+    gen = 0
+    step = 0
+    for T in rounds:
+        for _ in range(T):
+            dq, dk, dv = WL.decode_inputs_all(wl, step, DEV)
+            eng.decode_attn(0, NL, dq, dk, dv, out)
+            torch.cuda.synchronize()
+            for s in heads:
+                l, b, h = s
+                rows_k[s] = np.concatenate([rows_k[s], WL.to_f64(dk[l, b, h])[None]])
+                rows_v[s] = np.concatenate([rows_v[s], WL.to_f64(dv[l, b, h])[None]])
+                origin[s] = np.concatenate([origin[s], [L + gen]])
+            for (l, b, h) in heads[::5]:
+                for g in range(G):
+                    ref = O.attend(WL.to_f64(dq[l, b, h * G + g]), rows_k[(l, b, h)], rows_v[(l, b, h)], p.scale)
+                    assert np.abs(out[l, b, h * G + g].cpu().numpy() - ref).max() <= PU.DECODE_ATOL
+            q_hist.append(dq); q_hist = q_hist[-W:]
+            gen += 1; step += 1
+        q_recent = torch.stack(q_hist, dim=3).contiguous()     # [NL, B, Hq, W, d]
+        say(f"{name}: madakv_reevict after {T} more steps")
+        eng.reevict_ws = None
+        eng.reevict(0, NL, q_recent, mask)
+        torch.cuda.synchronize()
+        ws = eng.reevict_ws
+        psi_g = ws[:cap * 4].view(torch.float32).cpu().numpy()
+        up = lambda x: (x + 255) // 256 * 256
+        stats_at = 3 * up(cap * 4) + up(cap)
+        M = 2
+        rec = ws[stats_at:stats_at + NL * B * H * 8 * M].view(torch.int32).reshape(NL, B, H, 2 * M).cpu()
+        w_g = rec[..., :M].contiguous().view(torch.float32).numpy(); n_g = rec[..., M:].numpy()
+        bud_g = eng.budgets.cpu().numpy()
+        new_len = eng.kv_len.cpu().numpy()
+        assert (new_len == len0).all(), "every head is back at the length the prompt eviction gave it"
+        kept_all = eng.kept_idx.cpu().numpy()
+        for s in heads:
+            l, b, h = s
+            n = rows_k[s].shape[0]
+            qh = WL.to_f64(q_recent[l, b, h * G:(h + 1) * G])
+            sel_o, bud_o, w_o, n_o, psi_o, pool_o = O.reevict_head(qh, rows_k[s], rows_v[s], origin[s], masks[b], int(len0[s]) - W, p)
+            pg = psi_g[off[s]:off[s] + n]
+            nbad, worst = PU.psi_close(pg, psi_o, G, W, n)
+            assert nbad == 0, (s, worst)
+            # from here on both sides read the GPU's scores
+            rowmod = np.where(origin[s] < L, masks[b][np.minimum(origin[s], L - 1)], 0)
+            w_r, n_r = O.modality_mass(pg.astype(np.float64), rowmod, W, M)
+            assert tuple(n_g[s]) == tuple(n_r)
+            np.testing.assert_allclose(w_g[s], w_r, rtol=2e-6, atol=1e-30)
+            bud_r = O.mpa_split_n(int(len0[s]) - W, w_g[s].astype(np.float64), n_r, p.mpa_mode)
+            assert list(bud_g[s]) == list(bud_r)
+            pool_r = O.pool_scores(pg.astype(np.float64)[None], W, p.pool_k)[0].astype(np.float32).astype(np.float64)
+            sel_r = O.select_n(pool_r, rowmod, bud_r, n, W, p.mpa_mode)
+            got_k = WL.to_f64(eng.k_c[off[s]:off[s] + len0[s]]); got_v = WL.to_f64(eng.v_c[off[s]:off[s] + len0[s]])
+            np.testing.assert_array_equal(got_k, rows_k[s][sel_r])
+            np.testing.assert_array_equal(got_v, rows_v[s][sel_r])
+            np.testing.assert_array_equal(kept_all[off[s]:off[s] + len0[s]], origin[s][sel_r])
+            rows_k[s], rows_v[s], origin[s] = rows_k[s][sel_r], rows_v[s][sel_r], origin[s][sel_r]
+    # generation goes on over the re-evicted cache
+    dq, dk, dv = WL.decode_inputs_all(wl, step, DEV)
+    eng.decode_attn(0, NL, dq, dk, dv, out)
+    torch.cuda.synchronize()
+    for (l, b, h) in heads:
+        kc = np.concatenate([rows_k[(l, b, h)], WL.to_f64(dk[l, b, h])[None]]); vc = np.concatenate([rows_v[(l, b, h)], WL.to_f64(dv[l, b, h])[None]])
+        for g in range(G):
+            ref = O.attend(WL.to_f64(dq[l, b, h * G + g]), kc, vc, p.scale)
+            assert np.abs(out[l, b, h * G + g].cpu().numpy() - ref).max() <= PU.DECODE_ATOL
+    eng.close()
+
+
+def test_reeviction_refusals():
+    wl = small_workloads()["bf16_mha"].scaled(n_layers=1, batch=1, decode_steps=2)
+    q, k, v, mask, masks = PU.make_inputs(wl, DEV)
+    qr = q.clone()
+    for kw, status in ((dict(page_rows=16), -7), (dict(cache_fp8=1), -7), (dict(budget=wl.ctx_len), -3)):
+        eng = engine(wl, **kw)
+        eng.reevict_ws = torch.empty(MB.madakv_reevict_workspace_bytes(eng.h, 1), dtype=torch.uint8, device=DEV)
+        with pytest.raises(MB.MadaKVError) as ei:
+            eng.reevict(0, 1, qr, mask)
+        assert ei.value.status == status
+        eng.close()
+    f32 = small_workloads()["tiny_fp32"]
+    eng = engine(f32)
+    eng.reevict_ws = torch.empty(MB.madakv_reevict_workspace_bytes(eng.h, 1), dtype=torch.uint8, device=DEV)
+    with pytest.raises(MB.MadaKVError) as ei:
+        eng.reevict(0, 1, torch.zeros(1, 1, 8, 16, 64, device=DEV), torch.zeros(1, 1024, dtype=torch.uint8, device=DEV))
+    assert ei.value.status == -7
+    eng.close()
+
+
 def test_error_paths_and_streams():
     """Host-side refusals on a live handle (nothing is enqueued), and calls on a non-default stream."""
     wl = small_workloads()["bf16_mha"].scaled(n_layers=2, batch=1, decode_steps=1)

@@ -603,3 +603,46 @@ def test_split_products_on_a_half_go_up_to_text():
     """Eq. 8 in integers, hand-worked: share_t * a exactly on x.5 rounds up (to text)."""
     for wt, wv, a, bt in [(1.0, 1.0, 7, 4), (3.0, 1.0, 6, 5), (1.0, 3.0, 6, 2), (0.25, 0.75, 1002, 251), (5.0, 3.0, 4, 3)]:
         assert O.mpa_split(a, wt, wv, a, a) == (bt, a - bt)
+
+
+# ---- re-eviction during generation (an extension: the paper evicts once) -------------------------
+def test_reevict_head_reduces_to_the_prompt_eviction_and_to_the_identity():
+    """On a cache that still holds the whole prompt, with the prompt's own proxy queries and uniform head
+    totals, re-eviction is the prompt eviction (whose pieces are pinned above); with nothing appended
+    and the total it already has, a head keeps every row."""
+    r = rng(21)
+    NL, H, G, L, W, d = 1, 3, 2, 60, 4, 8
+    q = r.standard_normal((NL, H * G, W, d)); k = r.standard_normal((NL, H, L, d)); v = r.standard_normal((NL, H, L, d))
+    mask = (r.random(L) < 0.5).astype(np.uint8); mask[-W:] = 0
+    p = O.Params(n_layers=NL, n_q_heads=H * G, n_kv_heads=H, head_dim=d, ctx_len=L, window=W, budget=20, pool_k=3, hcc_mode=0)
+    res = O.evict(q, k, v, mask, p)
+    for h in range(H):
+        sel, bud, w, n_mod, psi, pool = O.reevict_head(q[0, h * G:(h + 1) * G], k[0, h], v[0, h], np.arange(L), mask, 20 - W, p)
+        np.testing.assert_array_equal(sel, res["kept"][0][h])
+        assert list(bud) == list(res["budgets"][0, h])
+        np.testing.assert_allclose(psi, res["psi"][0, h], rtol=0, atol=0)
+        # the reduced cache itself, nothing appended: all of it stays
+        kept = res["kept"][0][h]
+        sel2, bud2, *_ = O.reevict_head(q[0, h * G:(h + 1) * G], k[0, h][kept], v[0, h][kept], kept, mask, len(kept) - W, p)
+        np.testing.assert_array_equal(sel2, np.arange(len(kept)))
+        assert sum(bud2) == len(kept) - W
+
+
+def test_reevict_head_hand_example_generated_tokens_are_text():
+    """Identical keys: every proxy row spreads its attention evenly over the rows it sees, so all
+    candidates score alike, masses are proportional to counts and ties go to the lower rows."""
+    L, W, d = 100, 2, 4
+    mask = np.zeros(L, dtype=np.uint8); mask[10:60] = 1
+    p = O.Params(n_layers=1, n_q_heads=1, n_kv_heads=1, head_dim=d, ctx_len=L, window=W, budget=8)
+    # cache: prompt positions 0 (text), 12, 13, 20 (image), 70 (text), then the old window 98, 99, then 3 generated tokens
+    origin = np.array([0, 12, 13, 20, 70, 98, 99, L + 0, L + 1, L + 2])
+    n = len(origin)
+    kr = np.ones((n, d)); vr = np.arange(n * d, dtype=np.float64).reshape(n, d)
+    qr = np.ones((1, W, d))
+    sel, bud, w, n_mod, psi, pool = O.reevict_head(qr, kr, vr, origin, mask, 5, p)
+    # candidates: rows 0..7 = text {0, 4, 5, 6, 7} (the generated row 7 is text), image {1, 2, 3}
+    assert list(n_mod) == [5, 3]
+    np.testing.assert_allclose(psi[:8], 1.0 / 9 + 1.0 / 10)                # both proxy rows see rows 0..7
+    np.testing.assert_allclose(w, [5 * psi[0], 3 * psi[0]])
+    assert bud == [3, 2]                                                   # floor(5/8 * 5 + 0.5) = 3
+    np.testing.assert_array_equal(sel, [0, 1, 2, 4, 5, 8, 9])              # lowest rows of each modality, then the proxies
