@@ -146,6 +146,29 @@ def window_scores_from_lse(q_win: np.ndarray, k: np.ndarray, lse: np.ndarray, sc
     return psi
 
 
+def window_attention(q_win: np.ndarray, k: np.ndarray, v: np.ndarray, scale: float):
+    """The prefill attention of the last W prompt positions (Eq. 5 applied to the proxy rows of
+    Sec. 3.3): out[j, r] = softmax(scale * q_win[j, r] . K^T) V over the keys row r sees (causal:
+    keys 0 .. L-W+r), and the natural log-sum-exp of each row.  Query head j reads KV head j // G.
+    This is the step before the eviction path: the softmax rows it forms are the alpha of Eq. 7.
+    Returns (out [Hq, W, d], lse [Hq, W])."""
+    q_win = np.asarray(q_win, dtype=np.float64); k = np.asarray(k, dtype=np.float64); v = np.asarray(v, dtype=np.float64)
+    Hq, W, d = q_win.shape
+    H, L, _ = k.shape
+    G = Hq // H
+    out = np.zeros((Hq, W, d), dtype=np.float64)
+    lse = np.zeros((Hq, W), dtype=np.float64)
+    for j in range(Hq):
+        for r in range(W):
+            n = L - W + r + 1
+            s = scale * (k[j // G, :n] @ q_win[j, r])
+            mx = s.max()
+            e = np.exp(s - mx)
+            out[j, r] = (e / e.sum()) @ v[j // G, :n]
+            lse[j, r] = mx + math.log(e.sum())
+    return out, lse
+
+
 # --------------------------------------------------------------------------- #
 # Eq. 6 and Eq. 9: modality mass and theta-mass counts
 # --------------------------------------------------------------------------- #

@@ -646,3 +646,31 @@ def test_reevict_head_hand_example_generated_tokens_are_text():
     np.testing.assert_allclose(w, [5 * psi[0], 3 * psi[0]])
     assert bud == [3, 2]                                                   # floor(5/8 * 5 + 0.5) = 3
     np.testing.assert_array_equal(sel, [0, 1, 2, 4, 5, 8, 9])              # lowest rows of each modality, then the proxies
+
+
+def test_window_attention_textbook_and_consistency_with_the_scores():
+    """The last-window prefill attention against a library masked softmax attention in fp64, its last
+    row against plain Eq. 5 over the whole prompt, its log-sum-exp against proxy_row_lse, and its
+    softmax rows against Eq. 7: psi is their column sum."""
+    r = rng(31)
+    Hq, H, L, W, d = 6, 3, 40, 5, 8
+    q = r.standard_normal((Hq, W, d)); k = r.standard_normal((H, L, d)); v = r.standard_normal((H, L, d))
+    scale = 0.3
+    out, lse = O.window_attention(q, k, v, scale)
+    G = Hq // H
+    qt, kt, vt = torch.from_numpy(q), torch.from_numpy(k).repeat_interleave(G, 0), torch.from_numpy(v).repeat_interleave(G, 0)
+    logits = scale * torch.einsum("jwd,jld->jwl", qt, kt)
+    pos = torch.arange(L)[None, None, :]; rowpos = (L - W + torch.arange(W))[None, :, None]
+    logits = logits.masked_fill(pos > rowpos, float("-inf"))
+    ref = torch.softmax(logits, -1) @ vt
+    np.testing.assert_allclose(out, ref.numpy(), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(lse, torch.logsumexp(logits, -1).numpy(), rtol=1e-12)
+    np.testing.assert_allclose(lse, O.proxy_row_lse(q, k, scale), rtol=1e-12)
+    for j in range(Hq):
+        np.testing.assert_allclose(out[j, W - 1], O.attend(q[j, W - 1], k[j // G], v[j // G], scale), rtol=1e-12, atol=1e-13)
+    psi = torch.softmax(logits, -1).reshape(H, G * W, L).sum(1).numpy()
+    np.testing.assert_allclose(O.window_scores(q, k, scale), psi, rtol=1e-12, atol=1e-15)
+    # identical keys: every row is the mean of the values it sees
+    out1, _ = O.window_attention(q, np.ones((H, L, d)), v, scale)
+    for rr in range(W):
+        np.testing.assert_allclose(out1[0, rr], v[0, :L - W + rr + 1].mean(0), rtol=1e-12)
