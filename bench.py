@@ -529,6 +529,22 @@ def main():
             del pgd, pgc
         except Exception as ex:
             result["paged_cache"] = {"error": str(ex)[:200]}
+        # the prefill's last-window attention with the scores as a by-product (one pass over K and V, timed as the
+        # producer it is), and what is left of the eviction after it: allocation, selection, gather
+        try:
+            wout = torch.empty(NL, B, Hq, W, d, dtype=wl.torch_dtype, device=dev)
+            wlse = torch.empty(NL, B, Hq, W, dtype=torch.float32, device=dev)
+            t_prod = timed(lambda: eng.window_attn_score(0, NL, q, k, v, mask, wout, wlse))
+            t_rest = timed(lambda: (eng.allocate(0, NL), eng.select_gather(0, NL, k, v, mask)))
+            kvb = 2 * NL * B * H * L * d * es
+            result["evict_after_window_attn"] = {"window_attn_score_ms": t_prod, "window_attn_GBps": kvb / (t_prod * 1e-3) / 1e9,
+                                                 "window_attn_frac_of_hbm_peak": kvb / (t_prod * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                                 "allocate_select_gather_ms": t_rest, "ctx_tokens_per_s": B * L / (t_rest * 1e-3),
+                                                 "note": "the attention of the last W prompt positions is prefill work (K and V read once, out and "
+                                                         "log-sum-exp written); psi, the statistics and pooled scores come out of the same pass"}
+            del wout, wlse
+        except Exception as ex:
+            result["evict_after_window_attn"] = {"error": str(ex)[:200]}
         # eviction when the caller's prefill hands over the proxy rows' log-sum-exp (one pass over K).
         # The normalisers are made here with torch, outside the timed region, as a prefill kernel would.
         scale = 1.0 / (d ** 0.5)

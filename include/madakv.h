@@ -17,6 +17,8 @@
  *   madakv_evict          Sec. 3.3 Eq. 6-11 and the eviction itself: the first three calls in one
  *   madakv_score_lse      Sec. 3.3 Eq. 7 with the softmax normalisers of the proxy rows given
  *                         (the prefill attention of Sec. 3.1 Eq. 5 has them)
+ *   madakv_window_attn_score  that prefill attention for the proxy rows (Sec. 3.1 Eq. 5) with Eq. 7, 6, 9 as
+ *                         by-products of the same pass
  *
  * General rules
  *   - Plain C, no exceptions.  Every call returns a madakv_status (0 = OK).
@@ -174,6 +176,24 @@ int32_t madakv_score_lse(madakv_handle* h, int32_t layer0, int32_t n,
                          const void* q_win, const void* k, const uint8_t* mask, const float* row_lse,
                          float* psi, float* psi_pool, void* stats, int32_t* n_mod,
                          void* ws, size_t ws_bytes, void* stream);
+
+/* The step before the eviction path, fused with its first step: the prefill attention of the last W prompt
+ * positions (Sec. 3.1 Eq. 5 for the proxy rows of Sec. 3.3), whose softmax rows are the alpha of Eq. 7.  One pass
+ * over K and V gives
+ *   out      [n, B, Hq, W, d]  softmax(scale * q_win k^T) v over the keys each proxy row sees (float if out_fp32
+ *                              else dtype)
+ *   row_lse  [n, B, Hq, W]     optional (may be NULL): natural log-sum-exp of each row
+ * and psi, psi_pool, stats, n_mod exactly as madakv_score defines them (up to the rounding order of psi).  A model
+ * whose prefill calls this for its last W positions needs no scoring sweep of its own: madakv_allocate and
+ * madakv_select_gather follow directly.  v [n, B, H, L, d]; ws: madakv_window_attn_workspace_bytes(h, n) bytes;
+ * everything else as in madakv_score.  MADAKV_ERR_UNIMPLEMENTED unless dtype is bf16, G * W <= 32 and
+ * ctx_len <= 32768 (head_dim 128) / 49152 (head_dim 64). */
+int32_t madakv_window_attn_workspace_bytes(const madakv_handle* h, int32_t n_layers_per_call, size_t* bytes);
+int32_t madakv_window_attn_score(madakv_handle* h, int32_t layer0, int32_t n,
+                                 const void* q_win, const void* k, const void* v, const uint8_t* mask,
+                                 void* out, float* row_lse,
+                                 float* psi, float* psi_pool, void* stats, int32_t* n_mod,
+                                 void* ws, size_t ws_bytes, void* stream);
 
 /* Eq. 8, Eq. 10-11 for layers [layer0, layer0 + n) in order.
  *   stats    [n, B, H]        from madakv_score

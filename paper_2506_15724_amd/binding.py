@@ -61,6 +61,8 @@ def lib() -> C.CDLL:
         L.madakv_decode_attn.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.madakv_decode_attn_static.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.madakv_page_table.argtypes = [vp, C.POINTER(vp), C.POINTER(i32)]
+        L.madakv_window_attn_workspace_bytes.argtypes = [vp, i32, C.POINTER(sz)]
+        L.madakv_window_attn_score.argtypes = [vp, i32, i32] + [vp] * 10 + [vp, sz, vp]
         L.madakv_reevict_workspace_bytes.argtypes = [vp, i32, C.POINTER(sz)]
         L.madakv_reevict.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         for name in EXPORTS:
@@ -72,7 +74,7 @@ def lib() -> C.CDLL:
 EXPORTS = ["madakv_create", "madakv_destroy", "madakv_last_hip_error", "madakv_workspace_bytes",
            "madakv_compact_capacity_tokens", "madakv_score", "madakv_score_lse", "madakv_allocate", "madakv_select_gather", "madakv_evict",
            "madakv_decode_attn", "madakv_decode_attn_static", "madakv_page_table",
-           "madakv_reevict_workspace_bytes", "madakv_reevict"]
+           "madakv_reevict_workspace_bytes", "madakv_reevict", "madakv_window_attn_workspace_bytes", "madakv_window_attn_score"]
 
 
 def _ptr(t):
@@ -153,6 +155,18 @@ def madakv_decode_attn(h, layer0, n, q, k_new, v_new, k_c, v_c, kv_off, kv_len, 
 def madakv_decode_attn_static(h, layer0, n, q, k_new, v_new, k_c, v_c, kv_off, kv_len, out):
     _check("madakv_decode_attn_static", lib().madakv_decode_attn_static(
         h, layer0, n, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_c), _ptr(v_c), _ptr(kv_off), _ptr(kv_len), _ptr(out), _stream()))
+
+
+def madakv_window_attn_workspace_bytes(h, n_layers_per_call: int) -> int:
+    b = C.c_size_t()
+    _check("madakv_window_attn_workspace_bytes", lib().madakv_window_attn_workspace_bytes(h, n_layers_per_call, C.byref(b)))
+    return b.value
+
+
+def madakv_window_attn_score(h, layer0, n, q_win, k, v, mask, out, row_lse, psi, psi_pool, stats, n_mod, ws):
+    _check("madakv_window_attn_score", lib().madakv_window_attn_score(
+        h, layer0, n, _ptr(q_win), _ptr(k), _ptr(v), _ptr(mask), _ptr(out), _ptr(row_lse), _ptr(psi), _ptr(psi_pool),
+        _ptr(stats), _ptr(n_mod), _ptr(ws), ws.numel() * ws.element_size(), _stream()))
 
 
 def madakv_reevict_workspace_bytes(h, n_layers_per_call: int) -> int:
@@ -259,6 +273,12 @@ class MadaKV:
     def decode_attn_static(self, l0, n, q, k_new, v_new, out):
         madakv_decode_attn_static(self.h, l0, n, q, k_new, v_new, self.k_c, self.v_c, self._sl(self.kv_off, l0, n),
                                   self._sl(self.kv_len, l0, n), out)
+
+    def window_attn_score(self, l0, n, q_win, k, v, mask, out, row_lse=None):
+        if getattr(self, "window_ws", None) is None:
+            self.window_ws = torch.empty(max(16, madakv_window_attn_workspace_bytes(self.h, self.n_call)), dtype=torch.uint8, device=self.device)
+        madakv_window_attn_score(self.h, l0, n, q_win, k, v, mask, out, row_lse, self._sl(self.psi, l0, n),
+                                 self._sl(self.psi_pool, l0, n), self._sl(self.stats, l0, n), self.n_mod, self.window_ws)
 
     def reevict(self, l0, n, q_recent, mask):
         if getattr(self, "reevict_ws", None) is None:

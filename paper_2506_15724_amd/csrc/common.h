@@ -64,6 +64,11 @@ bool score_ragged_supported(const Dims& dm, const madakv_config& c, int longest_
 size_t score_ragged_ws_bytes(const Dims& dm, const madakv_config& c, int longest_rows);
 hipError_t launch_score_ragged(const Dims& dm, const madakv_config& c, const void* q_recent, const void* k_c,
                                const int64_t* seg_off, const int32_t* seg_len, int longest_rows, float* psi_c, void* ws, hipStream_t st);
+// the last-window prefill attention with the Eq. 7 scores as a by-product
+bool window_attn_supported(const Dims& dm, const madakv_config& c);
+size_t window_attn_ws_bytes(const Dims& dm, const madakv_config& c);
+hipError_t launch_window_attn(const Dims& dm, const madakv_config& c, const void* q_win, const void* k, const void* v,
+                              void* out, float* row_lse, float* psi, void* ws, hipStream_t st);
 hipError_t launch_restats(const Dims& dm, const madakv_config& c, const float* psi_c, const int32_t* kept_idx, const uint8_t* mask,
                           const int64_t* seg_off, const int32_t* seg_len, int appended, float* pool_c, uint8_t* rowmod,
                           void* stats, int32_t* budgets, hipStream_t st);

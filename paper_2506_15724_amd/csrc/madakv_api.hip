@@ -166,6 +166,14 @@ int largest_group(int n) {
   return m;
 }
 
+size_t window_ws_for_call(const madakv_config& c, int n) {
+  int b[MAX_GROUPS + 1];
+  const int ng = layer_groups(n, b);
+  size_t need = 0;
+  for (int g = 0; g < ng; ++g) need = std::max(need, window_attn_ws_bytes(make_dims(c, b[g + 1] - b[g]), c));
+  return need;
+}
+
 size_t score_ws_for_call(const madakv_config& c, int n) {
   int b[MAX_GROUPS + 1];
   const int ng = layer_groups(n, b);
@@ -347,15 +355,21 @@ int32_t madakv_compact_capacity_tokens(const madakv_handle* h, int64_t* tokens) 
   return MADAKV_OK;
 }
 
+// window_attn: v, out (and optionally lse_out) given: the scores come out of the last-window attention kernel
 static int32_t score_impl(madakv_handle* h, int32_t layer0, int32_t n,
                           const void* q_win, const void* k, const uint8_t* mask, const float* row_lse,
                           float* psi, float* psi_pool, void* stats, int32_t* n_mod,
-                          void* ws, size_t ws_bytes, void* stream) {
+                          void* ws, size_t ws_bytes, void* stream,
+                          const void* v = nullptr, void* out = nullptr, float* lse_out = nullptr) {
   int32_t r = check_range(h, layer0, n);
   if (r != MADAKV_OK) return r;
   if (bad_ptr(q_win) || bad_ptr(k) || bad_ptr(mask, 1) || bad_ptr(psi, 4) || bad_ptr(psi_pool, 4) || bad_ptr(stats, 4) ||
       bad_ptr(n_mod, 4) || bad_ptr(ws)) return MADAKV_ERR_INVALID_ARG;
-  if (ws_bytes < score_ws_for_call(h->cfg, n)) return MADAKV_ERR_WORKSPACE_TOO_SMALL;
+  const bool window_attn = v != nullptr;
+  if (window_attn) {
+    if (!window_attn_supported(make_dims(h->cfg, n), h->cfg)) return MADAKV_ERR_UNIMPLEMENTED;
+    if (ws_bytes < window_ws_for_call(h->cfg, n)) return MADAKV_ERR_WORKSPACE_TOO_SMALL;
+  } else if (ws_bytes < score_ws_for_call(h->cfg, n)) return MADAKV_ERR_WORKSPACE_TOO_SMALL;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   const madakv_config& c = h->cfg;
   // The call is cut into up to MAX_GROUPS layer groups: the score sweeps of a group run on the
@@ -374,7 +388,14 @@ static int32_t score_impl(madakv_handle* h, int32_t layer0, int32_t n,
     float* psi_g = psi + lb * c.n_kv_heads * (size_t)c.ctx_len;
     float* pool_g = psi_pool + lb * c.n_kv_heads * (size_t)(c.ctx_len - c.window);
     const float* lse_g = row_lse ? row_lse + lb * c.n_q_heads * c.window : nullptr;
-    e = launch_score(dg, c, qg, kg, lse_g, psi_g, ws, st);
+    if (window_attn) {
+      const size_t oes = c.out_fp32 ? 4 : es;
+      e = launch_window_attn(dg, c, qg, kg, static_cast<const char*>(v) + lb * c.n_kv_heads * (size_t)c.ctx_len * c.head_dim * es,
+                             static_cast<char*>(out) + lb * c.n_q_heads * c.window * c.head_dim * oes,
+                             lse_out ? lse_out + lb * c.n_q_heads * c.window : nullptr, psi_g, ws, st);
+    } else {
+      e = launch_score(dg, c, qg, kg, lse_g, psi_g, ws, st);
+    }
     hipStream_t ss = st;
     if (overlap && e == hipSuccess) {
       e = hipEventRecord(h->ev_grp[gi], st);
@@ -402,6 +423,21 @@ int32_t madakv_score_lse(madakv_handle* h, int32_t layer0, int32_t n,
                          void* ws, size_t ws_bytes, void* stream) {
   if (row_lse == nullptr || (reinterpret_cast<uintptr_t>(row_lse) & 3u)) return MADAKV_ERR_INVALID_ARG;
   return score_impl(h, layer0, n, q_win, k, mask, row_lse, psi, psi_pool, stats, n_mod, ws, ws_bytes, stream);
+}
+
+int32_t madakv_window_attn_workspace_bytes(const madakv_handle* h, int32_t n_layers_per_call, size_t* bytes) {
+  if (!h || !bytes || n_layers_per_call < 1 || n_layers_per_call > h->cfg.n_layers) return MADAKV_ERR_INVALID_ARG;
+  *bytes = window_ws_for_call(h->cfg, n_layers_per_call);
+  return MADAKV_OK;
+}
+
+int32_t madakv_window_attn_score(madakv_handle* h, int32_t layer0, int32_t n,
+                                 const void* q_win, const void* k, const void* v, const uint8_t* mask,
+                                 void* out, float* row_lse,
+                                 float* psi, float* psi_pool, void* stats, int32_t* n_mod,
+                                 void* ws, size_t ws_bytes, void* stream) {
+  if (bad_ptr(v) || bad_ptr(out) || (row_lse && (reinterpret_cast<uintptr_t>(row_lse) & 3u))) return MADAKV_ERR_INVALID_ARG;
+  return score_impl(h, layer0, n, q_win, k, mask, nullptr, psi, psi_pool, stats, n_mod, ws, ws_bytes, stream, v, out, row_lse);
 }
 
 int32_t madakv_allocate(madakv_handle* h, int32_t layer0, int32_t n,

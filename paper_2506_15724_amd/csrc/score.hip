@@ -358,6 +358,73 @@ __device__ __forceinline__ void score_head_stats_alone(const ScoreArgs& a, int L
   }
 }
 
+// After a workgroup has left the (max, sum) of every proxy row over its own keys in part[4 waves][mpad][2]
+// (LDS, behind a barrier): the head-wide exchange described above.  Leaves offs[r] = max + log2(sum) over
+// all keys of the head (log2 domain; +inf for padding rows).  All threads call it; the caller adds the
+// barrier after it.
+template <int D>
+__device__ __forceinline__ void exchange_row_stats(const ScoreArgs& a, int head, int split, int fs, int Lh, const uint16_t* kg,
+                                                   const uint16_t* qs, const float* part, float* offs, float* pm, int* s_fail) {
+  const int tid = threadIdx.x;
+  // a row none of whose keys here is visible has max NEG_BIG and a meaningless sum: merging it with
+  // anything real scales it by exp2(NEG_BIG - m) = 0
+  const int nparts = SCORE_THREADS / a.mpad;    // mpad is 32 or 64
+  const int r = tid % a.mpad, pt = tid / a.mpad;
+  if (fs == 1) {
+    if (tid < a.mpad) {
+      float m = NEG_BIG, l = 0.f;
+      for (int w = 0; w < 4; ++w) merge_ml(m, l, part[(w * a.mpad + tid) * 2], part[(w * a.mpad + tid) * 2 + 1]);
+      offs[tid] = (tid < a.M) ? m + log2f(l) : __builtin_inff();
+    }
+  } else {
+    unsigned long long* xh = a.xchg + (long long)head * a.fsplit * a.mpad;
+    if (tid < a.mpad) {
+      float m = NEG_BIG, l = 0.f;
+      for (int w = 0; w < 4; ++w) merge_ml(m, l, part[(w * a.mpad + tid) * 2], part[(w * a.mpad + tid) * 2 + 1]);
+      unsigned long long word = ((unsigned long long)__float_as_uint(l) << 32) | __float_as_uint(m);
+      if (word == XCHG_EMPTY) word = 0x7fc000007fc00000ULL;            // cannot happen with finite inputs
+      __hip_atomic_store(xh + (long long)split * a.mpad + tid, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    // thread (r, pt) merges the chunks [pt * cpp, (pt + 1) * cpp) of row r in order, eight loads at a time
+    const int cpp = (fs + nparts - 1) / nparts;
+    int s = min(pt * cpp, fs);
+    const int s1 = min(s + cpp, fs);
+    float m = NEG_BIG, l = 0.f;
+    int patience = a.spin_limit;
+    bool fail = false;
+    while (s < s1) {
+      unsigned long long v[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        v[j] = __hip_atomic_load(xh + (long long)min(s + j, s1 - 1) * a.mpad + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      int got = 0;
+      bool open = true;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        open = open && (s + j < s1) && (v[j] != XCHG_EMPTY);
+        if (open) { merge_ml(m, l, __uint_as_float((uint32_t)v[j]), __uint_as_float((uint32_t)(v[j] >> 32))); ++got; }
+      }
+      s += got;
+      if (got == 0) {
+        if (--patience == 0) { fail = true; break; }
+        __builtin_amdgcn_s_sleep(8);
+      }
+    }
+    if (fail) *s_fail = 1;
+    pm[(pt * a.mpad + r) * 2] = m;
+    pm[(pt * a.mpad + r) * 2 + 1] = l;
+    __syncthreads();
+    if (__builtin_expect(*s_fail, 0)) {         // uniform over the workgroup
+      if (tid == 0) atomicAdd(a.status, 1);
+      score_head_stats_alone<D>(a, Lh, kg, qs, offs);
+    } else if (tid < a.mpad) {
+      float mm = NEG_BIG, ll = 0.f;
+      for (int q = 0; q < nparts; ++q) merge_ml(mm, ll, pm[(q * a.mpad + tid) * 2], pm[(q * a.mpad + tid) * 2 + 1]);
+      offs[tid] = (tid < a.M) ? mm + log2f(ll) : __builtin_inff();
+    }
+  }
+}
+
 #ifndef MADAKV_FUSED_NS1      // tuning constants of the one-sweep kernel (measured on MI355X)
 #define MADAKV_FUSED_NS1 8    // subtiles per wave with one row block
 #define MADAKV_FUSED_NS2 6    // ... with two row blocks
@@ -496,63 +563,7 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(M
     }
   }
   __syncthreads();
-  // a row none of whose keys here is visible has max NEG_BIG and a meaningless sum: merging it with
-  // anything real scales it by exp2(NEG_BIG - m) = 0
-  const int nparts = SCORE_THREADS / a.mpad;    // mpad is 32 or 64
-  const int r = tid % a.mpad, pt = tid / a.mpad;
-  if (fs == 1) {
-    if (tid < a.mpad) {
-      float m = NEG_BIG, l = 0.f;
-      for (int w = 0; w < 4; ++w) merge_ml(m, l, part[(w * a.mpad + tid) * 2], part[(w * a.mpad + tid) * 2 + 1]);
-      offs[tid] = (tid < a.M) ? m + log2f(l) : __builtin_inff();
-    }
-  } else {
-    unsigned long long* xh = a.xchg + (long long)head * a.fsplit * a.mpad;
-    if (tid < a.mpad) {
-      float m = NEG_BIG, l = 0.f;
-      for (int w = 0; w < 4; ++w) merge_ml(m, l, part[(w * a.mpad + tid) * 2], part[(w * a.mpad + tid) * 2 + 1]);
-      unsigned long long word = ((unsigned long long)__float_as_uint(l) << 32) | __float_as_uint(m);
-      if (word == XCHG_EMPTY) word = 0x7fc000007fc00000ULL;            // cannot happen with finite inputs
-      __hip_atomic_store(xh + (long long)split * a.mpad + tid, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    // thread (r, pt) merges the chunks [pt * cpp, (pt + 1) * cpp) of row r in order, eight loads at a time
-    const int cpp = (fs + nparts - 1) / nparts;
-    int s = min(pt * cpp, fs);
-    const int s1 = min(s + cpp, fs);
-    float m = NEG_BIG, l = 0.f;
-    int patience = a.spin_limit;
-    bool fail = false;
-    while (s < s1) {
-      unsigned long long v[8];
-#pragma unroll
-      for (int j = 0; j < 8; ++j)
-        v[j] = __hip_atomic_load(xh + (long long)min(s + j, s1 - 1) * a.mpad + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      int got = 0;
-      bool open = true;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        open = open && (s + j < s1) && (v[j] != XCHG_EMPTY);
-        if (open) { merge_ml(m, l, __uint_as_float((uint32_t)v[j]), __uint_as_float((uint32_t)(v[j] >> 32))); ++got; }
-      }
-      s += got;
-      if (got == 0) {
-        if (--patience == 0) { fail = true; break; }
-        __builtin_amdgcn_s_sleep(8);
-      }
-    }
-    if (fail) s_fail = 1;
-    pm[(pt * a.mpad + r) * 2] = m;
-    pm[(pt * a.mpad + r) * 2 + 1] = l;
-    __syncthreads();
-    if (__builtin_expect(s_fail, 0)) {         // uniform over the workgroup
-      if (tid == 0) atomicAdd(a.status, 1);
-      score_head_stats_alone<D>(a, Lh, kg, qs, offs);
-    } else if (tid < a.mpad) {
-      float mm = NEG_BIG, ll = 0.f;
-      for (int q = 0; q < nparts; ++q) merge_ml(mm, ll, pm[(q * a.mpad + tid) * 2], pm[(q * a.mpad + tid) * 2 + 1]);
-      offs[tid] = (tid < a.M) ? mm + log2f(ll) : __builtin_inff();
-    }
-  }
+  exchange_row_stats<D>(a, head, split, fs, Lh, kg, qs, part, offs, pm, &s_fail);
   __syncthreads();
 
   // ---- column sums from the registers
@@ -571,6 +582,237 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(M
     colsum += __shfl_xor(colsum, 32, 64);
     const int key = chunk0 + (it * 4 + wave) * 32 + col;
     if (half == 0 && key < chunk1) __builtin_nontemporal_store(colsum, a.psi + (base + key));
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// The prefill attention of the last W prompt positions (paper Sec. 3.1 Eq. 5 for the proxy rows of
+// Sec. 3.3) with the proxy-token scores of Eq. 7 as a by-product: out = softmax(scale Q K^T) V for
+// the G*W <= 32 proxy rows of a KV head, their log-sum-exp, and psi = the column sums of the same
+// softmax rows.  A model's prefill runs this attention anyway; taking psi from it removes the
+// eviction's own sweep over K.
+// Same structure as score_fused_kernel (a workgroup's logits stay in registers across the
+// head-wide exchange of row statistics), with the contraction transposed: S^T = K Q^T, so a
+// lane holds one proxy row and 16 keys of a subtile.  Row statistics are then in-lane, the
+// column sums of Eq. 7 one half-wave reduction per key, and P is already laid out as the A
+// operand of O += P V: the contraction index of that product is numbered so that a lane's
+// eight keys of a 16-key step are the eight it holds.  V subtiles are streamed through the same
+// wave-private LDS tile as K was; a B fragment (eight keys of one output column) is gathered
+// from it two bytes at a time.  P goes in as bf16 hi + lo parts (two MFMAs), which keeps
+// fp32-level accuracy.  Every workgroup leaves its share of O (already normalised: p uses the
+// head-wide statistics) in memory; window_attn_reduce_kernel adds the shares in chunk order.
+// ------------------------------------------------------------------------------------
+struct WinArgs {
+  ScoreArgs s;
+  const void* v;       // [heads, L, d]
+  float* opart;        // [heads, fsplit, 32, d] shares of O
+  float* lse;          // optional [heads/H * Hq, W] natural log-sum-exp of every proxy row
+  void* out;           // [heads/H * Hq, W, d]
+  int out_fp32;
+};
+
+template <int D, int NS>
+__global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void window_attn_kernel(WinArgs wa) {
+  const ScoreArgs& a = wa.s;
+  constexpr int KS = D / 16, RS = D + 8, PPR = D / 8, LPS = 32 * PPR / 64, CK = 4 * NS * 32, PF = 2, DB = D / 32;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  uint16_t* qs = reinterpret_cast<uint16_t*>(smem);                       // [32][RS]
+  uint16_t* kt_all = qs + 32 * RS;                                        // [4 waves][32][RS]
+  float* part = reinterpret_cast<float*>(kt_all + 4 * 32 * RS);           // [4 waves][32][2]
+  float* offs = part + 4 * 32 * 2;                                        // [32]
+  float* pm = offs + 32;                                                  // [8 parts][32][2]
+  __shared__ int s_fail;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int split = blockIdx.x;
+  const int head = a.head0 + blockIdx.y;
+  const int kvh = head % a.H;
+  const long long lb = head / a.H;
+  const uint16_t* qg = reinterpret_cast<const uint16_t*>(a.q_win) + (lb * a.H + kvh) * (long long)a.G * a.W * D;
+  const uint16_t* kg = reinterpret_cast<const uint16_t*>(a.k) + (long long)head * a.L * D;
+  const uint16_t* vg = reinterpret_cast<const uint16_t*>(wa.v) + (long long)head * a.L * D;
+  const int Lh = a.L, fs = a.fsplit;
+  const int chunk0 = split * CK;
+  const int chunk1 = min(Lh, chunk0 + CK);
+  uint16_t* kt = kt_all + (size_t)wave * 32 * RS;
+  if (tid == 0) s_fail = 0;
+
+  u32x4_t pre[PF][LPS];
+#define MADAKV_WIN_LOAD(BASE, SET, IT)                                                           \
+  {                                                                                              \
+    const int lt0 = chunk0 + ((IT) * 4 + wave) * 32;                                             \
+    _Pragma("unroll") for (int i = 0; i < LPS; ++i) {                                            \
+      const int idx = i * 64 + lane;                                                             \
+      const int lkey = min(lt0 + idx / PPR, Lh - 1); /* past the end: a valid row, masked */     \
+      pre[SET][i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(BASE + (long long)lkey * D + (idx % PPR) * 8)); \
+    }                                                                                            \
+  }
+#define MADAKV_WIN_PARK(SET)                                                                     \
+  _Pragma("unroll") for (int i = 0; i < LPS; ++i) {                                              \
+    const int idx = i * 64 + lane;                                                               \
+    *reinterpret_cast<u32x4_t*>(kt + (idx / PPR) * RS + (idx % PPR) * 8) = pre[SET][i];          \
+  }
+#pragma unroll
+  for (int it = 0; it < PF; ++it) MADAKV_WIN_LOAD(kg, it, it)
+
+  for (int e = tid; e < 32 * PPR; e += SCORE_THREADS) {                   // Q tile, padding rows zero
+    const int r = e / PPR, c = e % PPR;
+    uint4 val = make_uint4(0, 0, 0, 0);
+    if (r < a.M) val = *reinterpret_cast<const uint4*>(qg + (long long)r * D + c * 8);
+    *reinterpret_cast<uint4*>(qs + r * RS + c * 8) = val;
+  }
+  __syncthreads();
+
+  const int half = lane >> 5, col = lane & 31;            // col = this lane's proxy row
+  const int first_masked = Lh - a.W + 1;
+  const int pos = Lh - a.W + (col % a.W);                 // last key the row sees
+  bf16x8_t qfrag[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks)
+    qfrag[ks] = *reinterpret_cast<const bf16x8_t*>(qs + col * RS + half * (D / 2) + ks * 8);
+
+  // ---- S^T = K Q^T: lg[it][j] = scaled logit of row `col` and key t0 + 8 (j >> 2) + 4 half + (j & 3)
+  float lg[NS][16];
+#pragma unroll
+  for (int it = 0; it < NS; ++it) {
+    MADAKV_WIN_PARK(it % PF)
+    if (it + PF < NS) MADAKV_WIN_LOAD(kg, it % PF, it + PF)
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const int t0 = chunk0 + (it * 4 + wave) * 32;
+    const bool tail = (t0 + 32 > first_masked) || (t0 + 32 > chunk1) || (a.M < 32);
+    const uint16_t* krow = kt + col * RS + half * (D / 2);
+    f32x16_t acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const bf16x8_t kfrag = *reinterpret_cast<const bf16x8_t*>(krow + ks * 8);
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfrag, qfrag[ks], acc, 0, 0, 0);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const int key = t0 + 8 * (j >> 2) + 4 * half + (j & 3);
+      const bool valid = !tail || ((key < chunk1) && (key <= pos) && (col < a.M));
+      lg[it][j] = valid ? acc[j] * a.scale_log2 : NEG_BIG;
+    }
+  }
+
+  // ---- (max, sum) of the lane's row over this wave's keys: in-lane, then the two halves
+  {
+    float mx = NEG_BIG;
+#pragma unroll
+    for (int it = 0; it < NS; ++it)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) mx = fmaxf(mx, lg[it][j]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    float sm = 0.f;
+#pragma unroll
+    for (int it = 0; it < NS; ++it)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) sm += fast_exp2(lg[it][j] - mx);
+    sm += __shfl_xor(sm, 32, 64);
+    if (half == 0) { part[(wave * 32 + col) * 2] = mx; part[(wave * 32 + col) * 2 + 1] = sm; }
+  }
+  // the first V subtiles can be on their way during the exchange
+#pragma unroll
+  for (int it = 0; it < PF; ++it) MADAKV_WIN_LOAD(vg, it, it)
+  __syncthreads();
+  exchange_row_stats<D>(a, head, split, fs, Lh, kg, qs, part, offs, pm, &s_fail);
+  __syncthreads();
+  const float off = offs[col];
+  if (split == 0 && wa.lse && tid < a.M) wa.lse[(lb * a.H + kvh) * (long long)a.G * a.W + tid] = offs[tid] * 0.6931471805599453f;
+
+  // ---- p = exp2(logit - off), Eq. 7 column sums, O += P V
+  f32x16_t oacc[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db) oacc[db] = f32x16_t{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int it = 0; it < NS; ++it) {
+    MADAKV_WIN_PARK(it % PF)
+    if (it + PF < NS) MADAKV_WIN_LOAD(vg, it % PF, it + PF)
+    const int t0 = chunk0 + (it * 4 + wave) * 32;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const float pj = fast_exp2(lg[it][j] - off);
+      lg[it][j] = pj;
+      const float cs = half_reduce<1>(pj);                 // over the 32 rows: psi of this key
+      const int key = t0 + 8 * (j >> 2) + 4 * half + (j & 3);
+      if (col == 0 && key < chunk1) a.psi[(long long)head * a.L + key] = cs;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int st = 0; st < 2; ++st) {                       // two 16-key steps of the subtile
+      uint32_t hi[4], lo[4];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float pv = lg[it][8 * st + i];
+        const uint32_t hb = f32_to_bf16_rne(pv);
+        const uint32_t lb2 = f32_to_bf16_rne(pv - bf16_bits_to_f32(hb));
+        if (i & 1) { hi[i >> 1] |= hb << 16; lo[i >> 1] |= lb2 << 16; }
+        else { hi[i >> 1] = hb; lo[i >> 1] = lb2; }
+      }
+      const bf16x8_t pa_hi = __builtin_bit_cast(bf16x8_t, u32x4_t{hi[0], hi[1], hi[2], hi[3]});
+      const bf16x8_t pa_lo = __builtin_bit_cast(bf16x8_t, u32x4_t{lo[0], lo[1], lo[2], lo[3]});
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {                      // V[key of contraction index 8 half + i][32 db + col]
+          const int row = 16 * st + 8 * (i >> 2) + 4 * half + (i & 3);
+          const uint32_t x = kt[row * RS + db * 32 + col];
+          if (i & 1) w[i >> 1] |= x << 16; else w[i >> 1] = x;
+        }
+        const bf16x8_t vb = __builtin_bit_cast(bf16x8_t, u32x4_t{w[0], w[1], w[2], w[3]});
+        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa_hi, vb, oacc[db], 0, 0, 0);
+        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa_lo, vb, oacc[db], 0, 0, 0);
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  }
+#undef MADAKV_WIN_LOAD
+#undef MADAKV_WIN_PARK
+
+  // ---- the four waves' shares of O, added in wave order, CR output columns at a time through the K/V tiles' space
+  constexpr int DPR = D == 128 ? 2 : 1, CR = 32 * DPR;     // 4 waves x 32 rows x CR floats fit the four tiles
+  static_assert(4 * 32 * CR * sizeof(float) <= 4 * 32 * RS * sizeof(uint16_t), "the shares must fit the tiles");
+  float* fl = reinterpret_cast<float*>(kt_all);           // [4 waves][32 rows][CR]
+  float* op = wa.opart + ((long long)head * fs + split) * 32 * D;
+  for (int rd = 0; rd < DB / DPR; ++rd) {
+    __syncthreads();
+#pragma unroll
+    for (int dd = 0; dd < DPR; ++dd)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int m = 8 * (j >> 2) + 4 * half + (j & 3);   // O[row m][column 32 db + col] sits in oacc[db][j]
+        fl[(wave * 32 + m) * CR + dd * 32 + col] = oacc[rd * DPR + dd][j];
+      }
+    __syncthreads();
+    for (int e = tid; e < 32 * CR; e += SCORE_THREADS) {
+      const int m = e / CR, c = e % CR;
+      op[m * D + rd * CR + c] = ((fl[(0 * 32 + m) * CR + c] + fl[(1 * 32 + m) * CR + c]) + fl[(2 * 32 + m) * CR + c]) + fl[(3 * 32 + m) * CR + c];
+    }
+  }
+}
+
+// out[row][c] = sum over the head's chunks, in chunk order, of their shares
+__global__ __launch_bounds__(256) void window_attn_reduce_kernel(WinArgs wa) {
+  const ScoreArgs& a = wa.s;
+  const int head = a.head0 + blockIdx.x;
+  const int kvh = head % a.H;
+  const long long lb = head / a.H;
+  const float* op = wa.opart + (long long)head * a.fsplit * 32 * a.d;
+  const long long obase = (lb * a.H + kvh) * (long long)a.G * a.W * a.d;
+  for (int e = threadIdx.x; e < a.M * a.d; e += blockDim.x) {
+    const int m = e / a.d, c = e % a.d;
+    float sum = 0.f;
+    for (int sp = 0; sp < a.fsplit; ++sp) sum += op[((long long)sp * 32 + m) * a.d + c];
+    if (wa.out_fp32) reinterpret_cast<float*>(wa.out)[obase + e] = sum;
+    else reinterpret_cast<uint16_t*>(wa.out)[obase + e] = f32_to_bf16_rne(sum);
   }
 }
 
@@ -758,6 +1000,46 @@ hipError_t launch_score_ragged(const Dims& dm, const madakv_config& c, const voi
     a.head0 = h0;
     if (dm.d == 128) { if (MB == 1) launch_mfma_pair<128, 1, 1>(a, nh, 0, 0, st); else launch_mfma_pair<128, 1, 2>(a, nh, 0, 0, st); }
     else { if (MB == 1) launch_mfma_pair<64, 1, 1>(a, nh, 0, 0, st); else launch_mfma_pair<64, 1, 2>(a, nh, 0, 0, st); }
+  }
+  return hipGetLastError();
+}
+
+// ---- the last-window attention with the scores as a by-product
+constexpr int WIN_NS_128 = 4, WIN_NS_64 = 6;             // subtiles per wave (registers: logits + the O tile)
+static int win_split(const Dims& dm) { const int ck = 4 * 32 * (dm.d == 128 ? WIN_NS_128 : WIN_NS_64); return (dm.L + ck - 1) / ck; }
+bool window_attn_supported(const Dims& dm, const madakv_config& c) {
+  return use_mfma(dm, c.dtype) && dm.M <= 32 && win_split(dm) <= FUSED_MAX_SPLIT;
+}
+size_t window_attn_ws_bytes(const Dims& dm, const madakv_config& c) {
+  if (!window_attn_supported(dm, c)) return 256;
+  return 256 + ((size_t)dm.heads * win_split(dm) * 32 * 8 + 255) / 256 * 256 + (size_t)dm.heads * win_split(dm) * 32 * dm.d * sizeof(float);
+}
+hipError_t launch_window_attn(const Dims& dm, const madakv_config& c, const void* q_win, const void* k, const void* v,
+                              void* out, float* row_lse, float* psi, void* ws, hipStream_t st) {
+  WinArgs wa;
+  ScoreArgs& a = wa.s;
+  a.lse = nullptr; a.q_win = q_win; a.k = k; a.psi = psi;
+  a.status = reinterpret_cast<int*>(ws);
+  a.rowstat = nullptr; a.sink = nullptr; a.seg_off = nullptr; a.seg_len = nullptr;
+  a.xchg = reinterpret_cast<unsigned long long*>(static_cast<char*>(ws) + 256);
+  a.H = dm.H; a.G = dm.G; a.d = dm.d; a.L = dm.L; a.W = dm.W; a.M = dm.M;
+  a.mpad = 32; a.nsplit = 0; a.nmerge = 0; a.chunk = 0; a.head0 = 0;
+  a.fsplit = win_split(dm);
+  const char* spin = getenv("MADAKV_SCORE_SPIN_LIMIT");
+  a.spin_limit = spin && atoi(spin) > 0 ? atoi(spin) : FUSED_SPIN_LIMIT;
+  const float scale = c.softmax_scale > 0.f ? c.softmax_scale : 1.0f / sqrtf((float)dm.d);
+  a.scale_log2 = scale * 1.4426950408889634f;
+  wa.v = v; wa.lse = row_lse; wa.out = out; wa.out_fp32 = c.out_fp32;
+  wa.opart = reinterpret_cast<float*>(static_cast<char*>(ws) + 256 + ((size_t)dm.heads * a.fsplit * 32 * 8 + 255) / 256 * 256);
+  const long long nx = (long long)dm.heads * a.fsplit * 32;
+  if (a.fsplit > 1) hipLaunchKernelGGL(score_xchg_init_kernel, dim3((unsigned)((nx + 255) / 256)), dim3(256), 0, st, a.xchg, nx);
+  const size_t lds = ((size_t)32 + 4 * 32) * (dm.d + 8) * 2 + ((size_t)4 * 32 * 2 + 32 + 512) * sizeof(float);
+  for (int h0 = 0; h0 < dm.heads; h0 += 65535) {
+    const int nh = std::min(65535, dm.heads - h0);
+    a.head0 = h0;
+    if (dm.d == 128) hipLaunchKernelGGL((window_attn_kernel<128, WIN_NS_128>), dim3(a.fsplit, nh), dim3(SCORE_THREADS), lds, st, wa);
+    else hipLaunchKernelGGL((window_attn_kernel<64, WIN_NS_64>), dim3(a.fsplit, nh), dim3(SCORE_THREADS), lds, st, wa);
+    hipLaunchKernelGGL(window_attn_reduce_kernel, dim3(nh), dim3(256), 0, st, wa);
   }
   return hipGetLastError();
 }

@@ -855,6 +855,86 @@ def test_reeviction_refusals():
     eng.close()
 
 
+def _window_workloads():
+    W = small_workloads()
+    return {"bf16_mha": W["bf16_mha"], "bf16_d64_gqa2": W["bf16_d64_gqa2"],
+            "bf16_w20_odd": W["bf16_mha"].scaled(name="bf16_w20_odd", ctx_len=1777, window=20, budget=222, n_layers=2, batch=1)}
+
+
+@pytest.mark.parametrize("name", list(_window_workloads().keys()))
+@pytest.mark.parametrize("fp32_out", [1, 0])
+def test_window_attention_with_scores(name, fp32_out):
+    """madakv_window_attn_score: the prefill attention of the last W positions (Eq. 5) and, from the same
+    pass, Eq. 7 / 6 / 9 as madakv_score gives them.  out and the row log-sum-exp against the oracle's
+    window_attention, psi against window_scores, statistics and pooled scores against the oracle on the
+    GPU's own psi; the whole eviction that follows equals the one after madakv_score wherever the two
+    psi agree to the last bit of every decision (checked through the free-running rules)."""
+    import os
+    wl = _window_workloads()[name]
+    NL, B, H, Hq, L, W, d = wl.n_layers, wl.batch, wl.n_kv_heads, wl.n_q_heads, wl.ctx_len, wl.window, wl.head_dim
+    G, nc = Hq // H, L - W
+    p = PU.oracle_params(wl)
+    q, k, v, mask, masks = PU.make_inputs(wl, DEV)
+    eng = engine(wl, out_fp32=fp32_out)
+    out = torch.full((NL, B, Hq, W, d), float("nan"), dtype=torch.float32 if fp32_out else torch.bfloat16, device=DEV)
+    lse = torch.full((NL, B, Hq, W), float("nan"), dtype=torch.float32, device=DEV)
+    for spin in (None, "1"):
+        if spin:
+            os.environ["MADAKV_SCORE_SPIN_LIMIT"] = spin          # workgroups that find a word missing go their own way
+        try:
+            eng.window_attn_score(0, NL, q, k, v, mask, out, lse)
+            torch.cuda.synchronize()
+        finally:
+            os.environ.pop("MADAKV_SCORE_SPIN_LIMIT", None)
+        qh, kh, vh = WL.to_f64(q), WL.to_f64(k), WL.to_f64(v)
+        psi_g, pool_g = eng.psi.cpu().numpy(), eng.psi_pool.cpu().numpy()
+        w_g, k_g = eng.stats_host()
+        worst_o = worst_l = 0.0
+        for l in range(NL):
+            for b in range(B):
+                o_ref, lse_ref = O.window_attention(qh[l, b], kh[l, b], vh[l, b], p.scale)
+                o_g = out[l, b].float().cpu().numpy()
+                tol = PU.DECODE_ATOL if fp32_out else PU.DECODE_ATOL + 2.0 ** -8 * np.abs(o_ref)     # bf16 output: half an ulp on top
+                assert (np.abs(o_g - o_ref) <= tol).all(), (l, b, np.abs(o_g - o_ref).max())
+                worst_o = max(worst_o, float(np.abs(o_g - o_ref).max()))
+                np.testing.assert_allclose(lse[l, b].cpu().numpy(), lse_ref, atol=2e-4, rtol=0)
+                worst_l = max(worst_l, float(np.abs(lse[l, b].cpu().numpy() - lse_ref).max()))
+                psi_o = O.window_scores(qh[l, b], kh[l, b], p.scale)
+                nbad, worst = PU.psi_close(psi_g[l, b], psi_o, G, W, L)
+                assert nbad == 0, worst
+                psi_in = psi_g[l, b].astype(np.float64)
+                w_o, k_o, n_o = O.modality_stats(psi_in, masks[b], W, p.theta)
+                np.testing.assert_allclose(w_g[l, b], w_o, rtol=2e-6, atol=1e-30)
+                np.testing.assert_array_equal(pool_g[l, b], O.pool_scores(psi_in, W, p.pool_k).astype(np.float32))
+                for h in range(H):
+                    for m in (0, 1):
+                        if k_g[l, b, h, m] != k_o[h, m]:
+                            assert PU.k_count_ok(int(k_g[l, b, h, m]), psi_in[h, :nc][masks[b][:nc] == m], p.theta)
+        say(f"{name} spin={spin}: out worst abs err {worst_o:.2e}, lse {worst_l:.2e}")
+    # the eviction that follows, against the whole oracle
+    eng.allocate(0, NL); eng.select_gather(0, NL, k, v, mask)
+    torch.cuda.synchronize()
+    bud_g = eng.budgets.cpu().numpy(); kv_off, kv_len = eng.kv_off.cpu().numpy(), eng.kv_len.cpu().numpy()
+    kept_all = eng.kept_idx.cpu().numpy(); nmod_g = eng.n_mod.cpu().numpy()
+    for b in range(B):
+        res = O.evict(qh[:, b], kh[:, b], vh[:, b], masks[b], p)
+        cnt = PU.free_running_check(p, res, masks[b], w_g[:, b], k_g[:, b], nmod_g[b], bud_g[:, b],
+                                    lambda l, h: kept_all[kv_off[l, b, h]:kv_off[l, b, h] + kv_len[l, b, h]], say)
+        assert cnt["budget_unexcused"] == 0 and cnt["kept_unexcused"] == 0, cnt
+    eng.close()
+
+
+def test_window_attention_refusals():
+    wl = small_workloads()["bf16_gqa7"]                       # 224 proxy rows
+    q, k, v, mask, masks = PU.make_inputs(wl, DEV)
+    eng = engine(wl)
+    out = torch.empty(wl.n_layers, wl.batch, wl.n_q_heads, wl.window, wl.head_dim, dtype=torch.float32, device=DEV)
+    with pytest.raises(MB.MadaKVError) as ei:
+        eng.window_attn_score(0, wl.n_layers, q, k, v, mask, out)
+    assert ei.value.status == -7
+    eng.close()
+
+
 def test_error_paths_and_streams():
     """Host-side refusals on a live handle (nothing is enqueued), and calls on a non-default stream."""
     wl = small_workloads()["bf16_mha"].scaled(n_layers=2, batch=1, decode_steps=1)
