@@ -623,6 +623,19 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_gqa_kernel(DecodeArgs a) {
 template <typename T>
 __global__ __launch_bounds__(1024) void decode_merge_kernel(DecodeArgs a) {
   const long long hidx = blockIdx.x;
+  const int D = a.d;
+  const int g = min((int)threadIdx.x / D, a.G - 1), t = threadIdx.x % D;   // one thread per (query head of the group, element)
+  const long long cstride = (long long)a.G * (D + 2);
+  const float* pg = a.part + (hidx * a.max_chunks * a.G + g) * (long long)(D + 2);
+  // The first eight chunks' partials are fetched before the head's length is known (slots past the
+  // head's last chunk hold old values and are masked below): one round trip to memory instead of two.
+  const int lim = a.max_chunks - 1;
+  float mc[8], lc[8], ac[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const float* p = pg + (long long)min(j, lim) * cstride;
+    mc[j] = p[D]; lc[j] = p[D + 1]; ac[j] = p[t];
+  }
   const int len_old = a.kv_len[hidx];
   __syncthreads();                                   // every wave has read the length before anyone stores the new one
   const bool can_append = can_append_to(a, a.kv_off[hidx], len_old);
@@ -630,22 +643,23 @@ __global__ __launch_bounds__(1024) void decode_merge_kernel(DecodeArgs a) {
   const int nch = max(1, (len + a.chunk_rows - 1) / a.chunk_rows);
   if (can_append && threadIdx.x == 0) a.kv_len[hidx] = len;
   if (nch == 1) return;                              // output already written by the attention kernel
-  const int D = a.d;
-  const int g = threadIdx.x / D, t = threadIdx.x % D;   // one thread per (query head of the group, element)
-  if (g >= a.G) return;
+  if ((int)threadIdx.x / D >= a.G) return;
   const long long lb = hidx / a.H;
   const int h = (int)(hidx % a.H);
   const long long obase = (lb * a.H + h) * (long long)a.G * D;
-  const long long cstride = (long long)a.G * (D + 2);
-  const float* pg = a.part + (hidx * a.max_chunks * a.G + g) * (long long)(D + 2);
   float m = DNEG_BIG, ls = 0.f, av = 0.f;
   for (int c0 = 0; c0 < nch; c0 += 8) {              // 24 independent loads in flight per batch
-    float mc[8], lc[8], ac[8];
+    if (c0 > 0) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float* p = pg + (long long)min(c0 + j, lim) * cstride;
+        mc[j] = p[D]; lc[j] = p[D + 1]; ac[j] = p[t];
+      }
+    }
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const bool ok = c0 + j < nch;
-      const float* p = pg + (long long)(ok ? c0 + j : c0) * cstride;
-      mc[j] = ok ? p[D] : DNEG_BIG; lc[j] = ok ? p[D + 1] : 0.f; ac[j] = ok ? p[t] : 0.f;
+      mc[j] = ok ? mc[j] : DNEG_BIG; lc[j] = ok ? lc[j] : 0.f; ac[j] = ok ? ac[j] : 0.f;
     }
     float bm = m;
 #pragma unroll
