@@ -41,6 +41,12 @@ struct ScoreArgs {
   int fsplit;          // chunks per head of the one-sweep kernel
   const int64_t* seg_off;   // one-sweep kernel on ragged heads (null: every head has L keys at head * L): first row and
   const int32_t* seg_len;   // number of rows of each head in k; psi is indexed the same way
+  // one-sweep kernel with more than 64 proxy rows: the rows are cut into rb_count blocks of 64, each handled
+  // like a head of its own (grid.y = heads * rb_count); their column sums go to psi_part [rb][heads][L stride]
+  // and are added in block order afterwards
+  int rb_count;
+  float* psi_part;
+  long long psi_part_stride;   // floats between two row blocks' copies
   int spin_limit;      // polls a workgroup of the one-sweep kernel spends on one missing word before it goes its own way
   int head0;           // first head of this launch (grid.y indexes head0 + y)
   float scale_log2;    // softmax scale * log2(e)
@@ -327,13 +333,13 @@ __global__ __launch_bounds__(256) void score_xchg_init_kernel(unsigned long long
 // else: wave w takes rows w, w + 4, ...; lanes stride over the keys the row sees.  Q comes from
 // the staged tile.  Leaves offs[r] = max + log2(sum) (log2 domain), +inf for padding rows.
 template <int D>
-__device__ __forceinline__ void score_head_stats_alone(const ScoreArgs& a, int Lh, const uint16_t* kg, const uint16_t* qs, float* offs) {
+__device__ __forceinline__ void score_head_stats_alone(const ScoreArgs& a, int Lh, int Mh, int rowbase, const uint16_t* kg, const uint16_t* qs, float* offs) {
   constexpr int RS = D + 8;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   for (int r = wave; r < a.mpad; r += 4) {
     float m = NEG_BIG, l = 0.f;
-    if (r < a.M) {
-      const int pos = Lh - a.W + (r % a.W);
+    if (r < Mh) {
+      const int pos = Lh - a.W + ((rowbase + r) % a.W);
       for (int key = lane; key <= pos; key += 64) {
         float sdot = 0.f;
         for (int c = 0; c < D / 8; ++c) {
@@ -354,7 +360,7 @@ __device__ __forceinline__ void score_head_stats_alone(const ScoreArgs& a, int L
         merge_ml(m, l, m2, l2);
       }
     }
-    if (lane == 0) offs[r] = (r < a.M) ? m + log2f(l) : __builtin_inff();
+    if (lane == 0) offs[r] = (r < Mh) ? m + log2f(l) : __builtin_inff();
   }
 }
 
@@ -363,8 +369,8 @@ __device__ __forceinline__ void score_head_stats_alone(const ScoreArgs& a, int L
 // all keys of the head (log2 domain; +inf for padding rows).  All threads call it; the caller adds the
 // barrier after it.
 template <int D>
-__device__ __forceinline__ void exchange_row_stats(const ScoreArgs& a, int head, int split, int fs, int Lh, const uint16_t* kg,
-                                                   const uint16_t* qs, const float* part, float* offs, float* pm, int* s_fail) {
+__device__ __forceinline__ void exchange_row_stats(const ScoreArgs& a, int head, int split, int fs, int Lh, int Mh, int rowbase,
+                                                   const uint16_t* kg, const uint16_t* qs, const float* part, float* offs, float* pm, int* s_fail) {
   const int tid = threadIdx.x;
   // a row none of whose keys here is visible has max NEG_BIG and a meaningless sum: merging it with
   // anything real scales it by exp2(NEG_BIG - m) = 0
@@ -374,7 +380,7 @@ __device__ __forceinline__ void exchange_row_stats(const ScoreArgs& a, int head,
     if (tid < a.mpad) {
       float m = NEG_BIG, l = 0.f;
       for (int w = 0; w < 4; ++w) merge_ml(m, l, part[(w * a.mpad + tid) * 2], part[(w * a.mpad + tid) * 2 + 1]);
-      offs[tid] = (tid < a.M) ? m + log2f(l) : __builtin_inff();
+      offs[tid] = (tid < Mh) ? m + log2f(l) : __builtin_inff();
     }
   } else {
     unsigned long long* xh = a.xchg + (long long)head * a.fsplit * a.mpad;
@@ -416,11 +422,11 @@ __device__ __forceinline__ void exchange_row_stats(const ScoreArgs& a, int head,
     __syncthreads();
     if (__builtin_expect(*s_fail, 0)) {         // uniform over the workgroup
       if (tid == 0) atomicAdd(a.status, 1);
-      score_head_stats_alone<D>(a, Lh, kg, qs, offs);
+      score_head_stats_alone<D>(a, Lh, Mh, rowbase, kg, qs, offs);
     } else if (tid < a.mpad) {
       float mm = NEG_BIG, ll = 0.f;
       for (int q = 0; q < nparts; ++q) merge_ml(mm, ll, pm[(q * a.mpad + tid) * 2], pm[(q * a.mpad + tid) * 2 + 1]);
-      offs[tid] = (tid < a.M) ? mm + log2f(ll) : __builtin_inff();
+      offs[tid] = (tid < Mh) ? mm + log2f(ll) : __builtin_inff();
     }
   }
 }
@@ -452,10 +458,13 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(M
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int split = blockIdx.x;
-  const int head = a.head0 + blockIdx.y;
+  const int hv = a.head0 + blockIdx.y;        // head, or (head, block of 64 proxy rows) when there are more than 64
+  const int head = hv / a.rb_count;
+  const int rowbase = (hv % a.rb_count) * 64; // first proxy row of this workgroup's block
+  const int Mh = min(a.M - rowbase, a.mpad);  // its rows
   const int kvh = head % a.H;
   const long long lb = head / a.H;            // (layer, batch) index
-  const uint16_t* qg = reinterpret_cast<const uint16_t*>(a.q_win) + (lb * a.H + kvh) * (long long)a.G * a.W * D;
+  const uint16_t* qg = reinterpret_cast<const uint16_t*>(a.q_win) + ((lb * a.H + kvh) * (long long)a.G * a.W + rowbase) * D;
   // keys of this head: L rows at head * L, or (ragged: the rows of a reduced cache) seg_len rows at seg_off
   const int Lh = a.seg_len ? a.seg_len[head] : a.L;
   const long long base = a.seg_off ? a.seg_off[head] : (long long)head * a.L;
@@ -484,7 +493,7 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(M
   for (int e = tid; e < a.mpad * PPR; e += SCORE_THREADS) {               // Q tile, padding rows zero
     const int r = e / PPR, c = e % PPR;
     uint4 val = make_uint4(0, 0, 0, 0);
-    if (r < a.M) val = *reinterpret_cast<const uint4*>(qg + (long long)r * D + c * 8);
+    if (r < Mh) val = *reinterpret_cast<const uint4*>(qg + (long long)r * D + c * 8);
     *reinterpret_cast<uint4*>(qs + r * RS + c * 8) = val;
   }
   __syncthreads();
@@ -510,7 +519,7 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(M
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     const int t0 = chunk0 + (it * 4 + wave) * 32;
     const int key = t0 + col;
-    const bool tail = (t0 + 32 > first_masked) || (t0 + 32 > chunk1);
+    const bool tail = (t0 + 32 > first_masked) || (t0 + 32 > chunk1);     // (padding rows need no mask: their offset is +inf)
     const uint16_t* krow = kt + col * RS + half * (D / 2);
     bf16x8_t bfrag[KS];
 #pragma unroll
@@ -533,8 +542,8 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(M
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
           const int row = b * 32 + (j >> 2) * 8 + half * 4 + (j & 3);
-          const int pos = Lh - a.W + (row % a.W);
-          const bool valid = (key < chunk1) && (key <= pos) && (row < a.M);
+          const int pos = Lh - a.W + ((rowbase + row) % a.W);
+          const bool valid = (key < chunk1) && (key <= pos) && (row < Mh);
           lg[it][b][j] = valid ? acc[j] * a.scale_log2 : NEG_BIG;
         }
       }
@@ -563,7 +572,7 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(M
     }
   }
   __syncthreads();
-  exchange_row_stats<D>(a, head, split, fs, Lh, kg, qs, part, offs, pm, &s_fail);
+  exchange_row_stats<D>(a, hv, split, fs, Lh, Mh, rowbase, kg, qs, part, offs, pm, &s_fail);
   __syncthreads();
 
   // ---- column sums from the registers
@@ -581,7 +590,7 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(M
       for (int j = 0; j < 16; ++j) colsum += fast_exp2(lg[it][b][j] - off_r[b][j]);
     colsum += __shfl_xor(colsum, 32, 64);
     const int key = chunk0 + (it * 4 + wave) * 32 + col;
-    if (half == 0 && key < chunk1) __builtin_nontemporal_store(colsum, a.psi + (base + key));
+    if (half == 0 && key < chunk1) __builtin_nontemporal_store(colsum, (a.rb_count > 1 ? a.psi_part + (hv % a.rb_count) * a.psi_part_stride : a.psi) + (base + key));
   }
 }
 
@@ -719,7 +728,7 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(2
 #pragma unroll
   for (int it = 0; it < PF; ++it) MADAKV_WIN_LOAD(vg, it, it)
   __syncthreads();
-  exchange_row_stats<D>(a, head, split, fs, Lh, kg, qs, part, offs, pm, &s_fail);
+  exchange_row_stats<D>(a, head, split, fs, Lh, a.M, 0, kg, qs, part, offs, pm, &s_fail);
   __syncthreads();
   const float off = offs[col];
   if (split == 0 && wa.lse && tid < a.M) wa.lse[(lb * a.H + kvh) * (long long)a.G * a.W + tid] = offs[tid] * 0.6931471805599453f;
@@ -925,20 +934,63 @@ constexpr int FUSED_NS1 = MADAKV_FUSED_NS1, FUSED_NS2 = MADAKV_FUSED_NS2;
 constexpr int FUSED_MAX_SPLIT = MADAKV_FUSED_MAX_SPLIT;
 static int fused_chunk(const Dims& dm) { return 4 * 32 * ((dm.M + 31) / 32 == 1 ? FUSED_NS1 : FUSED_NS2); }
 static int fused_split(const Dims& dm) { return (dm.L + fused_chunk(dm) - 1) / fused_chunk(dm); }
+static int fused_mpad(const Dims& dm) { return dm.M <= 32 ? 32 : 64; }
+static int fused_blocks(const Dims& dm) { return dm.M <= 64 ? 1 : (dm.M + 63) / 64; }   // blocks of 64 proxy rows handled like heads
+static bool fused_fits(const Dims& dm, int dtype) {
+  return use_mfma(dm, dtype) && dm.M <= 256 && fused_split(dm) <= FUSED_MAX_SPLIT && (long long)dm.heads * fused_blocks(dm) <= 65535;
+}
 static bool use_fused(const Dims& dm, int dtype) {
   const char* e = getenv("MADAKV_SCORE_TWO_SWEEPS");      // diagnostic switch: the two-sweep kernels everywhere
   const bool off = e && atoi(e) != 0;
-  return !off && use_mfma(dm, dtype) && dm.M <= 64 && fused_split(dm) <= FUSED_MAX_SPLIT;
+  return !off && fused_fits(dm, dtype);
 }
 
 static size_t rowstat_bytes(const Dims& dm, int dtype) {
   ScorePlan p = score_plan(dm, dtype);
   return ((size_t)dm.heads * p.nsplit * p.mpad * 2 * sizeof(float) + 255) / 256 * 256;
 }
+static size_t xchg_bytes(const Dims& dm, int dtype) {
+  return fused_fits(dm, dtype) ? ((size_t)dm.heads * fused_blocks(dm) * fused_split(dm) * fused_mpad(dm) * 8 + 255) / 256 * 256 : 0;
+}
 size_t score_ws_bytes(const Dims& dm, int dtype) {
-  // the counter of lone workgroups, the row statistics of the two sweeps, the store sink, the exchange array of the one-sweep kernel
-  size_t xchg = use_mfma(dm, dtype) && dm.M <= 64 && fused_split(dm) <= FUSED_MAX_SPLIT ? (size_t)dm.heads * fused_split(dm) * ((dm.M + 31) / 32 * 32) * 8 : 0;
-  return 256 + rowstat_bytes(dm, dtype) + 256 + (xchg + 255) / 256 * 256;
+  // the counter of lone workgroups, the row statistics of the two sweeps, the store sink, the exchange array of the
+  // one-sweep kernel, its per-row-block copies of psi when there are more than 64 proxy rows
+  const size_t part = fused_fits(dm, dtype) && fused_blocks(dm) > 1 ? (size_t)fused_blocks(dm) * dm.heads * dm.L * sizeof(float) : 0;
+  return 256 + rowstat_bytes(dm, dtype) + 256 + xchg_bytes(dm, dtype) + part;
+}
+
+// psi = the row blocks' column sums added in block order (more than 64 proxy rows)
+__global__ __launch_bounds__(256) void score_blocks_sum_kernel(const float* part, long long stride, int blocks, float* psi, long long n) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  float acc = part[i];
+  for (int b = 1; b < blocks; ++b) acc += part[b * stride + i];
+  psi[i] = acc;
+}
+
+// the one-sweep kernel over `heads` heads (each cut into a.rb_count blocks of proxy rows)
+template <int D>
+static void launch_fused(const ScoreArgs& a, int heads, hipStream_t st) {
+  const int vheads = heads * a.rb_count;
+  const long long nx = (long long)vheads * a.fsplit * a.mpad;
+  if (a.fsplit > 1)
+    hipLaunchKernelGGL(score_xchg_init_kernel, dim3((unsigned)((nx + 255) / 256)), dim3(256), 0, st,
+                       a.xchg + (long long)a.head0 * a.rb_count * a.fsplit * a.mpad, nx);
+  const size_t ldsf = ((size_t)a.mpad + 4 * 32) * (D + 8) * 2 + ((size_t)4 * a.mpad * 2 + a.mpad + 512) * sizeof(float);
+  ScoreArgs b = a;
+  b.head0 = a.head0 * a.rb_count;
+  if (a.mpad == 32) {
+    hipLaunchKernelGGL((score_fused_kernel<D, 1, FUSED_NS1>), dim3(a.fsplit, vheads), dim3(SCORE_THREADS), ldsf, st, b);
+  } else {
+    if (ldsf > 48 * 1024)
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_fused_kernel<D, 2, FUSED_NS2>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)ldsf);
+    hipLaunchKernelGGL((score_fused_kernel<D, 2, FUSED_NS2>), dim3(a.fsplit, vheads), dim3(SCORE_THREADS), ldsf, st, b);
+  }
+  if (a.rb_count > 1) {
+    const long long n = (long long)heads * a.L;
+    hipLaunchKernelGGL(score_blocks_sum_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
+                       a.psi_part + (long long)a.head0 * a.L, a.psi_part_stride, a.rb_count, a.psi + (long long)a.head0 * a.L, n);
+  }
 }
 
 template <int D, int WPT, int NRB>
@@ -950,18 +1002,6 @@ static void launch_mfma_pair(const ScoreArgs& a0, int heads, size_t lds1, size_t
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_mfma_kernel<D, WPT, NRB, 2>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
-  }
-  if (!a.lse && a.fsplit > 0 && WPT == 1) {
-    constexpr int NS = NRB == 1 ? FUSED_NS1 : FUSED_NS2;
-    const long long nx = (long long)heads * a.fsplit * a.mpad;
-    if (a.fsplit > 1)
-      hipLaunchKernelGGL(score_xchg_init_kernel, dim3((unsigned)((nx + 255) / 256)), dim3(256), 0, st,
-                         a.xchg + (long long)a.head0 * a.fsplit * a.mpad, nx);
-    const size_t ldsf = ((size_t)a.mpad + 4 * 32) * (D + 8) * 2 + ((size_t)4 * a.mpad * 2 + a.mpad + 512) * sizeof(float);
-    if (ldsf > 48 * 1024)
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_fused_kernel<D, NRB, NS>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)ldsf);
-    hipLaunchKernelGGL((score_fused_kernel<D, NRB, NS>), dim3(a.fsplit, heads), dim3(SCORE_THREADS), ldsf, st, a);
-    return;
   }
   if (!a.lse) {
     hipLaunchKernelGGL((score_mfma_kernel<D, WPT, NRB, 1>), grid, dim3(SCORE_THREADS), lds1, st, a);
@@ -988,18 +1028,17 @@ hipError_t launch_score_ragged(const Dims& dm, const madakv_config& c, const voi
   a.xchg = reinterpret_cast<unsigned long long*>(static_cast<char*>(ws) + 256);
   a.seg_off = seg_off; a.seg_len = seg_len;
   a.H = dm.H; a.G = dm.G; a.d = dm.d; a.L = dm.L; a.W = dm.W; a.M = dm.M;
-  a.mpad = (dm.M + 31) / 32 * 32; a.nsplit = 0; a.nmerge = 0; a.chunk = 0; a.head0 = 0;
+  a.mpad = fused_mpad(dm); a.nsplit = 0; a.nmerge = 0; a.chunk = 0; a.head0 = 0;
   a.fsplit = ragged_split(dm, longest_rows);
   const char* spin = getenv("MADAKV_SCORE_SPIN_LIMIT");
   a.spin_limit = spin && atoi(spin) > 0 ? atoi(spin) : FUSED_SPIN_LIMIT;
   const float scale = c.softmax_scale > 0.f ? c.softmax_scale : 1.0f / sqrtf((float)dm.d);
   a.scale_log2 = scale * 1.4426950408889634f;
-  const int MB = a.mpad / 32;
+  a.rb_count = 1; a.psi_part = nullptr; a.psi_part_stride = 0;
   for (int h0 = 0; h0 < dm.heads; h0 += 65535) {
     const int nh = std::min(65535, dm.heads - h0);
     a.head0 = h0;
-    if (dm.d == 128) { if (MB == 1) launch_mfma_pair<128, 1, 1>(a, nh, 0, 0, st); else launch_mfma_pair<128, 1, 2>(a, nh, 0, 0, st); }
-    else { if (MB == 1) launch_mfma_pair<64, 1, 1>(a, nh, 0, 0, st); else launch_mfma_pair<64, 1, 2>(a, nh, 0, 0, st); }
+    if (dm.d == 128) launch_fused<128>(a, nh, st); else launch_fused<64>(a, nh, st);
   }
   return hipGetLastError();
 }
@@ -1024,6 +1063,7 @@ hipError_t launch_window_attn(const Dims& dm, const madakv_config& c, const void
   a.xchg = reinterpret_cast<unsigned long long*>(static_cast<char*>(ws) + 256);
   a.H = dm.H; a.G = dm.G; a.d = dm.d; a.L = dm.L; a.W = dm.W; a.M = dm.M;
   a.mpad = 32; a.nsplit = 0; a.nmerge = 0; a.chunk = 0; a.head0 = 0;
+  a.rb_count = 1; a.psi_part = nullptr; a.psi_part_stride = 0;
   a.fsplit = win_split(dm);
   const char* spin = getenv("MADAKV_SCORE_SPIN_LIMIT");
   a.spin_limit = spin && atoi(spin) > 0 ? atoi(spin) : FUSED_SPIN_LIMIT;
@@ -1054,6 +1094,9 @@ hipError_t launch_score(const Dims& dm, const madakv_config& c, const void* q_wi
   a.rowstat = reinterpret_cast<float*>(static_cast<char*>(ws) + 256);
   a.sink = reinterpret_cast<float*>(static_cast<char*>(ws) + 256 + rowstat_bytes(dm, c.dtype));
   a.xchg = reinterpret_cast<unsigned long long*>(static_cast<char*>(ws) + 256 + rowstat_bytes(dm, c.dtype) + 256);
+  a.rb_count = fused_blocks(dm);
+  a.psi_part = reinterpret_cast<float*>(static_cast<char*>(ws) + 256 + rowstat_bytes(dm, c.dtype) + 256 + xchg_bytes(dm, c.dtype));
+  a.psi_part_stride = (long long)dm.heads * dm.L;
   a.fsplit = (!row_lse && use_fused(dm, c.dtype)) ? fused_split(dm) : 0;
   a.seg_off = nullptr; a.seg_len = nullptr;
   // (a test can force the lone-workgroup path of the one-sweep kernel from the host with a spin limit of 1)
@@ -1063,6 +1106,11 @@ hipError_t launch_score(const Dims& dm, const madakv_config& c, const void* q_wi
   a.mpad = p.mpad; a.nsplit = p.nsplit; a.nmerge = p.nsplit; a.chunk = p.chunk; a.head0 = 0;
   float scale = c.softmax_scale > 0.f ? c.softmax_scale : 1.0f / sqrtf((float)dm.d);
   a.scale_log2 = scale * 1.4426950408889634f;
+  if (a.fsplit > 0) {                                      // one sweep (heads * row blocks fit one launch)
+    a.mpad = fused_mpad(dm);
+    if (dm.d == 128) launch_fused<128>(a, dm.heads, st); else launch_fused<64>(a, dm.heads, st);
+    return hipGetLastError();
+  }
   for (int h0 = 0; h0 < dm.heads; h0 += p.group_heads) {
     int nh = std::min(p.group_heads, dm.heads - h0);
     a.head0 = h0;
