@@ -280,8 +280,9 @@ int32_t madakv_decode_attn(madakv_handle* h, int32_t layer0, int32_t n,
  *   budgets  [n, B, H, M]       out: the new split
  *   ws                          madakv_reevict_workspace_bytes(h, n) bytes
  * The decode-step counters of the layers are reset: max_new_tokens rows can be appended again.
- * MADAKV_ERR_UNIMPLEMENTED with a paged or 8-bit cache, dtype fp32, G * W > 64 or segments longer than
- * 65536 rows; MADAKV_ERR_BAD_BUDGET when budget >= ctx_len (nothing was evicted). */
+ * MADAKV_ERR_UNIMPLEMENTED with a paged or 8-bit cache, dtype fp32, or segments longer than 64 chunks of the
+ * scoring kernel (65536 rows at G * W <= 32, 49152 beyond); MADAKV_ERR_BAD_BUDGET when budget >= ctx_len
+ * (nothing was evicted). */
 int32_t madakv_reevict_workspace_bytes(const madakv_handle* h, int32_t n_layers_per_call, size_t* bytes);
 int32_t madakv_reevict(madakv_handle* h, int32_t layer0, int32_t n,
                        const void* q_recent, const uint8_t* mask,

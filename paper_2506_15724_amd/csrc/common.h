@@ -61,9 +61,10 @@ hipError_t launch_select(const Dims& dm, const madakv_config& c, const float* ps
                          hipStream_t st, const int32_t* seg_len = nullptr, const uint8_t* rowmod = nullptr);
 // re-eviction during generation (reevict.hip, and the one-sweep scoring kernel on ragged segments)
 bool score_ragged_supported(const Dims& dm, const madakv_config& c, int longest_rows);
-size_t score_ragged_ws_bytes(const Dims& dm, const madakv_config& c, int longest_rows);
+size_t score_ragged_ws_bytes(const Dims& dm, const madakv_config& c, int longest_rows, long long cache_rows);
 hipError_t launch_score_ragged(const Dims& dm, const madakv_config& c, const void* q_recent, const void* k_c,
-                               const int64_t* seg_off, const int32_t* seg_len, int longest_rows, float* psi_c, void* ws, hipStream_t st);
+                               const int64_t* seg_off, const int32_t* seg_len, int longest_rows, long long cache_rows,
+                               float* psi_c, void* ws, hipStream_t st);
 // the last-window prefill attention with the Eq. 7 scores as a by-product
 bool window_attn_supported(const Dims& dm, const madakv_config& c);
 size_t window_attn_ws_bytes(const Dims& dm, const madakv_config& c);

@@ -579,7 +579,7 @@ ReevictWs reevict_layout(const madakv_handle* h, int n) {
   w.psi = 0; w.pool = up(cap * 4); w.sel = w.pool + up(cap * 4); w.rowmod = w.sel + up(cap * 4);
   w.stats = w.rowmod + up(cap);
   w.score = w.stats + up((size_t)dm.heads * 8 * c.n_modalities);
-  w.total = w.score + score_ragged_ws_bytes(dm, c, c.ctx_len + c.max_new_tokens);
+  w.total = w.score + score_ragged_ws_bytes(dm, c, c.ctx_len + c.max_new_tokens, (long long)cap);
   return w;
 }
 }  // namespace
@@ -621,7 +621,7 @@ int32_t madakv_reevict(madakv_handle* h, int32_t layer0, int32_t n,
     const char* qr = static_cast<const char*>(q_recent) + (size_t)(l0 - layer0) * c.batch * c.n_q_heads * c.window * c.head_dim * es;
     char* stats_r = wsb + w.stats + heads0 * 8 * c.n_modalities;
     int32_t* bud_r = budgets + heads0 * c.n_modalities;
-    e = launch_score_ragged(dr, c, qr, k_c, kv_off + heads0, kv_len + heads0, longest, psi_c, wsb + w.score, st);
+    e = launch_score_ragged(dr, c, qr, k_c, kv_off + heads0, kv_len + heads0, longest, region_tokens(c) * c.batch, psi_c, wsb + w.score, st);
     if (e == hipSuccess) e = launch_restats(dr, c, psi_c, kept_idx, mask, kv_off + heads0, kv_len + heads0, h->appended[l0], pool_c, rowmod,
                                             stats_r, bud_r, st);
     if (e == hipSuccess) e = launch_select(dr, c, pool_c, mask, bud_r, kv_off + heads0, kv_len + heads0, sel, st, kv_len + heads0, rowmod);

@@ -1013,14 +1013,20 @@ static void launch_mfma_pair(const ScoreArgs& a0, int heads, size_t lds1, size_t
 // ---- the one-sweep kernel on ragged heads: the rows of a reduced cache, scored against the most recent queries
 static int ragged_split(const Dims& dm, int longest_rows) { return (std::max(longest_rows, 1) + fused_chunk(dm) - 1) / fused_chunk(dm); }
 bool score_ragged_supported(const Dims& dm, const madakv_config& c, int longest_rows) {
-  return use_mfma(dm, c.dtype) && dm.M <= 64 && ragged_split(dm, longest_rows) <= FUSED_MAX_SPLIT;
+  return use_mfma(dm, c.dtype) && dm.M <= 256 && ragged_split(dm, longest_rows) <= FUSED_MAX_SPLIT &&
+         (long long)dm.heads * fused_blocks(dm) <= 65535;
 }
-size_t score_ragged_ws_bytes(const Dims& dm, const madakv_config& c, int longest_rows) {
+static size_t ragged_xchg_bytes(const Dims& dm, int longest_rows) {
+  return ((size_t)dm.heads * fused_blocks(dm) * ragged_split(dm, longest_rows) * fused_mpad(dm) * 8 + 255) / 256 * 256;
+}
+// cache_rows: rows of the whole reduced cache (psi_c is indexed like it; so are the row blocks' copies)
+size_t score_ragged_ws_bytes(const Dims& dm, const madakv_config& c, int longest_rows, long long cache_rows) {
   (void)c;
-  return 256 + ((size_t)dm.heads * ragged_split(dm, longest_rows) * ((dm.M + 31) / 32 * 32) * 8 + 255) / 256 * 256;
+  return 256 + ragged_xchg_bytes(dm, longest_rows) + (fused_blocks(dm) > 1 ? (size_t)fused_blocks(dm) * cache_rows * sizeof(float) : 0);
 }
 hipError_t launch_score_ragged(const Dims& dm, const madakv_config& c, const void* q_recent, const void* k_c,
-                               const int64_t* seg_off, const int32_t* seg_len, int longest_rows, float* psi_c, void* ws, hipStream_t st) {
+                               const int64_t* seg_off, const int32_t* seg_len, int longest_rows, long long cache_rows,
+                               float* psi_c, void* ws, hipStream_t st) {
   ScoreArgs a;
   a.lse = nullptr; a.q_win = q_recent; a.k = k_c; a.psi = psi_c;
   a.status = reinterpret_cast<int*>(ws);
@@ -1034,11 +1040,27 @@ hipError_t launch_score_ragged(const Dims& dm, const madakv_config& c, const voi
   a.spin_limit = spin && atoi(spin) > 0 ? atoi(spin) : FUSED_SPIN_LIMIT;
   const float scale = c.softmax_scale > 0.f ? c.softmax_scale : 1.0f / sqrtf((float)dm.d);
   a.scale_log2 = scale * 1.4426950408889634f;
-  a.rb_count = 1; a.psi_part = nullptr; a.psi_part_stride = 0;
-  for (int h0 = 0; h0 < dm.heads; h0 += 65535) {
-    const int nh = std::min(65535, dm.heads - h0);
-    a.head0 = h0;
-    if (dm.d == 128) launch_fused<128>(a, nh, st); else launch_fused<64>(a, nh, st);
+  a.rb_count = fused_blocks(dm);
+  a.psi_part = reinterpret_cast<float*>(static_cast<char*>(ws) + 256 + ragged_xchg_bytes(dm, longest_rows));
+  a.psi_part_stride = cache_rows;
+  if (a.rb_count == 1) {
+    if (dm.d == 128) launch_fused<128>(a, dm.heads, st); else launch_fused<64>(a, dm.heads, st);
+  } else {
+    // the kernel writes the row blocks' copies at the rows' own places; they are added over the whole cache
+    // (rows outside the call's segments hold old values of the workspace and are not read by anybody)
+    const ScoreArgs& b = a;
+    const int vheads = dm.heads * a.rb_count;
+    const long long nx = (long long)vheads * a.fsplit * a.mpad;
+    if (a.fsplit > 1) hipLaunchKernelGGL(score_xchg_init_kernel, dim3((unsigned)((nx + 255) / 256)), dim3(256), 0, st, a.xchg, nx);
+    const size_t ldsf = ((size_t)a.mpad + 4 * 32) * (dm.d + 8) * 2 + ((size_t)4 * a.mpad * 2 + a.mpad + 512) * sizeof(float);
+    if (dm.d == 128) {
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_fused_kernel<128, 2, FUSED_NS2>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)ldsf);
+      hipLaunchKernelGGL((score_fused_kernel<128, 2, FUSED_NS2>), dim3(a.fsplit, vheads), dim3(SCORE_THREADS), ldsf, st, b);
+    } else {
+      hipLaunchKernelGGL((score_fused_kernel<64, 2, FUSED_NS2>), dim3(a.fsplit, vheads), dim3(SCORE_THREADS), ldsf, st, b);
+    }
+    hipLaunchKernelGGL(score_blocks_sum_kernel, dim3((unsigned)((cache_rows + 255) / 256)), dim3(256), 0, st,
+                       a.psi_part, a.psi_part_stride, a.rb_count, psi_c, cache_rows);
   }
   return hipGetLastError();
 }

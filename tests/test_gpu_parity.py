@@ -742,7 +742,7 @@ def test_paged_reduced_cache(name, P, fp8):
     flat.close(); paged.close()
 
 
-@pytest.mark.parametrize("name", ["bf16_mha", "bf16_w64", "bf16_d64_gqa2", "bf16_odd"])
+@pytest.mark.parametrize("name", ["bf16_mha", "bf16_w64", "bf16_d64_gqa2", "bf16_odd", "bf16_gqa7"])
 def test_reeviction_during_generation(name):
     """madakv_reevict after some decode steps, twice: every head is brought back to the length the prompt
     eviction gave it.  Stage by stage against the oracle on the GPU's own upstream values (scores within
