@@ -600,8 +600,16 @@ int32_t madakv_reevict(madakv_handle* h, int32_t layer0, int32_t n,
   if (bad_ptr(q_recent) || bad_ptr(mask, 1) || bad_ptr(k_c) || bad_ptr(v_c) || bad_ptr(kept_idx, 4) || bad_ptr(kv_off, 8) ||
       bad_ptr(kv_len, 4) || bad_ptr(budgets, 4) || bad_ptr(ws)) return MADAKV_ERR_INVALID_ARG;
   if (c.budget >= c.ctx_len) return MADAKV_ERR_BAD_BUDGET;                 // nothing was evicted, nothing to bring back
-  const int longest = longest_rows(h, layer0, n);
-  if (c.page_rows || c.cache_fp8 || !score_ragged_supported(make_dims(c, n), c, longest)) return MADAKV_ERR_UNIMPLEMENTED;
+  if (c.page_rows || c.cache_fp8) return MADAKV_ERR_UNIMPLEMENTED;
+  int longest = longest_rows(h, layer0, n);
+  if (!score_ragged_supported(make_dims(c, n), c, longest)) {
+    // the bound may be the worst case only because the lengths of the eviction have not reached the host
+    // yet: this call is rare enough to wait for them once
+    bool pending = false;
+    for (int l = layer0; l < layer0 + n; ++l) pending = pending || h->maxlen_state[l] == 1;
+    if (pending && hipEventSynchronize(h->maxlen_event) == hipSuccess) longest = longest_rows(h, layer0, n);
+    if (!score_ragged_supported(make_dims(c, n), c, longest)) return MADAKV_ERR_UNIMPLEMENTED;
+  }
   const ReevictWs w = reevict_layout(h, n);
   if (ws_bytes < w.total) return MADAKV_ERR_WORKSPACE_TOO_SMALL;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
