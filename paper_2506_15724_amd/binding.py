@@ -266,15 +266,24 @@ class MadaKV:
                      self._sl(self.kv_off, l0, n), self._sl(self.kv_len, l0, n), self.k_c, self.v_c,
                      self.score_ws, self.select_ws)
 
+    def _check_out(self, out, numel):
+        """`out` is written in the handle's output type: a buffer of another type or size would be overrun."""
+        want = torch.float32 if self.cfg.out_fp32 else self.tdtype
+        if out.dtype != want or out.numel() < numel:
+            raise ValueError(f"out must hold {numel} elements of {want} (out_fp32={self.cfg.out_fp32}); got {out.numel()} of {out.dtype}")
+
     def decode_attn(self, l0, n, q, k_new, v_new, out):
+        self._check_out(out, n * self.cfg.batch * self.cfg.n_q_heads * self.cfg.head_dim)
         madakv_decode_attn(self.h, l0, n, q, k_new, v_new, self.k_c, self.v_c, self._sl(self.kv_off, l0, n),
                            self._sl(self.kv_len, l0, n), out, self.decode_ws)
 
     def decode_attn_static(self, l0, n, q, k_new, v_new, out):
+        self._check_out(out, n * self.cfg.batch * self.cfg.n_q_heads * self.cfg.head_dim)
         madakv_decode_attn_static(self.h, l0, n, q, k_new, v_new, self.k_c, self.v_c, self._sl(self.kv_off, l0, n),
                                   self._sl(self.kv_len, l0, n), out)
 
     def window_attn_score(self, l0, n, q_win, k, v, mask, out, row_lse=None):
+        self._check_out(out, n * self.cfg.batch * self.cfg.n_q_heads * self.cfg.window * self.cfg.head_dim)
         if getattr(self, "window_ws", None) is None:
             self.window_ws = torch.empty(max(16, madakv_window_attn_workspace_bytes(self.h, self.n_call)), dtype=torch.uint8, device=self.device)
         madakv_window_attn_score(self.h, l0, n, q_win, k, v, mask, out, row_lse, self._sl(self.psi, l0, n),

@@ -19,6 +19,8 @@ namespace madakv {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
 constexpr float NEG_BIG = -1.0e30f;
 constexpr int SCORE_THREADS = 256;
@@ -365,15 +367,28 @@ __device__ __forceinline__ void score_head_stats_alone(const ScoreArgs& a, int L
 }
 
 // After a workgroup has left the (max, sum) of every proxy row over its own keys in part[4 waves][mpad][2]
-// (LDS, behind a barrier): the head-wide exchange described above.  Leaves offs[r] = max + log2(sum) over
-// all keys of the head (log2 domain; +inf for padding rows).  All threads call it; the caller adds the
-// barrier after it.
-template <int D>
-__device__ __forceinline__ void exchange_row_stats(const ScoreArgs& a, int head, int split, int fs, int Lh, int Mh, int rowbase,
-                                                   const uint16_t* kg, const uint16_t* qs, const float* part, float* offs, float* pm, int* s_fail) {
+// (LDS, behind a barrier): the head-wide exchange described above, in two halves.  post_row_stats
+// publishes this workgroup's words and waits for nobody; collect_row_stats gathers the head's words and
+// leaves offs[r] = max + log2(sum) over all keys of the head (log2 domain; +inf for padding rows).
+// All threads call both; work that needs nobody else's statistics can sit between them.  The caller
+// adds the barrier after collect_row_stats.
+__device__ __forceinline__ void post_row_stats(const ScoreArgs& a, int head, int split, int fs, const float* part) {
   const int tid = threadIdx.x;
+  if (fs == 1 || tid >= a.mpad) return;
   // a row none of whose keys here is visible has max NEG_BIG and a meaningless sum: merging it with
   // anything real scales it by exp2(NEG_BIG - m) = 0
+  unsigned long long* xh = a.xchg + (long long)head * a.fsplit * a.mpad;
+  float m = NEG_BIG, l = 0.f;
+  for (int w = 0; w < 4; ++w) merge_ml(m, l, part[(w * a.mpad + tid) * 2], part[(w * a.mpad + tid) * 2 + 1]);
+  unsigned long long word = ((unsigned long long)__float_as_uint(l) << 32) | __float_as_uint(m);
+  if (word == XCHG_EMPTY) word = 0x7fc000007fc00000ULL;            // cannot happen with finite inputs
+  __hip_atomic_store(xh + (long long)split * a.mpad + tid, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <int D>
+__device__ __forceinline__ void collect_row_stats(const ScoreArgs& a, int head, int fs, int Lh, int Mh, int rowbase,
+                                                  const uint16_t* kg, const uint16_t* qs, const float* part, float* offs, float* pm, int* s_fail) {
+  const int tid = threadIdx.x;
   const int nparts = SCORE_THREADS / a.mpad;    // mpad is 32 or 64
   const int r = tid % a.mpad, pt = tid / a.mpad;
   if (fs == 1) {
@@ -383,14 +398,7 @@ __device__ __forceinline__ void exchange_row_stats(const ScoreArgs& a, int head,
       offs[tid] = (tid < Mh) ? m + log2f(l) : __builtin_inff();
     }
   } else {
-    unsigned long long* xh = a.xchg + (long long)head * a.fsplit * a.mpad;
-    if (tid < a.mpad) {
-      float m = NEG_BIG, l = 0.f;
-      for (int w = 0; w < 4; ++w) merge_ml(m, l, part[(w * a.mpad + tid) * 2], part[(w * a.mpad + tid) * 2 + 1]);
-      unsigned long long word = ((unsigned long long)__float_as_uint(l) << 32) | __float_as_uint(m);
-      if (word == XCHG_EMPTY) word = 0x7fc000007fc00000ULL;            // cannot happen with finite inputs
-      __hip_atomic_store(xh + (long long)split * a.mpad + tid, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
+    const unsigned long long* xh = a.xchg + (long long)head * a.fsplit * a.mpad;
     // thread (r, pt) merges the chunks [pt * cpp, (pt + 1) * cpp) of row r in order, eight loads at a time
     const int cpp = (fs + nparts - 1) / nparts;
     int s = min(pt * cpp, fs);
@@ -429,6 +437,13 @@ __device__ __forceinline__ void exchange_row_stats(const ScoreArgs& a, int head,
       offs[tid] = (tid < Mh) ? mm + log2f(ll) : __builtin_inff();
     }
   }
+}
+
+template <int D>
+__device__ __forceinline__ void exchange_row_stats(const ScoreArgs& a, int head, int split, int fs, int Lh, int Mh, int rowbase,
+                                                   const uint16_t* kg, const uint16_t* qs, const float* part, float* offs, float* pm, int* s_fail) {
+  post_row_stats(a, head, split, fs, part);
+  collect_row_stats<D>(a, head, fs, Lh, Mh, rowbase, kg, qs, part, offs, pm, s_fail);
 }
 
 #ifndef MADAKV_FUSED_NS1      // tuning constants of the one-sweep kernel (measured on MI355X)
@@ -600,16 +615,18 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(M
 // the G*W <= 32 proxy rows of a KV head, their log-sum-exp, and psi = the column sums of the same
 // softmax rows.  A model's prefill runs this attention anyway; taking psi from it removes the
 // eviction's own sweep over K.
-// Same structure as score_fused_kernel (a workgroup's logits stay in registers across the
-// head-wide exchange of row statistics), with the contraction transposed: S^T = K Q^T, so a
+// Same structure as score_fused_kernel (a workgroup's logits stay in registers while the row
+// statistics travel among the head's workgroups), with the contraction transposed: S^T = K Q^T, so a
 // lane holds one proxy row and 16 keys of a subtile.  Row statistics are then in-lane, the
 // column sums of Eq. 7 one half-wave reduction per key, and P is already laid out as the A
 // operand of O += P V: the contraction index of that product is numbered so that a lane's
 // eight keys of a 16-key step are the eight it holds.  V subtiles are streamed through the same
 // wave-private LDS tile as K was; a B fragment (eight keys of one output column) is gathered
 // from it two bytes at a time.  P goes in as bf16 hi + lo parts (two MFMAs), which keeps
-// fp32-level accuracy.  Every workgroup leaves its share of O (already normalised: p uses the
-// head-wide statistics) in memory; window_attn_reduce_kernel adds the shares in chunk order.
+// fp32-level accuracy.  The V sweep does not wait for the exchange: it exponentiates against the
+// wave's own row maxima, and the head-wide statistics, collected after it, enter as one factor per
+// row (for O and for the column sums alike).  Every workgroup leaves its share of O, normalised
+// that way, in memory; window_attn_reduce_kernel adds the shares in chunk order.
 // ------------------------------------------------------------------------------------
 struct WinArgs {
   ScoreArgs s;
@@ -709,13 +726,14 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(2
   }
 
   // ---- (max, sum) of the lane's row over this wave's keys: in-lane, then the two halves
+  float mx = NEG_BIG;
+#pragma unroll
+  for (int it = 0; it < NS; ++it)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) mx = fmaxf(mx, lg[it][j]);
+  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+  const float mloc = mx > NEG_BIG ? mx : 0.f;              // NEG_BIG: the row sees none of this wave's keys
   {
-    float mx = NEG_BIG;
-#pragma unroll
-    for (int it = 0; it < NS; ++it)
-#pragma unroll
-      for (int j = 0; j < 16; ++j) mx = fmaxf(mx, lg[it][j]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     float sm = 0.f;
 #pragma unroll
     for (int it = 0; it < NS; ++it)
@@ -724,16 +742,13 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(2
     sm += __shfl_xor(sm, 32, 64);
     if (half == 0) { part[(wave * 32 + col) * 2] = mx; part[(wave * 32 + col) * 2 + 1] = sm; }
   }
-  // the first V subtiles can be on their way during the exchange
 #pragma unroll
   for (int it = 0; it < PF; ++it) MADAKV_WIN_LOAD(vg, it, it)
   __syncthreads();
-  exchange_row_stats<D>(a, head, split, fs, Lh, a.M, 0, kg, qs, part, offs, pm, &s_fail);
-  __syncthreads();
-  const float off = offs[col];
-  if (split == 0 && wa.lse && tid < a.M) wa.lse[(lb * a.H + kvh) * (long long)a.G * a.W + tid] = offs[tid] * 0.6931471805599453f;
+  post_row_stats(a, head, split, fs, part);
 
-  // ---- p = exp2(logit - off), Eq. 7 column sums, O += P V
+  // ---- O += P V with p taken against the wave's own row maxima, so that nothing here waits for the
+  // other workgroups of the head; the head-wide statistics come in as one factor per row afterwards
   f32x16_t oacc[DB];
 #pragma unroll
   for (int db = 0; db < DB; ++db) oacc[db] = f32x16_t{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -741,15 +756,8 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(2
   for (int it = 0; it < NS; ++it) {
     MADAKV_WIN_PARK(it % PF)
     if (it + PF < NS) MADAKV_WIN_LOAD(vg, it % PF, it + PF)
-    const int t0 = chunk0 + (it * 4 + wave) * 32;
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      const float pj = fast_exp2(lg[it][j] - off);
-      lg[it][j] = pj;
-      const float cs = half_reduce<1>(pj);                 // over the 32 rows: psi of this key
-      const int key = t0 + 8 * (j >> 2) + 4 * half + (j & 3);
-      if (col == 0 && key < chunk1) a.psi[(long long)head * a.L + key] = cs;
-    }
+    for (int j = 0; j < 16; ++j) lg[it][j] = fast_exp2(lg[it][j] - mloc);   // masked: exp2(NEG_BIG) = 0
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -786,6 +794,32 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(2
 #undef MADAKV_WIN_LOAD
 #undef MADAKV_WIN_PARK
 
+  // ---- the head-wide statistics (by now the other workgroups have normally posted theirs)
+  collect_row_stats<D>(a, head, fs, Lh, a.M, 0, kg, qs, part, offs, pm, &s_fail);
+  __syncthreads();
+  if (split == 0 && wa.lse && tid < a.M) wa.lse[(lb * a.H + kvh) * (long long)a.G * a.W + tid] = offs[tid] * 0.6931471805599453f;
+  const float mxw = part[(wave * 32 + col) * 2];           // the wave's own row maximum again
+  const float rs = mxw > NEG_BIG ? fast_exp2(mxw - offs[col]) : 0.f;   // this wave's p times rs = the softmax entry
+
+  // ---- Eq. 7 column sums
+#pragma unroll
+  for (int it = 0; it < NS; ++it) {
+    const int t0 = chunk0 + (it * 4 + wave) * 32;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const float cs = half_reduce<1>(lg[it][j] * rs);     // over the 32 rows: psi of this key
+      const int key = t0 + 8 * (j >> 2) + 4 * half + (j & 3);
+      if (col == 0 && key < chunk1) a.psi[(long long)head * a.L + key] = cs;
+    }
+  }
+  // ---- O rows take their factor: row m of the tile sits in lane m's rs
+#pragma unroll
+  for (int j = 0; j < 16; ++j) {
+    const float f = __shfl(rs, 8 * (j >> 2) + 4 * half + (j & 3), 64);
+#pragma unroll
+    for (int db = 0; db < DB; ++db) oacc[db][j] *= f;
+  }
+
   // ---- the four waves' shares of O, added in wave order, CR output columns at a time through the K/V tiles' space
   constexpr int DPR = D == 128 ? 2 : 1, CR = 32 * DPR;     // 4 waves x 32 rows x CR floats fit the four tiles
   static_assert(4 * 32 * CR * sizeof(float) <= 4 * 32 * RS * sizeof(uint16_t), "the shares must fit the tiles");
@@ -808,20 +842,34 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(2
   }
 }
 
-// out[row][c] = sum over the head's chunks, in chunk order, of their shares
+// out[row][c] = sum over the head's chunks, in chunk order, of their shares.  Grid (head, slice of
+// 256 float4 of the 32 x d tile); eight shares in flight per thread.
 __global__ __launch_bounds__(256) void window_attn_reduce_kernel(WinArgs wa) {
   const ScoreArgs& a = wa.s;
   const int head = a.head0 + blockIdx.x;
   const int kvh = head % a.H;
   const long long lb = head / a.H;
-  const float* op = wa.opart + (long long)head * a.fsplit * 32 * a.d;
-  const long long obase = (lb * a.H + kvh) * (long long)a.G * a.W * a.d;
-  for (int e = threadIdx.x; e < a.M * a.d; e += blockDim.x) {
-    const int m = e / a.d, c = e % a.d;
-    float sum = 0.f;
-    for (int sp = 0; sp < a.fsplit; ++sp) sum += op[((long long)sp * 32 + m) * a.d + c];
-    if (wa.out_fp32) reinterpret_cast<float*>(wa.out)[obase + e] = sum;
-    else reinterpret_cast<uint16_t*>(wa.out)[obase + e] = f32_to_bf16_rne(sum);
+  const int e4 = blockIdx.y * 256 + threadIdx.x;           // float4 index in the [32][d] tile
+  const int tile4 = 32 * a.d / 4;
+  if (e4 >= a.M * a.d / 4) return;
+  const f32x4_t* op = reinterpret_cast<const f32x4_t*>(wa.opart) + (long long)head * a.fsplit * tile4 + e4;
+  f32x4_t sum = {0.f, 0.f, 0.f, 0.f};
+  int sp = 0;
+  for (; sp + 8 <= a.fsplit; sp += 8) {
+    f32x4_t x[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) x[j] = __builtin_nontemporal_load(op + (long long)(sp + j) * tile4);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) sum += x[j];
+  }
+  for (; sp < a.fsplit; ++sp) sum += __builtin_nontemporal_load(op + (long long)sp * tile4);
+  const long long o = (lb * a.H + kvh) * (long long)a.G * a.W * a.d + (long long)e4 * 4;
+  if (wa.out_fp32) *reinterpret_cast<f32x4_t*>(reinterpret_cast<float*>(wa.out) + o) = sum;
+  else {
+    u32x2_t pk;
+    pk[0] = (uint32_t)f32_to_bf16_rne(sum[0]) | ((uint32_t)f32_to_bf16_rne(sum[1]) << 16);
+    pk[1] = (uint32_t)f32_to_bf16_rne(sum[2]) | ((uint32_t)f32_to_bf16_rne(sum[3]) << 16);
+    *reinterpret_cast<u32x2_t*>(reinterpret_cast<uint16_t*>(wa.out) + o) = pk;
   }
 }
 
@@ -1101,7 +1149,7 @@ hipError_t launch_window_attn(const Dims& dm, const madakv_config& c, const void
     a.head0 = h0;
     if (dm.d == 128) hipLaunchKernelGGL((window_attn_kernel<128, WIN_NS_128>), dim3(a.fsplit, nh), dim3(SCORE_THREADS), lds, st, wa);
     else hipLaunchKernelGGL((window_attn_kernel<64, WIN_NS_64>), dim3(a.fsplit, nh), dim3(SCORE_THREADS), lds, st, wa);
-    hipLaunchKernelGGL(window_attn_reduce_kernel, dim3(nh), dim3(256), 0, st, wa);
+    hipLaunchKernelGGL(window_attn_reduce_kernel, dim3(nh, (32 * dm.d / 4 + 255) / 256), dim3(256), 0, st, wa);
   }
   return hipGetLastError();
 }

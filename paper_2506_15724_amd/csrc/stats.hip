@@ -41,81 +41,110 @@ __device__ __forceinline__ uint32_t nonneg_bits(float v) {
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
 
-// Thread t owns STATS_EPT consecutive candidates of a chunk; values and modality bits stay in
-// registers through the three levels when the head fits one chunk (16384 candidates).
-__device__ __forceinline__ void load_owned(const float* psi, const uint8_t* mask, int i0, int nc, int M,
-                                           float (&v)[STATS_EPT], unsigned long long& mbits) {
-  const bool full = i0 + STATS_EPT <= nc;
-  if (full && ((reinterpret_cast<uintptr_t>(psi + i0) & 15u) == 0)) {
+// Ownership inside a chunk of STATS_THREADS * STATS_EPT candidates: thread t owns the groups of four
+// consecutive candidates number j * STATS_THREADS + t, j = 0 .. STATS_EPT / 4 - 1, so that a wave's
+// loads and stores cover whole cache lines.  Element e = 4 j + q of the thread is candidate
+// cbase + 4 (j * STATS_THREADS + t) + q.  Values and modality bits stay in registers through the three
+// levels when the head fits one chunk (16384 candidates).
+constexpr int STATS_GROUPS = STATS_EPT / 4;
+constexpr int POOL_R_REG = 3;                    // widest pooling half-width served from registers
+__device__ __forceinline__ int owned_start(int cbase, int tid, int j) { return cbase + 4 * (j * STATS_THREADS + tid); }
+
+// Also fetches, for the first and the last lane of a wave, the POOL_R_REG values before / after each of
+// its groups (the other lanes get theirs from the neighbouring lanes): edge[j][r] = psi[i - 3 + r] in
+// lane 0, psi[i + 4 + r] in lane 63, where i is the group's first candidate.
+__device__ __forceinline__ void load_owned(const float* psi, const uint8_t* mask, int cbase, int tid, int nc, int M, bool want_edges,
+                                           float (&v)[STATS_EPT], unsigned long long& mbits, float (&edge)[STATS_GROUPS][POOL_R_REG]) {
+  const bool al = (reinterpret_cast<uintptr_t>(psi + cbase) & 15u) == 0;
+  const bool alm = (reinterpret_cast<uintptr_t>(mask + cbase) & 3u) == 0;
+  const int lane = tid & 63;
+  const uint32_t top = (uint32_t)(M - 1);
+  uint32_t mw[STATS_GROUPS];
 #pragma unroll
-    for (int j = 0; j < STATS_EPT / 4; ++j) {
-      const f32x4_t x = *reinterpret_cast<const f32x4_t*>(psi + i0 + j * 4);
+  for (int j = 0; j < STATS_GROUPS; ++j) {
+    const int i = owned_start(cbase, tid, j);
+    if (al && i + 4 <= nc) {
+      const f32x4_t x = *reinterpret_cast<const f32x4_t*>(psi + i);
       v[j * 4 + 0] = x[0]; v[j * 4 + 1] = x[1]; v[j * 4 + 2] = x[2]; v[j * 4 + 3] = x[3];
-    }
-  } else {
+    } else {
 #pragma unroll
-    for (int e = 0; e < STATS_EPT; ++e) v[e] = (i0 + e < nc) ? psi[i0 + e] : 0.f;
+      for (int q = 0; q < 4; ++q) v[j * 4 + q] = (i + q < nc) ? psi[i + q] : 0.f;
+    }
+    if (alm && i + 4 <= nc) mw[j] = *reinterpret_cast<const uint32_t*>(mask + i);
+    else {
+      mw[j] = 0u;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) if (i + q < nc) mw[j] |= (uint32_t)mask[i + q] << (8 * q);
+    }
+    if (want_edges) {
+#pragma unroll
+      for (int r = 0; r < POOL_R_REG; ++r) {
+        float x = 0.f;
+        const int il = i - POOL_R_REG + r, ir = i + 4 + r;
+        if (lane == 0 && il >= 0 && il < nc) x = psi[il];
+        if (lane == 63 && ir < nc) x = psi[ir];
+        edge[j][r] = x;
+      }
+    }
   }
   // modality ids, two bits per element (ids above the last modality count as the last one)
   mbits = 0ULL;
-  const uint32_t top = (uint32_t)(M - 1);
-  if (full && ((reinterpret_cast<uintptr_t>(mask + i0) & 15u) == 0)) {
 #pragma unroll
-    for (int j = 0; j < STATS_EPT / 16; ++j) {
-      const u32x4_t w = *reinterpret_cast<const u32x4_t*>(mask + i0 + j * 16);
+  for (int j = 0; j < STATS_GROUPS; ++j)
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
-#pragma unroll
-        for (int bb = 0; bb < 4; ++bb)
-          mbits |= (unsigned long long)min((w[q] >> (8 * bb)) & 0xffu, top) << (2 * (j * 16 + q * 4 + bb));
-    }
-  } else {
-#pragma unroll
-    for (int e = 0; e < STATS_EPT; ++e)
-      if (i0 + e < nc) mbits |= (unsigned long long)min((uint32_t)mask[i0 + e], top) << (2 * e);
-  }
+    for (int q = 0; q < 4; ++q)
+      mbits |= (unsigned long long)min((mw[j] >> (8 * q)) & 0xffu, top) << (2 * (j * 4 + q));
 }
 
-// max-pool of half-width R over the candidates: the thread's own stretch plus R neighbours
-// on each side from memory; positions outside [0, nc) do not take part
+// pooling of half-width R <= POOL_R_REG over the candidates: a group's neighbours come from the lanes
+// next to it (from memory at the ends of a wave); positions outside [0, nc) do not take part
 template <int R, int AVG>
-__device__ __forceinline__ void pool_owned(const float* psi, float* pool, int i0, int nc, const float (&v)[STATS_EPT]) {
+__device__ __forceinline__ void pool_owned(float* pool, int cbase, int tid, int nc, const float (&v)[STATS_EPT],
+                                           const float (&edge)[STATS_GROUPS][POOL_R_REG]) {
   const float none = AVG ? 0.f : -__builtin_inff();          // what a position outside [0, nc) contributes
-  float ext[STATS_EPT + 2 * R + 1];
+  const int lane = tid & 63;
+  const bool alp = (reinterpret_cast<uintptr_t>(pool + cbase) & 15u) == 0;
 #pragma unroll
-  for (int r = 0; r < R; ++r) {
-    const int il = i0 - R + r, ir = i0 + STATS_EPT + r;
-    ext[r] = (il >= 0 && il < nc) ? psi[il] : none;
-    ext[R + STATS_EPT + r] = (ir < nc) ? psi[ir] : none;
-  }
+  for (int j = 0; j < STATS_GROUPS; ++j) {
+    const int i = owned_start(cbase, tid, j);
+    float ext[4 + 2 * POOL_R_REG];
 #pragma unroll
-  for (int e = 0; e < STATS_EPT; ++e) ext[R + e] = (i0 + e < nc) ? v[e] : none;
-  float o[STATS_EPT];
+    for (int r = 0; r < POOL_R_REG; ++r) {
+      // (all lanes take part in the shuffles; what is not needed for this R is dropped by the compiler)
+      const float fl = __shfl_up(v[j * 4 + 1 + r], 1, 64);                 // previous lane's elements 1, 2, 3
+      const float fr = __shfl_down(v[j * 4 + r], 1, 64);                   // next lane's elements 0, 1, 2
+      const int il = i - POOL_R_REG + r, ir = i + 4 + r;
+      const float xl = lane == 0 ? edge[j][r] : fl;
+      const float xr = lane == 63 ? edge[j][r] : fr;
+      ext[r] = (il >= 0 && il < nc) ? xl : none;
+      ext[POOL_R_REG + 4 + r] = (ir < nc) ? xr : none;
+    }
 #pragma unroll
-  for (int e = 0; e < STATS_EPT; ++e) {
-    if (AVG) {
-      float sm = 0.f;                                          // left to right over the clipped neighbourhood
+    for (int q = 0; q < 4; ++q) ext[POOL_R_REG + q] = (i + q < nc) ? v[j * 4 + q] : none;
+    float o[4];
 #pragma unroll
-      for (int r = -R; r <= R; ++r) sm += ext[R + e + r];
-      const int i = i0 + e;
-      const int cntw = min(i + R, nc - 1) - max(i - R, 0) + 1;
-      o[e] = sm / (float)cntw;
+    for (int q = 0; q < 4; ++q) {
+      if (AVG) {
+        float sm = 0.f;                                          // left to right over the clipped neighbourhood
+#pragma unroll
+        for (int r = -R; r <= R; ++r) sm += ext[POOL_R_REG + q + r];
+        const int ii = i + q;
+        const int cntw = min(ii + R, nc - 1) - max(ii - R, 0) + 1;
+        o[q] = sm / (float)cntw;
+      } else {
+        float mx = ext[POOL_R_REG + q];
+#pragma unroll
+        for (int r = 1; r <= R; ++r) mx = fmaxf(mx, fmaxf(ext[POOL_R_REG + q - r], ext[POOL_R_REG + q + r]));
+        o[q] = mx;
+      }
+    }
+    if (alp && i + 4 <= nc) {
+      f32x4_t x = {o[0], o[1], o[2], o[3]};
+      *reinterpret_cast<f32x4_t*>(pool + i) = x;
     } else {
-      float mx = ext[R + e];
 #pragma unroll
-      for (int r = 1; r <= R; ++r) mx = fmaxf(mx, fmaxf(ext[R + e - r], ext[R + e + r]));
-      o[e] = mx;
+      for (int q = 0; q < 4; ++q) if (i + q < nc) pool[i + q] = o[q];
     }
-  }
-  if (i0 + STATS_EPT <= nc && ((reinterpret_cast<uintptr_t>(pool + i0) & 15u) == 0)) {
-#pragma unroll
-    for (int j = 0; j < STATS_EPT / 4; ++j) {
-      f32x4_t x = {o[j * 4], o[j * 4 + 1], o[j * 4 + 2], o[j * 4 + 3]};
-      *reinterpret_cast<f32x4_t*>(pool + i0 + j * 4) = x;
-    }
-  } else {
-#pragma unroll
-    for (int e = 0; e < STATS_EPT; ++e) if (i0 + e < nc) pool[i0 + e] = o[e];
   }
 }
 
@@ -150,7 +179,9 @@ __global__ __launch_bounds__(STATS_THREADS) __attribute__((amdgpu_waves_per_eu(4
   }
   float v[STATS_EPT];
   unsigned long long mbits = 0ULL;
-  if (single) load_owned(psi, mask, tid * STATS_EPT, a.nc, M, v, mbits);
+  const bool reg_pool = a.pool_r <= POOL_R_REG;
+  float edge[STATS_GROUPS][POOL_R_REG];
+  if (single) load_owned(psi, mask, 0, tid, a.nc, M, reg_pool, v, mbits, edge);
 
   for (int level = 0; level < 3; ++level) {
     for (int e = tid; e < M * BINS; e += STATS_THREADS) { cnt[e] = 0; sum[e] = 0ULL; }
@@ -161,34 +192,35 @@ __global__ __launch_bounds__(STATS_THREADS) __attribute__((amdgpu_waves_per_eu(4
 #pragma unroll
     for (int m = 0; m < MM; ++m) { pfx[m] = (level > 0 && m < M) ? s_prefix[m] : 0u; dn[m] = (level > 0 && m < M) ? s_done[m] != 0 : false; }
     for (int c = 0; c < nchunks; ++c) {
-      const int i0 = c * CH + tid * STATS_EPT;
-      if (!single) load_owned(psi, mask, i0, a.nc, M, v, mbits);
-      const int nvalid = min(max(a.nc - i0, 0), STATS_EPT);
-      if (level == 0 && nvalid > 0) {
-        // pooled score for ranking (raw values); widths up to 7 from registers, wider ones the slow way
+      const int cbase = c * CH;
+      if (!single) load_owned(psi, mask, cbase, tid, a.nc, M, level == 0 && reg_pool, v, mbits, edge);
+      if (level == 0) {
+        // pooled scores for ranking (raw values): windows up to 7 from registers, wider ones the slow way
         switch (a.pool_r + (a.pool_mode ? 100 : 0)) {
-          case 0: case 100: pool_owned<0, 0>(psi, pool, i0, a.nc, v); break;
-          case 1: pool_owned<1, 0>(psi, pool, i0, a.nc, v); break;
-          case 2: pool_owned<2, 0>(psi, pool, i0, a.nc, v); break;
-          case 3: pool_owned<3, 0>(psi, pool, i0, a.nc, v); break;
-          case 101: pool_owned<1, 1>(psi, pool, i0, a.nc, v); break;
-          case 102: pool_owned<2, 1>(psi, pool, i0, a.nc, v); break;
-          case 103: pool_owned<3, 1>(psi, pool, i0, a.nc, v); break;
+          case 0: case 100: pool_owned<0, 0>(pool, cbase, tid, a.nc, v, edge); break;
+          case 1: pool_owned<1, 0>(pool, cbase, tid, a.nc, v, edge); break;
+          case 2: pool_owned<2, 0>(pool, cbase, tid, a.nc, v, edge); break;
+          case 3: pool_owned<3, 0>(pool, cbase, tid, a.nc, v, edge); break;
+          case 101: pool_owned<1, 1>(pool, cbase, tid, a.nc, v, edge); break;
+          case 102: pool_owned<2, 1>(pool, cbase, tid, a.nc, v, edge); break;
+          case 103: pool_owned<3, 1>(pool, cbase, tid, a.nc, v, edge); break;
           default:
-            for (int e = 0; e < nvalid; ++e) {
-              const int i = i0 + e;
-              const int lo = max(i - a.pool_r, 0), hi = min(i + a.pool_r, a.nc - 1);
-              float acc = a.pool_mode ? 0.f : psi[i];
-              for (int j = lo; j <= hi; ++j) acc = a.pool_mode ? acc + psi[j] : fmaxf(acc, psi[j]);
-              pool[i] = a.pool_mode ? acc / (float)(hi - lo + 1) : acc;
-            }
+            for (int g = 0; g < STATS_GROUPS; ++g)
+              for (int q = 0; q < 4; ++q) {
+                const int i = owned_start(cbase, tid, g) + q;
+                if (i >= a.nc) continue;
+                const int lo = max(i - a.pool_r, 0), hi = min(i + a.pool_r, a.nc - 1);
+                float acc = a.pool_mode ? 0.f : psi[i];
+                for (int j = lo; j <= hi; ++j) acc = a.pool_mode ? acc + psi[j] : fmaxf(acc, psi[j]);
+                pool[i] = a.pool_mode ? acc / (float)(hi - lo + 1) : acc;
+              }
         }
       }
 #pragma unroll
       for (int e = 0; e < STATS_EPT; ++e) {
         const int m = (int)((mbits >> (2 * e)) & 3ULL);
         const uint32_t key = nonneg_bits(v[e]);
-        bool match = e < nvalid;
+        bool match = owned_start(cbase, tid, e >> 2) + (e & 3) < a.nc;
         // (the per-modality state is picked with selects: indexing a register array by m would spill it)
         uint32_t pm = pfx[0]; bool dm_ = dn[0];
 #pragma unroll
