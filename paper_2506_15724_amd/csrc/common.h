@@ -78,7 +78,7 @@ hipError_t launch_compact(const Dims& dm, const madakv_config& c, void* k_c, voi
 hipError_t launch_gather(const Dims& dm, const madakv_config& c, int li0, int nli, const void* k, const void* v,
                          const int32_t* kept_idx, const int64_t* kv_off, const int32_t* kv_len,
                          void* k_c, void* v_c, const void* ws, long long region_tokens,
-                         int blocks_per_batch, int grid_blocks, hipStream_t st);
+                         int blocks_per_batch, int grid_blocks, hipStream_t st, bool leave_room = false);
 hipError_t launch_decode(const Dims& dm, const madakv_config& c, const void* q, const void* k_new,
                          const void* v_new, void* k_c, void* v_c, const int64_t* kv_off, int32_t* kv_len,
                          void* out, void* ws, long long capacity_tokens, int longest_rows, const Paging& pg, int layer0, hipStream_t st);

@@ -11,6 +11,8 @@
 
 namespace madakv {
 
+constexpr size_t GATHER_ROOM_LDS = 36 * 1024;   // four claims fit the 160 KB of a compute unit, five do not
+
 // native vector type: arrays of it stay in registers (the HIP uint4 struct ends up in scratch)
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
 
@@ -132,7 +134,7 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
 hipError_t launch_gather(const Dims& dm, const madakv_config& c, int li0, int nli, const void* k, const void* v,
                          const int32_t* kept_idx, const int64_t* kv_off, const int32_t* kv_len,
                          void* k_c, void* v_c, const void* ws, long long region_tokens,
-                         int blocks_per_batch, int grid_blocks, hipStream_t st) {
+                         int blocks_per_batch, int grid_blocks, hipStream_t st, bool leave_room) {
   GatherArgs a;
   a.k = k; a.v = v; a.kept_idx = kept_idx; a.kv_off = kv_off; a.kv_len = kv_len; a.k_c = k_c; a.v_c = v_c;
   a.call_range = reinterpret_cast<const long long*>(ws);
@@ -143,13 +145,18 @@ hipError_t launch_gather(const Dims& dm, const madakv_config& c, int li0, int nl
   const int row_bytes = dm.d * (c.dtype == MADAKV_BF16 ? 2 : 4);
   const int lpr = row_bytes / 16;
   dim3 grid(std::min(grid_blocks, blocks_per_batch), dm.B);
+  // leave_room: statistics / selection kernels of another layer group run on a second stream meanwhile.
+  // Eight of these workgroups fit a compute unit and would keep it full until the grid has drained; the
+  // claim of GATHER_ROOM_LDS bytes of (unused) LDS holds them to four, which costs the copy nothing
+  // (measured: 2 to 8 workgroups per compute unit move the same bytes per second) and lets the others in.
+  const size_t lds = leave_room ? GATHER_ROOM_LDS : 0;
   if (c.cache_fp8) {
-    if (lpr == 8) hipLaunchKernelGGL((gather_kernel<8, true>), grid, dim3(256), 0, st, a);
-    else if (lpr == 16) hipLaunchKernelGGL((gather_kernel<16, true>), grid, dim3(256), 0, st, a);
+    if (lpr == 8) hipLaunchKernelGGL((gather_kernel<8, true>), grid, dim3(256), lds, st, a);
+    else if (lpr == 16) hipLaunchKernelGGL((gather_kernel<16, true>), grid, dim3(256), lds, st, a);
     else return hipErrorInvalidValue;
-  } else if (lpr == 8) hipLaunchKernelGGL((gather_kernel<8, false>), grid, dim3(256), 0, st, a);
-  else if (lpr == 16) hipLaunchKernelGGL((gather_kernel<16, false>), grid, dim3(256), 0, st, a);
-  else if (lpr == 32) hipLaunchKernelGGL((gather_kernel<32, false>), grid, dim3(256), 0, st, a);
+  } else if (lpr == 8) hipLaunchKernelGGL((gather_kernel<8, false>), grid, dim3(256), lds, st, a);
+  else if (lpr == 16) hipLaunchKernelGGL((gather_kernel<16, false>), grid, dim3(256), lds, st, a);
+  else if (lpr == 32) hipLaunchKernelGGL((gather_kernel<32, false>), grid, dim3(256), lds, st, a);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }

@@ -145,17 +145,11 @@ void destroy_side(madakv_handle* h) {
   for (int g = 0; g < MAX_GROUPS; ++g) if (h->ev_sel[g]) (void)hipEventDestroy(h->ev_sel[g]);
 }
 
-// Layers per group when a call over n layers is cut up for the overlap (1 group below 4 layers).
-// A call over n >= 4 layers is cut into MAX_GROUPS layer groups for the overlap: a short last group
-// (its statistics / selection have nothing to hide under) and the rest split evenly.  Fills
-// begin[0 .. groups] and returns the number of groups.
+// A call over n >= 4 layers is cut into MAX_GROUPS layer groups of (nearly) equal size for the overlap;
+// fewer layers make one group.  Fills begin[0 .. groups] and returns the number of groups.
 int layer_groups(int n, int* begin) {
   if (n < MAX_GROUPS) { begin[0] = 0; begin[1] = n; return 1; }
-  const int last = std::max(1, n / 16);
-  const int rest = n - last;
-  begin[0] = 0;
-  for (int g = 1; g < MAX_GROUPS; ++g) begin[g] = (int)((long long)rest * g / (MAX_GROUPS - 1));
-  begin[MAX_GROUPS] = n;
+  for (int g = 0; g <= MAX_GROUPS; ++g) begin[g] = (int)((long long)n * g / MAX_GROUPS);
   return MAX_GROUPS;
 }
 int largest_group(int n) {
@@ -470,10 +464,9 @@ int32_t madakv_select_gather(madakv_handle* h, int32_t layer0, int32_t n,
   const long long region = region_tokens(c);
   const int bpb = blocks_per_batch(c, n);
   hipError_t e = launch_offsets(dm, c, layer0, budgets, kv_off, kv_len, h->d_state + c.batch, h->d_maxlen + (size_t)layer0 * c.batch, ws, make_paging(h), bpb, st);
-  // (Running the selection of one layer group on the side stream under the gather of the
-  // previous group was measured: the two starve each other and nothing is gained.)
+  // (One group here: selection of all layers, then one gather.  madakv_evict pipelines layer groups.)
   if (e == hipSuccess) e = launch_select(dm, c, psi_pool, mask, budgets, kv_off, kv_len, kept_idx, st);
-  if (e == hipSuccess) e = launch_gather(dm, c, 0, n, k, v, kept_idx, kv_off, kv_len, k_c, v_c, ws, region, bpb, bpb, st);
+  if (e == hipSuccess) e = launch_gather(dm, c, 0, n, k, v, kept_idx, kv_off, kv_len, k_c, v_c, ws, region, bpb, bpb, st, false);
   for (int l = layer0; l < layer0 + n; ++l) { h->appended[l] = 0; h->gen_base[l] = 0; }
   e = publish_maxlen(h, layer0, n, st, e);
   return hip_fail(h, e);
@@ -504,9 +497,21 @@ int32_t madakv_evict(madakv_handle* h, int32_t layer0, int32_t n,
   const long long region = region_tokens(c);
   const size_t M = (size_t)c.n_modalities;
   hipError_t e = hipSuccess;
-  // Caller's stream: the score sweeps of every group, then the gathers.  Side stream: statistics,
-  // allocation, segment layout and selection of a group, as soon as its sweeps are done, under the
-  // sweeps of the following groups (these kernels are latency- and LDS-bound, the sweeps HBM-bound).
+  // Caller's stream: sweeps of group 0, sweeps of group 1, gather of group 0, sweeps of group 2, gather
+  // of group 1, ..., gather of the last group.  Side stream: statistics, allocation, segment layout and
+  // selection of a group as soon as its sweeps are done.  Only group 0's run beside sweeps (which they
+  // slow down by about their own duration); the others run beside the gather of the group before.
+  auto gather_group = [&](int gi) {
+    const int g0 = gb[gi], ng = gb[gi + 1] - g0;
+    Dims dg = make_dims(c, ng);
+    const size_t heads0 = (size_t)g0 * c.batch * c.n_kv_heads;
+    const char* kg = static_cast<const char*>(k) + heads0 * (size_t)c.ctx_len * c.head_dim * es;
+    const char* vg = static_cast<const char*>(v) + heads0 * (size_t)c.ctx_len * c.head_dim * es;
+    const char* ws_g = static_cast<const char*>(select_ws) + sel_slice * gi;
+    if (overlap) e = hipStreamWaitEvent(st, h->ev_sel[gi], 0);
+    const int bpb = blocks_per_batch(c, ng);
+    if (e == hipSuccess) e = launch_gather(dg, c, 0, ng, kg, vg, kept_idx, kv_off + heads0, kv_len + heads0, k_c, v_c, ws_g, region, bpb, bpb, st, overlap);
+  };
   for (int gi = 0; gi < ngroups && e == hipSuccess; ++gi) {
     const int g0 = gb[gi], ng = gb[gi + 1] - g0;
     Dims dg = make_dims(c, ng);
@@ -531,18 +536,11 @@ int32_t madakv_evict(madakv_handle* h, int32_t layer0, int32_t n,
                                             h->d_maxlen + (size_t)(layer0 + g0) * c.batch, ws_g, make_paging(h), blocks_per_batch(c, ng), ss);
     if (e == hipSuccess) e = launch_select(dg, c, pool_g, mask, bud_g, kv_off + heads0, kv_len + heads0, kept_idx, ss);
     if (overlap && e == hipSuccess) e = hipEventRecord(h->ev_sel[gi], h->side);
+    // the gather of the group before goes behind this group's sweeps: this group's statistics and
+    // selection then run beside a gather, which leaves them room, and not beside the next sweeps
+    if (gi >= 1 && e == hipSuccess) gather_group(gi - 1);
   }
-  for (int gi = 0; gi < ngroups && e == hipSuccess; ++gi) {
-    const int g0 = gb[gi], ng = gb[gi + 1] - g0;
-    Dims dg = make_dims(c, ng);
-    const size_t heads0 = (size_t)g0 * c.batch * c.n_kv_heads;
-    const char* kg = static_cast<const char*>(k) + heads0 * (size_t)c.ctx_len * c.head_dim * es;
-    const char* vg = static_cast<const char*>(v) + heads0 * (size_t)c.ctx_len * c.head_dim * es;
-    const char* ws_g = static_cast<const char*>(select_ws) + sel_slice * gi;
-    if (overlap) e = hipStreamWaitEvent(st, h->ev_sel[gi], 0);
-    const int bpb = blocks_per_batch(c, ng);
-    if (e == hipSuccess) e = launch_gather(dg, c, 0, ng, kg, vg, kept_idx, kv_off + heads0, kv_len + heads0, k_c, v_c, ws_g, region, bpb, bpb, st);
-  }
+  if (e == hipSuccess) gather_group(ngroups - 1);
   if (overlap && e != hipSuccess) e = join_side(h, st, e);   // an enqueue failed: whatever did reach the side stream is still joined
   for (int l = layer0; l < layer0 + n; ++l) { h->appended[l] = 0; h->gen_base[l] = 0; }
   e = publish_maxlen(h, layer0, n, st, e);

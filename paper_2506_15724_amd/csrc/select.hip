@@ -35,7 +35,10 @@ struct OffsetsArgs {
 
 // One workgroup per batch item; thread f of a trip owns head f of the call's (layer, head)
 // sequence.  Offsets are a prefix sum over that sequence (wave shuffles + one LDS hop).
-constexpr int OFF_THREADS = 1024;
+// The workgroup is kept small (one wave per SIMD, few registers): it has to find room on a compute
+// unit while the score sweeps or a gather of another layer group fill the chip, and a 1024-thread
+// workgroup would wait there until that kernel's grid has drained.
+constexpr int OFF_THREADS = 256;
 constexpr int OFF_MAX_LAYERS = 1024;
 
 __global__ __launch_bounds__(OFF_THREADS) void offsets_kernel(OffsetsArgs a) {
