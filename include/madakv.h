@@ -234,8 +234,8 @@ int32_t madakv_select_gather(madakv_handle* h, int32_t layer0, int32_t n,
  * madakv_score + madakv_allocate + madakv_select_gather for layers [layer0, layer0 + n) in one call,
  * with the same arguments and the same results bit for bit.  A call over four or more layers is
  * cut into four layer groups: the statistics, allocation and selection of a group run on a side
- * stream under the score passes of the following groups, the gathers follow on the caller's
- * stream.  Keep-all configurations (budget >= ctx_len) have nothing to score: use
+ * stream while the caller's stream holds the score passes of the next group and the gather of the
+ * group before.  Keep-all configurations (budget >= ctx_len) have nothing to score: use
  * madakv_select_gather for them.  score_ws / select_ws: at least what madakv_workspace_bytes
  * reports for n layers. */
 int32_t madakv_evict(madakv_handle* h, int32_t layer0, int32_t n,
