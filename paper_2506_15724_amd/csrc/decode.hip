@@ -13,11 +13,15 @@
 // exit at once, and since the chunk index is the slow grid dimension they are dispatched
 // after all the real work.  A second, small kernel merges the partial (max, sum, acc) triples
 // of each head in chunk order.  (Merging inside the first kernel by the last workgroup to
-// arrive was measured twice and lost both times: with device-scope fences, which write back and
+// arrive was measured three times and lost every time: with device-scope fences, which write back and
 // invalidate the whole L2 of an XCD per workgroup, 15x slower; with fence-free agent-scope
 // atomic stores / loads of the partials and one arrival counter per head, 10% slower per call
 // on 128 heads of ~2K rows and 4x slower on 32 heads of ~4K rows: every workgroup then ends in
 // a store acknowledgement plus an atomic round trip, and the last one adds a dependent read.
+// Without any counter: the workgroup of a head's last chunk, which is
+// dispatched after the others, polls their partials, written as self-validating 64-bit words
+// {value, call number}; 30.2 against 29.5 us per call for the same kernel followed by the merge
+// kernel, and the extra state costs the attention loop registers: 142 instead of 122, or spills.
 // Cutting the rows of all heads, laid end to end, into equal stretches per workgroup, so that
 // the launch has a single, perfectly balanced round of workgroups, was measured too: 27.3 us
 // against 26.9 us for the attention part on 128 heads of ~2K rows, the table of head starts

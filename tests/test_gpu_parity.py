@@ -1163,6 +1163,52 @@ def test_widest_shapes():
     _run_and_check_whole_path(wl)
 
 
+def test_decode_long_heads_across_a_chunk_boundary():
+    """Eq. 3-5 on heads of 2300 rows (nine 256-row chunks per head, merged in chunk order) that grow past 2304
+    during the steps: one step appends the row that opens a tenth chunk, which then holds nothing but that row.
+    Outputs against the oracle step by step, lengths and appended rows exactly."""
+    wl = small_workloads()["bf16_mha"].scaled(name="bf16_long_heads", n_layers=2, batch=1, n_q_heads=3, n_kv_heads=3,
+                                               ctx_len=3000, budget=2300, decode_steps=8)
+    NL, B, H, d = wl.n_layers, wl.batch, wl.n_kv_heads, wl.head_dim
+    p = PU.oracle_params(wl)
+    q, k, v, mask, masks = PU.make_inputs(wl, DEV)
+    eng = engine(wl, hcc_mode=0)                                   # every head keeps exactly `budget` rows
+    eng.evict(0, NL, q, k, v, mask)
+    torch.cuda.synchronize()
+    kv_off, kv_len = eng.kv_off.cpu().numpy(), eng.kv_len.cpu().numpy()
+    assert (kv_len == wl.budget).all()
+    kc_all, vc_all = eng.k_c.cpu(), eng.v_c.cpu()
+    k_cache = [[[WL.to_f64(kc_all[kv_off[l, b, h]:kv_off[l, b, h] + kv_len[l, b, h]]) for h in range(H)]
+                for b in range(B)] for l in range(NL)]
+    v_cache = [[[WL.to_f64(vc_all[kv_off[l, b, h]:kv_off[l, b, h] + kv_len[l, b, h]]) for h in range(H)]
+                for b in range(B)] for l in range(NL)]
+    out = torch.full((NL, B, wl.n_q_heads, d), float("nan"), dtype=torch.float32, device=DEV)
+    for step in range(wl.decode_steps):
+        rows = [[WL.decode_inputs(wl, l, b, step, DEV) for b in range(B)] for l in range(NL)]
+        dq = torch.stack([torch.stack([r[0] for r in row]) for row in rows]).contiguous()
+        dk = torch.stack([torch.stack([r[1] for r in row]) for row in rows]).contiguous()
+        dv = torch.stack([torch.stack([r[2] for r in row]) for row in rows]).contiguous()
+        say(f"decode step {step}, head length {wl.budget + step}")
+        for l in range(NL):                                        # one call per layer: 256-row chunks
+            eng.decode_attn(l, 1, dq[l:l + 1], dk[l:l + 1], dv[l:l + 1], out[l:l + 1])
+        torch.cuda.synchronize()
+        out_g = out.cpu().numpy()
+        for l in range(NL):
+            for b in range(B):
+                ref = O.decode_step(WL.to_f64(dq[l, b]), WL.to_f64(dk[l, b]), WL.to_f64(dv[l, b]),
+                                    k_cache[l][b], v_cache[l][b], p.scale)
+                err = np.abs(out_g[l, b] - ref).max()
+                assert err <= PU.DECODE_ATOL, (step, l, b, err)
+        assert (eng.kv_len.cpu().numpy() == kv_len + step + 1).all(), step
+    kc2 = eng.k_c.cpu()
+    for l in range(NL):
+        for b in range(B):
+            for h in range(H):
+                o = kv_off[l, b, h]
+                np.testing.assert_array_equal(WL.to_f64(kc2[o:o + wl.budget + wl.decode_steps]), k_cache[l][b][h])
+    eng.close()
+
+
 @pytest.mark.parametrize("nl", [3, 6, 9])
 def test_fused_eviction_call_matches_the_three_calls(nl):
     """madakv_evict (pipelined over layer groups on two streams) against score + allocate + select_gather."""
