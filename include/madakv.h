@@ -30,12 +30,12 @@
  *     misaligned pointer gives MADAKV_ERR_INVALID_ARG; nothing is enqueued then.
  *   - All work is ordered on the caller's stream (a hipStream_t passed as void*, NULL = the
  *     null stream): it starts after what the stream held before the call and is complete, as far
- *     as the stream is concerned, before anything enqueued after it.  madakv_allocate,
- *     madakv_select_gather and madakv_decode_attn enqueue on that stream only.  madakv_score,
- *     madakv_score_lse and madakv_evict over four or more layers also use the handle's own
- *     stream for the per-head statistics / selection kernels of one layer group while the next
- *     group is scored; that stream forks from and joins the caller's stream through events inside
- *     the call.  No call synchronises the device.
+ *     as the stream is concerned, before anything enqueued after it.  madakv_allocate
+ *     and madakv_decode_attn enqueue on that stream only.  madakv_score, madakv_score_lse,
+ *     madakv_select_gather and madakv_evict over four or more layers also use the handle's own
+ *     stream for the per-head statistics / selection kernels of one layer group while another
+ *     group is scored or gathered; that stream forks from and joins the caller's stream through
+ *     events inside the call.  No call synchronises the device.
  *   - Arguments are validated on the host before anything is enqueued.  Errors
  *     found there leave all outputs untouched.
  *   - The handle belongs to the HIP device that was current in madakv_create; that device must

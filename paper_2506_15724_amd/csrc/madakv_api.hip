@@ -462,11 +462,40 @@ int32_t madakv_select_gather(madakv_handle* h, int32_t layer0, int32_t n,
   if (ws_bytes < select_ws_bytes(dm, c)) return MADAKV_ERR_WORKSPACE_TOO_SMALL;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   const long long region = region_tokens(c);
-  const int bpb = blocks_per_batch(c, n);
-  hipError_t e = launch_offsets(dm, c, layer0, budgets, kv_off, kv_len, h->d_state + c.batch, h->d_maxlen + (size_t)layer0 * c.batch, ws, make_paging(h), bpb, st);
-  // (One group here: selection of all layers, then one gather.  madakv_evict pipelines layer groups.)
-  if (e == hipSuccess) e = launch_select(dm, c, psi_pool, mask, budgets, kv_off, kv_len, kept_idx, st);
-  if (e == hipSuccess) e = launch_gather(dm, c, 0, n, k, v, kept_idx, kv_off, kv_len, k_c, v_c, ws, region, bpb, bpb, st, false);
+  // Layer groups as in madakv_evict when the workspace has room for a slice per group (what
+  // madakv_workspace_bytes reports has): segment layout and selection of a group on the side stream beside
+  // the gather of the group before, which leaves them room.  One group otherwise.
+  int gb[MAX_GROUPS + 1];
+  int ngroups = layer_groups(n, gb);
+  const size_t sel_slice = (select_ws_bytes(make_dims(c, largest_group(n)), c) + 255) / 256 * 256;
+  if (ngroups > 1 && ws_bytes < sel_slice * ngroups) { ngroups = 1; gb[0] = 0; gb[1] = n; }
+  const bool overlap = ngroups > 1;
+  const size_t es = c.dtype == MADAKV_BF16 ? 2 : 4;
+  const size_t M = (size_t)c.n_modalities;
+  hipError_t e = hipSuccess;
+  if (overlap) {
+    e = hipEventRecord(h->ev_fork, st);
+    if (e == hipSuccess) e = hipStreamWaitEvent(h->side, h->ev_fork, 0);
+  }
+  hipStream_t ss = overlap ? h->side : st;
+  for (int gi = 0; gi < ngroups && e == hipSuccess; ++gi) {
+    const int g0 = gb[gi], ng = gb[gi + 1] - g0;
+    Dims dg = make_dims(c, ng);
+    const size_t heads0 = (size_t)g0 * c.batch * c.n_kv_heads;
+    char* ws_g = static_cast<char*>(ws) + (overlap ? sel_slice * gi : 0);
+    const float* pool_g = psi_pool ? psi_pool + heads0 * (size_t)(c.ctx_len - c.window) : nullptr;
+    const int32_t* bud_g = budgets ? budgets + heads0 * M : nullptr;
+    const int bpb = blocks_per_batch(c, ng);
+    e = launch_offsets(dg, c, layer0 + g0, bud_g, kv_off + heads0, kv_len + heads0, h->d_state + c.batch,
+                       h->d_maxlen + (size_t)(layer0 + g0) * c.batch, ws_g, make_paging(h), bpb, ss);
+    if (e == hipSuccess) e = launch_select(dg, c, pool_g, mask, bud_g, kv_off + heads0, kv_len + heads0, kept_idx, ss);
+    if (overlap && e == hipSuccess) e = hipEventRecord(h->ev_sel[gi], h->side);
+    if (overlap && e == hipSuccess) e = hipStreamWaitEvent(st, h->ev_sel[gi], 0);
+    const char* kg = static_cast<const char*>(k) + heads0 * (size_t)c.ctx_len * c.head_dim * es;
+    const char* vg = static_cast<const char*>(v) + heads0 * (size_t)c.ctx_len * c.head_dim * es;
+    if (e == hipSuccess) e = launch_gather(dg, c, 0, ng, kg, vg, kept_idx, kv_off + heads0, kv_len + heads0, k_c, v_c, ws_g, region, bpb, bpb, st, overlap);
+  }
+  if (overlap && e != hipSuccess) e = join_side(h, st, e);   // an enqueue failed: whatever did reach the side stream is still joined
   for (int l = layer0; l < layer0 + n; ++l) { h->appended[l] = 0; h->gen_base[l] = 0; }
   e = publish_maxlen(h, layer0, n, st, e);
   return hip_fail(h, e);
