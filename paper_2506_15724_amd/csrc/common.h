@@ -49,8 +49,15 @@ size_t decode_ws_bytes_for(const Dims& dm, const madakv_config& c, int longest_r
 // Each launcher validates nothing: shapes were checked by the ABI layer.
 hipError_t launch_score(const Dims& dm, const madakv_config& c, const void* q_win, const void* k, const float* row_lse,
                         float* psi, void* ws, hipStream_t st);
+// Long heads on few heads: statistics and selection give every 16384-candidate chunk of a head a workgroup of its own
+// and go through a buffer of split_buffer_bytes (owned by the handle) in several launches; split_chunks = chunks per
+// head then, 0 otherwise.
+int split_chunks(const Dims& dm);
+size_t split_buffer_bytes(int heads, int M, int nchunks);
+void launch_split_zero(uint32_t* p, long long words, hipStream_t st);   // a fill kernel (no memset node in captured streams)
 hipError_t launch_stats(const Dims& dm, const madakv_config& c, const float* psi, const uint8_t* mask,
-                        float* psi_pool, void* stats, int32_t* n_mod, int layer0, hipStream_t st);
+                        float* psi_pool, void* stats, int32_t* n_mod, int layer0, hipStream_t st,
+                        void* split_buf = nullptr, size_t split_bytes = 0);
 hipError_t launch_allocate(const Dims& dm, const madakv_config& c, int layer0, const void* stats,
                            const int32_t* n_mod, int32_t* budgets, long long* pool_state, hipStream_t st);
 hipError_t launch_offsets(const Dims& dm, const madakv_config& c, int layer0, const int32_t* budgets,
@@ -58,7 +65,8 @@ hipError_t launch_offsets(const Dims& dm, const madakv_config& c, int layer0, co
                           const Paging& pg, int blocks_per_batch, hipStream_t st);
 hipError_t launch_select(const Dims& dm, const madakv_config& c, const float* psi_pool, const uint8_t* mask,
                          const int32_t* budgets, const int64_t* kv_off, const int32_t* kv_len, int32_t* kept_idx,
-                         hipStream_t st, const int32_t* seg_len = nullptr, const uint8_t* rowmod = nullptr);
+                         hipStream_t st, const int32_t* seg_len = nullptr, const uint8_t* rowmod = nullptr,
+                         void* split_buf = nullptr, size_t split_bytes = 0);
 // re-eviction during generation (reevict.hip, and the one-sweep scoring kernel on ragged segments)
 bool score_ragged_supported(const Dims& dm, const madakv_config& c, int longest_rows);
 size_t score_ragged_ws_bytes(const Dims& dm, const madakv_config& c, int longest_rows, long long cache_rows);

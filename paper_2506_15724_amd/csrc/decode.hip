@@ -720,7 +720,10 @@ static hipError_t launch_decode_t(const Dims& dm, DecodeArgs& a, hipStream_t st)
     if (a.max_chunks > 1) hipLaunchKernelGGL((decode_merge_kernel<T>), dim3(dm.heads), dim3(dm.G * dm.d), 0, st, a);
     return hipGetLastError();
   }
-  if (dm.G == 1) hipLaunchKernelGGL((decode_attn_kernel<T, CT, LPR, 1, 8, 4>), grid, block, 0, st, a);
+  // (8-bit cache: a lane holds 16 elements per 16-byte load; four rows in flight per lane keep the kernel at 3 waves
+  // per SIMD, eight would need 230 registers: 21.2 against 23.3 us per layer call)
+  if (dm.G == 1 && sizeof(CT) == 1) hipLaunchKernelGGL((decode_attn_kernel<T, CT, LPR, 1, 4, 4>), grid, block, 0, st, a);
+  else if (dm.G == 1) hipLaunchKernelGGL((decode_attn_kernel<T, CT, LPR, 1, 8, 4>), grid, block, 0, st, a);
   else if (dm.G == 2) hipLaunchKernelGGL((decode_attn_kernel<T, CT, LPR, 2, 4, 4>), grid, block, 0, st, a);
   else if (dm.G <= 4) hipLaunchKernelGGL((decode_attn_kernel<T, CT, LPR, 4, 4, 4>), grid, block, 0, st, a);
   else hipLaunchKernelGGL((decode_attn_kernel<T, CT, LPR, 8, 2, 4>), grid, block, 0, st, a);

@@ -29,6 +29,7 @@ struct madakv_handle {
   int32_t last_hip_error;
   long long* d_state;              // [3 * B]: HCC pool, cache cursor, pages taken for appended rows (paged cache), per batch item
   int32_t* d_page_tbl;             // paged cache: [n_layers * B * H][entries] page table (null otherwise)
+  void* d_split; size_t split_bytes;   // long contexts: buffer of the chunk-parallel statistics / selection (null otherwise)
   std::vector<int32_t> appended;   // decode rows appended since the last (re-)eviction, per layer
   std::vector<int32_t> gen_base;   // tokens generated before that, per layer (their original positions are ctx_len + 0, 1, ...)
   // Longest head of each layer after eviction: written by the device, copied to pinned host
@@ -282,6 +283,7 @@ int32_t madakv_create(const madakv_config* cfg, madakv_handle** out) {
   h->appended.assign(cfg->n_layers, 0);
   h->gen_base.assign(cfg->n_layers, 0);
   h->static_scratch = nullptr; h->d_page_tbl = nullptr;
+  h->d_split = nullptr; h->split_bytes = 0;
   hipError_t e = hipGetDevice(&h->device);
   if (e == hipSuccess) e = static_scratch_on_current_device(h->device, &h->static_scratch);
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&h->d_state), sizeof(long long) * 3 * cfg->batch);
@@ -290,6 +292,16 @@ int32_t madakv_create(const madakv_config* cfg, madakv_handle** out) {
     const size_t tb = sizeof(int32_t) * (size_t)cfg->n_layers * cfg->batch * cfg->n_kv_heads * page_table_entries(*cfg);
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&h->d_page_tbl), tb);
     if (e == hipSuccess) e = hipMemset(h->d_page_tbl, 0, tb);
+  }
+  {
+    // contexts of more than one 16384-candidate chunk: room for the largest launch that would use the chunk-parallel path
+    Dims d1 = make_dims(*cfg, 1);
+    if (d1.nc > 16384) {
+      const int nchunks = (d1.nc + 16383) / 16384;
+      const int heads = std::min(cfg->n_layers * cfg->batch * cfg->n_kv_heads, 128);
+      h->split_bytes = split_buffer_bytes(heads, cfg->n_modalities, nchunks);
+      if (e == hipSuccess) e = hipMalloc(&h->d_split, h->split_bytes);
+    }
   }
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&h->d_maxlen), sizeof(int32_t) * cfg->n_layers * cfg->batch);
   if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&h->h_maxlen), sizeof(int32_t) * cfg->n_layers * cfg->batch, hipHostMallocDefault);
@@ -303,6 +315,7 @@ int32_t madakv_create(const madakv_config* cfg, madakv_handle** out) {
   if (e != hipSuccess) {
     if (h->d_maxlen) (void)hipFree(h->d_maxlen);
     if (h->d_page_tbl) (void)hipFree(h->d_page_tbl);
+    if (h->d_split) (void)hipFree(h->d_split);
     if (h->h_maxlen) (void)hipHostFree(h->h_maxlen);
     if (h->maxlen_event) (void)hipEventDestroy(h->maxlen_event);
     destroy_side(h);
@@ -319,6 +332,7 @@ int32_t madakv_destroy(madakv_handle* h) {
   hipError_t e = hipFree(h->d_state);
   (void)hipFree(h->d_maxlen);
   if (h->d_page_tbl) (void)hipFree(h->d_page_tbl);
+  if (h->d_split) (void)hipFree(h->d_split);
   (void)hipHostFree(h->h_maxlen);
   (void)hipEventDestroy(h->maxlen_event);
   destroy_side(h);
@@ -398,7 +412,7 @@ static int32_t score_impl(madakv_handle* h, int32_t layer0, int32_t n,
     }
     if (e == hipSuccess)
       e = launch_stats(dg, c, psi_g, mask, pool_g, static_cast<char*>(stats) + lb * c.n_kv_heads * 8 * (size_t)c.n_modalities,
-                       g0 == 0 ? n_mod : nullptr, layer0 + g0, ss);
+                       g0 == 0 ? n_mod : nullptr, layer0 + g0, ss, h->d_split, h->split_bytes);
   }
   if (overlap) e = join_side(h, st, e);
   return hip_fail(h, e);
@@ -488,7 +502,7 @@ int32_t madakv_select_gather(madakv_handle* h, int32_t layer0, int32_t n,
     const int bpb = blocks_per_batch(c, ng);
     e = launch_offsets(dg, c, layer0 + g0, bud_g, kv_off + heads0, kv_len + heads0, h->d_state + c.batch,
                        h->d_maxlen + (size_t)(layer0 + g0) * c.batch, ws_g, make_paging(h), bpb, ss);
-    if (e == hipSuccess) e = launch_select(dg, c, pool_g, mask, bud_g, kv_off + heads0, kv_len + heads0, kept_idx, ss);
+    if (e == hipSuccess) e = launch_select(dg, c, pool_g, mask, bud_g, kv_off + heads0, kv_len + heads0, kept_idx, ss, nullptr, nullptr, h->d_split, h->split_bytes);
     if (overlap && e == hipSuccess) e = hipEventRecord(h->ev_sel[gi], h->side);
     if (overlap && e == hipSuccess) e = hipStreamWaitEvent(st, h->ev_sel[gi], 0);
     const char* kg = static_cast<const char*>(k) + heads0 * (size_t)c.ctx_len * c.head_dim * es;
@@ -559,11 +573,11 @@ int32_t madakv_evict(madakv_handle* h, int32_t layer0, int32_t n,
       if (e == hipSuccess) e = hipStreamWaitEvent(h->side, h->ev_grp[gi], 0);
       ss = h->side;
     }
-    if (e == hipSuccess) e = launch_stats(dg, c, psi_g, mask, pool_g, stats_g, g0 == 0 ? n_mod : nullptr, layer0 + g0, ss);
+    if (e == hipSuccess) e = launch_stats(dg, c, psi_g, mask, pool_g, stats_g, g0 == 0 ? n_mod : nullptr, layer0 + g0, ss, h->d_split, h->split_bytes);
     if (e == hipSuccess) e = launch_allocate(dg, c, layer0 + g0, stats_g, n_mod, bud_g, h->d_state, ss);
     if (e == hipSuccess) e = launch_offsets(dg, c, layer0 + g0, bud_g, kv_off + heads0, kv_len + heads0, h->d_state + c.batch,
                                             h->d_maxlen + (size_t)(layer0 + g0) * c.batch, ws_g, make_paging(h), blocks_per_batch(c, ng), ss);
-    if (e == hipSuccess) e = launch_select(dg, c, pool_g, mask, bud_g, kv_off + heads0, kv_len + heads0, kept_idx, ss);
+    if (e == hipSuccess) e = launch_select(dg, c, pool_g, mask, bud_g, kv_off + heads0, kv_len + heads0, kept_idx, ss, nullptr, nullptr, h->d_split, h->split_bytes);
     if (overlap && e == hipSuccess) e = hipEventRecord(h->ev_sel[gi], h->side);
     // the gather of the group before goes behind this group's sweeps: this group's statistics and
     // selection then run beside a gather, which leaves them room, and not beside the next sweeps

@@ -24,6 +24,10 @@ constexpr int SEL_BINS = 2048;
 
 constexpr int SEL_EPT = 32;                      // consecutive candidates a thread owns per chunk
 
+// what the walk of one level hands on, per head and modality, and what a chunk reports (phases 1-4 of select_kernel)
+struct SelCarry { uint32_t prefix, need, done, pad; };
+struct SelChunk { uint32_t gt, pad; unsigned long long eq; };   // kept for sure; threshold-valued ones, 16 bits per modality
+
 struct OffsetsArgs {
   const int32_t* budgets; int64_t* kv_off; int32_t* kv_len; long long* cursor; int32_t* blk2head; long long* call_range; int32_t* layer_maxlen;
   int n, B, H, L, W, layer0, max_new, keep_all, blocks_per_batch, M;
@@ -124,6 +128,15 @@ struct SelectArgs {
   const float* psi_pool; const uint8_t* mask; const int32_t* budgets; const int64_t* kv_off; const int32_t* kv_len; int32_t* kept_idx;
   int B, H, L, W, nc, mpa_mode, keep_all, select_mode, sink_tokens, M;
   const int32_t* seg_len; const uint8_t* rowmod;   // ragged candidates (re-eviction), else null
+  // Long heads on few heads (see launch_select): the chunks of a head go to workgroups of their own.
+  // phase 0 = the whole head in one workgroup; 1 = count histogram of one chunk at `level`, added to the
+  // head's histogram in memory; 2 = the walk over that histogram (one workgroup per head); 3 = a chunk's
+  // numbers of kept and of threshold-valued candidates; 4 = a chunk's kept positions written behind those
+  // of the chunks before it.
+  int phase, level, heads, nchunks;
+  uint32_t* gcnt;                 // [3 levels][heads][M][SEL_BINS]
+  SelCarry* carry;                // [heads][4]
+  SelChunk* chunkinfo;            // [heads][nchunks]
 };
 
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
@@ -228,7 +241,9 @@ __global__ __launch_bounds__(SEL_THREADS) __attribute__((amdgpu_waves_per_eu(MM 
   const int M = a.M;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int head = blockIdx.x;
+  const int phase = a.phase;
+  const bool per_chunk = phase == 1 || phase >= 3;             // grid (chunks, heads)
+  const int head = per_chunk ? blockIdx.y : blockIdx.x;
   const int b = (head / a.H) % a.B;
   // candidates of this head: the L - W prompt positions before the window with the batch item's modality
   // mask, or (ragged: the rows of a reduced cache, re-eviction) the rows before the head's last W with a
@@ -262,13 +277,22 @@ __global__ __launch_bounds__(SEL_THREADS) __attribute__((amdgpu_waves_per_eu(MM 
   const int widths[3] = {11, 11, 10};
   constexpr int CH = SEL_THREADS * SEL_EPT;      // candidates per chunk
   const int nchunks = (nc + CH - 1) / CH;
-  const bool single = nchunks == 1;              // the usual case: everything stays in registers
+  const int c_first = per_chunk ? blockIdx.x : 0, c_end = per_chunk ? blockIdx.x + 1 : nchunks;
+  const bool single = c_end - c_first == 1;      // the usual case: everything stays in registers
+  const int lv_first = phase == 0 ? 0 : (phase <= 2 ? a.level : 3), lv_end = phase == 0 ? 3 : (phase <= 2 ? a.level + 1 : 3);
+  uint32_t* gcnt = phase ? a.gcnt + ((size_t)(phase <= 2 ? a.level : 0) * a.heads + head) * (size_t)M * SEL_BINS : nullptr;
+  SelCarry* carry = phase ? a.carry + (size_t)head * 4 : nullptr;
+  if (phase != 0 && (phase >= 3 || a.level > 0) && tid < M) {   // what the walks before left
+    const SelCarry cy = carry[tid];
+    s_prefix[tid] = cy.prefix; s_need[tid] = cy.need; s_done[tid] = cy.done;
+  }
+  if (phase >= 3) __syncthreads();
 
   uint32_t key[SEL_EPT];
   unsigned long long mbits = 0ULL;
-  if (single) load_owned(sc, mask, tid * SEL_EPT, nc, a.mpa_mode, M, key, mbits);
+  if (single && phase != 2) load_owned(sc, mask, c_first * CH + tid * SEL_EPT, nc, a.mpa_mode, M, key, mbits);
 
-  for (int level = 0; level < 3; ++level) {
+  for (int level = lv_first; level < lv_end; ++level) {
     for (int e = tid; e < M * SEL_BINS; e += SEL_THREADS) (&cnt[0][0])[e] = 0;
     __syncthreads();
     const int sh = shifts[level], wd = widths[level];
@@ -279,7 +303,10 @@ __global__ __launch_bounds__(SEL_THREADS) __attribute__((amdgpu_waves_per_eu(MM 
       pfx[m] = (level > 0 && m < M) ? s_prefix[m] : 0u;
       dn[m] = (level > 0 && m < M) ? s_done[m] != 0 : false;
     }
-    for (int c = 0; c < nchunks; ++c) {
+    if (phase == 2) {                              // the head's histogram of this level, gathered by the chunks' workgroups
+      for (int e = tid; e < M * SEL_BINS; e += SEL_THREADS) (&cnt[0][0])[e] = gcnt[e];
+    }
+    for (int c = (phase == 2 ? c_end : c_first); c < c_end; ++c) {
       const int i0 = c * CH + tid * SEL_EPT;
       if (!single) load_owned(sc, mask, i0, nc, a.mpa_mode, M, key, mbits);
       const int nvalid = min(max(nc - i0, 0), SEL_EPT);
@@ -292,6 +319,13 @@ __global__ __launch_bounds__(SEL_THREADS) __attribute__((amdgpu_waves_per_eu(MM 
       }
     }
     __syncthreads();
+    if (phase == 1) {                              // add the chunk's bins to the head's and leave
+      for (int e = tid; e < M * SEL_BINS; e += SEL_THREADS) {
+        const uint32_t x = (&cnt[0][0])[e];
+        if (x) atomicAdd(&gcnt[e], x);
+      }
+      return;
+    }
     if (wave < M) {
       const int m = wave;
       const int nb = 1 << wd;
@@ -334,6 +368,10 @@ __global__ __launch_bounds__(SEL_THREADS) __attribute__((amdgpu_waves_per_eu(MM 
     }
     __syncthreads();
   }
+  if (phase == 2) {                                // hand over to the next level, or to the chunks' compaction
+    if (tid < M) { SelCarry cy; cy.prefix = s_prefix[tid]; cy.need = s_need[tid]; cy.done = s_done[tid]; cy.pad = 0; carry[tid] = cy; }
+    return;
+  }
   // tau_m = s_prefix (full key); take every key > tau_m and the first s_need[m] keys == tau_m.
   uint32_t tau[MM], ties[MM];
 #pragma unroll
@@ -347,7 +385,19 @@ __global__ __launch_bounds__(SEL_THREADS) __attribute__((amdgpu_waves_per_eu(MM 
 #pragma unroll
   for (int m = 0; m < MM; ++m) run_eq[m] = 0;
   uint32_t run_out = 0;
-  for (int c = 0; c < nchunks; ++c) {
+  if (phase == 4) {
+    // what the chunks in front of this one keep: their sure ones, and of the threshold-valued ones as many as are needed
+    const SelChunk* ci = a.chunkinfo + (size_t)head * a.nchunks;
+    for (int c = 0; c < c_first; ++c) {
+      const SelChunk x = ci[c];
+      run_out += x.gt;
+#pragma unroll
+      for (int m = 0; m < MM; ++m) run_eq[m] += (uint32_t)((x.eq >> (16 * m)) & 0xffffULL);
+    }
+#pragma unroll
+    for (int m = 0; m < MM; ++m) run_out += min(run_eq[m], ties[m]);
+  }
+  for (int c = c_first; c < c_end; ++c) {
     const int i0 = c * CH + tid * SEL_EPT;
     if (!single) load_owned(sc, mask, i0, nc, a.mpa_mode, M, key, mbits);
     const int nvalid = min(max(nc - i0, 0), SEL_EPT);
@@ -367,6 +417,12 @@ __global__ __launch_bounds__(SEL_THREADS) __attribute__((amdgpu_waves_per_eu(MM 
     }
     unsigned long long eqtot;
     const unsigned long long eqbefore = block_excl_scan64(eqcnt, wave_tot64, eqtot);
+    if (phase == 3) {                              // report and leave
+      uint32_t gttot;
+      (void)block_excl_scan((uint32_t)__popcll(gtbits), wave_tot, gttot);
+      if (tid == 0) { SelChunk x; x.gt = gttot; x.pad = 0; x.eq = eqtot; a.chunkinfo[(size_t)head * a.nchunks + c] = x; }
+      return;
+    }
     uint32_t rank[MM];
 #pragma unroll
     for (int m = 0; m < MM; ++m) rank[m] = run_eq[m] + (uint32_t)((eqbefore >> (16 * m)) & 0xffffULL);
@@ -393,6 +449,7 @@ __global__ __launch_bounds__(SEL_THREADS) __attribute__((amdgpu_waves_per_eu(MM 
     for (int m = 0; m < MM; ++m) run_eq[m] += (uint32_t)((eqtot >> (16 * m)) & 0xffffULL);
     run_out += ktot;
   }
+  if (phase == 4 && c_end != nchunks) return;      // the window positions follow the last chunk's
   for (int r = tid; r < a.W; r += SEL_THREADS) out[run_out + r] = nc + r;
 }
 
@@ -422,13 +479,34 @@ hipError_t launch_offsets(const Dims& dm, const madakv_config& c, int layer0, co
 
 hipError_t launch_select(const Dims& dm, const madakv_config& c, const float* psi_pool, const uint8_t* mask,
                          const int32_t* budgets, const int64_t* kv_off, const int32_t* kv_len, int32_t* kept_idx,
-                         hipStream_t st, const int32_t* seg_len, const uint8_t* rowmod) {
+                         hipStream_t st, const int32_t* seg_len, const uint8_t* rowmod, void* split_buf, size_t split_bytes) {
   SelectArgs a;
   a.seg_len = seg_len; a.rowmod = rowmod;
   a.psi_pool = psi_pool; a.mask = mask; a.budgets = budgets; a.kv_off = kv_off; a.kv_len = kv_len; a.kept_idx = kept_idx;
   a.B = dm.B; a.H = dm.H; a.L = dm.L; a.W = dm.W; a.nc = dm.nc; a.mpa_mode = c.mpa_mode;
   a.keep_all = (c.budget >= c.ctx_len && !seg_len) ? 1 : 0;
   a.select_mode = c.select_mode; a.sink_tokens = c.sink_tokens; a.M = c.n_modalities;
+  a.phase = 0; a.level = 0; a.heads = dm.heads; a.nchunks = 0; a.gcnt = nullptr; a.carry = nullptr; a.chunkinfo = nullptr;
+  const int nchunks = split_chunks(dm);
+  if (nchunks && !seg_len && !a.keep_all && a.select_mode != 1 && split_buf &&
+      split_bytes >= split_buffer_bytes(dm.heads, a.M, nchunks)) {
+    // per level: the chunks' workgroups add their count histograms into the head's (in memory), one workgroup per head
+    // walks it; then every chunk reports what it keeps and writes it behind the chunks in front of it
+    const size_t hist = (size_t)3 * dm.heads * a.M * SEL_BINS;
+    a.gcnt = reinterpret_cast<uint32_t*>(split_buf);
+    a.carry = reinterpret_cast<SelCarry*>(a.gcnt + hist);
+    a.chunkinfo = reinterpret_cast<SelChunk*>(a.carry + (size_t)dm.heads * 4);
+    a.nchunks = nchunks;
+    launch_split_zero(a.gcnt, (long long)hist, st);
+    for (int step = 0; step < 8; ++step) {
+      a.phase = step < 6 ? 1 + (step & 1) : step - 3;          // 1, 2, 1, 2, 1, 2, 3, 4
+      a.level = step < 6 ? step / 2 : 0;
+      const dim3 grid = a.phase == 2 ? dim3(dm.heads) : dim3(nchunks, dm.heads);
+      if (a.M == 2) hipLaunchKernelGGL((select_kernel<2>), grid, dim3(SEL_THREADS), 0, st, a);
+      else hipLaunchKernelGGL((select_kernel<4>), grid, dim3(SEL_THREADS), 0, st, a);
+    }
+    return hipGetLastError();
+  }
   if (a.M == 2) hipLaunchKernelGGL((select_kernel<2>), dim3(dm.heads), dim3(SEL_THREADS), 0, st, a);
   else hipLaunchKernelGGL((select_kernel<4>), dim3(dm.heads), dim3(SEL_THREADS), 0, st, a);
   return hipGetLastError();

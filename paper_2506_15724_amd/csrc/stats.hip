@@ -22,11 +22,24 @@ constexpr int STATS_EPT = 32;                    // consecutive candidates a thr
 constexpr int BINS = 2048;
 constexpr float FX_SCALE = 17592186044416.0f;    // 2^44
 constexpr float PSI_MAX = 256.0f;                // G * W <= 256 bounds any column sum
+constexpr int SPLIT_MAX_HEADS = 128;             // most heads of a launch whose chunks get workgroups of their own
+
+// what the walk of one level hands to the next, per head and modality (phases 1 and 2)
+struct StatsCarry {
+  unsigned long long sum_gt, w, target, binsum, wwin;
+  uint32_t prefix, cnt_gt, n, done, bincnt, pad;
+};
 
 struct StatsArgs {
   const float* psi; const uint8_t* mask; float* psi_pool; void* stats; int32_t* n_mod;
   int B, H, L, W, nc, pool_r, pool_mode, share_mode, M;
   double theta;
+  // Long heads on few heads (see launch_stats): the chunks of a head go to workgroups of their own.
+  // phase 0 = the whole head in one workgroup, all levels; 1 = histogram of one chunk at `level`, added
+  // to the head's histogram in memory; 2 = the walk over that histogram (one workgroup per head).
+  int phase, level, heads;
+  unsigned long long* gsum; uint32_t* gcnt;      // [3 levels][heads][M][BINS]
+  StatsCarry* carry;                             // [heads][4]
 };
 
 __device__ __forceinline__ unsigned long long to_fx(float v) {
@@ -158,7 +171,8 @@ __global__ __launch_bounds__(STATS_THREADS) __attribute__((amdgpu_waves_per_eu(4
   const int M = a.M;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int head = blockIdx.x;
+  const int phase = a.phase;
+  const int head = phase == 1 ? blockIdx.y : blockIdx.x;      // phase 1: grid (chunks, heads)
   const int b = (head / a.H) % a.B;
   const float* psi = a.psi + (long long)head * a.L;
   const uint8_t* mask = a.mask + (long long)b * a.L;
@@ -168,11 +182,22 @@ __global__ __launch_bounds__(STATS_THREADS) __attribute__((amdgpu_waves_per_eu(4
   const int widths[3] = {11, 11, 9};
   constexpr int CH = STATS_THREADS * STATS_EPT;
   const int nchunks = (a.nc + CH - 1) / CH;
-  const bool single = nchunks == 1;
+  const int c_first = phase == 1 ? blockIdx.x : 0, c_end = phase == 1 ? blockIdx.x + 1 : nchunks;
+  const bool single = c_end - c_first == 1;      // the workgroup's candidates stay in registers through its levels
+  const int lv_first = phase == 0 ? 0 : a.level, lv_end = phase == 0 ? 3 : a.level + 1;
+  const size_t hist_words = (size_t)M * BINS;
+  unsigned long long* gsum = phase ? a.gsum + ((size_t)a.level * a.heads + head) * hist_words : nullptr;
+  uint32_t* gcnt = phase ? a.gcnt + ((size_t)a.level * a.heads + head) * hist_words : nullptr;
+  StatsCarry* carry = phase ? a.carry + (size_t)head * 4 : nullptr;
 
   if (tid < MM) s_wwin[tid] = 0ULL;
+  if (phase != 0 && a.level > 0 && tid < M) {    // what the walk of the level above left
+    const StatsCarry cy = carry[tid];
+    s_prefix[tid] = cy.prefix; s_cnt_gt[tid] = cy.cnt_gt; s_n[tid] = cy.n; s_done[tid] = cy.done; s_bincnt[tid] = cy.bincnt;
+    s_sum_gt[tid] = cy.sum_gt; s_w[tid] = cy.w; s_target[tid] = cy.target; s_binsum[tid] = cy.binsum; s_wwin[tid] = cy.wwin;
+  }
   __syncthreads();
-  if (a.share_mode && tid < a.W) {
+  if (a.share_mode && tid < a.W && (phase == 0 || (phase == 2 && a.level == 0))) {
     // the other reading of Eq. 6: the proxy columns count towards the masses as well
     const int i = a.nc + tid;
     atomicAdd(&s_wwin[min((int)mask[i], M - 1)], to_fx(psi[i]));
@@ -181,9 +206,9 @@ __global__ __launch_bounds__(STATS_THREADS) __attribute__((amdgpu_waves_per_eu(4
   unsigned long long mbits = 0ULL;
   const bool reg_pool = a.pool_r <= POOL_R_REG;
   float edge[STATS_GROUPS][POOL_R_REG];
-  if (single) load_owned(psi, mask, 0, tid, a.nc, M, reg_pool, v, mbits, edge);
+  if (single && phase != 2) load_owned(psi, mask, c_first * CH, tid, a.nc, M, reg_pool && lv_first == 0, v, mbits, edge);
 
-  for (int level = 0; level < 3; ++level) {
+  for (int level = lv_first; level < lv_end; ++level) {
     for (int e = tid; e < M * BINS; e += STATS_THREADS) { cnt[e] = 0; sum[e] = 0ULL; }
     __syncthreads();
     const int sh = shifts[level], wd = widths[level];
@@ -191,7 +216,10 @@ __global__ __launch_bounds__(STATS_THREADS) __attribute__((amdgpu_waves_per_eu(4
     uint32_t pfx[MM]; bool dn[MM];
 #pragma unroll
     for (int m = 0; m < MM; ++m) { pfx[m] = (level > 0 && m < M) ? s_prefix[m] : 0u; dn[m] = (level > 0 && m < M) ? s_done[m] != 0 : false; }
-    for (int c = 0; c < nchunks; ++c) {
+    if (phase == 2) {                              // the head's histogram of this level, gathered by the chunks' workgroups
+      for (int e = tid; e < M * BINS; e += STATS_THREADS) { cnt[e] = gcnt[e]; sum[e] = gsum[e]; }
+    }
+    for (int c = (phase == 2 ? c_end : c_first); c < c_end; ++c) {
       const int cbase = c * CH;
       if (!single) load_owned(psi, mask, cbase, tid, a.nc, M, level == 0 && reg_pool, v, mbits, edge);
       if (level == 0) {
@@ -234,6 +262,11 @@ __global__ __launch_bounds__(STATS_THREADS) __attribute__((amdgpu_waves_per_eu(4
       }
     }
     __syncthreads();
+    if (phase == 1) {                              // add the chunk's bins to the head's and leave
+      for (int e = tid; e < M * BINS; e += STATS_THREADS)
+        if (cnt[e]) { atomicAdd(&gcnt[e], cnt[e]); atomicAdd(&gsum[e], sum[e]); }
+      return;
+    }
     // wave m walks the histogram of modality m from the top bin down
     if (wave < M) {
       const int m = wave;
@@ -297,6 +330,15 @@ __global__ __launch_bounds__(STATS_THREADS) __attribute__((amdgpu_waves_per_eu(4
     __syncthreads();
   }
 
+  if (phase == 2 && a.level < 2) {               // hand over to the next level
+    if (tid < M) {
+      StatsCarry cy;
+      cy.prefix = s_prefix[tid]; cy.cnt_gt = s_cnt_gt[tid]; cy.n = s_n[tid]; cy.done = s_done[tid]; cy.bincnt = s_bincnt[tid]; cy.pad = 0;
+      cy.sum_gt = s_sum_gt[tid]; cy.w = s_w[tid]; cy.target = s_target[tid]; cy.binsum = s_binsum[tid]; cy.wwin = s_wwin[tid];
+      carry[tid] = cy;
+    }
+    return;
+  }
   if (tid < M) {
     const int m = tid;
     int32_t k = 0;
@@ -319,23 +361,66 @@ __global__ __launch_bounds__(STATS_THREADS) __attribute__((amdgpu_waves_per_eu(4
   }
 }
 
+__global__ __launch_bounds__(256) void split_zero_kernel(uint32_t* p, long long n) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+
+void launch_split_zero(uint32_t* p, long long words, hipStream_t st) {
+  hipLaunchKernelGGL(split_zero_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st, p, words);
+}
+
+// Chunks per head that go to workgroups of their own, or 0: heads of more than one 16384-candidate chunk,
+// so few of them that one workgroup per head would leave most of the chip idle.
+int split_chunks(const Dims& dm) {
+  const int nchunks = (dm.nc + STATS_THREADS * STATS_EPT - 1) / (STATS_THREADS * STATS_EPT);
+  return (nchunks >= 2 && dm.heads <= SPLIT_MAX_HEADS) ? nchunks : 0;
+}
+size_t split_buffer_bytes(int heads, int M, int nchunks) {
+  const size_t hist = (size_t)3 * heads * M * BINS;
+  return hist * (sizeof(unsigned long long) + sizeof(uint32_t)) + (size_t)heads * 4 * sizeof(StatsCarry) + (size_t)heads * nchunks * 16 + 256;
+}
+
 hipError_t launch_stats(const Dims& dm, const madakv_config& c, const float* psi, const uint8_t* mask,
-                        float* psi_pool, void* stats, int32_t* n_mod, int layer0, hipStream_t st) {
+                        float* psi_pool, void* stats, int32_t* n_mod, int layer0, hipStream_t st,
+                        void* split_buf, size_t split_bytes) {
   StatsArgs a;
   a.psi = psi; a.mask = mask; a.psi_pool = psi_pool; a.stats = stats; a.n_mod = n_mod;
   a.B = dm.B; a.H = dm.H; a.L = dm.L; a.W = dm.W; a.nc = dm.nc; a.pool_r = (c.pool_k - 1) / 2;
   (void)layer0;
   a.pool_mode = c.pool_mode; a.share_mode = c.share_mode; a.theta = (double)c.theta;
   a.M = c.n_modalities;
+  a.phase = 0; a.level = 0; a.heads = dm.heads; a.gsum = nullptr; a.gcnt = nullptr; a.carry = nullptr;
   const size_t lds = (size_t)a.M * BINS * (sizeof(unsigned long long) + sizeof(uint32_t));
   if (a.M == 2) {
     if (lds > 48 * 1024)
       (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&stats_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    hipLaunchKernelGGL((stats_kernel<2>), dim3(dm.heads), dim3(STATS_THREADS), lds, st, a);
   } else {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&stats_kernel<4>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    hipLaunchKernelGGL((stats_kernel<4>), dim3(dm.heads), dim3(STATS_THREADS), lds, st, a);
   }
+  const int nchunks = split_chunks(dm);
+  if (nchunks && split_buf && split_bytes >= split_buffer_bytes(dm.heads, a.M, nchunks)) {
+    // per level: the chunks' workgroups add their histograms into the head's (in memory), then one workgroup per
+    // head walks it; the kernel boundary is the synchronisation
+    const size_t hist = (size_t)3 * dm.heads * a.M * BINS;
+    a.gsum = reinterpret_cast<unsigned long long*>(split_buf);
+    a.gcnt = reinterpret_cast<uint32_t*>(a.gsum + hist);
+    a.carry = reinterpret_cast<StatsCarry*>(a.gcnt + hist);
+    const long long zw = (long long)(hist * 3);                // 32-bit words of the two histogram arrays
+    launch_split_zero(reinterpret_cast<uint32_t*>(split_buf), zw, st);
+    for (int level = 0; level < 3; ++level) {
+      a.level = level;
+      for (int phase = 1; phase <= 2; ++phase) {
+        a.phase = phase;
+        const dim3 grid = phase == 1 ? dim3(nchunks, dm.heads) : dim3(dm.heads);
+        if (a.M == 2) hipLaunchKernelGGL((stats_kernel<2>), grid, dim3(STATS_THREADS), lds, st, a);
+        else hipLaunchKernelGGL((stats_kernel<4>), grid, dim3(STATS_THREADS), lds, st, a);
+      }
+    }
+    return hipGetLastError();
+  }
+  if (a.M == 2) hipLaunchKernelGGL((stats_kernel<2>), dim3(dm.heads), dim3(STATS_THREADS), lds, st, a);
+  else hipLaunchKernelGGL((stats_kernel<4>), dim3(dm.heads), dim3(STATS_THREADS), lds, st, a);
   return hipGetLastError();
 }
 

@@ -1163,6 +1163,67 @@ def test_widest_shapes():
     _run_and_check_whole_path(wl)
 
 
+def test_long_heads_take_the_chunk_parallel_path():
+    """Heads of more than 16384 candidates on a handful of heads: statistics (Eq. 6, 9, pooling) and selection give
+    every 16384-candidate chunk a workgroup of its own and meet in memory between launches.  Three chunks per head
+    here, the last one ragged.  Statistics and pooled scores against the oracle on the GPU's own psi, kept positions
+    against the oracle on the GPU's pooled scores and budgets, then hand-made scores with few distinct values, so
+    that the threshold-valued candidates to keep are counted across chunk boundaries."""
+    wl = small_workloads()["bf16_mha"].scaled(name="bf16_long_ctx", n_layers=2, batch=1, n_q_heads=2, n_kv_heads=2,
+                                               ctx_len=40001, budget=3000, n_images=3, decode_steps=1)
+    NL, B, H, L, W = wl.n_layers, wl.batch, wl.n_kv_heads, wl.ctx_len, wl.window
+    G, nc = wl.n_q_heads // H, L - W
+    p = PU.oracle_params(wl)
+    q, k, v, mask, masks = PU.make_inputs(wl, DEV)
+    eng = engine(wl)
+    say("long heads: madakv_score")
+    eng.score(0, NL, q, k, mask)
+    torch.cuda.synchronize()
+    psi_g, pool_g = eng.psi.cpu().numpy(), eng.psi_pool.cpu().numpy()
+    w_g, k_g = eng.stats_host()
+    nmod_g = eng.n_mod.cpu().numpy()
+    for l in range(NL):
+        psi_in = psi_g[l, 0].astype(np.float64)
+        w_o, k_o, n_o = O.modality_stats(psi_in, masks[0], W, p.theta)
+        assert tuple(nmod_g[0]) == tuple(n_o)
+        np.testing.assert_allclose(w_g[l, 0], w_o, rtol=2e-6, atol=1e-30)
+        np.testing.assert_array_equal(pool_g[l, 0], O.pool_scores(psi_in, W, p.pool_k).astype(np.float32))
+        for h in range(H):
+            for m in (0, 1):
+                if k_g[l, 0, h, m] != k_o[h, m]:
+                    assert PU.k_count_ok(int(k_g[l, 0, h, m]), psi_in[h, :nc][masks[0][:nc] == m], p.theta)
+    eng.allocate(0, NL)
+    eng.select_gather(0, NL, k, v, mask)
+    torch.cuda.synchronize()
+    bud_g = eng.budgets.cpu().numpy()
+    kept_all, off, ln = eng.kept_idx.cpu().numpy(), eng.kv_off.cpu().numpy(), eng.kv_len.cpu().numpy()
+    kc_all = eng.k_c.cpu()
+    for l in range(NL):
+        for h in range(H):
+            bt, bv = (int(x) for x in bud_g[l, 0, h])
+            ref = O.select(pool_g[l, 0, h].astype(np.float64), masks[0], bt, bv, L, W)
+            np.testing.assert_array_equal(kept_all[off[l, 0, h]:off[l, 0, h] + ln[l, 0, h]], ref)
+            assert torch.equal(kc_all[off[l, 0, h]:off[l, 0, h] + len(ref)], k[l, 0, h].cpu()[ref])
+    # few distinct values: ties everywhere, resolved by position across the chunks
+    r = np.random.default_rng(11)
+    m0 = masks[0]
+    n_t, n_v = int((m0[:nc] == 0).sum()), int((m0[:nc] == 1).sum())
+    pool = r.integers(0, 4, size=(NL, 1, H, nc)).astype(np.float32) * 0.5
+    pool[1, 0, 1] = 2.0                                            # one value only
+    tot = wl.budget - W                                            # what a head's segment has room for on average
+    bud = np.array([[[[min(n_t, tot // 3), min(n_v, tot - tot // 3)], [0, min(n_v, tot)]]],
+                    [[[min(n_t, 17), min(n_v, tot - 17)], [min(n_t, tot // 2), min(n_v, tot - tot // 2)]]]], dtype=np.int32)
+    assert int(bud.sum()) + NL * H * (W + wl.decode_steps) <= eng.capacity
+    eng.select_gather(0, NL, k, v, mask, psi_pool=torch.from_numpy(pool).to(DEV), budgets=torch.from_numpy(bud).to(DEV))
+    torch.cuda.synchronize()
+    kept_all, off, ln = eng.kept_idx.cpu().numpy(), eng.kv_off.cpu().numpy(), eng.kv_len.cpu().numpy()
+    for l in range(NL):
+        for h in range(H):
+            ref = O.select(pool[l, 0, h].astype(np.float64), m0, int(bud[l, 0, h, 0]), int(bud[l, 0, h, 1]), L, W)
+            np.testing.assert_array_equal(kept_all[off[l, 0, h]:off[l, 0, h] + ln[l, 0, h]], ref)
+    eng.close()
+
+
 def test_decode_long_heads_across_a_chunk_boundary():
     """Eq. 3-5 on heads of 2300 rows (nine 256-row chunks per head, merged in chunk order) that grow past 2304
     during the steps: one step appends the row that opens a tenth chunk, which then holds nothing but that row.
