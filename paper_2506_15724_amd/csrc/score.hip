@@ -38,6 +38,8 @@ struct ScoreArgs {
   // one-sweep kernel: row statistics of the head's chunks as (max, sum) pairs in one 64-bit word each,
   // [heads, fsplit, mpad], all ones = not yet there; status[0] != 0 = a workgroup gave up waiting
   unsigned long long* xchg;
+  int xgroups;            // 0: every workgroup reads every chunk's words; else the number of groups of XCHG_GROUP chunks (two levels)
+  long long xstride;      // exchange words per head: (fsplit + xgroups) * mpad
   int* status;         // status[0]: workgroups of one-sweep launches that gave up waiting so far (diagnostic counter,
                        // the first word of the workspace; never cleared here)
   int fsplit;          // chunks per head of the one-sweep kernel
@@ -377,7 +379,7 @@ __device__ __forceinline__ void post_row_stats(const ScoreArgs& a, int head, int
   if (fs == 1 || tid >= a.mpad) return;
   // a row none of whose keys here is visible has max NEG_BIG and a meaningless sum: merging it with
   // anything real scales it by exp2(NEG_BIG - m) = 0
-  unsigned long long* xh = a.xchg + (long long)head * a.fsplit * a.mpad;
+  unsigned long long* xh = a.xchg + (long long)head * a.xstride;
   float m = NEG_BIG, l = 0.f;
   for (int w = 0; w < 4; ++w) merge_ml(m, l, part[(w * a.mpad + tid) * 2], part[(w * a.mpad + tid) * 2 + 1]);
   unsigned long long word = ((unsigned long long)__float_as_uint(l) << 32) | __float_as_uint(m);
@@ -385,57 +387,88 @@ __device__ __forceinline__ void post_row_stats(const ScoreArgs& a, int head, int
   __hip_atomic_store(xh + (long long)split * a.mpad + tid, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-template <int D>
-__device__ __forceinline__ void collect_row_stats(const ScoreArgs& a, int head, int fs, int Lh, int Mh, int rowbase,
-                                                  const uint16_t* kg, const uint16_t* qs, const float* part, float* offs, float* pm, int* s_fail) {
+// Thread (r, pt) of the workgroup merges, in order, its share of the `n` words base[item * mpad + r]
+// (items [pt * cpp, (pt + 1) * cpp), cpp = ceil(n / parts)), waiting for each at most spin_limit polls,
+// eight loads at a time; leaves (max, sum) in pm[(pt * mpad + r) * 2 ..] and raises *s_fail if a word stayed away.
+__device__ __forceinline__ void poll_row_words(const ScoreArgs& a, const unsigned long long* base, int n, float* pm, int* s_fail) {
   const int tid = threadIdx.x;
   const int nparts = SCORE_THREADS / a.mpad;    // mpad is 32 or 64
   const int r = tid % a.mpad, pt = tid / a.mpad;
+  const int cpp = (n + nparts - 1) / nparts;
+  int s = min(pt * cpp, n);
+  const int s1 = min(s + cpp, n);
+  float m = NEG_BIG, l = 0.f;
+  int patience = a.spin_limit;
+  bool fail = false;
+  while (s < s1) {
+    unsigned long long v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      v[j] = __hip_atomic_load(base + (long long)min(s + j, s1 - 1) * a.mpad + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    int got = 0;
+    bool open = true;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      open = open && (s + j < s1) && (v[j] != XCHG_EMPTY);
+      if (open) { merge_ml(m, l, __uint_as_float((uint32_t)v[j]), __uint_as_float((uint32_t)(v[j] >> 32))); ++got; }
+    }
+    s += got;
+    if (got == 0) {
+      if (--patience == 0) { fail = true; break; }
+      __builtin_amdgcn_s_sleep(8);
+    }
+  }
+  if (fail) *s_fail = 1;
+  pm[(pt * a.mpad + r) * 2] = m;
+  pm[(pt * a.mpad + r) * 2 + 1] = l;
+}
+
+constexpr int XCHG_GROUP = 16;       // chunks per group when the exchange has two levels
+
+template <int D>
+__device__ __forceinline__ void collect_row_stats(const ScoreArgs& a, int head, int split, int fs, int Lh, int Mh, int rowbase,
+                                                  const uint16_t* kg, const uint16_t* qs, const float* part, float* offs, float* pm, int* s_fail) {
+  const int tid = threadIdx.x;
+  const int nparts = SCORE_THREADS / a.mpad;
   if (fs == 1) {
     if (tid < a.mpad) {
       float m = NEG_BIG, l = 0.f;
       for (int w = 0; w < 4; ++w) merge_ml(m, l, part[(w * a.mpad + tid) * 2], part[(w * a.mpad + tid) * 2 + 1]);
       offs[tid] = (tid < Mh) ? m + log2f(l) : __builtin_inff();
     }
+    return;
+  }
+  unsigned long long* xh = a.xchg + (long long)head * a.xstride;
+  if (a.xgroups == 0) {
+    poll_row_words(a, xh, fs, pm, s_fail);
   } else {
-    const unsigned long long* xh = a.xchg + (long long)head * a.fsplit * a.mpad;
-    // thread (r, pt) merges the chunks [pt * cpp, (pt + 1) * cpp) of row r in order, eight loads at a time
-    const int cpp = (fs + nparts - 1) / nparts;
-    int s = min(pt * cpp, fs);
-    const int s1 = min(s + cpp, fs);
-    float m = NEG_BIG, l = 0.f;
-    int patience = a.spin_limit;
-    bool fail = false;
-    while (s < s1) {
-      unsigned long long v[8];
-#pragma unroll
-      for (int j = 0; j < 8; ++j)
-        v[j] = __hip_atomic_load(xh + (long long)min(s + j, s1 - 1) * a.mpad + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      int got = 0;
-      bool open = true;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        open = open && (s + j < s1) && (v[j] != XCHG_EMPTY);
-        if (open) { merge_ml(m, l, __uint_as_float((uint32_t)v[j]), __uint_as_float((uint32_t)(v[j] >> 32))); ++got; }
+    // Two levels, so that a workgroup reads tens of words per row instead of one per chunk of a long head.
+    // The workgroup of a group's last chunk (it starts after the group's others) merges the group's
+    // words and leaves one word per row for the group; everybody merges the groups' words.
+    unsigned long long* gw = xh + (long long)fs * a.mpad;
+    const int g = split / XCHG_GROUP, c0 = g * XCHG_GROUP, c1 = min(c0 + XCHG_GROUP, fs);
+    if (split == c1 - 1) {
+      poll_row_words(a, xh + (long long)c0 * a.mpad, c1 - c0, pm, s_fail);
+      __syncthreads();
+      if (!*s_fail && tid < a.mpad) {
+        float mm = NEG_BIG, ll = 0.f;
+        for (int q = 0; q < nparts; ++q) merge_ml(mm, ll, pm[(q * a.mpad + tid) * 2], pm[(q * a.mpad + tid) * 2 + 1]);
+        unsigned long long word = ((unsigned long long)__float_as_uint(ll) << 32) | __float_as_uint(mm);
+        if (word == XCHG_EMPTY) word = 0x7fc000007fc00000ULL;
+        __hip_atomic_store(gw + (long long)g * a.mpad + tid, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
-      s += got;
-      if (got == 0) {
-        if (--patience == 0) { fail = true; break; }
-        __builtin_amdgcn_s_sleep(8);
-      }
+      __syncthreads();                              // pm is written again below
     }
-    if (fail) *s_fail = 1;
-    pm[(pt * a.mpad + r) * 2] = m;
-    pm[(pt * a.mpad + r) * 2 + 1] = l;
-    __syncthreads();
-    if (__builtin_expect(*s_fail, 0)) {         // uniform over the workgroup
-      if (tid == 0) atomicAdd(a.status, 1);
-      score_head_stats_alone<D>(a, Lh, Mh, rowbase, kg, qs, offs);
-    } else if (tid < a.mpad) {
-      float mm = NEG_BIG, ll = 0.f;
-      for (int q = 0; q < nparts; ++q) merge_ml(mm, ll, pm[(q * a.mpad + tid) * 2], pm[(q * a.mpad + tid) * 2 + 1]);
-      offs[tid] = (tid < Mh) ? mm + log2f(ll) : __builtin_inff();
-    }
+    if (!*s_fail) poll_row_words(a, gw, a.xgroups, pm, s_fail);   // (uniform: s_fail was read behind a barrier)
+  }
+  __syncthreads();
+  if (__builtin_expect(*s_fail, 0)) {         // uniform over the workgroup
+    if (tid == 0) atomicAdd(a.status, 1);
+    score_head_stats_alone<D>(a, Lh, Mh, rowbase, kg, qs, offs);
+  } else if (tid < a.mpad) {
+    float mm = NEG_BIG, ll = 0.f;
+    for (int q = 0; q < nparts; ++q) merge_ml(mm, ll, pm[(q * a.mpad + tid) * 2], pm[(q * a.mpad + tid) * 2 + 1]);
+    offs[tid] = (tid < Mh) ? mm + log2f(ll) : __builtin_inff();
   }
 }
 
@@ -443,7 +476,7 @@ template <int D>
 __device__ __forceinline__ void exchange_row_stats(const ScoreArgs& a, int head, int split, int fs, int Lh, int Mh, int rowbase,
                                                    const uint16_t* kg, const uint16_t* qs, const float* part, float* offs, float* pm, int* s_fail) {
   post_row_stats(a, head, split, fs, part);
-  collect_row_stats<D>(a, head, fs, Lh, Mh, rowbase, kg, qs, part, offs, pm, s_fail);
+  collect_row_stats<D>(a, head, split, fs, Lh, Mh, rowbase, kg, qs, part, offs, pm, s_fail);
 }
 
 #ifndef MADAKV_FUSED_NS1      // tuning constants of the one-sweep kernel (measured on MI355X)
@@ -795,7 +828,7 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(2
 #undef MADAKV_WIN_PARK
 
   // ---- the head-wide statistics (by now the other workgroups have normally posted theirs)
-  collect_row_stats<D>(a, head, fs, Lh, a.M, 0, kg, qs, part, offs, pm, &s_fail);
+  collect_row_stats<D>(a, head, split, fs, Lh, a.M, 0, kg, qs, part, offs, pm, &s_fail);
   __syncthreads();
   if (split == 0 && wa.lse && tid < a.M) wa.lse[(lb * a.H + kvh) * (long long)a.G * a.W + tid] = offs[tid] * 0.6931471805599453f;
   const float mxw = part[(wave * 32 + col) * 2];           // the wave's own row maximum again
@@ -984,8 +1017,13 @@ static int fused_chunk(const Dims& dm) { return 4 * 32 * ((dm.M + 31) / 32 == 1 
 static int fused_split(const Dims& dm) { return (dm.L + fused_chunk(dm) - 1) / fused_chunk(dm); }
 static int fused_mpad(const Dims& dm) { return dm.M <= 32 ? 32 : 64; }
 static int fused_blocks(const Dims& dm) { return dm.M <= 64 ? 1 : (dm.M + 63) / 64; }   // blocks of 64 proxy rows handled like heads
+// exchange levels: one up to FUSED_MAX_SPLIT chunks per head, two (groups of XCHG_GROUP chunks) up to
+// FUSED_MAX_SPLIT_2L.  All workgroups of a head wait for each other, so a head must never need more
+// workgroups than the chip holds at once (512 of this kernel): half of that is the limit.
+constexpr int FUSED_MAX_SPLIT_2L = 256;
+static int xchg_groups(int split) { return split <= FUSED_MAX_SPLIT ? 0 : (split + XCHG_GROUP - 1) / XCHG_GROUP; }
 static bool fused_fits(const Dims& dm, int dtype) {
-  return use_mfma(dm, dtype) && dm.M <= 256 && fused_split(dm) <= FUSED_MAX_SPLIT && (long long)dm.heads * fused_blocks(dm) <= 65535;
+  return use_mfma(dm, dtype) && dm.M <= 256 && fused_split(dm) <= FUSED_MAX_SPLIT_2L && (long long)dm.heads * fused_blocks(dm) <= 65535;
 }
 static bool use_fused(const Dims& dm, int dtype) {
   const char* e = getenv("MADAKV_SCORE_TWO_SWEEPS");      // diagnostic switch: the two-sweep kernels everywhere
@@ -998,7 +1036,8 @@ static size_t rowstat_bytes(const Dims& dm, int dtype) {
   return ((size_t)dm.heads * p.nsplit * p.mpad * 2 * sizeof(float) + 255) / 256 * 256;
 }
 static size_t xchg_bytes(const Dims& dm, int dtype) {
-  return fused_fits(dm, dtype) ? ((size_t)dm.heads * fused_blocks(dm) * fused_split(dm) * fused_mpad(dm) * 8 + 255) / 256 * 256 : 0;
+  const size_t per_head = (size_t)(fused_split(dm) + xchg_groups(fused_split(dm))) * fused_mpad(dm);
+  return fused_fits(dm, dtype) ? ((size_t)dm.heads * fused_blocks(dm) * per_head * 8 + 255) / 256 * 256 : 0;
 }
 size_t score_ws_bytes(const Dims& dm, int dtype) {
   // the counter of lone workgroups, the row statistics of the two sweeps, the store sink, the exchange array of the
@@ -1020,10 +1059,10 @@ __global__ __launch_bounds__(256) void score_blocks_sum_kernel(const float* part
 template <int D>
 static void launch_fused(const ScoreArgs& a, int heads, hipStream_t st) {
   const int vheads = heads * a.rb_count;
-  const long long nx = (long long)vheads * a.fsplit * a.mpad;
+  const long long nx = (long long)vheads * a.xstride;
   if (a.fsplit > 1)
     hipLaunchKernelGGL(score_xchg_init_kernel, dim3((unsigned)((nx + 255) / 256)), dim3(256), 0, st,
-                       a.xchg + (long long)a.head0 * a.rb_count * a.fsplit * a.mpad, nx);
+                       a.xchg + (long long)a.head0 * a.rb_count * a.xstride, nx);
   const size_t ldsf = ((size_t)a.mpad + 4 * 32) * (D + 8) * 2 + ((size_t)4 * a.mpad * 2 + a.mpad + 512) * sizeof(float);
   ScoreArgs b = a;
   b.head0 = a.head0 * a.rb_count;
@@ -1084,6 +1123,7 @@ hipError_t launch_score_ragged(const Dims& dm, const madakv_config& c, const voi
   a.H = dm.H; a.G = dm.G; a.d = dm.d; a.L = dm.L; a.W = dm.W; a.M = dm.M;
   a.mpad = fused_mpad(dm); a.nsplit = 0; a.nmerge = 0; a.chunk = 0; a.head0 = 0;
   a.fsplit = ragged_split(dm, longest_rows);
+  a.xgroups = 0; a.xstride = (long long)a.fsplit * fused_mpad(dm);
   const char* spin = getenv("MADAKV_SCORE_SPIN_LIMIT");
   a.spin_limit = spin && atoi(spin) > 0 ? atoi(spin) : FUSED_SPIN_LIMIT;
   const float scale = c.softmax_scale > 0.f ? c.softmax_scale : 1.0f / sqrtf((float)dm.d);
@@ -1135,6 +1175,7 @@ hipError_t launch_window_attn(const Dims& dm, const madakv_config& c, const void
   a.mpad = 32; a.nsplit = 0; a.nmerge = 0; a.chunk = 0; a.head0 = 0;
   a.rb_count = 1; a.psi_part = nullptr; a.psi_part_stride = 0;
   a.fsplit = win_split(dm);
+  a.xgroups = 0; a.xstride = (long long)a.fsplit * 32;
   const char* spin = getenv("MADAKV_SCORE_SPIN_LIMIT");
   a.spin_limit = spin && atoi(spin) > 0 ? atoi(spin) : FUSED_SPIN_LIMIT;
   const float scale = c.softmax_scale > 0.f ? c.softmax_scale : 1.0f / sqrtf((float)dm.d);
@@ -1168,6 +1209,7 @@ hipError_t launch_score(const Dims& dm, const madakv_config& c, const void* q_wi
   a.psi_part = reinterpret_cast<float*>(static_cast<char*>(ws) + 256 + rowstat_bytes(dm, c.dtype) + 256 + xchg_bytes(dm, c.dtype));
   a.psi_part_stride = (long long)dm.heads * dm.L;
   a.fsplit = (!row_lse && use_fused(dm, c.dtype)) ? fused_split(dm) : 0;
+  a.xgroups = xchg_groups(a.fsplit); a.xstride = (long long)(a.fsplit + a.xgroups) * fused_mpad(dm);
   a.seg_off = nullptr; a.seg_len = nullptr;
   // (a test can force the lone-workgroup path of the one-sweep kernel from the host with a spin limit of 1)
   const char* spin = getenv("MADAKV_SCORE_SPIN_LIMIT");

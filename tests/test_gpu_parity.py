@@ -605,7 +605,16 @@ def test_allocate_rounds_after_every_operation():
         eng.close()
 
 
-@pytest.mark.parametrize("name", ["bf16_mha", "bf16_w64", "bf16_d64_gqa2", "bf16_odd"])
+def _one_sweep_workloads():
+    W = small_workloads()
+    out = {n: W[n] for n in ("bf16_mha", "bf16_w64", "bf16_d64_gqa2", "bf16_odd")}
+    # 69 chunks of 1024 keys per head: the row statistics travel in two levels (groups of 16 chunks)
+    out["bf16_70k"] = W["bf16_mha"].scaled(name="bf16_70k", n_layers=1, batch=1, n_q_heads=2, n_kv_heads=2, ctx_len=70001,
+                                           budget=500, n_images=3)
+    return out
+
+
+@pytest.mark.parametrize("name", list(_one_sweep_workloads().keys()))
 def test_one_sweep_scoring_and_its_lone_workgroup_path(name):
     """Scoring in one sweep over K: the workgroups of a head exchange their row statistics through
     memory and wait for each other, with a bounded wait.  In a normal run nobody gives up (the
@@ -613,7 +622,7 @@ def test_one_sweep_scoring_and_its_lone_workgroup_path(name):
     the host, workgroups that find a word missing compute the head's statistics on their own: every
     kernel still ends normally and the scores still match the oracle."""
     import os
-    wl = small_workloads()[name]
+    wl = _one_sweep_workloads()[name]
     NL, B, H, L, W = wl.n_layers, wl.batch, wl.n_kv_heads, wl.ctx_len, wl.window
     G = wl.n_q_heads // H
     p = PU.oracle_params(wl)
