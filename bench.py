@@ -618,8 +618,8 @@ def main():
 
     if not a.no_extras and wl.name == "llava_16k":
         # the other named configurations that are large enough to time: the Qwen-shaped grouped-query model
-        # (224 proxy rows per KV head: the two-sweep MFMA path, and the MFMA decode kernel) and the 128K context
-        # at both budgets of its sweep
+        # (224 proxy rows per KV head: four blocks of 64 rows on the one-sweep kernel, and the MFMA decode kernel) and
+        # the 128K context at both budgets of its sweep (two-level exchange, chunk-parallel statistics / selection)
         others = {}
         for key, (nm, bud) in {"qwen_gqa": ("qwen_gqa", None), "long_128k_budget_512": ("long_128k", 512),
                                "long_128k_budget_4096": ("long_128k", 4096)}.items():

@@ -22,6 +22,14 @@ from paper_2506_15724_amd import workloads as WL
 PSI_RTOL = 1e-3
 DECODE_ATOL = 2e-3
 TIE_RTOL = 1e-4
+W_RTOL = 2e-6                  # masses when both sides read the same psi bits: the fp32 rounding of the result ...
+W_QUANTUM = 2.0 ** -44         # ... plus the fixed point the GPU sums in: every addend is rounded to a multiple of this
+
+
+def assert_masses_close(w_gpu, w_ref, n_candidates):
+    """Eq. 6 on the same psi bits.  The GPU adds the scores in 2^-44 fixed point (integer adds commute, so the sum is
+    the same on every run) and rounds the total to fp32 once: |gpu - exact| <= n * 2^-45 + 2^-24 * |exact|."""
+    np.testing.assert_allclose(w_gpu, w_ref, rtol=W_RTOL, atol=n_candidates * W_QUANTUM / 2)
 
 
 def oracle_params(wl: WL.Workload, **kw) -> O.Params:

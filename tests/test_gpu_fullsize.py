@@ -94,7 +94,7 @@ def run_full(wl, samples, decode_steps=2, check_steps=None):
         w_o, k_o, _ = O.modality_stats(psi_in, masks[b], W, p.theta)
         st = eng.stats[l, b, h].cpu()
         w_g = st[:2].view(torch.float32).numpy(); k_g = st[2:].numpy()
-        np.testing.assert_allclose(w_g, w_o[0], rtol=2e-6)
+        PU.assert_masses_close(w_g, w_o[0], L)
         for m in (0, 1):
             if k_g[m] != k_o[0, m]:
                 assert PU.k_count_ok(int(k_g[m]), psi_in[0, :nc][masks[b][:nc] == m], p.theta)

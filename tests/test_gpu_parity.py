@@ -91,7 +91,7 @@ def test_stagewise_parity(name):
             psi_in = psi_g[l, b].astype(np.float64)
             w_o, k_o, n_o = O.modality_stats(psi_in, masks[b], W, p.theta)
             assert tuple(nmod_g[b]) == tuple(n_o)
-            np.testing.assert_allclose(w_g[l, b], w_o, rtol=2e-6, atol=1e-30)
+            PU.assert_masses_close(w_g[l, b], w_o, L)
             np.testing.assert_array_equal(pool_g[l, b], O.pool_scores(psi_in, W, p.pool_k).astype(np.float32))
             for h in range(H):
                 for m in (0, 1):
@@ -502,7 +502,7 @@ def test_more_than_two_modalities(M, mpa):
             psi_in = psi_g[l, b].astype(np.float64)
             w_o, k_o, n_o = O.modality_stats(psi_in, masks[b], W, p.theta, 0, M)
             assert tuple(nmod[b]) == tuple(n_o)
-            np.testing.assert_allclose(w_g[l, b], w_o, rtol=2e-6, atol=1e-30)
+            PU.assert_masses_close(w_g[l, b], w_o, L)
             np.testing.assert_array_equal(pool_g[l, b], O.pool_scores(psi_in, W, p.pool_k).astype(np.float32))
             for h in range(H):
                 for m in range(M):
@@ -822,7 +822,7 @@ def test_reeviction_during_generation(name):
             rowmod = np.where(origin[s] < L, masks[b][np.minimum(origin[s], L - 1)], 0)
             w_r, n_r = O.modality_mass(pg.astype(np.float64), rowmod, W, M)
             assert tuple(n_g[s]) == tuple(n_r)
-            np.testing.assert_allclose(w_g[s], w_r, rtol=2e-6, atol=1e-30)
+            PU.assert_masses_close(w_g[s], w_r, len(pg))
             bud_r = O.mpa_split_n(int(len0[s]) - W, w_g[s].astype(np.float64), n_r, p.mpa_mode)
             assert list(bud_g[s]) == list(bud_r)
             pool_r = O.pool_scores(pg.astype(np.float64)[None], W, p.pool_k)[0].astype(np.float32).astype(np.float64)
@@ -913,7 +913,7 @@ def test_window_attention_with_scores(name, fp32_out):
                 assert nbad == 0, worst
                 psi_in = psi_g[l, b].astype(np.float64)
                 w_o, k_o, n_o = O.modality_stats(psi_in, masks[b], W, p.theta)
-                np.testing.assert_allclose(w_g[l, b], w_o, rtol=2e-6, atol=1e-30)
+                PU.assert_masses_close(w_g[l, b], w_o, L)
                 np.testing.assert_array_equal(pool_g[l, b], O.pool_scores(psi_in, W, p.pool_k).astype(np.float32))
                 for h in range(H):
                     for m in (0, 1):
@@ -1126,7 +1126,7 @@ def _run_and_check_whole_path(wl, decode_steps=1):
             psi_in = psi_g[l, b].astype(np.float64)
             w_o, k_o, n_o = O.modality_stats(psi_in, masks[b], W, p.theta)
             assert tuple(nmod[b]) == tuple(n_o)
-            np.testing.assert_allclose(w_g[l, b], w_o, rtol=2e-6, atol=1e-30)
+            PU.assert_masses_close(w_g[l, b], w_o, L)
             if not p.keep_all:
                 np.testing.assert_array_equal(pool_g[l, b], O.pool_scores(psi_in, W, p.pool_k).astype(np.float32))
         np.testing.assert_array_equal(bud_g[:, b], O.allocate(w_g[:, b], k_g[:, b].astype(np.int64), nmod[b], p))
@@ -1170,6 +1170,11 @@ def test_widest_shapes():
     wl = WL.CONFIGS["llava_layer"].scaled(name="g8", n_layers=1, batch=2, n_q_heads=16, n_kv_heads=2, head_dim=128,
                                           ctx_len=1300, window=32, budget=200, n_images=1)
     _run_and_check_whole_path(wl)
+    # 20 layers of 64 heads: a layer group lays out 320 segments per batch item, more than one trip of the
+    # segment-layout workgroup
+    wl = WL.CONFIGS["llava_layer"].scaled(name="deep_wide", n_layers=20, batch=1, n_q_heads=64, n_kv_heads=64, head_dim=64,
+                                          ctx_len=900, window=8, budget=120, n_images=1)
+    _run_and_check_whole_path(wl)
 
 
 def test_long_heads_take_the_chunk_parallel_path():
@@ -1195,7 +1200,7 @@ def test_long_heads_take_the_chunk_parallel_path():
         psi_in = psi_g[l, 0].astype(np.float64)
         w_o, k_o, n_o = O.modality_stats(psi_in, masks[0], W, p.theta)
         assert tuple(nmod_g[0]) == tuple(n_o)
-        np.testing.assert_allclose(w_g[l, 0], w_o, rtol=2e-6, atol=1e-30)
+        PU.assert_masses_close(w_g[l, 0], w_o, L)
         np.testing.assert_array_equal(pool_g[l, 0], O.pool_scores(psi_in, W, p.pool_k).astype(np.float32))
         for h in range(H):
             for m in (0, 1):
