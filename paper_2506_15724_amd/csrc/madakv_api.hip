@@ -294,9 +294,9 @@ int32_t madakv_create(const madakv_config* cfg, madakv_handle** out) {
     if (e == hipSuccess) e = hipMemset(h->d_page_tbl, 0, tb);
   }
   {
-    // contexts of more than one 16384-candidate chunk: room for the largest launch that would use the chunk-parallel path
+    // long contexts on few heads: room for the largest launch that would use the chunk-parallel statistics / selection
     Dims d1 = make_dims(*cfg, 1);
-    if (d1.nc > 16384) {
+    if (split_chunks(d1) > 0) {
       const int nchunks = (d1.nc + 16383) / 16384;
       const int heads = std::min(cfg->n_layers * cfg->batch * cfg->n_kv_heads, 128);
       h->split_bytes = split_buffer_bytes(heads, cfg->n_modalities, nchunks);

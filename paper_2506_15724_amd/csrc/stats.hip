@@ -370,11 +370,12 @@ void launch_split_zero(uint32_t* p, long long words, hipStream_t st) {
   hipLaunchKernelGGL(split_zero_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st, p, words);
 }
 
-// Chunks per head that go to workgroups of their own, or 0: heads of more than one 16384-candidate chunk,
+// Chunks per head that go to workgroups of their own, or 0: heads of at least four 16384-candidate chunks
+// (with two, the 16 small launches cost what the parallelism gains: measured on 28 heads of 32K candidates),
 // so few of them that one workgroup per head would leave most of the chip idle.
 int split_chunks(const Dims& dm) {
   const int nchunks = (dm.nc + STATS_THREADS * STATS_EPT - 1) / (STATS_THREADS * STATS_EPT);
-  return (nchunks >= 2 && dm.heads <= SPLIT_MAX_HEADS) ? nchunks : 0;
+  return (nchunks >= 4 && dm.heads <= SPLIT_MAX_HEADS) ? nchunks : 0;
 }
 size_t split_buffer_bytes(int heads, int M, int nchunks) {
   const size_t hist = (size_t)3 * heads * M * BINS;

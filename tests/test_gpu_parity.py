@@ -1179,12 +1179,12 @@ def test_widest_shapes():
 
 def test_long_heads_take_the_chunk_parallel_path():
     """Heads of more than 16384 candidates on a handful of heads: statistics (Eq. 6, 9, pooling) and selection give
-    every 16384-candidate chunk a workgroup of its own and meet in memory between launches.  Three chunks per head
+    every 16384-candidate chunk a workgroup of its own and meet in memory between launches.  Four chunks per head
     here, the last one ragged.  Statistics and pooled scores against the oracle on the GPU's own psi, kept positions
     against the oracle on the GPU's pooled scores and budgets, then hand-made scores with few distinct values, so
     that the threshold-valued candidates to keep are counted across chunk boundaries."""
     wl = small_workloads()["bf16_mha"].scaled(name="bf16_long_ctx", n_layers=2, batch=1, n_q_heads=2, n_kv_heads=2,
-                                               ctx_len=40001, budget=3000, n_images=3, decode_steps=1)
+                                               ctx_len=50001, budget=3000, n_images=3, decode_steps=1)
     NL, B, H, L, W = wl.n_layers, wl.batch, wl.n_kv_heads, wl.ctx_len, wl.window
     G, nc = wl.n_q_heads // H, L - W
     p = PU.oracle_params(wl)
