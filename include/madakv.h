@@ -40,8 +40,11 @@
  *     found there leave all outputs untouched.
  *   - The handle belongs to the HIP device that was current in madakv_create; that device must
  *     be current in every later call on it.  It owns a few KB of device memory (carry state of
- *     the layer recurrence and cache cursors), a little pinned host memory, one extra stream of
- *     default priority and a few events.  Calls on one handle must not overlap.
+ *     the layer recurrence and cache cursors; with a paged cache its page table; for contexts of
+ *     four or more 16384-token chunks on at most 128 heads per layer a few MB of histograms that
+ *     the per-head statistics and selection kernels share between launches), a little pinned
+ *     host memory, one extra stream of default priority and a few events.  Calls on one handle
+ *     must not overlap.
  *   - Layers are addressed as a range [layer0, layer0 + n).  Tensor arguments hold
  *     only the n layers of the call, layer-major.  madakv_allocate and
  *     madakv_select_gather carry state from layer to layer and must be called in
