@@ -283,7 +283,8 @@ int32_t madakv_decode_attn(madakv_handle* h, int32_t layer0, int32_t n,
  *   budgets  [n, B, H, M]       out: the new split
  *   ws                          madakv_reevict_workspace_bytes(h, n) bytes
  * The decode-step counters of the layers are reset: max_new_tokens rows can be appended again.
- * MADAKV_ERR_UNIMPLEMENTED with a paged or 8-bit cache, dtype fp32, or segments longer than 64 chunks of the
+ * An 8-bit cache is scored and moved as it is stored (E4M3 rows).
+ * MADAKV_ERR_UNIMPLEMENTED with a paged cache, dtype fp32, or segments longer than 64 chunks of the
  * scoring kernel (65536 rows at G * W <= 32, 49152 beyond); MADAKV_ERR_BAD_BUDGET when budget >= ctx_len
  * (nothing was evicted). */
 int32_t madakv_reevict_workspace_bytes(const madakv_handle* h, int32_t n_layers_per_call, size_t* bytes);

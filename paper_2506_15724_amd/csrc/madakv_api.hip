@@ -641,7 +641,7 @@ int32_t madakv_reevict(madakv_handle* h, int32_t layer0, int32_t n,
   if (bad_ptr(q_recent) || bad_ptr(mask, 1) || bad_ptr(k_c) || bad_ptr(v_c) || bad_ptr(kept_idx, 4) || bad_ptr(kv_off, 8) ||
       bad_ptr(kv_len, 4) || bad_ptr(budgets, 4) || bad_ptr(ws)) return MADAKV_ERR_INVALID_ARG;
   if (c.budget >= c.ctx_len) return MADAKV_ERR_BAD_BUDGET;                 // nothing was evicted, nothing to bring back
-  if (c.page_rows || c.cache_fp8) return MADAKV_ERR_UNIMPLEMENTED;
+  if (c.page_rows) return MADAKV_ERR_UNIMPLEMENTED;
   int longest = longest_rows(h, layer0, n);
   if (!score_ragged_supported(make_dims(c, n), c, longest)) {
     // the bound may be the worst case only because the lengths of the eviction have not reached the host

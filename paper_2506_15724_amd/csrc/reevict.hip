@@ -163,8 +163,9 @@ hipError_t launch_compact(const Dims& dm, const madakv_config& c, void* k_c, voi
   CompactArgs a;
   a.k_c = k_c; a.v_c = v_c; a.kept_idx = kept_idx; a.sel = sel; a.seg_off = seg_off; a.kv_len = kv_len; a.budgets = budgets;
   a.W = dm.W; a.M = c.n_modalities; a.L = dm.L; a.appended = appended; a.gen_base = gen_base;
-  const int lpr = dm.d * (c.dtype == MADAKV_BF16 ? 2 : 4) / 16;
-  if (lpr == 8) hipLaunchKernelGGL((compact_kernel<8>), dim3(dm.heads), dim3(RE_THREADS), 0, st, a);
+  const int lpr = dm.d * (c.cache_fp8 ? 1 : (c.dtype == MADAKV_BF16 ? 2 : 4)) / 16;     // 16-byte pieces per cached row
+  if (lpr == 4) hipLaunchKernelGGL((compact_kernel<4>), dim3(dm.heads), dim3(RE_THREADS), 0, st, a);
+  else if (lpr == 8) hipLaunchKernelGGL((compact_kernel<8>), dim3(dm.heads), dim3(RE_THREADS), 0, st, a);
   else if (lpr == 16) hipLaunchKernelGGL((compact_kernel<16>), dim3(dm.heads), dim3(RE_THREADS), 0, st, a);
   else if (lpr == 32) hipLaunchKernelGGL((compact_kernel<32>), dim3(dm.heads), dim3(RE_THREADS), 0, st, a);
   else return hipErrorInvalidValue;

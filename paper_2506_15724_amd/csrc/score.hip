@@ -38,6 +38,7 @@ struct ScoreArgs {
   // one-sweep kernel: row statistics of the head's chunks as (max, sum) pairs in one 64-bit word each,
   // [heads, fsplit, mpad], all ones = not yet there; status[0] != 0 = a workgroup gave up waiting
   unsigned long long* xchg;
+  int k_fp8;              // keys are E4M3 bytes (rows of d bytes: the 8-bit reduced cache), else bf16
   int xgroups;            // 0: every workgroup reads every chunk's words; else the number of groups of XCHG_GROUP chunks (two levels)
   long long xstride;      // exchange words per head: (fsplit + xgroups) * mpad
   int* status;         // status[0]: workgroups of one-sweep launches that gave up waiting so far (diagnostic counter,
@@ -325,6 +326,16 @@ _Pragma("unroll") \
 // status[0] and computes the row statistics of the whole head on its own with plain FMA code
 // (slow, and its last bits differ from the exchanged ones, but it depends on nobody).
 // ------------------------------------------------------------------------------------
+// 4 E4M3 bytes -> 4 bf16 (exact: 3 mantissa bits fit bf16's 7), as two packed dwords
+__device__ __forceinline__ u32x2_t e4m3x4_as_bf16x4(uint32_t w) {
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  const f32x2_t a = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, false), b = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, true);
+  u32x2_t o;
+  o[0] = (__float_as_uint(a[0]) >> 16) | (__float_as_uint(a[1]) & 0xffff0000u);
+  o[1] = (__float_as_uint(b[0]) >> 16) | (__float_as_uint(b[1]) & 0xffff0000u);
+  return o;
+}
+
 constexpr unsigned long long XCHG_EMPTY = ~0ULL;
 constexpr int FUSED_SPIN_LIMIT = 1 << 16;     // default spin_limit: polls of ~1 us each
 
@@ -336,7 +347,7 @@ __global__ __launch_bounds__(256) void score_xchg_init_kernel(unsigned long long
 // Row statistics of a whole head by one workgroup, without matrix cores and without anybody
 // else: wave w takes rows w, w + 4, ...; lanes stride over the keys the row sees.  Q comes from
 // the staged tile.  Leaves offs[r] = max + log2(sum) (log2 domain), +inf for padding rows.
-template <int D>
+template <int D, bool F8 = false>
 __device__ __forceinline__ void score_head_stats_alone(const ScoreArgs& a, int Lh, int Mh, int rowbase, const uint16_t* kg, const uint16_t* qs, float* offs) {
   constexpr int RS = D + 8;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -347,7 +358,14 @@ __device__ __forceinline__ void score_head_stats_alone(const ScoreArgs& a, int L
       for (int key = lane; key <= pos; key += 64) {
         float sdot = 0.f;
         for (int c = 0; c < D / 8; ++c) {
-          const uint4 kk = *reinterpret_cast<const uint4*>(kg + (long long)key * D + c * 8);
+          uint4 kk;
+          if (F8) {      // 8 of the row's D bytes -> 8 bf16
+            const u32x2_t raw = *reinterpret_cast<const u32x2_t*>(reinterpret_cast<const unsigned char*>(kg) + (long long)key * D + c * 8);
+            const u32x2_t lo = e4m3x4_as_bf16x4(raw[0]), hi = e4m3x4_as_bf16x4(raw[1]);
+            kk = make_uint4(lo[0], lo[1], hi[0], hi[1]);
+          } else {
+            kk = *reinterpret_cast<const uint4*>(kg + (long long)key * D + c * 8);
+          }
           const uint4 qq = *reinterpret_cast<const uint4*>(qs + r * RS + c * 8);
           sdot = fmaf(bf16_lo(kk.x), bf16_lo(qq.x), sdot); sdot = fmaf(bf16_hi(kk.x), bf16_hi(qq.x), sdot);
           sdot = fmaf(bf16_lo(kk.y), bf16_lo(qq.y), sdot); sdot = fmaf(bf16_hi(kk.y), bf16_hi(qq.y), sdot);
@@ -425,7 +443,7 @@ __device__ __forceinline__ void poll_row_words(const ScoreArgs& a, const unsigne
 
 constexpr int XCHG_GROUP = 16;       // chunks per group when the exchange has two levels
 
-template <int D>
+template <int D, bool F8 = false>
 __device__ __forceinline__ void collect_row_stats(const ScoreArgs& a, int head, int split, int fs, int Lh, int Mh, int rowbase,
                                                   const uint16_t* kg, const uint16_t* qs, const float* part, float* offs, float* pm, int* s_fail) {
   const int tid = threadIdx.x;
@@ -464,7 +482,7 @@ __device__ __forceinline__ void collect_row_stats(const ScoreArgs& a, int head, 
   __syncthreads();
   if (__builtin_expect(*s_fail, 0)) {         // uniform over the workgroup
     if (tid == 0) atomicAdd(a.status, 1);
-    score_head_stats_alone<D>(a, Lh, Mh, rowbase, kg, qs, offs);
+    score_head_stats_alone<D, F8>(a, Lh, Mh, rowbase, kg, qs, offs);
   } else if (tid < a.mpad) {
     float mm = NEG_BIG, ll = 0.f;
     for (int q = 0; q < nparts; ++q) merge_ml(mm, ll, pm[(q * a.mpad + tid) * 2], pm[(q * a.mpad + tid) * 2 + 1]);
@@ -472,11 +490,11 @@ __device__ __forceinline__ void collect_row_stats(const ScoreArgs& a, int head, 
   }
 }
 
-template <int D>
+template <int D, bool F8 = false>
 __device__ __forceinline__ void exchange_row_stats(const ScoreArgs& a, int head, int split, int fs, int Lh, int Mh, int rowbase,
                                                    const uint16_t* kg, const uint16_t* qs, const float* part, float* offs, float* pm, int* s_fail) {
   post_row_stats(a, head, split, fs, part);
-  collect_row_stats<D>(a, head, split, fs, Lh, Mh, rowbase, kg, qs, part, offs, pm, s_fail);
+  collect_row_stats<D, F8>(a, head, split, fs, Lh, Mh, rowbase, kg, qs, part, offs, pm, s_fail);
 }
 
 #ifndef MADAKV_FUSED_NS1      // tuning constants of the one-sweep kernel (measured on MI355X)
@@ -488,7 +506,7 @@ __device__ __forceinline__ void exchange_row_stats(const ScoreArgs& a, int head,
 #ifndef MADAKV_FUSED_MAX_SPLIT
 #define MADAKV_FUSED_MAX_SPLIT 64   // most chunks per head the one-sweep kernel is used for
 #endif
-template <int D, int NRB, int NS>
+template <int D, int NRB, int NS, bool F8 = false>   // F8: the keys are E4M3 bytes (the 8-bit reduced cache), turned into bf16 when parked in LDS
 __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(MADAKV_FUSED_WPE, MADAKV_FUSED_WPE))) void score_fused_kernel(ScoreArgs a) {
   constexpr int PF = MADAKV_FUSED_PF < NS ? MADAKV_FUSED_PF : NS;
   constexpr int KS = D / 16;                  // MFMA k-steps
@@ -518,21 +536,26 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(M
   const long long base = a.seg_off ? a.seg_off[head] : (long long)head * a.L;
   const int fs = a.seg_len ? (Lh + CK - 1) / CK : a.fsplit;      // chunks of this head (the grid is sized for the longest)
   if (split >= fs) return;
-  const uint16_t* kg = reinterpret_cast<const uint16_t*>(a.k) + base * D;
+  // (F8: rows of D bytes; kg then counts in 2-byte units from a byte address that is base * D)
+  const uint16_t* kg = F8 ? reinterpret_cast<const uint16_t*>(reinterpret_cast<const unsigned char*>(a.k) + base * D)
+                          : reinterpret_cast<const uint16_t*>(a.k) + base * D;
   const int chunk0 = split * CK;
   const int chunk1 = min(Lh, chunk0 + CK);
   uint16_t* kt = kt_all + (size_t)wave * 32 * RS;
   if (tid == 0) s_fail = 0;
 
   // subtile `it` of this wave: keys chunk0 + (it * 4 + wave) * 32 ...; PF subtiles in flight
-  u32x4_t pre[PF][LPS];
+  constexpr int CPR = F8 ? PPR / 2 : PPR;      // 16-byte pieces per cached row
+  constexpr int LPSK = F8 ? LPS / 2 : LPS;     // loads per lane and subtile
+  u32x4_t pre[PF][LPSK];
 #define MADAKV_FUSED_LOAD(SET, IT)                                                               \
   {                                                                                              \
     const int lt0 = chunk0 + ((IT) * 4 + wave) * 32;                                             \
-    _Pragma("unroll") for (int i = 0; i < LPS; ++i) {                                            \
+    _Pragma("unroll") for (int i = 0; i < LPSK; ++i) {                                           \
       const int idx = i * 64 + lane;                                                             \
-      const int lkey = min(lt0 + idx / PPR, Lh - 1); /* past the end: a valid row, masked later */ \
-      pre[SET][i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(kg + (long long)lkey * D + (idx % PPR) * 8)); \
+      const int lkey = min(lt0 + idx / CPR, Lh - 1); /* past the end: a valid row, masked later */ \
+      pre[SET][i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(                 \
+          reinterpret_cast<const unsigned char*>(kg) + ((long long)lkey * CPR + (idx % CPR)) * 16)); \
     }                                                                                            \
   }
 #pragma unroll
@@ -557,9 +580,16 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(M
 #pragma unroll
   for (int it = 0; it < NS; ++it) {
 #pragma unroll
-    for (int i = 0; i < LPS; ++i) {
+    for (int i = 0; i < LPSK; ++i) {
       const int idx = i * 64 + lane;
-      *reinterpret_cast<u32x4_t*>(kt + (idx / PPR) * RS + (idx % PPR) * 8) = pre[it % PF][i];
+      if (F8) {                                   // 16 bytes of a row -> 16 bf16
+        const u32x4_t raw = pre[it % PF][i];
+        const u32x2_t c0 = e4m3x4_as_bf16x4(raw[0]), c1 = e4m3x4_as_bf16x4(raw[1]), c2 = e4m3x4_as_bf16x4(raw[2]), c3 = e4m3x4_as_bf16x4(raw[3]);
+        *reinterpret_cast<u32x4_t*>(kt + (idx / CPR) * RS + (idx % CPR) * 16) = u32x4_t{c0[0], c0[1], c1[0], c1[1]};
+        *reinterpret_cast<u32x4_t*>(kt + (idx / CPR) * RS + (idx % CPR) * 16 + 8) = u32x4_t{c2[0], c2[1], c3[0], c3[1]};
+      } else {
+        *reinterpret_cast<u32x4_t*>(kt + (idx / PPR) * RS + (idx % PPR) * 8) = pre[it % PF][i];
+      }
     }
     if (it + PF < NS) MADAKV_FUSED_LOAD(it % PF, it + PF)
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -620,7 +650,7 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(M
     }
   }
   __syncthreads();
-  exchange_row_stats<D>(a, hv, split, fs, Lh, Mh, rowbase, kg, qs, part, offs, pm, &s_fail);
+  exchange_row_stats<D, F8>(a, hv, split, fs, Lh, Mh, rowbase, kg, qs, part, offs, pm, &s_fail);
   __syncthreads();
 
   // ---- column sums from the registers
@@ -1066,12 +1096,18 @@ static void launch_fused(const ScoreArgs& a, int heads, hipStream_t st) {
   const size_t ldsf = ((size_t)a.mpad + 4 * 32) * (D + 8) * 2 + ((size_t)4 * a.mpad * 2 + a.mpad + 512) * sizeof(float);
   ScoreArgs b = a;
   b.head0 = a.head0 * a.rb_count;
+  const dim3 grid(a.fsplit, vheads);
   if (a.mpad == 32) {
-    hipLaunchKernelGGL((score_fused_kernel<D, 1, FUSED_NS1>), dim3(a.fsplit, vheads), dim3(SCORE_THREADS), ldsf, st, b);
+    if (a.k_fp8) hipLaunchKernelGGL((score_fused_kernel<D, 1, FUSED_NS1, true>), grid, dim3(SCORE_THREADS), ldsf, st, b);
+    else hipLaunchKernelGGL((score_fused_kernel<D, 1, FUSED_NS1>), grid, dim3(SCORE_THREADS), ldsf, st, b);
+  } else if (a.k_fp8) {
+    if (ldsf > 48 * 1024)
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_fused_kernel<D, 2, FUSED_NS2, true>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)ldsf);
+    hipLaunchKernelGGL((score_fused_kernel<D, 2, FUSED_NS2, true>), grid, dim3(SCORE_THREADS), ldsf, st, b);
   } else {
     if (ldsf > 48 * 1024)
       (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_fused_kernel<D, 2, FUSED_NS2>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)ldsf);
-    hipLaunchKernelGGL((score_fused_kernel<D, 2, FUSED_NS2>), dim3(a.fsplit, vheads), dim3(SCORE_THREADS), ldsf, st, b);
+    hipLaunchKernelGGL((score_fused_kernel<D, 2, FUSED_NS2>), grid, dim3(SCORE_THREADS), ldsf, st, b);
   }
   if (a.rb_count > 1) {
     const long long n = (long long)heads * a.L;
@@ -1124,6 +1160,7 @@ hipError_t launch_score_ragged(const Dims& dm, const madakv_config& c, const voi
   a.mpad = fused_mpad(dm); a.nsplit = 0; a.nmerge = 0; a.chunk = 0; a.head0 = 0;
   a.fsplit = ragged_split(dm, longest_rows);
   a.xgroups = 0; a.xstride = (long long)a.fsplit * fused_mpad(dm);
+  a.k_fp8 = c.cache_fp8 ? 1 : 0;                  // the reduced cache is what is scored here
   const char* spin = getenv("MADAKV_SCORE_SPIN_LIMIT");
   a.spin_limit = spin && atoi(spin) > 0 ? atoi(spin) : FUSED_SPIN_LIMIT;
   const float scale = c.softmax_scale > 0.f ? c.softmax_scale : 1.0f / sqrtf((float)dm.d);
@@ -1141,11 +1178,17 @@ hipError_t launch_score_ragged(const Dims& dm, const madakv_config& c, const voi
     const long long nx = (long long)vheads * a.fsplit * a.mpad;
     if (a.fsplit > 1) hipLaunchKernelGGL(score_xchg_init_kernel, dim3((unsigned)((nx + 255) / 256)), dim3(256), 0, st, a.xchg, nx);
     const size_t ldsf = ((size_t)a.mpad + 4 * 32) * (dm.d + 8) * 2 + ((size_t)4 * a.mpad * 2 + a.mpad + 512) * sizeof(float);
-    if (dm.d == 128) {
+    const dim3 grid(a.fsplit, vheads);
+    if (dm.d == 128 && a.k_fp8) {
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_fused_kernel<128, 2, FUSED_NS2, true>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)ldsf);
+      hipLaunchKernelGGL((score_fused_kernel<128, 2, FUSED_NS2, true>), grid, dim3(SCORE_THREADS), ldsf, st, b);
+    } else if (dm.d == 128) {
       (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_fused_kernel<128, 2, FUSED_NS2>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)ldsf);
-      hipLaunchKernelGGL((score_fused_kernel<128, 2, FUSED_NS2>), dim3(a.fsplit, vheads), dim3(SCORE_THREADS), ldsf, st, b);
+      hipLaunchKernelGGL((score_fused_kernel<128, 2, FUSED_NS2>), grid, dim3(SCORE_THREADS), ldsf, st, b);
+    } else if (a.k_fp8) {
+      hipLaunchKernelGGL((score_fused_kernel<64, 2, FUSED_NS2, true>), grid, dim3(SCORE_THREADS), ldsf, st, b);
     } else {
-      hipLaunchKernelGGL((score_fused_kernel<64, 2, FUSED_NS2>), dim3(a.fsplit, vheads), dim3(SCORE_THREADS), ldsf, st, b);
+      hipLaunchKernelGGL((score_fused_kernel<64, 2, FUSED_NS2>), grid, dim3(SCORE_THREADS), ldsf, st, b);
     }
     hipLaunchKernelGGL(score_blocks_sum_kernel, dim3((unsigned)((cache_rows + 255) / 256)), dim3(256), 0, st,
                        a.psi_part, a.psi_part_stride, a.rb_count, psi_c, cache_rows);
@@ -1175,7 +1218,7 @@ hipError_t launch_window_attn(const Dims& dm, const madakv_config& c, const void
   a.mpad = 32; a.nsplit = 0; a.nmerge = 0; a.chunk = 0; a.head0 = 0;
   a.rb_count = 1; a.psi_part = nullptr; a.psi_part_stride = 0;
   a.fsplit = win_split(dm);
-  a.xgroups = 0; a.xstride = (long long)a.fsplit * 32;
+  a.xgroups = 0; a.xstride = (long long)a.fsplit * 32; a.k_fp8 = 0;
   const char* spin = getenv("MADAKV_SCORE_SPIN_LIMIT");
   a.spin_limit = spin && atoi(spin) > 0 ? atoi(spin) : FUSED_SPIN_LIMIT;
   const float scale = c.softmax_scale > 0.f ? c.softmax_scale : 1.0f / sqrtf((float)dm.d);
@@ -1209,7 +1252,7 @@ hipError_t launch_score(const Dims& dm, const madakv_config& c, const void* q_wi
   a.psi_part = reinterpret_cast<float*>(static_cast<char*>(ws) + 256 + rowstat_bytes(dm, c.dtype) + 256 + xchg_bytes(dm, c.dtype));
   a.psi_part_stride = (long long)dm.heads * dm.L;
   a.fsplit = (!row_lse && use_fused(dm, c.dtype)) ? fused_split(dm) : 0;
-  a.xgroups = xchg_groups(a.fsplit); a.xstride = (long long)(a.fsplit + a.xgroups) * fused_mpad(dm);
+  a.xgroups = xchg_groups(a.fsplit); a.xstride = (long long)(a.fsplit + a.xgroups) * fused_mpad(dm); a.k_fp8 = 0;
   a.seg_off = nullptr; a.seg_len = nullptr;
   // (a test can force the lone-workgroup path of the one-sweep kernel from the host with a spin limit of 1)
   const char* spin = getenv("MADAKV_SCORE_SPIN_LIMIT");

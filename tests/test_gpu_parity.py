@@ -751,28 +751,34 @@ def test_paged_reduced_cache(name, P, fp8):
     flat.close(); paged.close()
 
 
-@pytest.mark.parametrize("name", ["bf16_mha", "bf16_w64", "bf16_d64_gqa2", "bf16_odd", "bf16_gqa7"])
-def test_reeviction_during_generation(name):
+@pytest.mark.parametrize("name,fp8", [("bf16_mha", 0), ("bf16_w64", 0), ("bf16_d64_gqa2", 0), ("bf16_odd", 0), ("bf16_gqa7", 0),
+                                      ("bf16_mha", 1), ("bf16_d64_gqa2", 1), ("bf16_gqa7", 1)])
+def test_reeviction_during_generation(name, fp8):
     """madakv_reevict after some decode steps, twice: every head is brought back to the length the prompt
     eviction gave it.  Stage by stage against the oracle on the GPU's own upstream values (scores within
     the psi tolerance, then masses 2e-6, budgets / surviving rows / moved K, V rows / original positions
-    bit for bit), and decode afterwards against Eq. 5 over the oracle's copy of the new cache."""
+    bit for bit), and decode afterwards against Eq. 5 over the oracle's copy of the new cache.
+    fp8: the reduced cache holds E4M3 rows; the oracle works on the values those bytes stand for."""
+    import os
     rounds = (5, 3)
     wl = small_workloads()[name].scaled(decode_steps=max(rounds))
     NL, B, H, Hq, L, W, d = wl.n_layers, wl.batch, wl.n_kv_heads, wl.n_q_heads, wl.ctx_len, wl.window, wl.head_dim
     G = Hq // H
     p = PU.oracle_params(wl)
     q, k, v, mask, masks = PU.make_inputs(wl, DEV)
-    eng = engine(wl)
+    eng = engine(wl, cache_fp8=fp8)
     eng.score(0, NL, q, k, mask); eng.allocate(0, NL); eng.select_gather(0, NL, k, v, mask)
     torch.cuda.synchronize()
     off = eng.kv_off.cpu().numpy()
     len0 = eng.kv_len.cpu().numpy().copy()
     cap = eng.capacity
+    # what cached rows stand for (float64), and what a new row becomes once it is in the cache
+    cached = (lambda t: O.dequantize_e4m3(t.cpu().numpy())) if fp8 else WL.to_f64
+    as_cached = (lambda t: O.dequantize_e4m3(O.quantize_e4m3(WL.to_f64(t)))) if fp8 else WL.to_f64
     # the oracle's view of every head: rows (float64), original positions
     heads = [(l, b, h) for l in range(NL) for b in range(B) for h in range(H)]
-    rows_k = {s: WL.to_f64(eng.k_c[off[s]:off[s] + len0[s]]) for s in heads}
-    rows_v = {s: WL.to_f64(eng.v_c[off[s]:off[s] + len0[s]]) for s in heads}
+    rows_k = {s: cached(eng.k_c[off[s]:off[s] + len0[s]]) for s in heads}
+    rows_v = {s: cached(eng.v_c[off[s]:off[s] + len0[s]]) for s in heads}
     origin = {s: eng.kept_idx[off[s]:off[s] + len0[s]].cpu().numpy().astype(np.int64) for s in heads}
     q_hist = [q[:, :, :, r] for r in range(W)]                 # queries of the tokens in the last W rows, oldest first
     out = torch.empty(NL, B, Hq, d, dtype=torch.float32, device=DEV)
@@ -785,8 +791,8 @@ def test_reeviction_during_generation(name):
             torch.cuda.synchronize()
             for s in heads:
                 l, b, h = s
-                rows_k[s] = np.concatenate([rows_k[s], WL.to_f64(dk[l, b, h])[None]])
-                rows_v[s] = np.concatenate([rows_v[s], WL.to_f64(dv[l, b, h])[None]])
+                rows_k[s] = np.concatenate([rows_k[s], as_cached(dk[l, b, h])[None]])
+                rows_v[s] = np.concatenate([rows_v[s], as_cached(dv[l, b, h])[None]])
                 origin[s] = np.concatenate([origin[s], [L + gen]])
             for (l, b, h) in heads[::5]:
                 for g in range(G):
@@ -797,8 +803,15 @@ def test_reeviction_during_generation(name):
         q_recent = torch.stack(q_hist, dim=3).contiguous()     # [NL, B, Hq, W, d]
         say(f"{name}: madakv_reevict after {T} more steps")
         eng.reevict_ws = None
-        eng.reevict(0, NL, q_recent, mask)
-        torch.cuda.synchronize()
+        lone = fp8 and T == rounds[-1]          # once with the scoring kernel's wait cut to one poll: its own-way path on E4M3 rows
+        if lone:
+            os.environ["MADAKV_SCORE_SPIN_LIMIT"] = "1"
+        try:
+            eng.reevict(0, NL, q_recent, mask)
+            torch.cuda.synchronize()
+        finally:
+            if lone:
+                del os.environ["MADAKV_SCORE_SPIN_LIMIT"]
         ws = eng.reevict_ws
         psi_g = ws[:cap * 4].view(torch.float32).cpu().numpy()
         up = lambda x: (x + 255) // 256 * 256
@@ -827,7 +840,7 @@ def test_reeviction_during_generation(name):
             assert list(bud_g[s]) == list(bud_r)
             pool_r = O.pool_scores(pg.astype(np.float64)[None], W, p.pool_k)[0].astype(np.float32).astype(np.float64)
             sel_r = O.select_n(pool_r, rowmod, bud_r, n, W, p.mpa_mode)
-            got_k = WL.to_f64(eng.k_c[off[s]:off[s] + len0[s]]); got_v = WL.to_f64(eng.v_c[off[s]:off[s] + len0[s]])
+            got_k = cached(eng.k_c[off[s]:off[s] + len0[s]]); got_v = cached(eng.v_c[off[s]:off[s] + len0[s]])
             np.testing.assert_array_equal(got_k, rows_k[s][sel_r])
             np.testing.assert_array_equal(got_v, rows_v[s][sel_r])
             np.testing.assert_array_equal(kept_all[off[s]:off[s] + len0[s]], origin[s][sel_r])
@@ -837,7 +850,7 @@ def test_reeviction_during_generation(name):
     eng.decode_attn(0, NL, dq, dk, dv, out)
     torch.cuda.synchronize()
     for (l, b, h) in heads:
-        kc = np.concatenate([rows_k[(l, b, h)], WL.to_f64(dk[l, b, h])[None]]); vc = np.concatenate([rows_v[(l, b, h)], WL.to_f64(dv[l, b, h])[None]])
+        kc = np.concatenate([rows_k[(l, b, h)], as_cached(dk[l, b, h])[None]]); vc = np.concatenate([rows_v[(l, b, h)], as_cached(dv[l, b, h])[None]])
         for g in range(G):
             ref = O.attend(WL.to_f64(dq[l, b, h * G + g]), kc, vc, p.scale)
             assert np.abs(out[l, b, h * G + g].cpu().numpy() - ref).max() <= PU.DECODE_ATOL
@@ -848,7 +861,7 @@ def test_reeviction_refusals():
     wl = small_workloads()["bf16_mha"].scaled(n_layers=1, batch=1, decode_steps=2)
     q, k, v, mask, masks = PU.make_inputs(wl, DEV)
     qr = q.clone()
-    for kw, status in ((dict(page_rows=16), -7), (dict(cache_fp8=1), -7), (dict(budget=wl.ctx_len), -3)):
+    for kw, status in ((dict(page_rows=16), -7), (dict(budget=wl.ctx_len), -3)):
         eng = engine(wl, **kw)
         eng.reevict_ws = torch.empty(MB.madakv_reevict_workspace_bytes(eng.h, 1), dtype=torch.uint8, device=DEV)
         with pytest.raises(MB.MadaKVError) as ei:
