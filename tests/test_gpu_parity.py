@@ -425,11 +425,16 @@ VARIANTS = {
 }
 
 
-@pytest.mark.parametrize("variant", list(VARIANTS.keys()))
-def test_alternative_readings_and_baselines(variant):
-    """The switchable readings / baseline policies, stage by stage against their oracle branch."""
+@pytest.mark.parametrize("variant,shape", [(v, "small") for v in VARIANTS] +
+                         [(v, "long") for v in ("text_first", "average_pool", "shares_over_all_columns")])
+def test_alternative_readings_and_baselines(variant, shape):
+    """The switchable readings / baseline policies, stage by stage against their oracle branch.  shape "long": heads of
+    four 16384-candidate chunks, where statistics and selection run chunk-parallel."""
     kw = VARIANTS[variant]
     wl = small_workloads()["bf16_mha"]
+    if shape == "long":
+        wl = wl.scaled(name="bf16_long_ctx", n_layers=2, batch=1, n_q_heads=2, n_kv_heads=2, ctx_len=50001, budget=3000,
+                       n_images=3, decode_steps=1)
     if "pool_k" in kw:
         wl = wl.scaled(pool_k=kw["pool_k"])
     NL, B, H, L, W = wl.n_layers, wl.batch, wl.n_kv_heads, wl.ctx_len, wl.window
@@ -450,7 +455,7 @@ def test_alternative_readings_and_baselines(variant):
         for l in range(NL):
             psi_in = psi_g[l, b].astype(np.float64)
             w_o, k_o, _ = O.modality_stats(psi_in, masks[b], W, p.theta, p.share_mode)
-            np.testing.assert_allclose(w_g[l, b], w_o, rtol=2e-6)
+            PU.assert_masses_close(w_g[l, b], w_o, L)
             pool_o = O.pool_scores(psi_in, W, p.pool_k, p.pool_mode)
             if p.pool_mode == 0:
                 np.testing.assert_array_equal(pool_g[l, b], pool_o.astype(np.float32))
@@ -478,10 +483,14 @@ def test_alternative_readings_and_baselines(variant):
     eng.close()
 
 
-@pytest.mark.parametrize("M,mpa", [(3, 1), (4, 1), (3, 2), (3, 0), (4, 3)])
-def test_more_than_two_modalities(M, mpa):
-    """Eq. 6, 8, 9 and the selection with M modalities, stage by stage against the oracle."""
+@pytest.mark.parametrize("M,mpa,long_ctx", [(3, 1, 0), (4, 1, 0), (3, 2, 0), (3, 0, 0), (4, 3, 0), (3, 1, 1), (4, 1, 1)])
+def test_more_than_two_modalities(M, mpa, long_ctx):
+    """Eq. 6, 8, 9 and the selection with M modalities, stage by stage against the oracle.  long_ctx: heads of four
+    16384-candidate chunks (chunk-parallel statistics and selection, the 4-modality build of those kernels)."""
     wl = small_workloads()["bf16_mha"].scaled(name=f"bf16_m{M}", n_images=5, ctx_len=4100, budget=500, n_modalities=M)
+    if long_ctx:
+        wl = wl.scaled(name=f"bf16_m{M}_long", n_layers=1, batch=1, n_q_heads=2, n_kv_heads=2, ctx_len=50001, budget=3000,
+                       n_images=6, decode_steps=1)
     NL, B, H, L, W = wl.n_layers, wl.batch, wl.n_kv_heads, wl.ctx_len, wl.window
     nc = L - W
     p = PU.oracle_params(wl, n_modalities=M, mpa_mode=mpa)
