@@ -384,9 +384,12 @@ def main():
             entry("gather_kernel (+ segment layout and selection kernels)", gather_bytes + 5 * NL * B * H * (L - W), sg_ms,
                   "algorithmic bytes = kept K,V rows read and written + pooled scores and mask read; a plain copy reaches "
                   "5.2-5.7 TB/s on this machine", None),
-            entry("gather_kernel alone", gather_bytes, read_profile(prof, "gather_total_us_per_eviction") / 1e3
-                  if read_profile(prof, "gather_total_us_per_eviction") else sg_ms,
-                  "duration from the committed rocprofv3 trace when present (else the call above); copy ceiling 5.2-5.7 TB/s", None),
+            entry("gather_kernel launches of an eviction (kernel time only)", gather_bytes,
+                  read_profile(prof, "gather_total_us_per_eviction") / 1e3 if read_profile(prof, "gather_total_us_per_eviction") else sg_ms,
+                  "duration summed over an eviction's gather launches in the committed rocprofv3 trace when present (else the call "
+                  "above); in madakv_evict three of the four run beside the next group's statistics and selection kernels and "
+                  "hold 4 workgroups per compute unit; one gather over all layers with nothing beside it takes 1.49 ms "
+                  "(0.72 of peak); copy ceiling 5.2-5.7 TB/s", None),
             dict(roofline, kernel="decode_attn_kernel + decode_merge_kernel (one call per layer)",
                  note="a plain streaming read of the same 135 MB takes 22.6-25.6 us on this machine (0.66-0.75 of peak)",
                  kernel_only_us_from_profile=read_profile(prof, "decode_attn_kernel_avg_us"),
