@@ -317,7 +317,12 @@ int32_t madakv_page_table(const madakv_handle* h, const int32_t** table, int32_t
  *     enqueued in that case.
  *   - Every call on one GPU, from any handle, uses the same array: calls that may run
  *     concurrently on one GPU (different streams) race on it and must not be issued.  Nothing in
- *     the array has to survive between calls. */
+ *     the array has to survive between calls.
+ *   - On a stream under graph capture (this call or madakv_decode_attn) the launch is sized for every
+ *     row the segments have room for, so that the captured step can be replayed while the heads
+ *     grow; each replay appends a row like a call would, but the library's count of appended rows
+ *     only sees the capture itself: the caller must not replay beyond max_new_tokens rows per
+ *     head, and takes up eager calls again only after a new eviction or re-eviction. */
 #define MADAKV_STATIC_SCRATCH_BYTES ((size_t)8 << 20)
 int32_t madakv_decode_attn_static(madakv_handle* h, int32_t layer0, int32_t n,
                                   const void* q, const void* k_new, const void* v_new,

@@ -200,17 +200,20 @@ hipError_t publish_maxlen(madakv_handle* h, int layer0, int n, hipStream_t st, h
 // Upper bound on the rows of any head of layers [layer0, layer0 + n) after this call's append:
 // from the lengths the eviction produced when they are known to have reached the host, the
 // worst case otherwise.
-int longest_rows(madakv_handle* h, int layer0, int n) {
+// replayed: the launch may run again later without coming through here (a stream under graph capture): the bound
+// then covers every row the segments have room for, not only the rows of this step.
+int longest_rows(madakv_handle* h, int layer0, int n, bool replayed = false) {
   const madakv_config& c = h->cfg;
   const int worst = c.ctx_len + c.max_new_tokens;
   bool pending = false;
   for (int l = layer0; l < layer0 + n; ++l) pending = pending || h->maxlen_state[l] == 1;
-  if (pending && hipEventQuery(h->maxlen_event) == hipSuccess)
+  if (pending && !replayed && hipEventQuery(h->maxlen_event) == hipSuccess)       // (no event query on a capturing stream's behalf)
     for (auto& sflag : h->maxlen_state) if (sflag == 1) sflag = 2;
   int mx = 0;
   for (int l = layer0; l < layer0 + n; ++l) {
     if (h->maxlen_state[l] != 2) return worst;
-    for (int b = 0; b < c.batch; ++b) mx = std::max(mx, h->h_maxlen[(size_t)l * c.batch + b] + h->appended[l] + 1);
+    const int grown = replayed ? c.max_new_tokens : h->appended[l] + 1;
+    for (int b = 0; b < c.batch; ++b) mx = std::max(mx, h->h_maxlen[(size_t)l * c.batch + b] + grown);
   }
   return std::min(worst, mx);
 }
@@ -248,7 +251,12 @@ int32_t decode_impl(madakv_handle* h, int32_t layer0, int32_t n,
   if ((k_new == nullptr) != (v_new == nullptr)) return MADAKV_ERR_INVALID_ARG;
   if (k_new && (!aligned16(k_new) || !aligned16(v_new))) return MADAKV_ERR_INVALID_ARG;
   Dims dm = make_dims(h->cfg, n);
-  const int longest = longest_rows(h, layer0, n);
+  // Under graph capture the launch is sized once and replayed while the heads grow: the grid (and the share of the
+  // workspace) then covers all the rows the segments have room for.
+  hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+  const bool replayed = hipStreamIsCapturing(reinterpret_cast<hipStream_t>(stream), &capturing) != hipSuccess ||
+                        capturing != hipStreamCaptureStatusNone;
+  const int longest = longest_rows(h, layer0, n, replayed);
   // a caller's workspace is sized for the worst case; the static one must hold what this launch uses
   const size_t need = ws_is_static ? decode_ws_bytes_for(dm, h->cfg, longest) : decode_ws_bytes(dm, h->cfg);
   if (ws_bytes < need) return MADAKV_ERR_WORKSPACE_TOO_SMALL;

@@ -117,3 +117,56 @@ def test_static_scratch_refuses_what_does_not_fit():
         eng.decode_attn_static(0, 1, q, None, None, out)
     assert ei.value.status == -4
     eng.close()
+
+
+def test_captured_decode_step_replays_while_heads_grow():
+    """The use the entry point names first: a decode step (one call per layer) captured into a HIP graph and replayed.
+    Heads of 2300 rows that grow past 2304 during the replays, so the captured launch has to cover a chunk that did
+    not exist at capture time.  Every replay (with eager work and a synchronisation in between) against an engine that
+    takes the same steps with ordinary calls: outputs bit for bit, lengths and the appended rows exactly."""
+    wl = WL.CONFIGS["llava_layer"].scaled(name="na_graph", n_layers=2, batch=1, n_q_heads=3, n_kv_heads=3, ctx_len=3000,
+                                          budget=2300, n_images=2, decode_steps=8)
+    NL = wl.n_layers
+    eager, graphed = evicted_engine(wl, hcc_mode=0), evicted_engine(wl, hcc_mode=0)
+    assert (graphed.kv_len.cpu().numpy() == wl.budget).all()
+    shape = (NL, wl.batch, wl.n_q_heads, wl.head_dim)
+    out_e = torch.full(shape, float("nan"), dtype=torch.float32, device=DEV)
+    out_g = torch.full(shape, float("nan"), dtype=torch.float32, device=DEV)
+    # one ordinary step on both (the length of the longest head reaches the host meanwhile)
+    dq, dk, dv = step_inputs(wl, 0)
+    for eng, out in ((eager, out_e), (graphed, out_g)):
+        for l in range(NL):
+            eng.decode_attn_static(l, 1, dq[l:l + 1], dk[l:l + 1], dv[l:l + 1], out[l:l + 1])
+    torch.cuda.synchronize()
+    assert torch.equal(out_e, out_g)
+    # the step as a graph: inputs at fixed addresses
+    sq, sk, sv = dq.clone(), dk.clone(), dv.clone()
+    g = torch.cuda.CUDAGraph()
+    say("capturing one decode step (two layers) on the static scratch")
+    with torch.cuda.graph(g):
+        for l in range(NL):
+            graphed.decode_attn_static(l, 1, sq[l:l + 1], sk[l:l + 1], sv[l:l + 1], out_g[l:l + 1])
+    torch.cuda.synchronize()
+    assert (graphed.kv_len.cpu().numpy() == wl.budget + 1).all(), "capturing runs nothing"
+    for step in range(1, 7):                                   # lengths 2301 .. 2307: a tenth chunk appears on the way
+        dq, dk, dv = step_inputs(wl, step)
+        sq.copy_(dq); sk.copy_(dk); sv.copy_(dv)               # eager work between the replays
+        out_g.fill_(float("nan"))
+        torch.cuda.synchronize()
+        say(f"replay {step}: head length {wl.budget + step}")
+        g.replay()
+        for l in range(NL):
+            eager.decode_attn_static(l, 1, dq[l:l + 1], dk[l:l + 1], dv[l:l + 1], out_e[l:l + 1])
+        torch.cuda.synchronize()
+        assert torch.equal(out_g, out_e), (step, float((out_g - out_e).abs().max()))
+        assert torch.equal(graphed.kv_len, eager.kv_len) and int(graphed.kv_len.max()) == wl.budget + step + 1
+    off, ln = eager.kv_off.cpu().numpy().ravel(), eager.kv_len.cpu().numpy().ravel()
+    for o, n in zip(off, ln):                                   # the rows in use (the room beyond them was never written)
+        assert torch.equal(graphed.k_c[o:o + n], eager.k_c[o:o + n]) and torch.equal(graphed.v_c[o:o + n], eager.v_c[o:o + n])
+    want = oracle_outputs(eager, wl, dq)                        # the last step's queries over the cache as it is now ...
+    got = torch.full(shape, float("nan"), dtype=torch.float32, device=DEV)
+    for l in range(NL):
+        eager.decode_attn_static(l, 1, dq[l:l + 1], None, None, got[l:l + 1])   # ... attended once more without appending
+    torch.cuda.synchronize()
+    assert np.abs(got.cpu().numpy() - want).max() <= PU.DECODE_ATOL
+    eager.close(); graphed.close()
