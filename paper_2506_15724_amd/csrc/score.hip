@@ -507,6 +507,250 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 }
 
 // ------------------------------------------------------------------------------------
+// The same two sweeps with the keys fetched straight into LDS (global_load_lds, 16 bytes per lane): no
+// register holds a key on its way, so three tiles of DMA_TK keys form a ring with two tiles in flight
+// while the third is multiplied, and two row blocks per wave fit 256 registers in both sweeps (two
+// workgroups of four waves per CU, in step with nobody: one's contractions run under the other's
+// vector arithmetic).
+// A wave's load instruction fills 1 KB of consecutive LDS (lane i at base + 16 i), so rows cannot be
+// padded; instead the 16-byte pieces of a row are stored permuted, piece c of row r at slot
+// c ^ (r mod pieces per row): the lane that writes slot s of row r fetches piece s ^ (r mod ...) from
+// memory (a row's pieces are still one contiguous stretch per 16 lanes), and the operand reads of 16
+// lanes with consecutive rows fall into 16 different slots.
+// The compiler cannot tell which LDS bytes such a load writes and would wait for ALL outstanding loads
+// before every LDS access it sees; so inside the loop every LDS access and every wait is written out:
+// loads are counted (they complete in order), "tile t is there" is s_waitcnt vmcnt(loads of one tile),
+// and the barrier that follows also tells that everybody is done with the tile the next load overwrites.
+// ------------------------------------------------------------------------------------
+constexpr int DMA_NBUF = 3;
+
+typedef __attribute__((address_space(3))) void* lds_void_ptr_t;
+typedef const __attribute__((address_space(1))) void* global_void_ptr_t;
+
+template <int D, int NW, int NRB, int DMA_TK, int BS, int PASS>   // NW waves of NRB row blocks each; tiles of DMA_TK keys; the vector arithmetic runs on BS subtiles at a time
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void score_wide_dma_kernel(ScoreArgs a) {
+  constexpr int NT = NW * 64;
+  constexpr int KS = D / 16;                  // MFMA k-steps
+  constexpr int PPR = D / 8;                  // 16-byte pieces per row
+  constexpr int ROWB = D * 2;                 // bytes per row
+  constexpr int LPT = DMA_TK * PPR / NT;              // load instructions per thread and tile (each fills 1 KB per wave)
+  constexpr int NSUB = DMA_TK / 32;
+  constexpr int TILEB = DMA_TK * ROWB;
+  static_assert((LPT == 4 || LPT == 2 || LPT == 1) && NSUB % BS == 0 && (PASS == 1 || DMA_TK == 64), "the waits below are written for these");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  unsigned char* ring = smem;                                              // [DMA_NBUF][DMA_TK][ROWB], pieces permuted
+  float* offs = reinterpret_cast<float*>(smem + DMA_NBUF * TILEB);         // sweep 2: [mpad]
+  float* red = offs + a.mpad;                                              // sweep 2: [2][NW][DMA_TK]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int split = blockIdx.x;
+  const int head = a.head0 + blockIdx.y;
+  const int kvh = head % a.H;
+  const long long lb = head / a.H;            // (layer, batch) index
+  const uint16_t* qg = reinterpret_cast<const uint16_t*>(a.q_win) + (lb * a.H + kvh) * (long long)a.G * a.W * D;
+  const unsigned char* kg = reinterpret_cast<const unsigned char*>(a.k) + (long long)head * a.L * ROWB;
+  const int chunk0 = split * a.chunk;
+  const int chunk1 = min(a.L, chunk0 + a.chunk);
+  const int ntiles = (chunk1 - chunk0 + DMA_TK - 1) / DMA_TK;
+  const int half = lane >> 5, col = lane & 31;
+  const int MB = a.mpad / 32;
+  const int rb0 = wave * NRB;                  // first row block of this wave
+  const int first_masked = a.L - a.W + 1;      // keys below this are visible to every proxy row
+
+  // sweep 2: the rows' offsets (ordinary LDS traffic, so before the first key is on its way)
+  float st_m[NRB][16], st_l[NRB][16];          // sweep 1: running (max in accumulator units, sum); sweep 2: st_m holds the rows' offsets
+  if (PASS == 2) {
+    const float* rs = a.rowstat + (long long)head * a.nsplit * a.mpad * 2;
+    for (int r = tid; r < a.mpad; r += NT) {
+      float m = NEG_BIG, l = 0.f;
+      if (a.lse) {                                               // the caller's prefill attention already has the row normalisers
+        if (r < a.M) { m = a.lse[(lb * a.H + kvh) * (long long)a.G * a.W + r] * 1.4426950408889634f; l = 1.f; }
+      } else {
+        for (int s = 0; s < a.nmerge; ++s) merge_ml(m, l, rs[(s * a.mpad + r) * 2], rs[(s * a.mpad + r) * 2 + 1]);
+      }
+      offs[r] = (r < a.M) ? m + log2f(l) : __builtin_inff();     // padding rows contribute exp2(-inf) = 0
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int b = 0; b < NRB; ++b)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const int row = (rb0 + b) * 32 + (j >> 2) * 8 + half * 4 + (j & 3);     // (a block past the last: rows that count for nothing)
+      st_m[b][j] = (PASS == 2) ? (row < a.mpad ? offs[row] : __builtin_inff()) : NEG_BIG;
+      st_l[b][j] = 0.f;
+    }
+  __syncthreads();                             // (the last ordinary LDS access of the kernel)
+
+  // tile T of the chunk -> ring slot T mod 3.  Load j of wave w fills bytes [(w LPT + j) 1024, + 1024) of the slot:
+  // lane i writes piece P = (w LPT + j) 64 + i, i.e. slot P mod PPR of row P / PPR, and fetches that row's piece
+  // (P mod PPR) ^ (row mod PPR).  Rows past the head's end: its last row (masked where it is used).
+  const uint32_t ring_lds = (uint32_t)(uintptr_t)ring;
+#define MADAKV_DMA_ISSUE(T)                                                                          \
+  {                                                                                                  \
+    const int tt = (T);                                                                              \
+    const int lt0 = chunk0 + tt * DMA_TK;                                                            \
+    const uint32_t slot_lds = ring_lds + (uint32_t)(tt % DMA_NBUF) * TILEB;                          \
+    _Pragma("unroll") for (int j = 0; j < LPT; ++j) {                                                \
+      const int piece = (wave * LPT + j) * 64 + lane;                                                \
+      const int row = piece / PPR;                                                                   \
+      const int lkey = min(lt0 + row, a.L - 1);                                                      \
+      const unsigned char* src = kg + (long long)lkey * ROWB + (((piece % PPR) ^ (row % PPR)) * 16); \
+      const uint32_t dst = __builtin_amdgcn_readfirstlane(slot_lds + (uint32_t)(wave * LPT + j) * 1024u); \
+      __builtin_amdgcn_global_load_lds((global_void_ptr_t)(uintptr_t)src, (lds_void_ptr_t)(uintptr_t)dst, 16, 0, 0); \
+    }                                                                                                \
+  }
+  MADAKV_DMA_ISSUE(0)
+  MADAKV_DMA_ISSUE(min(1, ntiles - 1))
+
+  // Q fragments of the wave's rows straight from memory (rows past M: zeros); a lane holds, for k-step ks,
+  // elements [half * D/2 + ks * 8, + 8) of row `col` of the block
+  bf16x8_t areg[NRB][KS];
+#pragma unroll
+  for (int b = 0; b < NRB; ++b) {
+    const int row = (rb0 + b) * 32 + col;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      uint4 val = make_uint4(0, 0, 0, 0);
+      if (row < a.M) val = *reinterpret_cast<const uint4*>(qg + (long long)row * D + half * (D / 2) + ks * 8);
+      areg[b][ks] = __builtin_bit_cast(bf16x8_t, val);
+    }
+  }
+  // where this lane's operand pieces of row `col` of a subtile sit, relative to the subtile's first byte
+  uint32_t frag_off[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) frag_off[ks] = (uint32_t)(col * ROWB + (((half * KS + ks) ^ (col % PPR)) * 16));
+  const uint32_t red_lds = (uint32_t)(uintptr_t)red;
+
+  for (int t = 0; t < ntiles; ++t) {
+    // tile t has landed (the loads of tile t + 1 may still be out), this wave's LDS stores of the last trip are
+    // done; after the barrier that holds for every wave, and nobody reads tile t - 1 any more
+    if (LPT == 4) asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else if (LPT == 2) asm volatile("s_waitcnt vmcnt(2) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(1) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    MADAKV_DMA_ISSUE(min(t + 2, ntiles - 1))   // into the slot of tile t - 1 (past the end: the last tile once more, which keeps the count of loads in flight)
+    if (PASS == 2 && t > 0 && tid < DMA_TK) {  // the column sums of tile t - 1, the waves' shares added in wave order
+      const int key = chunk0 + (t - 1) * DMA_TK + tid;
+      const uint32_t r4 = red_lds + (uint32_t)((((t - 1) & 1) * NW * DMA_TK + tid) * 4);
+      static_assert(NW == 4 || PASS == 1, "sweep 2 adds four waves' shares");
+      float c0, c1, c2, c3;
+      asm volatile("ds_read_b32 %0, %4\n\tds_read_b32 %1, %4 offset:256\n\tds_read_b32 %2, %4 offset:512\n\tds_read_b32 %3, %4 offset:768\n\ts_waitcnt lgkmcnt(0)"
+                   : "=&v"(c0), "=&v"(c1), "=&v"(c2), "=&v"(c3) : "v"(r4) : "memory");
+      if (key < chunk1) __builtin_nontemporal_store(((c0 + c1) + c2) + c3, a.psi + ((long long)head * a.L + key));
+    }
+    const uint32_t tile_lds = ring_lds + (uint32_t)(t % DMA_NBUF) * TILEB;
+    const int tile_end = chunk0 + (t + 1) * DMA_TK;
+    const bool tail = tile_end > first_masked || tile_end > chunk1;
+
+    // the sweep's vector arithmetic runs on the BS logits a lane holds of every row after the contractions of BS
+    // subtiles.  Sweep 1 keeps the running maximum in accumulator units (scale > 0): per row and batch one
+    // rescaling of the sum and one exp2 per logit.  A row that has seen no key yet holds NEG_BIG and a meaningless,
+    // finite sum, which the first real key (and any merge with real statistics) multiplies by exp2(-huge) = 0.
+    // In a tail tile (it holds keys that some proxy row must not see: the last W - 1 keys of the head, keys past
+    // the chunk's end) such logits become NEG_BIG.
+#define MADAKV_DMA_VECTOR(TAIL)                                                                      \
+    _Pragma("unroll") for (int b = 0; b < NRB; ++b) {                                                \
+      _Pragma("unroll") for (int j = 0; j < 16; ++j) {                                               \
+        float x[BS];                                                                                 \
+        _Pragma("unroll") for (int u = 0; u < BS; ++u) {                                             \
+          x[u] = acc[u][b][j];                                                                       \
+          if (TAIL) {                                                                                \
+            const int key = chunk0 + t * DMA_TK + (s0 + u) * 32 + col;                               \
+            const int row = (rb0 + b) * 32 + (j >> 2) * 8 + half * 4 + (j & 3);                      \
+            const int pos = a.L - a.W + (row % a.W);                                                 \
+            const bool valid = (key < chunk1) && (key <= pos) && (row < a.M);                        \
+            x[u] = valid ? x[u] : NEG_BIG;                                                           \
+          }                                                                                          \
+        }                                                                                            \
+        if (PASS == 1) {                                                                             \
+          float mn = st_m[b][j];                                                                     \
+          _Pragma("unroll") for (int u = 0; u < BS; ++u) mn = fmaxf(mn, x[u]);                       \
+          float l = st_l[b][j] * fast_exp2((st_m[b][j] - mn) * a.scale_log2);                        \
+          const float ms = mn * a.scale_log2;                                                        \
+          _Pragma("unroll") for (int u = 0; u < BS; ++u) l += fast_exp2(fmaf(x[u], a.scale_log2, -ms)); \
+          st_m[b][j] = mn; st_l[b][j] = l;                                                           \
+        } else {                                                                                     \
+          _Pragma("unroll") for (int u = 0; u < BS; ++u) colsum[u] += fast_exp2(fmaf(x[u], a.scale_log2, -st_m[b][j])); \
+        }                                                                                            \
+      }                                                                                              \
+    }
+#pragma unroll 1
+    for (int s0 = 0; s0 < NSUB; s0 += BS) {
+      f32x16_t acc[BS][NRB];
+      float colsum[BS];
+#pragma unroll
+      for (int u = 0; u < BS; ++u) colsum[u] = 0.f;
+#pragma unroll
+      for (int u = 0; u < BS; ++u) {
+        bf16x8_t bfrag[KS];
+        const uint32_t sub_lds = tile_lds + (uint32_t)(s0 + u) * 32 * ROWB;
+        if (KS == 8) {
+          asm volatile("ds_read_b128 %0, %8\n\tds_read_b128 %1, %9\n\tds_read_b128 %2, %10\n\tds_read_b128 %3, %11\n\t"
+                       "ds_read_b128 %4, %12\n\tds_read_b128 %5, %13\n\tds_read_b128 %6, %14\n\tds_read_b128 %7, %15\n\t"
+                       "s_waitcnt lgkmcnt(0)"
+                       : "=&v"(bfrag[0]), "=&v"(bfrag[1]), "=&v"(bfrag[2]), "=&v"(bfrag[3]), "=&v"(bfrag[4 % KS]), "=&v"(bfrag[5 % KS]), "=&v"(bfrag[6 % KS]), "=&v"(bfrag[7 % KS])
+                       : "v"(sub_lds + frag_off[0]), "v"(sub_lds + frag_off[1]), "v"(sub_lds + frag_off[2]), "v"(sub_lds + frag_off[3]),
+                         "v"(sub_lds + frag_off[4 % KS]), "v"(sub_lds + frag_off[5 % KS]), "v"(sub_lds + frag_off[6 % KS]), "v"(sub_lds + frag_off[7 % KS])
+                       : "memory");
+        } else {
+          asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %5\n\tds_read_b128 %2, %6\n\tds_read_b128 %3, %7\n\t"
+                       "s_waitcnt lgkmcnt(0)"
+                       : "=&v"(bfrag[0]), "=&v"(bfrag[1]), "=&v"(bfrag[2]), "=&v"(bfrag[3])
+                       : "v"(sub_lds + frag_off[0]), "v"(sub_lds + frag_off[1]), "v"(sub_lds + frag_off[2]), "v"(sub_lds + frag_off[3])
+                       : "memory");
+        }
+#pragma unroll
+        for (int b = 0; b < NRB; ++b) {
+          acc[u][b] = f32x16_t{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks)
+            acc[u][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(areg[b][ks], bfrag[ks], acc[u][b], 0, 0, 0);
+        }
+      }
+      if (tail) { MADAKV_DMA_VECTOR(true) } else { MADAKV_DMA_VECTOR(false) }
+      if (PASS == 2) {
+#pragma unroll
+        for (int u = 0; u < BS; ++u) {
+          const float cs = colsum[u] + __shfl_xor(colsum[u], 32, 64);
+          const uint32_t dst = red_lds + (uint32_t)((((t & 1) * NW + wave) * DMA_TK + (s0 + u) * 32 + col) * 4);
+          if (half == 0) asm volatile("ds_write_b32 %0, %1" :: "v"(dst), "v"(cs) : "memory");
+        }
+      }
+    }
+#undef MADAKV_DMA_VECTOR
+  }
+#undef MADAKV_DMA_ISSUE
+  // nothing may still be on its way into this workgroup's LDS when it ends
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+
+  if (PASS == 2) {
+    if (tid < DMA_TK) {
+      const int key = chunk0 + (ntiles - 1) * DMA_TK + tid;
+      const uint32_t r4 = red_lds + (uint32_t)((((ntiles - 1) & 1) * NW * DMA_TK + tid) * 4);
+      float c0, c1, c2, c3;
+      asm volatile("ds_read_b32 %0, %4\n\tds_read_b32 %1, %4 offset:256\n\tds_read_b32 %2, %4 offset:512\n\tds_read_b32 %3, %4 offset:768\n\ts_waitcnt lgkmcnt(0)"
+                   : "=&v"(c0), "=&v"(c1), "=&v"(c2), "=&v"(c3) : "v"(r4) : "memory");
+      if (key < chunk1) __builtin_nontemporal_store(((c0 + c1) + c2) + c3, a.psi + ((long long)head * a.L + key));
+    }
+  } else {
+    // per row: maximum over the 32 key columns of the half, sums rescaled to it and added
+    float* rs = a.rowstat + ((long long)head * a.nsplit + split) * a.mpad * 2;
+#pragma unroll
+    for (int b = 0; b < NRB; ++b) {
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const float m = half_reduce<0>(st_m[b][j]);
+        const float l = half_reduce<1>(st_l[b][j] * fast_exp2((st_m[b][j] - m) * a.scale_log2));
+        if (rb0 + b < MB && col == 0) {
+          const int row = (rb0 + b) * 32 + (j >> 2) * 8 + half * 4 + (j & 3);
+          rs[row * 2] = m * a.scale_log2; rs[row * 2 + 1] = l;
+        }
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------
 // One sweep over K (bf16, at most two row blocks: G*W <= 64).  The logits of a workgroup's
 // keys fit in its registers: a wave keeps the D tiles of its NS subtiles (NS * NRB * 16 floats
 // per lane) instead of reducing them on the fly.  After its last subtile a workgroup knows the
@@ -1216,9 +1460,10 @@ __global__ __launch_bounds__(256) void score_combine_kernel(ScoreArgs a) {
 // chunks per head from which the merge is hoisted out of sweep 2
 constexpr int COMBINE_FROM = 8;
 #ifndef MADAKV_WIDE_WGS
-#define MADAKV_WIDE_WGS 512
+#define MADAKV_WIDE_WGS 256
+#define MADAKV_WIDE_WGS2 512
 #endif
-constexpr int WIDE_WGS = MADAKV_WIDE_WGS;   // workgroups per launch the chunking aims at with more than 64 proxy rows
+constexpr int WIDE_WGS = MADAKV_WIDE_WGS, WIDE_WGS2 = MADAKV_WIDE_WGS2;   // workgroups per launch the chunking aims at with more than 64 proxy rows: sweep 1, sweep 2
 
 static bool use_mfma(const Dims& dm, int dtype) { return dtype == MADAKV_BF16 && (dm.d == 64 || dm.d == 128); }
 
@@ -1258,8 +1503,11 @@ static int fused_blocks(const Dims& dm) { return dm.M <= 64 ? 1 : (dm.M + 63) / 
 // workgroups than the chip holds at once (512 of this kernel): half of that is the limit.
 constexpr int FUSED_MAX_SPLIT_2L = 256;
 static int xchg_groups(int split) { return split <= FUSED_MAX_SPLIT ? 0 : (split + XCHG_GROUP - 1) / XCHG_GROUP; }
+// (More than 64 proxy rows: the prompt's keys take the two-sweep kernels above, which are bound by their vector
+// arithmetic either way and twice as fast as one sweep per block of 64 rows; the ragged rows of a reduced cache
+// still go through the one-sweep kernel in blocks.)
 static bool fused_fits(const Dims& dm, int dtype) {
-  return use_mfma(dm, dtype) && dm.M <= 256 && fused_split(dm) <= FUSED_MAX_SPLIT_2L && (long long)dm.heads * fused_blocks(dm) <= 65535;
+  return use_mfma(dm, dtype) && dm.M <= 64 && fused_split(dm) <= FUSED_MAX_SPLIT_2L && dm.heads <= 65535;
 }
 static bool use_fused(const Dims& dm, int dtype) {
   const char* e = getenv("MADAKV_SCORE_TWO_SWEEPS");      // diagnostic switch: the two-sweep kernels everywhere
@@ -1344,18 +1592,37 @@ template <int D, bool WIDE8>
 static void launch_wide_pair(const ScoreArgs& a0, int heads, hipStream_t st) {
   ScoreArgs a = a0;
   dim3 grid(a.nsplit, heads);
-  // (tiles: four subtiles in sweep 1; in sweep 2 with two row blocks per wave two, which is what the registers hold)
-#ifdef MADAKV_WIDE_P2_8W
-  constexpr int NW1 = WIDE8 ? 8 : 4, NW2 = NW1, NRB2 = 1, TK1 = 128, TK2 = 128, TK = 128;
+#ifndef MADAKV_WIDE_REGS
+  // sweep 1 carries a running (max, sum) per row and lane on top of the fragments: with two row blocks per wave
+  // that does not fit 256 registers, so up to 256 rows take eight waves of one block each (one workgroup per CU,
+  // tiles of 128 keys whose four subtiles share one rescaling), sweep 2 four waves of two blocks (two per CU)
+  constexpr int NW1 = WIDE8 ? 8 : 4, NRB2 = WIDE8 ? 2 : 1;
+  constexpr int TK1 = WIDE8 ? 128 : 64, BS1 = WIDE8 ? 4 : 2, BS2 = WIDE8 ? 1 : 2;     // (what the registers hold)
+  const size_t lds1 = (size_t)DMA_NBUF * TK1 * D * 2;
+  const size_t lds2 = (size_t)DMA_NBUF * 64 * D * 2 + ((size_t)a.mpad + 2 * 4 * 64) * sizeof(float);
+  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_wide_dma_kernel<D, NW1, 1, TK1, BS1, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
+  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_wide_dma_kernel<D, 4, NRB2, 64, BS2, 2>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
+  if (!a.lse) {
+    hipLaunchKernelGGL((score_wide_dma_kernel<D, NW1, 1, TK1, BS1, 1>), grid, dim3(NW1 * 64), lds1, st, a);
+    hipLaunchKernelGGL(score_combine_kernel, dim3(heads), dim3(256), 0, st, a);
+    a.nmerge = 1;
+  }
+  // sweep 2 in chunks of its own (about two workgroups per CU); a.nsplit stays what the row statistics are laid out by
+  const int want2 = std::max(1, (WIDE_WGS2 + heads / 2) / heads);
+  const int ns2 = std::min(want2, std::max(1, a.L / 512));
+  a.chunk = ((a.L + ns2 - 1) / ns2 + 63) / 64 * 64;
+  dim3 grid2((a.L + a.chunk - 1) / a.chunk, heads);
+  hipLaunchKernelGGL((score_wide_dma_kernel<D, 4, NRB2, 64, BS2, 2>), grid2, dim3(SCORE_THREADS), lds2, st, a);
 #else
+  // (tiles: four subtiles in sweep 1; in sweep 2 with two row blocks per wave two, which is what the registers hold)
   constexpr int NW1 = WIDE8 ? 8 : 4, NW2 = 4, NRB2 = WIDE8 ? 2 : 1, TK1 = 128, TK2 = WIDE8 ? 64 : 128, TK = 128;
-#endif
   const size_t lds = (size_t)TK * (D + 8) * 2 + ((size_t)a.mpad + 2 * 8 * TK) * sizeof(float);
   if (!a.lse) {
     hipLaunchKernelGGL((score_wide_kernel<D, NW1, 1, TK1, 1>), grid, dim3(NW1 * 64), lds, st, a);
     if (a.nsplit >= COMBINE_FROM) { hipLaunchKernelGGL(score_combine_kernel, dim3(heads), dim3(256), 0, st, a); a.nmerge = 1; }
   }
   hipLaunchKernelGGL((score_wide_kernel<D, NW2, NRB2, TK2, 2>), grid, dim3(NW2 * 64), lds, st, a);
+#endif
 }
 
 // ---- the one-sweep kernel on ragged heads: the rows of a reduced cache, scored against the most recent queries
