@@ -308,210 +308,15 @@ _Pragma("unroll") \
 }
 
 // ------------------------------------------------------------------------------------
-// More than 64 proxy rows (grouped queries: G*W up to 256), the same two sweeps.  The arithmetic
-// per key grows with the rows and is what bounds these kernels (one exp2 per logit and sweep on the
-// vector unit; the contraction is a fraction of that), so the layout keeps the vector unit busy:
-// wave w owns proxy rows [32 NRB w, 32 NRB (w + 1)) for all keys of the workgroup's chunk and keeps
-// their Q fragments in registers; the four waves share the keys, which pass through ONE LDS tile of
-// WIDE_TK keys (rows padded by 16 bytes) that the whole workgroup fills: each thread fetches its
-// 16-byte pieces of the next tile into registers while the current tile is being multiplied, and
-// parks them between two barriers.  A key is fetched once per workgroup and sweep.  Sweep 1 needs no
-// merge among the waves (a row's statistics over the chunk are complete in its wave); sweep 2 adds
-// the four waves' partial column sums through LDS, in wave order, one tile behind the arithmetic.
-// ------------------------------------------------------------------------------------
-template <int D, int NW, int NRB, int WIDE_TK, int PASS>   // NW waves of NRB row blocks each; WIDE_TK keys per LDS tile
-__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void score_wide_kernel(ScoreArgs a) {
-  constexpr int NT = NW * 64;
-  constexpr int KS = D / 16;                  // MFMA k-steps
-  constexpr int RS = D + 8;                   // bf16 elements per LDS row (16 B pad)
-  constexpr int PPR = D / 8;                  // 16-byte pieces per row
-  constexpr int LPT = WIDE_TK * PPR / NT;         // pieces per thread and tile
-  constexpr int NSUB = WIDE_TK / 32;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  uint16_t* kt = reinterpret_cast<uint16_t*>(smem);                        // [WIDE_TK][RS]
-  float* offs = reinterpret_cast<float*>(kt + WIDE_TK * RS);               // sweep 2: [mpad]
-  float* red = offs + a.mpad;                                              // sweep 2: [2][NW][WIDE_TK]
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int split = blockIdx.x;
-  const int head = a.head0 + blockIdx.y;
-  const int kvh = head % a.H;
-  const long long lb = head / a.H;            // (layer, batch) index
-  const uint16_t* qg = reinterpret_cast<const uint16_t*>(a.q_win) + (lb * a.H + kvh) * (long long)a.G * a.W * D;
-  const uint16_t* kg = reinterpret_cast<const uint16_t*>(a.k) + (long long)head * a.L * D;
-  const int chunk0 = split * a.chunk;
-  const int chunk1 = min(a.L, chunk0 + a.chunk);
-  const int ntiles = (chunk1 - chunk0 + WIDE_TK - 1) / WIDE_TK;
-  const int half = lane >> 5, col = lane & 31;
-  const int MB = a.mpad / 32;
-  const int rb0 = wave * NRB;                  // first row block of this wave
-  const int first_masked = a.L - a.W + 1;      // keys below this are visible to every proxy row
-
-  u32x4_t pre[LPT];
-#define MADAKV_WIDE_LOAD(T)                                                                      \
-  {                                                                                              \
-    const int lt0 = chunk0 + (T) * WIDE_TK;                                                      \
-    _Pragma("unroll") for (int i = 0; i < LPT; ++i) {                                            \
-      const int idx = i * NT + tid;                                                   \
-      const int lkey = min(lt0 + idx / PPR, a.L - 1); /* past the end: a valid row, masked later */ \
-      pre[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(kg + (long long)lkey * D + (idx % PPR) * 8)); \
-    }                                                                                            \
-  }
-  MADAKV_WIDE_LOAD(0)
-
-  // Q fragments of the wave's rows straight from memory (rows past M: zeros); a lane holds, for k-step ks,
-  // elements [half * D/2 + ks * 8, + 8) of row `col` of the block
-  bf16x8_t areg[NRB][KS];
-#pragma unroll
-  for (int b = 0; b < NRB; ++b) {
-    const int row = (rb0 + b) * 32 + col;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      uint4 val = make_uint4(0, 0, 0, 0);
-      if (row < a.M) val = *reinterpret_cast<const uint4*>(qg + (long long)row * D + half * (D / 2) + ks * 8);
-      areg[b][ks] = __builtin_bit_cast(bf16x8_t, val);
-    }
-  }
-  if (PASS == 2) {
-    const float* rs = a.rowstat + (long long)head * a.nsplit * a.mpad * 2;
-    for (int r = tid; r < a.mpad; r += NT) {
-      float m = NEG_BIG, l = 0.f;
-      if (a.lse) {                                               // the caller's prefill attention already has the row normalisers
-        if (r < a.M) { m = a.lse[(lb * a.H + kvh) * (long long)a.G * a.W + r] * 1.4426950408889634f; l = 1.f; }
-      } else {
-        for (int s = 0; s < a.nmerge; ++s) merge_ml(m, l, rs[(s * a.mpad + r) * 2], rs[(s * a.mpad + r) * 2 + 1]);
-      }
-      offs[r] = (r < a.M) ? m + log2f(l) : __builtin_inff();     // padding rows contribute exp2(-inf) = 0
-    }
-    __syncthreads();
-  }
-
-  float st_m[NRB][16], st_l[NRB][16];          // sweep 1: running (max, sum); sweep 2: st_m holds the rows' offsets
-#pragma unroll
-  for (int b = 0; b < NRB; ++b)
-#pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      const int row = (rb0 + b) * 32 + (j >> 2) * 8 + half * 4 + (j & 3);     // (a block past the last: rows that count for nothing)
-      st_m[b][j] = (PASS == 2) ? (row < a.mpad ? offs[row] : __builtin_inff()) : NEG_BIG;
-      st_l[b][j] = 0.f;
-    }
-
-  // One tile: first the contractions of all its subtiles and the wave's row blocks (independent accumulation
-  // chains keep the matrix core busy back to back), then the sweep's vector arithmetic on the NSUB logits a lane
-  // now holds of every row.  All NRB blocks are computed: one past the last works on zero rows, and
-  // the workgroup's barriers wait for the slowest wave anyway.  The two phases are long; the other wave of the
-  // SIMD, which belongs to another workgroup and is in step with nobody here, fills the gaps.
-  // Sweep 1 keeps the running maximum in accumulator units (scale > 0): per row and tile one rescaling of the sum
-  // and one exp2 per logit.  A row that has seen no key yet holds NEG_BIG and a meaningless, finite sum, which the
-  // first real key (and any merge with real statistics) multiplies by exp2(-huge) = 0.
-  // TAIL: the tile holds keys that some proxy row must not see (the last W - 1 keys of the head, keys past the
-  // chunk's end); such logits are replaced by NEG_BIG.
-#define MADAKV_WIDE_TILE(TAIL)                                                                       \
-  {                                                                                                  \
-    float colsum[NSUB];                                                                              \
-    _Pragma("unroll") for (int sidx = 0; sidx < NSUB; ++sidx) colsum[sidx] = 0.f;                    \
-    f32x16_t acc[NSUB][NRB];                                                                         \
-    _Pragma("unroll") for (int sidx = 0; sidx < NSUB; ++sidx) {                                      \
-      const uint16_t* krow = kt + (sidx * 32 + col) * RS + half * (D / 2);                           \
-      bf16x8_t bfrag[KS];                                                                            \
-      _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) bfrag[ks] = *reinterpret_cast<const bf16x8_t*>(krow + ks * 8); \
-      _Pragma("unroll") for (int b = 0; b < NRB; ++b) {                                              \
-        acc[sidx][b] = f32x16_t{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}; \
-        _Pragma("unroll") for (int ks = 0; ks < KS; ++ks)                                            \
-          acc[sidx][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(areg[b][ks], bfrag[ks], acc[sidx][b], 0, 0, 0); \
-      }                                                                                              \
-    }                                                                                                \
-    _Pragma("unroll") for (int b = 0; b < NRB; ++b) {                                                \
-      _Pragma("unroll") for (int j = 0; j < 16; ++j) {                                               \
-        float x[NSUB];                                                                               \
-        _Pragma("unroll") for (int sidx = 0; sidx < NSUB; ++sidx) {                                  \
-          x[sidx] = acc[sidx][b][j];                                                                 \
-          if (TAIL) {                                                                                \
-            const int key = chunk0 + t * WIDE_TK + sidx * 32 + col;                                  \
-            const int row = (rb0 + b) * 32 + (j >> 2) * 8 + half * 4 + (j & 3);                      \
-            const int pos = a.L - a.W + (row % a.W);                                                 \
-            const bool valid = (key < chunk1) && (key <= pos) && (row < a.M);                        \
-            x[sidx] = valid ? x[sidx] : NEG_BIG;                                                     \
-          }                                                                                          \
-        }                                                                                            \
-        if (PASS == 1) {                                                                             \
-          float mn = st_m[b][j];                                                                     \
-          _Pragma("unroll") for (int sidx = 0; sidx < NSUB; ++sidx) mn = fmaxf(mn, x[sidx]);         \
-          float l = st_l[b][j] * fast_exp2((st_m[b][j] - mn) * a.scale_log2);                        \
-          const float ms = mn * a.scale_log2;                                                        \
-          _Pragma("unroll") for (int sidx = 0; sidx < NSUB; ++sidx) l += fast_exp2(fmaf(x[sidx], a.scale_log2, -ms)); \
-          st_m[b][j] = mn; st_l[b][j] = l;                                                           \
-        } else {                                                                                     \
-          _Pragma("unroll") for (int sidx = 0; sidx < NSUB; ++sidx) colsum[sidx] += fast_exp2(fmaf(x[sidx], a.scale_log2, -st_m[b][j])); \
-        }                                                                                            \
-      }                                                                                              \
-    }                                                                                                \
-    if (PASS == 2) {                                                                                 \
-      _Pragma("unroll") for (int sidx = 0; sidx < NSUB; ++sidx) {                                    \
-        const float cs = colsum[sidx] + __shfl_xor(colsum[sidx], 32, 64);                            \
-        if (half == 0) red[((t & 1) * NW + wave) * WIDE_TK + sidx * 32 + col] = cs;                  \
-      }                                                                                              \
-    }                                                                                                \
-  }
-
-  for (int t = 0; t < ntiles; ++t) {
-    __syncthreads();                           // everybody is done with the tile in LDS (and with red[(t - 1) & 1] of two tiles ago)
-    if (PASS == 2 && t > 0 && tid < WIDE_TK) {
-      const int key = chunk0 + (t - 1) * WIDE_TK + tid;
-      const float* r4 = red + ((t - 1) & 1) * NW * WIDE_TK;
-      float s4 = r4[tid];
-#pragma unroll
-      for (int w = 1; w < NW; ++w) s4 += r4[w * WIDE_TK + tid];
-      if (key < chunk1) __builtin_nontemporal_store(s4, a.psi + ((long long)head * a.L + key));
-    }
-#pragma unroll
-    for (int i = 0; i < LPT; ++i) {
-      const int idx = i * NT + tid;
-      *reinterpret_cast<u32x4_t*>(kt + (idx / PPR) * RS + (idx % PPR) * 8) = pre[i];
-    }
-    MADAKV_WIDE_LOAD(min(t + 1, ntiles - 1))   // (the last trip fetches its own tile again: an unconditional load keeps the wait counts exact)
-    __syncthreads();
-    const int tile_end = chunk0 + (t + 1) * WIDE_TK;
-    if (tile_end > first_masked || tile_end > chunk1) MADAKV_WIDE_TILE(true)
-    else MADAKV_WIDE_TILE(false)
-  }
-#undef MADAKV_WIDE_TILE
-#undef MADAKV_WIDE_LOAD
-
-  if (PASS == 2) {
-    __syncthreads();
-    if (tid < WIDE_TK) {
-      const int key = chunk0 + (ntiles - 1) * WIDE_TK + tid;
-      const float* r4 = red + ((ntiles - 1) & 1) * NW * WIDE_TK;
-      float s4 = r4[tid];
-#pragma unroll
-      for (int w = 1; w < NW; ++w) s4 += r4[w * WIDE_TK + tid];
-      if (key < chunk1) __builtin_nontemporal_store(s4, a.psi + ((long long)head * a.L + key));
-    }
-  } else {
-    // per row: maximum over the 32 key columns of the half, sums rescaled to it and added
-    float* rs = a.rowstat + ((long long)head * a.nsplit + split) * a.mpad * 2;
-#pragma unroll
-    for (int b = 0; b < NRB; ++b) {
-#pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        const float m = half_reduce<0>(st_m[b][j]);
-        const float l = half_reduce<1>(st_l[b][j] * fast_exp2((st_m[b][j] - m) * a.scale_log2));
-        if (rb0 + b < MB && col == 0) {
-          const int row = (rb0 + b) * 32 + (j >> 2) * 8 + half * 4 + (j & 3);
-          rs[row * 2] = m * a.scale_log2; rs[row * 2 + 1] = l;
-        }
-      }
-    }
-  }
-}
-
-// ------------------------------------------------------------------------------------
-// The same two sweeps with the keys fetched straight into LDS (global_load_lds, 16 bytes per lane): no
-// register holds a key on its way, so three tiles of DMA_TK keys form a ring with two tiles in flight
-// while the third is multiplied, and two row blocks per wave fit 256 registers in both sweeps (two
-// workgroups of four waves per CU, in step with nobody: one's contractions run under the other's
-// vector arithmetic).
+// More than 64 proxy rows (grouped queries: G*W up to 256), the same two sweeps.  The arithmetic per
+// key grows with the rows and is what bounds these kernels (one exp2 per logit and sweep on the vector
+// unit; the contraction is a fraction of that), so the layout serves the vector unit: wave w owns
+// proxy rows [32 NRB w, 32 NRB (w + 1)) for all keys of the workgroup's chunk and keeps their Q
+// fragments in registers; the waves share the keys.  Sweep 1 needs no merge among the waves (a row's
+// statistics over the chunk are complete in its wave); sweep 2 adds the waves' partial column sums
+// through LDS, in wave order, one tile behind the arithmetic.
+// The keys are fetched straight into LDS (global_load_lds, 16 bytes per lane): no register holds a
+// key on its way, so three tiles form a ring with two tiles in flight while the third is multiplied.
 // A wave's load instruction fills 1 KB of consecutive LDS (lane i at base + 16 i), so rows cannot be
 // padded; instead the 16-byte pieces of a row are stored permuted, piece c of row r at slot
 // c ^ (r mod pieces per row): the lane that writes slot s of row r fetches piece s ^ (r mod ...) from
@@ -1592,7 +1397,6 @@ template <int D, bool WIDE8>
 static void launch_wide_pair(const ScoreArgs& a0, int heads, hipStream_t st) {
   ScoreArgs a = a0;
   dim3 grid(a.nsplit, heads);
-#ifndef MADAKV_WIDE_REGS
   // sweep 1 carries a running (max, sum) per row and lane on top of the fragments: with two row blocks per wave
   // that does not fit 256 registers, so up to 256 rows take eight waves of one block each (one workgroup per CU,
   // tiles of 128 keys whose four subtiles share one rescaling), sweep 2 four waves of two blocks (two per CU)
@@ -1613,16 +1417,6 @@ static void launch_wide_pair(const ScoreArgs& a0, int heads, hipStream_t st) {
   a.chunk = ((a.L + ns2 - 1) / ns2 + 63) / 64 * 64;
   dim3 grid2((a.L + a.chunk - 1) / a.chunk, heads);
   hipLaunchKernelGGL((score_wide_dma_kernel<D, 4, NRB2, 64, BS2, 2>), grid2, dim3(SCORE_THREADS), lds2, st, a);
-#else
-  // (tiles: four subtiles in sweep 1; in sweep 2 with two row blocks per wave two, which is what the registers hold)
-  constexpr int NW1 = WIDE8 ? 8 : 4, NW2 = 4, NRB2 = WIDE8 ? 2 : 1, TK1 = 128, TK2 = WIDE8 ? 64 : 128, TK = 128;
-  const size_t lds = (size_t)TK * (D + 8) * 2 + ((size_t)a.mpad + 2 * 8 * TK) * sizeof(float);
-  if (!a.lse) {
-    hipLaunchKernelGGL((score_wide_kernel<D, NW1, 1, TK1, 1>), grid, dim3(NW1 * 64), lds, st, a);
-    if (a.nsplit >= COMBINE_FROM) { hipLaunchKernelGGL(score_combine_kernel, dim3(heads), dim3(256), 0, st, a); a.nmerge = 1; }
-  }
-  hipLaunchKernelGGL((score_wide_kernel<D, NW2, NRB2, TK2, 2>), grid, dim3(NW2 * 64), lds, st, a);
-#endif
 }
 
 // ---- the one-sweep kernel on ragged heads: the rows of a reduced cache, scored against the most recent queries
@@ -1762,8 +1556,8 @@ hipError_t launch_score(const Dims& dm, const madakv_config& c, const void* q_wi
     int nh = std::min(p.group_heads, dm.heads - h0);
     a.head0 = h0;
     if (use_mfma(dm, c.dtype)) {
-      // row blocks of 32 proxy rows: 1-2 -> every wave its own keys; 3-4 -> pairs of waves share
-      // keys; 5-8 -> all four waves share keys.  NRB = row blocks per wave.
+      // row blocks of 32 proxy rows: 1-2 -> every wave its own keys and all rows; 3-8 -> the waves share the
+      // keys and own row blocks (the kernels with the LDS ring)
       const int MB = p.mpad / 32;
       const size_t qbytes = ((size_t)p.mpad + 4 * 32) * (dm.d + 8) * 2;      // Q tile + one K subtile per wave
       const size_t lds1 = qbytes + (size_t)4 * p.mpad * 2 * sizeof(float);

@@ -1198,6 +1198,43 @@ def test_widest_shapes():
                                           ctx_len=900, window=8, budget=120, n_images=1)
     _run_and_check_whole_path(wl)
 
+@pytest.mark.parametrize("shape", ["m128_d128", "m192_d64", "m80_d64_odd", "m224_long"])
+def test_more_than_64_proxy_rows(shape):
+    """G*W between 65 and 256: the two-sweep scoring kernels whose waves own blocks of proxy rows and share the keys
+    through an LDS ring.  One and two row blocks per wave, both head dims, several chunks per head in both sweeps
+    (the second sweep cuts the keys its own way), a ragged last tile; with and without given row normalisers."""
+    kw = {"m128_d128": dict(n_q_heads=8, n_kv_heads=2, head_dim=128, window=32, ctx_len=5000),
+          "m192_d64": dict(n_q_heads=6, n_kv_heads=2, head_dim=64, window=64, ctx_len=4100),
+          "m80_d64_odd": dict(n_q_heads=4, n_kv_heads=2, head_dim=64, window=40, ctx_len=3001),
+          "m224_long": dict(n_q_heads=7, n_kv_heads=1, head_dim=128, window=32, ctx_len=9001)}[shape]
+    wl = WL.CONFIGS["llava_layer"].scaled(name=shape, n_layers=2, batch=1, budget=300, n_images=3, decode_steps=1, **kw)
+    NL, B, H, L, W = wl.n_layers, wl.batch, wl.n_kv_heads, wl.ctx_len, wl.window
+    G = wl.n_q_heads // H
+    assert 64 < G * W <= 256
+    p = PU.oracle_params(wl)
+    q, k, v, mask, masks = PU.make_inputs(wl, DEV)
+    qh, kh = WL.to_f64(q), WL.to_f64(k)
+    psi_o = np.stack([np.stack([O.window_scores(qh[l, b], kh[l, b], p.scale) for b in range(B)]) for l in range(NL)])
+    eng = engine(wl)
+    say(f"{shape}: madakv_score, {G * W} proxy rows")
+    eng.score(0, NL, q, k, mask)
+    torch.cuda.synchronize()
+    psi_1 = eng.psi.clone()
+    nbad, worst = PU.psi_close(psi_1.cpu().numpy(), psi_o, G, W, L)
+    say(f"{shape}: psi worst scaled error {worst:.2e}")
+    assert nbad == 0, f"psi: {nbad} entries outside tolerance (worst {worst})"
+    np.testing.assert_allclose(psi_1.cpu().numpy().sum(-1), G * W, rtol=2e-4)
+    eng.score(0, NL, q, k, mask)                                        # run to run: bit for bit
+    torch.cuda.synchronize()
+    assert torch.equal(eng.psi, psi_1)
+    lse_o = np.stack([np.stack([O.proxy_row_lse(qh[l, b], kh[l, b], p.scale) for b in range(B)]) for l in range(NL)])
+    say(f"{shape}: madakv_score_lse")
+    eng.score_lse(0, NL, q, k, mask, torch.from_numpy(lse_o.astype(np.float32)).to(DEV).contiguous())
+    torch.cuda.synchronize()
+    assert torch.allclose(eng.psi, psi_1, rtol=2e-5, atol=1e-12)
+    _run_and_check_whole_path(wl)
+    eng.close()
+
 
 def test_long_heads_take_the_chunk_parallel_path():
     """Heads of more than 16384 candidates on a handful of heads: statistics (Eq. 6, 9, pooling) and selection give
