@@ -378,7 +378,9 @@ def main():
                 d_["kernel_only_frac_from_profile"] = byts / (ko * 1e-6) / 1e9 / HBM_PEAK_GBS
             return d_
         result["roofline_by_kernel"] = [
-            entry("score_fused_kernel (one sweep over K; statistics kernels overlapped)", k_bytes + psi_bytes, score_ms,
+            entry("score_fused_kernel (one sweep over K; statistics kernels overlapped)" if (Hq // H) * W <= 64 else
+                  "score_wide_dma_kernel x 2 sweeps (more than 64 proxy rows: bound by the vector arithmetic; statistics kernels overlapped)",
+                  k_bytes + psi_bytes, score_ms,
                   "algorithmic bytes = K read once + psi written; the statistics of the last layer group are not hidden; "
                   "a plain streaming read reaches 6.1-6.5 TB/s on this machine", "score_total_us_per_eviction"),
             entry("gather_kernel (+ segment layout and selection kernels)", gather_bytes + 5 * NL * B * H * (L - W), sg_ms,
@@ -402,7 +404,9 @@ def main():
                                 "intensity_flop_per_byte": score_flops / k_bytes,
                                 "mfma_busy_pct_from_counters": read_profile(ctr, "mfma_busy_pct"),
                                 "mfma_flops_per_launch_from_counters": read_profile(ctr, "mfma_flops_per_launch"),
-                                "note": "HBM-bound (intensity = G*W flop per byte of K against a ridge of about 310): the matrix cores idle most of the time by design"}
+                                "note": "HBM-bound (intensity = G*W flop per byte of K against a ridge of about 310): the matrix cores idle most of the time by design"
+                                if (Hq // H) * W <= 64 else
+                                "two sweeps (the contraction runs twice: the flops counted here are one sweep's); bound by one exp2 per logit and sweep on the vector unit"}
         # restore the state the sections below expect (cache rebuilt, counters reset)
         eng.evict(0, NL, q, k, v, mask)
         torch.cuda.synchronize()

@@ -485,34 +485,66 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       float colsum[BS];
 #pragma unroll
       for (int u = 0; u < BS; ++u) colsum[u] = 0.f;
+      bf16x8_t bfrag[BS][KS];
 #pragma unroll
       for (int u = 0; u < BS; ++u) {
-        bf16x8_t bfrag[KS];
         const uint32_t sub_lds = tile_lds + (uint32_t)(s0 + u) * 32 * ROWB;
         if (KS == 8) {
           asm volatile("ds_read_b128 %0, %8\n\tds_read_b128 %1, %9\n\tds_read_b128 %2, %10\n\tds_read_b128 %3, %11\n\t"
                        "ds_read_b128 %4, %12\n\tds_read_b128 %5, %13\n\tds_read_b128 %6, %14\n\tds_read_b128 %7, %15\n\t"
                        "s_waitcnt lgkmcnt(0)"
-                       : "=&v"(bfrag[0]), "=&v"(bfrag[1]), "=&v"(bfrag[2]), "=&v"(bfrag[3]), "=&v"(bfrag[4 % KS]), "=&v"(bfrag[5 % KS]), "=&v"(bfrag[6 % KS]), "=&v"(bfrag[7 % KS])
+                       : "=&v"(bfrag[u][0]), "=&v"(bfrag[u][1]), "=&v"(bfrag[u][2]), "=&v"(bfrag[u][3]), "=&v"(bfrag[u][4 % KS]), "=&v"(bfrag[u][5 % KS]), "=&v"(bfrag[u][6 % KS]), "=&v"(bfrag[u][7 % KS])
                        : "v"(sub_lds + frag_off[0]), "v"(sub_lds + frag_off[1]), "v"(sub_lds + frag_off[2]), "v"(sub_lds + frag_off[3]),
                          "v"(sub_lds + frag_off[4 % KS]), "v"(sub_lds + frag_off[5 % KS]), "v"(sub_lds + frag_off[6 % KS]), "v"(sub_lds + frag_off[7 % KS])
                        : "memory");
         } else {
           asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %5\n\tds_read_b128 %2, %6\n\tds_read_b128 %3, %7\n\t"
                        "s_waitcnt lgkmcnt(0)"
-                       : "=&v"(bfrag[0]), "=&v"(bfrag[1]), "=&v"(bfrag[2]), "=&v"(bfrag[3])
+                       : "=&v"(bfrag[u][0]), "=&v"(bfrag[u][1]), "=&v"(bfrag[u][2]), "=&v"(bfrag[u][3])
                        : "v"(sub_lds + frag_off[0]), "v"(sub_lds + frag_off[1]), "v"(sub_lds + frag_off[2]), "v"(sub_lds + frag_off[3])
                        : "memory");
         }
+        if (BS > 1) {                            // (a batch of several subtiles: its contractions as the fragments come)
 #pragma unroll
-        for (int b = 0; b < NRB; ++b) {
-          acc[u][b] = f32x16_t{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+          for (int b = 0; b < NRB; ++b) {
+            acc[u][b] = f32x16_t{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-          for (int ks = 0; ks < KS; ++ks)
-            acc[u][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(areg[b][ks], bfrag[ks], acc[u][b], 0, 0, 0);
+            for (int ks = 0; ks < KS; ++ks)
+              acc[u][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(areg[b][ks], bfrag[u][ks], acc[u][b], 0, 0, 0);
+          }
         }
       }
-      if (tail) { MADAKV_DMA_VECTOR(true) } else { MADAKV_DMA_VECTOR(false) }
+      // One subtile per batch: contractions and vector arithmetic of the subtile in one stretch of straight-line
+      // code, so that the second row block's contraction can be issued between the first block's vector
+      // instructions (a wave issues in order: what follows a matrix instruction that waits for its predecessor
+      // waits with it).
+#define MADAKV_DMA_CONTRACT                                                                          \
+      if (BS == 1) {                                                                                 \
+        _Pragma("unroll") for (int b = 0; b < NRB; ++b) {                                            \
+          acc[0][b] = f32x16_t{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}; \
+          _Pragma("unroll") for (int ks = 0; ks < KS; ++ks)                                          \
+            acc[0][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(areg[b][ks], bfrag[0][ks], acc[0][b], 0, 0, 0); \
+        }                                                                                            \
+      }
+      if (tail) {
+        MADAKV_DMA_CONTRACT
+        MADAKV_DMA_VECTOR(true)
+      } else {
+        MADAKV_DMA_CONTRACT
+        MADAKV_DMA_VECTOR(false)
+        if (BS == 1 && NRB == 2 && PASS == 2 && KS == 8) {
+          // the order asked of the compiler: the first block's eight matrix instructions, then each of the second
+          // block's followed by four plain and two exp2 instructions of the first block's arithmetic
+          __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+            __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
+          }
+        }
+      }
+#undef MADAKV_DMA_CONTRACT
       if (PASS == 2) {
 #pragma unroll
         for (int u = 0; u < BS; ++u) {
@@ -1266,6 +1298,8 @@ __global__ __launch_bounds__(256) void score_combine_kernel(ScoreArgs a) {
 constexpr int COMBINE_FROM = 8;
 #ifndef MADAKV_WIDE_WGS
 #define MADAKV_WIDE_WGS 256
+#endif
+#ifndef MADAKV_WIDE_WGS2
 #define MADAKV_WIDE_WGS2 512
 #endif
 constexpr int WIDE_WGS = MADAKV_WIDE_WGS, WIDE_WGS2 = MADAKV_WIDE_WGS2;   // workgroups per launch the chunking aims at with more than 64 proxy rows: sweep 1, sweep 2
