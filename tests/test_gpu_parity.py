@@ -1198,7 +1198,7 @@ def test_widest_shapes():
                                           ctx_len=900, window=8, budget=120, n_images=1)
     _run_and_check_whole_path(wl)
 
-@pytest.mark.parametrize("shape", ["m128_d128", "m192_d64", "m80_d64_odd", "m224_long"])
+@pytest.mark.parametrize("shape", ["m128_d128", "m192_d64", "m80_d64_odd", "m224_long", "m96_one_tile", "m256_two_tiles"])
 def test_more_than_64_proxy_rows(shape):
     """G*W between 65 and 256: the two-sweep scoring kernels whose waves own blocks of proxy rows and share the keys
     through an LDS ring.  One and two row blocks per wave, both head dims, several chunks per head in both sweeps
@@ -1206,8 +1206,14 @@ def test_more_than_64_proxy_rows(shape):
     kw = {"m128_d128": dict(n_q_heads=8, n_kv_heads=2, head_dim=128, window=32, ctx_len=5000),
           "m192_d64": dict(n_q_heads=6, n_kv_heads=2, head_dim=64, window=64, ctx_len=4100),
           "m80_d64_odd": dict(n_q_heads=4, n_kv_heads=2, head_dim=64, window=40, ctx_len=3001),
-          "m224_long": dict(n_q_heads=7, n_kv_heads=1, head_dim=128, window=32, ctx_len=9001)}[shape]
-    wl = WL.CONFIGS["llava_layer"].scaled(name=shape, n_layers=2, batch=1, budget=300, n_images=3, decode_steps=1, **kw)
+          "m224_long": dict(n_q_heads=7, n_kv_heads=1, head_dim=128, window=32, ctx_len=9001),
+          # contexts of one and two LDS tiles: the ring's start-up and its end meet
+          "m96_one_tile": dict(n_q_heads=3, n_kv_heads=1, head_dim=128, window=32, ctx_len=60, budget=44, n_images=1,
+                               image_tokens=(10, 10), text_tokens=(4, 30)),
+          "m256_two_tiles": dict(n_q_heads=8, n_kv_heads=1, head_dim=64, window=32, ctx_len=150, budget=60, n_images=1,
+                                 image_tokens=(40, 40), text_tokens=(4, 60))}[shape]
+    kw = dict(dict(budget=300, n_images=3), **kw)
+    wl = WL.CONFIGS["llava_layer"].scaled(name=shape, n_layers=2, batch=1, decode_steps=1, **kw)
     NL, B, H, L, W = wl.n_layers, wl.batch, wl.n_kv_heads, wl.ctx_len, wl.window
     G = wl.n_q_heads // H
     assert 64 < G * W <= 256
