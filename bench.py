@@ -202,6 +202,21 @@ def time_config(name, budget=None, steps=None):
            "decode_step_us": de * 1e3 / S, "decode_us_per_layer_call": de * 1e3 / (S * NL),
            "decode_GBps": dec_bytes / (de * 1e-3) / 1e9, "decode_frac_of_hbm_peak": dec_bytes / (de * 1e-3) / 1e9 / HBM_PEAK_GBS,
            "decode_bytes_per_layer_call": dec_bytes / (S * NL)}
+    # the prefill's last-window attention with the scores as a by-product, where the library takes the shape
+    # (more than 32 proxy rows: one pass over K and V per block of 32 rows)
+    try:
+        wout = torch.empty(NL, B, Hq, W, d, dtype=wl.torch_dtype, device=dev)
+        ts = []
+        for rep in range(3):
+            e[0].record(); eng.window_attn_score(0, NL, q, k, v, mask, wout); e[1].record()
+            torch.cuda.synchronize()
+            ts.append(e[0].elapsed_time(e[1]))
+        res["window_attn_score_ms"] = float(np.median(ts[1:]))
+        res["window_attn_passes_over_k_and_v"] = ((Hq // H) * W + 31) // 32
+        del wout
+    except MB.MadaKVError as ex:
+        res["window_attn_score_ms"] = None
+        res["window_attn_note"] = str(ex)[:120]
     eng.close()
     del q, k, v, dq, dk, dv, eng
     torch.cuda.empty_cache()
@@ -625,7 +640,7 @@ def main():
 
     if not a.no_extras and wl.name == "llava_16k":
         # the other named configurations that are large enough to time: the Qwen-shaped grouped-query model
-        # (224 proxy rows per KV head: four blocks of 64 rows on the one-sweep kernel, and the MFMA decode kernel) and
+        # (224 proxy rows per KV head: the two-sweep kernels with the LDS ring, and the MFMA decode kernel) and
         # the 128K context at both budgets of its sweep (two-level exchange, chunk-parallel statistics / selection)
         others = {}
         for key, (nm, bud) in {"qwen_gqa": ("qwen_gqa", None), "long_128k_budget_512": ("long_128k", 512),

@@ -189,8 +189,9 @@ int32_t madakv_score_lse(madakv_handle* h, int32_t layer0, int32_t n,
  * and psi, psi_pool, stats, n_mod exactly as madakv_score defines them (up to the rounding order of psi).  A model
  * whose prefill calls this for its last W positions needs no scoring sweep of its own: madakv_allocate and
  * madakv_select_gather follow directly.  v [n, B, H, L, d]; ws: madakv_window_attn_workspace_bytes(h, n) bytes;
- * everything else as in madakv_score.  MADAKV_ERR_UNIMPLEMENTED unless dtype is bf16, G * W <= 32 and
- * ctx_len <= 32768 (head_dim 128) / 49152 (head_dim 64). */
+ * everything else as in madakv_score.  With more than 32 proxy rows (grouped queries, wide windows) the rows are
+ * taken in blocks of 32, each with a pass over K and V of its own.  MADAKV_ERR_UNIMPLEMENTED unless dtype is bf16
+ * and ctx_len <= 131072 (head_dim 128) / 196608 (head_dim 64). */
 int32_t madakv_window_attn_workspace_bytes(const madakv_handle* h, int32_t n_layers_per_call, size_t* bytes);
 int32_t madakv_window_attn_score(madakv_handle* h, int32_t layer0, int32_t n,
                                  const void* q_win, const void* k, const void* v, const uint8_t* mask,

@@ -994,10 +994,13 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(2
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int split = blockIdx.x;
-  const int head = a.head0 + blockIdx.y;
+  const int hv = a.head0 + blockIdx.y;        // head, or (head, block of 32 proxy rows) when there are more than 32
+  const int head = hv / a.rb_count;
+  const int rowbase = (hv % a.rb_count) * 32; // first proxy row of this workgroup's block
+  const int Mh = min(a.M - rowbase, 32);      // its rows
   const int kvh = head % a.H;
   const long long lb = head / a.H;
-  const uint16_t* qg = reinterpret_cast<const uint16_t*>(a.q_win) + (lb * a.H + kvh) * (long long)a.G * a.W * D;
+  const uint16_t* qg = reinterpret_cast<const uint16_t*>(a.q_win) + ((lb * a.H + kvh) * (long long)a.G * a.W + rowbase) * D;
   const uint16_t* kg = reinterpret_cast<const uint16_t*>(a.k) + (long long)head * a.L * D;
   const uint16_t* vg = reinterpret_cast<const uint16_t*>(wa.v) + (long long)head * a.L * D;
   const int Lh = a.L, fs = a.fsplit;
@@ -1027,14 +1030,14 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(2
   for (int e = tid; e < 32 * PPR; e += SCORE_THREADS) {                   // Q tile, padding rows zero
     const int r = e / PPR, c = e % PPR;
     uint4 val = make_uint4(0, 0, 0, 0);
-    if (r < a.M) val = *reinterpret_cast<const uint4*>(qg + (long long)r * D + c * 8);
+    if (r < Mh) val = *reinterpret_cast<const uint4*>(qg + (long long)r * D + c * 8);
     *reinterpret_cast<uint4*>(qs + r * RS + c * 8) = val;
   }
   __syncthreads();
 
-  const int half = lane >> 5, col = lane & 31;            // col = this lane's proxy row
+  const int half = lane >> 5, col = lane & 31;            // col = this lane's proxy row (of the block)
   const int first_masked = Lh - a.W + 1;
-  const int pos = Lh - a.W + (col % a.W);                 // last key the row sees
+  const int pos = Lh - a.W + ((rowbase + col) % a.W);     // last key the row sees
   bf16x8_t qfrag[KS];
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks)
@@ -1050,7 +1053,7 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(2
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     const int t0 = chunk0 + (it * 4 + wave) * 32;
-    const bool tail = (t0 + 32 > first_masked) || (t0 + 32 > chunk1) || (a.M < 32);
+    const bool tail = (t0 + 32 > first_masked) || (t0 + 32 > chunk1) || (Mh < 32);
     const uint16_t* krow = kt + col * RS + half * (D / 2);
     f32x16_t acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -1063,7 +1066,7 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(2
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
       const int key = t0 + 8 * (j >> 2) + 4 * half + (j & 3);
-      const bool valid = !tail || ((key < chunk1) && (key <= pos) && (col < a.M));
+      const bool valid = !tail || ((key < chunk1) && (key <= pos) && (col < Mh));
       lg[it][j] = valid ? acc[j] * a.scale_log2 : NEG_BIG;
     }
   }
@@ -1088,7 +1091,7 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(2
 #pragma unroll
   for (int it = 0; it < PF; ++it) MADAKV_WIN_LOAD(vg, it, it)
   __syncthreads();
-  post_row_stats(a, head, split, fs, part);
+  post_row_stats(a, hv, split, fs, part);
 
   // ---- O += P V with p taken against the wave's own row maxima, so that nothing here waits for the
   // other workgroups of the head; the head-wide statistics come in as one factor per row afterwards
@@ -1138,9 +1141,9 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(2
 #undef MADAKV_WIN_PARK
 
   // ---- the head-wide statistics (by now the other workgroups have normally posted theirs)
-  collect_row_stats<D>(a, head, split, fs, Lh, a.M, 0, kg, qs, part, offs, pm, &s_fail);
+  collect_row_stats<D>(a, hv, split, fs, Lh, Mh, rowbase, kg, qs, part, offs, pm, &s_fail);
   __syncthreads();
-  if (split == 0 && wa.lse && tid < a.M) wa.lse[(lb * a.H + kvh) * (long long)a.G * a.W + tid] = offs[tid] * 0.6931471805599453f;
+  if (split == 0 && wa.lse && tid < Mh) wa.lse[(lb * a.H + kvh) * (long long)a.G * a.W + rowbase + tid] = offs[tid] * 0.6931471805599453f;
   const float mxw = part[(wave * 32 + col) * 2];           // the wave's own row maximum again
   const float rs = mxw > NEG_BIG ? fast_exp2(mxw - offs[col]) : 0.f;   // this wave's p times rs = the softmax entry
 
@@ -1152,7 +1155,9 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(2
     for (int j = 0; j < 16; ++j) {
       const float cs = half_reduce<1>(lg[it][j] * rs);     // over the 32 rows: psi of this key
       const int key = t0 + 8 * (j >> 2) + 4 * half + (j & 3);
-      if (col == 0 && key < chunk1) a.psi[(long long)head * a.L + key] = cs;
+      // (more than 32 proxy rows: the block's share of psi, added to the other blocks' in block order afterwards)
+      float* psi_dst = a.rb_count > 1 ? a.psi_part + (hv % a.rb_count) * a.psi_part_stride : a.psi;
+      if (col == 0 && key < chunk1) psi_dst[(long long)head * a.L + key] = cs;
     }
   }
   // ---- O rows take their factor: row m of the tile sits in lane m's rs
@@ -1167,7 +1172,7 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(2
   constexpr int DPR = D == 128 ? 2 : 1, CR = 32 * DPR;     // 4 waves x 32 rows x CR floats fit the four tiles
   static_assert(4 * 32 * CR * sizeof(float) <= 4 * 32 * RS * sizeof(uint16_t), "the shares must fit the tiles");
   float* fl = reinterpret_cast<float*>(kt_all);           // [4 waves][32 rows][CR]
-  float* op = wa.opart + ((long long)head * fs + split) * 32 * D;
+  float* op = wa.opart + ((long long)hv * fs + split) * 32 * D;
   for (int rd = 0; rd < DB / DPR; ++rd) {
     __syncthreads();
 #pragma unroll
@@ -1189,13 +1194,14 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(2
 // 256 float4 of the 32 x d tile); eight shares in flight per thread.
 __global__ __launch_bounds__(256) void window_attn_reduce_kernel(WinArgs wa) {
   const ScoreArgs& a = wa.s;
-  const int head = a.head0 + blockIdx.x;
+  const int hv = a.head0 + blockIdx.x;
+  const int head = hv / a.rb_count, rowbase = (hv % a.rb_count) * 32;
   const int kvh = head % a.H;
   const long long lb = head / a.H;
   const int e4 = blockIdx.y * 256 + threadIdx.x;           // float4 index in the [32][d] tile
   const int tile4 = 32 * a.d / 4;
-  if (e4 >= a.M * a.d / 4) return;
-  const f32x4_t* op = reinterpret_cast<const f32x4_t*>(wa.opart) + (long long)head * a.fsplit * tile4 + e4;
+  if (e4 >= min(a.M - rowbase, 32) * a.d / 4) return;
+  const f32x4_t* op = reinterpret_cast<const f32x4_t*>(wa.opart) + (long long)hv * a.fsplit * tile4 + e4;
   f32x4_t sum = {0.f, 0.f, 0.f, 0.f};
   int sp = 0;
   for (; sp + 8 <= a.fsplit; sp += 8) {
@@ -1206,7 +1212,7 @@ __global__ __launch_bounds__(256) void window_attn_reduce_kernel(WinArgs wa) {
     for (int j = 0; j < 8; ++j) sum += x[j];
   }
   for (; sp < a.fsplit; ++sp) sum += __builtin_nontemporal_load(op + (long long)sp * tile4);
-  const long long o = (lb * a.H + kvh) * (long long)a.G * a.W * a.d + (long long)e4 * 4;
+  const long long o = ((lb * a.H + kvh) * (long long)a.G * a.W + rowbase) * a.d + (long long)e4 * 4;
   if (wa.out_fp32) *reinterpret_cast<f32x4_t*>(reinterpret_cast<float*>(wa.out) + o) = sum;
   else {
     u32x2_t pk;
@@ -1519,12 +1525,18 @@ hipError_t launch_score_ragged(const Dims& dm, const madakv_config& c, const voi
 // ---- the last-window attention with the scores as a by-product
 constexpr int WIN_NS_128 = 4, WIN_NS_64 = 6;             // subtiles per wave (registers: logits + the O tile)
 static int win_split(const Dims& dm) { const int ck = 4 * 32 * (dm.d == 128 ? WIN_NS_128 : WIN_NS_64); return (dm.L + ck - 1) / ck; }
+static int win_blocks(const Dims& dm) { return (dm.M + 31) / 32; }   // blocks of 32 proxy rows, each handled like a head of its own
 bool window_attn_supported(const Dims& dm, const madakv_config& c) {
-  return use_mfma(dm, c.dtype) && dm.M <= 32 && win_split(dm) <= FUSED_MAX_SPLIT;
+  return use_mfma(dm, c.dtype) && dm.M <= 256 && win_split(dm) <= FUSED_MAX_SPLIT_2L;
 }
+static size_t win_xchg_bytes(const Dims& dm) {
+  return ((size_t)dm.heads * win_blocks(dm) * (win_split(dm) + xchg_groups(win_split(dm))) * 32 * 8 + 255) / 256 * 256;
+}
+static size_t win_opart_bytes(const Dims& dm) { return ((size_t)dm.heads * win_blocks(dm) * win_split(dm) * 32 * dm.d * sizeof(float) + 255) / 256 * 256; }
 size_t window_attn_ws_bytes(const Dims& dm, const madakv_config& c) {
   if (!window_attn_supported(dm, c)) return 256;
-  return 256 + ((size_t)dm.heads * win_split(dm) * 32 * 8 + 255) / 256 * 256 + (size_t)dm.heads * win_split(dm) * 32 * dm.d * sizeof(float);
+  // the counter of lone workgroups, the exchange words, the workgroups' shares of O, the row blocks' shares of psi
+  return 256 + win_xchg_bytes(dm) + win_opart_bytes(dm) + (win_blocks(dm) > 1 ? (size_t)win_blocks(dm) * dm.heads * dm.L * sizeof(float) : 0);
 }
 hipError_t launch_window_attn(const Dims& dm, const madakv_config& c, const void* q_win, const void* k, const void* v,
                               void* out, float* row_lse, float* psi, void* ws, hipStream_t st) {
@@ -1536,24 +1548,32 @@ hipError_t launch_window_attn(const Dims& dm, const madakv_config& c, const void
   a.xchg = reinterpret_cast<unsigned long long*>(static_cast<char*>(ws) + 256);
   a.H = dm.H; a.G = dm.G; a.d = dm.d; a.L = dm.L; a.W = dm.W; a.M = dm.M;
   a.mpad = 32; a.nsplit = 0; a.nmerge = 0; a.chunk = 0; a.head0 = 0;
-  a.rb_count = 1; a.psi_part = nullptr; a.psi_part_stride = 0;
+  const int rb = win_blocks(dm);
+  a.rb_count = rb;
+  a.psi_part = reinterpret_cast<float*>(static_cast<char*>(ws) + 256 + win_xchg_bytes(dm) + win_opart_bytes(dm));
+  a.psi_part_stride = (long long)dm.heads * dm.L;
   a.fsplit = win_split(dm);
-  a.xgroups = 0; a.xstride = (long long)a.fsplit * 32; a.k_fp8 = 0;
+  a.xgroups = xchg_groups(a.fsplit); a.xstride = (long long)(a.fsplit + a.xgroups) * 32; a.k_fp8 = 0;   // (two exchange levels above 64 chunks)
   const char* spin = getenv("MADAKV_SCORE_SPIN_LIMIT");
   a.spin_limit = spin && atoi(spin) > 0 ? atoi(spin) : FUSED_SPIN_LIMIT;
   const float scale = c.softmax_scale > 0.f ? c.softmax_scale : 1.0f / sqrtf((float)dm.d);
   a.scale_log2 = scale * 1.4426950408889634f;
   wa.v = v; wa.lse = row_lse; wa.out = out; wa.out_fp32 = c.out_fp32;
-  wa.opart = reinterpret_cast<float*>(static_cast<char*>(ws) + 256 + ((size_t)dm.heads * a.fsplit * 32 * 8 + 255) / 256 * 256);
-  const long long nx = (long long)dm.heads * a.fsplit * 32;
+  wa.opart = reinterpret_cast<float*>(static_cast<char*>(ws) + 256 + win_xchg_bytes(dm));
+  const long long nx = (long long)dm.heads * rb * a.xstride;
   if (a.fsplit > 1) hipLaunchKernelGGL(score_xchg_init_kernel, dim3((unsigned)((nx + 255) / 256)), dim3(256), 0, st, a.xchg, nx);
   const size_t lds = ((size_t)32 + 4 * 32) * (dm.d + 8) * 2 + ((size_t)4 * 32 * 2 + 32 + 512) * sizeof(float);
-  for (int h0 = 0; h0 < dm.heads; h0 += 65535) {
-    const int nh = std::min(65535, dm.heads - h0);
+  const int vheads = dm.heads * rb, step = 65535 / rb * rb;       // whole heads per launch (the grid's y limit)
+  for (int h0 = 0; h0 < vheads; h0 += step) {
+    const int nh = std::min(step, vheads - h0);
     a.head0 = h0;
     if (dm.d == 128) hipLaunchKernelGGL((window_attn_kernel<128, WIN_NS_128>), dim3(a.fsplit, nh), dim3(SCORE_THREADS), lds, st, wa);
     else hipLaunchKernelGGL((window_attn_kernel<64, WIN_NS_64>), dim3(a.fsplit, nh), dim3(SCORE_THREADS), lds, st, wa);
     hipLaunchKernelGGL(window_attn_reduce_kernel, dim3(nh, (32 * dm.d / 4 + 255) / 256), dim3(256), 0, st, wa);
+  }
+  if (rb > 1) {
+    const long long n = (long long)dm.heads * dm.L;
+    hipLaunchKernelGGL(score_blocks_sum_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a.psi_part, a.psi_part_stride, rb, psi, n);
   }
   return hipGetLastError();
 }

@@ -888,8 +888,14 @@ def test_reeviction_refusals():
 
 def _window_workloads():
     W = small_workloads()
+    # (the last three: more than 32 proxy rows, taken in blocks of 32: 224 = 7 blocks, 64 = 2, 2 x 20 = a ragged second block)
     return {"bf16_mha": W["bf16_mha"], "bf16_d64_gqa2": W["bf16_d64_gqa2"],
-            "bf16_w20_odd": W["bf16_mha"].scaled(name="bf16_w20_odd", ctx_len=1777, window=20, budget=222, n_layers=2, batch=1)}
+            "bf16_w20_odd": W["bf16_mha"].scaled(name="bf16_w20_odd", ctx_len=1777, window=20, budget=222, n_layers=2, batch=1),
+            "bf16_gqa7": W["bf16_gqa7"], "bf16_w64": W["bf16_w64"],
+            # 79 chunks per head: the row statistics travel in two levels
+            "bf16_40k": W["bf16_mha"].scaled(name="bf16_40k", ctx_len=40001, budget=600, n_layers=1, batch=1, n_q_heads=2, n_kv_heads=2, n_images=20),
+            "bf16_gqa2_w20": W["bf16_mha"].scaled(name="bf16_gqa2_w20", ctx_len=1777, window=20, budget=222, n_layers=2, batch=1,
+                                                  n_q_heads=4, n_kv_heads=2)}
 
 
 @pytest.mark.parametrize("name", list(_window_workloads().keys()))
@@ -956,7 +962,17 @@ def test_window_attention_with_scores(name, fp32_out):
 
 
 def test_window_attention_refusals():
-    wl = small_workloads()["bf16_gqa7"]                       # 224 proxy rows
+    # contexts beyond what the heads' workgroups can exchange among themselves (256 chunks of 512 keys at head_dim 128)
+    wl = small_workloads()["bf16_mha"].scaled(name="win_too_long", n_layers=1, batch=1, n_q_heads=1, n_kv_heads=1, ctx_len=131073,
+                                              budget=300, n_images=2)
+    q, k, v, mask, masks = PU.make_inputs(wl, DEV)
+    eng = engine(wl)
+    out = torch.empty(wl.n_layers, wl.batch, wl.n_q_heads, wl.window, wl.head_dim, dtype=torch.float32, device=DEV)
+    with pytest.raises(MB.MadaKVError) as ei:
+        eng.window_attn_score(0, wl.n_layers, q, k, v, mask, out)
+    assert ei.value.status == -7
+    eng.close()
+    wl = small_workloads()["tiny_fp32"]                       # fp32 inputs
     q, k, v, mask, masks = PU.make_inputs(wl, DEV)
     eng = engine(wl)
     out = torch.empty(wl.n_layers, wl.batch, wl.n_q_heads, wl.window, wl.head_dim, dtype=torch.float32, device=DEV)
