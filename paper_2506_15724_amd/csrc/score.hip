@@ -955,7 +955,8 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(M
 // ------------------------------------------------------------------------------------
 // The prefill attention of the last W prompt positions (paper Sec. 3.1 Eq. 5 for the proxy rows of
 // Sec. 3.3) with the proxy-token scores of Eq. 7 as a by-product: out = softmax(scale Q K^T) V for
-// the G*W <= 32 proxy rows of a KV head, their log-sum-exp, and psi = the column sums of the same
+// a block of up to 32 of the G*W proxy rows of a KV head (more rows: more blocks, each with a pass of its own over
+// K and V, their column sums added in block order afterwards), their log-sum-exp, and psi = the column sums of the same
 // softmax rows.  A model's prefill runs this attention anyway; taking psi from it removes the
 // eviction's own sweep over K.
 // Same structure as score_fused_kernel (a workgroup's logits stay in registers while the row
