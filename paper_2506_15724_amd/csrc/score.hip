@@ -78,9 +78,8 @@ __device__ __forceinline__ void merge_ml(float& m, float& l, float m2, float l2)
 // execute in order.
 // In D a lane holds one key column and 16 rows: the column sum is in-lane, the row
 // statistics need one cross-lane merge at the end of the chunk.
-// The 4 waves form KG key groups x WPT row-block groups (WPT * KG = 4): with at most two
-// row blocks (M <= 64) every wave has its own keys; with more, WPT waves take the same keys
-// and different row blocks, and their column sums meet in LDS.
+// Every wave has its own keys and all (at most two) row blocks; more than 64 proxy rows take the
+// kernels further down, whose waves share the keys and own row blocks.
 // ------------------------------------------------------------------------------------
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }   // x <= ~0 here; tiny results may flush to 0
 
@@ -97,18 +96,18 @@ __device__ __forceinline__ float half_reduce(float x) {
   return x;
 }
 
-template <int D, int WPT, int NRB, int PASS>
+template <int D, int NRB, int PASS>
 __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void score_mfma_kernel(ScoreArgs a) {
   constexpr int KS = D / 16;                  // MFMA k-steps
   constexpr int RS = D + 8;                   // bf16 elements per LDS row (16 B pad)
-  constexpr int KG = 4 / WPT;                 // key groups
+  constexpr int KG = 4;                       // key groups: the waves
   constexpr int PPR = D / 8;                  // 16-byte pieces per row
   constexpr int LPS = 32 * PPR / 64;          // 16-byte loads per lane per subtile
   constexpr int PF = 2;                       // subtiles in flight per wave
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   uint16_t* qs = reinterpret_cast<uint16_t*>(smem);                       // [mpad][RS]
   uint16_t* kt_all = qs + (size_t)a.mpad * RS;                            // [4 waves][32][RS]
-  float* fbuf = reinterpret_cast<float*>(kt_all + 4 * 32 * RS);           // pass 1: [KG][mpad][2]; pass 2: off[mpad] + red[2][4][32]
+  float* fbuf = reinterpret_cast<float*>(kt_all + 4 * 32 * RS);           // pass 1: [KG][mpad][2]; pass 2: off[mpad]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int split = blockIdx.x;
@@ -120,9 +119,8 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(2
   const int chunk0 = split * a.chunk;
   const int chunk1 = min(a.L, chunk0 + a.chunk);
   const int nsub = (chunk1 - chunk0 + 31) / 32;
-  const int niter = (nsub + KG - 1) / KG;     // the same for every wave (the pass-2 merge uses workgroup barriers)
-  const int wsub = wave % WPT;                // row blocks of this wave: wsub, wsub + WPT
-  const int kgid = wave / WPT;                // subtiles of this wave: kgid, kgid + KG, ...
+  const int niter = (nsub + KG - 1) / KG;
+  const int kgid = wave;                      // subtiles of this wave: kgid, kgid + KG, ...
   uint16_t* kt = kt_all + (size_t)wave * 32 * RS;
 
   // PF subtiles of K on their way before anything else
@@ -171,15 +169,14 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(2
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
       st_m[b][j] = NEG_BIG; st_l[b][j] = 0.f;
-      const int row = min((wsub + b * WPT) * 32 + (j >> 2) * 8 + half * 4 + (j & 3), a.mpad - 1);
+      const int row = min(b * 32 + (j >> 2) * 8 + half * 4 + (j & 3), a.mpad - 1);
       off_r[b][j] = (PASS == 2) ? offs[row] : 0.f;
     }
-  float* red = fbuf + a.mpad;                  // pass 2, WPT > 1: [2][4][32] partial column sums
   // with a single row block per wave the Q fragments stay in registers (no LDS reads in the loop)
   bf16x8_t areg[KS];
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks)
-    areg[ks] = *reinterpret_cast<const bf16x8_t*>(qs + (min(wsub, a.mpad / 32 - 1) * 32 + col) * RS + half * (D / 2) + ks * 8);
+    areg[ks] = *reinterpret_cast<const bf16x8_t*>(qs + col * RS + half * (D / 2) + ks * 8);
   const int MB = a.mpad / 32;
 
   // one subtile per step: registers -> LDS tile -> MFMA -> statistics / column sums.
@@ -207,7 +204,7 @@ _Pragma("unroll") \
     float colsum = 0.f; \
 _Pragma("unroll") \
     for (int b = 0; b < NRB; ++b) { \
-      const int rb = wsub + b * WPT; \
+      const int rb = b; \
       if (rb < MB) { \
         f32x16_t acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}; \
         const uint16_t* qrow = qs + (rb * 32 + col) * RS + half * (D / 2); \
@@ -252,18 +249,7 @@ _Pragma("unroll") \
     } \
     if (PASS == 2) { \
       colsum += __shfl_xor(colsum, 32, 64); \
-      if (WPT == 1) { \
-        { float* dst = (key < chunk1) ? a.psi + ((long long)head * a.L + key) : a.sink + col; __builtin_nontemporal_store(colsum, dst); } \
-      } else { \
-        if (half == 0) red[((it & 1) * 4 + wave) * 32 + col] = colsum; \
-        __syncthreads(); \
-        if (wsub == 0 && half == 0 && key < chunk1) { \
-          float s = 0.f; \
-_Pragma("unroll") \
-          for (int w = 0; w < WPT; ++w) s += red[((it & 1) * 4 + kgid * WPT + w) * 32 + col]; \
-          a.psi[(long long)head * a.L + key] = s; \
-        } \
-      } \
+      { float* dst = (key < chunk1) ? a.psi + ((long long)head * a.L + key) : a.sink + col; __builtin_nontemporal_store(colsum, dst); } \
     } \
   } }
   // Four unconditional steps per trip; the step count is rounded up (a step past the end works on
@@ -289,7 +275,7 @@ _Pragma("unroll") \
       for (int j = 0; j < 16; ++j) {
         const float m = half_reduce<0>(st_m[b][j]);
         const float l = half_reduce<1>(st_l[b][j] * fast_exp2(st_m[b][j] - m));
-        const int rb = wsub + b * WPT;
+        const int rb = b;
         if (rb < MB && col == 0) {
           const int row = rb * 32 + (j >> 2) * 8 + half * 4 + (j & 3);
           part[(kgid * a.mpad + row) * 2] = m;
@@ -1416,21 +1402,21 @@ static void launch_fused(const ScoreArgs& a, int heads, hipStream_t st) {
   }
 }
 
-template <int D, int WPT, int NRB>
+template <int D, int NRB>
 static void launch_mfma_pair(const ScoreArgs& a0, int heads, size_t lds1, size_t lds2, hipStream_t st) {
   ScoreArgs a = a0;
   dim3 grid(a.nsplit, heads);
   if (lds1 > 48 * 1024 || lds2 > 48 * 1024) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_mfma_kernel<D, WPT, NRB, 1>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_mfma_kernel<D, NRB, 1>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_mfma_kernel<D, WPT, NRB, 2>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_mfma_kernel<D, NRB, 2>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
   }
   if (!a.lse) {
-    hipLaunchKernelGGL((score_mfma_kernel<D, WPT, NRB, 1>), grid, dim3(SCORE_THREADS), lds1, st, a);
+    hipLaunchKernelGGL((score_mfma_kernel<D, NRB, 1>), grid, dim3(SCORE_THREADS), lds1, st, a);
     if (a.nsplit >= COMBINE_FROM) { hipLaunchKernelGGL(score_combine_kernel, dim3(heads), dim3(256), 0, st, a); a.nmerge = 1; }
   }
-  hipLaunchKernelGGL((score_mfma_kernel<D, WPT, NRB, 2>), grid, dim3(SCORE_THREADS), lds2, st, a);
+  hipLaunchKernelGGL((score_mfma_kernel<D, NRB, 2>), grid, dim3(SCORE_THREADS), lds2, st, a);
 }
 
 // more than 64 proxy rows (up to 128 with WIDE8 = false, else up to 256)
@@ -1616,10 +1602,10 @@ hipError_t launch_score(const Dims& dm, const madakv_config& c, const void* q_wi
       const int MB = p.mpad / 32;
       const size_t qbytes = ((size_t)p.mpad + 4 * 32) * (dm.d + 8) * 2;      // Q tile + one K subtile per wave
       const size_t lds1 = qbytes + (size_t)4 * p.mpad * 2 * sizeof(float);
-      const size_t lds2 = qbytes + ((size_t)p.mpad + 2 * 4 * 32) * sizeof(float);
-#define MADAKV_SCORE_CASE(DD, WW, NN) launch_mfma_pair<DD, WW, NN>(a, nh, lds1, lds2, st)
+      const size_t lds2 = qbytes + (size_t)p.mpad * sizeof(float);
+#define MADAKV_SCORE_CASE(DD, NN) launch_mfma_pair<DD, NN>(a, nh, lds1, lds2, st)
 #define MADAKV_SCORE_BY_MB(DD) \
-      if (MB == 1) MADAKV_SCORE_CASE(DD, 1, 1); else if (MB == 2) MADAKV_SCORE_CASE(DD, 1, 2); \
+      if (MB == 1) MADAKV_SCORE_CASE(DD, 1); else if (MB == 2) MADAKV_SCORE_CASE(DD, 2); \
       else if (MB <= 4) launch_wide_pair<DD, false>(a, nh, st); else launch_wide_pair<DD, true>(a, nh, st)
       if (dm.d == 128) { MADAKV_SCORE_BY_MB(128); } else { MADAKV_SCORE_BY_MB(64); }
 #undef MADAKV_SCORE_BY_MB
