@@ -284,8 +284,11 @@ int32_t madakv_decode_attn(madakv_handle* h, int32_t layer0, int32_t n,
  *   budgets  [n, B, H, M]       out: the new split
  *   ws                          madakv_reevict_workspace_bytes(h, n) bytes
  * The decode-step counters of the layers are reset: max_new_tokens rows can be appended again.
- * An 8-bit cache is scored and moved as it is stored (E4M3 rows).
- * MADAKV_ERR_UNIMPLEMENTED with a paged cache, dtype fp32, or segments longer than 64 chunks of the
+ * An 8-bit cache is scored and moved as it is stored (E4M3 rows).  A paged cache is re-evicted as a whole
+ * (layer0 = 0, n = n_layers, else MADAKV_ERR_INVALID_ARG): the survivors end up in the heads' initial pages
+ * and every page taken since the eviction goes back to the pools, which all layers share; the work is done
+ * on a linear copy of the rows in the workspace (as many rows as the cache holds).
+ * MADAKV_ERR_UNIMPLEMENTED with dtype fp32 or segments longer than 64 chunks of the
  * scoring kernel (65536 rows at G * W <= 32, 49152 beyond); MADAKV_ERR_BAD_BUDGET when budget >= ctx_len
  * (nothing was evicted). */
 int32_t madakv_reevict_workspace_bytes(const madakv_handle* h, int32_t n_layers_per_call, size_t* bytes);

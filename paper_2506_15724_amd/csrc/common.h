@@ -83,6 +83,10 @@ hipError_t launch_restats(const Dims& dm, const madakv_config& c, const float* p
                           void* stats, int32_t* budgets, hipStream_t st);
 hipError_t launch_compact(const Dims& dm, const madakv_config& c, void* k_c, void* v_c, int32_t* kept_idx, const int32_t* sel,
                           const int64_t* seg_off, int32_t* kv_len, const int32_t* budgets, int appended, int gen_base, hipStream_t st);
+hipError_t launch_linear_copy(const Dims& dm, const madakv_config& c, void* k_c, void* v_c, int32_t* kept_idx, const int64_t* seg_off,
+                              const int32_t* seg_len, const Paging& pg, long long head0, int longest, void* k_lin, void* v_lin,
+                              int32_t* kept_lin, int64_t* lin_off, bool back, hipStream_t st);
+hipError_t launch_pool_reset(const Paging& pg, int batch, hipStream_t st);
 hipError_t launch_gather(const Dims& dm, const madakv_config& c, int li0, int nli, const void* k, const void* v,
                          const int32_t* kept_idx, const int64_t* kv_off, const int32_t* kv_len,
                          void* k_c, void* v_c, const void* ws, long long region_tokens,

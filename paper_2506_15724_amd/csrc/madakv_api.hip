@@ -618,17 +618,23 @@ int32_t madakv_decode_attn_static(madakv_handle* h, int32_t layer0, int32_t n,
 namespace {
 // workspace of madakv_reevict: per-row arrays over the whole reduced cache (rows are addressed as in k_c),
 // the per-head records of the call, the exchange array of the scoring kernel
-struct ReevictWs { size_t psi, pool, sel, rowmod, stats, score, total; };
+// (paged cache: the per-row arrays cover the linear copy of the heads' rows, which follows them: K, V, the
+// original positions, the heads' offsets in the copy; it has as many rows as the cache)
+struct ReevictWs { size_t psi, pool, sel, rowmod, stats, score, lin_k, lin_v, lin_idx, lin_off, total; };
 ReevictWs reevict_layout(const madakv_handle* h, int n) {
   const madakv_config& c = h->cfg;
-  const size_t cap = (size_t)(region_tokens(c) * c.batch);
   const Dims dm = make_dims(c, n);
-  auto up = [](size_t x) { return (x + 255) / 256 * 256; };
   ReevictWs w;
+  const size_t cap = (size_t)(region_tokens(c) * c.batch);
+  auto up = [](size_t x) { return (x + 255) / 256 * 256; };
   w.psi = 0; w.pool = up(cap * 4); w.sel = w.pool + up(cap * 4); w.rowmod = w.sel + up(cap * 4);
   w.stats = w.rowmod + up(cap);
   w.score = w.stats + up((size_t)dm.heads * 8 * c.n_modalities);
-  w.total = w.score + score_ragged_ws_bytes(dm, c, c.ctx_len + c.max_new_tokens, (long long)cap);
+  w.lin_k = w.score + up(score_ragged_ws_bytes(dm, c, c.ctx_len + c.max_new_tokens, (long long)cap));
+  const size_t row_bytes = (size_t)c.head_dim * (c.cache_fp8 ? 1 : (c.dtype == MADAKV_BF16 ? 2 : 4));
+  const size_t lin = c.page_rows ? up(cap * row_bytes) : 0;
+  w.lin_v = w.lin_k + lin; w.lin_idx = w.lin_v + lin; w.lin_off = w.lin_idx + (c.page_rows ? up(cap * 4) : 0);
+  w.total = w.lin_off + (c.page_rows ? up((size_t)dm.heads * 8) : 0);
   return w;
 }
 }  // namespace
@@ -649,7 +655,8 @@ int32_t madakv_reevict(madakv_handle* h, int32_t layer0, int32_t n,
   if (bad_ptr(q_recent) || bad_ptr(mask, 1) || bad_ptr(k_c) || bad_ptr(v_c) || bad_ptr(kept_idx, 4) || bad_ptr(kv_off, 8) ||
       bad_ptr(kv_len, 4) || bad_ptr(budgets, 4) || bad_ptr(ws)) return MADAKV_ERR_INVALID_ARG;
   if (c.budget >= c.ctx_len) return MADAKV_ERR_BAD_BUDGET;                 // nothing was evicted, nothing to bring back
-  if (c.page_rows) return MADAKV_ERR_UNIMPLEMENTED;
+  // a paged cache hands the pages taken since the eviction back to the pools, which all layers share
+  if (c.page_rows && (layer0 != 0 || n != c.n_layers)) return MADAKV_ERR_INVALID_ARG;
   int longest = longest_rows(h, layer0, n);
   if (!score_ragged_supported(make_dims(c, n), c, longest)) {
     // the bound may be the worst case only because the lengths of the eviction have not reached the host
@@ -669,6 +676,15 @@ int32_t madakv_reevict(madakv_handle* h, int32_t layer0, int32_t n,
   uint8_t* rowmod = reinterpret_cast<uint8_t*>(wsb + w.rowmod);
   const size_t es = c.dtype == MADAKV_BF16 ? 2 : 4;
   hipError_t e = hipSuccess;
+  // paged cache: the kernels below work on a linear copy of the call's heads
+  void* k_work = k_c; void* v_work = v_c; int32_t* idx_work = kept_idx; const int64_t* off_work = kv_off;
+  const long long cache_rows = region_tokens(c) * c.batch;
+  if (c.page_rows) {
+    k_work = wsb + w.lin_k; v_work = wsb + w.lin_v; idx_work = reinterpret_cast<int32_t*>(wsb + w.lin_idx);
+    off_work = reinterpret_cast<const int64_t*>(wsb + w.lin_off);
+    e = launch_linear_copy(make_dims(c, n), c, k_c, v_c, kept_idx, kv_off, kv_len, make_paging(h), (long long)layer0 * c.batch * c.n_kv_heads,
+                           longest, k_work, v_work, idx_work, reinterpret_cast<int64_t*>(wsb + w.lin_off), false, st);
+  }
   // layers that have appended the same number of rows since their last (re-)eviction go in one set of launches
   for (int l0 = layer0; l0 < layer0 + n && e == hipSuccess;) {
     int l1 = l0 + 1;
@@ -678,14 +694,20 @@ int32_t madakv_reevict(madakv_handle* h, int32_t layer0, int32_t n,
     const char* qr = static_cast<const char*>(q_recent) + (size_t)(l0 - layer0) * c.batch * c.n_q_heads * c.window * c.head_dim * es;
     char* stats_r = wsb + w.stats + heads0 * 8 * c.n_modalities;
     int32_t* bud_r = budgets + heads0 * c.n_modalities;
-    e = launch_score_ragged(dr, c, qr, k_c, kv_off + heads0, kv_len + heads0, longest, region_tokens(c) * c.batch, psi_c, wsb + w.score, st);
-    if (e == hipSuccess) e = launch_restats(dr, c, psi_c, kept_idx, mask, kv_off + heads0, kv_len + heads0, h->appended[l0], pool_c, rowmod,
+    e = launch_score_ragged(dr, c, qr, k_work, off_work + heads0, kv_len + heads0, longest, cache_rows, psi_c, wsb + w.score, st);
+    if (e == hipSuccess) e = launch_restats(dr, c, psi_c, idx_work, mask, off_work + heads0, kv_len + heads0, h->appended[l0], pool_c, rowmod,
                                             stats_r, bud_r, st);
-    if (e == hipSuccess) e = launch_select(dr, c, pool_c, mask, bud_r, kv_off + heads0, kv_len + heads0, sel, st, kv_len + heads0, rowmod);
-    if (e == hipSuccess) e = launch_compact(dr, c, k_c, v_c, kept_idx, sel, kv_off + heads0, kv_len + heads0, bud_r, h->appended[l0],
+    if (e == hipSuccess) e = launch_select(dr, c, pool_c, mask, bud_r, off_work + heads0, kv_len + heads0, sel, st, kv_len + heads0, rowmod);
+    if (e == hipSuccess) e = launch_compact(dr, c, k_work, v_work, idx_work, sel, off_work + heads0, kv_len + heads0, bud_r, h->appended[l0],
                                             h->gen_base[l0], st);
     if (e == hipSuccess) for (int l = l0; l < l1; ++l) { h->gen_base[l] += h->appended[l]; h->appended[l] = 0; }
     l0 = l1;
+  }
+  if (c.page_rows && e == hipSuccess) {
+    // the survivors go back to the heads' initial pages; every page taken since is free again
+    e = launch_linear_copy(make_dims(c, n), c, k_c, v_c, kept_idx, kv_off, kv_len, make_paging(h), (long long)layer0 * c.batch * c.n_kv_heads,
+                           longest, k_work, v_work, idx_work, reinterpret_cast<int64_t*>(wsb + w.lin_off), true, st);
+    if (e == hipSuccess) e = launch_pool_reset(make_paging(h), c.batch, st);
   }
   return hip_fail(h, e);
 }

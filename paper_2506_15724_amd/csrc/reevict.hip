@@ -17,6 +17,8 @@
 //                    batches of rows, read completely before any is written, never overwrite a row
 //                    that is still to be read
 #include "common.h"
+
+#include <algorithm>
 #include "mpa_split.h"
 
 namespace madakv {
@@ -169,6 +171,113 @@ hipError_t launch_compact(const Dims& dm, const madakv_config& c, void* k_c, voi
   else if (lpr == 16) hipLaunchKernelGGL((compact_kernel<16>), dim3(dm.heads), dim3(RE_THREADS), 0, st, a);
   else if (lpr == 32) hipLaunchKernelGGL((compact_kernel<32>), dim3(dm.heads), dim3(RE_THREADS), 0, st, a);
   else return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+// ---- paged reduced cache ------------------------------------------------------------------------------
+// A head's rows are its initial pages (which follow each other at kv_off) and pages taken later from the
+// top of the batch item's region, listed in its table.  Re-eviction works on a linear copy: the rows of
+// every head are laid end to end in the workspace (linear_offsets_kernel, linear_copy_kernel: as many rows
+// as the cache itself holds), the kernels above run on that copy
+// as they run on contiguous segments, and the surviving rows, never more than the initial pages hold, go
+// back to the head's initial pages (write_back_kernel).  The pages taken since are free again afterwards:
+// the call covers all layers, so the pools start over (pool_reset_kernel).
+struct LinearArgs {
+  ru32x4_t* k_c; ru32x4_t* v_c; int32_t* kept_idx;          // the paged cache
+  ru32x4_t* k_lin; ru32x4_t* v_lin; int32_t* kept_lin;      // the linear copy: head i at rows [lin_off[i], + its length)
+  int64_t* lin_off;                                         // [heads] running sum of the lengths (linear_offsets_kernel)
+  const int64_t* seg_off; const int32_t* seg_len; const int32_t* page_tbl;
+  int entries, shift, lpr;                                  // table entries per head, log2(page rows), 16-byte pieces per row
+  int heads;
+};
+constexpr int LIN_ROWS = 64;                                // rows per workgroup
+
+// lin_off[i] = sum of the lengths of the heads before i: one workgroup, every thread a stretch of consecutive heads
+__global__ __launch_bounds__(1024) void linear_offsets_kernel(LinearArgs a) {
+  __shared__ long long s_sum[1024];
+  const int tid = threadIdx.x;
+  const int per = (a.heads + 1023) / 1024;
+  const int h0 = min(tid * per, a.heads), h1 = min(h0 + per, a.heads);
+  long long mine = 0;
+  for (int h = h0; h < h1; ++h) mine += max(a.seg_len[h], 0);
+  s_sum[tid] = mine;
+  __syncthreads();
+  for (int o = 1; o < 1024; o <<= 1) {                     // inclusive scan of the stretches' sums
+    const long long add = tid >= o ? s_sum[tid - o] : 0;
+    __syncthreads();
+    s_sum[tid] += add;
+    __syncthreads();
+  }
+  long long run = s_sum[tid] - mine;
+  for (int h = h0; h < h1; ++h) { a.lin_off[h] = run; run += max(a.seg_len[h], 0); }
+}
+
+__global__ __launch_bounds__(RE_THREADS) void linear_copy_kernel(LinearArgs a) {
+  const int head = blockIdx.y, tid = threadIdx.x;
+  const int len = a.seg_len[head];
+  const int r0 = blockIdx.x * LIN_ROWS;
+  if (r0 >= len) return;
+  const long long off = a.seg_off[head];
+  const int32_t* tbl = a.page_tbl + (long long)head * a.entries;
+  const int init_rows = tbl[0] << a.shift;
+  const int rows = min(LIN_ROWS, len - r0);
+  for (int e = tid; e < rows * a.lpr; e += RE_THREADS) {
+    const int r = r0 + e / a.lpr, piece = e % a.lpr;
+    long long src = off + r;
+    if (r >= init_rows) { const int q = r - init_rows; src = ((long long)tbl[1 + (q >> a.shift)] << a.shift) + (q & ((1 << a.shift) - 1)); }
+    const long long dst = a.lin_off[head] + r;
+    a.k_lin[dst * a.lpr + piece] = __builtin_nontemporal_load(a.k_c + src * a.lpr + piece);
+    a.v_lin[dst * a.lpr + piece] = __builtin_nontemporal_load(a.v_c + src * a.lpr + piece);
+    if (piece == 0) a.kept_lin[dst] = r < init_rows ? a.kept_idx[src] : 0;   // (rows in later pages are generated tokens: their positions are computed)
+  }
+}
+
+__global__ __launch_bounds__(RE_THREADS) void write_back_kernel(LinearArgs a) {
+  const int head = blockIdx.y, tid = threadIdx.x;
+  const int len = a.seg_len[head];                          // the length after compaction
+  const int r0 = blockIdx.x * LIN_ROWS;
+  if (r0 >= len) return;
+  const long long off = a.seg_off[head];
+  const int rows = min(LIN_ROWS, len - r0);
+  for (int e = tid; e < rows * a.lpr; e += RE_THREADS) {
+    const int r = r0 + e / a.lpr, piece = e % a.lpr;
+    const long long src = a.lin_off[head] + r, dst = off + r;
+    a.k_c[dst * a.lpr + piece] = a.k_lin[src * a.lpr + piece];
+    a.v_c[dst * a.lpr + piece] = a.v_lin[src * a.lpr + piece];
+    if (piece == 0) a.kept_idx[dst] = a.kept_lin[src];
+  }
+}
+
+__global__ __launch_bounds__(256) void pool_reset_kernel(unsigned long long* pool_top, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) pool_top[i] = 0ULL;
+}
+
+// longest: at least the length of the longest head of the call (sizes the grids).  back = false: the copy (and the
+// heads' offsets in it); true: the first seg_len rows of every head's copy go back to its initial pages
+hipError_t launch_linear_copy(const Dims& dm, const madakv_config& c, void* k_c, void* v_c, int32_t* kept_idx, const int64_t* seg_off,
+                              const int32_t* seg_len, const Paging& pg, long long head0, int longest, void* k_lin, void* v_lin,
+                              int32_t* kept_lin, int64_t* lin_off, bool back, hipStream_t st) {
+  LinearArgs a;
+  a.k_c = static_cast<ru32x4_t*>(k_c); a.v_c = static_cast<ru32x4_t*>(v_c); a.kept_idx = kept_idx;
+  a.k_lin = static_cast<ru32x4_t*>(k_lin); a.v_lin = static_cast<ru32x4_t*>(v_lin); a.kept_lin = kept_lin; a.lin_off = lin_off;
+  a.seg_off = seg_off; a.seg_len = seg_len; a.page_tbl = pg.table + head0 * pg.entries;
+  a.entries = pg.entries; a.shift = 0;
+  while ((1 << a.shift) < pg.page_rows) ++a.shift;
+  a.lpr = dm.d * (c.cache_fp8 ? 1 : (c.dtype == MADAKV_BF16 ? 2 : 4)) / 16;
+  a.heads = dm.heads;
+  const dim3 grid((unsigned)((std::max(longest, 1) + LIN_ROWS - 1) / LIN_ROWS), dm.heads);
+  if (back) {
+    hipLaunchKernelGGL(write_back_kernel, grid, dim3(RE_THREADS), 0, st, a);
+  } else {
+    hipLaunchKernelGGL(linear_offsets_kernel, dim3(1), dim3(1024), 0, st, a);
+    hipLaunchKernelGGL(linear_copy_kernel, grid, dim3(RE_THREADS), 0, st, a);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_pool_reset(const Paging& pg, int batch, hipStream_t st) {
+  hipLaunchKernelGGL(pool_reset_kernel, dim3((batch + 255) / 256), dim3(256), 0, st, pg.pool_top, batch);
   return hipGetLastError();
 }
 

@@ -866,17 +866,90 @@ def test_reeviction_during_generation(name, fp8):
     eng.close()
 
 
+@pytest.mark.parametrize("name,P,fp8", [("bf16_mha", 16, 0), ("bf16_gqa7", 16, 0), ("bf16_odd", 16, 1)])
+def test_reeviction_on_a_paged_cache(name, P, fp8):
+    """madakv_reevict with page_rows > 0, twice, next to the same steps on contiguous segments (which
+    test_reeviction_during_generation checks stage by stage against the oracle): the same budgets, lengths,
+    surviving rows and original positions bit for bit, the survivors back in the heads' initial pages, and the
+    same decode outputs afterwards for more steps than the page pools hold without the pages handed back."""
+    rounds = (21, 9)                    # (every head fills its last initial page and one or two later pages)
+    wl = small_workloads()[name].scaled(decode_steps=max(rounds))
+    NL, B, H, Hq, L, W, d = wl.n_layers, wl.batch, wl.n_kv_heads, wl.n_q_heads, wl.ctx_len, wl.window, wl.head_dim
+    q, k, v, mask, masks = PU.make_inputs(wl, DEV)
+    flat, paged = engine(wl, cache_fp8=fp8), engine(wl, cache_fp8=fp8, page_rows=P)
+    for eng in (flat, paged):
+        eng.score(0, NL, q, k, mask); eng.allocate(0, NL); eng.select_gather(0, NL, k, v, mask)
+    torch.cuda.synchronize()
+    len0 = flat.kv_len.cpu().numpy().copy()
+    off_f, off_p = flat.kv_off.cpu().numpy(), paged.kv_off.cpu().numpy()
+    q_hist = [q[:, :, :, r] for r in range(W)]
+    out_f = torch.empty(NL, B, Hq, d, dtype=torch.float32, device=DEV)
+    out_p = torch.empty_like(out_f)
+    step = 0
+
+    def decode_both():
+        nonlocal step, q_hist
+        dq, dk, dv = WL.decode_inputs_all(wl, step, DEV)
+        flat.decode_attn(0, NL, dq, dk, dv, out_f)
+        paged.decode_attn(0, NL, dq, dk, dv, out_p)
+        torch.cuda.synchronize()
+        assert torch.equal(out_f, out_p), f"paged and contiguous caches differ at step {step}"
+        q_hist.append(dq); q_hist = q_hist[-W:]
+        step += 1
+
+    for T in rounds:
+        for _ in range(T):
+            decode_both()
+        q_recent = torch.stack(q_hist, dim=3).contiguous()
+        say(f"{name}: madakv_reevict on both caches after {T} more steps")
+        for eng in (flat, paged):
+            eng.reevict_ws = None
+            eng.reevict(0, NL, q_recent, mask)
+        torch.cuda.synchronize()
+        assert torch.equal(flat.kv_len, paged.kv_len) and (paged.kv_len.cpu().numpy() == len0).all()
+        assert torch.equal(flat.budgets, paged.budgets)
+        for l in range(NL):
+            for b in range(B):
+                for h in range(H):
+                    n, of, op = int(len0[l, b, h]), int(off_f[l, b, h]), int(off_p[l, b, h])
+                    assert torch.equal(paged.k_c[op:op + n], flat.k_c[of:of + n]) and torch.equal(paged.v_c[op:op + n], flat.v_c[of:of + n])
+                    assert torch.equal(paged.kept_idx[op:op + n], flat.kept_idx[of:of + n])
+    # generation goes on: five more steps would not fit the pools if the pages of the rounds above were still taken
+    for _ in range(max(rounds)):
+        decode_both()
+    tbl = paged.page_table_host()
+    cap_b = paged.capacity // B
+    for b in range(B):
+        taken = []
+        for l in range(NL):
+            for h in range(H):
+                n0 = int(len0[l, b, h]); init = int(tbl[l, b, h, 0])
+                extra = max(0, -(-(n0 + max(rounds) - init * P) // P))
+                taken += [int(x) for x in tbl[l, b, h, 1:1 + extra]]
+        assert len(set(taken)) == len(taken)
+        assert all(b * cap_b // P <= x < (b + 1) * cap_b // P for x in taken)
+    flat.close(); paged.close()
+
+
 def test_reeviction_refusals():
     wl = small_workloads()["bf16_mha"].scaled(n_layers=1, batch=1, decode_steps=2)
     q, k, v, mask, masks = PU.make_inputs(wl, DEV)
     qr = q.clone()
-    for kw, status in ((dict(page_rows=16), -7), (dict(budget=wl.ctx_len), -3)):
+    for kw, status in ((dict(budget=wl.ctx_len), -3),):
         eng = engine(wl, **kw)
         eng.reevict_ws = torch.empty(MB.madakv_reevict_workspace_bytes(eng.h, 1), dtype=torch.uint8, device=DEV)
         with pytest.raises(MB.MadaKVError) as ei:
             eng.reevict(0, 1, qr, mask)
         assert ei.value.status == status
         eng.close()
+    # a paged cache is re-evicted as a whole (the pages it hands back belong to pools that all layers share)
+    wl2 = wl.scaled(n_layers=2)
+    eng = engine(wl2, page_rows=16)
+    eng.reevict_ws = torch.empty(MB.madakv_reevict_workspace_bytes(eng.h, 2), dtype=torch.uint8, device=DEV)
+    with pytest.raises(MB.MadaKVError) as ei:
+        eng.reevict(1, 1, qr, mask)
+    assert ei.value.status == -1
+    eng.close()
     f32 = small_workloads()["tiny_fp32"]
     eng = engine(f32)
     eng.reevict_ws = torch.empty(MB.madakv_reevict_workspace_bytes(eng.h, 1), dtype=torch.uint8, device=DEV)
