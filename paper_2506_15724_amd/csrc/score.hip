@@ -1431,8 +1431,19 @@ static void launch_wide_pair(const ScoreArgs& a0, int heads, hipStream_t st) {
   constexpr int TK1 = WIDE8 ? 128 : 64, BS1 = WIDE8 ? 4 : 2, BS2 = WIDE8 ? 1 : 2;     // (what the registers hold)
   const size_t lds1 = (size_t)DMA_NBUF * TK1 * D * 2;
   const size_t lds2 = (size_t)DMA_NBUF * 64 * D * 2 + ((size_t)a.mpad + 2 * 4 * 64) * sizeof(float);
-  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_wide_dma_kernel<D, NW1, 1, TK1, BS1, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
-  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_wide_dma_kernel<D, 4, NRB2, 64, BS2, 2>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
+  static size_t allowed[2][64] = {};            // (per instantiation and device; set again only when a call needs more)
+  int dev = 0;
+  (void)hipGetDevice(&dev);
+  size_t& allowed1 = allowed[0][dev & 63];
+  size_t& allowed2 = allowed[1][dev & 63];
+  if (lds1 > allowed1) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_wide_dma_kernel<D, NW1, 1, TK1, BS1, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
+    allowed1 = lds1;
+  }
+  if (lds2 > allowed2) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_wide_dma_kernel<D, 4, NRB2, 64, BS2, 2>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
+    allowed2 = lds2;
+  }
   if (!a.lse) {
     hipLaunchKernelGGL((score_wide_dma_kernel<D, NW1, 1, TK1, BS1, 1>), grid, dim3(NW1 * 64), lds1, st, a);
     hipLaunchKernelGGL(score_combine_kernel, dim3(heads), dim3(256), 0, st, a);
