@@ -967,6 +967,8 @@ def _window_workloads():
             "bf16_gqa7": W["bf16_gqa7"], "bf16_w64": W["bf16_w64"],
             # 79 chunks per head: the row statistics travel in two levels
             "bf16_40k": W["bf16_mha"].scaled(name="bf16_40k", ctx_len=40001, budget=600, n_layers=1, batch=1, n_q_heads=2, n_kv_heads=2, n_images=20),
+            # both at once: two blocks of proxy rows, 66 chunks per head
+            "bf16_w64_34k": W["bf16_w64"].scaled(name="bf16_w64_34k", ctx_len=33555, budget=500, n_layers=1, batch=1, n_q_heads=1, n_kv_heads=1, n_images=16),
             "bf16_gqa2_w20": W["bf16_mha"].scaled(name="bf16_gqa2_w20", ctx_len=1777, window=20, budget=222, n_layers=2, batch=1,
                                                   n_q_heads=4, n_kv_heads=2)}
 
