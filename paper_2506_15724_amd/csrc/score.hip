@@ -299,8 +299,10 @@ _Pragma("unroll") \
 // unit; the contraction is a fraction of that), so the layout serves the vector unit: wave w owns
 // proxy rows [32 NRB w, 32 NRB (w + 1)) for all keys of the workgroup's chunk and keeps their Q
 // fragments in registers; the waves share the keys.  Sweep 1 needs no merge among the waves (a row's
-// statistics over the chunk are complete in its wave); sweep 2 adds the waves' partial column sums
-// through LDS, in wave order, one tile behind the arithmetic.
+// statistics over the chunk are complete in its wave) and multiplies the other way round, S^T = K Q^T:
+// a lane then holds one row against 16 keys, the running (max, sum) of a row is one register pair and
+// in-lane work.  Sweep 2 (S = Q K^T: a lane holds one key against 16 rows, the column sum is in-lane)
+// adds the waves' partial column sums through LDS, in wave order, one tile behind the arithmetic.
 // The keys are fetched straight into LDS (global_load_lds, 16 bytes per lane): no register holds a
 // key on its way, so three tiles form a ring with two tiles in flight while the third is multiplied.
 // A wave's load instruction fills 1 KB of consecutive LDS (lane i at base + 16 i), so rows cannot be
@@ -314,12 +316,15 @@ _Pragma("unroll") \
 // and the barrier that follows also tells that everybody is done with the tile the next load overwrites.
 // ------------------------------------------------------------------------------------
 constexpr int DMA_NBUF = 3;
+#ifndef MADAKV_P1_WPE
+#define MADAKV_P1_WPE 3      // waves per SIMD of sweep 1 (its registers allow three)
+#endif
 
 typedef __attribute__((address_space(3))) void* lds_void_ptr_t;
 typedef const __attribute__((address_space(1))) void* global_void_ptr_t;
 
 template <int D, int NW, int NRB, int DMA_TK, int BS, int PASS>   // NW waves of NRB row blocks each; tiles of DMA_TK keys; the vector arithmetic runs on BS subtiles at a time
-__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void score_wide_dma_kernel(ScoreArgs a) {
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(PASS == 1 ? MADAKV_P1_WPE : 2, PASS == 1 ? MADAKV_P1_WPE : 2))) void score_wide_dma_kernel(ScoreArgs a) {
   constexpr int NT = NW * 64;
   constexpr int KS = D / 16;                  // MFMA k-steps
   constexpr int PPR = D / 8;                  // 16-byte pieces per row
@@ -349,7 +354,11 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const int first_masked = a.L - a.W + 1;      // keys below this are visible to every proxy row
 
   // sweep 2: the rows' offsets (ordinary LDS traffic, so before the first key is on its way)
-  float st_m[NRB][16], st_l[NRB][16];          // sweep 1: running (max in accumulator units, sum); sweep 2: st_m holds the rows' offsets
+  // sweep 2: st_m holds the offsets of the 16 rows a lane has of each block.  Sweep 1 runs the contraction the
+  // other way round (S^T = K Q^T: a lane holds ONE row and 16 keys of a subtile), so its running (max in
+  // accumulator units, sum) is one pair per lane and block: row_m, row_l.
+  float st_m[PASS == 2 ? NRB : 1][16];
+  float row_m[NRB], row_l[NRB];
   if (PASS == 2) {
     const float* rs = a.rowstat + (long long)head * a.nsplit * a.mpad * 2;
     for (int r = tid; r < a.mpad; r += NT) {
@@ -368,9 +377,10 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
       const int row = (rb0 + b) * 32 + (j >> 2) * 8 + half * 4 + (j & 3);     // (a block past the last: rows that count for nothing)
-      st_m[b][j] = (PASS == 2) ? (row < a.mpad ? offs[row] : __builtin_inff()) : NEG_BIG;
-      st_l[b][j] = 0.f;
+      if (PASS == 2) st_m[b][j] = row < a.mpad ? offs[row] : __builtin_inff();
     }
+#pragma unroll
+  for (int b = 0; b < NRB; ++b) { row_m[b] = NEG_BIG; row_l[b] = 0.f; }
   __syncthreads();                             // (the last ordinary LDS access of the kernel)
 
   // tile T of the chunk -> ring slot T mod 3.  Load j of wave w fills bytes [(w LPT + j) 1024, + 1024) of the slot:
@@ -453,17 +463,31 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
             x[u] = valid ? x[u] : NEG_BIG;                                                           \
           }                                                                                          \
         }                                                                                            \
-        if (PASS == 1) {                                                                             \
-          float mn = st_m[b][j];                                                                     \
-          _Pragma("unroll") for (int u = 0; u < BS; ++u) mn = fmaxf(mn, x[u]);                       \
-          float l = st_l[b][j] * fast_exp2((st_m[b][j] - mn) * a.scale_log2);                        \
-          const float ms = mn * a.scale_log2;                                                        \
-          _Pragma("unroll") for (int u = 0; u < BS; ++u) l += fast_exp2(fmaf(x[u], a.scale_log2, -ms)); \
-          st_m[b][j] = mn; st_l[b][j] = l;                                                           \
-        } else {                                                                                     \
-          _Pragma("unroll") for (int u = 0; u < BS; ++u) colsum[u] += fast_exp2(fmaf(x[u], a.scale_log2, -st_m[b][j])); \
+        _Pragma("unroll") for (int u = 0; u < BS; ++u) colsum[u] += fast_exp2(fmaf(x[u], a.scale_log2, -st_m[b][j])); \
+      }                                                                                              \
+    }
+    // Sweep 1 on one subtile: S^T = K Q^T, so that D[key][row] leaves a lane with the logits of its own row
+    // (row `col` of the block) against 16 keys: keys t0 + 8 (j >> 2) + 4 half + (j & 3).  The row's maximum and sum
+    // are then in-lane work, one rescaling of the sum per subtile; the two halves of a row meet after the last tile.
+#define MADAKV_DMA_ROWS(TAIL)                                                                        \
+    _Pragma("unroll") for (int b = 0; b < NRB; ++b) {                                                \
+      f32x16_t xt = f32x16_t{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}; \
+      _Pragma("unroll") for (int ks = 0; ks < KS; ++ks)                                              \
+        xt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag[0][ks], areg[b][ks], xt, 0, 0, 0);        \
+      if (TAIL) {                                                                                    \
+        const int row = (rb0 + b) * 32 + col;                                                        \
+        const int pos = a.L - a.W + (row % a.W);                                                     \
+        _Pragma("unroll") for (int j = 0; j < 16; ++j) {                                             \
+          const int key = chunk0 + t * DMA_TK + s0 * 32 + 8 * (j >> 2) + 4 * half + (j & 3);         \
+          xt[j] = ((key < chunk1) && (key <= pos) && (row < a.M)) ? xt[j] : NEG_BIG;                 \
         }                                                                                            \
       }                                                                                              \
+      float mn = row_m[b];                                                                           \
+      _Pragma("unroll") for (int j = 0; j < 16; ++j) mn = fmaxf(mn, xt[j]);                          \
+      float l = row_l[b] * fast_exp2((row_m[b] - mn) * a.scale_log2);                                \
+      const float ms = mn * a.scale_log2;                                                            \
+      _Pragma("unroll") for (int j = 0; j < 16; ++j) l += fast_exp2(fmaf(xt[j], a.scale_log2, -ms)); \
+      row_m[b] = mn; row_l[b] = l;                                                                   \
     }
 #pragma unroll 1
     for (int s0 = 0; s0 < NSUB; s0 += BS) {
@@ -512,7 +536,11 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
             acc[0][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(areg[b][ks], bfrag[0][ks], acc[0][b], 0, 0, 0); \
         }                                                                                            \
       }
-      if (tail) {
+      if (PASS == 1) {
+        static_assert(PASS == 2 || BS == 1, "sweep 1 takes one subtile at a time");
+        (void)acc;
+        if (tail) { MADAKV_DMA_ROWS(true) } else { MADAKV_DMA_ROWS(false) }
+      } else if (tail) {
         MADAKV_DMA_CONTRACT
         MADAKV_DMA_VECTOR(true)
       } else {
@@ -541,6 +569,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       }
     }
 #undef MADAKV_DMA_VECTOR
+#undef MADAKV_DMA_ROWS
   }
 #undef MADAKV_DMA_ISSUE
   // nothing may still be on its way into this workgroup's LDS when it ends
@@ -556,18 +585,16 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       if (key < chunk1) __builtin_nontemporal_store(((c0 + c1) + c2) + c3, a.psi + ((long long)head * a.L + key));
     }
   } else {
-    // per row: maximum over the 32 key columns of the half, sums rescaled to it and added
+    // the two halves of a row (their keys interleave in groups of four) meet; lanes 0..31 hold rows 0..31 of a block
     float* rs = a.rowstat + ((long long)head * a.nsplit + split) * a.mpad * 2;
 #pragma unroll
     for (int b = 0; b < NRB; ++b) {
-#pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        const float m = half_reduce<0>(st_m[b][j]);
-        const float l = half_reduce<1>(st_l[b][j] * fast_exp2((st_m[b][j] - m) * a.scale_log2));
-        if (rb0 + b < MB && col == 0) {
-          const int row = (rb0 + b) * 32 + (j >> 2) * 8 + half * 4 + (j & 3);
-          rs[row * 2] = m * a.scale_log2; rs[row * 2 + 1] = l;
-        }
+      const float m2 = __shfl_xor(row_m[b], 32, 64), l2 = __shfl_xor(row_l[b], 32, 64);
+      const float m = fmaxf(row_m[b], m2);
+      const float l = row_l[b] * fast_exp2((row_m[b] - m) * a.scale_log2) + l2 * fast_exp2((m2 - m) * a.scale_log2);
+      if (rb0 + b < MB && half == 0) {
+        const int row = (rb0 + b) * 32 + col;
+        rs[row * 2] = m * a.scale_log2; rs[row * 2 + 1] = l;
       }
     }
   }
@@ -1290,7 +1317,7 @@ __global__ __launch_bounds__(256) void score_combine_kernel(ScoreArgs a) {
 // chunks per head from which the merge is hoisted out of sweep 2
 constexpr int COMBINE_FROM = 8;
 #ifndef MADAKV_WIDE_WGS
-#define MADAKV_WIDE_WGS 256
+#define MADAKV_WIDE_WGS 768
 #endif
 #ifndef MADAKV_WIDE_WGS2
 #define MADAKV_WIDE_WGS2 512
@@ -1424,11 +1451,9 @@ template <int D, bool WIDE8>
 static void launch_wide_pair(const ScoreArgs& a0, int heads, hipStream_t st) {
   ScoreArgs a = a0;
   dim3 grid(a.nsplit, heads);
-  // sweep 1 carries a running (max, sum) per row and lane on top of the fragments: with two row blocks per wave
-  // that does not fit 256 registers, so up to 256 rows take eight waves of one block each (one workgroup per CU,
-  // tiles of 128 keys whose four subtiles share one rescaling), sweep 2 four waves of two blocks (two per CU)
-  constexpr int NW1 = WIDE8 ? 8 : 4, NRB2 = WIDE8 ? 2 : 1;
-  constexpr int TK1 = WIDE8 ? 128 : 64, BS1 = WIDE8 ? 4 : 2, BS2 = WIDE8 ? 1 : 2;     // (what the registers hold)
+  // both sweeps: four waves of one (up to 128 rows) or two row blocks, tiles of 64 keys, two workgroups per CU
+  constexpr int NW1 = 4, NRB1 = WIDE8 ? 2 : 1, NRB2 = NRB1;
+  constexpr int TK1 = 64, BS1 = 1, BS2 = WIDE8 ? 1 : 2;     // (sweep 2: what the registers hold)
   const size_t lds1 = (size_t)DMA_NBUF * TK1 * D * 2;
   const size_t lds2 = (size_t)DMA_NBUF * 64 * D * 2 + ((size_t)a.mpad + 2 * 4 * 64) * sizeof(float);
   static size_t allowed[2][64] = {};            // (per instantiation and device; set again only when a call needs more)
@@ -1437,7 +1462,7 @@ static void launch_wide_pair(const ScoreArgs& a0, int heads, hipStream_t st) {
   size_t& allowed1 = allowed[0][dev & 63];
   size_t& allowed2 = allowed[1][dev & 63];
   if (lds1 > allowed1) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_wide_dma_kernel<D, NW1, 1, TK1, BS1, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_wide_dma_kernel<D, NW1, NRB1, TK1, BS1, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
     allowed1 = lds1;
   }
   if (lds2 > allowed2) {
@@ -1445,7 +1470,7 @@ static void launch_wide_pair(const ScoreArgs& a0, int heads, hipStream_t st) {
     allowed2 = lds2;
   }
   if (!a.lse) {
-    hipLaunchKernelGGL((score_wide_dma_kernel<D, NW1, 1, TK1, BS1, 1>), grid, dim3(NW1 * 64), lds1, st, a);
+    hipLaunchKernelGGL((score_wide_dma_kernel<D, NW1, NRB1, TK1, BS1, 1>), grid, dim3(NW1 * 64), lds1, st, a);
     hipLaunchKernelGGL(score_combine_kernel, dim3(heads), dim3(256), 0, st, a);
     a.nmerge = 1;
   }
