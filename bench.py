@@ -414,15 +414,15 @@ def main():
                  if read_profile(prof, "decode_attn_kernel_avg_us") else None)]
         if (Hq // H) * W > 64:
             # more than 64 proxy rows: the scoring kernels are bound by the vector unit.  Issue slots per logit
-            # (a wave instruction occupies a SIMD's 16 lanes for 4 cycles, exp2 for 16): sweep 1 = 1.25 exp2 + 4.75
-            # plain instructions = 9.75 slots, sweep 2 = 1 exp2 + 2 plain = 6; peak = 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz
+            # (a wave instruction occupies a SIMD's 16 lanes for 4 cycles, exp2 for 16): sweep 1 = 1.06 exp2 + 3.25
+            # plain instructions = 7.5 slots, sweep 2 = 1 exp2 + 2 plain = 6; peak = 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz
             rows_pad = ((Hq // H) * W + 31) // 32 * 32
-            slots = 15.75 * rows_pad * L * NL * B * H
+            slots = 13.5 * rows_pad * L * NL * B * H
             alu_peak = 256 * 4 * 16 * 2.4e9
             e0_ = result["roofline_by_kernel"][0]
             e0_.update({"bound": "alu", "alu_lane_slots": slots, "alu_achieved_Tslots_per_s": slots / (score_ms * 1e-3) / 1e12,
                         "alu_peak_Tslots_per_s": alu_peak / 1e12, "alu_frac": slots / (score_ms * 1e-3) / alu_peak,
-                        "alu_note": "vector-unit issue slots of the two sweeps' arithmetic (15.75 per logit, padded rows included) against "
+                        "alu_note": "vector-unit issue slots of the two sweeps' arithmetic (13.5 per logit, padded rows included) against "
                                     "256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz; the HBM figures beside it count K once"})
         # the contraction side of scoring: flops of Eq. 7's Q K^T (computed once per key) against the dense bf16 MFMA peak
         ctr = "score_fused_kernel_" + wl.name + "_mfma_counters.txt"
