@@ -443,12 +443,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(PASS ==
     const int tile_end = chunk0 + (t + 1) * DMA_TK;
     const bool tail = tile_end > first_masked || tile_end > chunk1;
 
-    // the sweep's vector arithmetic runs on the BS logits a lane holds of every row after the contractions of BS
-    // subtiles.  Sweep 1 keeps the running maximum in accumulator units (scale > 0): per row and batch one
-    // rescaling of the sum and one exp2 per logit.  A row that has seen no key yet holds NEG_BIG and a meaningless,
-    // finite sum, which the first real key (and any merge with real statistics) multiplies by exp2(-huge) = 0.
-    // In a tail tile (it holds keys that some proxy row must not see: the last W - 1 keys of the head, keys past
-    // the chunk's end) such logits become NEG_BIG.
+    // Sweep 2's vector arithmetic runs on the BS logits a lane holds of every row after the contractions of BS
+    // subtiles.  In a tail tile (it holds keys that some proxy row must not see: the last W - 1 keys of the head,
+    // keys past the chunk's end) such logits become NEG_BIG, in both sweeps.
 #define MADAKV_DMA_VECTOR(TAIL)                                                                      \
     _Pragma("unroll") for (int b = 0; b < NRB; ++b) {                                                \
       _Pragma("unroll") for (int j = 0; j < 16; ++j) {                                               \
@@ -469,6 +466,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(PASS ==
     // Sweep 1 on one subtile: S^T = K Q^T, so that D[key][row] leaves a lane with the logits of its own row
     // (row `col` of the block) against 16 keys: keys t0 + 8 (j >> 2) + 4 half + (j & 3).  The row's maximum and sum
     // are then in-lane work, one rescaling of the sum per subtile; the two halves of a row meet after the last tile.
+    // The running maximum stays in accumulator units (scale > 0).  A row that has seen no key yet holds NEG_BIG and
+    // a meaningless, finite sum, which the first real key (and any merge with real statistics) multiplies by
+    // exp2(-huge) = 0.
 #define MADAKV_DMA_ROWS(TAIL)                                                                        \
     _Pragma("unroll") for (int b = 0; b < NRB; ++b) {                                                \
       f32x16_t xt = f32x16_t{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}; \
