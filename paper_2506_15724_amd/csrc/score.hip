@@ -485,7 +485,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(PASS ==
       float mn = row_m[b];                                                                           \
       _Pragma("unroll") for (int j = 0; j < 16; ++j) mn = fmaxf(mn, xt[j]);                          \
       float l = row_l[b] * fast_exp2((row_m[b] - mn) * a.scale_log2);                                \
-      const float ms = mn * a.scale_log2;                                                            \
+      /* (no key of the row seen yet: every x is NEG_BIG too, and x * scale - round(NEG_BIG * scale) would be the   \
+         product's rounding error, some 1e21 of either sign; against 0 the terms are exp2(-huge) = 0) */            \
+      const float ms = mn > 0.5f * NEG_BIG ? mn * a.scale_log2 : 0.f;                                \
       _Pragma("unroll") for (int j = 0; j < 16; ++j) l += fast_exp2(fmaf(xt[j], a.scale_log2, -ms)); \
       row_m[b] = mn; row_l[b] = l;                                                                   \
     }

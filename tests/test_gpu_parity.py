@@ -1289,7 +1289,8 @@ def test_widest_shapes():
                                           ctx_len=900, window=8, budget=120, n_images=1)
     _run_and_check_whole_path(wl)
 
-@pytest.mark.parametrize("shape", ["m128_d128", "m192_d64", "m80_d64_odd", "m224_long", "m96_one_tile", "m256_two_tiles"])
+@pytest.mark.parametrize("shape", ["m128_d128", "m192_d64", "m80_d64_odd", "m224_long", "m96_one_tile", "m256_two_tiles",
+                                   "m192_short_last_chunk", "m128_short_last_chunk"])
 def test_more_than_64_proxy_rows(shape):
     """G*W between 65 and 256: the two-sweep scoring kernels whose waves own blocks of proxy rows and share the keys
     through an LDS ring.  One and two row blocks per wave, both head dims, several chunks per head in both sweeps
@@ -1298,6 +1299,10 @@ def test_more_than_64_proxy_rows(shape):
           "m192_d64": dict(n_q_heads=6, n_kv_heads=2, head_dim=64, window=64, ctx_len=4100),
           "m80_d64_odd": dict(n_q_heads=4, n_kv_heads=2, head_dim=64, window=40, ctx_len=3001),
           "m224_long": dict(n_q_heads=7, n_kv_heads=1, head_dim=128, window=32, ctx_len=9001),
+          # the first sweep's last chunk holds 34 keys, fewer than the window: the first 30 rows of every query head
+          # see none of them (a workgroup whose rows have nothing to add up)
+          "m192_short_last_chunk": dict(n_q_heads=3, n_kv_heads=1, head_dim=128, window=64, ctx_len=9250),
+          "m128_short_last_chunk": dict(n_q_heads=2, n_kv_heads=1, head_dim=64, window=64, ctx_len=9250),
           # contexts of one and two LDS tiles: the ring's start-up and its end meet
           "m96_one_tile": dict(n_q_heads=3, n_kv_heads=1, head_dim=128, window=32, ctx_len=60, budget=44, n_images=1,
                                image_tokens=(10, 10), text_tokens=(4, 30)),
