@@ -1338,6 +1338,45 @@ def test_more_than_64_proxy_rows(shape):
     eng.close()
 
 
+def test_seeded_shapes_with_many_proxy_rows():
+    """Twenty seeded random shapes with 33..256 proxy rows (group sizes 1..8, windows 16..64, both head dims, lengths
+    around the chunk boundaries of both sweeps): psi of madakv_score and of madakv_window_attn_score, and the
+    attention output, against the oracle."""
+    rng = np.random.default_rng(20250615)
+    for it in range(20):
+        d = int(rng.choice([64, 128]))
+        while True:
+            G = int(rng.integers(1, 9)); W = int(rng.choice([16, 20, 32, 40, 64]))
+            if 32 < G * W <= 256:
+                break
+        H = int(rng.integers(1, 4)); NL = int(rng.integers(1, 3))
+        L = max(W + 40, int(rng.choice([300, 1024, 2048, 4096, 9216, 10240])) + int(rng.integers(-70, 70)))
+        budget = W + 20 + int(rng.integers(0, min(L - W - 30, 300)))
+        wl = WL.CONFIGS["llava_layer"].scaled(name=f"seeded{it}", n_layers=NL, batch=1, n_q_heads=G * H, n_kv_heads=H, head_dim=d,
+                                              window=W, ctx_len=L, budget=budget, n_images=1, image_tokens=(20, 60),
+                                              text_tokens=(10, 100), decode_steps=1)
+        say(f"shape {it}: d={d} G={G} W={W} ({G * W} rows) H={H} layers={NL} L={L}")
+        p = PU.oracle_params(wl)
+        q, k, v, mask, masks = PU.make_inputs(wl, DEV)
+        qh, kh, vh = WL.to_f64(q), WL.to_f64(k), WL.to_f64(v)
+        eng = engine(wl, out_fp32=1)
+        eng.score(0, NL, q, k, mask)
+        torch.cuda.synchronize()
+        psi_s = eng.psi.cpu().numpy().copy()
+        out = torch.full((NL, 1, G * H, W, d), float("nan"), dtype=torch.float32, device=DEV)
+        eng.window_attn_score(0, NL, q, k, v, mask, out)
+        torch.cuda.synchronize()
+        psi_w = eng.psi.cpu().numpy()
+        for l in range(NL):
+            psi_o = O.window_scores(qh[l, 0], kh[l, 0], p.scale)
+            for what, pg in (("score", psi_s[l, 0]), ("window attention", psi_w[l, 0])):
+                nbad, worst = PU.psi_close(pg, psi_o, G, W, L)
+                assert nbad == 0, (it, what, l, nbad, worst)
+            o_ref, _ = O.window_attention(qh[l, 0], kh[l, 0], vh[l, 0], p.scale)
+            assert np.abs(out[l, 0].cpu().numpy() - o_ref).max() <= PU.DECODE_ATOL, (it, l)
+        eng.close()
+
+
 def test_long_heads_take_the_chunk_parallel_path():
     """Heads of more than 16384 candidates on a handful of heads: statistics (Eq. 6, 9, pooling) and selection give
     every 16384-candidate chunk a workgroup of its own and meet in memory between launches.  Four chunks per head
