@@ -707,7 +707,7 @@ def test_paged_reduced_cache(name, P, fp8):
                 assert torch.equal(paged.v_c[off_p[l, b, h]:off_p[l, b, h] + n], flat.v_c[off_f[l, b, h]:off_f[l, b, h] + n])
     # the oracle's copy of two sampled heads' caches (decoded values for the 8-bit cache)
     dec = (lambda t: O.dequantize_e4m3(t.cpu().numpy())) if fp8 else WL.to_f64
-    samples = [(0, 0, 0), (NL - 1, B - 1, H - 1)]
+    samples = sorted({(0, 0, 0), (NL - 1, B - 1, H - 1)})
     caches = {s: [dec(flat.k_c[off_f[s]:off_f[s] + int(len0[s])]), dec(flat.v_c[off_f[s]:off_f[s] + int(len0[s])])] for s in samples}
     out_f = torch.empty(NL, B, wl.n_q_heads, d, dtype=torch.float32, device=DEV)
     out_p = torch.empty_like(out_f)
