@@ -148,7 +148,9 @@ int32_t madakv_compact_capacity_tokens(const madakv_handle* h, int64_t* tokens);
 /* Environment variables (diagnostics, read at every scoring call; not needed in normal use):
  *   MADAKV_SCORE_TWO_SWEEPS=1   score with the two-sweep kernels (K read twice) everywhere
  *   MADAKV_SCORE_SPIN_LIMIT=n   polls a workgroup of the one-sweep scoring kernel spends on a missing word
- *                               before it computes the head's row statistics alone (default 65536) */
+ *                               before it computes the head's row statistics alone (default 65536)
+ *   MADAKV_SCORE_NO_PARKED_CHUNKS=1   long heads: all chunks of a head in one launch of the one-sweep kernel, also
+ *                               where a few of them are in the way of one more head fitting the chip */
 
 /* Eq. 7, Eq. 6, Eq. 9 and pooling for layers [layer0, layer0 + n).
  *   q_win    [n, B, Hq, W, d]  queries of the last W prompt positions

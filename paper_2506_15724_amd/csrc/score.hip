@@ -53,6 +53,13 @@ struct ScoreArgs {
   float* psi_part;
   long long psi_part_stride;   // floats between two row blocks' copies
   int spin_limit;      // polls a workgroup of the one-sweep kernel spends on one missing word before it goes its own way
+  // one-sweep kernel on long heads whose chunks do not pack the chip's workgroup slots (see launch_fused): the last
+  // nstrag chunks of every head run in a launch of their own before the others (chunk_lo = first chunk of a launch),
+  // leave their row statistics as exchange words of the group level and their logits in `park`, and do not wait;
+  // the other chunks' launch leaves the heads' row offsets in offs_out, a small kernel finishes the parked chunks
+  int chunk_lo = 0, nstrag = 0;
+  float* park = nullptr;
+  float* offs_out = nullptr;
   int head0;           // first head of this launch (grid.y indexes head0 + y)
   float scale_log2;    // softmax scale * log2(e)
 };
@@ -687,7 +694,7 @@ __device__ __forceinline__ void score_head_stats_alone(const ScoreArgs& a, int L
 // leaves offs[r] = max + log2(sum) over all keys of the head (log2 domain; +inf for padding rows).
 // All threads call both; work that needs nobody else's statistics can sit between them.  The caller
 // adds the barrier after collect_row_stats.
-__device__ __forceinline__ void post_row_stats(const ScoreArgs& a, int head, int split, int fs, const float* part) {
+__device__ __forceinline__ void post_row_stats(const ScoreArgs& a, int head, int slot, int fs, const float* part) {   // slot: the chunk, or a word of the group level
   const int tid = threadIdx.x;
   if (fs == 1 || tid >= a.mpad) return;
   // a row none of whose keys here is visible has max NEG_BIG and a meaningless sum: merging it with
@@ -697,7 +704,7 @@ __device__ __forceinline__ void post_row_stats(const ScoreArgs& a, int head, int
   for (int w = 0; w < 4; ++w) merge_ml(m, l, part[(w * a.mpad + tid) * 2], part[(w * a.mpad + tid) * 2 + 1]);
   unsigned long long word = ((unsigned long long)__float_as_uint(l) << 32) | __float_as_uint(m);
   if (word == XCHG_EMPTY) word = 0x7fc000007fc00000ULL;            // cannot happen with finite inputs
-  __hip_atomic_store(xh + (long long)split * a.mpad + tid, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(xh + (long long)slot * a.mpad + tid, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Thread (r, pt) of the workgroup merges, in order, its share of the `n` words base[item * mpad + r]
@@ -818,7 +825,7 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(M
   __shared__ int s_fail;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int split = blockIdx.x;
+  const int split = blockIdx.x + a.chunk_lo;
   const int hv = a.head0 + blockIdx.y;        // head, or (head, block of 64 proxy rows) when there are more than 64
   const int head = hv / a.rb_count;
   const int rowbase = (hv % a.rb_count) * 64; // first proxy row of this workgroup's block
@@ -830,7 +837,8 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(M
   const int Lh = a.seg_len ? a.seg_len[head] : a.L;
   const long long base = a.seg_off ? a.seg_off[head] : (long long)head * a.L;
   const int fs = a.seg_len ? (Lh + CK - 1) / CK : a.fsplit;      // chunks of this head (the grid is sized for the longest)
-  if (split >= fs) return;
+  if (split >= fs + a.nstrag) return;
+  const bool parked = split >= fs;            // one of the head's last chunks, run ahead of the others
   // (F8: rows of D bytes; kg then counts in 2-byte units from a byte address that is base * D)
   const uint16_t* kg = F8 ? reinterpret_cast<const uint16_t*>(reinterpret_cast<const unsigned char*>(a.k) + base * D)
                           : reinterpret_cast<const uint16_t*>(a.k) + base * D;
@@ -945,8 +953,21 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(M
     }
   }
   __syncthreads();
+  if (parked) {
+    // its statistics as a word of the group level (behind the groups' own), its logits to memory; nobody is waited for
+    post_row_stats(a, hv, fs + (a.xgroups - a.nstrag) + (split - fs), fs, part);
+    float* pk = a.park + ((long long)hv * a.nstrag + (split - fs)) * (NS * NRB * 16 * SCORE_THREADS);
+#pragma unroll
+    for (int it = 0; it < NS; ++it)
+#pragma unroll
+      for (int b = 0; b < NRB; ++b)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) __builtin_nontemporal_store(lg[it][b][j], pk + ((it * NRB + b) * 16 + j) * SCORE_THREADS + tid);
+    return;
+  }
   exchange_row_stats<D, F8>(a, hv, split, fs, Lh, Mh, rowbase, kg, qs, part, offs, pm, &s_fail);
   __syncthreads();
+  if (a.offs_out && split == 0 && tid < a.mpad) a.offs_out[(long long)hv * a.mpad + tid] = offs[tid];
 
   // ---- column sums from the registers
   float off_r[NRB][16];
@@ -964,6 +985,36 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(M
     colsum += __shfl_xor(colsum, 32, 64);
     const int key = chunk0 + (it * 4 + wave) * 32 + col;
     if (half == 0 && key < chunk1) __builtin_nontemporal_store(colsum, (a.rb_count > 1 ? a.psi_part + (hv % a.rb_count) * a.psi_part_stride : a.psi) + (base + key));
+  }
+}
+
+// The parked chunks' column sums, from their logits and the heads' row offsets: the arithmetic (and its order) of the
+// kernel's own last step.  Grid (parked chunk, head).
+template <int NRB, int NS>
+__global__ __launch_bounds__(SCORE_THREADS) void score_fused_finish_kernel(ScoreArgs a) {
+  constexpr int CK = 4 * NS * 32;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int half = lane >> 5, col = lane & 31;
+  const int hv = a.head0 + blockIdx.y, sidx = blockIdx.x;
+  const int chunk0 = (a.fsplit + sidx) * CK;
+  const int chunk1 = min(a.L, chunk0 + CK);
+  const float* pk = a.park + ((long long)hv * a.nstrag + sidx) * (NS * NRB * 16 * SCORE_THREADS);
+  const float* offs = a.offs_out + (long long)hv * a.mpad;
+  float off_r[NRB][16];
+#pragma unroll
+  for (int b = 0; b < NRB; ++b)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) off_r[b][j] = offs[b * 32 + (j >> 2) * 8 + half * 4 + (j & 3)];
+#pragma unroll
+  for (int it = 0; it < NS; ++it) {
+    float colsum = 0.f;
+#pragma unroll
+    for (int b = 0; b < NRB; ++b)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) colsum += fast_exp2(__builtin_nontemporal_load(pk + ((it * NRB + b) * 16 + j) * SCORE_THREADS + tid) - off_r[b][j]);
+    colsum += __shfl_xor(colsum, 32, 64);
+    const int key = chunk0 + (it * 4 + wave) * 32 + col;
+    if (half == 0 && key < chunk1) __builtin_nontemporal_store(colsum, a.psi + ((long long)hv * a.L + key));
   }
 }
 
@@ -1367,6 +1418,19 @@ static int xchg_groups(int split) { return split <= FUSED_MAX_SPLIT ? 0 : (split
 // (More than 64 proxy rows: the prompt's keys take the two-sweep kernels above, which are bound by their vector
 // arithmetic either way and twice as fast as one sweep per block of 64 rows; the ragged rows of a reduced cache
 // still go through the one-sweep kernel in blocks.)
+// Long heads whose chunks pack the workgroup slots badly.  A workgroup keeps its slot until its whole head is
+// through; the chip holds FUSED_SLOTS workgroups of the kernel; k = slots / chunks heads fit at once, and when a
+// few chunks fewer per head would let k + 1 fit (171 chunks at a 128K context: 3 x 171 = 513), every (k + 1)-th
+// head's last chunk waits for a slot while its head-mates hold theirs idle.  Those few last chunks per head then
+// run ahead of the launch of the others (ScoreArgs::nstrag).  Returns their number (0: nothing to gain).
+constexpr int FUSED_SLOTS = 512, FUSED_MAX_PARKED = 8;
+static int fused_parked_chunks(int split) {
+  if (split <= FUSED_MAX_SPLIT) return 0;                 // (the parked chunks' words live at the group level)
+  const int k = FUSED_SLOTS / split, fewer = FUSED_SLOTS / (k + 1);
+  const int n = split - fewer;
+  return (fewer > FUSED_MAX_SPLIT && n >= 1 && n <= FUSED_MAX_PARKED && k * split * 10 < FUSED_SLOTS * 9) ? n : 0;
+}
+static size_t fused_park_bytes(const Dims& dm, int dtype);
 static bool fused_fits(const Dims& dm, int dtype) {
   return use_mfma(dm, dtype) && dm.M <= 64 && fused_split(dm) <= FUSED_MAX_SPLIT_2L && dm.heads <= 65535;
 }
@@ -1384,11 +1448,18 @@ static size_t xchg_bytes(const Dims& dm, int dtype) {
   const size_t per_head = (size_t)(fused_split(dm) + xchg_groups(fused_split(dm))) * fused_mpad(dm);
   return fused_fits(dm, dtype) ? ((size_t)dm.heads * fused_blocks(dm) * per_head * 8 + 255) / 256 * 256 : 0;
 }
+static size_t fused_park_bytes(const Dims& dm, int dtype) {
+  if (!fused_fits(dm, dtype)) return 0;
+  const int n = fused_parked_chunks(fused_split(dm));
+  const int ns = fused_mpad(dm) == 32 ? FUSED_NS1 : FUSED_NS2, nrb = fused_mpad(dm) / 32;
+  // the parked logits (one float per thread and logit register) and the heads' row offsets
+  return n ? ((size_t)dm.heads * n * ns * nrb * 16 * SCORE_THREADS * sizeof(float) + (size_t)dm.heads * fused_mpad(dm) * sizeof(float) + 255) / 256 * 256 : 0;
+}
 size_t score_ws_bytes(const Dims& dm, int dtype) {
   // the counter of lone workgroups, the row statistics of the two sweeps, the store sink, the exchange array of the
   // one-sweep kernel, its per-row-block copies of psi when there are more than 64 proxy rows
   const size_t part = fused_fits(dm, dtype) && fused_blocks(dm) > 1 ? (size_t)fused_blocks(dm) * dm.heads * dm.L * sizeof(float) : 0;
-  return 256 + rowstat_bytes(dm, dtype) + 256 + xchg_bytes(dm, dtype) + part;
+  return 256 + rowstat_bytes(dm, dtype) + 256 + xchg_bytes(dm, dtype) + part + fused_park_bytes(dm, dtype);
 }
 
 // psi = the row blocks' column sums added in block order (more than 64 proxy rows)
@@ -1411,18 +1482,27 @@ static void launch_fused(const ScoreArgs& a, int heads, hipStream_t st) {
   const size_t ldsf = ((size_t)a.mpad + 4 * 32) * (D + 8) * 2 + ((size_t)4 * a.mpad * 2 + a.mpad + 512) * sizeof(float);
   ScoreArgs b = a;
   b.head0 = a.head0 * a.rb_count;
-  const dim3 grid(a.fsplit, vheads);
-  if (a.mpad == 32) {
-    if (a.k_fp8) hipLaunchKernelGGL((score_fused_kernel<D, 1, FUSED_NS1, true>), grid, dim3(SCORE_THREADS), ldsf, st, b);
-    else hipLaunchKernelGGL((score_fused_kernel<D, 1, FUSED_NS1>), grid, dim3(SCORE_THREADS), ldsf, st, b);
-  } else if (a.k_fp8) {
-    if (ldsf > 48 * 1024)
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_fused_kernel<D, 2, FUSED_NS2, true>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)ldsf);
-    hipLaunchKernelGGL((score_fused_kernel<D, 2, FUSED_NS2, true>), grid, dim3(SCORE_THREADS), ldsf, st, b);
-  } else {
-    if (ldsf > 48 * 1024)
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_fused_kernel<D, 2, FUSED_NS2>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)ldsf);
-    hipLaunchKernelGGL((score_fused_kernel<D, 2, FUSED_NS2>), grid, dim3(SCORE_THREADS), ldsf, st, b);
+  // (a.nstrag > 0: a.fsplit counts the chunks of the main launch; the parked ones go first, the finish kernel last)
+  for (int pass = a.nstrag ? 0 : 1; pass < 2; ++pass) {
+    b.chunk_lo = pass == 0 ? a.fsplit : 0;
+    const dim3 grid(pass == 0 ? a.nstrag : a.fsplit, vheads);
+    if (a.mpad == 32) {
+      if (a.k_fp8) hipLaunchKernelGGL((score_fused_kernel<D, 1, FUSED_NS1, true>), grid, dim3(SCORE_THREADS), ldsf, st, b);
+      else hipLaunchKernelGGL((score_fused_kernel<D, 1, FUSED_NS1>), grid, dim3(SCORE_THREADS), ldsf, st, b);
+    } else if (a.k_fp8) {
+      if (ldsf > 48 * 1024)
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_fused_kernel<D, 2, FUSED_NS2, true>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)ldsf);
+      hipLaunchKernelGGL((score_fused_kernel<D, 2, FUSED_NS2, true>), grid, dim3(SCORE_THREADS), ldsf, st, b);
+    } else {
+      if (ldsf > 48 * 1024)
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_fused_kernel<D, 2, FUSED_NS2>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)ldsf);
+      hipLaunchKernelGGL((score_fused_kernel<D, 2, FUSED_NS2>), grid, dim3(SCORE_THREADS), ldsf, st, b);
+    }
+  }
+  if (a.nstrag) {
+    b.chunk_lo = 0;
+    if (a.mpad == 32) hipLaunchKernelGGL((score_fused_finish_kernel<1, FUSED_NS1>), dim3(a.nstrag, vheads), dim3(SCORE_THREADS), 0, st, b);
+    else hipLaunchKernelGGL((score_fused_finish_kernel<2, FUSED_NS2>), dim3(a.nstrag, vheads), dim3(SCORE_THREADS), 0, st, b);
   }
   if (a.rb_count > 1) {
     const long long n = (long long)heads * a.L;
@@ -1617,7 +1697,16 @@ hipError_t launch_score(const Dims& dm, const madakv_config& c, const void* q_wi
   a.psi_part = reinterpret_cast<float*>(static_cast<char*>(ws) + 256 + rowstat_bytes(dm, c.dtype) + 256 + xchg_bytes(dm, c.dtype));
   a.psi_part_stride = (long long)dm.heads * dm.L;
   a.fsplit = (!row_lse && use_fused(dm, c.dtype)) ? fused_split(dm) : 0;
-  a.xgroups = xchg_groups(a.fsplit); a.xstride = (long long)(a.fsplit + a.xgroups) * fused_mpad(dm); a.k_fp8 = 0;
+  a.nstrag = a.fsplit ? fused_parked_chunks(a.fsplit) : 0;
+  if (getenv("MADAKV_SCORE_NO_PARKED_CHUNKS")) a.nstrag = 0;                      // (measurement switch)
+  a.fsplit -= a.nstrag;                                                            // the chunks of the main launch
+  a.xgroups = xchg_groups(a.fsplit) + a.nstrag; a.xstride = (long long)(a.fsplit + a.xgroups) * fused_mpad(dm); a.k_fp8 = 0;
+  {
+    char* pk = static_cast<char*>(ws) + 256 + rowstat_bytes(dm, c.dtype) + 256 + xchg_bytes(dm, c.dtype) +
+               (fused_fits(dm, c.dtype) && fused_blocks(dm) > 1 ? (size_t)fused_blocks(dm) * dm.heads * dm.L * sizeof(float) : 0);
+    a.offs_out = a.nstrag ? reinterpret_cast<float*>(pk) : nullptr;
+    a.park = a.nstrag ? reinterpret_cast<float*>(pk) + (size_t)dm.heads * fused_mpad(dm) : nullptr;
+  }
   a.seg_off = nullptr; a.seg_len = nullptr;
   // (a test can force the lone-workgroup path of the one-sweep kernel from the host with a spin limit of 1)
   const char* spin = getenv("MADAKV_SCORE_SPIN_LIMIT");

@@ -620,6 +620,13 @@ def _one_sweep_workloads():
     # 69 chunks of 1024 keys per head: the row statistics travel in two levels (groups of 16 chunks)
     out["bf16_70k"] = W["bf16_mha"].scaled(name="bf16_70k", n_layers=1, batch=1, n_q_heads=2, n_kv_heads=2, ctx_len=70001,
                                            budget=500, n_images=3)
+    # 75 chunks of 768 keys per head (64 proxy rows): six heads fit the chip's workgroup slots, one chunk per head in the
+    # way of a seventh, so the last two chunks of every head run ahead, parked (their words at the group level)
+    out["bf16_w64_57k"] = W["bf16_w64"].scaled(name="bf16_w64_57k", n_layers=1, batch=1, n_q_heads=2, n_kv_heads=2, ctx_len=57001,
+                                               budget=600, n_images=20)
+    # ... and 80 chunks of 1024 keys (32 rows): seven parked
+    out["bf16_81k"] = W["bf16_mha"].scaled(name="bf16_81k", n_layers=1, batch=1, n_q_heads=1, n_kv_heads=1, ctx_len=81001,
+                                           budget=500, n_images=30)
     return out
 
 
