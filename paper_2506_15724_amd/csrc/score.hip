@@ -54,10 +54,10 @@ struct ScoreArgs {
   long long psi_part_stride;   // floats between two row blocks' copies
   int spin_limit;      // polls a workgroup of the one-sweep kernel spends on one missing word before it goes its own way
   // one-sweep kernel on long heads whose chunks do not pack the chip's workgroup slots (see launch_fused): the last
-  // nstrag chunks of every head run in a launch of their own before the others (chunk_lo = first chunk of a launch),
-  // leave their row statistics as exchange words of the group level and their logits in `park`, and do not wait;
-  // the other chunks' launch leaves the heads' row offsets in offs_out, a small kernel finishes the parked chunks
-  int chunk_lo = 0, nstrag = 0;
+  // nstrag chunks of every head come first in the grid (x < nstrag), leave their row statistics as exchange words
+  // of the group level and their logits in `park`, and do not wait; the other chunks' workgroups leave the heads'
+  // row offsets in offs_out, a small kernel finishes the parked chunks
+  int nstrag = 0;
   float* park = nullptr;
   float* offs_out = nullptr;
   int head0;           // first head of this launch (grid.y indexes head0 + y)
@@ -825,7 +825,7 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(M
   __shared__ int s_fail;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int split = blockIdx.x + a.chunk_lo;
+  const int bx = blockIdx.x;                  // (the parked chunks first: split is set below, once fs is known)
   const int hv = a.head0 + blockIdx.y;        // head, or (head, block of 64 proxy rows) when there are more than 64
   const int head = hv / a.rb_count;
   const int rowbase = (hv % a.rb_count) * 64; // first proxy row of this workgroup's block
@@ -837,6 +837,7 @@ __global__ __launch_bounds__(SCORE_THREADS) __attribute__((amdgpu_waves_per_eu(M
   const int Lh = a.seg_len ? a.seg_len[head] : a.L;
   const long long base = a.seg_off ? a.seg_off[head] : (long long)head * a.L;
   const int fs = a.seg_len ? (Lh + CK - 1) / CK : a.fsplit;      // chunks of this head (the grid is sized for the longest)
+  const int split = bx < a.nstrag ? fs + bx : bx - a.nstrag;
   if (split >= fs + a.nstrag) return;
   const bool parked = split >= fs;            // one of the head's last chunks, run ahead of the others
   // (F8: rows of D bytes; kg then counts in 2-byte units from a byte address that is base * D)
@@ -1482,25 +1483,21 @@ static void launch_fused(const ScoreArgs& a, int heads, hipStream_t st) {
   const size_t ldsf = ((size_t)a.mpad + 4 * 32) * (D + 8) * 2 + ((size_t)4 * a.mpad * 2 + a.mpad + 512) * sizeof(float);
   ScoreArgs b = a;
   b.head0 = a.head0 * a.rb_count;
-  // (a.nstrag > 0: a.fsplit counts the chunks of the main launch; the parked ones go first, the finish kernel last)
-  for (int pass = a.nstrag ? 0 : 1; pass < 2; ++pass) {
-    b.chunk_lo = pass == 0 ? a.fsplit : 0;
-    const dim3 grid(pass == 0 ? a.nstrag : a.fsplit, vheads);
-    if (a.mpad == 32) {
-      if (a.k_fp8) hipLaunchKernelGGL((score_fused_kernel<D, 1, FUSED_NS1, true>), grid, dim3(SCORE_THREADS), ldsf, st, b);
-      else hipLaunchKernelGGL((score_fused_kernel<D, 1, FUSED_NS1>), grid, dim3(SCORE_THREADS), ldsf, st, b);
-    } else if (a.k_fp8) {
-      if (ldsf > 48 * 1024)
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_fused_kernel<D, 2, FUSED_NS2, true>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)ldsf);
-      hipLaunchKernelGGL((score_fused_kernel<D, 2, FUSED_NS2, true>), grid, dim3(SCORE_THREADS), ldsf, st, b);
-    } else {
-      if (ldsf > 48 * 1024)
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_fused_kernel<D, 2, FUSED_NS2>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)ldsf);
-      hipLaunchKernelGGL((score_fused_kernel<D, 2, FUSED_NS2>), grid, dim3(SCORE_THREADS), ldsf, st, b);
-    }
+  // (a.nstrag > 0: a.fsplit counts the chunks that wait for each other; the parked ones are the first in the grid)
+  const dim3 grid(a.nstrag + a.fsplit, vheads);
+  if (a.mpad == 32) {
+    if (a.k_fp8) hipLaunchKernelGGL((score_fused_kernel<D, 1, FUSED_NS1, true>), grid, dim3(SCORE_THREADS), ldsf, st, b);
+    else hipLaunchKernelGGL((score_fused_kernel<D, 1, FUSED_NS1>), grid, dim3(SCORE_THREADS), ldsf, st, b);
+  } else if (a.k_fp8) {
+    if (ldsf > 48 * 1024)
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_fused_kernel<D, 2, FUSED_NS2, true>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)ldsf);
+    hipLaunchKernelGGL((score_fused_kernel<D, 2, FUSED_NS2, true>), grid, dim3(SCORE_THREADS), ldsf, st, b);
+  } else {
+    if (ldsf > 48 * 1024)
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&score_fused_kernel<D, 2, FUSED_NS2>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)ldsf);
+    hipLaunchKernelGGL((score_fused_kernel<D, 2, FUSED_NS2>), grid, dim3(SCORE_THREADS), ldsf, st, b);
   }
   if (a.nstrag) {
-    b.chunk_lo = 0;
     if (a.mpad == 32) hipLaunchKernelGGL((score_fused_finish_kernel<1, FUSED_NS1>), dim3(a.nstrag, vheads), dim3(SCORE_THREADS), 0, st, b);
     else hipLaunchKernelGGL((score_fused_finish_kernel<2, FUSED_NS2>), dim3(a.nstrag, vheads), dim3(SCORE_THREADS), 0, st, b);
   }
