@@ -145,10 +145,12 @@ int32_t madakv_workspace_bytes(const madakv_handle* h, int32_t n_layers_per_call
  * Known without a device sync because the sum of budgets is conserved exactly. */
 int32_t madakv_compact_capacity_tokens(const madakv_handle* h, int64_t* tokens);
 
-/* Environment variables (diagnostics, read at every scoring call; not needed in normal use):
+/* Environment variables (diagnostics, read at every call they concern; not needed in normal use):
  *   MADAKV_SCORE_TWO_SWEEPS=1   score with the two-sweep kernels (K read twice) everywhere
  *   MADAKV_SCORE_SPIN_LIMIT=n   polls a workgroup of the one-sweep scoring kernel spends on a missing word
  *                               before it computes the head's row statistics alone (default 65536)
+ *   MADAKV_LAYER_GROUPS=n       layer groups a call over several layers is pipelined in (1..4; default: as many as
+ *                               leave a group 256 heads)
  *   MADAKV_SCORE_NO_PARKED_CHUNKS=1   long heads: all chunks of a head in one launch of the one-sweep kernel, also
  *                               where a few of them are in the way of one more head fitting the chip */
 

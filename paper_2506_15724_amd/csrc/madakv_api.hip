@@ -146,16 +146,22 @@ void destroy_side(madakv_handle* h) {
   for (int g = 0; g < MAX_GROUPS; ++g) if (h->ev_sel[g]) (void)hipEventDestroy(h->ev_sel[g]);
 }
 
-// A call over n >= 4 layers is cut into MAX_GROUPS layer groups of (nearly) equal size for the overlap;
-// fewer layers make one group.  Fills begin[0 .. groups] and returns the number of groups.
-int layer_groups(int n, int* begin) {
-  if (n < MAX_GROUPS) { begin[0] = 0; begin[1] = n; return 1; }
-  for (int g = 0; g <= MAX_GROUPS; ++g) begin[g] = (int)((long long)n * g / MAX_GROUPS);
-  return MAX_GROUPS;
+// A call over n layers is cut into up to MAX_GROUPS layer groups of (nearly) equal size for the overlap, as many as
+// leave a group at least one head per compute unit: the per-head kernels of a group then fill the chip and are worth
+// hiding under the next group's sweeps and gathers.  With fewer heads (grouped-query models) only the last group's
+// per-head kernels are exposed however the layers are cut, and more groups only add launches: the Qwen-shaped
+// eviction takes 1.00-1.05 ms in one or two groups against 1.16 ms in four.
+// Fills begin[0 .. groups] and returns the number of groups.
+int layer_groups(const madakv_config& c, int n, int* begin) {
+  const long long heads = (long long)n * c.batch * c.n_kv_heads;
+  int ng = (int)std::max<long long>(1, std::min<long long>(std::min(MAX_GROUPS, n), heads / 256));
+  if (const char* e = getenv("MADAKV_LAYER_GROUPS")) ng = std::max(1, std::min(std::min(MAX_GROUPS, n), atoi(e)));   // (tests, measurements)
+  for (int g = 0; g <= ng; ++g) begin[g] = (int)((long long)n * g / ng);
+  return ng;
 }
-int largest_group(int n) {
+int largest_group(const madakv_config& c, int n) {
   int b[MAX_GROUPS + 1];
-  const int ng = layer_groups(n, b);
+  const int ng = layer_groups(c, n, b);
   int m = 0;
   for (int g = 0; g < ng; ++g) m = std::max(m, b[g + 1] - b[g]);
   return m;
@@ -163,7 +169,7 @@ int largest_group(int n) {
 
 size_t window_ws_for_call(const madakv_config& c, int n) {
   int b[MAX_GROUPS + 1];
-  const int ng = layer_groups(n, b);
+  const int ng = layer_groups(c, n, b);
   size_t need = 0;
   for (int g = 0; g < ng; ++g) need = std::max(need, window_attn_ws_bytes(make_dims(c, b[g + 1] - b[g]), c));
   return need;
@@ -171,7 +177,7 @@ size_t window_ws_for_call(const madakv_config& c, int n) {
 
 size_t score_ws_for_call(const madakv_config& c, int n) {
   int b[MAX_GROUPS + 1];
-  const int ng = layer_groups(n, b);
+  const int ng = layer_groups(c, n, b);
   size_t need = 0;
   for (int g = 0; g < ng; ++g) need = std::max(need, score_ws_bytes(make_dims(c, b[g + 1] - b[g]), c.dtype));
   return need;
@@ -357,7 +363,7 @@ int32_t madakv_workspace_bytes(const madakv_handle* h, int32_t n_layers_per_call
   if (score_ws) *score_ws = score_ws_for_call(h->cfg, n_layers_per_call);
   if (select_ws) {
     // enough for madakv_select_gather over n layers and for madakv_evict (one slice per layer group)
-    const int gl = largest_group(n_layers_per_call);
+    const int gl = largest_group(h->cfg, n_layers_per_call);
     const size_t slices = ((select_ws_bytes(make_dims(h->cfg, gl), h->cfg) + 255) / 256 * 256) * MAX_GROUPS;
     *select_ws = std::max(select_ws_bytes(dm, h->cfg), slices);
   }
@@ -391,7 +397,7 @@ static int32_t score_impl(madakv_handle* h, int32_t layer0, int32_t n,
   // The call is cut into up to MAX_GROUPS layer groups: the score sweeps of a group run on the
   // caller's stream, its statistics on the side stream, under the sweeps of the next group.
   int gb[MAX_GROUPS + 1];
-  const int ngroups = layer_groups(n, gb);
+  const int ngroups = layer_groups(c, n, gb);
   const bool overlap = ngroups > 1;
   const size_t es = c.dtype == MADAKV_BF16 ? 2 : 4;
   hipError_t e = hipSuccess;
@@ -488,8 +494,8 @@ int32_t madakv_select_gather(madakv_handle* h, int32_t layer0, int32_t n,
   // madakv_workspace_bytes reports has): segment layout and selection of a group on the side stream beside
   // the gather of the group before, which leaves them room.  One group otherwise.
   int gb[MAX_GROUPS + 1];
-  int ngroups = layer_groups(n, gb);
-  const size_t sel_slice = (select_ws_bytes(make_dims(c, largest_group(n)), c) + 255) / 256 * 256;
+  int ngroups = layer_groups(c, n, gb);
+  const size_t sel_slice = (select_ws_bytes(make_dims(c, largest_group(c, n)), c) + 255) / 256 * 256;
   if (ngroups > 1 && ws_bytes < sel_slice * ngroups) { ngroups = 1; gb[0] = 0; gb[1] = n; }
   const bool overlap = ngroups > 1;
   const size_t es = c.dtype == MADAKV_BF16 ? 2 : 4;
@@ -536,8 +542,8 @@ int32_t madakv_evict(madakv_handle* h, int32_t layer0, int32_t n,
       bad_ptr(kv_len, 4) || bad_ptr(k_c) || bad_ptr(v_c) || bad_ptr(score_ws) || bad_ptr(select_ws))
     return MADAKV_ERR_INVALID_ARG;
   int gb[MAX_GROUPS + 1];
-  const int ngroups = layer_groups(n, gb);
-  const int gl = largest_group(n);
+  const int ngroups = layer_groups(c, n, gb);
+  const int gl = largest_group(c, n);
   // every layer group gets its own slice of the selection workspace (its block table is still in
   // use by its gather while the next group's table is being written)
   const size_t sel_slice = (select_ws_bytes(make_dims(c, gl), c) + 255) / 256 * 256;

@@ -17,6 +17,14 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
+@pytest.fixture(autouse=True)
+def _four_layer_groups(monkeypatch):
+    """The library pipelines a call over several layers in as many layer groups as leave a group 256 heads: one for
+    the small shapes here.  The tests of this file ask for four, so that the pipelined path (two streams, events,
+    per-group workspaces) is what they run; test_fused_eviction_call_matches_the_three_calls also runs the default."""
+    monkeypatch.setenv("MADAKV_LAYER_GROUPS", "4")
+
+
 def say(msg):
     print(f"[parity] {msg}", flush=True)
     sys.stdout.flush()
@@ -1491,9 +1499,14 @@ def test_decode_long_heads_across_a_chunk_boundary():
     eng.close()
 
 
-@pytest.mark.parametrize("nl", [3, 6, 9])
-def test_fused_eviction_call_matches_the_three_calls(nl):
-    """madakv_evict (pipelined over layer groups on two streams) against score + allocate + select_gather."""
+@pytest.mark.parametrize("nl,groups", [(3, "4"), (6, "4"), (9, "4"), (6, "2"), (9, None)])
+def test_fused_eviction_call_matches_the_three_calls(nl, groups, monkeypatch):
+    """madakv_evict (pipelined over layer groups on two streams) against score + allocate + select_gather.
+    groups None: the library's own choice (one group for a shape this small)."""
+    if groups is None:
+        monkeypatch.delenv("MADAKV_LAYER_GROUPS")
+    else:
+        monkeypatch.setenv("MADAKV_LAYER_GROUPS", groups)
     wl = small_workloads()["bf16_mha"].scaled(n_layers=nl, batch=2, ctx_len=1900)
     NL = wl.n_layers
     q, k, v, mask, masks = PU.make_inputs(wl, DEV)
